@@ -1,0 +1,602 @@
+// CPU ORACLE -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+//
+// A plain, slow, direct-loop implementation of what one model partition computes in
+// HyPar-Flow-style model-parallel training: the forward pass of the partition's layers on
+// activations received from the previous partition, the back-propagation from the partial
+// error received from the next partition (producing weight gradients and the partial error
+// with respect to the partition's own input -- the paper's "grad layer" result, Section
+// "Implementing Distributed Back-Propagation", Eq. 5-7), accumulation of weight gradients over
+// the micro-batches of one batch ("Exploiting Pipeline Stages within Each Minibatch"; one
+// synchronous update per batch, Section "Background", Data-Parallelism) and the optimizer
+// step (apply_gradients, same section as Eq. 5-7).
+//
+// The method reaches exactly the result of ordinary back-propagation, so every function here is
+// the textbook definition written out: no blocking, no im2col, no BLAS, no fusion.  Storage type
+// T is float (the fp32 reference) or double (for finite-difference checks); every reduction
+// accumulates in double, so the reference is not the noisy side of a comparison.
+//
+// Only tests, the smoke check and the benchmark's cpu_baseline leg may call this library.  It
+// shares no code with the HIP path.
+//
+// Pins (tests/test_oracle_*.py): finite differences for every gradient, 1x1 conv == matmul,
+// delta-filter identity, stride-2 == subsampled stride-1, adjoint identities for dgrad/wgrad,
+// BN moment identities, softmax-CE closed forms, the two-linear-layer closed form of Eq. 1-7,
+// partition equivalence, micro-batch equivalence with frozen BN, accumulation and SGD closed
+// forms.  Parity unpinned: anything tied to trained accuracy (needs the paper's dataset).
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Convolution, NHWC activations, [R][S][Cin][Cout] weights, zero padding (R-1)/2, no bias.
+// y[n,p,q,k] = sum_{r,s,c} x[n, p*st + r - pad, q*st + s - pad, c] * w[r,s,c,k]
+// ------------------------------------------------------------------------------------------
+template <class T>
+void conv_fwd(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int cout, int R, int st) {
+  const int pad = (R - 1) / 2;
+  const int ho = (h + 2 * pad - R) / st + 1, wo = (wd + 2 * pad - R) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int in = 0; in < n; ++in)
+    for (int p = 0; p < ho; ++p) {
+      std::vector<double> acc(cout);
+      for (int q = 0; q < wo; ++q) {
+        std::fill(acc.begin(), acc.end(), 0.0);
+        for (int r = 0; r < R; ++r) {
+          const int hi = p * st + r - pad;
+          if (hi < 0 || hi >= h) continue;
+          for (int s = 0; s < R; ++s) {
+            const int wi = q * st + s - pad;
+            if (wi < 0 || wi >= wd) continue;
+            const T* xp = x + ((size_t)(in * h + hi) * wd + wi) * cin;
+            const T* wp = w + (size_t)(r * R + s) * cin * cout;
+            for (int c = 0; c < cin; ++c) {
+              const double xv = xp[c];
+              const T* wr = wp + (size_t)c * cout;
+              for (int k = 0; k < cout; ++k) acc[k] += xv * (double)wr[k];
+            }
+          }
+        }
+        T* yp = y + ((size_t)(in * ho + p) * wo + q) * cout;
+        for (int k = 0; k < cout; ++k) yp[k] = (T)acc[k];
+      }
+    }
+}
+
+// dx[n,h,w,c] = sum over (p,q,r,s,k) with p*st + r - pad == h and q*st + s - pad == w of
+//               dy[n,p,q,k] * w[r,s,c,k]          (the adjoint of conv_fwd in x)
+template <class T>
+void conv_dgrad(const T* dy, const T* w, T* dx, int n, int h, int wd, int cin, int cout, int R, int st) {
+  const int pad = (R - 1) / 2;
+  const int ho = (h + 2 * pad - R) / st + 1, wo = (wd + 2 * pad - R) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int in = 0; in < n; ++in)
+    for (int hi = 0; hi < h; ++hi) {
+      std::vector<double> acc(cin);
+      for (int wi = 0; wi < wd; ++wi) {
+        std::fill(acc.begin(), acc.end(), 0.0);
+        for (int r = 0; r < R; ++r) {
+          const int t = hi + pad - r;
+          if (t < 0 || t % st != 0 || t / st >= ho) continue;
+          const int p = t / st;
+          for (int s = 0; s < R; ++s) {
+            const int u = wi + pad - s;
+            if (u < 0 || u % st != 0 || u / st >= wo) continue;
+            const int q = u / st;
+            const T* dyp = dy + ((size_t)(in * ho + p) * wo + q) * cout;
+            const T* wp = w + (size_t)(r * R + s) * cin * cout;
+            for (int c = 0; c < cin; ++c) {
+              const T* wr = wp + (size_t)c * cout;
+              double a = 0.0;
+              for (int k = 0; k < cout; ++k) a += (double)dyp[k] * (double)wr[k];
+              acc[c] += a;
+            }
+          }
+        }
+        T* dxp = dx + ((size_t)(in * h + hi) * wd + wi) * cin;
+        for (int c = 0; c < cin; ++c) dxp[c] = (T)acc[c];
+      }
+    }
+}
+
+// dw[r,s,c,k] += sum_{n,p,q} x[n, p*st + r - pad, q*st + s - pad, c] * dy[n,p,q,k]
+template <class T>
+void conv_wgrad(const T* x, const T* dy, double* dw, int n, int h, int wd, int cin, int cout, int R, int st) {
+  const int pad = (R - 1) / 2;
+  const int ho = (h + 2 * pad - R) / st + 1, wo = (wd + 2 * pad - R) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int rs = 0; rs < R * R; ++rs)
+    for (int c = 0; c < cin; ++c) {
+      const int r = rs / R, s = rs % R;
+      std::vector<double> acc(cout, 0.0);
+      for (int in = 0; in < n; ++in)
+        for (int p = 0; p < ho; ++p) {
+          const int hi = p * st + r - pad;
+          if (hi < 0 || hi >= h) continue;
+          for (int q = 0; q < wo; ++q) {
+            const int wi = q * st + s - pad;
+            if (wi < 0 || wi >= wd) continue;
+            const double xv = x[((size_t)(in * h + hi) * wd + wi) * cin + c];
+            const T* dyp = dy + ((size_t)(in * ho + p) * wo + q) * cout;
+            for (int k = 0; k < cout; ++k) acc[k] += xv * (double)dyp[k];
+          }
+        }
+      double* o = dw + ((size_t)rs * cin + c) * cout;
+      for (int k = 0; k < cout; ++k) o[k] += acc[k];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// BatchNorm + ReLU over the M = b*H*W rows of one micro-batch, per channel.
+// mode 0: mean = mean(x), var = mean((x-mean)^2) (biased); mode 1: frozen mean 0, var 1.
+// xhat = (x-mean)/sqrt(var+eps); z = gamma*xhat + beta; a = max(z, 0).
+// ------------------------------------------------------------------------------------------
+template <class T>
+void bn_relu_fwd(const T* x, const T* gamma, const T* beta, T* a, double* mean, double* invstd,
+                 size_t M, int C, double eps, int mode) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    double mu = 0.0, var = 1.0;
+    if (mode == 0) {
+      double s = 0.0;
+      for (size_t m = 0; m < M; ++m) s += (double)x[m * C + c];
+      mu = s / (double)M;
+      double v = 0.0;
+      for (size_t m = 0; m < M; ++m) { const double d = (double)x[m * C + c] - mu; v += d * d; }
+      var = v / (double)M;
+    }
+    const double is = 1.0 / std::sqrt(var + eps);
+    mean[c] = mu; invstd[c] = is;
+    for (size_t m = 0; m < M; ++m) {
+      const double z = (double)gamma[c] * (((double)x[m * C + c] - mu) * is) + (double)beta[c];
+      a[m * C + c] = (T)(z > 0.0 ? z : 0.0);
+    }
+  }
+}
+
+// dz = da * [z > 0]; dbeta = sum dz; dgamma = sum dz*xhat;
+// mode 0: dx = gamma*invstd * (dz - dbeta/M - xhat*dgamma/M); mode 1: dx = gamma*invstd*dz.
+// dgamma/dbeta are added into the accumulators.  The ReLU mask is recomputed from z as the
+// forward pass computed it (same precision, same expression).
+template <class T>
+void bn_relu_bwd(const T* x, const T* da, const T* gamma, const T* beta, const double* mean,
+                 const double* invstd, T* dx, double* dgamma, double* dbeta, size_t M, int C, int mode) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    const double mu = mean[c], is = invstd[c], g = gamma[c], bt = beta[c];
+    double sb = 0.0, sg = 0.0;
+    for (size_t m = 0; m < M; ++m) {
+      const double xh = ((double)x[m * C + c] - mu) * is;
+      const double z = g * xh + bt;
+      const double dz = z > 0.0 ? (double)da[m * C + c] : 0.0;
+      sb += dz; sg += dz * xh;
+    }
+    dbeta[c] += sb; dgamma[c] += sg;
+    for (size_t m = 0; m < M; ++m) {
+      const double xh = ((double)x[m * C + c] - mu) * is;
+      const double z = g * xh + bt;
+      const double dz = z > 0.0 ? (double)da[m * C + c] : 0.0;
+      const double v = mode == 0 ? (dz - sb / (double)M - xh * sg / (double)M) : dz;
+      dx[m * C + c] = (T)(g * is * v);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Head after its BN+ReLU: global average pool, FC with bias, softmax cross-entropy.
+// g[n,c] = mean_{h,w} a[n,h,w,c]; logits = g*Wfc + bfc; loss_n = -log softmax(logits_n)[y_n];
+// returns sum_n loss_n / divisor and dlogits = (softmax - onehot)/divisor.
+// ------------------------------------------------------------------------------------------
+template <class T>
+double head_fwd(const T* a, const T* wfc, const T* bfc, const int32_t* labels, T* g, T* dlogits,
+                int n, int hw, int C, int classes, double divisor) {
+  double loss = 0.0;
+  for (int in = 0; in < n; ++in) {
+    for (int c = 0; c < C; ++c) {
+      double s = 0.0;
+      for (int i = 0; i < hw; ++i) s += (double)a[((size_t)in * hw + i) * C + c];
+      g[(size_t)in * C + c] = (T)(s / (double)hw);
+    }
+    std::vector<double> lg(classes);
+    double mx = -1e300;
+    for (int j = 0; j < classes; ++j) {
+      double s = (double)bfc[j];
+      for (int c = 0; c < C; ++c) s += (double)g[(size_t)in * C + c] * (double)wfc[(size_t)c * classes + j];
+      lg[j] = s; if (s > mx) mx = s;
+    }
+    double den = 0.0;
+    for (int j = 0; j < classes; ++j) den += std::exp(lg[j] - mx);
+    const int y = labels[in];
+    loss += -(lg[y] - mx - std::log(den)) / divisor;
+    for (int j = 0; j < classes; ++j)
+      dlogits[(size_t)in * classes + j] = (T)((std::exp(lg[j] - mx) / den - (j == y ? 1.0 : 0.0)) / divisor);
+  }
+  return loss;
+}
+
+// dWfc += g^T dlogits; dbfc += sum_n dlogits; dg = dlogits * Wfc^T; da[n,h,w,c] = dg[n,c]/(H*W).
+template <class T>
+void head_bwd(const T* g, const T* dlogits, const T* wfc, double* dwfc, double* dbfc, T* da,
+              int n, int hw, int C, int classes) {
+  for (int in = 0; in < n; ++in) {
+    for (int j = 0; j < classes; ++j) dbfc[j] += (double)dlogits[(size_t)in * classes + j];
+    for (int c = 0; c < C; ++c) {
+      double dg = 0.0;
+      for (int j = 0; j < classes; ++j) {
+        const double d = dlogits[(size_t)in * classes + j];
+        dwfc[(size_t)c * classes + j] += (double)g[(size_t)in * C + c] * d;
+        dg += d * (double)wfc[(size_t)c * classes + j];
+      }
+      for (int i = 0; i < hw; ++i) da[((size_t)in * hw + i) * C + c] = (T)(dg / (double)hw);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// The partition: stem? + residual blocks + head?, canonical flat parameter order
+//   stem W; per block bn1.g, bn1.b, W1, bn2.g, bn2.b, W2, [bn3.g, bn3.b, W3], [Wproj];
+//   head bn.g, bn.b, Wfc, bfc.
+// ------------------------------------------------------------------------------------------
+struct BlockDesc { int kind, c_in, c_mid, c_out, stride; };
+
+struct Desc {
+  int in_h, in_w, in_c, has_stem, stem_c_out, n_blocks, has_head, num_classes;
+  int microbatch, num_microbatches, loss_divisor, bn_mode;
+  double bn_eps;
+  std::vector<BlockDesc> blocks;
+};
+
+struct ConvP { size_t w; int cin, cout, R, st; };
+struct BnP { size_t g, b; int c; };
+struct BlockP {
+  BlockDesc d; int h_in, w_in, h_out, w_out; bool proj;
+  BnP bn[3]; ConvP cv[3]; ConvP pj; int nconv;
+};
+
+template <class T>
+struct BnSave { std::vector<T> x; std::vector<double> mean, invstd; };
+
+template <class T>
+struct BlockStash { BnSave<T> bn[3]; std::vector<T> a[3]; };
+
+template <class T>
+struct MbStash {
+  std::vector<T> stem_in;
+  std::vector<BlockStash<T>> blk;
+  BnSave<T> head_bn; std::vector<T> head_a, g, dlogits;
+  bool fwd_done = false, bwd_done = false;
+};
+
+enum { OK = 0, E_INVAL = 1, E_STATE = 2 };
+
+template <class T>
+struct Partition {
+  Desc d;
+  std::vector<T> params, momentum;
+  std::vector<double> grad;
+  std::vector<BlockP> bp;
+  size_t stem_w = 0; BnP head_bn{}; size_t wfc = 0, bfc = 0;
+  int out_h, out_w, out_c, c0;
+  std::vector<MbStash<T>> st;
+  int n_bwd_done = 0;
+
+  size_t plan() {
+    size_t off = 0;
+    int h = d.in_h, w = d.in_w, c = d.in_c;
+    if (d.has_stem) { stem_w = off; off += (size_t)9 * d.in_c * d.stem_c_out; c = d.stem_c_out; }
+    c0 = c;
+    for (auto& b : d.blocks) {
+      BlockP p{}; p.d = b; p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride;
+      p.proj = (b.stride != 1 || b.c_in != b.c_out);
+      auto bn = [&](int ch) { BnP r{off, off + (size_t)ch, ch}; off += 2 * (size_t)ch; return r; };
+      auto cv = [&](int ci, int co, int R, int s) { ConvP r{off, ci, co, R, s}; off += (size_t)R * R * ci * co; return r; };
+      if (b.kind == 0) {
+        p.nconv = 2;
+        p.bn[0] = bn(b.c_in);  p.cv[0] = cv(b.c_in, b.c_mid, 3, b.stride);
+        p.bn[1] = bn(b.c_mid); p.cv[1] = cv(b.c_mid, b.c_out, 3, 1);
+      } else {
+        p.nconv = 3;
+        p.bn[0] = bn(b.c_in);  p.cv[0] = cv(b.c_in, b.c_mid, 1, b.stride);
+        p.bn[1] = bn(b.c_mid); p.cv[1] = cv(b.c_mid, b.c_mid, 3, 1);
+        p.bn[2] = bn(b.c_mid); p.cv[2] = cv(b.c_mid, b.c_out, 1, 1);
+      }
+      if (p.proj) p.pj = cv(b.c_in, b.c_out, 1, b.stride);
+      bp.push_back(p);
+      h = p.h_out; w = p.w_out; c = b.c_out;
+    }
+    out_h = h; out_w = w; out_c = c;
+    if (d.has_head) {
+      head_bn = BnP{off, off + (size_t)c, c}; off += 2 * (size_t)c;
+      wfc = off; off += (size_t)c * d.num_classes;
+      bfc = off; off += d.num_classes;
+    }
+    return off;
+  }
+
+  Partition(const Desc& dd, const T* host_params) : d(dd) {
+    const size_t P = plan();
+    params.assign(host_params, host_params + P);
+    momentum.assign(P, (T)0);
+    grad.assign(P, 0.0);
+    st.resize(d.num_microbatches);
+  }
+
+  int forward(int mb, const T* act_in, const int32_t* labels, T* act_out, double* loss_accum) {
+    if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
+    MbStash<T>& S = st[mb];
+    if (S.fwd_done) return E_STATE;
+    const int b = d.microbatch;
+    const T* P = params.data();
+    std::vector<T> x;
+    int h = d.in_h, w = d.in_w;
+    if (d.has_stem) {
+      S.stem_in.assign(act_in, act_in + (size_t)b * h * w * d.in_c);
+      x.resize((size_t)b * h * w * d.stem_c_out);
+      conv_fwd(S.stem_in.data(), P + stem_w, x.data(), b, h, w, d.in_c, d.stem_c_out, 3, 1);
+    } else {
+      x.assign(act_in, act_in + (size_t)b * h * w * d.in_c);
+    }
+    S.blk.assign(bp.size(), BlockStash<T>());
+    for (size_t i = 0; i < bp.size(); ++i) {
+      const BlockP& p = bp[i]; BlockStash<T>& B = S.blk[i];
+      const size_t M_in = (size_t)b * p.h_in * p.w_in, M_out = (size_t)b * p.h_out * p.w_out;
+      // a = relu(bn1(x))
+      auto bnrelu = [&](int j, std::vector<T>& in) {
+        B.bn[j].x = in; B.bn[j].mean.resize(p.bn[j].c); B.bn[j].invstd.resize(p.bn[j].c);
+        B.a[j].resize(in.size());
+        bn_relu_fwd(in.data(), P + p.bn[j].g, P + p.bn[j].b, B.a[j].data(), B.bn[j].mean.data(),
+                    B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode);
+      };
+      bnrelu(0, x);
+      std::vector<T> sc;
+      if (p.proj) {
+        sc.resize(M_out * p.d.c_out);
+        conv_fwd(B.a[0].data(), P + p.pj.w, sc.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+      } else {
+        sc = x;
+      }
+      std::vector<T> r(M_out * p.cv[0].cout);
+      conv_fwd(B.a[0].data(), P + p.cv[0].w, r.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
+      for (int j = 1; j < p.nconv; ++j) {
+        bnrelu(j, r);
+        std::vector<T> r2(M_out * p.cv[j].cout);
+        conv_fwd(B.a[j].data(), P + p.cv[j].w, r2.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
+        r.swap(r2);
+      }
+      x.resize(M_out * p.d.c_out);
+      for (size_t e = 0; e < x.size(); ++e) x[e] = (T)((double)sc[e] + (double)r[e]);
+      (void)M_in;
+    }
+    if (d.has_head) {
+      const int C = out_c, hw = out_h * out_w;
+      S.head_bn.x = x; S.head_bn.mean.resize(C); S.head_bn.invstd.resize(C);
+      S.head_a.resize(x.size());
+      bn_relu_fwd(x.data(), P + head_bn.g, P + head_bn.b, S.head_a.data(), S.head_bn.mean.data(),
+                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode);
+      S.g.resize((size_t)b * C); S.dlogits.resize((size_t)b * d.num_classes);
+      const double l = head_fwd(S.head_a.data(), P + wfc, P + bfc, labels, S.g.data(), S.dlogits.data(),
+                                b, hw, C, d.num_classes, (double)d.loss_divisor);
+      if (loss_accum) *loss_accum += l;
+    } else {
+      std::memcpy(act_out, x.data(), x.size() * sizeof(T));
+    }
+    S.fwd_done = true;
+    return OK;
+  }
+
+  int backward(int mb, const T* err_in, T* err_out) {
+    if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
+    MbStash<T>& S = st[mb];
+    if (!S.fwd_done || S.bwd_done) return E_STATE;
+    const int b = d.microbatch;
+    const T* P = params.data();
+    double* G = grad.data();
+    std::vector<T> dy;   // gradient w.r.t. the current unit's output
+    if (d.has_head) {
+      const int C = out_c, hw = out_h * out_w;
+      std::vector<T> da((size_t)b * hw * C);
+      head_bwd(S.g.data(), S.dlogits.data(), P + wfc, G + wfc, G + bfc, da.data(), b, hw, C, d.num_classes);
+      dy.resize(da.size());
+      bn_relu_bwd(S.head_bn.x.data(), da.data(), P + head_bn.g, P + head_bn.b, S.head_bn.mean.data(),
+                  S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode);
+    } else {
+      dy.assign(err_in, err_in + (size_t)b * out_h * out_w * out_c);
+    }
+    for (size_t ii = bp.size(); ii-- > 0;) {
+      const BlockP& p = bp[ii]; BlockStash<T>& B = S.blk[ii];
+      const size_t M_in = (size_t)b * p.h_in * p.w_in, M_out = (size_t)b * p.h_out * p.w_out;
+      // residual branch, last conv to first
+      std::vector<T> dr = dy;
+      for (int j = p.nconv - 1; j >= 1; --j) {
+        conv_wgrad(B.a[j].data(), dr.data(), G + p.cv[j].w, b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
+        std::vector<T> da(M_out * p.cv[j].cin);
+        conv_dgrad(dr.data(), P + p.cv[j].w, da.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
+        std::vector<T> dx(da.size());
+        bn_relu_bwd(B.bn[j].x.data(), da.data(), P + p.bn[j].g, P + p.bn[j].b, B.bn[j].mean.data(),
+                    B.bn[j].invstd.data(), dx.data(), G + p.bn[j].g, G + p.bn[j].b, M_out, p.bn[j].c, d.bn_mode);
+        dr.swap(dx);
+      }
+      conv_wgrad(B.a[0].data(), dr.data(), G + p.cv[0].w, b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
+      std::vector<T> da(M_in * p.d.c_in);
+      conv_dgrad(dr.data(), P + p.cv[0].w, da.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
+      if (p.proj) {
+        conv_wgrad(B.a[0].data(), dy.data(), G + p.pj.w, b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+        std::vector<T> da2(da.size());
+        conv_dgrad(dy.data(), P + p.pj.w, da2.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+        for (size_t e = 0; e < da.size(); ++e) da[e] = (T)((double)da[e] + (double)da2[e]);
+      }
+      std::vector<T> dx(da.size());
+      bn_relu_bwd(B.bn[0].x.data(), da.data(), P + p.bn[0].g, P + p.bn[0].b, B.bn[0].mean.data(),
+                  B.bn[0].invstd.data(), dx.data(), G + p.bn[0].g, G + p.bn[0].b, M_in, p.bn[0].c, d.bn_mode);
+      if (!p.proj)
+        for (size_t e = 0; e < dx.size(); ++e) dx[e] = (T)((double)dx[e] + (double)dy[e]);
+      dy.swap(dx);
+    }
+    if (d.has_stem) {
+      conv_wgrad(S.stem_in.data(), dy.data(), G + stem_w, b, d.in_h, d.in_w, d.in_c, d.stem_c_out, 3, 1);
+      if (err_out) conv_dgrad(dy.data(), P + stem_w, err_out, b, d.in_h, d.in_w, d.in_c, d.stem_c_out, 3, 1);
+    } else if (err_out) {
+      std::memcpy(err_out, dy.data(), dy.size() * sizeof(T));
+    }
+    S.bwd_done = true; ++n_bwd_done;
+    S.blk.clear(); S.blk.shrink_to_fit();
+    return OK;
+  }
+
+  int grad_read(T* dst, size_t n) {
+    if (n != grad.size()) return E_INVAL;
+    for (size_t i = 0; i < n; ++i) dst[i] = (T)grad[i];
+    return OK;
+  }
+
+  void new_step() {
+    for (auto& s : st) { s.fwd_done = s.bwd_done = false; }
+    n_bwd_done = 0;
+  }
+
+  // v <- mu*v + G; w <- w - lr*v; then the gradient buffer is cleared and a new step begins.
+  int sgd_step(double lr, double mu) {
+    if (n_bwd_done != d.num_microbatches) return E_STATE;
+    for (size_t i = 0; i < params.size(); ++i) {
+      const double v = mu * (double)momentum[i] + grad[i];
+      momentum[i] = (T)v;
+      params[i] = (T)((double)params[i] - lr * v);
+      grad[i] = 0.0;
+    }
+    new_step();
+    return OK;
+  }
+};
+
+struct Handle {
+  bool f64;
+  std::unique_ptr<Partition<float>> pf;
+  std::unique_ptr<Partition<double>> pd;
+};
+
+bool valid(const Desc& d) {
+  if (d.in_h <= 0 || d.in_w <= 0 || d.in_c <= 0 || d.microbatch <= 0 || d.num_microbatches <= 0) return false;
+  if (d.loss_divisor <= 0 || d.n_blocks < 0) return false;
+  if (!d.has_stem && !d.has_head && d.n_blocks == 0) return false;
+  int h = d.in_h, w = d.in_w, c = d.has_stem ? d.stem_c_out : d.in_c;
+  if (d.has_stem && d.stem_c_out <= 0) return false;
+  for (auto& b : d.blocks) {
+    if (b.kind != 0 && b.kind != 1) return false;
+    if (b.c_in != c || b.c_mid <= 0 || b.c_out <= 0) return false;
+    if (b.kind == 0 && b.c_mid != b.c_out) return false;
+    if (b.stride != 1 && b.stride != 2) return false;
+    if (h % b.stride || w % b.stride) return false;
+    h /= b.stride; w /= b.stride; c = b.c_out;
+  }
+  if (d.has_head && d.num_classes <= 0) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+// desc_i: in_h,in_w,in_c,has_stem,stem_c_out,n_blocks,has_head,num_classes,microbatch,
+//         num_microbatches,loss_divisor,bn_mode ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
+void* oracle_partition_create(const int32_t* desc_i, double bn_eps, const int32_t* blocks,
+                              const void* host_params, int is_f64) {
+  Desc d;
+  d.in_h = desc_i[0]; d.in_w = desc_i[1]; d.in_c = desc_i[2]; d.has_stem = desc_i[3];
+  d.stem_c_out = desc_i[4]; d.n_blocks = desc_i[5]; d.has_head = desc_i[6]; d.num_classes = desc_i[7];
+  d.microbatch = desc_i[8]; d.num_microbatches = desc_i[9]; d.loss_divisor = desc_i[10]; d.bn_mode = desc_i[11];
+  d.bn_eps = bn_eps;
+  for (int i = 0; i < d.n_blocks; ++i)
+    d.blocks.push_back(BlockDesc{blocks[5 * i], blocks[5 * i + 1], blocks[5 * i + 2], blocks[5 * i + 3], blocks[5 * i + 4]});
+  if (!valid(d)) return nullptr;
+  Handle* h = new Handle();
+  h->f64 = is_f64 != 0;
+  if (h->f64) h->pd.reset(new Partition<double>(d, (const double*)host_params));
+  else h->pf.reset(new Partition<float>(d, (const float*)host_params));
+  return h;
+}
+
+void oracle_partition_destroy(void* hp) { delete (Handle*)hp; }
+
+size_t oracle_n_params(void* hp) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->params.size() : h->pf->params.size();
+}
+
+int oracle_forward_microbatch(void* hp, int mb, const void* act_in, const int32_t* labels, void* act_out,
+                              double* loss_accum) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->forward(mb, (const double*)act_in, labels, (double*)act_out, loss_accum)
+                : h->pf->forward(mb, (const float*)act_in, labels, (float*)act_out, loss_accum);
+}
+
+int oracle_backward_microbatch(void* hp, int mb, const void* err_in, void* err_out) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->backward(mb, (const double*)err_in, (double*)err_out)
+                : h->pf->backward(mb, (const float*)err_in, (float*)err_out);
+}
+
+int oracle_grad_accum_read(void* hp, void* dst, size_t n) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->grad_read((double*)dst, n) : h->pf->grad_read((float*)dst, n);
+}
+
+int oracle_sgd_step(void* hp, double lr, double mu) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->sgd_step(lr, mu) : h->pf->sgd_step(lr, mu);
+}
+
+// Clears the accumulated gradients and begins a new batch (all micro-batches may run again).
+int oracle_grad_accum_zero(void* hp) {
+  Handle* h = (Handle*)hp;
+  if (h->f64) { std::fill(h->pd->grad.begin(), h->pd->grad.end(), 0.0); h->pd->new_step(); }
+  else { std::fill(h->pf->grad.begin(), h->pf->grad.end(), 0.0); h->pf->new_step(); }
+  return OK;
+}
+
+int oracle_params_read(void* hp, void* dst, size_t n) {
+  Handle* h = (Handle*)hp;
+  if (n != oracle_n_params(hp)) return E_INVAL;
+  if (h->f64) std::memcpy(dst, h->pd->params.data(), n * sizeof(double));
+  else std::memcpy(dst, h->pf->params.data(), n * sizeof(float));
+  return OK;
+}
+
+int oracle_params_write(void* hp, const void* src, size_t n) {
+  Handle* h = (Handle*)hp;
+  if (n != oracle_n_params(hp)) return E_INVAL;
+  if (h->f64) std::memcpy(h->pd->params.data(), src, n * sizeof(double));
+  else std::memcpy(h->pf->params.data(), src, n * sizeof(float));
+  return OK;
+}
+
+#define ORACLE_OPS(SUF, T)                                                                              \
+  void oracle_conv_fwd_##SUF(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int cout,     \
+                             int R, int st) { conv_fwd<T>(x, w, y, n, h, wd, cin, cout, R, st); }       \
+  void oracle_conv_dgrad_##SUF(const T* dy, const T* w, T* dx, int n, int h, int wd, int cin, int cout, \
+                               int R, int st) { conv_dgrad<T>(dy, w, dx, n, h, wd, cin, cout, R, st); } \
+  void oracle_conv_wgrad_##SUF(const T* x, const T* dy, double* dw, int n, int h, int wd, int cin,      \
+                               int cout, int R, int st) {                                               \
+    conv_wgrad<T>(x, dy, dw, n, h, wd, cin, cout, R, st); }                                             \
+  void oracle_bn_relu_fwd_##SUF(const T* x, const T* g, const T* b, T* a, double* mean, double* invstd, \
+                                size_t M, int C, double eps, int mode) {                                \
+    bn_relu_fwd<T>(x, g, b, a, mean, invstd, M, C, eps, mode); }                                        \
+  void oracle_bn_relu_bwd_##SUF(const T* x, const T* da, const T* g, const T* b, const double* mean,    \
+                                const double* invstd, T* dx, double* dg, double* db, size_t M, int C,   \
+                                int mode) {                                                             \
+    bn_relu_bwd<T>(x, da, g, b, mean, invstd, dx, dg, db, M, C, mode); }                                \
+  double oracle_head_fwd_##SUF(const T* a, const T* wfc, const T* bfc, const int32_t* labels, T* g,     \
+                               T* dlogits, int n, int hw, int C, int classes, double divisor) {         \
+    return head_fwd<T>(a, wfc, bfc, labels, g, dlogits, n, hw, C, classes, divisor); }                  \
+  void oracle_head_bwd_##SUF(const T* g, const T* dl, const T* wfc, double* dwfc, double* dbfc, T* da,  \
+                             int n, int hw, int C, int classes) {                                       \
+    head_bwd<T>(g, dl, wfc, dwfc, dbfc, da, n, hw, C, classes); }
+
+ORACLE_OPS(f32, float)
+ORACLE_OPS(f64, double)
+
+}  // extern "C"

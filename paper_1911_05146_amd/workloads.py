@@ -1,0 +1,292 @@
+"""Partition descriptions and seeded synthetic inputs.
+
+This module describes WHAT is run (which residual blocks a partition holds,
+tensor shapes, the canonical flat parameter order) and draws the seeded random
+tensors that are handed, unchanged, both to the CPU oracle and to the HIP
+library.  It contains none of the method's arithmetic and imports neither of
+them.
+
+The workloads are the model partitions of HyPar-Flow-style model-parallel
+training (paper Section "Designing Distributed Model Representation" and the
+ResNet experiments of "Model-Parallelism on a Single Node"): a deep
+pre-activation ResNet is cut into contiguous partitions at residual-block
+boundaries, each batch is cut into micro-batches ("pipeline stages", Section
+"Exploiting Pipeline Stages within Each Minibatch"), and one partition's share
+of the work is run with seeded tensors standing in for what the neighbouring
+partitions would send.  Images have the 32x32x3 and 224x224x3 shapes of the
+CIFAR-10 / ImageNet-style inputs the paper's models take; the values are
+N(0,1) noise, not dataset items.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+BASIC = 0
+BOTTLENECK = 1
+
+SEED_BASE = 191105146
+
+
+@dataclass(frozen=True)
+class Block:
+    """One pre-activation residual block.
+
+    kind BASIC:      bn-relu-conv3x3(stride) - bn-relu-conv3x3, c_mid == c_out
+    kind BOTTLENECK: bn-relu-conv1x1(stride) - bn-relu-conv3x3 - bn-relu-conv1x1
+    A 1x1 projection shortcut (same stride) exists iff stride != 1 or c_in != c_out.
+    """
+    kind: int
+    c_in: int
+    c_mid: int
+    c_out: int
+    stride: int
+
+    @property
+    def has_proj(self) -> bool:
+        return self.stride != 1 or self.c_in != self.c_out
+
+
+@dataclass(frozen=True)
+class PartitionSpec:
+    name: str
+    in_h: int
+    in_w: int
+    in_c: int
+    blocks: Tuple[Block, ...]
+    has_stem: bool = False
+    stem_c_out: int = 0
+    has_head: bool = False
+    num_classes: int = 0
+    microbatch: int = 1
+    num_microbatches: int = 1
+    loss_divisor: int = 0          # full batch B; 0 -> microbatch * num_microbatches
+    bn_eps: float = 1e-5
+    bn_mode: int = 0               # 0: statistics of the micro-batch, 1: frozen mean 0 / var 1
+    seed: int = SEED_BASE
+
+    @property
+    def batch(self) -> int:
+        return self.microbatch * self.num_microbatches
+
+    @property
+    def divisor(self) -> int:
+        return self.loss_divisor if self.loss_divisor > 0 else self.batch
+
+    def out_shape(self) -> Tuple[int, int, int]:
+        """(H, W, C) of the tensor leaving the last residual block."""
+        h, w = self.in_h, self.in_w
+        c = self.stem_c_out if self.has_stem else self.in_c
+        for b in self.blocks:
+            assert b.c_in == c, (self.name, b, c)
+            h, w, c = h // b.stride, w // b.stride, b.c_out
+        return h, w, c
+
+
+# ----------------------------------------------------------------------------
+# model families
+# ----------------------------------------------------------------------------
+def basic_resnet_blocks(n_per_stage: int, widths=(16, 32, 64)) -> List[Block]:
+    blocks, c = [], widths[0]
+    for s, wdt in enumerate(widths):
+        for i in range(n_per_stage):
+            stride = 2 if (s > 0 and i == 0) else 1
+            blocks.append(Block(BASIC, c, wdt, wdt, stride))
+            c = wdt
+    return blocks
+
+
+def bottleneck_resnet_blocks(n_per_stage, mids, outs, c0, first_stride=1) -> List[Block]:
+    blocks, c = [], c0
+    if isinstance(n_per_stage, int):
+        n_per_stage = [n_per_stage] * len(mids)
+    for s, (n, mid, out) in enumerate(zip(n_per_stage, mids, outs)):
+        for i in range(n):
+            stride = 1
+            if i == 0:
+                stride = first_stride if s == 0 else 2
+            blocks.append(Block(BOTTLENECK, c, mid, out, stride))
+            c = out
+    return blocks
+
+
+def split_range(n_blocks: int, n_parts: int, p: int) -> Tuple[int, int]:
+    """Even split of blocks over partitions: partition p holds [lo, hi)."""
+    return (p * n_blocks) // n_parts, ((p + 1) * n_blocks) // n_parts
+
+
+def partition_of(name, all_blocks, n_parts, p, in_hw, in_c0, stem_c, classes,
+                 microbatch, num_microbatches, seed, in_c_img=3) -> PartitionSpec:
+    """Partition p (0-based) of n_parts of a stem + blocks + head model."""
+    lo, hi = split_range(len(all_blocks), n_parts, p)
+    h = w = in_hw
+    for b in all_blocks[:lo]:
+        h, w = h // b.stride, w // b.stride
+    first, last = (p == 0), (p == n_parts - 1)
+    return PartitionSpec(
+        name=name, in_h=h, in_w=w,
+        in_c=in_c_img if first else all_blocks[lo].c_in,
+        blocks=tuple(all_blocks[lo:hi]),
+        has_stem=first, stem_c_out=stem_c if first else 0,
+        has_head=last, num_classes=classes if last else 0,
+        microbatch=microbatch, num_microbatches=num_microbatches, seed=seed)
+
+
+def resnet20(microbatch=4, num_microbatches=2, seed=SEED_BASE + 1) -> PartitionSpec:
+    return partition_of("resnet20-whole", basic_resnet_blocks(3), 1, 0, 32, 16, 16, 10,
+                        microbatch, num_microbatches, seed)
+
+
+def resnet110_partition(p=2, n_parts=4, microbatch=16, num_microbatches=8,
+                        seed=SEED_BASE + 2) -> PartitionSpec:
+    return partition_of(f"resnet110-part{p}of{n_parts}", basic_resnet_blocks(18), n_parts, p,
+                        32, 16, 16, 10, microbatch, num_microbatches, seed)
+
+
+def resnet1001_blocks() -> List[Block]:
+    return bottleneck_resnet_blocks(111, (16, 32, 64), (64, 128, 256), 16)
+
+
+def resnet1001_partition(p=7, n_parts=16, microbatch=32, num_microbatches=8,
+                         seed=SEED_BASE + 3) -> PartitionSpec:
+    return partition_of(f"resnet1001-part{p}of{n_parts}", resnet1001_blocks(), n_parts, p,
+                        32, 16, 16, 10, microbatch, num_microbatches, seed)
+
+
+def resnet1001_whole(microbatch=8, num_microbatches=8, seed=SEED_BASE + 4) -> PartitionSpec:
+    return partition_of("resnet1001-whole", resnet1001_blocks(), 1, 0, 32, 16, 16, 10,
+                        microbatch, num_microbatches, seed)
+
+
+def resnet152_stage3(n_blocks=36, microbatch=16, num_microbatches=4,
+                     seed=SEED_BASE + 5) -> PartitionSpec:
+    blocks = [Block(BOTTLENECK, 512, 256, 1024, 2)]
+    blocks += [Block(BOTTLENECK, 1024, 256, 1024, 1)] * (n_blocks - 1)
+    return PartitionSpec(name=f"resnet152v2-stage3-{n_blocks}blocks", in_h=28, in_w=28, in_c=512,
+                         blocks=tuple(blocks), microbatch=microbatch,
+                         num_microbatches=num_microbatches, seed=seed)
+
+
+def config(index: int) -> PartitionSpec:
+    """The five benchmark configurations, numbered 1..5."""
+    return {1: resnet20, 2: resnet110_partition, 3: resnet1001_partition,
+            4: resnet1001_whole, 5: resnet152_stage3}[index]()
+
+
+def with_microbatching(spec: PartitionSpec, microbatch: int, num_microbatches: int,
+                       **kw) -> PartitionSpec:
+    kw.setdefault("loss_divisor", 0)
+    return replace(spec, microbatch=microbatch, num_microbatches=num_microbatches, **kw)
+
+
+# ----------------------------------------------------------------------------
+# canonical flat parameter order
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class ParamEntry:
+    name: str
+    shape: Tuple[int, ...]
+    kind: str          # "conv" (HWIO), "gamma", "beta", "fc" ([C][classes]), "bias"
+    offset: int
+
+    @property
+    def size(self) -> int:
+        return int(np.prod(self.shape))
+
+
+def param_layout(spec: PartitionSpec) -> List[ParamEntry]:
+    """Units in model order; stem W; per block bn1.g, bn1.b, W1, bn2.g, bn2.b, W2,
+    [bn3.g, bn3.b, W3], [Wproj]; head bn.g, bn.b, Wfc, bfc.  Conv weights are
+    [R][S][Cin][Cout]."""
+    out: List[ParamEntry] = []
+    off = 0
+
+    def add(name, shape, kind):
+        nonlocal off
+        e = ParamEntry(name, tuple(shape), kind, off)
+        out.append(e)
+        off += e.size
+
+    if spec.has_stem:
+        add("stem.W", (3, 3, spec.in_c, spec.stem_c_out), "conv")
+    for i, b in enumerate(spec.blocks):
+        p = f"block{i}."
+        add(p + "bn1.gamma", (b.c_in,), "gamma")
+        add(p + "bn1.beta", (b.c_in,), "beta")
+        if b.kind == BASIC:
+            add(p + "W1", (3, 3, b.c_in, b.c_mid), "conv")
+            add(p + "bn2.gamma", (b.c_mid,), "gamma")
+            add(p + "bn2.beta", (b.c_mid,), "beta")
+            add(p + "W2", (3, 3, b.c_mid, b.c_out), "conv")
+        else:
+            add(p + "W1", (1, 1, b.c_in, b.c_mid), "conv")
+            add(p + "bn2.gamma", (b.c_mid,), "gamma")
+            add(p + "bn2.beta", (b.c_mid,), "beta")
+            add(p + "W2", (3, 3, b.c_mid, b.c_mid), "conv")
+            add(p + "bn3.gamma", (b.c_mid,), "gamma")
+            add(p + "bn3.beta", (b.c_mid,), "beta")
+            add(p + "W3", (1, 1, b.c_mid, b.c_out), "conv")
+        if b.has_proj:
+            add(p + "Wproj", (1, 1, b.c_in, b.c_out), "conv")
+    if spec.has_head:
+        c = spec.out_shape()[2]
+        add("head.bn.gamma", (c,), "gamma")
+        add("head.bn.beta", (c,), "beta")
+        add("head.Wfc", (c, spec.num_classes), "fc")
+        add("head.bfc", (spec.num_classes,), "bias")
+    return out
+
+
+def n_params(spec: PartitionSpec) -> int:
+    lay = param_layout(spec)
+    return lay[-1].offset + lay[-1].size if lay else 0
+
+
+# ----------------------------------------------------------------------------
+# seeded tensors
+# ----------------------------------------------------------------------------
+@dataclass
+class StepInputs:
+    params: np.ndarray                       # [P] float32, canonical order
+    act_in: List[np.ndarray]                 # per micro-batch [b,H,W,C] float32
+    labels: Optional[List[np.ndarray]]       # per micro-batch [b] int32 (head only)
+    err_in: Optional[List[np.ndarray]]       # per micro-batch [b,H',W',C'] float32 (no head)
+
+
+def make_params(spec: PartitionSpec, rng: np.random.Generator,
+                randomize_affine: bool = False) -> np.ndarray:
+    """He-normal conv/FC weights N(0, 2/fan_in), gamma=1, beta=0, bias=0.
+    randomize_affine draws gamma ~ U(0.5,1.5), beta, bias ~ N(0,0.1) instead
+    (used by tests so that no term is hidden by a neutral value)."""
+    flat = np.empty(n_params(spec), dtype=np.float32)
+    for e in param_layout(spec):
+        sl = slice(e.offset, e.offset + e.size)
+        if e.kind in ("conv", "fc"):
+            fan_in = int(np.prod(e.shape[:-1]))
+            flat[sl] = rng.normal(0.0, np.sqrt(2.0 / fan_in), e.size).astype(np.float32)
+        elif e.kind == "gamma":
+            flat[sl] = rng.uniform(0.5, 1.5, e.size) if randomize_affine else 1.0
+        else:
+            flat[sl] = rng.normal(0.0, 0.1, e.size) if randomize_affine else 0.0
+    return flat
+
+
+def make_inputs(spec: PartitionSpec, randomize_affine: bool = False) -> StepInputs:
+    """Draw order: parameters in canonical order, then per micro-batch in index
+    order: act_in ~ N(0,1); labels uniform in [0, classes) if the partition has
+    the head, else err_in ~ N(0, variance 1e-2) with the shape of act_out."""
+    rng = np.random.default_rng(spec.seed)
+    params = make_params(spec, rng, randomize_affine)
+    b = spec.microbatch
+    oh, ow, oc = spec.out_shape()
+    act_in, labels, err_in = [], [], []
+    for _ in range(spec.num_microbatches):
+        act_in.append(rng.standard_normal((b, spec.in_h, spec.in_w, spec.in_c), dtype=np.float32))
+        if spec.has_head:
+            labels.append(rng.integers(0, spec.num_classes, size=b, dtype=np.int32))
+        else:
+            err_in.append((0.1 * rng.standard_normal((b, oh, ow, oc), dtype=np.float32)))
+    return StepInputs(params, act_in, labels if spec.has_head else None,
+                      None if spec.has_head else err_in)
