@@ -1,0 +1,181 @@
+/*
+ * hpf.h -- C ABI of the MI355X partition engine.
+ *
+ * One handle = one contiguous model partition of a pre-activation ResNet in HyPar-Flow-style
+ * model/hybrid-parallel training, at one GPU's share of the work.  Per batch the caller runs, for
+ * every micro-batch ("pipeline stage", paper Section "Exploiting Pipeline Stages within Each
+ * Minibatch"), one forward call that consumes the activations the previous partition would send
+ * and produces those for the next partition (paper Section "Realizing Inter-Partition/-Replica
+ * Comm.", basic design: send/recv of partial predictions), and one backward call that consumes
+ * the partial error the next partition would send and produces the partial error for the previous
+ * partition (the "grad layer" result of Section "Implementing Distributed Back-Propagation",
+ * Eq. 5-7).  Weight gradients of all micro-batches are summed into one fp32 buffer -- the buffer
+ * the per-partition allreduce of the hybrid design would consume -- and applied once per batch
+ * (synchronous update, Section "Background"; optimizer.apply_gradients, Eq. 5-7 section).
+ *
+ * Conventions
+ *  - All pointers marked (dev) are raw device addresses on the current HIP device; (host) are
+ *    host addresses.  Streams are hipStream_t passed as void* (NULL = the default stream).
+ *  - The caller owns every device buffer, including the arena from which the library carves its
+ *    parameters, gradients, momentum, stashed activations and scratch.  The library calls no
+ *    hipMalloc.  The library owns only the host-side handle.
+ *  - Activations are NHWC.  Convolution weights are [R][S][Cin][Cout] fp32 in the flat parameter
+ *    vector.  Canonical flat parameter / gradient order: stem W; per block bn1.gamma, bn1.beta,
+ *    W1, bn2.gamma, bn2.beta, W2, [bn3.gamma, bn3.beta, W3], [Wproj]; head bn.gamma, bn.beta,
+ *    Wfc [C][classes], bfc.
+ *  - forward / backward / grad_accum_zero / sgd_step only enqueue work and return; ordering
+ *    between calls issued on different streams (micro-batches may each use their own stream) is
+ *    handled inside the library with events.  grad_accum_read to host memory blocks until done.
+ *  - Every call returns a status; nothing throws or aborts.  A call that returns HPF_EINVAL,
+ *    HPF_ESTATE or HPF_EUNSUPPORTED has had no effect.  hpf_last_error() gives a message.
+ *  - Call order per batch (else HPF_ESTATE): forward(mb) once, then backward(mb) once, for every
+ *    mb in [0, num_microbatches) in any interleaving; then grad_accum_read any number of times;
+ *    then sgd_step (applies and clears the gradients) or grad_accum_zero (clears them) starts the
+ *    next batch.
+ *  - A handle is not thread-safe; use one host thread per handle.
+ */
+#ifndef HPF_H
+#define HPF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HPF_ABI_VERSION 1u
+
+typedef struct hpf_partition hpf_partition; /* opaque, owned by the library */
+
+typedef enum {
+  HPF_OK = 0,
+  HPF_EINVAL = 1,       /* bad argument or descriptor */
+  HPF_ESTATE = 2,       /* call order violated */
+  HPF_ENOMEM = 3,       /* arena too small */
+  HPF_EDEVICE = 4,      /* a HIP call failed */
+  HPF_EUNSUPPORTED = 5  /* valid description this build has no kernels for */
+} hpf_status;
+
+typedef enum {
+  HPF_F32 = 0, /* check mode: fp32 tensors, fp32 FMA convolutions */
+  HPF_BF16 = 1 /* bf16 tensors and MFMA operands, fp32 accumulation, fp32 statistics/gradients */
+} hpf_dtype;
+
+/* One pre-activation residual block.
+ * kind 0 (basic):      bn-relu-conv3x3(stride) -> bn-relu-conv3x3;            c_mid must equal c_out
+ * kind 1 (bottleneck): bn-relu-conv1x1(stride) -> bn-relu-conv3x3 -> bn-relu-conv1x1
+ * Shortcut: identity if stride == 1 and c_in == c_out, else a 1x1 convolution (same stride) of the
+ * block's first bn-relu output.  3x3 convolutions use symmetric zero padding 1; no conv bias. */
+typedef struct {
+  int32_t kind;
+  int32_t c_in, c_mid, c_out;
+  int32_t stride; /* 1 or 2 */
+} hpf_block_desc;
+
+typedef struct {
+  uint32_t abi_version;           /* HPF_ABI_VERSION */
+  int32_t in_h, in_w, in_c;       /* shape of act_in per image */
+  int32_t has_stem, stem_c_out;   /* first partition: 3x3 stride-1 conv in_c -> stem_c_out */
+  int32_t n_blocks;
+  const hpf_block_desc* blocks;   /* (host) n_blocks entries, copied */
+  int32_t has_head, num_classes;  /* last partition: bn-relu, global average pool, FC+bias, softmax-CE */
+  int32_t microbatch;             /* images per micro-batch */
+  int32_t num_microbatches;       /* micro-batches per batch */
+  int32_t loss_divisor;           /* full batch size B: loss = sum over samples of CE / B */
+  hpf_dtype compute_dtype;        /* dtype of interior boundary tensors, stash and conv operands */
+  float bn_eps;
+  int32_t bn_mode;                /* 0: statistics of the micro-batch; 1: frozen mean 0, variance 1 */
+} hpf_partition_desc;
+
+typedef struct {
+  size_t n_params;       /* floats in the flat parameter / gradient vector */
+  size_t arena_bytes;    /* device bytes hpf_partition_create needs (256-byte aligned base) */
+  size_t stash_bytes;    /* part of arena_bytes: stashed activations of all micro-batches */
+  size_t act_in_elems;   /* elements per micro-batch of act_in / err_out */
+  size_t act_out_elems;  /* elements per micro-batch of act_out / err_in (0 if has_head) */
+} hpf_sizes;
+
+/* Validates the description and reports sizes.  No device work. */
+hpf_status hpf_partition_sizes(const hpf_partition_desc* desc, hpf_sizes* out);
+
+/* Builds a partition inside `device_arena` (dev, >= arena_bytes, 256-byte aligned).  host_params
+ * (host): n_params fp32 values in canonical order, copied.  Gradients and momentum start at zero.
+ * Synchronous.  The arena must outlive the handle. */
+hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_arena, size_t arena_bytes,
+                                const float* host_params, hpf_partition** out);
+
+/* Forward of micro-batch mb.
+ *  act_in  (dev) [microbatch, in_h, in_w, in_c]; fp32 if has_stem, else compute_dtype.  It is read
+ *          again by backward(mb) and must stay valid and unchanged until that call's work is done.
+ *  labels  (dev) [microbatch] int32 in [0, num_classes); required iff has_head.
+ *  act_out (dev) [microbatch, out_h, out_w, out_c] compute_dtype; required iff !has_head.
+ *  loss_accum (dev) one float, atomically incremented by this micro-batch's share of the loss;
+ *          required iff has_head. */
+hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels,
+                                  void* act_out, float* loss_accum, void* hip_stream);
+
+/* Backward of micro-batch mb (after its forward).
+ *  err_in  (dev) gradient of the loss w.r.t. act_out, same shape/dtype; required iff !has_head.
+ *  err_out (dev) gradient w.r.t. act_in, compute_dtype, shape of act_in; required iff !has_stem,
+ *          must be NULL if has_stem (images have no upstream partition).
+ * Adds this micro-batch's weight gradients into the fp32 gradient buffer. */
+hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out,
+                                   void* hip_stream);
+
+/* Copies the accumulated gradient (n_params floats) to dst after all backward work issued so far.
+ * dst_is_device != 0: dst is (dev) and the copy is enqueued on hip_stream; else dst is (host) and
+ * the call blocks until the copy is complete.  Needs all micro-batches' backward calls. */
+hpf_status hpf_grad_accum_read(hpf_partition* p, float* dst, size_t n_floats, int32_t dst_is_device,
+                               void* hip_stream);
+
+/* Clears the gradient buffer and starts the next batch without updating the weights. */
+hpf_status hpf_grad_accum_zero(hpf_partition* p, void* hip_stream);
+
+/* v <- momentum*v + G; w <- w - lr*v on the fp32 masters (all parameters, BN and bias included);
+ * refreshes the bf16 weight copies; clears G; starts the next batch.  Needs all backward calls. */
+hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_stream);
+
+/* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
+hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
+
+/* Frees the host-side handle (after synchronising the device).  The arena is the caller's. */
+void hpf_partition_destroy(hpf_partition* p);
+
+/* ---- Single-kernel entry points ------------------------------------------------------------
+ * The kernels the partition schedule is made of, callable one at a time on caller tensors, for
+ * kernel-level parity tests and roofline measurements.  All pointers (dev); tensors NHWC of `dtype`
+ * (fp32 or bf16 bits); weights and weight gradients fp32 [R][R][Cin][Cout]; statistics fp32.
+ * `workspace` (dev, 256-byte aligned) holds packed bf16 weights / reduction partials; its size
+ * comes from hpf_op_workspace_bytes.  Work is enqueued on hip_stream.  Convolution layers and
+ * their gradients: paper Section "Background" (DNN training) and Eq. 5-7. */
+size_t hpf_op_workspace_bytes(int32_t cin, int32_t cout, int32_t R);
+
+/* y[b,h/stride,w/stride,cout] = conv(x[b,h,w,cin], w) (+ add, same shape as y, may alias y). */
+hpf_status hpf_op_conv_forward(hpf_dtype dtype, const void* x, const float* w, void* y, const void* add,
+                               int32_t b, int32_t h, int32_t wd, int32_t cin, int32_t cout, int32_t R,
+                               int32_t stride, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* dx[b,h,w,cin] = adjoint of the convolution applied to dy[b,h/stride,w/stride,cout] (+ add). */
+hpf_status hpf_op_conv_dgrad(hpf_dtype dtype, const void* dy, const float* w, void* dx, const void* add,
+                             int32_t b, int32_t h, int32_t wd, int32_t cin, int32_t cout, int32_t R,
+                             int32_t stride, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* dw[R][R][cin][cout] (fp32) += sum over pixels of x (x) dy. */
+hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, float* dw, int32_t b, int32_t h,
+                             int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* hip_stream);
+/* stats[2C] = {mean, 1/sqrt(var+eps)} of x[M,C]; a = max(gamma*xhat + beta, 0). */
+hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* gamma, const float* beta,
+                                  float eps, void* a, float* stats, int32_t M, int32_t C, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+/* dgamma[C], dbeta[C] += reductions; dx = BN+ReLU backward of da (+ skip if non-NULL). */
+hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* da, const float* gamma,
+                                   const float* beta, const float* stats, const void* skip, void* dx,
+                                   float* dgamma, float* dbeta, int32_t M, int32_t C, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
+/* Message for the last non-OK status on this thread (static storage, never NULL). */
+const char* hpf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPF_H */

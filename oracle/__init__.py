@@ -48,13 +48,15 @@ def lib():
         L.oracle_sgd_step.argtypes = [C.c_void_p, C.c_double, C.c_double]
         L.oracle_params_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.oracle_params_write.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+        L.oracle_round_bf16.argtypes = [C.c_float]
+        L.oracle_round_bf16.restype = C.c_float
         for suf in ("f32", "f64"):
             i, d, p, z = C.c_int, C.c_double, C.c_void_p, C.c_size_t
-            getattr(L, f"oracle_conv_fwd_{suf}").argtypes = [p, p, p, i, i, i, i, i, i, i]
-            getattr(L, f"oracle_conv_dgrad_{suf}").argtypes = [p, p, p, i, i, i, i, i, i, i]
+            getattr(L, f"oracle_conv_fwd_{suf}").argtypes = [p, p, p, i, i, i, i, i, i, i, p, i]
+            getattr(L, f"oracle_conv_dgrad_{suf}").argtypes = [p, p, p, i, i, i, i, i, i, i, p, i]
             getattr(L, f"oracle_conv_wgrad_{suf}").argtypes = [p, p, p, i, i, i, i, i, i, i]
-            getattr(L, f"oracle_bn_relu_fwd_{suf}").argtypes = [p, p, p, p, p, p, z, i, d, i]
-            getattr(L, f"oracle_bn_relu_bwd_{suf}").argtypes = [p, p, p, p, p, p, p, p, p, z, i, i]
+            getattr(L, f"oracle_bn_relu_fwd_{suf}").argtypes = [p, p, p, p, p, p, z, i, d, i, i]
+            getattr(L, f"oracle_bn_relu_bwd_{suf}").argtypes = [p, p, p, p, p, p, p, p, p, z, i, i, p, i]
             getattr(L, f"oracle_head_fwd_{suf}").argtypes = [p, p, p, p, p, p, i, i, i, i, d]
             getattr(L, f"oracle_head_fwd_{suf}").restype = d
             getattr(L, f"oracle_head_bwd_{suf}").argtypes = [p, p, p, p, p, p, i, i, i, i]
@@ -83,25 +85,37 @@ def conv_out_hw(h, w, R, stride):
     return (h + 2 * pad - R) // stride + 1, (w + 2 * pad - R) // stride + 1
 
 
-def conv_fwd(x, w, stride=1):
+STORAGE = {"none": 0, "bf16": 1}
+
+
+def round_bf16(v: float) -> float:
+    """Nearest-even bfloat16 of a float32 value (the oracle's storage rounding)."""
+    return float(lib().oracle_round_bf16(float(v)))
+
+
+def conv_fwd(x, w, stride=1, add=None, storage="none"):
     dt = x.dtype
     x, w = _c(x, dt), _c(w, dt)
     n, h, wd, cin = x.shape
     R, _, _, cout = w.shape
     ho, wo = conv_out_hw(h, wd, R, stride)
     y = np.empty((n, ho, wo, cout), dt)
-    getattr(lib(), f"oracle_conv_fwd_{_suf(dt)}")(_p(x), _p(w), _p(y), n, h, wd, cin, cout, R, stride)
+    add = _c(add, dt) if add is not None else None
+    getattr(lib(), f"oracle_conv_fwd_{_suf(dt)}")(_p(x), _p(w), _p(y), n, h, wd, cin, cout, R, stride,
+                                                  _p(add), STORAGE[storage])
     return y
 
 
-def conv_dgrad(dy, w, in_hw, stride=1):
+def conv_dgrad(dy, w, in_hw, stride=1, add=None, storage="none"):
     dt = dy.dtype
     dy, w = _c(dy, dt), _c(w, dt)
     n = dy.shape[0]
     R, _, cin, cout = w.shape
     h, wd = in_hw
     dx = np.empty((n, h, wd, cin), dt)
-    getattr(lib(), f"oracle_conv_dgrad_{_suf(dt)}")(_p(dy), _p(w), _p(dx), n, h, wd, cin, cout, R, stride)
+    add = _c(add, dt) if add is not None else None
+    getattr(lib(), f"oracle_conv_dgrad_{_suf(dt)}")(_p(dy), _p(w), _p(dx), n, h, wd, cin, cout, R, stride,
+                                                    _p(add), STORAGE[storage])
     return dx
 
 
@@ -115,7 +129,7 @@ def conv_wgrad(x, dy, R, stride=1):
     return dw
 
 
-def bn_relu_fwd(x, gamma, beta, eps=1e-5, mode=0):
+def bn_relu_fwd(x, gamma, beta, eps=1e-5, mode=0, storage="none"):
     dt = x.dtype
     x, gamma, beta = _c(x, dt), _c(gamma, dt), _c(beta, dt)
     Cc = x.shape[-1]
@@ -123,11 +137,11 @@ def bn_relu_fwd(x, gamma, beta, eps=1e-5, mode=0):
     a = np.empty_like(x)
     mean, invstd = np.empty(Cc), np.empty(Cc)
     getattr(lib(), f"oracle_bn_relu_fwd_{_suf(dt)}")(_p(x), _p(gamma), _p(beta), _p(a), _p(mean), _p(invstd),
-                                                     M, Cc, eps, mode)
+                                                     M, Cc, eps, mode, STORAGE[storage])
     return a, mean, invstd
 
 
-def bn_relu_bwd(x, da, gamma, beta, mean, invstd, mode=0):
+def bn_relu_bwd(x, da, gamma, beta, mean, invstd, mode=0, skip=None, storage="none"):
     dt = x.dtype
     x, da, gamma, beta = _c(x, dt), _c(da, dt), _c(gamma, dt), _c(beta, dt)
     mean, invstd = _c(mean, np.float64), _c(invstd, np.float64)
@@ -135,8 +149,9 @@ def bn_relu_bwd(x, da, gamma, beta, mean, invstd, mode=0):
     M = x.size // Cc
     dx = np.empty_like(x)
     dg, db = np.zeros(Cc), np.zeros(Cc)
+    skip = _c(skip, dt) if skip is not None else None
     getattr(lib(), f"oracle_bn_relu_bwd_{_suf(dt)}")(_p(x), _p(da), _p(gamma), _p(beta), _p(mean), _p(invstd),
-                                                     _p(dx), _p(dg), _p(db), M, Cc, mode)
+                                                     _p(dx), _p(dg), _p(db), M, Cc, mode, _p(skip), STORAGE[storage])
     return dx, dg, db
 
 
@@ -173,14 +188,14 @@ class OraclePartition:
     """Host-pointer twin of the HIP library's partition handle.  `spec` is any object with
     the fields of workloads.PartitionSpec (duck-typed; this package imports nothing else)."""
 
-    def __init__(self, spec, params, dtype=np.float32):
+    def __init__(self, spec, params, dtype=np.float32, storage="none"):
         self.spec = spec
         self.dtype = np.dtype(dtype)
         blocks = np.array([[b.kind, b.c_in, b.c_mid, b.c_out, b.stride] for b in spec.blocks],
                           dtype=np.int32).reshape(-1, 5)
         desc = np.array([spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
                          len(spec.blocks), int(spec.has_head), spec.num_classes, spec.microbatch,
-                         spec.num_microbatches, spec.divisor, spec.bn_mode], dtype=np.int32)
+                         spec.num_microbatches, spec.divisor, spec.bn_mode, STORAGE[storage]], dtype=np.int32)
         params = _c(params, self.dtype)
         self._h = lib().oracle_partition_create(_p(desc), float(spec.bn_eps), _p(blocks), _p(params),
                                                 int(self.dtype == np.float64))
@@ -246,11 +261,11 @@ class OraclePartition:
         self._check(lib().oracle_params_write(self._h, _p(p), p.size), "params_write")
 
 
-def run_step(spec, inputs, dtype=np.float32, sgd=None):
+def run_step(spec, inputs, dtype=np.float32, sgd=None, storage="none"):
     """One batch: m forwards then m backwards (micro-batch index order).  Returns a dict with
     per-micro-batch act_out / err_out, the loss, the accumulated gradient and, when `sgd` =
     (lr, momentum) is given, the parameters after the step."""
-    part = OraclePartition(spec, inputs.params, dtype)
+    part = OraclePartition(spec, inputs.params, dtype, storage)
     outs, errs = [], []
     for i in range(spec.num_microbatches):
         outs.append(part.forward(i, inputs.act_in[i], inputs.labels[i] if inputs.labels else None))

@@ -15,6 +15,15 @@
 // T is float (the fp32 reference) or double (for finite-difference checks); every reduction
 // accumulates in double, so the reference is not the noisy side of a comparison.
 //
+// Storage reading for the GPU's bf16 mode (the paper never states a precision): with storage = 1 every
+// tensor that the bf16 mode keeps in memory as bfloat16 -- convolution operands (activations after
+// BN+ReLU, weight copies, im2col columns of the stem), convolution outputs including the residual sum,
+// and the gradient tensors flowing backward -- is rounded to the nearest-even bfloat16 at the point it
+// is produced; statistics, parameters, weight gradients, the loss and all arithmetic in between stay
+// in double.  This puts the ReLU decisions z > 0 on the same stored values on both sides of a parity
+// test (a floating-point value deciding a boolean must be decided in the same precision).  With
+// storage = 0 nothing is rounded: that is the plain reference.
+//
 // Only tests, the smoke check and the benchmark's cpu_baseline leg may call this library.  It
 // shares no code with the HIP path.
 //
@@ -33,12 +42,39 @@
 
 namespace {
 
+// Nearest-even rounding of a value to bfloat16 (8 exponent bits, 7 stored mantissa bits), returned
+// in the storage type.  st == 0: identity.
+template <class T>
+inline T rnd(T v, int st) {
+  if (!st) return v;
+  float f = (float)v;
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return v;   // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  std::memcpy(&f, &u, 4);
+  return (T)f;
+}
+
+template <class T>
+std::vector<T> rounded_copy(const T* w, size_t n, int st) {
+  std::vector<T> r(w, w + n);
+  if (st) for (auto& v : r) v = rnd(v, st);
+  return r;
+}
+
 // ------------------------------------------------------------------------------------------
 // Convolution, NHWC activations, [R][S][Cin][Cout] weights, zero padding (R-1)/2, no bias.
-// y[n,p,q,k] = sum_{r,s,c} x[n, p*st + r - pad, q*st + s - pad, c] * w[r,s,c,k]
+// y[n,p,q,k] = sum_{r,s,c} x[n, p*st + r - pad, q*st + s - pad, c] * w[r,s,c,k]  (+ add[n,p,q,k])
+// `add` (may be null, may alias y) is the shortcut of a residual block: the sum is formed before the
+// result is stored.  bf: storage reading (weights are used, and y is stored, as bfloat16).
 // ------------------------------------------------------------------------------------------
 template <class T>
-void conv_fwd(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int cout, int R, int st) {
+void conv_fwd(const T* x, const T* w_in, T* y, int n, int h, int wd, int cin, int cout, int R, int st,
+              const T* add = nullptr, int bf = 0) {
+  const std::vector<T> wq = rounded_copy(w_in, (size_t)R * R * cin * cout, bf);
+  const T* w = wq.data();
   const int pad = (R - 1) / 2;
   const int ho = (h + 2 * pad - R) / st + 1, wo = (wd + 2 * pad - R) / st + 1;
 #pragma omp parallel for collapse(2) schedule(static)
@@ -62,8 +98,8 @@ void conv_fwd(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int c
             }
           }
         }
-        T* yp = y + ((size_t)(in * ho + p) * wo + q) * cout;
-        for (int k = 0; k < cout; ++k) yp[k] = (T)acc[k];
+        const size_t o = ((size_t)(in * ho + p) * wo + q) * cout;
+        for (int k = 0; k < cout; ++k) y[o + k] = rnd((T)(acc[k] + (add ? (double)add[o + k] : 0.0)), bf);
       }
     }
 }
@@ -71,7 +107,10 @@ void conv_fwd(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int c
 // dx[n,h,w,c] = sum over (p,q,r,s,k) with p*st + r - pad == h and q*st + s - pad == w of
 //               dy[n,p,q,k] * w[r,s,c,k]          (the adjoint of conv_fwd in x)
 template <class T>
-void conv_dgrad(const T* dy, const T* w, T* dx, int n, int h, int wd, int cin, int cout, int R, int st) {
+void conv_dgrad(const T* dy, const T* w_in, T* dx, int n, int h, int wd, int cin, int cout, int R, int st,
+                const T* add = nullptr, int bf = 0) {
+  const std::vector<T> wq = rounded_copy(w_in, (size_t)R * R * cin * cout, bf);
+  const T* w = wq.data();
   const int pad = (R - 1) / 2;
   const int ho = (h + 2 * pad - R) / st + 1, wo = (wd + 2 * pad - R) / st + 1;
 #pragma omp parallel for collapse(2) schedule(static)
@@ -98,8 +137,8 @@ void conv_dgrad(const T* dy, const T* w, T* dx, int n, int h, int wd, int cin, i
             }
           }
         }
-        T* dxp = dx + ((size_t)(in * h + hi) * wd + wi) * cin;
-        for (int c = 0; c < cin; ++c) dxp[c] = (T)acc[c];
+        const size_t o = ((size_t)(in * h + hi) * wd + wi) * cin;
+        for (int c = 0; c < cin; ++c) dx[o + c] = rnd((T)(acc[c] + (add ? (double)add[o + c] : 0.0)), bf);
       }
     }
 }
@@ -138,7 +177,7 @@ void conv_wgrad(const T* x, const T* dy, double* dw, int n, int h, int wd, int c
 // ------------------------------------------------------------------------------------------
 template <class T>
 void bn_relu_fwd(const T* x, const T* gamma, const T* beta, T* a, double* mean, double* invstd,
-                 size_t M, int C, double eps, int mode) {
+                 size_t M, int C, double eps, int mode, int bf = 0) {
 #pragma omp parallel for schedule(static)
   for (int c = 0; c < C; ++c) {
     double mu = 0.0, var = 1.0;
@@ -154,18 +193,20 @@ void bn_relu_fwd(const T* x, const T* gamma, const T* beta, T* a, double* mean, 
     mean[c] = mu; invstd[c] = is;
     for (size_t m = 0; m < M; ++m) {
       const double z = (double)gamma[c] * (((double)x[m * C + c] - mu) * is) + (double)beta[c];
-      a[m * C + c] = (T)(z > 0.0 ? z : 0.0);
+      a[m * C + c] = rnd((T)(z > 0.0 ? z : 0.0), bf);
     }
   }
 }
 
 // dz = da * [z > 0]; dbeta = sum dz; dgamma = sum dz*xhat;
 // mode 0: dx = gamma*invstd * (dz - dbeta/M - xhat*dgamma/M); mode 1: dx = gamma*invstd*dz.
+// `skip` (may be null) is the gradient arriving over an identity shortcut, added before storing.
 // dgamma/dbeta are added into the accumulators.  The ReLU mask is recomputed from z as the
 // forward pass computed it (same precision, same expression).
 template <class T>
 void bn_relu_bwd(const T* x, const T* da, const T* gamma, const T* beta, const double* mean,
-                 const double* invstd, T* dx, double* dgamma, double* dbeta, size_t M, int C, int mode) {
+                 const double* invstd, T* dx, double* dgamma, double* dbeta, size_t M, int C, int mode,
+                 const T* skip = nullptr, int bf = 0) {
 #pragma omp parallel for schedule(static)
   for (int c = 0; c < C; ++c) {
     const double mu = mean[c], is = invstd[c], g = gamma[c], bt = beta[c];
@@ -182,7 +223,7 @@ void bn_relu_bwd(const T* x, const T* da, const T* gamma, const T* beta, const d
       const double z = g * xh + bt;
       const double dz = z > 0.0 ? (double)da[m * C + c] : 0.0;
       const double v = mode == 0 ? (dz - sb / (double)M - xh * sg / (double)M) : dz;
-      dx[m * C + c] = (T)(g * is * v);
+      dx[m * C + c] = rnd((T)(g * is * v + (skip ? (double)skip[m * C + c] : 0.0)), bf);
     }
   }
 }
@@ -222,7 +263,7 @@ double head_fwd(const T* a, const T* wfc, const T* bfc, const int32_t* labels, T
 // dWfc += g^T dlogits; dbfc += sum_n dlogits; dg = dlogits * Wfc^T; da[n,h,w,c] = dg[n,c]/(H*W).
 template <class T>
 void head_bwd(const T* g, const T* dlogits, const T* wfc, double* dwfc, double* dbfc, T* da,
-              int n, int hw, int C, int classes) {
+              int n, int hw, int C, int classes, int bf = 0) {
   for (int in = 0; in < n; ++in) {
     for (int j = 0; j < classes; ++j) dbfc[j] += (double)dlogits[(size_t)in * classes + j];
     for (int c = 0; c < C; ++c) {
@@ -232,7 +273,7 @@ void head_bwd(const T* g, const T* dlogits, const T* wfc, double* dwfc, double* 
         dwfc[(size_t)c * classes + j] += (double)g[(size_t)in * C + c] * d;
         dg += d * (double)wfc[(size_t)c * classes + j];
       }
-      for (int i = 0; i < hw; ++i) da[((size_t)in * hw + i) * C + c] = (T)(dg / (double)hw);
+      for (int i = 0; i < hw; ++i) da[((size_t)in * hw + i) * C + c] = rnd((T)(dg / (double)hw), bf);
     }
   }
 }
@@ -247,6 +288,7 @@ struct BlockDesc { int kind, c_in, c_mid, c_out, stride; };
 struct Desc {
   int in_h, in_w, in_c, has_stem, stem_c_out, n_blocks, has_head, num_classes;
   int microbatch, num_microbatches, loss_divisor, bn_mode;
+  int storage = 0;   // 0: nothing rounded; 1: stored tensors and conv weight operands are bfloat16
   double bn_eps;
   std::vector<BlockDesc> blocks;
 };
@@ -330,54 +372,54 @@ struct Partition {
     if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
     MbStash<T>& S = st[mb];
     if (S.fwd_done) return E_STATE;
-    const int b = d.microbatch;
+    const int b = d.microbatch, bf = d.storage;
     const T* P = params.data();
     std::vector<T> x;
     int h = d.in_h, w = d.in_w;
     if (d.has_stem) {
       S.stem_in.assign(act_in, act_in + (size_t)b * h * w * d.in_c);
+      for (auto& v : S.stem_in) v = rnd(v, bf);          // the stem's operand tensor is stored
       x.resize((size_t)b * h * w * d.stem_c_out);
-      conv_fwd(S.stem_in.data(), P + stem_w, x.data(), b, h, w, d.in_c, d.stem_c_out, 3, 1);
+      conv_fwd(S.stem_in.data(), P + stem_w, x.data(), b, h, w, d.in_c, d.stem_c_out, 3, 1, (const T*)nullptr, bf);
     } else {
       x.assign(act_in, act_in + (size_t)b * h * w * d.in_c);
     }
     S.blk.assign(bp.size(), BlockStash<T>());
     for (size_t i = 0; i < bp.size(); ++i) {
       const BlockP& p = bp[i]; BlockStash<T>& B = S.blk[i];
-      const size_t M_in = (size_t)b * p.h_in * p.w_in, M_out = (size_t)b * p.h_out * p.w_out;
-      // a = relu(bn1(x))
+      const size_t M_out = (size_t)b * p.h_out * p.w_out;
       auto bnrelu = [&](int j, std::vector<T>& in) {
         B.bn[j].x = in; B.bn[j].mean.resize(p.bn[j].c); B.bn[j].invstd.resize(p.bn[j].c);
         B.a[j].resize(in.size());
         bn_relu_fwd(in.data(), P + p.bn[j].g, P + p.bn[j].b, B.a[j].data(), B.bn[j].mean.data(),
-                    B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode);
+                    B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode, bf);
       };
-      bnrelu(0, x);
-      std::vector<T> sc;
+      bnrelu(0, x);                                        // a = relu(bn1(x))
+      std::vector<T> sc;                                   // shortcut: x, or the 1x1 projection of a
       if (p.proj) {
         sc.resize(M_out * p.d.c_out);
-        conv_fwd(B.a[0].data(), P + p.pj.w, sc.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+        conv_fwd(B.a[0].data(), P + p.pj.w, sc.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st,
+                 (const T*)nullptr, bf);
       } else {
         sc = x;
       }
-      std::vector<T> r(M_out * p.cv[0].cout);
-      conv_fwd(B.a[0].data(), P + p.cv[0].w, r.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
-      for (int j = 1; j < p.nconv; ++j) {
-        bnrelu(j, r);
+      std::vector<T> r;
+      for (int j = 0; j < p.nconv; ++j) {
+        const bool last = (j == p.nconv - 1);
+        if (j > 0) bnrelu(j, r);
         std::vector<T> r2(M_out * p.cv[j].cout);
-        conv_fwd(B.a[j].data(), P + p.cv[j].w, r2.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
-        r.swap(r2);
+        conv_fwd(B.a[j].data(), P + p.cv[j].w, r2.data(), b, j == 0 ? p.h_in : p.h_out, j == 0 ? p.w_in : p.w_out,
+                 p.cv[j].cin, p.cv[j].cout, p.cv[j].R, p.cv[j].st, last ? sc.data() : (const T*)nullptr, bf);
+        r.swap(r2);                                        // after the last conv: y = shortcut + branch
       }
-      x.resize(M_out * p.d.c_out);
-      for (size_t e = 0; e < x.size(); ++e) x[e] = (T)((double)sc[e] + (double)r[e]);
-      (void)M_in;
+      x.swap(r);
     }
     if (d.has_head) {
       const int C = out_c, hw = out_h * out_w;
       S.head_bn.x = x; S.head_bn.mean.resize(C); S.head_bn.invstd.resize(C);
       S.head_a.resize(x.size());
       bn_relu_fwd(x.data(), P + head_bn.g, P + head_bn.b, S.head_a.data(), S.head_bn.mean.data(),
-                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode);
+                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode, bf);
       S.g.resize((size_t)b * C); S.dlogits.resize((size_t)b * d.num_classes);
       const double l = head_fwd(S.head_a.data(), P + wfc, P + bfc, labels, S.g.data(), S.dlogits.data(),
                                 b, hw, C, d.num_classes, (double)d.loss_divisor);
@@ -393,17 +435,18 @@ struct Partition {
     if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
     MbStash<T>& S = st[mb];
     if (!S.fwd_done || S.bwd_done) return E_STATE;
-    const int b = d.microbatch;
+    const int b = d.microbatch, bf = d.storage;
     const T* P = params.data();
     double* G = grad.data();
+    const T* none = nullptr;
     std::vector<T> dy;   // gradient w.r.t. the current unit's output
     if (d.has_head) {
       const int C = out_c, hw = out_h * out_w;
       std::vector<T> da((size_t)b * hw * C);
-      head_bwd(S.g.data(), S.dlogits.data(), P + wfc, G + wfc, G + bfc, da.data(), b, hw, C, d.num_classes);
+      head_bwd(S.g.data(), S.dlogits.data(), P + wfc, G + wfc, G + bfc, da.data(), b, hw, C, d.num_classes, bf);
       dy.resize(da.size());
       bn_relu_bwd(S.head_bn.x.data(), da.data(), P + head_bn.g, P + head_bn.b, S.head_bn.mean.data(),
-                  S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode);
+                  S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode, none, bf);
     } else {
       dy.assign(err_in, err_in + (size_t)b * out_h * out_w * out_c);
     }
@@ -415,31 +458,28 @@ struct Partition {
       for (int j = p.nconv - 1; j >= 1; --j) {
         conv_wgrad(B.a[j].data(), dr.data(), G + p.cv[j].w, b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
         std::vector<T> da(M_out * p.cv[j].cin);
-        conv_dgrad(dr.data(), P + p.cv[j].w, da.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
+        conv_dgrad(dr.data(), P + p.cv[j].w, da.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1, none, bf);
         std::vector<T> dx(da.size());
         bn_relu_bwd(B.bn[j].x.data(), da.data(), P + p.bn[j].g, P + p.bn[j].b, B.bn[j].mean.data(),
-                    B.bn[j].invstd.data(), dx.data(), G + p.bn[j].g, G + p.bn[j].b, M_out, p.bn[j].c, d.bn_mode);
+                    B.bn[j].invstd.data(), dx.data(), G + p.bn[j].g, G + p.bn[j].b, M_out, p.bn[j].c, d.bn_mode, none, bf);
         dr.swap(dx);
       }
       conv_wgrad(B.a[0].data(), dr.data(), G + p.cv[0].w, b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
       std::vector<T> da(M_in * p.d.c_in);
-      conv_dgrad(dr.data(), P + p.cv[0].w, da.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
-      if (p.proj) {
+      conv_dgrad(dr.data(), P + p.cv[0].w, da.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st, none, bf);
+      if (p.proj) {   // a = relu(bn1(x)) feeds both the branch and the projection: their gradients add
         conv_wgrad(B.a[0].data(), dy.data(), G + p.pj.w, b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
-        std::vector<T> da2(da.size());
-        conv_dgrad(dy.data(), P + p.pj.w, da2.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
-        for (size_t e = 0; e < da.size(); ++e) da[e] = (T)((double)da[e] + (double)da2[e]);
+        conv_dgrad(dy.data(), P + p.pj.w, da.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st, da.data(), bf);
       }
-      std::vector<T> dx(da.size());
+      std::vector<T> dx(da.size());  // identity shortcut: x also feeds the output directly, so dy is added
       bn_relu_bwd(B.bn[0].x.data(), da.data(), P + p.bn[0].g, P + p.bn[0].b, B.bn[0].mean.data(),
-                  B.bn[0].invstd.data(), dx.data(), G + p.bn[0].g, G + p.bn[0].b, M_in, p.bn[0].c, d.bn_mode);
-      if (!p.proj)
-        for (size_t e = 0; e < dx.size(); ++e) dx[e] = (T)((double)dx[e] + (double)dy[e]);
+                  B.bn[0].invstd.data(), dx.data(), G + p.bn[0].g, G + p.bn[0].b, M_in, p.bn[0].c, d.bn_mode,
+                  p.proj ? none : dy.data(), bf);
       dy.swap(dx);
     }
     if (d.has_stem) {
       conv_wgrad(S.stem_in.data(), dy.data(), G + stem_w, b, d.in_h, d.in_w, d.in_c, d.stem_c_out, 3, 1);
-      if (err_out) conv_dgrad(dy.data(), P + stem_w, err_out, b, d.in_h, d.in_w, d.in_c, d.stem_c_out, 3, 1);
+      if (err_out) conv_dgrad(dy.data(), P + stem_w, err_out, b, d.in_h, d.in_w, d.in_c, d.stem_c_out, 3, 1, none, bf);
     } else if (err_out) {
       std::memcpy(err_out, dy.data(), dy.size() * sizeof(T));
     }
@@ -494,6 +534,7 @@ bool valid(const Desc& d) {
     h /= b.stride; w /= b.stride; c = b.c_out;
   }
   if (d.has_head && d.num_classes <= 0) return false;
+  if (d.storage != 0 && d.storage != 1) return false;
   return true;
 }
 
@@ -502,13 +543,14 @@ bool valid(const Desc& d) {
 extern "C" {
 
 // desc_i: in_h,in_w,in_c,has_stem,stem_c_out,n_blocks,has_head,num_classes,microbatch,
-//         num_microbatches,loss_divisor,bn_mode ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
+//         num_microbatches,loss_divisor,bn_mode,storage ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
 void* oracle_partition_create(const int32_t* desc_i, double bn_eps, const int32_t* blocks,
                               const void* host_params, int is_f64) {
   Desc d;
   d.in_h = desc_i[0]; d.in_w = desc_i[1]; d.in_c = desc_i[2]; d.has_stem = desc_i[3];
   d.stem_c_out = desc_i[4]; d.n_blocks = desc_i[5]; d.has_head = desc_i[6]; d.num_classes = desc_i[7];
   d.microbatch = desc_i[8]; d.num_microbatches = desc_i[9]; d.loss_divisor = desc_i[10]; d.bn_mode = desc_i[11];
+  d.storage = desc_i[12];
   d.bn_eps = bn_eps;
   for (int i = 0; i < d.n_blocks; ++i)
     d.blocks.push_back(BlockDesc{blocks[5 * i], blocks[5 * i + 1], blocks[5 * i + 2], blocks[5 * i + 3], blocks[5 * i + 4]});
@@ -576,25 +618,29 @@ int oracle_params_write(void* hp, const void* src, size_t n) {
 
 #define ORACLE_OPS(SUF, T)                                                                              \
   void oracle_conv_fwd_##SUF(const T* x, const T* w, T* y, int n, int h, int wd, int cin, int cout,     \
-                             int R, int st) { conv_fwd<T>(x, w, y, n, h, wd, cin, cout, R, st); }       \
+                             int R, int st, const T* add, int bf) {                                     \
+    conv_fwd<T>(x, w, y, n, h, wd, cin, cout, R, st, add, bf); }                                        \
   void oracle_conv_dgrad_##SUF(const T* dy, const T* w, T* dx, int n, int h, int wd, int cin, int cout, \
-                               int R, int st) { conv_dgrad<T>(dy, w, dx, n, h, wd, cin, cout, R, st); } \
+                               int R, int st, const T* add, int bf) {                                   \
+    conv_dgrad<T>(dy, w, dx, n, h, wd, cin, cout, R, st, add, bf); }                                    \
   void oracle_conv_wgrad_##SUF(const T* x, const T* dy, double* dw, int n, int h, int wd, int cin,      \
                                int cout, int R, int st) {                                               \
     conv_wgrad<T>(x, dy, dw, n, h, wd, cin, cout, R, st); }                                             \
   void oracle_bn_relu_fwd_##SUF(const T* x, const T* g, const T* b, T* a, double* mean, double* invstd, \
-                                size_t M, int C, double eps, int mode) {                                \
-    bn_relu_fwd<T>(x, g, b, a, mean, invstd, M, C, eps, mode); }                                        \
+                                size_t M, int C, double eps, int mode, int bf) {                        \
+    bn_relu_fwd<T>(x, g, b, a, mean, invstd, M, C, eps, mode, bf); }                                    \
   void oracle_bn_relu_bwd_##SUF(const T* x, const T* da, const T* g, const T* b, const double* mean,    \
                                 const double* invstd, T* dx, double* dg, double* db, size_t M, int C,   \
-                                int mode) {                                                             \
-    bn_relu_bwd<T>(x, da, g, b, mean, invstd, dx, dg, db, M, C, mode); }                                \
+                                int mode, const T* skip, int bf) {                                      \
+    bn_relu_bwd<T>(x, da, g, b, mean, invstd, dx, dg, db, M, C, mode, skip, bf); }                      \
   double oracle_head_fwd_##SUF(const T* a, const T* wfc, const T* bfc, const int32_t* labels, T* g,     \
                                T* dlogits, int n, int hw, int C, int classes, double divisor) {         \
     return head_fwd<T>(a, wfc, bfc, labels, g, dlogits, n, hw, C, classes, divisor); }                  \
   void oracle_head_bwd_##SUF(const T* g, const T* dl, const T* wfc, double* dwfc, double* dbfc, T* da,  \
                              int n, int hw, int C, int classes) {                                       \
     head_bwd<T>(g, dl, wfc, dwfc, dbfc, da, n, hw, C, classes); }
+
+float oracle_round_bf16(float v) { return rnd<float>(v, 1); }
 
 ORACLE_OPS(f32, float)
 ORACLE_OPS(f64, double)

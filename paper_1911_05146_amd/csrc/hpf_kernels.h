@@ -1,0 +1,83 @@
+// Internal interface between the host runtime and the HIP kernels of the partition engine.
+// Every launcher only enqueues work on `stream` and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hpf {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+enum : int { DT_F32 = 0, DT_BF16 = 1 };
+enum : int { CONV_FWD = 0, CONV_DGRAD = 1 };
+
+// Geometry of one gather-GEMM:  out[m, n] = sum_{tap, c} src[row(m, tap), c] * W(tap, c, n).
+// The output row space is b x Ho x Wo; the source tensor is b x Hs x Ws x Cs.
+//   CONV_FWD  : out = conv output,      src = conv input,   row(m,tap) = (p*stride + r - pad, q*stride + s - pad)
+//   CONV_DGRAD: out = input gradient,   src = output grad,  row(m,tap) = ((p + pad - r)/stride, (q + pad - s)/stride)
+//               where both quotients must be exact.
+struct ConvGeom {
+  int b, Ho, Wo, Hs, Ws, Cs, N, R, stride, pad;
+  int M;     // b*Ho*Wo
+  int Ktot;  // R*R*Cs
+  int Kpad;  // Ktot rounded up to 32 (packed bf16 weights are [N][Kpad], zero padded)
+};
+
+// Weight gradient of one convolution: dw[tap][c][n] += sum_m a[row(m,tap), c] * dy[m, n],
+// a is b x H x W x Cin, dy is b x Ho x Wo x N, row(m,tap) as in CONV_FWD.  Only rows c < c_valid
+// are written and dw has c_valid rows per tap (the stem runs on im2col columns padded to Cin).
+struct WgradGeom {
+  int b, H, W, Cin, Ho, Wo, N, R, stride, pad, M, c_valid;
+};
+
+// One convolution's fp32 master and its packed bf16 copies (offsets in elements).
+struct PackDesc {
+  unsigned long long w_off;   // fp32 master [T][Cin][Cout] in the parameter vector
+  unsigned long long wf_off;  // bf16 [Cout][Kf]  k = tap*Cin + c     (forward operand)
+  unsigned long long wd_off;  // bf16 [Cin][Kd]   k = tap*Cout + n    (data-gradient operand); ~0 = none
+  int T, Cin, Cout, Kf, Kd;
+};
+
+hipError_t launch_conv_mfma(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
+                            const ConvGeom& g, hipStream_t stream);
+hipError_t launch_wgrad_mfma(const bf16_t* a, const bf16_t* dy, float* dw, const WgradGeom& g, hipStream_t stream);
+
+hipError_t launch_conv_f32(int mode, const float* src, const float* w_hwio, float* out, const float* add,
+                           const ConvGeom& g, hipStream_t stream);
+hipError_t launch_wgrad_f32(const float* a, const float* dy, float* dw, const WgradGeom& g, hipStream_t stream);
+
+// BatchNorm + ReLU.  stats = [mean(C), invstd(C)].  partials: >= bn_partials_floats(C) floats,
+// tickets: >= 64 zero-initialised unsigned (left at zero).  All tensors are [M, C] of dtype dt.
+size_t bn_partials_floats(int C);
+hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, float* stats, float* partials,
+                           unsigned* tickets, hipStream_t stream);
+hipError_t launch_bn_apply_relu(int dt, const void* x, void* a, const float* gamma, const float* beta,
+                                const float* stats, int M, int C, hipStream_t stream);
+// sums = [dbeta(C), dgamma(C)] of this micro-batch; also atomically added into g_gamma / g_beta.
+hipError_t launch_bn_bwd_reduce(int dt, const void* x, const void* da, const float* gamma, const float* beta,
+                                const float* stats, int M, int C, float* sums, float* g_gamma, float* g_beta,
+                                float* partials, unsigned* tickets, hipStream_t stream);
+// dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M) [+ skip]; frozen: dx = gamma*invstd*dz [+ skip].
+hipError_t launch_bn_bwd_apply(int dt, const void* x, const void* da, const float* gamma, const float* beta,
+                               const float* stats, const float* sums, const void* skip, void* dx, int M, int C,
+                               int frozen, hipStream_t stream);
+hipError_t launch_bn_frozen_stats(float* stats, int C, float eps, hipStream_t stream);
+
+// Stem: fp32 image [b,H,W,Cin] -> bf16 im2col columns [b*H*W, Kc], k = (r*3+s)*Cin + c, zero padded.
+hipError_t launch_im2col3x3(const float* img, bf16_t* col, int b, int H, int W, int Cin, int Kc, hipStream_t stream);
+
+// Head: a [b,hw,C] (dtype dt) -> g [b,C] fp32, dlogits [b,classes] fp32, loss_accum += sum CE / divisor.
+hipError_t launch_head_fwd(int dt, const void* a, const float* wfc, const float* bfc, const int32_t* labels,
+                           float* g, float* dlogits, float* loss_accum, int b, int hw, int C, int classes,
+                           float divisor, hipStream_t stream);
+hipError_t launch_head_bwd(int dt, const float* g, const float* dlogits, const float* wfc, float* g_wfc,
+                           float* g_bfc, void* da, int b, int hw, int C, int classes, hipStream_t stream);
+
+hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, hipStream_t stream);
+hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream);
+hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
+                               hipStream_t stream);
+hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+}  // namespace hpf

@@ -1,0 +1,725 @@
+// Host runtime of the partition engine: description validation, arena layout, the per-micro-batch
+// kernel schedule of one partition's forward and backward pass, the call-order state machine and
+// the C ABI of include/hpf.h.
+//
+// What runs per micro-batch (paper Sections "Implementing Distributed Back-Propagation" and
+// "Exploiting Pipeline Stages within Each Minibatch"): forward over the partition's units on the
+// received activations, stashing what the backward pass needs; backward from the received partial
+// error, adding weight gradients into the shared fp32 buffer and emitting the partial error for
+// the previous partition.  Units: [stem conv] + pre-activation residual blocks + [head].
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/hpf.h"
+#include "hpf_kernels.h"
+
+using namespace hpf;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+hpf_status fail(hpf_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+int round_up32(int v) { return (v + 31) / 32 * 32; }
+
+// Where a tensor lives: inside this micro-batch's arena region, or in a caller buffer.
+enum LocKind { IN_MB = 0, CALLER_ACT_IN, CALLER_ACT_OUT, CALLER_ERR_IN, CALLER_ERR_OUT, NOWHERE };
+struct Loc { LocKind kind = NOWHERE; size_t off = 0; };
+
+struct ConvPlan {
+  int cin = 0, cout = 0, R = 1, stride = 1, h_in = 0, w_in = 0, h_out = 0, w_out = 0;
+  size_t w_off = 0;                 // fp32 master / gradient offset (floats)
+  size_t wf_off = 0, wd_off = 0;    // packed bf16 offsets (elements)
+  int Kf = 0, Kd = 0;
+};
+struct BnPlan { int C = 0; size_t g_off = 0, b_off = 0; size_t stats_off = 0; /* bytes in mb region */ };
+struct BlockPlan {
+  hpf_block_desc d{};
+  int h_in = 0, w_in = 0, h_out = 0, w_out = 0, nconv = 0;
+  bool proj = false;
+  BnPlan bn[3]; ConvPlan cv[3]; ConvPlan pj;
+  Loc x_in, a[3], c[2], y;
+};
+
+struct Plan {
+  hpf_partition_desc d{};
+  std::vector<hpf_block_desc> blocks;
+  int dt = DT_BF16; size_t esz = 2;
+  size_t n_params = 0;
+  // stem
+  ConvPlan stem; int stem_kc = 0; Loc stem_col, stem_out;
+  std::vector<BlockPlan> bp;
+  // head
+  BnPlan head_bn; size_t wfc_off = 0, bfc_off = 0; Loc head_x, head_a, head_g, head_dl;
+  int out_h = 0, out_w = 0, out_c = 0;
+  // per-micro-batch region
+  size_t mb_bytes = 0, stash_bytes_per_mb = 0;
+  size_t sums_off = 0, partials_off = 0, tickets_off = 0;
+  size_t scratch_off[4] = {0, 0, 0, 0};
+  size_t max_elems = 0; int max_c = 0;
+  // global regions (bytes from arena base)
+  size_t params_off = 0, grads_off = 0, mom_off = 0, packed_off = 0, table_off = 0, mb_off = 0;
+  size_t packed_elems = 0; int n_convs = 0;
+  size_t arena_bytes = 0;
+  size_t act_in_elems = 0, act_out_elems = 0;
+  std::vector<PackDesc> table;
+};
+
+hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
+  if (!desc) return fail(HPF_EINVAL, "null description");
+  if (desc->abi_version != HPF_ABI_VERSION) return fail(HPF_EINVAL, "abi_version %u, expected %u", desc->abi_version, HPF_ABI_VERSION);
+  P.d = *desc;
+  const hpf_partition_desc& d = P.d;
+  if (d.in_h <= 0 || d.in_w <= 0 || d.in_c <= 0) return fail(HPF_EINVAL, "input shape must be positive");
+  if (d.microbatch <= 0 || d.num_microbatches <= 0 || d.loss_divisor <= 0) return fail(HPF_EINVAL, "microbatch, num_microbatches and loss_divisor must be positive");
+  if (d.n_blocks < 0 || (d.n_blocks > 0 && !d.blocks)) return fail(HPF_EINVAL, "bad block list");
+  if (!d.has_stem && !d.has_head && d.n_blocks == 0) return fail(HPF_EINVAL, "a partition needs at least one unit");
+  if (d.compute_dtype != HPF_F32 && d.compute_dtype != HPF_BF16) return fail(HPF_EINVAL, "unknown compute_dtype");
+  if (d.bn_mode != 0 && d.bn_mode != 1) return fail(HPF_EINVAL, "bn_mode must be 0 or 1");
+  if (!(d.bn_eps > 0.f)) return fail(HPF_EINVAL, "bn_eps must be positive");
+  if (d.has_stem && d.stem_c_out <= 0) return fail(HPF_EINVAL, "stem_c_out must be positive");
+  if (d.has_head && d.num_classes <= 0) return fail(HPF_EINVAL, "num_classes must be positive");
+  P.blocks.assign(d.blocks, d.blocks + d.n_blocks);
+  P.d.blocks = nullptr;
+  P.dt = d.compute_dtype == HPF_BF16 ? DT_BF16 : DT_F32;
+  P.esz = P.dt == DT_BF16 ? 2 : 4;
+  const int cmul = P.dt == DT_BF16 ? 16 : 8;
+
+  // ---- shape chain + validation
+  int h = d.in_h, w = d.in_w, c = d.has_stem ? d.stem_c_out : d.in_c;
+  if (c % cmul) return fail(HPF_EUNSUPPORTED, "channel count %d is not a multiple of %d", c, cmul);
+  for (int i = 0; i < d.n_blocks; ++i) {
+    const hpf_block_desc& b = P.blocks[i];
+    if (b.kind != 0 && b.kind != 1) return fail(HPF_EINVAL, "block %d: kind %d", i, b.kind);
+    if (b.c_in != c) return fail(HPF_EINVAL, "block %d: c_in %d does not continue the chain (%d)", i, b.c_in, c);
+    if (b.c_mid <= 0 || b.c_out <= 0) return fail(HPF_EINVAL, "block %d: channel counts must be positive", i);
+    if (b.kind == 0 && b.c_mid != b.c_out) return fail(HPF_EINVAL, "block %d: a basic block needs c_mid == c_out", i);
+    if (b.stride != 1 && b.stride != 2) return fail(HPF_EINVAL, "block %d: stride %d", i, b.stride);
+    if (h % b.stride || w % b.stride) return fail(HPF_EINVAL, "block %d: %dx%d not divisible by stride", i, h, w);
+    if (b.c_mid % cmul || b.c_out % cmul) return fail(HPF_EUNSUPPORTED, "block %d: channel counts must be multiples of %d", i, cmul);
+    h /= b.stride; w /= b.stride; c = b.c_out;
+  }
+  P.out_h = h; P.out_w = w; P.out_c = c;
+  if ((size_t)d.microbatch * d.in_h * d.in_w >= (1u << 30)) return fail(HPF_EUNSUPPORTED, "micro-batch too large");
+
+  // ---- parameters (canonical order) and packed weights
+  size_t off = 0, pk = 0;
+  auto add_pack = [&](ConvPlan& cv, int pack_cin, bool want_dgrad) {
+    if (P.dt != DT_BF16) return;
+    const int T = cv.R * cv.R;
+    cv.Kf = round_up32(T * pack_cin);
+    cv.wf_off = pk; pk += (size_t)cv.cout * cv.Kf; pk = (pk + 7) / 8 * 8;
+    PackDesc pd{};
+    pd.w_off = cv.w_off; pd.wf_off = cv.wf_off; pd.wd_off = ~0ull;
+    pd.T = T; pd.Cin = pack_cin; pd.Cout = cv.cout; pd.Kf = cv.Kf; pd.Kd = 0;
+    if (want_dgrad) {
+      cv.Kd = round_up32(T * cv.cout);
+      cv.wd_off = pk; pk += (size_t)cv.cin * cv.Kd; pk = (pk + 7) / 8 * 8;
+      pd.wd_off = cv.wd_off; pd.Kd = cv.Kd;
+    }
+    P.table.push_back(pd);
+  };
+  auto mk_conv = [&](int ci, int co, int R, int st, int hi, int wi) {
+    ConvPlan cv; cv.cin = ci; cv.cout = co; cv.R = R; cv.stride = st; cv.h_in = hi; cv.w_in = wi;
+    cv.h_out = hi / st; cv.w_out = wi / st; cv.w_off = off; off += (size_t)R * R * ci * co;
+    return cv;
+  };
+  auto mk_bn = [&](int ch) { BnPlan b; b.C = ch; b.g_off = off; b.b_off = off + ch; off += 2 * (size_t)ch; return b; };
+
+  h = d.in_h; w = d.in_w;
+  if (d.has_stem) {
+    P.stem = mk_conv(d.in_c, d.stem_c_out, 3, 1, h, w);
+    P.stem_kc = round_up32(9 * d.in_c);
+    if (P.dt == DT_BF16) {
+      // runs as a 1x1 convolution over im2col columns: k = tap*in_c + c, a single "tap" of 9*in_c channels
+      ConvPlan as1x1 = P.stem; as1x1.R = 1;
+      add_pack(as1x1, 9 * d.in_c, false);
+      P.stem.Kf = as1x1.Kf; P.stem.wf_off = as1x1.wf_off;
+    }
+  }
+  P.bp.resize(d.n_blocks);
+  for (int i = 0; i < d.n_blocks; ++i) {
+    BlockPlan& p = P.bp[i];
+    const hpf_block_desc& b = P.blocks[i];
+    p.d = b; p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride;
+    p.proj = (b.stride != 1 || b.c_in != b.c_out);
+    if (b.kind == 0) {
+      p.nconv = 2;
+      p.bn[0] = mk_bn(b.c_in);  p.cv[0] = mk_conv(b.c_in, b.c_mid, 3, b.stride, h, w);
+      p.bn[1] = mk_bn(b.c_mid); p.cv[1] = mk_conv(b.c_mid, b.c_out, 3, 1, p.h_out, p.w_out);
+    } else {
+      p.nconv = 3;
+      p.bn[0] = mk_bn(b.c_in);  p.cv[0] = mk_conv(b.c_in, b.c_mid, 1, b.stride, h, w);
+      p.bn[1] = mk_bn(b.c_mid); p.cv[1] = mk_conv(b.c_mid, b.c_mid, 3, 1, p.h_out, p.w_out);
+      p.bn[2] = mk_bn(b.c_mid); p.cv[2] = mk_conv(b.c_mid, b.c_out, 1, 1, p.h_out, p.w_out);
+    }
+    if (p.proj) p.pj = mk_conv(b.c_in, b.c_out, 1, b.stride, h, w);
+    for (int j = 0; j < p.nconv; ++j) add_pack(p.cv[j], p.cv[j].cin, true);
+    if (p.proj) add_pack(p.pj, p.pj.cin, true);
+    h = p.h_out; w = p.w_out;
+  }
+  if (d.has_head) {
+    P.head_bn = mk_bn(P.out_c);
+    P.wfc_off = off; off += (size_t)P.out_c * d.num_classes;
+    P.bfc_off = off; off += d.num_classes;
+  }
+  P.n_params = off;
+  P.packed_elems = pk;
+  P.n_convs = (int)P.table.size();
+
+  // ---- per-micro-batch region
+  size_t mo = 0;
+  size_t max_elems = 0; int max_c = 0;
+  const size_t b_ = (size_t)d.microbatch;
+  auto alloc = [&](size_t bytes) { Loc l; l.kind = IN_MB; l.off = mo; mo += align_up(bytes); return l; };
+  auto tensor = [&](size_t elems) { if (elems > max_elems) max_elems = elems; return alloc(elems * P.esz); };
+  auto stats = [&](BnPlan& bn) { bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(float)).off; if (bn.C > max_c) max_c = bn.C; };
+
+  P.act_in_elems = b_ * d.in_h * d.in_w * d.in_c;
+  P.act_out_elems = d.has_head ? 0 : b_ * P.out_h * P.out_w * P.out_c;
+  Loc cur; cur.kind = CALLER_ACT_IN;
+  if (d.has_stem) {
+    const size_t Mst = b_ * d.in_h * d.in_w;
+    if (P.dt == DT_BF16) P.stem_col = alloc(Mst * P.stem_kc * 2);
+    const bool direct_out = (d.n_blocks == 0 && !d.has_head);
+    if (direct_out) { P.stem_out.kind = CALLER_ACT_OUT; } else P.stem_out = tensor(Mst * d.stem_c_out);
+    if (Mst * d.stem_c_out > max_elems) max_elems = Mst * d.stem_c_out;
+    cur = P.stem_out;
+  } else if (P.act_in_elems > max_elems) {
+    max_elems = P.act_in_elems;
+  }
+  for (int i = 0; i < d.n_blocks; ++i) {
+    BlockPlan& p = P.bp[i];
+    const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
+    p.x_in = cur;
+    stats(p.bn[0]); p.a[0] = tensor(M_in * p.d.c_in);
+    for (int j = 1; j < p.nconv; ++j) {
+      p.c[j - 1] = tensor(M_out * p.cv[j - 1].cout);
+      stats(p.bn[j]); p.a[j] = tensor(M_out * p.cv[j].cin);
+    }
+    const bool last = (i == d.n_blocks - 1);
+    if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
+    else p.y = tensor(M_out * p.d.c_out);
+    cur = p.y;
+  }
+  if (d.has_head) {
+    P.head_x = cur;
+    stats(P.head_bn);
+    P.head_a = tensor(b_ * P.out_h * P.out_w * P.out_c);
+    P.head_g = alloc(b_ * P.out_c * sizeof(float));
+    P.head_dl = alloc(b_ * d.num_classes * sizeof(float));
+  }
+  P.stash_bytes_per_mb = mo;
+  P.max_elems = max_elems; P.max_c = max_c;
+  if (max_c > 0) {
+    P.sums_off = alloc(2 * (size_t)max_c * sizeof(float)).off;
+    P.partials_off = alloc(bn_partials_floats(max_c) * sizeof(float)).off;
+  }
+  P.tickets_off = alloc(64 * sizeof(unsigned)).off;
+  for (int i = 0; i < 4; ++i) P.scratch_off[i] = alloc(max_elems * P.esz).off;
+  P.mb_bytes = mo;
+
+  // ---- global regions
+  size_t g = 0;
+  P.params_off = g; g += align_up(P.n_params * sizeof(float));
+  P.grads_off = g;  g += align_up(P.n_params * sizeof(float));
+  P.mom_off = g;    g += align_up(P.n_params * sizeof(float));
+  P.packed_off = g; g += align_up(P.packed_elems * 2);
+  P.table_off = g;  g += align_up(P.table.size() * sizeof(PackDesc));
+  P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
+  P.arena_bytes = g;
+  return HPF_OK;
+}
+
+}  // namespace
+
+struct hpf_partition {
+  Plan P;
+  char* arena = nullptr;
+  std::vector<unsigned char> fwd_done, bwd_done;
+  std::vector<const void*> act_in;
+  int n_bwd = 0;
+  std::vector<hipEvent_t> ev_fwd, ev_bwd;
+  hipEvent_t ev_step = nullptr;
+  bool step_recorded = false;
+
+  float* params() const { return (float*)(arena + P.params_off); }
+  float* grads() const { return (float*)(arena + P.grads_off); }
+  float* mom() const { return (float*)(arena + P.mom_off); }
+  bf16_t* packed() const { return (bf16_t*)(arena + P.packed_off); }
+  char* mb_base(int mb) const { return arena + P.mb_off + (size_t)mb * P.mb_bytes; }
+};
+
+namespace {
+
+struct Ctx {
+  hpf_partition* h; int mb; hipStream_t s;
+  const void* act_in; void* act_out; const void* err_in; void* err_out;
+  hipError_t err = hipSuccess;
+  const char* where = "";
+
+  void* ptr(const Loc& l) const {
+    switch (l.kind) {
+      case IN_MB: return h->mb_base(mb) + l.off;
+      case CALLER_ACT_IN: return const_cast<void*>(act_in);
+      case CALLER_ACT_OUT: return act_out;
+      case CALLER_ERR_IN: return const_cast<void*>(err_in);
+      case CALLER_ERR_OUT: return err_out;
+      default: return nullptr;
+    }
+  }
+  float* mbf(size_t off) const { return (float*)(h->mb_base(mb) + off); }
+  void* scratch(int i) const { return h->mb_base(mb) + h->P.scratch_off[i]; }
+  void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
+
+  void bn_fwd(const BnPlan& bn, const void* x, void* a, size_t M) {
+    const Plan& P = h->P;
+    float* st = mbf(bn.stats_off);
+    if (P.d.bn_mode == 0)
+      chk(launch_bn_stats(P.dt, x, (int)M, bn.C, P.d.bn_eps, st, mbf(P.partials_off), (unsigned*)mbf(P.tickets_off), s), "bn_stats");
+    else
+      chk(launch_bn_frozen_stats(st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
+    chk(launch_bn_apply_relu(P.dt, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
+  }
+  void bn_bwd(const BnPlan& bn, const void* x, const void* da, const void* skip, void* dx, size_t M) {
+    const Plan& P = h->P;
+    float* st = mbf(bn.stats_off);
+    chk(launch_bn_bwd_reduce(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbf(P.sums_off),
+                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbf(P.partials_off), (unsigned*)mbf(P.tickets_off), s),
+        "bn_bwd_reduce");
+    chk(launch_bn_bwd_apply(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbf(P.sums_off), skip, dx, (int)M,
+                            bn.C, P.d.bn_mode, s),
+        "bn_bwd_apply");
+  }
+  ConvGeom geom_fwd(const ConvPlan& cv) const {
+    ConvGeom g{};
+    g.b = h->P.d.microbatch; g.Ho = cv.h_out; g.Wo = cv.w_out; g.Hs = cv.h_in; g.Ws = cv.w_in; g.Cs = cv.cin; g.N = cv.cout;
+    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.Ktot = cv.R * cv.R * cv.cin; g.Kpad = cv.Kf;
+    return g;
+  }
+  ConvGeom geom_dgrad(const ConvPlan& cv) const {
+    ConvGeom g{};
+    g.b = h->P.d.microbatch; g.Ho = cv.h_in; g.Wo = cv.w_in; g.Hs = cv.h_out; g.Ws = cv.w_out; g.Cs = cv.cout; g.N = cv.cin;
+    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.Ktot = cv.R * cv.R * cv.cout; g.Kpad = cv.Kd;
+    return g;
+  }
+  void conv_fwd(const ConvPlan& cv, const void* x, void* y, const void* add) {
+    const ConvGeom g = geom_fwd(cv);
+    if (h->P.dt == DT_BF16)
+      chk(launch_conv_mfma(CONV_FWD, (const bf16_t*)x, h->packed() + cv.wf_off, (bf16_t*)y, (const bf16_t*)add, g, s), "conv_fwd");
+    else
+      chk(launch_conv_f32(CONV_FWD, (const float*)x, h->params() + cv.w_off, (float*)y, (const float*)add, g, s), "conv_fwd_f32");
+  }
+  void conv_dgrad(const ConvPlan& cv, const void* dy, void* dx, const void* add) {
+    const ConvGeom g = geom_dgrad(cv);
+    if (h->P.dt == DT_BF16)
+      chk(launch_conv_mfma(CONV_DGRAD, (const bf16_t*)dy, h->packed() + cv.wd_off, (bf16_t*)dx, (const bf16_t*)add, g, s), "conv_dgrad");
+    else
+      chk(launch_conv_f32(CONV_DGRAD, (const float*)dy, h->params() + cv.w_off, (float*)dx, (const float*)add, g, s), "conv_dgrad_f32");
+  }
+  void conv_wgrad(const ConvPlan& cv, const void* a, const void* dy) {
+    WgradGeom g{};
+    g.b = h->P.d.microbatch; g.H = cv.h_in; g.W = cv.w_in; g.Cin = cv.cin; g.Ho = cv.h_out; g.Wo = cv.w_out; g.N = cv.cout;
+    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.c_valid = cv.cin;
+    if (h->P.dt == DT_BF16)
+      chk(launch_wgrad_mfma((const bf16_t*)a, (const bf16_t*)dy, h->grads() + cv.w_off, g, s), "conv_wgrad");
+    else
+      chk(launch_wgrad_f32((const float*)a, (const float*)dy, h->grads() + cv.w_off, g, s), "conv_wgrad_f32");
+  }
+};
+
+void run_forward(Ctx& c, const int32_t* labels, float* loss_accum) {
+  const Plan& P = c.h->P;
+  const size_t b = (size_t)P.d.microbatch;
+  if (P.d.has_stem) {
+    if (P.dt == DT_BF16) {
+      bf16_t* col = (bf16_t*)c.ptr(P.stem_col);
+      c.chk(launch_im2col3x3((const float*)c.act_in, col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
+      ConvPlan cv = P.stem; cv.R = 1; cv.cin = P.stem_kc;
+      ConvGeom g = c.geom_fwd(cv);
+      g.Ktot = P.stem_kc; g.Kpad = P.stem.Kf;
+      c.chk(launch_conv_mfma(CONV_FWD, col, c.h->packed() + P.stem.wf_off, (bf16_t*)c.ptr(P.stem_out), nullptr, g, c.s), "stem_conv");
+    } else {
+      c.conv_fwd(P.stem, c.act_in, c.ptr(P.stem_out), nullptr);
+    }
+  }
+  for (const BlockPlan& p : P.bp) {
+    const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
+    const void* x = c.ptr(p.x_in);
+    void* y = c.ptr(p.y);
+    c.bn_fwd(p.bn[0], x, c.ptr(p.a[0]), M_in);
+    if (p.proj) c.conv_fwd(p.pj, c.ptr(p.a[0]), y, nullptr);
+    const void* shortcut = p.proj ? y : x;
+    for (int j = 0; j < p.nconv; ++j) {
+      const bool last = (j == p.nconv - 1);
+      void* out = last ? y : c.ptr(p.c[j]);
+      c.conv_fwd(p.cv[j], c.ptr(p.a[j]), out, last ? shortcut : nullptr);
+      if (!last) c.bn_fwd(p.bn[j + 1], out, c.ptr(p.a[j + 1]), M_out);
+    }
+  }
+  if (P.d.has_head) {
+    const size_t M = b * P.out_h * P.out_w;
+    c.bn_fwd(P.head_bn, c.ptr(P.head_x), c.ptr(P.head_a), M);
+    c.chk(launch_head_fwd(P.dt, c.ptr(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
+                          (float*)c.ptr(P.head_g), (float*)c.ptr(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c,
+                          P.d.num_classes, (float)P.d.loss_divisor, c.s),
+          "head_fwd");
+  }
+}
+
+void run_backward(Ctx& c) {
+  const Plan& P = c.h->P;
+  const size_t b = (size_t)P.d.microbatch;
+  void* dyA = c.scratch(0); void* dyB = c.scratch(1); void* tA = c.scratch(2); void* tB = c.scratch(3);
+  const void* dy = c.err_in;
+  if (P.d.has_head) {
+    const size_t M = b * P.out_h * P.out_w;
+    c.chk(launch_head_bwd(P.dt, (const float*)c.ptr(P.head_g), (const float*)c.ptr(P.head_dl), c.h->params() + P.wfc_off,
+                          c.h->grads() + P.wfc_off, c.h->grads() + P.bfc_off, tA, (int)b, P.out_h * P.out_w, P.out_c,
+                          P.d.num_classes, c.s),
+          "head_bwd");
+    const bool to_caller = (P.bp.empty() && !P.d.has_stem);
+    void* dx = to_caller ? c.err_out : dyA;
+    c.bn_bwd(P.head_bn, c.ptr(P.head_x), tA, nullptr, dx, M);
+    dy = dx;
+  }
+  for (size_t ii = P.bp.size(); ii-- > 0;) {
+    const BlockPlan& p = P.bp[ii];
+    const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
+    const void* dr = dy;
+    for (int j = p.nconv - 1; j >= 1; --j) {
+      c.conv_wgrad(p.cv[j], c.ptr(p.a[j]), dr);
+      c.conv_dgrad(p.cv[j], dr, tA, nullptr);
+      c.bn_bwd(p.bn[j], c.ptr(p.c[j - 1]), tA, nullptr, tB, M_out);
+      dr = tB;
+    }
+    c.conv_wgrad(p.cv[0], c.ptr(p.a[0]), dr);
+    c.conv_dgrad(p.cv[0], dr, tA, nullptr);
+    if (p.proj) {
+      c.conv_wgrad(p.pj, c.ptr(p.a[0]), dy);
+      c.conv_dgrad(p.pj, dy, tA, tA);
+    }
+    void* dx;
+    if (ii == 0 && !P.d.has_stem) dx = c.err_out;
+    else dx = (dy == dyA) ? dyB : dyA;
+    c.bn_bwd(p.bn[0], c.ptr(p.x_in), tA, p.proj ? nullptr : dy, dx, M_in);
+    dy = dx;
+  }
+  if (P.d.has_stem) {
+    if (P.dt == DT_BF16) {
+      WgradGeom g{};
+      g.b = (int)b; g.H = P.d.in_h; g.W = P.d.in_w; g.Cin = P.stem_kc; g.Ho = g.H; g.Wo = g.W; g.N = P.d.stem_c_out;
+      g.R = 1; g.stride = 1; g.pad = 0; g.M = g.b * g.H * g.W; g.c_valid = 9 * P.d.in_c;
+      c.chk(launch_wgrad_mfma((const bf16_t*)c.ptr(P.stem_col), (const bf16_t*)dy, c.h->grads() + P.stem.w_off, g, c.s), "stem_wgrad");
+    } else {
+      c.conv_wgrad(P.stem, c.act_in, dy);
+    }
+  }
+}
+
+bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_microbatches; }
+
+hpf_status wait_all_backward(hpf_partition* p, hipStream_t s) {
+  for (int i = 0; i < p->P.d.num_microbatches; ++i)
+    if (p->bwd_done[i] && hipStreamWaitEvent(s, p->ev_bwd[i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  return HPF_OK;
+}
+
+void begin_next_batch(hpf_partition* p, hipStream_t s) {
+  std::fill(p->fwd_done.begin(), p->fwd_done.end(), 0);
+  std::fill(p->bwd_done.begin(), p->bwd_done.end(), 0);
+  p->n_bwd = 0;
+  (void)hipEventRecord(p->ev_step, s);
+  p->step_recorded = true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hpf_last_error(void) { return g_err; }
+
+hpf_status hpf_partition_sizes(const hpf_partition_desc* desc, hpf_sizes* out) {
+  if (!out) return fail(HPF_EINVAL, "null output");
+  Plan P;
+  const hpf_status st = build_plan(desc, P);
+  if (st != HPF_OK) return st;
+  out->n_params = P.n_params;
+  out->arena_bytes = P.arena_bytes;
+  out->stash_bytes = P.stash_bytes_per_mb * (size_t)P.d.num_microbatches;
+  out->act_in_elems = P.act_in_elems;
+  out->act_out_elems = P.act_out_elems;
+  return HPF_OK;
+}
+
+hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_arena, size_t arena_bytes,
+                                const float* host_params, hpf_partition** out) {
+  if (!out) return fail(HPF_EINVAL, "null output");
+  *out = nullptr;
+  if (!device_arena || !host_params) return fail(HPF_EINVAL, "null arena or parameters");
+  if ((uintptr_t)device_arena % ALIGN) return fail(HPF_EINVAL, "arena must be %zu-byte aligned", ALIGN);
+  hpf_partition* p = new (std::nothrow) hpf_partition();
+  if (!p) return fail(HPF_ENOMEM, "host allocation failed");
+  hpf_status st = build_plan(desc, p->P);
+  if (st != HPF_OK) { delete p; return st; }
+  if (arena_bytes < p->P.arena_bytes) {
+    const size_t need = p->P.arena_bytes;
+    delete p;
+    return fail(HPF_ENOMEM, "arena has %zu bytes, %zu needed", arena_bytes, need);
+  }
+  p->arena = (char*)device_arena;
+  const Plan& P = p->P;
+  const int m = P.d.num_microbatches;
+  p->fwd_done.assign(m, 0); p->bwd_done.assign(m, 0); p->act_in.assign(m, nullptr);
+  hipError_t e = hipSuccess;
+  auto ok = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  ok(hipMemcpy(p->params(), host_params, P.n_params * sizeof(float), hipMemcpyHostToDevice));
+  ok(hipMemset(p->grads(), 0, P.n_params * sizeof(float)));
+  ok(hipMemset(p->mom(), 0, P.n_params * sizeof(float)));
+  for (int i = 0; i < m; ++i) ok(hipMemset(p->mb_base(i) + P.tickets_off, 0, 64 * sizeof(unsigned)));
+  if (!P.table.empty()) {
+    ok(hipMemcpy(p->arena + P.table_off, P.table.data(), P.table.size() * sizeof(PackDesc), hipMemcpyHostToDevice));
+    ok(launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, nullptr));
+  }
+  p->ev_fwd.resize(m); p->ev_bwd.resize(m);
+  for (int i = 0; i < m; ++i) {
+    ok(hipEventCreateWithFlags(&p->ev_fwd[i], hipEventDisableTiming));
+    ok(hipEventCreateWithFlags(&p->ev_bwd[i], hipEventDisableTiming));
+  }
+  ok(hipEventCreateWithFlags(&p->ev_step, hipEventDisableTiming));
+  ok(hipDeviceSynchronize());
+  if (e != hipSuccess) {
+    st = fail(HPF_EDEVICE, "create: %s", hipGetErrorString(e));
+    hpf_partition_destroy(p);
+    return st;
+  }
+  *out = p;
+  return HPF_OK;
+}
+
+void hpf_partition_destroy(hpf_partition* p) {
+  if (!p) return;
+  (void)hipDeviceSynchronize();
+  for (hipEvent_t ev : p->ev_fwd) if (ev) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : p->ev_bwd) if (ev) (void)hipEventDestroy(ev);
+  if (p->ev_step) (void)hipEventDestroy(p->ev_step);
+  delete p;
+}
+
+hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels,
+                                  void* act_out, float* loss_accum, void* hip_stream) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  const Plan& P = p->P;
+  if (mb < 0 || mb >= P.d.num_microbatches) return fail(HPF_EINVAL, "micro-batch %d out of range", mb);
+  if (!act_in) return fail(HPF_EINVAL, "act_in is required");
+  if (P.d.has_head && (!labels || !loss_accum)) return fail(HPF_EINVAL, "labels and loss_accum are required with a head");
+  if (!P.d.has_head && !act_out) return fail(HPF_EINVAL, "act_out is required without a head");
+  if (p->fwd_done[mb]) return fail(HPF_ESTATE, "forward(%d) already ran in this batch", mb);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  Ctx c{p, mb, s, act_in, act_out, nullptr, nullptr};
+  run_forward(c, labels, loss_accum);
+  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "forward: %s: %s", c.where, hipGetErrorString(c.err));
+  if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+  p->act_in[mb] = act_in;
+  p->fwd_done[mb] = 1;
+  return HPF_OK;
+}
+
+hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out, void* hip_stream) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  const Plan& P = p->P;
+  if (mb < 0 || mb >= P.d.num_microbatches) return fail(HPF_EINVAL, "micro-batch %d out of range", mb);
+  if (!P.d.has_head && !err_in) return fail(HPF_EINVAL, "err_in is required without a head");
+  if (P.d.has_stem && err_out) return fail(HPF_EINVAL, "err_out must be NULL for the partition that holds the stem");
+  if (!P.d.has_stem && !err_out) return fail(HPF_EINVAL, "err_out is required");
+  if (!p->fwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) before forward(%d)", mb, mb);
+  if (p->bwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) already ran in this batch", mb);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (hipStreamWaitEvent(s, p->ev_fwd[mb], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  Ctx c{p, mb, s, p->act_in[mb], nullptr, err_in, err_out};
+  run_backward(c);
+  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "backward: %s: %s", c.where, hipGetErrorString(c.err));
+  if (hipEventRecord(p->ev_bwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+  p->bwd_done[mb] = 1;
+  ++p->n_bwd;
+  return HPF_OK;
+}
+
+hpf_status hpf_grad_accum_read(hpf_partition* p, float* dst, size_t n_floats, int32_t dst_is_device, void* hip_stream) {
+  if (!p || !dst) return fail(HPF_EINVAL, "null argument");
+  if (n_floats != p->P.n_params) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_params);
+  if (!all_backward_done(p)) return fail(HPF_ESTATE, "gradients read before all micro-batches ran backward");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hpf_status st = wait_all_backward(p, s);
+  if (st != HPF_OK) return st;
+  if (dst_is_device) {
+    if (launch_copy_bytes(dst, p->grads(), n_floats * sizeof(float), s) != hipSuccess) return fail(HPF_EDEVICE, "copy failed");
+    return HPF_OK;
+  }
+  if (hipMemcpyAsync(dst, p->grads(), n_floats * sizeof(float), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return fail(HPF_EDEVICE, "device-to-host copy failed: %s", hipGetErrorString(hipGetLastError()));
+  return HPF_OK;
+}
+
+hpf_status hpf_grad_accum_zero(hpf_partition* p, void* hip_stream) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  for (int i = 0; i < p->P.d.num_microbatches; ++i)
+    if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hpf_status st = wait_all_backward(p, s);
+  if (st != HPF_OK) return st;
+  if (launch_zero_f32(p->grads(), p->P.n_params, s) != hipSuccess) return fail(HPF_EDEVICE, "zero failed");
+  begin_next_batch(p, s);
+  return HPF_OK;
+}
+
+hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_stream) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (!all_backward_done(p)) return fail(HPF_ESTATE, "sgd_step before all micro-batches ran backward");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hpf_status st = wait_all_backward(p, s);
+  if (st != HPF_OK) return st;
+  const Plan& P = p->P;
+  if (launch_sgd(p->params(), p->mom(), p->grads(), P.n_params, lr, momentum, s) != hipSuccess) return fail(HPF_EDEVICE, "sgd failed");
+  if (launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, s) != hipSuccess)
+    return fail(HPF_EDEVICE, "pack failed");
+  begin_next_batch(p, s);
+  return HPF_OK;
+}
+
+hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {
+  if (!p || !host_dst) return fail(HPF_EINVAL, "null argument");
+  if (n_floats != p->P.n_params) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_params);
+  if (hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(host_dst, p->params(), n_floats * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(HPF_EDEVICE, "device-to-host copy failed");
+  return HPF_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// single-kernel entry points
+// ---------------------------------------------------------------------------------------------
+static bool op_conv_args_ok(int b, int h, int wd, int cin, int cout, int R, int stride, bool bf16) {
+  if (b <= 0 || h <= 0 || wd <= 0 || cin <= 0 || cout <= 0) return false;
+  if ((R != 1 && R != 3) || (stride != 1 && stride != 2)) return false;
+  if (h % stride || wd % stride) return false;
+  if (bf16 && (cin % 16 || cout % 16)) return false;
+  return true;
+}
+
+// workspace layout: [0, 64*4) tickets | sums 2*Cmax floats | partials | packed bf16 weights (both copies)
+static size_t op_ws_tickets() { return 256; }
+static size_t op_ws_packed_off(int cmax) { return op_ws_tickets() + align_up(2 * (size_t)cmax * 4) + align_up(bn_partials_floats(cmax) * 4); }
+
+size_t hpf_op_workspace_bytes(int32_t cin, int32_t cout, int32_t R) {
+  const int cmax = cin > cout ? cin : cout;
+  const size_t T = (size_t)R * R;
+  return op_ws_packed_off(cmax) + align_up(((size_t)cout * round_up32((int)(T * cin)) + (size_t)cin * round_up32((int)(T * cout))) * 2 + 64) +
+         align_up(sizeof(PackDesc));
+}
+
+static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const float* w, void* out, const void* add, int b, int h,
+                          int wd, int cin, int cout, int R, int stride, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (!src || !w || !out) return fail(HPF_EINVAL, "null tensor");
+  const bool bf = dtype == HPF_BF16;
+  if (!op_conv_args_ok(b, h, wd, cin, cout, R, stride, bf)) return fail(HPF_EUNSUPPORTED, "unsupported convolution shape");
+  ConvGeom g{};
+  g.b = b; g.R = R; g.stride = stride; g.pad = (R - 1) / 2;
+  if (mode == CONV_FWD) { g.Ho = h / stride; g.Wo = wd / stride; g.Hs = h; g.Ws = wd; g.Cs = cin; g.N = cout; }
+  else { g.Ho = h; g.Wo = wd; g.Hs = h / stride; g.Ws = wd / stride; g.Cs = cout; g.N = cin; }
+  g.M = b * g.Ho * g.Wo; g.Ktot = R * R * g.Cs; g.Kpad = round_up32(g.Ktot);
+  if (!bf) {
+    if (launch_conv_f32(mode, (const float*)src, w, (float*)out, (const float*)add, g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+    return HPF_OK;
+  }
+  if (!ws || ws_bytes < hpf_op_workspace_bytes(cin, cout, R)) return fail(HPF_ENOMEM, "workspace too small");
+  const int cmax = cin > cout ? cin : cout;
+  char* base = (char*)ws + op_ws_packed_off(cmax);
+  PackDesc pd{};
+  pd.w_off = 0; pd.T = R * R; pd.Cin = cin; pd.Cout = cout;
+  pd.Kf = round_up32(pd.T * cin); pd.Kd = round_up32(pd.T * cout);
+  pd.wf_off = 0; pd.wd_off = ((size_t)cout * pd.Kf + 7) / 8 * 8;
+  const size_t table_off = align_up((pd.wd_off + (size_t)cin * pd.Kd) * 2);
+  if (hipMemcpyAsync(base + table_off, &pd, sizeof(pd), hipMemcpyHostToDevice, s) != hipSuccess) return fail(HPF_EDEVICE, "table copy failed");
+  if (hipStreamSynchronize(s) != hipSuccess) return fail(HPF_EDEVICE, "sync failed");   // pd is a stack object
+  if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
+  const bf16_t* wp = (const bf16_t*)base + (mode == CONV_FWD ? pd.wf_off : pd.wd_off);
+  if (launch_conv_mfma(mode, (const bf16_t*)src, wp, (bf16_t*)out, (const bf16_t*)add, g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  return HPF_OK;
+}
+
+hpf_status hpf_op_conv_forward(hpf_dtype dtype, const void* x, const float* w, void* y, const void* add, int32_t b, int32_t h,
+                               int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  return op_conv(CONV_FWD, dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+hpf_status hpf_op_conv_dgrad(hpf_dtype dtype, const void* dy, const float* w, void* dx, const void* add, int32_t b, int32_t h,
+                             int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  return op_conv(CONV_DGRAD, dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, float* dw, int32_t b, int32_t h, int32_t wd,
+                             int32_t cin, int32_t cout, int32_t R, int32_t stride, void* hip_stream) {
+  if (!x || !dy || !dw) return fail(HPF_EINVAL, "null tensor");
+  const bool bf = dtype == HPF_BF16;
+  if (!op_conv_args_ok(b, h, wd, cin, cout, R, stride, bf)) return fail(HPF_EUNSUPPORTED, "unsupported convolution shape");
+  WgradGeom g{};
+  g.b = b; g.H = h; g.W = wd; g.Cin = cin; g.Ho = h / stride; g.Wo = wd / stride; g.N = cout; g.R = R; g.stride = stride;
+  g.pad = (R - 1) / 2; g.M = b * g.Ho * g.Wo; g.c_valid = cin;
+  const hipError_t e = bf ? launch_wgrad_mfma((const bf16_t*)x, (const bf16_t*)dy, dw, g, (hipStream_t)hip_stream)
+                          : launch_wgrad_f32((const float*)x, (const float*)dy, dw, g, (hipStream_t)hip_stream);
+  return e == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "launch failed");
+}
+
+hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* gamma, const float* beta, float eps, void* a,
+                                  float* stats, int32_t M, int32_t C, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!x || !gamma || !beta || !a || !stats || !workspace) return fail(HPF_EINVAL, "null tensor");
+  if (M <= 0 || C <= 0 || C % 8) return fail(HPF_EUNSUPPORTED, "C must be a positive multiple of 8");
+  if (workspace_bytes < op_ws_packed_off(C)) return fail(HPF_ENOMEM, "workspace too small");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
+  char* ws = (char*)workspace;
+  float* partials = (float*)(ws + op_ws_tickets() + align_up(2 * (size_t)C * 4));
+  if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_stats(dt, x, M, C, eps, stats, partials, (unsigned*)ws, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_apply_relu(dt, x, a, gamma, beta, stats, M, C, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  return HPF_OK;
+}
+
+hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* da, const float* gamma, const float* beta,
+                                   const float* stats, const void* skip, void* dx, float* dgamma, float* dbeta, int32_t M,
+                                   int32_t C, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!x || !da || !gamma || !beta || !stats || !dx || !dgamma || !dbeta || !workspace) return fail(HPF_EINVAL, "null tensor");
+  if (M <= 0 || C <= 0 || C % 8) return fail(HPF_EUNSUPPORTED, "C must be a positive multiple of 8");
+  if (workspace_bytes < op_ws_packed_off(C)) return fail(HPF_ENOMEM, "workspace too small");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
+  char* ws = (char*)workspace;
+  float* sums = (float*)(ws + op_ws_tickets());
+  float* partials = (float*)(ws + op_ws_tickets() + align_up(2 * (size_t)C * 4));
+  if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_bwd_reduce(dt, x, da, gamma, beta, stats, M, C, sums, dgamma, dbeta, partials, (unsigned*)ws, s) != hipSuccess)
+    return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_bwd_apply(dt, x, da, gamma, beta, stats, sums, skip, dx, M, C, 0, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  return HPF_OK;
+}
+
+}  // extern "C"

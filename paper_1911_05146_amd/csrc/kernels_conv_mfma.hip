@@ -1,0 +1,187 @@
+// Implicit-GEMM convolution forward and data-gradient on bf16 MFMA (v_mfma_f32_16x16x32_bf16),
+// fp32 accumulation, NHWC tiles staged through LDS.
+//
+// Both passes are the same gather-GEMM
+//     out[m, n] = sum_k W[n, k] * src[row(m, tap(k)), c(k)],      k = tap*Cs + c,
+// with the reduction index k running over (filter tap, source channel).  The packed weights are
+// [N][Kpad] (k contiguous), the source tensor is NHWC, so for a fixed pixel row 8 consecutive k are
+// 16 contiguous bytes of one source pixel (Cs is a multiple of 8): the im2col matrix is never
+// materialised, each LDS-staging thread decodes (tap, c) for its 16-byte unit and either loads the
+// source pixel or writes zeros (padding, stride holes of the data-gradient, K padding).
+//
+// MFMA orientation: the weight tile is the first operand (rows = output channels) and the pixel
+// tile the second (columns = pixels), so each lane ends up with 4 consecutive output channels of
+// one pixel: the epilogue stores (and reads the optional residual) 8 bytes per lane, and the 4
+// lane groups of a wave cover 16 consecutive channels = 32 contiguous bytes per pixel.
+//
+// Work-group: 256 threads = 4 waves arranged WR x WC over a BM (pixels) x BN (channels) tile;
+// K advances 32 per step (one MFMA), double-buffered in LDS with one barrier per step and the
+// next step's global loads in flight during the MFMAs.
+#include "hpf_device.h"
+
+namespace hpf {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int KC = 32;          // reduction elements per step
+constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-free 16-byte reads)
+
+template <int BM, int BN, int WR, int WC, int MODE>
+__global__ __launch_bounds__(256) void k_conv_mfma(const bf16_t* __restrict__ src, const bf16_t* __restrict__ wpk,
+                                                   bf16_t* out, const bf16_t* add, ConvGeom g) {
+  static_assert(WR * WC == 4, "4 waves");
+  constexpr int WPX = BM / WR, WCH = BN / WC, PT = WPX / 16, CT = WCH / 16;
+  static_assert(PT >= 1 && CT >= 1, "tile too small");
+  constexpr int A_UNITS = (BM * 4) / 256;
+  static_assert(A_UNITS >= 1, "BM >= 64");
+  constexpr int W_UNITS = (BN * 4 + 255) / 256;
+
+  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * LSTR];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[2][BN * LSTR];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WC, wc = wave % WC;
+  const int row0 = blockIdx.x * BM, ch0 = blockIdx.y * BN;
+  const int grp = tid & 3;
+  const int HoWo = g.Ho * g.Wo;
+  const int sshift = g.stride - 1;  // stride is 1 or 2
+
+  int a_img[A_UNITS], a_h[A_UNITS], a_w[A_UNITS];
+  bool a_ok[A_UNITS];
+#pragma unroll
+  for (int u = 0; u < A_UNITS; ++u) {
+    const int m = row0 + (tid >> 2) + u * 64;
+    a_ok[u] = m < g.M;
+    const int mm = a_ok[u] ? m : 0;
+    const int img = mm / HoWo;
+    const int rem = mm - img * HoWo;
+    const int p = rem / g.Wo, q = rem - p * g.Wo;
+    a_img[u] = img * g.Hs * g.Ws;
+    if (MODE == CONV_FWD) { a_h[u] = p * g.stride - g.pad; a_w[u] = q * g.stride - g.pad; }
+    else { a_h[u] = p + g.pad; a_w[u] = q + g.pad; }
+  }
+
+  uint4 ra[A_UNITS], rw[W_UNITS];
+
+  auto load_chunk = [&](int kc) {
+    const int k = kc * KC + grp * 8;
+    const int tap = k / g.Cs;
+    const int c = k - tap * g.Cs;
+    const int r = tap / g.R, s = tap - r * g.R;
+    const bool kvalid = k < g.Ktot;
+#pragma unroll
+    for (int u = 0; u < A_UNITS; ++u) {
+      int hs, ws;
+      bool v = a_ok[u] && kvalid;
+      if (MODE == CONV_FWD) {
+        hs = a_h[u] + r; ws = a_w[u] + s;
+      } else {
+        const int th = a_h[u] - r, tw = a_w[u] - s;
+        v = v && th >= 0 && tw >= 0 && (((th | tw) & sshift) == 0);
+        hs = th >> sshift; ws = tw >> sshift;
+      }
+      v = v && (unsigned)hs < (unsigned)g.Hs && (unsigned)ws < (unsigned)g.Ws;
+      ra[u] = v ? *reinterpret_cast<const uint4*>(src + (size_t)(a_img[u] + hs * g.Ws + ws) * g.Cs + c)
+                : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int u = 0; u < W_UNITS; ++u) {
+      const int unit = tid + u * 256;
+      if (unit < BN * 4)
+        rw[u] = *reinterpret_cast<const uint4*>(wpk + (size_t)(ch0 + (unit >> 2)) * g.Kpad + kc * KC + (unit & 3) * 8);
+    }
+  };
+  auto store_chunk = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < A_UNITS; ++u)
+      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + u * 64) * LSTR + grp * 8]) = ra[u];
+#pragma unroll
+    for (int u = 0; u < W_UNITS; ++u) {
+      const int unit = tid + u * 256;
+      if (unit < BN * 4) *reinterpret_cast<uint4*>(&sW[buf][(unit >> 2) * LSTR + (unit & 3) * 8]) = rw[u];
+    }
+  };
+
+  floatx4 acc[CT][PT];
+#pragma unroll
+  for (int i = 0; i < CT; ++i)
+#pragma unroll
+    for (int j = 0; j < PT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int nk = g.Kpad / KC;
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+  for (int kc = 0; kc < nk; ++kc) {
+    const int buf = kc & 1;
+    if (kc + 1 < nk) load_chunk(kc + 1);
+    bf16x8 fa[PT], fw[CT];
+#pragma unroll
+    for (int j = 0; j < PT; ++j)
+      fa[j] = *reinterpret_cast<const bf16x8*>(&sA[buf][(wr * WPX + j * 16 + frag_row) * LSTR + frag_k]);
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+      fw[i] = *reinterpret_cast<const bf16x8*>(&sW[buf][(wc * WCH + i * 16 + frag_row) * LSTR + frag_k]);
+#pragma unroll
+    for (int i = 0; i < CT; ++i)
+#pragma unroll
+      for (int j = 0; j < PT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+    if (kc + 1 < nk) store_chunk(buf ^ 1);
+    __syncthreads();
+  }
+
+  // acc[i][j][v]: channel = ch0 + wc*WCH + i*16 + (lane>>4)*4 + v, pixel row = row0 + wr*WPX + j*16 + (lane&15)
+#pragma unroll
+  for (int j = 0; j < PT; ++j) {
+    const int m = row0 + wr * WPX + j * 16 + (lane & 15);
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+      const int ch = ch0 + wc * WCH + i * 16 + (lane >> 4) * 4;
+      const size_t o = (size_t)m * g.N + ch;
+      float v0 = acc[i][j][0], v1 = acc[i][j][1], v2 = acc[i][j][2], v3 = acc[i][j][3];
+      if (add) {
+        const uint2 t = *reinterpret_cast<const uint2*>(add + o);
+        v0 += __uint_as_float(t.x << 16); v1 += __uint_as_float(t.x & 0xffff0000u);
+        v2 += __uint_as_float(t.y << 16); v3 += __uint_as_float(t.y & 0xffff0000u);
+      }
+      uint2 st;
+      st.x = pack_bf16x2(v0, v1);
+      st.y = pack_bf16x2(v2, v3);
+      *reinterpret_cast<uint2*>(out + o) = st;
+    }
+  }
+}
+
+template <int BM, int BN, int WR, int WC>
+hipError_t launch_tile(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
+                       const ConvGeom& g, hipStream_t stream) {
+  const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN));
+  if (mode == CONV_FWD)
+    k_conv_mfma<BM, BN, WR, WC, CONV_FWD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g);
+  else
+    k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Tile choice: the widest channel tile that divides N, then the pixel tile that still gives the
+// chip (256 CUs) enough work-groups.
+hipError_t launch_conv_mfma(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
+                            const ConvGeom& g, hipStream_t stream) {
+  if (g.N % 16 != 0 || g.Cs % 8 != 0 || g.Kpad % KC != 0 || (g.stride != 1 && g.stride != 2)) return hipErrorInvalidValue;
+  if (g.N % 128 == 0) {
+    const long wgs = (long)((g.M + 127) / 128) * (g.N / 128);
+    if (wgs >= 192) return launch_tile<128, 128, 2, 2>(mode, src, wpk, out, add, g, stream);
+  }
+  if (g.N % 64 == 0) return launch_tile<64, 64, 2, 2>(mode, src, wpk, out, add, g, stream);
+  if (g.N % 32 == 0) return launch_tile<64, 32, 4, 1>(mode, src, wpk, out, add, g, stream);
+  return launch_tile<64, 16, 4, 1>(mode, src, wpk, out, add, g, stream);
+}
+
+}  // namespace hpf

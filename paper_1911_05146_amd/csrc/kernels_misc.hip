@@ -1,0 +1,224 @@
+// Small kernels around the convolutions: stem im2col, classification head (global average pool,
+// FC, softmax cross-entropy -- the loss of the last partition, paper Eq. 1-2), SGD with momentum
+// (apply_gradients), weight packing for the MFMA operands, fills and copies.
+#include "hpf_device.h"
+
+namespace hpf {
+namespace {
+
+// col[m, k] for k = (r*3+s)*Cin + c, zero for taps outside the image and for k >= 9*Cin.
+__global__ __launch_bounds__(256) void k_im2col3x3(const float* __restrict__ img, bf16_t* __restrict__ col, int b,
+                                                   int H, int W, int Cin, int Kc) {
+  const size_t total = (size_t)b * H * W * Kc;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int k = (int)(i % Kc);
+    const size_t m = i / Kc;
+    const int q = (int)(m % W);
+    const int p = (int)((m / W) % H);
+    const int n = (int)(m / ((size_t)W * H));
+    float v = 0.f;
+    if (k < 9 * Cin) {
+      const int tap = k / Cin, c = k - tap * Cin;
+      const int hi = p + tap / 3 - 1, wi = q + tap % 3 - 1;
+      if ((unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W) v = img[(((size_t)n * H + hi) * W + wi) * Cin + c];
+    }
+    col[i] = f32_to_bf16(v);
+  }
+}
+
+__device__ __forceinline__ float block_reduce_max(float v, float* sh) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = fmaxf(r, sh[w]);
+  __syncthreads();
+  return r;
+}
+
+__device__ __forceinline__ float block_reduce_sum(float v, float* sh) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r += sh[w];
+  __syncthreads();
+  return r;
+}
+
+// One block per sample.  Dynamic LDS: C + classes floats.
+template <class T>
+__global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ a, const float* __restrict__ wfc,
+                                                  const float* __restrict__ bfc, const int32_t* __restrict__ labels,
+                                                  float* __restrict__ g, float* __restrict__ dlogits,
+                                                  float* loss_accum, int hw, int C, int classes, float inv_div) {
+  extern __shared__ float dyn[];
+  __shared__ float red[8];
+  float* gs = dyn;
+  float* lg = dyn + C;
+  const int n = blockIdx.x;
+  const T* an = a + (size_t)n * hw * C;
+  const float inv_hw = 1.0f / (float)hw;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int i = 0; i < hw; ++i) s += to_f32(an[(size_t)i * C + c]);
+    s *= inv_hw;
+    gs[c] = s;
+    g[(size_t)n * C + c] = s;
+  }
+  __syncthreads();
+  float mx = -3.0e38f;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    float s = bfc[j];
+    for (int c = 0; c < C; ++c) s = fmaf(gs[c], wfc[(size_t)c * classes + j], s);
+    lg[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = block_reduce_max(mx, red);
+  float den = 0.f;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) den += expf(lg[j] - mx);
+  den = block_reduce_sum(den, red);
+  const int y = labels[n];
+  for (int j = threadIdx.x; j < classes; j += blockDim.x)
+    dlogits[(size_t)n * classes + j] = (expf(lg[j] - mx) / den - (j == y ? 1.f : 0.f)) * inv_div;
+  if (threadIdx.x == 0) atomicAdd(loss_accum, -(lg[y] - mx - logf(den)) * inv_div);
+}
+
+// One block per sample: dWfc += g^T dlogits, dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw.
+template <class T>
+__global__ __launch_bounds__(256) void k_head_bwd(const float* __restrict__ g, const float* __restrict__ dlogits,
+                                                  const float* __restrict__ wfc, float* g_wfc, float* g_bfc,
+                                                  T* __restrict__ da, int hw, int C, int classes) {
+  extern __shared__ float dyn[];
+  float* dl = dyn;          // classes
+  float* dg = dyn + classes;  // C
+  const int n = blockIdx.x;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    const float d = dlogits[(size_t)n * classes + j];
+    dl[j] = d;
+    atomicAdd(&g_bfc[j], d);
+  }
+  __syncthreads();
+  const float inv_hw = 1.0f / (float)hw;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int j = 0; j < classes; ++j) s = fmaf(dl[j], wfc[(size_t)c * classes + j], s);
+    dg[c] = s * inv_hw;
+  }
+  for (int i = threadIdx.x; i < C * classes; i += blockDim.x) {
+    const int c = i / classes, j = i - c * classes;
+    atomicAdd(&g_wfc[i], g[(size_t)n * C + c] * dl[j]);
+  }
+  __syncthreads();
+  T* dan = da + (size_t)n * hw * C;
+  for (int i = threadIdx.x; i < hw * C; i += blockDim.x) from_f32(&dan[i], dg[i % C]);
+}
+
+__global__ __launch_bounds__(256) void k_sgd(float* __restrict__ w, float* __restrict__ v, float* __restrict__ g,
+                                             size_t n, float lr, float mu) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float vel = fmaf(mu, v[i], g[i]);
+    v[i] = vel;
+    w[i] = fmaf(-lr, vel, w[i]);
+    g[i] = 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_zero_f32(float* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void k_copy16(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16,
+                                                unsigned char* dtail, const unsigned char* stail, int ntail) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) dtail[threadIdx.x] = stail[threadIdx.x];
+}
+
+// grid (n_convs, 8): block (i, j) fills every 8th 256-element chunk of conv i's two packed copies.
+__global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ params, bf16_t* __restrict__ packed,
+                                                      const PackDesc* __restrict__ table) {
+  const PackDesc d = table[blockIdx.x];
+  const float* w = params + d.w_off;
+  {
+    bf16_t* wf = packed + d.wf_off;  // [Cout][Kf], k = tap*Cin + c
+    const int total = d.Cout * d.Kf, ktot = d.T * d.Cin;
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < total; i += gridDim.y * 256) {
+      const int n = i / d.Kf, k = i - n * d.Kf;
+      wf[i] = f32_to_bf16(k < ktot ? w[(size_t)k * d.Cout + n] : 0.f);
+    }
+  }
+  if (d.wd_off != ~0ull) {
+    bf16_t* wd = packed + d.wd_off;  // [Cin][Kd], k = tap*Cout + n
+    const int total = d.Cin * d.Kd, ktot = d.T * d.Cout;
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < total; i += gridDim.y * 256) {
+      const int c = i / d.Kd, k = i - c * d.Kd;
+      float v = 0.f;
+      if (k < ktot) {
+        const int tap = k / d.Cout, n = k - tap * d.Cout;
+        v = w[((size_t)tap * d.Cin + c) * d.Cout + n];
+      }
+      wd[i] = f32_to_bf16(v);
+    }
+  }
+}
+
+unsigned grid_for(size_t n, unsigned cap = 2048) {
+  size_t g = (n + 255) / 256;
+  if (g < 1) g = 1;
+  return (unsigned)(g > cap ? cap : g);
+}
+
+}  // namespace
+
+hipError_t launch_im2col3x3(const float* img, bf16_t* col, int b, int H, int W, int Cin, int Kc, hipStream_t stream) {
+  k_im2col3x3<<<grid_for((size_t)b * H * W * Kc), 256, 0, stream>>>(img, col, b, H, W, Cin, Kc);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_fwd(int dt, const void* a, const float* wfc, const float* bfc, const int32_t* labels,
+                           float* g, float* dlogits, float* loss_accum, int b, int hw, int C, int classes,
+                           float divisor, hipStream_t stream) {
+  const size_t lds = (size_t)(C + classes) * sizeof(float);
+  if (dt == DT_BF16)
+    k_head_fwd<bf16_t><<<b, 256, lds, stream>>>((const bf16_t*)a, wfc, bfc, labels, g, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
+  else
+    k_head_fwd<float><<<b, 256, lds, stream>>>((const float*)a, wfc, bfc, labels, g, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_bwd(int dt, const float* g, const float* dlogits, const float* wfc, float* g_wfc,
+                           float* g_bfc, void* da, int b, int hw, int C, int classes, hipStream_t stream) {
+  const size_t lds = (size_t)(C + classes) * sizeof(float);
+  if (dt == DT_BF16)
+    k_head_bwd<bf16_t><<<b, 256, lds, stream>>>(g, dlogits, wfc, g_wfc, g_bfc, (bf16_t*)da, hw, C, classes);
+  else
+    k_head_bwd<float><<<b, 256, lds, stream>>>(g, dlogits, wfc, g_wfc, g_bfc, (float*)da, hw, C, classes);
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, hipStream_t stream) {
+  k_sgd<<<grid_for(n, 4096), 256, 0, stream>>>(w, v, g, n, lr, mu);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream) {
+  k_zero_f32<<<grid_for(n, 4096), 256, 0, stream>>>(p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
+                               hipStream_t stream) {
+  if (n_convs <= 0) return hipSuccess;
+  k_pack_weights<<<dim3((unsigned)n_convs, 8), 256, 0, stream>>>(params, packed, table_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  const int ntail = (int)(bytes - n16 * 16);
+  k_copy16<<<grid_for(n16, 4096), 256, 0, stream>>>((uint4*)dst, (const uint4*)src, n16, (unsigned char*)dst + n16 * 16,
+                                                    (const unsigned char*)src + n16 * 16, ntail);
+  return hipGetLastError();
+}
+
+}  // namespace hpf

@@ -1,0 +1,343 @@
+"""ctypes binding to libhpf.so -- argument marshalling only.
+
+Functions carry the names of the C ABI (include/hpf.h) and take raw device addresses
+(ints, e.g. torch.Tensor.data_ptr()) and stream handles; every step of the path runs in
+the library's HIP kernels.  `Partition` is a small convenience wrapper that owns the torch
+arena tensor and checks shapes/dtypes.  There is no CPU fallback: if the library cannot be
+loaded the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhpf.so")
+
+HPF_ABI_VERSION = 1
+HPF_OK, HPF_EINVAL, HPF_ESTATE, HPF_ENOMEM, HPF_EDEVICE, HPF_EUNSUPPORTED = range(6)
+HPF_F32, HPF_BF16 = 0, 1
+STATUS_NAMES = {0: "HPF_OK", 1: "HPF_EINVAL", 2: "HPF_ESTATE", 3: "HPF_ENOMEM", 4: "HPF_EDEVICE",
+                5: "HPF_EUNSUPPORTED"}
+
+
+class hpf_block_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("c_in", C.c_int32), ("c_mid", C.c_int32), ("c_out", C.c_int32),
+                ("stride", C.c_int32)]
+
+
+class hpf_partition_desc(C.Structure):
+    _fields_ = [("abi_version", C.c_uint32), ("in_h", C.c_int32), ("in_w", C.c_int32), ("in_c", C.c_int32),
+                ("has_stem", C.c_int32), ("stem_c_out", C.c_int32), ("n_blocks", C.c_int32),
+                ("blocks", C.POINTER(hpf_block_desc)), ("has_head", C.c_int32), ("num_classes", C.c_int32),
+                ("microbatch", C.c_int32), ("num_microbatches", C.c_int32), ("loss_divisor", C.c_int32),
+                ("compute_dtype", C.c_int), ("bn_eps", C.c_float), ("bn_mode", C.c_int32)]
+
+
+class hpf_sizes(C.Structure):
+    _fields_ = [("n_params", C.c_size_t), ("arena_bytes", C.c_size_t), ("stash_bytes", C.c_size_t),
+                ("act_in_elems", C.c_size_t), ("act_out_elems", C.c_size_t)]
+
+
+class HpfError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1911_05146_amd.build` "
+                          "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    L.hpf_last_error.restype = C.c_char_p
+    L.hpf_partition_sizes.argtypes = [C.POINTER(hpf_partition_desc), C.POINTER(hpf_sizes)]
+    L.hpf_partition_create.argtypes = [C.POINTER(hpf_partition_desc), vp, sz, vp, C.POINTER(vp)]
+    L.hpf_forward_microbatch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    L.hpf_backward_microbatch.argtypes = [vp, i32, vp, vp, vp]
+    L.hpf_grad_accum_read.argtypes = [vp, vp, sz, i32, vp]
+    L.hpf_grad_accum_zero.argtypes = [vp, vp]
+    L.hpf_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
+    L.hpf_params_read.argtypes = [vp, vp, sz]
+    L.hpf_partition_destroy.argtypes = [vp]
+    L.hpf_partition_destroy.restype = None
+    L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
+    L.hpf_op_workspace_bytes.restype = sz
+    L.hpf_op_conv_forward.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+    L.hpf_op_conv_dgrad.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+    L.hpf_op_conv_wgrad.argtypes = [C.c_int, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    L.hpf_op_bn_relu_forward.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]
+    L.hpf_op_bn_relu_backward.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    return L
+
+
+lib = _load()
+
+EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatch", "hpf_backward_microbatch",
+           "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
+           "hpf_partition_destroy", "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
+           "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
+
+
+def hpf_last_error() -> str:
+    return lib.hpf_last_error().decode()
+
+
+def _check(status):
+    if status != HPF_OK:
+        raise HpfError(status, hpf_last_error())
+
+
+def make_desc(spec, compute_dtype=HPF_BF16):
+    """hpf_partition_desc from an object with the fields of workloads.PartitionSpec.
+    Returns (desc, keepalive)."""
+    n = len(spec.blocks)
+    arr = (hpf_block_desc * max(n, 1))()
+    for i, b in enumerate(spec.blocks):
+        arr[i] = hpf_block_desc(b.kind, b.c_in, b.c_mid, b.c_out, b.stride)
+    d = hpf_partition_desc(HPF_ABI_VERSION, spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
+                           n, C.cast(arr, C.POINTER(hpf_block_desc)), int(spec.has_head), spec.num_classes,
+                           spec.microbatch, spec.num_microbatches, spec.divisor, compute_dtype,
+                           float(spec.bn_eps), spec.bn_mode)
+    return d, arr
+
+
+def hpf_partition_sizes(desc) -> hpf_sizes:
+    out = hpf_sizes()
+    _check(lib.hpf_partition_sizes(C.byref(desc), C.byref(out)))
+    return out
+
+
+def hpf_partition_create(desc, device_arena: int, arena_bytes: int, host_params) -> int:
+    """host_params: contiguous float32 numpy array."""
+    h = C.c_void_p()
+    _check(lib.hpf_partition_create(C.byref(desc), device_arena, arena_bytes,
+                                    host_params.ctypes.data_as(C.c_void_p), C.byref(h)))
+    return h.value
+
+
+def hpf_forward_microbatch(handle, mb, act_in, labels, act_out, loss_accum, stream=0):
+    _check(lib.hpf_forward_microbatch(handle, mb, act_in, labels or None, act_out or None, loss_accum or None,
+                                      stream or None))
+
+
+def hpf_backward_microbatch(handle, mb, err_in, err_out, stream=0):
+    _check(lib.hpf_backward_microbatch(handle, mb, err_in or None, err_out or None, stream or None))
+
+
+def hpf_grad_accum_read(handle, dst, n_floats, dst_is_device, stream=0):
+    _check(lib.hpf_grad_accum_read(handle, dst, n_floats, int(dst_is_device), stream or None))
+
+
+def hpf_grad_accum_zero(handle, stream=0):
+    _check(lib.hpf_grad_accum_zero(handle, stream or None))
+
+
+def hpf_sgd_step(handle, lr, momentum, stream=0):
+    _check(lib.hpf_sgd_step(handle, lr, momentum, stream or None))
+
+
+def hpf_params_read(handle, host_dst, n_floats):
+    _check(lib.hpf_params_read(handle, host_dst, n_floats))
+
+
+def hpf_partition_destroy(handle):
+    lib.hpf_partition_destroy(handle)
+
+
+def hpf_op_workspace_bytes(cin, cout, R) -> int:
+    return int(lib.hpf_op_workspace_bytes(cin, cout, R))
+
+
+def hpf_op_conv_forward(dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, stream=0):
+    _check(lib.hpf_op_conv_forward(dtype, x, w, y, add or None, b, h, wd, cin, cout, R, stride, workspace,
+                                   workspace_bytes, stream or None))
+
+
+def hpf_op_conv_dgrad(dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, stream=0):
+    _check(lib.hpf_op_conv_dgrad(dtype, dy, w, dx, add or None, b, h, wd, cin, cout, R, stride, workspace,
+                                 workspace_bytes, stream or None))
+
+
+def hpf_op_conv_wgrad(dtype, x, dy, dw, b, h, wd, cin, cout, R, stride, stream=0):
+    _check(lib.hpf_op_conv_wgrad(dtype, x, dy, dw, b, h, wd, cin, cout, R, stride, stream or None))
+
+
+def hpf_op_bn_relu_forward(dtype, x, gamma, beta, eps, a, stats, M, Cc, workspace, workspace_bytes, stream=0):
+    _check(lib.hpf_op_bn_relu_forward(dtype, x, gamma, beta, eps, a, stats, M, Cc, workspace, workspace_bytes,
+                                      stream or None))
+
+
+def hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip, dx, dgamma, dbeta, M, Cc, workspace,
+                            workspace_bytes, stream=0):
+    _check(lib.hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip or None, dx, dgamma, dbeta, M, Cc,
+                                       workspace, workspace_bytes, stream or None))
+
+
+class Ops:
+    """Single kernels on torch tensors (tests and kernel benchmarks)."""
+
+    def __init__(self, compute_dtype=HPF_BF16, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.dt = compute_dtype
+        self.tdtype = torch.bfloat16 if compute_dtype == HPF_BF16 else torch.float32
+        self.device = torch.device(device)
+        self._ws = None
+
+    def workspace(self, cin, cout, R):
+        n = hpf_op_workspace_bytes(cin, cout, R)
+        if self._ws is None or self._ws.numel() < n + 256:
+            self._ws = self.torch.zeros(n + 256, dtype=self.torch.uint8, device=self.device)
+        base = (self._ws.data_ptr() + 255) // 256 * 256
+        return base, n
+
+    def _s(self):
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def conv_forward(self, x, w, stride=1, add=None, out=None):
+        b, h, wd, cin = x.shape
+        R, _, _, cout = w.shape
+        y = out if out is not None else self.torch.empty((b, h // stride, wd // stride, cout), dtype=self.tdtype, device=self.device)
+        ws, n = self.workspace(cin, cout, R)
+        hpf_op_conv_forward(self.dt, x.data_ptr(), w.data_ptr(), y.data_ptr(), add.data_ptr() if add is not None else 0,
+                            b, h, wd, cin, cout, R, stride, ws, n, self._s())
+        return y
+
+    def conv_dgrad(self, dy, w, in_hw, stride=1, add=None, out=None):
+        b = dy.shape[0]
+        R, _, cin, cout = w.shape
+        h, wd = in_hw
+        dx = out if out is not None else self.torch.empty((b, h, wd, cin), dtype=self.tdtype, device=self.device)
+        ws, n = self.workspace(cin, cout, R)
+        hpf_op_conv_dgrad(self.dt, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), add.data_ptr() if add is not None else 0,
+                          b, h, wd, cin, cout, R, stride, ws, n, self._s())
+        return dx
+
+    def conv_wgrad(self, x, dy, R, stride=1, out=None):
+        b, h, wd, cin = x.shape
+        cout = dy.shape[-1]
+        dw = out if out is not None else self.torch.zeros((R, R, cin, cout), dtype=self.torch.float32, device=self.device)
+        hpf_op_conv_wgrad(self.dt, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), b, h, wd, cin, cout, R, stride, self._s())
+        return dw
+
+    def bn_relu_forward(self, x, gamma, beta, eps=1e-5, out=None):
+        Cc = x.shape[-1]
+        M = x.numel() // Cc
+        a = out if out is not None else self.torch.empty_like(x)
+        stats = self.torch.empty(2 * Cc, dtype=self.torch.float32, device=self.device)
+        ws, n = self.workspace(Cc, Cc, 1)
+        hpf_op_bn_relu_forward(self.dt, x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), eps, a.data_ptr(),
+                               stats.data_ptr(), M, Cc, ws, n, self._s())
+        return a, stats
+
+    def bn_relu_backward(self, x, da, gamma, beta, stats, skip=None, out=None):
+        Cc = x.shape[-1]
+        M = x.numel() // Cc
+        dx = out if out is not None else self.torch.empty_like(x)
+        dg = self.torch.zeros(Cc, dtype=self.torch.float32, device=self.device)
+        db = self.torch.zeros(Cc, dtype=self.torch.float32, device=self.device)
+        ws, n = self.workspace(Cc, Cc, 1)
+        hpf_op_bn_relu_backward(self.dt, x.data_ptr(), da.data_ptr(), gamma.data_ptr(), beta.data_ptr(), stats.data_ptr(),
+                                skip.data_ptr() if skip is not None else 0, dx.data_ptr(), dg.data_ptr(), db.data_ptr(),
+                                M, Cc, ws, n, self._s())
+        return dx, dg, db
+
+
+class Partition:
+    """One partition on the current torch device.  torch supplies device memory and streams."""
+
+    def __init__(self, spec, params, compute_dtype=HPF_BF16, device="cuda:0"):
+        import numpy as np
+        import torch
+        self.torch = torch
+        self.spec = spec
+        self.compute_dtype = compute_dtype
+        self.tdtype = torch.bfloat16 if compute_dtype == HPF_BF16 else torch.float32
+        self.device = torch.device(device)
+        self.desc, self._keep = make_desc(spec, compute_dtype)
+        self.sizes = hpf_partition_sizes(self.desc)
+        params = np.ascontiguousarray(params, dtype=np.float32)
+        if params.size != self.sizes.n_params:
+            raise ValueError(f"expected {self.sizes.n_params} parameters, got {params.size}")
+        self.n_params = int(self.sizes.n_params)
+        self.arena = torch.empty(int(self.sizes.arena_bytes) + 256, dtype=torch.uint8, device=self.device)
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        with torch.cuda.device(self.device):
+            self.handle = hpf_partition_create(self.desc, base, int(self.sizes.arena_bytes), params)
+        oh, ow, oc = spec.out_shape()
+        self.in_shape = (spec.microbatch, spec.in_h, spec.in_w, spec.in_c)
+        self.out_shape = (spec.microbatch, oh, ow, oc)
+        self.in_dtype = torch.float32 if spec.has_stem else self.tdtype
+        self.loss = torch.zeros(1, dtype=torch.float32, device=self.device)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            hpf_partition_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _stream(stream):
+        if stream is None:
+            return 0
+        return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+    def _stream_or_current(self, stream):
+        return self._stream(stream if stream is not None else self.torch.cuda.current_stream(self.device))
+
+    def forward_microbatch(self, mb, act_in, labels=None, act_out=None, stream=None):
+        assert tuple(act_in.shape) == self.in_shape and act_in.dtype == self.in_dtype and act_in.is_contiguous()
+        if self.spec.has_head:
+            assert labels is not None and labels.dtype == self.torch.int32 and labels.numel() == self.spec.microbatch
+        else:
+            if act_out is None:
+                act_out = self.torch.empty(self.out_shape, dtype=self.tdtype, device=self.device)
+            assert tuple(act_out.shape) == self.out_shape and act_out.dtype == self.tdtype and act_out.is_contiguous()
+        hpf_forward_microbatch(self.handle, mb, act_in.data_ptr(),
+                               labels.data_ptr() if labels is not None else 0,
+                               act_out.data_ptr() if act_out is not None else 0,
+                               self.loss.data_ptr() if self.spec.has_head else 0,
+                               self._stream_or_current(stream))
+        return act_out
+
+    def backward_microbatch(self, mb, err_in=None, err_out=None, stream=None):
+        if not self.spec.has_head:
+            assert tuple(err_in.shape) == self.out_shape and err_in.dtype == self.tdtype and err_in.is_contiguous()
+        if not self.spec.has_stem:
+            if err_out is None:
+                err_out = self.torch.empty(self.in_shape, dtype=self.tdtype, device=self.device)
+            assert tuple(err_out.shape) == self.in_shape and err_out.dtype == self.tdtype and err_out.is_contiguous()
+        hpf_backward_microbatch(self.handle, mb, err_in.data_ptr() if err_in is not None else 0,
+                                err_out.data_ptr() if err_out is not None else 0, self._stream_or_current(stream))
+        return err_out
+
+    def grad_accum_read(self, out=None, stream=None):
+        """Returns the accumulated gradient: into a device tensor `out` (async) or as a numpy array."""
+        if out is not None:
+            assert out.dtype == self.torch.float32 and out.numel() == self.n_params and out.is_contiguous()
+            hpf_grad_accum_read(self.handle, out.data_ptr(), self.n_params, True, self._stream_or_current(stream))
+            return out
+        import numpy as np
+        g = np.empty(self.n_params, np.float32)
+        hpf_grad_accum_read(self.handle, g.ctypes.data, self.n_params, False, self._stream_or_current(stream))
+        return g
+
+    def grad_accum_zero(self, stream=None):
+        hpf_grad_accum_zero(self.handle, self._stream_or_current(stream))
+
+    def sgd_step(self, lr, momentum, stream=None):
+        hpf_sgd_step(self.handle, lr, momentum, self._stream_or_current(stream))
+
+    def params_read(self):
+        import numpy as np
+        p = np.empty(self.n_params, np.float32)
+        hpf_params_read(self.handle, p.ctypes.data, self.n_params)
+        return p

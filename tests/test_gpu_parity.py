@@ -1,0 +1,207 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on the same seeded
+inputs, through the C ABI.  Tolerances (max|gpu-ref| / max|ref| per tensor): 2e-2 with bf16
+operands, 1e-4 in the fp32 check mode."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_1911_05146_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: these tests need a real MI355X")
+    from paper_1911_05146_amd import hpf
+    return hpf
+
+
+def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=True, tol=None):
+    from parity import compare, run_gpu_step
+    print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream}", flush=True)
+    inp = W.make_inputs(spec, randomize_affine=randomize_affine)
+    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd)
+    # bf16 mode: the reference stores the same tensors as bfloat16 (the precision reading of the
+    # bf16 mode), so every ReLU decision is taken on the same stored values on both sides
+    ref = oracle.run_step(spec, seen, np.float32, sgd=sgd, storage="bf16" if mode == "bf16" else "none")
+    rep = compare(spec, res, ref, mode, tol=tol)
+    print(f"[parity] {spec.name} {mode}: " + ", ".join(f"{k}={v:.2e}" for k, v in rep.items()), flush=True)
+    return rep
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet20_whole_model_with_sgd(gpu, oracle, mode):
+    check(oracle, W.config(1), mode, sgd=(0.1, 0.9))
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet20_default_init(gpu, oracle, mode):
+    check(oracle, W.config(1), mode, randomize_affine=False)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet110_partition(gpu, oracle, mode):
+    check(oracle, W.with_microbatching(W.config(2), 16, 2, loss_divisor=128), mode)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet110_other_partitions(gpu, oracle, mode):
+    for p in (0, 1, 3):
+        check(oracle, W.resnet110_partition(p=p, microbatch=4, num_microbatches=2), mode)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet1001_partition_two_microbatches(gpu, oracle, mode):
+    check(oracle, W.with_microbatching(W.config(3), 32, 2, loss_divisor=256), mode)
+
+
+def test_resnet1001_partition_full_batch_on_streams(gpu, oracle):
+    """The benchmark's launch configuration: 8 micro-batches of 32, one stream each."""
+    check(oracle, W.config(3), "bf16", multi_stream=True, randomize_affine=False)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet1001_whole_model_small_batch(gpu, oracle, mode):
+    check(oracle, W.resnet1001_whole(microbatch=2, num_microbatches=2), mode, sgd=(0.1, 0.9), randomize_affine=False)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet152_stage3_first_blocks(gpu, oracle, mode):
+    check(oracle, W.resnet152_stage3(n_blocks=3, microbatch=2, num_microbatches=2), mode)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_ragged_tiles_and_single_image(gpu, oracle, mode):
+    # 14x14 images, b = 3: 588 rows -- not a multiple of any tile; b = 1 with stride 2
+    blocks = (W.Block(W.BOTTLENECK, 64, 32, 128, 2), W.Block(W.BOTTLENECK, 128, 32, 128, 1),
+              W.Block(W.BASIC, 128, 48 if mode == "f32" else 64, 48 if mode == "f32" else 64, 1))
+    spec = W.PartitionSpec(name="ragged", in_h=28, in_w=28, in_c=64, blocks=blocks, microbatch=3, num_microbatches=2, seed=5)
+    check(oracle, spec, mode)
+    check(oracle, replace(spec, name="single-image", microbatch=1, num_microbatches=3), mode)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_head_only_and_stem_only_partitions(gpu, oracle, mode):
+    head = W.PartitionSpec(name="head-only", in_h=8, in_w=8, in_c=64, blocks=(), has_head=True, num_classes=10,
+                           microbatch=4, num_microbatches=2, seed=9)
+    check(oracle, head, mode)
+    stem = W.PartitionSpec(name="stem-only", in_h=16, in_w=16, in_c=3, blocks=(), has_stem=True, stem_c_out=16,
+                           microbatch=2, num_microbatches=2, seed=10)
+    check(oracle, stem, mode)
+    wide = W.PartitionSpec(name="head-1000-classes", in_h=7, in_w=7, in_c=256, blocks=(), has_head=True,
+                           num_classes=1000, microbatch=3, num_microbatches=1, seed=12)
+    check(oracle, wide, mode)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_frozen_batchnorm_mode(gpu, oracle, mode):
+    check(oracle, replace(W.resnet110_partition(p=2, microbatch=4, num_microbatches=2), bn_mode=1), mode)
+
+
+def test_streams_give_the_same_result_as_one_stream(gpu, oracle):
+    from parity import run_gpu_step, rel_err
+    spec = W.with_microbatching(W.config(2), 16, 4, loss_divisor=128)
+    inp = W.make_inputs(spec)
+    _, a = run_gpu_step(spec, inp, "bf16", multi_stream=False)
+    _, b = run_gpu_step(spec, inp, "bf16", multi_stream=True)
+    for x, y in zip(a["act_out"] + a["err_out"], b["act_out"] + b["err_out"]):
+        assert np.array_equal(x, y)                      # activations and errors: no atomics involved
+    assert rel_err(b["grad"], a["grad"]) < 1e-5          # gradient sums: fp32 atomics, order may differ
+
+
+def test_two_batches_accumulate_zero_and_step(gpu, oracle):
+    """Gradient buffer life cycle over consecutive batches on one handle."""
+    from parity import run_gpu_step, rel_err
+    spec = W.resnet110_partition(p=3, microbatch=4, num_microbatches=2)
+    inp = W.make_inputs(spec, randomize_affine=True)
+    seen, r1 = run_gpu_step(spec, inp, "f32", keep=True)
+    part = r1["part"]
+    part.grad_accum_zero()
+    _, r2 = run_gpu_step(spec, inp, "f32", part=part)          # same batch again after zeroing
+    assert rel_err(r2["grad"], r1["grad"]) < 1e-5
+    part.sgd_step(0.1, 0.9)
+    w1 = part.params_read()
+    assert rel_err(w1, inp.params - 0.1 * r2["grad"]) < 1e-6
+    _, r3 = run_gpu_step(spec, inp, "f32", part=part)          # next batch: buffer was cleared by the step
+    ref = oracle.OraclePartition(spec, w1)
+    for i in range(2):
+        ref.forward(i, seen.act_in[i], seen.labels[i])
+    for i in range(2):
+        ref.backward(i, None, want_err_out=False)
+    assert rel_err(r3["grad"], ref.grad()) < 1e-4
+    part.sgd_step(0.1, 0.9)
+    assert rel_err(part.params_read(), w1 - 0.1 * (0.9 * r2["grad"] + r3["grad"])) < 1e-5
+    part.close()
+
+
+def test_call_order_and_arguments_are_enforced(gpu):
+    import torch
+    hpf = gpu
+    spec = W.resnet110_partition(p=2, microbatch=2, num_microbatches=2)
+    inp = W.make_inputs(spec)
+    part = hpf.Partition(spec, inp.params)
+    x = torch.zeros(part.in_shape, dtype=torch.bfloat16, device="cuda:0")
+    e = torch.zeros(part.out_shape, dtype=torch.bfloat16, device="cuda:0")
+
+    def status(fn, *a, **k):
+        with pytest.raises(hpf.HpfError) as ei:
+            fn(*a, **k)
+        return ei.value.status
+
+    assert status(part.backward_microbatch, 0, e) == hpf.HPF_ESTATE
+    assert status(part.forward_microbatch, 2, x) == hpf.HPF_EINVAL
+    part.forward_microbatch(0, x)
+    assert status(part.forward_microbatch, 0, x) == hpf.HPF_ESTATE
+    assert status(part.grad_accum_read) == hpf.HPF_ESTATE
+    assert status(part.sgd_step, 0.1, 0.9) == hpf.HPF_ESTATE
+    assert status(part.grad_accum_zero) == hpf.HPF_ESTATE
+    part.backward_microbatch(0, e)
+    assert status(part.backward_microbatch, 0, e) == hpf.HPF_ESTATE
+    assert status(hpf.hpf_backward_microbatch, part.handle, 1, 0, 0) == hpf.HPF_EINVAL
+    part.forward_microbatch(1, x)
+    part.backward_microbatch(1, e)
+    part.grad_accum_read()
+    part.sgd_step(0.1, 0.9)
+    part.forward_microbatch(0, x)                          # next batch may start
+    torch.cuda.synchronize()
+    part.close()
+
+
+def test_partition_chain_on_device_equals_unsplit_model(gpu):
+    """The paper's premise on the GPU: ResNet-20 as 3 chained partitions == one partition."""
+    import torch
+    from parity import rel_err, run_gpu_step
+    hpf = gpu
+    whole = W.resnet20(microbatch=4, num_microbatches=2)
+    inp = W.make_inputs(whole, randomize_affine=True)
+    _, ref = run_gpu_step(whole, inp, "bf16")
+    blocks = W.basic_resnet_blocks(3)
+    specs = [W.partition_of(f"p{p}", blocks, 3, p, 32, 16, 16, 10, 4, 2, whole.seed) for p in range(3)]
+    parts, off = [], 0
+    for s in specs:
+        n = W.n_params(s)
+        parts.append(hpf.Partition(s, inp.params[off:off + n]))
+        off += n
+    dev = torch.device("cuda:0")
+    acts = []
+    for i in range(2):
+        x = torch.from_numpy(inp.act_in[i]).to(dev)
+        lab = torch.from_numpy(inp.labels[i]).to(dev)
+        chain = [x]
+        for p, part in enumerate(parts):
+            chain.append(part.forward_microbatch(i, chain[-1], lab if specs[p].has_head else None))
+        acts.append(chain)
+    for i in range(2):
+        e = None
+        for p in reversed(range(3)):
+            e = parts[p].backward_microbatch(i, e)
+    G = np.concatenate([p.grad_accum_read() for p in parts])
+    torch.cuda.synchronize()
+    assert abs(parts[-1].loss.item() - ref["loss"]) <= 1e-6 * abs(ref["loss"])
+    assert rel_err(G, ref["grad"]) < 1e-5
+    for p in parts:
+        p.close()

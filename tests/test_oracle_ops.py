@@ -246,3 +246,48 @@ def test_head_backward_finite_difference(oracle):
         e = np.zeros_like(a)
         e[idx] = h
         assert abs((f(a + e, wfc, bfc) - f(a - e, wfc, bfc)) / (2 * h) - da[idx]) < 1e-8
+
+
+# ------------------------------------------------------------------ bf16 storage reading
+def test_bf16_rounding_matches_library_and_closed_forms(oracle):
+    import torch
+    vals = np.concatenate([rng.standard_normal(2000) * 10.0 ** rng.integers(-6, 6, 2000),
+                           [0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-40]]).astype(np.float32)
+    got = np.array([oracle.round_bf16(v) for v in vals], np.float32)
+    ref = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got, ref)
+    # 8 significant bits, ties to even: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> 1 (even mantissa)
+    assert oracle.round_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert oracle.round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert oracle.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert oracle.round_bf16(257.0) == 256.0 and oracle.round_bf16(259.0) == 260.0
+
+
+def test_bf16_storage_rounds_outputs_once_and_is_exact_on_representable_data(oracle):
+    x = rng.integers(-3, 4, (2, 4, 4, 3)).astype(np.float32)
+    w = rng.integers(-2, 3, (3, 3, 3, 2)).astype(np.float32)
+    add = rng.integers(-5, 6, (2, 4, 4, 2)).astype(np.float32)
+    # small integers: every product, sum and result is representable -> both readings agree exactly
+    assert np.array_equal(oracle.conv_fwd(x, w, add=add, storage="bf16"), oracle.conv_fwd(x, w) + add)
+    # weights are used as bfloat16, the sum with the shortcut is rounded once
+    x1 = np.ones((1, 1, 1, 1), np.float32)
+    w1 = np.full((1, 1, 1, 1), 1.0 + 2.0 ** -9, np.float32)          # rounds to 1.0 as an operand
+    a1 = np.full((1, 1, 1, 1), 2.0 ** -8, np.float32)
+    y = oracle.conv_fwd(x1, w1, add=a1, storage="bf16")
+    assert y.item() == oracle.round_bf16(1.0 + 2.0 ** -8) == 1.0      # rnd(1*1 + 2^-8), not rnd(1) + 2^-8
+    assert oracle.conv_fwd(x1, w1, add=a1).item() == np.float32(1.0 + 2.0 ** -9 + 2.0 ** -8)
+    dx = oracle.conv_dgrad(x1, w1, (1, 1), storage="bf16")
+    assert dx.item() == 1.0
+    # BN+ReLU output and backward output are stored values
+    xb = rng.standard_normal((16, 8)).astype(np.float32)
+    g, b = np.ones(8, np.float32), np.zeros(8, np.float32)
+    a, mean, inv = oracle.bn_relu_fwd(xb, g, b, storage="bf16")
+    a0, _, _ = oracle.bn_relu_fwd(xb, g, b)
+    import torch
+    assert np.array_equal(a, torch.from_numpy(a0).to(torch.bfloat16).float().numpy())
+    da = rng.standard_normal((16, 8)).astype(np.float32)
+    sk = rng.standard_normal((16, 8)).astype(np.float32)
+    d1, dg1, db1 = oracle.bn_relu_bwd(xb, da, g, b, mean, inv, skip=sk, storage="bf16")
+    d0, dg0, db0 = oracle.bn_relu_bwd(xb, da, g, b, mean, inv)
+    assert np.array_equal(dg1, dg0) and np.array_equal(db1, db0)     # reductions are not rounded
+    assert np.array_equal(d1, torch.from_numpy((d0.astype(np.float64) + sk).astype(np.float32)).to(torch.bfloat16).float().numpy())

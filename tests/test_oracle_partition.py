@@ -286,3 +286,30 @@ def test_parameter_counts_of_the_benchmark_partitions():
     assert [W.n_params(W.config(i)) for i in range(1, 6)] == [272282, 446528, 373632, 10327706, 40610816]
     # ResNet-1001 = 9*111 + 2 weighted layers
     assert len(W.resnet1001_blocks()) * 3 + 2 == 1001
+
+
+def test_bf16_storage_reading_keeps_the_premise_and_stays_near_the_plain_reference(oracle):
+    """With stored tensors rounded to bfloat16 the partitioned model still equals the unsplit one
+    bitwise, boundary tensors are bfloat16 values, and the result is a small perturbation of the
+    plain reference in the forward direction (loss, activations)."""
+    import torch
+    whole = replace(W.resnet20(microbatch=2, num_microbatches=2), in_h=8, in_w=8)
+    inp = W.make_inputs(whole, randomize_affine=True)
+    ref = oracle.run_step(whole, inp, np.float32, storage="bf16")
+    plain = oracle.run_step(whole, inp, np.float32)
+    assert abs(ref["loss"] - plain["loss"]) < 2e-2 * abs(plain["loss"]) and ref["loss"] != plain["loss"]
+    blocks = W.basic_resnet_blocks(3)
+    specs = [W.partition_of(f"p{p}", blocks, 2, p, 8, 16, 16, 10, 2, 2, whole.seed) for p in range(2)]
+    n0 = W.n_params(specs[0])
+    parts = [oracle.OraclePartition(specs[0], inp.params[:n0], np.float32, "bf16"),
+             oracle.OraclePartition(specs[1], inp.params[n0:], np.float32, "bf16")]
+    for i in range(2):
+        mid = parts[0].forward(i, inp.act_in[i])
+        assert np.array_equal(mid, torch.from_numpy(mid).to(torch.bfloat16).float().numpy())
+        parts[1].forward(i, mid, inp.labels[i])
+    for i in range(2):
+        e = parts[1].backward(i, None)
+        assert np.array_equal(e, torch.from_numpy(e).to(torch.bfloat16).float().numpy())
+        parts[0].backward(i, e, want_err_out=False)
+    assert float(parts[1].loss[0]) == ref["loss"]
+    assert np.array_equal(np.concatenate([p.grad() for p in parts]), ref["grad"])
