@@ -58,7 +58,7 @@ typedef enum {
 } hpf_status;
 
 typedef enum {
-  HPF_F32 = 0, /* check mode: fp32 tensors, fp32 FMA convolutions */
+  HPF_F32 = 0, /* check mode: fp32 tensors; sums, statistics and ReLU decisions in double */
   HPF_BF16 = 1 /* bf16 tensors and MFMA operands, fp32 accumulation, fp32 statistics/gradients */
 } hpf_dtype;
 
@@ -162,13 +162,14 @@ hpf_status hpf_op_conv_dgrad(hpf_dtype dtype, const void* dy, const float* w, vo
 /* dw[R][R][cin][cout] (fp32) += sum over pixels of x (x) dy. */
 hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, float* dw, int32_t b, int32_t h,
                              int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* hip_stream);
-/* stats[2C] = {mean, 1/sqrt(var+eps)} of x[M,C]; a = max(gamma*xhat + beta, 0). */
+/* stats[2C] = {mean, 1/sqrt(var+eps)} of x[M,C]; a = max(gamma*xhat + beta, 0).  stats holds float
+ * values in bf16 mode and double values in the fp32 check mode (which reduces in double). */
 hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* gamma, const float* beta,
-                                  float eps, void* a, float* stats, int32_t M, int32_t C, void* workspace,
+                                  float eps, void* a, void* stats, int32_t M, int32_t C, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
 /* dgamma[C], dbeta[C] += reductions; dx = BN+ReLU backward of da (+ skip if non-NULL). */
 hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* da, const float* gamma,
-                                   const float* beta, const float* stats, const void* skip, void* dx,
+                                   const float* beta, const void* stats, const void* skip, void* dx,
                                    float* dgamma, float* dbeta, int32_t M, int32_t C, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
 

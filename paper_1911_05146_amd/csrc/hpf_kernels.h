@@ -47,22 +47,24 @@ hipError_t launch_conv_f32(int mode, const float* src, const float* w_hwio, floa
                            const ConvGeom& g, hipStream_t stream);
 hipError_t launch_wgrad_f32(const float* a, const float* dy, float* dw, const WgradGeom& g, hipStream_t stream);
 
-// BatchNorm + ReLU.  stats = [mean(C), invstd(C)].  partials: >= bn_partials_floats(C) floats,
-// tickets: >= 64 zero-initialised unsigned (left at zero).  All tensors are [M, C] of dtype dt.
+// BatchNorm + ReLU.  All tensors are [M, C] of dtype dt.  stats = [mean(C), invstd(C)], sums =
+// [dbeta(C), dgamma(C)] and partials are arrays of the arithmetic type: float for DT_BF16, double for
+// DT_F32 (the check mode reduces and takes the ReLU decision in double).  partials holds
+// bn_partials_floats(C) floats; tickets: >= 64 zero-initialised unsigned (left at zero).
 size_t bn_partials_floats(int C);
-hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, float* stats, float* partials,
+hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, void* stats, void* partials,
                            unsigned* tickets, hipStream_t stream);
 hipError_t launch_bn_apply_relu(int dt, const void* x, void* a, const float* gamma, const float* beta,
-                                const float* stats, int M, int C, hipStream_t stream);
-// sums = [dbeta(C), dgamma(C)] of this micro-batch; also atomically added into g_gamma / g_beta.
+                                const void* stats, int M, int C, hipStream_t stream);
+// sums of this micro-batch; also atomically added into g_gamma / g_beta (fp32 gradient buffer).
 hipError_t launch_bn_bwd_reduce(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                                const float* stats, int M, int C, float* sums, float* g_gamma, float* g_beta,
-                                float* partials, unsigned* tickets, hipStream_t stream);
+                                const void* stats, int M, int C, void* sums, float* g_gamma, float* g_beta,
+                                void* partials, unsigned* tickets, hipStream_t stream);
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M) [+ skip]; frozen: dx = gamma*invstd*dz [+ skip].
 hipError_t launch_bn_bwd_apply(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                               const float* stats, const float* sums, const void* skip, void* dx, int M, int C,
+                               const void* stats, const void* sums, const void* skip, void* dx, int M, int C,
                                int frozen, hipStream_t stream);
-hipError_t launch_bn_frozen_stats(float* stats, int C, float eps, hipStream_t stream);
+hipError_t launch_bn_frozen_stats(int dt, void* stats, int C, float eps, hipStream_t stream);
 
 // Stem: fp32 image [b,H,W,Cin] -> bf16 im2col columns [b*H*W, Kc], k = (r*3+s)*Cin + c, zero padded.
 hipError_t launch_im2col3x3(const float* img, bf16_t* col, int b, int H, int W, int Cin, int Kc, hipStream_t stream);

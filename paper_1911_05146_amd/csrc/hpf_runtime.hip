@@ -187,7 +187,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   const size_t b_ = (size_t)d.microbatch;
   auto alloc = [&](size_t bytes) { Loc l; l.kind = IN_MB; l.off = mo; mo += align_up(bytes); return l; };
   auto tensor = [&](size_t elems) { if (elems > max_elems) max_elems = elems; return alloc(elems * P.esz); };
-  auto stats = [&](BnPlan& bn) { bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(float)).off; if (bn.C > max_c) max_c = bn.C; };
+  auto stats = [&](BnPlan& bn) { bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(double)).off; if (bn.C > max_c) max_c = bn.C; };
 
   P.act_in_elems = b_ * d.in_h * d.in_w * d.in_c;
   P.act_out_elems = d.has_head ? 0 : b_ * P.out_h * P.out_w * P.out_c;
@@ -226,7 +226,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.stash_bytes_per_mb = mo;
   P.max_elems = max_elems; P.max_c = max_c;
   if (max_c > 0) {
-    P.sums_off = alloc(2 * (size_t)max_c * sizeof(float)).off;
+    P.sums_off = alloc(2 * (size_t)max_c * sizeof(double)).off;
     P.partials_off = alloc(bn_partials_floats(max_c) * sizeof(float)).off;
   }
   P.tickets_off = alloc(64 * sizeof(unsigned)).off;
@@ -282,26 +282,26 @@ struct Ctx {
       default: return nullptr;
     }
   }
-  float* mbf(size_t off) const { return (float*)(h->mb_base(mb) + off); }
+  void* mbp(size_t off) const { return h->mb_base(mb) + off; }
   void* scratch(int i) const { return h->mb_base(mb) + h->P.scratch_off[i]; }
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
 
   void bn_fwd(const BnPlan& bn, const void* x, void* a, size_t M) {
     const Plan& P = h->P;
-    float* st = mbf(bn.stats_off);
+    void* st = mbp(bn.stats_off);
     if (P.d.bn_mode == 0)
-      chk(launch_bn_stats(P.dt, x, (int)M, bn.C, P.d.bn_eps, st, mbf(P.partials_off), (unsigned*)mbf(P.tickets_off), s), "bn_stats");
+      chk(launch_bn_stats(P.dt, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), (unsigned*)mbp(P.tickets_off), s), "bn_stats");
     else
-      chk(launch_bn_frozen_stats(st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
+      chk(launch_bn_frozen_stats(P.dt, st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
     chk(launch_bn_apply_relu(P.dt, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
   }
   void bn_bwd(const BnPlan& bn, const void* x, const void* da, const void* skip, void* dx, size_t M) {
     const Plan& P = h->P;
-    float* st = mbf(bn.stats_off);
-    chk(launch_bn_bwd_reduce(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbf(P.sums_off),
-                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbf(P.partials_off), (unsigned*)mbf(P.tickets_off), s),
+    void* st = mbp(bn.stats_off);
+    chk(launch_bn_bwd_reduce(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbp(P.sums_off),
+                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbp(P.partials_off), (unsigned*)mbp(P.tickets_off), s),
         "bn_bwd_reduce");
-    chk(launch_bn_bwd_apply(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbf(P.sums_off), skip, dx, (int)M,
+    chk(launch_bn_bwd_apply(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbp(P.sums_off), skip, dx, (int)M,
                             bn.C, P.d.bn_mode, s),
         "bn_bwd_apply");
   }
@@ -625,7 +625,8 @@ static bool op_conv_args_ok(int b, int h, int wd, int cin, int cout, int R, int 
 
 // workspace layout: [0, 64*4) tickets | sums 2*Cmax floats | partials | packed bf16 weights (both copies)
 static size_t op_ws_tickets() { return 256; }
-static size_t op_ws_packed_off(int cmax) { return op_ws_tickets() + align_up(2 * (size_t)cmax * 4) + align_up(bn_partials_floats(cmax) * 4); }
+static size_t op_ws_sums_bytes(int cmax) { return align_up(2 * (size_t)cmax * sizeof(double)); }
+static size_t op_ws_packed_off(int cmax) { return op_ws_tickets() + op_ws_sums_bytes(cmax) + align_up(bn_partials_floats(cmax) * 4); }
 
 size_t hpf_op_workspace_bytes(int32_t cin, int32_t cout, int32_t R) {
   const int cmax = cin > cout ? cin : cout;
@@ -690,14 +691,14 @@ hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, flo
 }
 
 hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* gamma, const float* beta, float eps, void* a,
-                                  float* stats, int32_t M, int32_t C, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                  void* stats, int32_t M, int32_t C, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!x || !gamma || !beta || !a || !stats || !workspace) return fail(HPF_EINVAL, "null tensor");
   if (M <= 0 || C <= 0 || C % 8) return fail(HPF_EUNSUPPORTED, "C must be a positive multiple of 8");
   if (workspace_bytes < op_ws_packed_off(C)) return fail(HPF_ENOMEM, "workspace too small");
   hipStream_t s = (hipStream_t)hip_stream;
   const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
   char* ws = (char*)workspace;
-  float* partials = (float*)(ws + op_ws_tickets() + align_up(2 * (size_t)C * 4));
+  void* partials = ws + op_ws_tickets() + op_ws_sums_bytes(C);
   if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   if (launch_bn_stats(dt, x, M, C, eps, stats, partials, (unsigned*)ws, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   if (launch_bn_apply_relu(dt, x, a, gamma, beta, stats, M, C, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
@@ -705,7 +706,7 @@ hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* g
 }
 
 hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* da, const float* gamma, const float* beta,
-                                   const float* stats, const void* skip, void* dx, float* dgamma, float* dbeta, int32_t M,
+                                   const void* stats, const void* skip, void* dx, float* dgamma, float* dbeta, int32_t M,
                                    int32_t C, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!x || !da || !gamma || !beta || !stats || !dx || !dgamma || !dbeta || !workspace) return fail(HPF_EINVAL, "null tensor");
   if (M <= 0 || C <= 0 || C % 8) return fail(HPF_EUNSUPPORTED, "C must be a positive multiple of 8");
@@ -713,8 +714,8 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
   hipStream_t s = (hipStream_t)hip_stream;
   const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
   char* ws = (char*)workspace;
-  float* sums = (float*)(ws + op_ws_tickets());
-  float* partials = (float*)(ws + op_ws_tickets() + align_up(2 * (size_t)C * 4));
+  void* sums = ws + op_ws_tickets();
+  void* partials = ws + op_ws_tickets() + op_ws_sums_bytes(C);
   if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   if (launch_bn_bwd_reduce(dt, x, da, gamma, beta, stats, M, C, sums, dgamma, dbeta, partials, (unsigned*)ws, s) != hipSuccess)
     return fail(HPF_EDEVICE, "launch failed");

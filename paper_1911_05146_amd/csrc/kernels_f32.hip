@@ -1,6 +1,8 @@
-// fp32 check-mode convolutions: direct, one output element per thread, plain FMA.
-// They exist so that the whole runtime (scheduling, stash, indexing, BN, accumulation) can be
-// compared with the CPU reference at fp32 accuracy; speed is not their purpose.
+// fp32 check-mode convolutions: direct, one output element per thread, fp32 tensors, accumulation
+// in double (so a stored output is the correctly rounded sum, as in a double-accumulating
+// reference, and downstream ReLU decisions see the same values).  They exist so that the whole
+// runtime (scheduling, stash, indexing, BN, accumulation) can be compared with the CPU reference
+// at fp32 accuracy; speed is not their purpose.
 #include "hpf_device.h"
 
 namespace hpf {
@@ -19,7 +21,7 @@ __global__ __launch_bounds__(256) void k_conv_f32(const float* __restrict__ src,
   const int img = m / (g.Ho * g.Wo);
   const int rem = m - img * g.Ho * g.Wo;
   const int p = rem / g.Wo, q = rem - p * g.Wo;
-  float acc = 0.f;
+  double acc = 0.0;
   for (int r = 0; r < g.R; ++r) {
     int hs;
     if (MODE == CONV_FWD) {
@@ -44,15 +46,15 @@ __global__ __launch_bounds__(256) void k_conv_f32(const float* __restrict__ src,
       const int tap = r * g.R + s;
       if (MODE == CONV_FWD) {
         const float* wp = w + (size_t)tap * g.Cs * g.N + n;
-        for (int c = 0; c < g.Cs; ++c) acc = fmaf(sp[c], wp[(size_t)c * g.N], acc);
+        for (int c = 0; c < g.Cs; ++c) acc += (double)sp[c] * (double)wp[(size_t)c * g.N];
       } else {
         const float* wp = w + ((size_t)tap * g.N + n) * g.Cs;
-        for (int c = 0; c < g.Cs; ++c) acc = fmaf(sp[c], wp[c], acc);
+        for (int c = 0; c < g.Cs; ++c) acc += (double)sp[c] * (double)wp[c];
       }
     }
   }
-  if (add) acc += add[idx];
-  out[idx] = acc;
+  if (add) acc += (double)add[idx];
+  out[idx] = (float)acc;
 }
 
 // dw[tap][c][n] += sum over this block's row slice of a[row(m,tap), c] * dy[m, n]
@@ -67,16 +69,16 @@ __global__ __launch_bounds__(256) void k_wgrad_f32(const float* __restrict__ a, 
   const int r = tap / g.R, s = tap - r * g.R;
   const int m0 = blockIdx.y * rows_per_slice;
   const int m1 = min(g.M, m0 + rows_per_slice);
-  float acc = 0.f;
+  double acc = 0.0;
   for (int m = m0; m < m1; ++m) {
     const int img = m / (g.Ho * g.Wo);
     const int rem = m - img * g.Ho * g.Wo;
     const int p = rem / g.Wo, q = rem - p * g.Wo;
     const int hi = p * g.stride + r - g.pad, wi = q * g.stride + s - g.pad;
     if ((unsigned)hi >= (unsigned)g.H || (unsigned)wi >= (unsigned)g.W) continue;
-    acc = fmaf(a[((size_t)(img * g.H + hi) * g.W + wi) * g.Cin + c], dy[(size_t)m * g.N + n], acc);
+    acc += (double)a[((size_t)(img * g.H + hi) * g.W + wi) * g.Cin + c] * (double)dy[(size_t)m * g.N + n];
   }
-  atomicAdd(&dw[idx], acc);
+  atomicAdd(&dw[idx], (float)acc);
 }
 
 }  // namespace

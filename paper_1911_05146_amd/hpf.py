@@ -227,7 +227,8 @@ class Ops:
         Cc = x.shape[-1]
         M = x.numel() // Cc
         a = out if out is not None else self.torch.empty_like(x)
-        stats = self.torch.empty(2 * Cc, dtype=self.torch.float32, device=self.device)
+        stats = self.torch.empty(2 * Cc, device=self.device,
+                                 dtype=self.torch.float32 if self.dt == HPF_BF16 else self.torch.float64)
         ws, n = self.workspace(Cc, Cc, 1)
         hpf_op_bn_relu_forward(self.dt, x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), eps, a.data_ptr(),
                                stats.data_ptr(), M, Cc, ws, n, self._s())

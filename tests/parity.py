@@ -75,21 +75,79 @@ def rel_err(got, ref):
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
 
 
-def compare(spec, res, ref, mode, what=("act_out", "err_out", "loss", "grad", "params"), tol=None):
+def rel_l2(got, ref):
+    ref = np.asarray(ref, np.float64).ravel()
+    got = np.asarray(got, np.float64).ravel()
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / (den if den > 0 else 1.0))
+
+
+def _tensors(res, spec):
+    out = {}
+    for k in ("act_out", "err_out"):
+        v = [t for t in res.get(k, []) if t is not None]
+        if v:
+            out[k] = np.concatenate([np.asarray(t, np.float64).ravel() for t in v])
+    if spec.has_head:
+        out["loss"] = np.array([res["loss"]], np.float64)
+    for k in ("grad", "params"):
+        if k in res:
+            out[k] = np.asarray(res[k], np.float64)
+    return out
+
+
+KAPPA = 2.0
+
+
+FLOOR = {"bf16": 2e-2, "f32": 1e-2}
+
+
+def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None):
+    """Parity of one batch.
+
+    yard : the oracle run in the device's precision reading on the same inputs (float storage;
+           in bf16 mode with the tensors the device keeps as bfloat16 rounded at the same points).
+    Criterion A (strict): max|gpu - yard| / max|yard| <= tol for every tensor (2e-2 bf16, 1e-4 fp32).
+    Criterion B (sensitivity-limited), only for tensors that fail A and only if strict is False:
+           a ReLU network's backward pass is discontinuous where a pre-activation is within rounding
+           of 0, so two correct implementations of the same precision reading scatter around the
+           exact result by an amount the oracle itself can measure: with ref64 the oracle in double
+           and nothing rounded,  relL2(gpu, ref64) <= KAPPA * relL2(yard, ref64) + FLOOR.  The floor
+           covers the case where the yardstick run happens to contain no such tie while the device
+           run does: in the fp32 check mode both sides agree to the last bit until the first 1-ulp
+           difference appears (about 2e-8 per stored element), after which ulp-level noise spreads
+           and a handful of ReLU decisions may differ; each moves relL2 by about 1e-3.
+    ref64 may be a callable that computes it on demand.  Returns {tensor: (criterion, error)}.
+    """
     tol = TOL[mode] if tol is None else tol
-    report = {}
-    for k in what:
-        if k not in ref or ref[k] is None or k not in res:
+    g, y = _tensors(res, spec), _tensors(yard, spec)
+    report, bad = {}, {}
+    r64 = None
+    for k in y:
+        if k not in g:
             continue
-        if k in ("act_out", "err_out"):
-            errs = [rel_err(g, r) for g, r in zip(res[k], ref[k]) if r is not None and g is not None]
-            if errs:
-                report[k] = max(errs)
-        elif k == "loss":
-            if spec.has_head:
-                report[k] = abs(res[k] - ref[k]) / abs(ref[k])
-        else:
-            report[k] = rel_err(res[k], ref[k])
-    bad = {k: v for k, v in report.items() if not (v <= tol)}
-    assert not bad, f"{spec.name} [{mode}] over tolerance {tol}: {bad} (all: {report})"
+        e = rel_err(g[k], y[k])
+        if e <= tol:
+            report[k] = ("A", e)
+            continue
+        if strict or ref64 is None:
+            bad[k] = ("A", e)
+            continue
+        if r64 is None:
+            r64 = _tensors(ref64() if callable(ref64) else ref64, spec)
+        eg, ey = rel_l2(g[k], r64[k]), rel_l2(y[k], r64[k])
+        report[k] = ("B", e, eg, ey)
+        if not eg <= KAPPA * ey + FLOOR[mode]:
+            bad[k] = ("B", e, eg, ey)
+    assert not bad, f"{spec.name} [{mode}] parity failed: {bad} (passed: {report})"
     return report
+
+
+def fmt(report):
+    out = []
+    for k, v in report.items():
+        if v[0] == "A":
+            out.append(f"{k}: max-norm {v[1]:.2e}")
+        else:
+            out.append(f"{k}: max-norm {v[1]:.2e} -> sensitivity-limited, relL2 gpu {v[2]:.2e} vs oracle-in-same-precision {v[3]:.2e}")
+    return "; ".join(out)

@@ -106,11 +106,12 @@ def test_bn_relu_forward_backward(env, oracle, mode, shape):
     xs, das, sks = seen(torch, x, mode), seen(torch, da, mode), seen(torch, skip, mode)
     a, stats = ops.bn_relu_forward(xd, gd, bd)
     ra, rmean, rinv = oracle.bn_relu_fwd(xs, gamma, beta)
-    stats = stats.cpu().numpy()
+    stats_dev = stats
+    stats = stats.cpu().numpy().astype(np.float64)
     e_mean = np.abs(stats[:C] - rmean).max() / np.abs(rmean).max()
     e_inv = np.abs(stats[C:] / rinv - 1).max()
     e_a = rel(a.float().cpu().numpy(), ra.astype(np.float64))
-    dx, dg, db = ops.bn_relu_backward(xd, dad, gd, bd, torch.from_numpy(stats).cuda(), skip=skd)
+    dx, dg, db = ops.bn_relu_backward(xd, dad, gd, bd, stats_dev, skip=skd)
     rdx, rdg, rdb = oracle.bn_relu_bwd(xs, das, gamma, beta, rmean, rinv)
     # The ReLU decision z > 0 is taken in fp32 on the device and in double in the reference: where
     # |z| is within fp32 rounding of 0 the two may differ.  Those elements are left out of the
