@@ -136,6 +136,12 @@ hpf_status hpf_grad_accum_zero(hpf_partition* p, void* hip_stream);
  * refreshes the bf16 weight copies; clears G; starts the next batch.  Needs all backward calls. */
 hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_stream);
 
+/* Forward and backward kernel sequences of a micro-batch are captured into HIP graphs on first use
+ * and replayed while the caller passes the same buffers (a call with other pointers re-captures).
+ * enable == 0 switches to plain launches; default is enabled.  The default (NULL) stream and a
+ * stream that is itself being captured by the caller always get plain launches. */
+hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
+
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
 
@@ -147,18 +153,23 @@ void hpf_partition_destroy(hpf_partition* p);
  * kernel-level parity tests and roofline measurements.  All pointers (dev); tensors NHWC of `dtype`
  * (fp32 or bf16 bits); weights and weight gradients fp32 [R][R][Cin][Cout]; statistics fp32.
  * `workspace` (dev, 256-byte aligned) holds packed bf16 weights / reduction partials; its size
- * comes from hpf_op_workspace_bytes.  Work is enqueued on hip_stream.  Convolution layers and
- * their gradients: paper Section "Background" (DNN training) and Eq. 5-7. */
+ * comes from hpf_op_workspace_bytes.  Work is enqueued on hip_stream.  The bf16 convolutions read
+ * packed weight copies kept in the workspace: repack != 0 rebuilds them from w first (this
+ * synchronises the stream once); repack == 0 reuses the copies of the previous call with the same w,
+ * shape and workspace, and launches the convolution kernel only.  Convolution layers and their
+ * gradients: paper Section "Background" (DNN training) and Eq. 5-7. */
 size_t hpf_op_workspace_bytes(int32_t cin, int32_t cout, int32_t R);
 
 /* y[b,h/stride,w/stride,cout] = conv(x[b,h,w,cin], w) (+ add, same shape as y, may alias y). */
 hpf_status hpf_op_conv_forward(hpf_dtype dtype, const void* x, const float* w, void* y, const void* add,
                                int32_t b, int32_t h, int32_t wd, int32_t cin, int32_t cout, int32_t R,
-                               int32_t stride, void* workspace, size_t workspace_bytes, void* hip_stream);
+                               int32_t stride, void* workspace, size_t workspace_bytes, int32_t repack,
+                               void* hip_stream);
 /* dx[b,h,w,cin] = adjoint of the convolution applied to dy[b,h/stride,w/stride,cout] (+ add). */
 hpf_status hpf_op_conv_dgrad(hpf_dtype dtype, const void* dy, const float* w, void* dx, const void* add,
                              int32_t b, int32_t h, int32_t wd, int32_t cin, int32_t cout, int32_t R,
-                             int32_t stride, void* workspace, size_t workspace_bytes, void* hip_stream);
+                             int32_t stride, void* workspace, size_t workspace_bytes, int32_t repack,
+                             void* hip_stream);
 /* dw[R][R][cin][cout] (fp32) += sum over pixels of x (x) dy. */
 hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, float* dw, int32_t b, int32_t h,
                              int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* hip_stream);

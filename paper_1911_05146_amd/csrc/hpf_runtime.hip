@@ -247,8 +247,17 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
 }  // namespace
 
+// One captured HIP graph of a micro-batch's forward or backward kernel sequence, valid for the caller
+// pointers it was captured with.
+struct GraphSlot {
+  hipGraphExec_t exec = nullptr;
+  const void* key[4] = {nullptr, nullptr, nullptr, nullptr};
+};
+
 struct hpf_partition {
   Plan P;
+  bool use_graphs = true;
+  std::vector<GraphSlot> g_fwd, g_bwd;
   char* arena = nullptr;
   std::vector<unsigned char> fwd_done, bwd_done;
   std::vector<const void*> act_in;
@@ -439,6 +448,38 @@ hpf_status wait_all_backward(hpf_partition* p, hipStream_t s) {
   return HPF_OK;
 }
 
+// Runs `body` (kernel launches on stream s only) through a HIP graph: replayed if one captured with the
+// same caller pointers exists, captured and instantiated first otherwise.  The sequences contain kernel
+// nodes only.  Falls back to direct launches when graphs are off or the stream is already capturing.
+template <class Body>
+hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const void* k0, const void* k1, const void* k2, const void* k3,
+                       hipStream_t s, Ctx& c, Body body) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  // the default (NULL) stream cannot be captured
+  if (!p->use_graphs || s == nullptr || hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+    body();
+    return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
+  }
+  const bool hit = slot.exec && slot.key[0] == k0 && slot.key[1] == k1 && slot.key[2] == k2 && slot.key[3] == k3;
+  if (!hit) {
+    if (slot.exec) { (void)hipGraphExecDestroy(slot.exec); slot.exec = nullptr; }
+    hipGraph_t graph = nullptr;
+    if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamBeginCapture failed");
+    body();
+    const hipError_t e = hipStreamEndCapture(s, &graph);
+    if (c.err != hipSuccess || e != hipSuccess || !graph) {
+      if (graph) (void)hipGraphDestroy(graph);
+      return fail(HPF_EDEVICE, "graph capture failed: %s: %s", c.where, hipGetErrorString(c.err != hipSuccess ? c.err : e));
+    }
+    const hipError_t ei = hipGraphInstantiate(&slot.exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (ei != hipSuccess) { slot.exec = nullptr; return fail(HPF_EDEVICE, "hipGraphInstantiate: %s", hipGetErrorString(ei)); }
+    slot.key[0] = k0; slot.key[1] = k1; slot.key[2] = k2; slot.key[3] = k3;
+  }
+  if (hipGraphLaunch(slot.exec, s) != hipSuccess) return fail(HPF_EDEVICE, "hipGraphLaunch failed");
+  return HPF_OK;
+}
+
 void begin_next_batch(hpf_partition* p, hipStream_t s) {
   std::fill(p->fwd_done.begin(), p->fwd_done.end(), 0);
   std::fill(p->bwd_done.begin(), p->bwd_done.end(), 0);
@@ -485,6 +526,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   const Plan& P = p->P;
   const int m = P.d.num_microbatches;
   p->fwd_done.assign(m, 0); p->bwd_done.assign(m, 0); p->act_in.assign(m, nullptr);
+  p->g_fwd.resize(m); p->g_bwd.resize(m);
   hipError_t e = hipSuccess;
   auto ok = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   ok(hipMemcpy(p->params(), host_params, P.n_params * sizeof(float), hipMemcpyHostToDevice));
@@ -517,6 +559,8 @@ void hpf_partition_destroy(hpf_partition* p) {
   for (hipEvent_t ev : p->ev_fwd) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : p->ev_bwd) if (ev) (void)hipEventDestroy(ev);
   if (p->ev_step) (void)hipEventDestroy(p->ev_step);
+  for (GraphSlot& g : p->g_fwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  for (GraphSlot& g : p->g_bwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete p;
 }
 
@@ -532,8 +576,9 @@ hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_
   hipStream_t s = (hipStream_t)hip_stream;
   if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
   Ctx c{p, mb, s, act_in, act_out, nullptr, nullptr};
-  run_forward(c, labels, loss_accum);
-  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "forward: %s: %s", c.where, hipGetErrorString(c.err));
+  const hpf_status st = run_graphed(p, p->g_fwd[mb], act_in, labels, act_out, loss_accum, s, c,
+                                    [&] { run_forward(c, labels, loss_accum); });
+  if (st != HPF_OK) return st;
   if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
   p->act_in[mb] = act_in;
   p->fwd_done[mb] = 1;
@@ -552,8 +597,8 @@ hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err
   hipStream_t s = (hipStream_t)hip_stream;
   if (hipStreamWaitEvent(s, p->ev_fwd[mb], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
   Ctx c{p, mb, s, p->act_in[mb], nullptr, err_in, err_out};
-  run_backward(c);
-  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "backward: %s: %s", c.where, hipGetErrorString(c.err));
+  const hpf_status st = run_graphed(p, p->g_bwd[mb], p->act_in[mb], err_in, err_out, nullptr, s, c, [&] { run_backward(c); });
+  if (st != HPF_OK) return st;
   if (hipEventRecord(p->ev_bwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
   p->bwd_done[mb] = 1;
   ++p->n_bwd;
@@ -603,6 +648,12 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
   return HPF_OK;
 }
 
+hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  p->use_graphs = enable != 0;
+  return HPF_OK;
+}
+
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {
   if (!p || !host_dst) return fail(HPF_EINVAL, "null argument");
   if (n_floats != p->P.n_params) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_params);
@@ -636,7 +687,7 @@ size_t hpf_op_workspace_bytes(int32_t cin, int32_t cout, int32_t R) {
 }
 
 static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const float* w, void* out, const void* add, int b, int h,
-                          int wd, int cin, int cout, int R, int stride, void* ws, size_t ws_bytes, hipStream_t s) {
+                          int wd, int cin, int cout, int R, int stride, void* ws, size_t ws_bytes, int repack, hipStream_t s) {
   if (!src || !w || !out) return fail(HPF_EINVAL, "null tensor");
   const bool bf = dtype == HPF_BF16;
   if (!op_conv_args_ok(b, h, wd, cin, cout, R, stride, bf)) return fail(HPF_EUNSUPPORTED, "unsupported convolution shape");
@@ -657,9 +708,11 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
   pd.Kf = round_up32(pd.T * cin); pd.Kd = round_up32(pd.T * cout);
   pd.wf_off = 0; pd.wd_off = ((size_t)cout * pd.Kf + 7) / 8 * 8;
   const size_t table_off = align_up((pd.wd_off + (size_t)cin * pd.Kd) * 2);
-  if (hipMemcpyAsync(base + table_off, &pd, sizeof(pd), hipMemcpyHostToDevice, s) != hipSuccess) return fail(HPF_EDEVICE, "table copy failed");
-  if (hipStreamSynchronize(s) != hipSuccess) return fail(HPF_EDEVICE, "sync failed");   // pd is a stack object
-  if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
+  if (repack) {
+    if (hipMemcpyAsync(base + table_off, &pd, sizeof(pd), hipMemcpyHostToDevice, s) != hipSuccess) return fail(HPF_EDEVICE, "table copy failed");
+    if (hipStreamSynchronize(s) != hipSuccess) return fail(HPF_EDEVICE, "sync failed");   // pd is a stack object
+    if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
+  }
   const bf16_t* wp = (const bf16_t*)base + (mode == CONV_FWD ? pd.wf_off : pd.wd_off);
   if (launch_conv_mfma(mode, (const bf16_t*)src, wp, (bf16_t*)out, (const bf16_t*)add, g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
@@ -667,14 +720,14 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
 
 hpf_status hpf_op_conv_forward(hpf_dtype dtype, const void* x, const float* w, void* y, const void* add, int32_t b, int32_t h,
                                int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* workspace,
-                               size_t workspace_bytes, void* hip_stream) {
-  return op_conv(CONV_FWD, dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, (hipStream_t)hip_stream);
+                               size_t workspace_bytes, int32_t repack, void* hip_stream) {
+  return op_conv(CONV_FWD, dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, repack, (hipStream_t)hip_stream);
 }
 
 hpf_status hpf_op_conv_dgrad(hpf_dtype dtype, const void* dy, const float* w, void* dx, const void* add, int32_t b, int32_t h,
                              int32_t wd, int32_t cin, int32_t cout, int32_t R, int32_t stride, void* workspace,
-                             size_t workspace_bytes, void* hip_stream) {
-  return op_conv(CONV_DGRAD, dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, (hipStream_t)hip_stream);
+                             size_t workspace_bytes, int32_t repack, void* hip_stream) {
+  return op_conv(CONV_DGRAD, dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, repack, (hipStream_t)hip_stream);
 }
 
 hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, float* dw, int32_t b, int32_t h, int32_t wd,

@@ -10,10 +10,12 @@
 // backward: reduction pass (dbeta = sum dz, dgamma = sum dz*xhat with dz = da*[z>0]) then
 //           dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M) (+ the skip gradient of an identity
 //           shortcut).
-// Reductions: per-thread fp32 partial sums -> LDS across the row groups of a block -> one partial
-// per block in global memory -> the last block to finish (atomic ticket) adds the partials in block
-// order, so the result does not depend on scheduling.  The variance uses sums shifted by the first
-// row's value, which removes the cancellation of the sum-of-squares form.
+// Reductions: per-thread partial sums -> cross-lane shuffles and LDS across the row groups of a
+// block -> one partial per block in global memory; a second, one-block-per-256-channels kernel adds
+// the partials in a fixed order, so the result does not depend on scheduling (a grid-wide
+// "last block finishes" scheme was measured slower here: its device-scope fence and atomic round
+// trips cost more than a kernel boundary).  The variance uses sums shifted by the first row's
+// value, which removes the cancellation of the sum-of-squares form.
 //
 // Arithmetic type A: float in bf16 mode; double in the fp32 check mode, where tensors are fp32 but
 // every reduction, statistic and the pre-activation z are computed in double, so that the ReLU
@@ -66,11 +68,34 @@ __device__ __forceinline__ BnMap bn_map(int C) {
   return m;
 }
 
+__device__ __forceinline__ float shfl_xor_a(float v, int o) { return __shfl_xor(v, o); }
+__device__ __forceinline__ double shfl_xor_a(double v, int o) { return __shfl_xor(v, o); }
+
 // Sums the 16 per-thread values over the row groups of the block; result valid in threads rl == 0.
+// When the channel-group count per block is a power of two (every ResNet width here) the rows held
+// by one wavefront are added with cross-lane shuffles and only 4 values per column go through LDS;
+// otherwise the first row group adds the others serially.
 template <class A>
 __device__ __forceinline__ void block_reduce16(A (&s)[16], const BnMap& m, int C, A (*sh)[BN_THREADS]) {
   const int CG = C >> 3;
   const int CGB = CG < 32 ? CG : 32;
+  if ((CGB & (CGB - 1)) == 0) {
+    for (int o = CGB; o < 64; o <<= 1) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[j] += shfl_xor_a(s[j], o);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane < CGB) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) sh[j][wave * 32 + lane] = s[j];
+    }
+    __syncthreads();
+    if (m.rl == 0) {   // threads 0 .. CGB-1 of wave 0
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[j] = ((sh[j][lane] + sh[j][32 + lane]) + sh[j][64 + lane]) + sh[j][96 + lane];
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 16; ++j) sh[j][threadIdx.x] = s[j];
   __syncthreads();
@@ -82,24 +107,36 @@ __device__ __forceinline__ void block_reduce16(A (&s)[16], const BnMap& m, int C
   }
 }
 
-// Returns true in every thread of the block that finished last among the blocks with this blockIdx.y.
-__device__ __forceinline__ bool last_block_of_slice(unsigned* tickets) {
-  __shared__ int is_last;
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned t = atomicAdd(&tickets[blockIdx.y], 1u);
-    is_last = (t == gridDim.x - 1);
+// Sum of the per-block partials of channel `c` (this slice's channels are c_base .. c_base+255):
+// the 256 threads split into (channel, row-group) pairs, every pair adds a strided subset of the
+// blocks' partials, then the row-groups of a channel are added in order through LDS.  The order of
+// the additions is fixed.
+template <class A>
+__device__ __forceinline__ bool reduce_partials(const A* partials, int C, unsigned nblocks, A (*sh)[BN_THREADS], A& s1, A& s2) {
+  const int c_base = blockIdx.y * 256;
+  const int cw = min(256, C - c_base);          // channels in this slice
+  int jn = BN_THREADS / cw;                     // row-groups
+  const int cl = threadIdx.x % cw, j = threadIdx.x / cw;
+  A a1 = 0, a2 = 0;
+  if (j < jn) {
+    const A* p = partials + ((size_t)(c_base + cl)) * 2;
+    for (unsigned bx = j; bx < nblocks; bx += jn) {
+      a1 += p[(size_t)bx * C * 2];
+      a2 += p[(size_t)bx * C * 2 + 1];
+    }
   }
+  sh[0][threadIdx.x] = a1;
+  sh[1][threadIdx.x] = a2;
   __syncthreads();
-  if (is_last) __threadfence();
-  return is_last != 0;
+  if (j != 0) return false;
+  s1 = a1; s2 = a2;
+  for (int r = 1; r < jn; ++r) { s1 += sh[0][cl + r * cw]; s2 += sh[1][cl + r * cw]; }
+  return true;
 }
 
 template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(const T* __restrict__ x, int M, int C, int rows_per_block,
-                                                         float eps, A* __restrict__ stats, A* partials,
-                                                         unsigned* tickets) {
+                                                         A* __restrict__ partials) {
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16];
@@ -126,15 +163,17 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(const T* __restrict__ x
 #pragma unroll
     for (int j = 0; j < 8; ++j) { p[2 * j] = s[j]; p[2 * j + 1] = s[8 + j]; }
   }
-  if (!last_block_of_slice(tickets)) return;
-  const int c = blockIdx.y * 256 + threadIdx.x;
-  if (c < C) {
-    const volatile A* vp = partials;
-    A s1 = 0, s2 = 0;
-    for (unsigned bx = 0; bx < gridDim.x; ++bx) {
-      s1 += vp[((size_t)bx * C + c) * 2];
-      s2 += vp[((size_t)bx * C + c) * 2 + 1];
-    }
+}
+
+// grid (1, ceil(C/256)): statistics from the nblocks partials.
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(const T* __restrict__ x, int M, int C, unsigned nblocks,
+                                                                  float eps, const A* __restrict__ partials,
+                                                                  A* __restrict__ stats) {
+  __shared__ A sh[2][BN_THREADS];
+  A s1, s2;
+  if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
+    const int c = blockIdx.y * 256 + threadIdx.x;
     const A inv_m = (A)1 / (A)M;
     const A d = s1 * inv_m;
     A var = s2 * inv_m - d * d;
@@ -142,7 +181,6 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(const T* __restrict__ x
     stats[c] = (A)to_f32(x[c]) + d;
     stats[C + c] = rsqrt_exact(var + (A)eps);
   }
-  if (threadIdx.x == 0) tickets[blockIdx.y] = 0;
 }
 
 template <class T, class A>
@@ -170,9 +208,7 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(const T* __restric
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ beta,
                                                               const A* __restrict__ stats, int M, int C,
-                                                              int rows_per_block, A* __restrict__ sums,
-                                                              float* g_gamma, float* g_beta, A* partials,
-                                                              unsigned* tickets) {
+                                                              int rows_per_block, A* __restrict__ partials) {
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16];
@@ -202,21 +238,22 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(const T* __restric
 #pragma unroll
     for (int j = 0; j < 8; ++j) { p[2 * j] = s[j]; p[2 * j + 1] = s[8 + j]; }
   }
-  if (!last_block_of_slice(tickets)) return;
-  const int c = blockIdx.y * 256 + threadIdx.x;
-  if (c < C) {
-    const volatile A* vp = partials;
-    A s1 = 0, s2 = 0;
-    for (unsigned bx = 0; bx < gridDim.x; ++bx) {
-      s1 += vp[((size_t)bx * C + c) * 2];
-      s2 += vp[((size_t)bx * C + c) * 2 + 1];
-    }
+}
+
+// grid (1, ceil(C/256)): dbeta / dgamma of this micro-batch from the partials; also added into the
+// gradient buffer shared by all micro-batches.
+template <class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned nblocks, const A* __restrict__ partials,
+                                                                A* __restrict__ sums, float* g_gamma, float* g_beta) {
+  __shared__ A sh[2][BN_THREADS];
+  A s1, s2;
+  if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
+    const int c = blockIdx.y * 256 + threadIdx.x;
     sums[c] = s1;
     sums[C + c] = s2;
     atomicAdd(&g_beta[c], (float)s1);
     atomicAdd(&g_gamma[c], (float)s2);
   }
-  if (threadIdx.x == 0) tickets[blockIdx.y] = 0;
 }
 
 template <class T, class A>
@@ -282,12 +319,16 @@ dim3 apply_grid(int M, int C) {
 size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 2 * 2; }  // sized for double
 
 hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, void* stats, void* partials,
-                           unsigned* tickets, hipStream_t stream) {
+                           unsigned* /*tickets*/, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  if (dt == DT_BF16)
-    k_bn_stats<bf16_t, float><<<g.grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, M, C, g.rows_per_block, eps, (float*)stats, (float*)partials, tickets);
-  else
-    k_bn_stats<float, double><<<g.grid, BN_THREADS, 0, stream>>>((const float*)x, M, C, g.rows_per_block, eps, (double*)stats, (double*)partials, tickets);
+  const dim3 fin(1, g.grid.y);
+  if (dt == DT_BF16) {
+    k_bn_stats<bf16_t, float><<<g.grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, M, C, g.rows_per_block, (float*)partials);
+    k_bn_stats_finalize<bf16_t, float><<<fin, BN_THREADS, 0, stream>>>((const bf16_t*)x, M, C, g.grid.x, eps, (const float*)partials, (float*)stats);
+  } else {
+    k_bn_stats<float, double><<<g.grid, BN_THREADS, 0, stream>>>((const float*)x, M, C, g.rows_per_block, (double*)partials);
+    k_bn_stats_finalize<float, double><<<fin, BN_THREADS, 0, stream>>>((const float*)x, M, C, g.grid.x, eps, (const double*)partials, (double*)stats);
+  }
   return hipGetLastError();
 }
 
@@ -303,14 +344,18 @@ hipError_t launch_bn_apply_relu(int dt, const void* x, void* a, const float* gam
 
 hipError_t launch_bn_bwd_reduce(int dt, const void* x, const void* da, const float* gamma, const float* beta,
                                 const void* stats, int M, int C, void* sums, float* g_gamma, float* g_beta,
-                                void* partials, unsigned* tickets, hipStream_t stream) {
+                                void* partials, unsigned* /*tickets*/, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  if (dt == DT_BF16)
+  const dim3 fin(1, g.grid.y);
+  if (dt == DT_BF16) {
     k_bn_bwd_reduce<bf16_t, float><<<g.grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, (const bf16_t*)da, gamma, beta, (const float*)stats, M, C,
-                                                                      g.rows_per_block, (float*)sums, g_gamma, g_beta, (float*)partials, tickets);
-  else
+                                                                      g.rows_per_block, (float*)partials);
+    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, (const float*)partials, (float*)sums, g_gamma, g_beta);
+  } else {
     k_bn_bwd_reduce<float, double><<<g.grid, BN_THREADS, 0, stream>>>((const float*)x, (const float*)da, gamma, beta, (const double*)stats, M, C,
-                                                                      g.rows_per_block, (double*)sums, g_gamma, g_beta, (double*)partials, tickets);
+                                                                      g.rows_per_block, (double*)partials);
+    k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, (const double*)partials, (double*)sums, g_gamma, g_beta);
+  }
   return hipGetLastError();
 }
 

@@ -63,10 +63,11 @@ def _load():
     L.hpf_params_read.argtypes = [vp, vp, sz]
     L.hpf_partition_destroy.argtypes = [vp]
     L.hpf_partition_destroy.restype = None
+    L.hpf_partition_set_graphs.argtypes = [vp, i32]
     L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
     L.hpf_op_workspace_bytes.restype = sz
-    L.hpf_op_conv_forward.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
-    L.hpf_op_conv_dgrad.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+    L.hpf_op_conv_forward.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, i32, vp]
+    L.hpf_op_conv_dgrad.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, i32, vp]
     L.hpf_op_conv_wgrad.argtypes = [C.c_int, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     L.hpf_op_bn_relu_forward.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]
     L.hpf_op_bn_relu_backward.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
@@ -77,7 +78,7 @@ lib = _load()
 
 EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatch", "hpf_backward_microbatch",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
-           "hpf_partition_destroy", "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
+           "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
 
 
@@ -143,6 +144,10 @@ def hpf_params_read(handle, host_dst, n_floats):
     _check(lib.hpf_params_read(handle, host_dst, n_floats))
 
 
+def hpf_partition_set_graphs(handle, enable):
+    _check(lib.hpf_partition_set_graphs(handle, int(enable)))
+
+
 def hpf_partition_destroy(handle):
     lib.hpf_partition_destroy(handle)
 
@@ -151,14 +156,16 @@ def hpf_op_workspace_bytes(cin, cout, R) -> int:
     return int(lib.hpf_op_workspace_bytes(cin, cout, R))
 
 
-def hpf_op_conv_forward(dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, stream=0):
+def hpf_op_conv_forward(dtype, x, w, y, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes,
+                        repack=1, stream=0):
     _check(lib.hpf_op_conv_forward(dtype, x, w, y, add or None, b, h, wd, cin, cout, R, stride, workspace,
-                                   workspace_bytes, stream or None))
+                                   workspace_bytes, repack, stream or None))
 
 
-def hpf_op_conv_dgrad(dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes, stream=0):
+def hpf_op_conv_dgrad(dtype, dy, w, dx, add, b, h, wd, cin, cout, R, stride, workspace, workspace_bytes,
+                      repack=1, stream=0):
     _check(lib.hpf_op_conv_dgrad(dtype, dy, w, dx, add or None, b, h, wd, cin, cout, R, stride, workspace,
-                                 workspace_bytes, stream or None))
+                                 workspace_bytes, repack, stream or None))
 
 
 def hpf_op_conv_wgrad(dtype, x, dy, dw, b, h, wd, cin, cout, R, stride, stream=0):
@@ -197,23 +204,23 @@ class Ops:
     def _s(self):
         return self.torch.cuda.current_stream(self.device).cuda_stream
 
-    def conv_forward(self, x, w, stride=1, add=None, out=None):
+    def conv_forward(self, x, w, stride=1, add=None, out=None, repack=True):
         b, h, wd, cin = x.shape
         R, _, _, cout = w.shape
         y = out if out is not None else self.torch.empty((b, h // stride, wd // stride, cout), dtype=self.tdtype, device=self.device)
         ws, n = self.workspace(cin, cout, R)
         hpf_op_conv_forward(self.dt, x.data_ptr(), w.data_ptr(), y.data_ptr(), add.data_ptr() if add is not None else 0,
-                            b, h, wd, cin, cout, R, stride, ws, n, self._s())
+                            b, h, wd, cin, cout, R, stride, ws, n, int(repack), self._s())
         return y
 
-    def conv_dgrad(self, dy, w, in_hw, stride=1, add=None, out=None):
+    def conv_dgrad(self, dy, w, in_hw, stride=1, add=None, out=None, repack=True):
         b = dy.shape[0]
         R, _, cin, cout = w.shape
         h, wd = in_hw
         dx = out if out is not None else self.torch.empty((b, h, wd, cin), dtype=self.tdtype, device=self.device)
         ws, n = self.workspace(cin, cout, R)
         hpf_op_conv_dgrad(self.dt, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), add.data_ptr() if add is not None else 0,
-                          b, h, wd, cin, cout, R, stride, ws, n, self._s())
+                          b, h, wd, cin, cout, R, stride, ws, n, int(repack), self._s())
         return dx
 
     def conv_wgrad(self, x, dy, R, stride=1, out=None):
@@ -336,6 +343,9 @@ class Partition:
 
     def sgd_step(self, lr, momentum, stream=None):
         hpf_sgd_step(self.handle, lr, momentum, self._stream_or_current(stream))
+
+    def set_graphs(self, enable):
+        hpf_partition_set_graphs(self.handle, enable)
 
     def params_read(self):
         import numpy as np

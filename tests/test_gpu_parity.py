@@ -265,3 +265,66 @@ def test_partition_chain_on_device_equals_unsplit_model(gpu):
     assert rel_err(G, ref["grad"]) < 1e-5
     for p in parts:
         p.close()
+
+
+def test_graph_replay_matches_plain_launches(gpu):
+    """The per-micro-batch kernel sequences are replayed from HIP graphs; several replays, with eager
+    work and synchronisation in between, must each reproduce what plain launches give."""
+    import torch
+    from parity import device_inputs, rel_err
+    hpf = gpu
+    spec = W.resnet110_partition(p=2, microbatch=8, num_microbatches=2)
+    inp = W.make_inputs(spec, randomize_affine=True)
+    _, t = device_inputs(spec, inp, "bf16")
+    pg, pe = hpf.Partition(spec, inp.params), hpf.Partition(spec, inp.params)
+    pe.set_graphs(False)
+    outs = {id(pg): [torch.empty(pg.out_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)],
+            id(pe): [torch.empty(pg.out_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]}
+    errs = {id(pg): [torch.empty(pg.in_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)],
+            id(pe): [torch.empty(pg.in_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]}
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]      # graphs need a non-default stream
+    torch.cuda.synchronize()
+    for batch in range(4):
+        for part in (pg, pe):
+            for i in range(2):
+                part.forward_microbatch(i, t["act_in"][i], None, outs[id(part)][i], stream=streams[i])
+            for i in range(2):
+                part.backward_microbatch(i, t["err_in"][i], errs[id(part)][i], stream=streams[i])
+        gg, ge = pg.grad_accum_read(), pe.grad_accum_read()
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(outs[id(pg)][i], outs[id(pe)][i]), f"batch {batch}: act_out differs"
+            assert torch.equal(errs[id(pg)][i], errs[id(pe)][i]), f"batch {batch}: err_out differs"
+        assert rel_err(gg, ge) < 1e-5
+        scratch = torch.randn(1 << 20, device="cuda:0").sum().item()      # unrelated eager work between replays
+        for part in (pg, pe):
+            part.grad_accum_zero()
+    # new buffers: the graphs are re-captured for the new pointers
+    o2 = torch.empty_like(outs[id(pg)][0])
+    x2 = t["act_in"][0].clone()
+    torch.cuda.synchronize()
+    pg.forward_microbatch(0, x2, None, o2, stream=streams[0])
+    pe.forward_microbatch(0, t["act_in"][0], None, outs[id(pe)][0], stream=streams[0])
+    torch.cuda.synchronize()
+    assert torch.equal(o2, outs[id(pe)][0])
+    for part in (pg, pe):                                 # finish this batch
+        part.backward_microbatch(0, t["err_in"][0], errs[id(part)][0], stream=streams[0])
+        part.forward_microbatch(1, t["act_in"][1], None, outs[id(part)][1], stream=streams[1])
+        part.backward_microbatch(1, t["err_in"][1], errs[id(part)][1], stream=streams[1])
+        part.grad_accum_zero()
+    # an SGD step changes the packed weights the graphs read (the two handles' gradients differ in the
+    # order of their fp32 atomic sums, so from here on they agree to rounding, not bit for bit)
+    for part in (pg, pe):
+        for i in range(2):
+            part.forward_microbatch(i, t["act_in"][i], None, outs[id(part)][i], stream=streams[i])
+        for i in range(2):
+            part.backward_microbatch(i, t["err_in"][i], errs[id(part)][i], stream=streams[i])
+        part.sgd_step(0.05, 0.9)
+    assert rel_err(pg.params_read(), pe.params_read()) < 1e-6
+    for part in (pg, pe):
+        part.forward_microbatch(0, t["act_in"][0], None, outs[id(part)][0], stream=streams[0])
+    torch.cuda.synchronize()
+    assert rel_err(outs[id(pg)][0].float().cpu().numpy(), outs[id(pe)][0].float().cpu().numpy()) < 2e-2
+    assert not torch.equal(outs[id(pg)][0], o2)          # the step did change the result
+    pg.close()
+    pe.close()
