@@ -146,7 +146,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (default 3: ResNet-1001 partition)")
-    ap.add_argument("--single-stream", action="store_true", help="all micro-batches on one stream")
+    ap.add_argument("--schedule", choices=["grouped", "streams", "single-stream"], default="grouped",
+                    help="grouped: all micro-batches of the batch in one group call per direction (default); "
+                         "streams: one call and one stream per micro-batch; single-stream: one call per micro-batch, one stream")
     ap.add_argument("--no-graphs", action="store_true", help="plain kernel launches instead of HIP graph replay")
     ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel probes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -176,16 +178,24 @@ def main():
     err_in = [torch.from_numpy(e).to(dev, tdt) for e in inputs.err_in] if inputs.err_in else [None] * m
     act_out = [None if spec.has_head else torch.empty(part.out_shape, dtype=tdt, device=dev) for _ in range(m)]
     err_out = [None if spec.has_stem else torch.empty(part.in_shape, dtype=tdt, device=dev) for _ in range(m)]
-    streams = [torch.cuda.current_stream(dev)] * m if args.single_stream else [torch.cuda.Stream(dev) for _ in range(m)]
-    main_stream = torch.cuda.current_stream(dev)
+    main_stream = torch.cuda.Stream(dev)
+    streams = [torch.cuda.Stream(dev) for _ in range(m)] if args.schedule == "streams" else [main_stream] * m
+    lab_list = labels if inputs.labels else None
+    out_list = None if spec.has_head else act_out
+    ein_list = None if spec.has_head else err_in
+    eout_list = None if spec.has_stem else err_out
 
     def step():
         if sgd is None:
             part.grad_accum_zero(stream=main_stream)
-        for i in range(m):
-            part.forward_microbatch(i, act_in[i], labels[i], act_out[i], stream=streams[i])
-        for i in range(m):
-            part.backward_microbatch(i, err_in[i], err_out[i], stream=streams[i])
+        if args.schedule == "grouped":
+            part.forward_microbatches(0, act_in, lab_list, out_list, stream=main_stream)
+            part.backward_microbatches(0, m, ein_list, eout_list, stream=main_stream)
+        else:
+            for i in range(m):
+                part.forward_microbatch(i, act_in[i], labels[i], act_out[i], stream=streams[i])
+            for i in range(m):
+                part.backward_microbatch(i, err_in[i], err_out[i], stream=streams[i])
         if sgd is not None:
             part.sgd_step(*sgd, stream=main_stream)
 
@@ -217,7 +227,7 @@ def main():
                                f"{m} micro-batches of {spec.microbatch} images"
                                + (", + SGD step" if sgd else ""),
                    "batch": spec.batch, "microbatch": spec.microbatch, "num_microbatches": m,
-                   "streams": 1 if args.single_stream else m, "hip_graphs": not args.no_graphs},
+                   "schedule": args.schedule, "hip_graphs": not args.no_graphs},
     }
 
     if not args.no_probe:

@@ -123,6 +123,22 @@ hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_
 hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out,
                                    void* hip_stream);
 
+/* Several consecutive micro-batches [mb_first, mb_first + count) in one call: the same work as `count`
+ * single calls, but every layer is launched once for the whole group (the micro-batch is a grid
+ * dimension; BatchNorm statistics stay per micro-batch).  At small spatial sizes one micro-batch neither
+ * fills the GPU nor amortises a kernel dispatch, so this is how the micro-batches of a batch that are in
+ * flight at the same time should be issued on one GPU; the group size plays the role the paper's
+ * number of pipeline stages plays for its granularity/overlap trade-off.  Arrays are (host) arrays of
+ * `count` (dev) pointers with the meaning of the single-call arguments (labels / act_out / err_in /
+ * err_out arrays may be NULL exactly when the single-call argument would be NULL).  Groups larger than
+ * 8 are processed 8 at a time.  Outputs of all members are complete (in stream order) when the call's
+ * work is. */
+hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* act_in,
+                                   const int32_t* const* labels, void* const* act_out, float* loss_accum,
+                                   void* hip_stream);
+hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in,
+                                    void* const* err_out, void* hip_stream);
+
 /* Copies the accumulated gradient (n_params floats) to dst after all backward work issued so far.
  * dst_is_device != 0: dst is (dev) and the copy is enqueued on hip_stream; else dst is (host) and
  * the call blocks until the copy is complete.  Needs all micro-batches' backward calls. */

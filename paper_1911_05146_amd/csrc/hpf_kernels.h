@@ -10,6 +10,21 @@ namespace hpf {
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 enum : int { DT_F32 = 0, DT_BF16 = 1 };
+
+// Micro-batches of one batch are independent until the gradient accumulation, and at CIFAR shapes a
+// single micro-batch cannot fill 256 CUs nor amortise a kernel dispatch.  Every kernel of the
+// forward / backward schedule therefore takes a group of up to MAX_GROUP micro-batches in one launch:
+// blockIdx.z selects the member, PtrTab carries one pointer per member for every per-micro-batch
+// tensor (stash, statistics, scratch, caller buffers).  Statistics stay per micro-batch.
+constexpr int MAX_GROUP = 8;
+struct PtrTab {
+  void* p[MAX_GROUP];
+};
+inline PtrTab one_ptr(const void* q) {
+  PtrTab t{};
+  t.p[0] = const_cast<void*>(q);
+  return t;
+}
 enum : int { CONV_FWD = 0, CONV_DGRAD = 1 };
 
 // Geometry of one gather-GEMM:  out[m, n] = sum_{tap, c} src[row(m, tap), c] * W(tap, c, n).
@@ -39,42 +54,44 @@ struct PackDesc {
   int T, Cin, Cout, Kf, Kd;
 };
 
-hipError_t launch_conv_mfma(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
-                            const ConvGeom& g, hipStream_t stream);
-hipError_t launch_wgrad_mfma(const bf16_t* a, const bf16_t* dy, float* dw, const WgradGeom& g, hipStream_t stream);
+// g = number of group members (grid z); tables hold g valid pointers.  `add` tables may be all-null.
+hipError_t launch_conv_mfma(int mode, int g, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
+                            const ConvGeom& geom, hipStream_t stream);
+hipError_t launch_wgrad_mfma(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);
 
-hipError_t launch_conv_f32(int mode, const float* src, const float* w_hwio, float* out, const float* add,
-                           const ConvGeom& g, hipStream_t stream);
-hipError_t launch_wgrad_f32(const float* a, const float* dy, float* dw, const WgradGeom& g, hipStream_t stream);
+hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
+                           const ConvGeom& geom, hipStream_t stream);
+hipError_t launch_wgrad_f32(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);
 
 // BatchNorm + ReLU.  All tensors are [M, C] of dtype dt.  stats = [mean(C), invstd(C)], sums =
 // [dbeta(C), dgamma(C)] and partials are arrays of the arithmetic type: float for DT_BF16, double for
 // DT_F32 (the check mode reduces and takes the ReLU decision in double).  partials holds
-// bn_partials_floats(C) floats; tickets: >= 64 zero-initialised unsigned (left at zero).
+// bn_partials_floats(C) floats per member.
 size_t bn_partials_floats(int C);
-hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, void* stats, void* partials,
-                           unsigned* tickets, hipStream_t stream);
-hipError_t launch_bn_apply_relu(int dt, const void* x, void* a, const float* gamma, const float* beta,
-                                const void* stats, int M, int C, hipStream_t stream);
-// sums of this micro-batch; also atomically added into g_gamma / g_beta (fp32 gradient buffer).
-hipError_t launch_bn_bwd_reduce(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                                const void* stats, int M, int C, void* sums, float* g_gamma, float* g_beta,
-                                void* partials, unsigned* tickets, hipStream_t stream);
+hipError_t launch_bn_stats(int dt, int g, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
+                           const PtrTab& partials, hipStream_t stream);
+hipError_t launch_bn_apply_relu(int dt, int g, const PtrTab& x, const PtrTab& a, const float* gamma, const float* beta,
+                                const PtrTab& stats, int M, int C, hipStream_t stream);
+// sums of each micro-batch; also atomically added into g_gamma / g_beta (fp32 gradient buffer).
+hipError_t launch_bn_bwd_reduce(int dt, int g, const PtrTab& x, const PtrTab& da, const float* gamma, const float* beta,
+                                const PtrTab& stats, int M, int C, const PtrTab& sums, float* g_gamma, float* g_beta,
+                                const PtrTab& partials, hipStream_t stream);
 // dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M) [+ skip]; frozen: dx = gamma*invstd*dz [+ skip].
-hipError_t launch_bn_bwd_apply(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                               const void* stats, const void* sums, const void* skip, void* dx, int M, int C,
-                               int frozen, hipStream_t stream);
-hipError_t launch_bn_frozen_stats(int dt, void* stats, int C, float eps, hipStream_t stream);
+hipError_t launch_bn_bwd_apply(int dt, int g, const PtrTab& x, const PtrTab& da, const float* gamma, const float* beta,
+                               const PtrTab& stats, const PtrTab& sums, const PtrTab& skip, const PtrTab& dx, int M,
+                               int C, int frozen, hipStream_t stream);
+hipError_t launch_bn_frozen_stats(int dt, int g, const PtrTab& stats, int C, float eps, hipStream_t stream);
 
 // Stem: fp32 image [b,H,W,Cin] -> bf16 im2col columns [b*H*W, Kc], k = (r*3+s)*Cin + c, zero padded.
-hipError_t launch_im2col3x3(const float* img, bf16_t* col, int b, int H, int W, int Cin, int Kc, hipStream_t stream);
+hipError_t launch_im2col3x3(int g, const PtrTab& img, const PtrTab& col, int b, int H, int W, int Cin, int Kc,
+                            hipStream_t stream);
 
 // Head: a [b,hw,C] (dtype dt) -> g [b,C] fp32, dlogits [b,classes] fp32, loss_accum += sum CE / divisor.
-hipError_t launch_head_fwd(int dt, const void* a, const float* wfc, const float* bfc, const int32_t* labels,
-                           float* g, float* dlogits, float* loss_accum, int b, int hw, int C, int classes,
-                           float divisor, hipStream_t stream);
-hipError_t launch_head_bwd(int dt, const float* g, const float* dlogits, const float* wfc, float* g_wfc,
-                           float* g_bfc, void* da, int b, int hw, int C, int classes, hipStream_t stream);
+hipError_t launch_head_fwd(int dt, int g, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& labels,
+                           const PtrTab& gp, const PtrTab& dlogits, float* loss_accum, int b, int hw, int C,
+                           int classes, float divisor, hipStream_t stream);
+hipError_t launch_head_bwd(int dt, int g, const PtrTab& gp, const PtrTab& dlogits, const float* wfc, float* g_wfc,
+                           float* g_bfc, const PtrTab& da, int b, int hw, int C, int classes, hipStream_t stream);
 
 hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, hipStream_t stream);
 hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream);

@@ -251,7 +251,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 // pointers it was captured with.
 struct GraphSlot {
   hipGraphExec_t exec = nullptr;
-  const void* key[4] = {nullptr, nullptr, nullptr, nullptr};
+  std::vector<const void*> key;
 };
 
 struct hpf_partition {
@@ -275,117 +275,124 @@ struct hpf_partition {
 
 namespace {
 
+// Everything one call needs: the handle, the group of consecutive micro-batches [mb0, mb0+g), the stream
+// and the caller buffers of every member.
 struct Ctx {
-  hpf_partition* h; int mb; hipStream_t s;
-  const void* act_in; void* act_out; const void* err_in; void* err_out;
+  hpf_partition* h; int mb0; int g; hipStream_t s;
+  const void* act_in[MAX_GROUP]; void* act_out[MAX_GROUP]; const void* err_in[MAX_GROUP]; void* err_out[MAX_GROUP];
   hipError_t err = hipSuccess;
   const char* where = "";
 
-  void* ptr(const Loc& l) const {
-    switch (l.kind) {
-      case IN_MB: return h->mb_base(mb) + l.off;
-      case CALLER_ACT_IN: return const_cast<void*>(act_in);
-      case CALLER_ACT_OUT: return act_out;
-      case CALLER_ERR_IN: return const_cast<void*>(err_in);
-      case CALLER_ERR_OUT: return err_out;
-      default: return nullptr;
+  PtrTab tab(const Loc& l) const {
+    PtrTab t{};
+    for (int i = 0; i < g; ++i) {
+      switch (l.kind) {
+        case IN_MB: t.p[i] = h->mb_base(mb0 + i) + l.off; break;
+        case CALLER_ACT_IN: t.p[i] = const_cast<void*>(act_in[i]); break;
+        case CALLER_ACT_OUT: t.p[i] = act_out[i]; break;
+        case CALLER_ERR_IN: t.p[i] = const_cast<void*>(err_in[i]); break;
+        case CALLER_ERR_OUT: t.p[i] = err_out[i]; break;
+        default: t.p[i] = nullptr;
+      }
     }
+    return t;
   }
-  void* mbp(size_t off) const { return h->mb_base(mb) + off; }
-  void* scratch(int i) const { return h->mb_base(mb) + h->P.scratch_off[i]; }
+  PtrTab mbp(size_t off) const { Loc l; l.kind = IN_MB; l.off = off; return tab(l); }
+  PtrTab scratch(int i) const { return mbp(h->P.scratch_off[i]); }
+  static PtrTab none() { return PtrTab{}; }
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
 
-  void bn_fwd(const BnPlan& bn, const void* x, void* a, size_t M) {
+  void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M) {
     const Plan& P = h->P;
-    void* st = mbp(bn.stats_off);
+    const PtrTab st = mbp(bn.stats_off);
     if (P.d.bn_mode == 0)
-      chk(launch_bn_stats(P.dt, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), (unsigned*)mbp(P.tickets_off), s), "bn_stats");
+      chk(launch_bn_stats(P.dt, g, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), s), "bn_stats");
     else
-      chk(launch_bn_frozen_stats(P.dt, st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
-    chk(launch_bn_apply_relu(P.dt, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
+      chk(launch_bn_frozen_stats(P.dt, g, st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
+    chk(launch_bn_apply_relu(P.dt, g, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
   }
-  void bn_bwd(const BnPlan& bn, const void* x, const void* da, const void* skip, void* dx, size_t M) {
+  void bn_bwd(const BnPlan& bn, const PtrTab& x, const PtrTab& da, const PtrTab& skip, const PtrTab& dx, size_t M) {
     const Plan& P = h->P;
-    void* st = mbp(bn.stats_off);
-    chk(launch_bn_bwd_reduce(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbp(P.sums_off),
-                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbp(P.partials_off), (unsigned*)mbp(P.tickets_off), s),
+    const PtrTab st = mbp(bn.stats_off);
+    chk(launch_bn_bwd_reduce(P.dt, g, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbp(P.sums_off),
+                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbp(P.partials_off), s),
         "bn_bwd_reduce");
-    chk(launch_bn_bwd_apply(P.dt, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbp(P.sums_off), skip, dx, (int)M,
+    chk(launch_bn_bwd_apply(P.dt, g, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbp(P.sums_off), skip, dx, (int)M,
                             bn.C, P.d.bn_mode, s),
         "bn_bwd_apply");
   }
   ConvGeom geom_fwd(const ConvPlan& cv) const {
-    ConvGeom g{};
-    g.b = h->P.d.microbatch; g.Ho = cv.h_out; g.Wo = cv.w_out; g.Hs = cv.h_in; g.Ws = cv.w_in; g.Cs = cv.cin; g.N = cv.cout;
-    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.Ktot = cv.R * cv.R * cv.cin; g.Kpad = cv.Kf;
-    return g;
+    ConvGeom q{};
+    q.b = h->P.d.microbatch; q.Ho = cv.h_out; q.Wo = cv.w_out; q.Hs = cv.h_in; q.Ws = cv.w_in; q.Cs = cv.cin; q.N = cv.cout;
+    q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cin; q.Kpad = cv.Kf;
+    return q;
   }
   ConvGeom geom_dgrad(const ConvPlan& cv) const {
-    ConvGeom g{};
-    g.b = h->P.d.microbatch; g.Ho = cv.h_in; g.Wo = cv.w_in; g.Hs = cv.h_out; g.Ws = cv.w_out; g.Cs = cv.cout; g.N = cv.cin;
-    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.Ktot = cv.R * cv.R * cv.cout; g.Kpad = cv.Kd;
-    return g;
+    ConvGeom q{};
+    q.b = h->P.d.microbatch; q.Ho = cv.h_in; q.Wo = cv.w_in; q.Hs = cv.h_out; q.Ws = cv.w_out; q.Cs = cv.cout; q.N = cv.cin;
+    q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cout; q.Kpad = cv.Kd;
+    return q;
   }
-  void conv_fwd(const ConvPlan& cv, const void* x, void* y, const void* add) {
-    const ConvGeom g = geom_fwd(cv);
+  void conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add) {
+    const ConvGeom q = geom_fwd(cv);
     if (h->P.dt == DT_BF16)
-      chk(launch_conv_mfma(CONV_FWD, (const bf16_t*)x, h->packed() + cv.wf_off, (bf16_t*)y, (const bf16_t*)add, g, s), "conv_fwd");
+      chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s), "conv_fwd");
     else
-      chk(launch_conv_f32(CONV_FWD, (const float*)x, h->params() + cv.w_off, (float*)y, (const float*)add, g, s), "conv_fwd_f32");
+      chk(launch_conv_f32(CONV_FWD, g, x, h->params() + cv.w_off, y, add, q, s), "conv_fwd_f32");
   }
-  void conv_dgrad(const ConvPlan& cv, const void* dy, void* dx, const void* add) {
-    const ConvGeom g = geom_dgrad(cv);
+  void conv_dgrad(const ConvPlan& cv, const PtrTab& dy, const PtrTab& dx, const PtrTab& add) {
+    const ConvGeom q = geom_dgrad(cv);
     if (h->P.dt == DT_BF16)
-      chk(launch_conv_mfma(CONV_DGRAD, (const bf16_t*)dy, h->packed() + cv.wd_off, (bf16_t*)dx, (const bf16_t*)add, g, s), "conv_dgrad");
+      chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s), "conv_dgrad");
     else
-      chk(launch_conv_f32(CONV_DGRAD, (const float*)dy, h->params() + cv.w_off, (float*)dx, (const float*)add, g, s), "conv_dgrad_f32");
+      chk(launch_conv_f32(CONV_DGRAD, g, dy, h->params() + cv.w_off, dx, add, q, s), "conv_dgrad_f32");
   }
-  void conv_wgrad(const ConvPlan& cv, const void* a, const void* dy) {
-    WgradGeom g{};
-    g.b = h->P.d.microbatch; g.H = cv.h_in; g.W = cv.w_in; g.Cin = cv.cin; g.Ho = cv.h_out; g.Wo = cv.w_out; g.N = cv.cout;
-    g.R = cv.R; g.stride = cv.stride; g.pad = (cv.R - 1) / 2; g.M = g.b * g.Ho * g.Wo; g.c_valid = cv.cin;
+  void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {
+    WgradGeom q{};
+    q.b = h->P.d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cv.cin; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
+    q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = cv.cin;
     if (h->P.dt == DT_BF16)
-      chk(launch_wgrad_mfma((const bf16_t*)a, (const bf16_t*)dy, h->grads() + cv.w_off, g, s), "conv_wgrad");
+      chk(launch_wgrad_mfma(g, a, dy, h->grads() + cv.w_off, q, s), "conv_wgrad");
     else
-      chk(launch_wgrad_f32((const float*)a, (const float*)dy, h->grads() + cv.w_off, g, s), "conv_wgrad_f32");
+      chk(launch_wgrad_f32(g, a, dy, h->grads() + cv.w_off, q, s), "conv_wgrad_f32");
   }
 };
 
-void run_forward(Ctx& c, const int32_t* labels, float* loss_accum) {
+void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
   if (P.d.has_stem) {
+    Loc in; in.kind = CALLER_ACT_IN;
     if (P.dt == DT_BF16) {
-      bf16_t* col = (bf16_t*)c.ptr(P.stem_col);
-      c.chk(launch_im2col3x3((const float*)c.act_in, col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
+      const PtrTab col = c.tab(P.stem_col);
+      c.chk(launch_im2col3x3(c.g, c.tab(in), col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
       ConvPlan cv = P.stem; cv.R = 1; cv.cin = P.stem_kc;
-      ConvGeom g = c.geom_fwd(cv);
-      g.Ktot = P.stem_kc; g.Kpad = P.stem.Kf;
-      c.chk(launch_conv_mfma(CONV_FWD, col, c.h->packed() + P.stem.wf_off, (bf16_t*)c.ptr(P.stem_out), nullptr, g, c.s), "stem_conv");
+      ConvGeom q = c.geom_fwd(cv);
+      q.Ktot = P.stem_kc; q.Kpad = P.stem.Kf;
+      c.chk(launch_conv_mfma(CONV_FWD, c.g, col, c.h->packed() + P.stem.wf_off, c.tab(P.stem_out), Ctx::none(), q, c.s), "stem_conv");
     } else {
-      c.conv_fwd(P.stem, c.act_in, c.ptr(P.stem_out), nullptr);
+      c.conv_fwd(P.stem, c.tab(in), c.tab(P.stem_out), Ctx::none());
     }
   }
   for (const BlockPlan& p : P.bp) {
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
-    const void* x = c.ptr(p.x_in);
-    void* y = c.ptr(p.y);
-    c.bn_fwd(p.bn[0], x, c.ptr(p.a[0]), M_in);
-    if (p.proj) c.conv_fwd(p.pj, c.ptr(p.a[0]), y, nullptr);
-    const void* shortcut = p.proj ? y : x;
+    const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
+    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in);
+    if (p.proj) c.conv_fwd(p.pj, c.tab(p.a[0]), y, Ctx::none());
+    const PtrTab shortcut = p.proj ? y : x;
     for (int j = 0; j < p.nconv; ++j) {
       const bool last = (j == p.nconv - 1);
-      void* out = last ? y : c.ptr(p.c[j]);
-      c.conv_fwd(p.cv[j], c.ptr(p.a[j]), out, last ? shortcut : nullptr);
-      if (!last) c.bn_fwd(p.bn[j + 1], out, c.ptr(p.a[j + 1]), M_out);
+      const PtrTab out = last ? y : c.tab(p.c[j]);
+      c.conv_fwd(p.cv[j], c.tab(p.a[j]), out, last ? shortcut : Ctx::none());
+      if (!last) c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out);
     }
   }
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
-    c.bn_fwd(P.head_bn, c.ptr(P.head_x), c.ptr(P.head_a), M);
-    c.chk(launch_head_fwd(P.dt, c.ptr(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
-                          (float*)c.ptr(P.head_g), (float*)c.ptr(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c,
-                          P.d.num_classes, (float)P.d.loss_divisor, c.s),
+    c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M);
+    c.chk(launch_head_fwd(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
+                          c.tab(P.head_g), c.tab(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes,
+                          (float)P.d.loss_divisor, c.s),
           "head_fwd");
   }
 }
@@ -393,52 +400,56 @@ void run_forward(Ctx& c, const int32_t* labels, float* loss_accum) {
 void run_backward(Ctx& c) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
-  void* dyA = c.scratch(0); void* dyB = c.scratch(1); void* tA = c.scratch(2); void* tB = c.scratch(3);
-  const void* dy = c.err_in;
+  const PtrTab tA = c.scratch(2), tB = c.scratch(3);
+  Loc lin; lin.kind = CALLER_ERR_IN;
+  Loc lout; lout.kind = CALLER_ERR_OUT;
+  PtrTab dy = c.tab(lin);
+  int cur = -1;  // which ping-pong scratch holds dy: -1 = a caller buffer
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
-    c.chk(launch_head_bwd(P.dt, (const float*)c.ptr(P.head_g), (const float*)c.ptr(P.head_dl), c.h->params() + P.wfc_off,
-                          c.h->grads() + P.wfc_off, c.h->grads() + P.bfc_off, tA, (int)b, P.out_h * P.out_w, P.out_c,
-                          P.d.num_classes, c.s),
+    c.chk(launch_head_bwd(P.dt, c.g, c.tab(P.head_g), c.tab(P.head_dl), c.h->params() + P.wfc_off, c.h->grads() + P.wfc_off,
+                          c.h->grads() + P.bfc_off, tA, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes, c.s),
           "head_bwd");
     const bool to_caller = (P.bp.empty() && !P.d.has_stem);
-    void* dx = to_caller ? c.err_out : dyA;
-    c.bn_bwd(P.head_bn, c.ptr(P.head_x), tA, nullptr, dx, M);
-    dy = dx;
+    const PtrTab dx = to_caller ? c.tab(lout) : c.scratch(0);
+    c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), dx, M);
+    dy = dx; cur = to_caller ? -1 : 0;
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
-    const void* dr = dy;
+    PtrTab dr = dy;
     for (int j = p.nconv - 1; j >= 1; --j) {
-      c.conv_wgrad(p.cv[j], c.ptr(p.a[j]), dr);
-      c.conv_dgrad(p.cv[j], dr, tA, nullptr);
-      c.bn_bwd(p.bn[j], c.ptr(p.c[j - 1]), tA, nullptr, tB, M_out);
+      c.conv_wgrad(p.cv[j], c.tab(p.a[j]), dr);
+      c.conv_dgrad(p.cv[j], dr, tA, Ctx::none());
+      c.bn_bwd(p.bn[j], c.tab(p.c[j - 1]), tA, Ctx::none(), tB, M_out);
       dr = tB;
     }
-    c.conv_wgrad(p.cv[0], c.ptr(p.a[0]), dr);
-    c.conv_dgrad(p.cv[0], dr, tA, nullptr);
+    c.conv_wgrad(p.cv[0], c.tab(p.a[0]), dr);
+    c.conv_dgrad(p.cv[0], dr, tA, Ctx::none());
     if (p.proj) {
-      c.conv_wgrad(p.pj, c.ptr(p.a[0]), dy);
+      c.conv_wgrad(p.pj, c.tab(p.a[0]), dy);
       c.conv_dgrad(p.pj, dy, tA, tA);
     }
-    void* dx;
-    if (ii == 0 && !P.d.has_stem) dx = c.err_out;
-    else dx = (dy == dyA) ? dyB : dyA;
-    c.bn_bwd(p.bn[0], c.ptr(p.x_in), tA, p.proj ? nullptr : dy, dx, M_in);
-    dy = dx;
+    PtrTab dx; int nxt;
+    if (ii == 0 && !P.d.has_stem) { dx = c.tab(lout); nxt = -1; }
+    else { nxt = (cur == 0) ? 1 : 0; dx = c.scratch(nxt); }
+    c.bn_bwd(p.bn[0], c.tab(p.x_in), tA, p.proj ? Ctx::none() : dy, dx, M_in);
+    dy = dx; cur = nxt;
   }
   if (P.d.has_stem) {
     if (P.dt == DT_BF16) {
-      WgradGeom g{};
-      g.b = (int)b; g.H = P.d.in_h; g.W = P.d.in_w; g.Cin = P.stem_kc; g.Ho = g.H; g.Wo = g.W; g.N = P.d.stem_c_out;
-      g.R = 1; g.stride = 1; g.pad = 0; g.M = g.b * g.H * g.W; g.c_valid = 9 * P.d.in_c;
-      c.chk(launch_wgrad_mfma((const bf16_t*)c.ptr(P.stem_col), (const bf16_t*)dy, c.h->grads() + P.stem.w_off, g, c.s), "stem_wgrad");
+      WgradGeom q{};
+      q.b = (int)b; q.H = P.d.in_h; q.W = P.d.in_w; q.Cin = P.stem_kc; q.Ho = q.H; q.Wo = q.W; q.N = P.d.stem_c_out;
+      q.R = 1; q.stride = 1; q.pad = 0; q.M = q.b * q.H * q.W; q.c_valid = 9 * P.d.in_c;
+      c.chk(launch_wgrad_mfma(c.g, c.tab(P.stem_col), dy, c.h->grads() + P.stem.w_off, q, c.s), "stem_wgrad");
     } else {
-      c.conv_wgrad(P.stem, c.act_in, dy);
+      Loc in; in.kind = CALLER_ACT_IN;
+      c.conv_wgrad(P.stem, c.tab(in), dy);
     }
   }
 }
+
 
 bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_microbatches; }
 
@@ -452,15 +463,14 @@ hpf_status wait_all_backward(hpf_partition* p, hipStream_t s) {
 // same caller pointers exists, captured and instantiated first otherwise.  The sequences contain kernel
 // nodes only.  Falls back to direct launches when graphs are off or the stream is already capturing.
 template <class Body>
-hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const void* k0, const void* k1, const void* k2, const void* k3,
-                       hipStream_t s, Ctx& c, Body body) {
+hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<const void*>& key, hipStream_t s, Ctx& c, Body body) {
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   // the default (NULL) stream cannot be captured
   if (!p->use_graphs || s == nullptr || hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
     body();
     return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
   }
-  const bool hit = slot.exec && slot.key[0] == k0 && slot.key[1] == k1 && slot.key[2] == k2 && slot.key[3] == k3;
+  const bool hit = slot.exec && slot.key == key;
   if (!hit) {
     if (slot.exec) { (void)hipGraphExecDestroy(slot.exec); slot.exec = nullptr; }
     hipGraph_t graph = nullptr;
@@ -474,7 +484,7 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const void* k0, const 
     const hipError_t ei = hipGraphInstantiate(&slot.exec, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
     if (ei != hipSuccess) { slot.exec = nullptr; return fail(HPF_EDEVICE, "hipGraphInstantiate: %s", hipGetErrorString(ei)); }
-    slot.key[0] = k0; slot.key[1] = k1; slot.key[2] = k2; slot.key[3] = k3;
+    slot.key = key;
   }
   if (hipGraphLaunch(slot.exec, s) != hipSuccess) return fail(HPF_EDEVICE, "hipGraphLaunch failed");
   return HPF_OK;
@@ -564,45 +574,105 @@ void hpf_partition_destroy(hpf_partition* p) {
   delete p;
 }
 
-hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels,
-                                  void* act_out, float* loss_accum, void* hip_stream) {
+hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* act_in,
+                                   const int32_t* const* labels, void* const* act_out, float* loss_accum, void* hip_stream) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   const Plan& P = p->P;
-  if (mb < 0 || mb >= P.d.num_microbatches) return fail(HPF_EINVAL, "micro-batch %d out of range", mb);
+  if (count < 1 || mb_first < 0 || mb_first + count > P.d.num_microbatches)
+    return fail(HPF_EINVAL, "micro-batches [%d, %d) out of range", mb_first, mb_first + count);
   if (!act_in) return fail(HPF_EINVAL, "act_in is required");
   if (P.d.has_head && (!labels || !loss_accum)) return fail(HPF_EINVAL, "labels and loss_accum are required with a head");
   if (!P.d.has_head && !act_out) return fail(HPF_EINVAL, "act_out is required without a head");
-  if (p->fwd_done[mb]) return fail(HPF_ESTATE, "forward(%d) already ran in this batch", mb);
+  for (int i = 0; i < count; ++i) {
+    if (!act_in[i]) return fail(HPF_EINVAL, "act_in[%d] is null", i);
+    if (P.d.has_head && !labels[i]) return fail(HPF_EINVAL, "labels[%d] is null", i);
+    if (!P.d.has_head && !act_out[i]) return fail(HPF_EINVAL, "act_out[%d] is null", i);
+    if (p->fwd_done[mb_first + i]) return fail(HPF_ESTATE, "forward(%d) already ran in this batch", mb_first + i);
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  Ctx c{p, mb, s, act_in, act_out, nullptr, nullptr};
-  const hpf_status st = run_graphed(p, p->g_fwd[mb], act_in, labels, act_out, loss_accum, s, c,
-                                    [&] { run_forward(c, labels, loss_accum); });
-  if (st != HPF_OK) return st;
-  if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
-  p->act_in[mb] = act_in;
-  p->fwd_done[mb] = 1;
+  for (int c0 = 0; c0 < count; c0 += MAX_GROUP) {
+    const int g = count - c0 < MAX_GROUP ? count - c0 : MAX_GROUP;
+    Ctx c{p, mb_first + c0, g, s};
+    PtrTab lab{};
+    std::vector<const void*> key;
+    key.push_back((const void*)(intptr_t)g);
+    key.push_back(loss_accum);
+    for (int i = 0; i < g; ++i) {
+      c.act_in[i] = act_in[c0 + i];
+      c.act_out[i] = P.d.has_head ? nullptr : act_out[c0 + i];
+      c.err_in[i] = nullptr; c.err_out[i] = nullptr;
+      lab.p[i] = P.d.has_head ? const_cast<int32_t*>(labels[c0 + i]) : nullptr;
+      key.push_back(c.act_in[i]); key.push_back(c.act_out[i]); key.push_back(lab.p[i]);
+    }
+    const hpf_status st = run_graphed(p, p->g_fwd[mb_first + c0], key, s, c, [&] { run_forward(c, lab, loss_accum); });
+    if (st != HPF_OK) return st;
+    for (int i = 0; i < g; ++i) {
+      const int mb = mb_first + c0 + i;
+      if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+      p->act_in[mb] = c.act_in[i];
+      p->fwd_done[mb] = 1;
+    }
+  }
   return HPF_OK;
 }
 
-hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out, void* hip_stream) {
+hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in,
+                                    void* const* err_out, void* hip_stream) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   const Plan& P = p->P;
-  if (mb < 0 || mb >= P.d.num_microbatches) return fail(HPF_EINVAL, "micro-batch %d out of range", mb);
+  if (count < 1 || mb_first < 0 || mb_first + count > P.d.num_microbatches)
+    return fail(HPF_EINVAL, "micro-batches [%d, %d) out of range", mb_first, mb_first + count);
   if (!P.d.has_head && !err_in) return fail(HPF_EINVAL, "err_in is required without a head");
-  if (P.d.has_stem && err_out) return fail(HPF_EINVAL, "err_out must be NULL for the partition that holds the stem");
   if (!P.d.has_stem && !err_out) return fail(HPF_EINVAL, "err_out is required");
-  if (!p->fwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) before forward(%d)", mb, mb);
-  if (p->bwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) already ran in this batch", mb);
+  for (int i = 0; i < count; ++i) {
+    const int mb = mb_first + i;
+    if (!P.d.has_head && !err_in[i]) return fail(HPF_EINVAL, "err_in[%d] is null", i);
+    if (P.d.has_stem && err_out && err_out[i]) return fail(HPF_EINVAL, "err_out must be NULL for the partition that holds the stem");
+    if (!P.d.has_stem && !err_out[i]) return fail(HPF_EINVAL, "err_out[%d] is null", i);
+    if (!p->fwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) before forward(%d)", mb, mb);
+    if (p->bwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) already ran in this batch", mb);
+  }
   hipStream_t s = (hipStream_t)hip_stream;
-  if (hipStreamWaitEvent(s, p->ev_fwd[mb], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  Ctx c{p, mb, s, p->act_in[mb], nullptr, err_in, err_out};
-  const hpf_status st = run_graphed(p, p->g_bwd[mb], p->act_in[mb], err_in, err_out, nullptr, s, c, [&] { run_backward(c); });
-  if (st != HPF_OK) return st;
-  if (hipEventRecord(p->ev_bwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
-  p->bwd_done[mb] = 1;
-  ++p->n_bwd;
+  for (int i = 0; i < count; ++i)
+    if (hipStreamWaitEvent(s, p->ev_fwd[mb_first + i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  for (int c0 = 0; c0 < count; c0 += MAX_GROUP) {
+    const int g = count - c0 < MAX_GROUP ? count - c0 : MAX_GROUP;
+    Ctx c{p, mb_first + c0, g, s};
+    std::vector<const void*> key;
+    key.push_back((const void*)(intptr_t)g);
+    for (int i = 0; i < g; ++i) {
+      c.act_in[i] = p->act_in[mb_first + c0 + i];
+      c.act_out[i] = nullptr;
+      c.err_in[i] = P.d.has_head ? nullptr : err_in[c0 + i];
+      c.err_out[i] = P.d.has_stem ? nullptr : err_out[c0 + i];
+      key.push_back(c.act_in[i]); key.push_back(c.err_in[i]); key.push_back(c.err_out[i]);
+    }
+    const hpf_status st = run_graphed(p, p->g_bwd[mb_first + c0], key, s, c, [&] { run_backward(c); });
+    if (st != HPF_OK) return st;
+    for (int i = 0; i < g; ++i) {
+      const int mb = mb_first + c0 + i;
+      if (hipEventRecord(p->ev_bwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+      p->bwd_done[mb] = 1;
+      ++p->n_bwd;
+    }
+  }
   return HPF_OK;
+}
+
+hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels, void* act_out,
+                                  float* loss_accum, void* hip_stream) {
+  if (p && p->P.d.has_head && !labels) return fail(HPF_EINVAL, "labels and loss_accum are required with a head");
+  if (p && !p->P.d.has_head && !act_out) return fail(HPF_EINVAL, "act_out is required without a head");
+  if (!act_in) return fail(HPF_EINVAL, "act_in is required");
+  return hpf_forward_microbatches(p, mb, 1, &act_in, &labels, &act_out, loss_accum, hip_stream);
+}
+
+hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out, void* hip_stream) {
+  if (p && !p->P.d.has_head && !err_in) return fail(HPF_EINVAL, "err_in is required without a head");
+  if (p && !p->P.d.has_stem && !err_out) return fail(HPF_EINVAL, "err_out is required");
+  if (p && p->P.d.has_stem && err_out) return fail(HPF_EINVAL, "err_out must be NULL for the partition that holds the stem");
+  return hpf_backward_microbatches(p, mb, 1, &err_in, &err_out, hip_stream);
 }
 
 hpf_status hpf_grad_accum_read(hpf_partition* p, float* dst, size_t n_floats, int32_t dst_is_device, void* hip_stream) {
@@ -697,7 +767,7 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
   else { g.Ho = h; g.Wo = wd; g.Hs = h / stride; g.Ws = wd / stride; g.Cs = cout; g.N = cin; }
   g.M = b * g.Ho * g.Wo; g.Ktot = R * R * g.Cs; g.Kpad = round_up32(g.Ktot);
   if (!bf) {
-    if (launch_conv_f32(mode, (const float*)src, w, (float*)out, (const float*)add, g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+    if (launch_conv_f32(mode, 1, one_ptr(src), w, one_ptr(out), one_ptr(add), g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
     return HPF_OK;
   }
   if (!ws || ws_bytes < hpf_op_workspace_bytes(cin, cout, R)) return fail(HPF_ENOMEM, "workspace too small");
@@ -714,7 +784,7 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
     if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
   }
   const bf16_t* wp = (const bf16_t*)base + (mode == CONV_FWD ? pd.wf_off : pd.wd_off);
-  if (launch_conv_mfma(mode, (const bf16_t*)src, wp, (bf16_t*)out, (const bf16_t*)add, g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_conv_mfma(mode, 1, one_ptr(src), wp, one_ptr(out), one_ptr(add), g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
 }
 
@@ -738,8 +808,8 @@ hpf_status hpf_op_conv_wgrad(hpf_dtype dtype, const void* x, const void* dy, flo
   WgradGeom g{};
   g.b = b; g.H = h; g.W = wd; g.Cin = cin; g.Ho = h / stride; g.Wo = wd / stride; g.N = cout; g.R = R; g.stride = stride;
   g.pad = (R - 1) / 2; g.M = b * g.Ho * g.Wo; g.c_valid = cin;
-  const hipError_t e = bf ? launch_wgrad_mfma((const bf16_t*)x, (const bf16_t*)dy, dw, g, (hipStream_t)hip_stream)
-                          : launch_wgrad_f32((const float*)x, (const float*)dy, dw, g, (hipStream_t)hip_stream);
+  const hipError_t e = bf ? launch_wgrad_mfma(1, one_ptr(x), one_ptr(dy), dw, g, (hipStream_t)hip_stream)
+                          : launch_wgrad_f32(1, one_ptr(x), one_ptr(dy), dw, g, (hipStream_t)hip_stream);
   return e == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "launch failed");
 }
 
@@ -752,9 +822,8 @@ hpf_status hpf_op_bn_relu_forward(hpf_dtype dtype, const void* x, const float* g
   const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
   char* ws = (char*)workspace;
   void* partials = ws + op_ws_tickets() + op_ws_sums_bytes(C);
-  if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
-  if (launch_bn_stats(dt, x, M, C, eps, stats, partials, (unsigned*)ws, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
-  if (launch_bn_apply_relu(dt, x, a, gamma, beta, stats, M, C, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_stats(dt, 1, one_ptr(x), M, C, eps, one_ptr(stats), one_ptr(partials), s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_apply_relu(dt, 1, one_ptr(x), one_ptr(a), gamma, beta, one_ptr(stats), M, C, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
 }
 
@@ -769,10 +838,10 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
   char* ws = (char*)workspace;
   void* sums = ws + op_ws_tickets();
   void* partials = ws + op_ws_tickets() + op_ws_sums_bytes(C);
-  if (launch_zero_f32((float*)ws, 64, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
-  if (launch_bn_bwd_reduce(dt, x, da, gamma, beta, stats, M, C, sums, dgamma, dbeta, partials, (unsigned*)ws, s) != hipSuccess)
+  if (launch_bn_bwd_reduce(dt, 1, one_ptr(x), one_ptr(da), gamma, beta, one_ptr(stats), M, C, one_ptr(sums), dgamma, dbeta, one_ptr(partials), s) != hipSuccess)
     return fail(HPF_EDEVICE, "launch failed");
-  if (launch_bn_bwd_apply(dt, x, da, gamma, beta, stats, sums, skip, dx, M, C, 0, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_bwd_apply(dt, 1, one_ptr(x), one_ptr(da), gamma, beta, one_ptr(stats), one_ptr(sums), one_ptr(skip), one_ptr(dx), M, C, 0, s) != hipSuccess)
+    return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
 }
 

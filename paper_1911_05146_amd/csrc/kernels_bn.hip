@@ -135,8 +135,9 @@ __device__ __forceinline__ bool reduce_partials(const A* partials, int C, unsign
 }
 
 template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_stats(const T* __restrict__ x, int M, int C, int rows_per_block,
-                                                         A* __restrict__ partials) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_stats(PtrTab xs, int M, int C, int rows_per_block, PtrTab parts) {
+  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+  A* __restrict__ partials = (A*)parts.p[blockIdx.z];
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16];
@@ -167,9 +168,11 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(const T* __restrict__ x
 
 // grid (1, ceil(C/256)): statistics from the nblocks partials.
 template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(const T* __restrict__ x, int M, int C, unsigned nblocks,
-                                                                  float eps, const A* __restrict__ partials,
-                                                                  A* __restrict__ stats) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(PtrTab xs, int M, int C, unsigned nblocks, float eps,
+                                                                  PtrTab parts, PtrTab statss) {
+  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+  const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
+  A* __restrict__ stats = (A*)statss.p[blockIdx.z];
   __shared__ A sh[2][BN_THREADS];
   A s1, s2;
   if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
@@ -184,10 +187,12 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(const T* __res
 }
 
 template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_apply_relu(const T* __restrict__ x, T* __restrict__ a,
-                                                              const float* __restrict__ gamma,
-                                                              const float* __restrict__ beta,
-                                                              const A* __restrict__ stats, int M, int C) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_apply_relu(PtrTab xs, PtrTab as, const float* __restrict__ gamma,
+                                                              const float* __restrict__ beta, PtrTab statss, int M,
+                                                              int C) {
+  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+  T* __restrict__ a = (T*)as.p[blockIdx.z];
+  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
   const BnMap m = bn_map(C);
   if (!m.active) return;
   A mu[8], is[8], g[8], bt[8], v[8];
@@ -204,11 +209,13 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_apply_relu(const T* __restric
 }
 
 template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(const T* __restrict__ x, const T* __restrict__ da,
-                                                              const float* __restrict__ gamma,
-                                                              const float* __restrict__ beta,
-                                                              const A* __restrict__ stats, int M, int C,
-                                                              int rows_per_block, A* __restrict__ partials) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(PtrTab xs, PtrTab das, const float* __restrict__ gamma,
+                                                              const float* __restrict__ beta, PtrTab statss, int M,
+                                                              int C, int rows_per_block, PtrTab parts) {
+  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+  const T* __restrict__ da = (const T*)das.p[blockIdx.z];
+  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
+  A* __restrict__ partials = (A*)parts.p[blockIdx.z];
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16];
@@ -243,8 +250,10 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(const T* __restric
 // grid (1, ceil(C/256)): dbeta / dgamma of this micro-batch from the partials; also added into the
 // gradient buffer shared by all micro-batches.
 template <class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned nblocks, const A* __restrict__ partials,
-                                                                A* __restrict__ sums, float* g_gamma, float* g_beta) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned nblocks, PtrTab parts, PtrTab sumss,
+                                                                float* g_gamma, float* g_beta) {
+  const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
+  A* __restrict__ sums = (A*)sumss.p[blockIdx.z];
   __shared__ A sh[2][BN_THREADS];
   A s1, s2;
   if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
@@ -257,12 +266,15 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned 
 }
 
 template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_apply(const T* __restrict__ x, const T* __restrict__ da,
-                                                             const float* __restrict__ gamma,
-                                                             const float* __restrict__ beta,
-                                                             const A* __restrict__ stats,
-                                                             const A* __restrict__ sums, const T* skip,
-                                                             T* dx, int M, int C, int frozen) {
+__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_apply(PtrTab xs, PtrTab das, const float* __restrict__ gamma,
+                                                             const float* __restrict__ beta, PtrTab statss, PtrTab sumss,
+                                                             PtrTab skips, PtrTab dxs, int M, int C, int frozen) {
+  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+  const T* __restrict__ da = (const T*)das.p[blockIdx.z];
+  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
+  const A* __restrict__ sums = (const A*)sumss.p[blockIdx.z];
+  const T* skip = (const T*)skips.p[blockIdx.z];
+  T* dx = (T*)dxs.p[blockIdx.z];
   const BnMap m = bn_map(C);
   if (!m.active) return;
   A mu[8], is[8], g[8], bt[8], sb[8], sg[8], v[8], d[8], k[8];
@@ -290,7 +302,8 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_apply(const T* __restrict
 }
 
 template <class A>
-__global__ void k_bn_frozen_stats(A* stats, int C, float eps) {
+__global__ void k_bn_frozen_stats(PtrTab statss, int C, float eps) {
+  A* stats = (A*)statss.p[blockIdx.z];
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c < C) { stats[c] = 0; stats[C + c] = rsqrt_exact((A)1 + (A)eps); }
 }
@@ -318,63 +331,62 @@ dim3 apply_grid(int M, int C) {
 
 size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 2 * 2; }  // sized for double
 
-hipError_t launch_bn_stats(int dt, const void* x, int M, int C, float eps, void* stats, void* partials,
-                           unsigned* /*tickets*/, hipStream_t stream) {
+hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
+                           const PtrTab& partials, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  const dim3 fin(1, g.grid.y);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin(1, g.grid.y, (unsigned)ng);
   if (dt == DT_BF16) {
-    k_bn_stats<bf16_t, float><<<g.grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, M, C, g.rows_per_block, (float*)partials);
-    k_bn_stats_finalize<bf16_t, float><<<fin, BN_THREADS, 0, stream>>>((const bf16_t*)x, M, C, g.grid.x, eps, (const float*)partials, (float*)stats);
+    k_bn_stats<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
+    k_bn_stats_finalize<bf16_t, float><<<fin, BN_THREADS, 0, stream>>>(x, M, C, g.grid.x, eps, partials, stats);
   } else {
-    k_bn_stats<float, double><<<g.grid, BN_THREADS, 0, stream>>>((const float*)x, M, C, g.rows_per_block, (double*)partials);
-    k_bn_stats_finalize<float, double><<<fin, BN_THREADS, 0, stream>>>((const float*)x, M, C, g.grid.x, eps, (const double*)partials, (double*)stats);
+    k_bn_stats<float, double><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
+    k_bn_stats_finalize<float, double><<<fin, BN_THREADS, 0, stream>>>(x, M, C, g.grid.x, eps, partials, stats);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_bn_apply_relu(int dt, const void* x, void* a, const float* gamma, const float* beta,
-                                const void* stats, int M, int C, hipStream_t stream) {
-  const dim3 grid = apply_grid(M, C);
+hipError_t launch_bn_apply_relu(int dt, int ng, const PtrTab& x, const PtrTab& a, const float* gamma, const float* beta,
+                                const PtrTab& stats, int M, int C, hipStream_t stream) {
+  dim3 grid = apply_grid(M, C);
+  grid.z = (unsigned)ng;
   if (dt == DT_BF16)
-    k_bn_apply_relu<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, (bf16_t*)a, gamma, beta, (const float*)stats, M, C);
+    k_bn_apply_relu<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, a, gamma, beta, stats, M, C);
   else
-    k_bn_apply_relu<float, double><<<grid, BN_THREADS, 0, stream>>>((const float*)x, (float*)a, gamma, beta, (const double*)stats, M, C);
+    k_bn_apply_relu<float, double><<<grid, BN_THREADS, 0, stream>>>(x, a, gamma, beta, stats, M, C);
   return hipGetLastError();
 }
 
-hipError_t launch_bn_bwd_reduce(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                                const void* stats, int M, int C, void* sums, float* g_gamma, float* g_beta,
-                                void* partials, unsigned* /*tickets*/, hipStream_t stream) {
+hipError_t launch_bn_bwd_reduce(int dt, int ng, const PtrTab& x, const PtrTab& da, const float* gamma, const float* beta,
+                                const PtrTab& stats, int M, int C, const PtrTab& sums, float* g_gamma, float* g_beta,
+                                const PtrTab& partials, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  const dim3 fin(1, g.grid.y);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin(1, g.grid.y, (unsigned)ng);
   if (dt == DT_BF16) {
-    k_bn_bwd_reduce<bf16_t, float><<<g.grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, (const bf16_t*)da, gamma, beta, (const float*)stats, M, C,
-                                                                      g.rows_per_block, (float*)partials);
-    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, (const float*)partials, (float*)sums, g_gamma, g_beta);
+    k_bn_bwd_reduce<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, M, C, g.rows_per_block, partials);
+    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
   } else {
-    k_bn_bwd_reduce<float, double><<<g.grid, BN_THREADS, 0, stream>>>((const float*)x, (const float*)da, gamma, beta, (const double*)stats, M, C,
-                                                                      g.rows_per_block, (double*)partials);
-    k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, (const double*)partials, (double*)sums, g_gamma, g_beta);
+    k_bn_bwd_reduce<float, double><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, M, C, g.rows_per_block, partials);
+    k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_bn_bwd_apply(int dt, const void* x, const void* da, const float* gamma, const float* beta,
-                               const void* stats, const void* sums, const void* skip, void* dx, int M, int C,
-                               int frozen, hipStream_t stream) {
-  const dim3 grid = apply_grid(M, C);
+hipError_t launch_bn_bwd_apply(int dt, int ng, const PtrTab& x, const PtrTab& da, const float* gamma, const float* beta,
+                               const PtrTab& stats, const PtrTab& sums, const PtrTab& skip, const PtrTab& dx, int M,
+                               int C, int frozen, hipStream_t stream) {
+  dim3 grid = apply_grid(M, C);
+  grid.z = (unsigned)ng;
   if (dt == DT_BF16)
-    k_bn_bwd_apply<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>((const bf16_t*)x, (const bf16_t*)da, gamma, beta, (const float*)stats,
-                                                                   (const float*)sums, (const bf16_t*)skip, (bf16_t*)dx, M, C, frozen);
+    k_bn_bwd_apply<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, sums, skip, dx, M, C, frozen);
   else
-    k_bn_bwd_apply<float, double><<<grid, BN_THREADS, 0, stream>>>((const float*)x, (const float*)da, gamma, beta, (const double*)stats,
-                                                                   (const double*)sums, (const float*)skip, (float*)dx, M, C, frozen);
+    k_bn_bwd_apply<float, double><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, sums, skip, dx, M, C, frozen);
   return hipGetLastError();
 }
 
-hipError_t launch_bn_frozen_stats(int dt, void* stats, int C, float eps, hipStream_t stream) {
-  if (dt == DT_BF16) k_bn_frozen_stats<float><<<(C + 255) / 256, 256, 0, stream>>>((float*)stats, C, eps);
-  else k_bn_frozen_stats<double><<<(C + 255) / 256, 256, 0, stream>>>((double*)stats, C, eps);
+hipError_t launch_bn_frozen_stats(int dt, int ng, const PtrTab& stats, int C, float eps, hipStream_t stream) {
+  const dim3 grid((unsigned)((C + 255) / 256), 1, (unsigned)ng);
+  if (dt == DT_BF16) k_bn_frozen_stats<float><<<grid, 256, 0, stream>>>(stats, C, eps);
+  else k_bn_frozen_stats<double><<<grid, 256, 0, stream>>>(stats, C, eps);
   return hipGetLastError();
 }
 

@@ -29,8 +29,11 @@ constexpr int KC = 32;          // reduction elements per step
 constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-free 16-byte reads)
 
 template <int BM, int BN, int WR, int WC, int MODE>
-__global__ __launch_bounds__(256) void k_conv_mfma(const bf16_t* __restrict__ src, const bf16_t* __restrict__ wpk,
-                                                   bf16_t* out, const bf16_t* add, ConvGeom g) {
+__global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds,
+                                                   ConvGeom g) {
+  const bf16_t* __restrict__ src = (const bf16_t*)srcs.p[blockIdx.z];
+  bf16_t* out = (bf16_t*)outs.p[blockIdx.z];
+  const bf16_t* add = (const bf16_t*)adds.p[blockIdx.z];
   static_assert(WR * WC == 4, "4 waves");
   constexpr int WPX = BM / WR, WCH = BN / WC, PT = WPX / 16, CT = WCH / 16;
   static_assert(PT >= 1 && CT >= 1, "tile too small");
@@ -158,9 +161,9 @@ __global__ __launch_bounds__(256) void k_conv_mfma(const bf16_t* __restrict__ sr
 }
 
 template <int BM, int BN, int WR, int WC>
-hipError_t launch_tile(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
+hipError_t launch_tile(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
                        const ConvGeom& g, hipStream_t stream) {
-  const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN));
+  const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN), (unsigned)ng);
   if (mode == CONV_FWD)
     k_conv_mfma<BM, BN, WR, WC, CONV_FWD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g);
   else
@@ -172,16 +175,17 @@ hipError_t launch_tile(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* o
 
 // Tile choice: the widest channel tile that divides N, then the pixel tile that still gives the
 // chip (256 CUs) enough work-groups.
-hipError_t launch_conv_mfma(int mode, const bf16_t* src, const bf16_t* wpk, bf16_t* out, const bf16_t* add,
+hipError_t launch_conv_mfma(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
                             const ConvGeom& g, hipStream_t stream) {
+  if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
   if (g.N % 16 != 0 || g.Cs % 8 != 0 || g.Kpad % KC != 0 || (g.stride != 1 && g.stride != 2)) return hipErrorInvalidValue;
   if (g.N % 128 == 0) {
-    const long wgs = (long)((g.M + 127) / 128) * (g.N / 128);
-    if (wgs >= 192) return launch_tile<128, 128, 2, 2>(mode, src, wpk, out, add, g, stream);
+    const long wgs = (long)((g.M + 127) / 128) * (g.N / 128) * ng;
+    if (wgs >= 192) return launch_tile<128, 128, 2, 2>(mode, ng, src, wpk, out, add, g, stream);
   }
-  if (g.N % 64 == 0) return launch_tile<64, 64, 2, 2>(mode, src, wpk, out, add, g, stream);
-  if (g.N % 32 == 0) return launch_tile<64, 32, 4, 1>(mode, src, wpk, out, add, g, stream);
-  return launch_tile<64, 16, 4, 1>(mode, src, wpk, out, add, g, stream);
+  if (g.N % 64 == 0) return launch_tile<64, 64, 2, 2>(mode, ng, src, wpk, out, add, g, stream);
+  if (g.N % 32 == 0) return launch_tile<64, 32, 4, 1>(mode, ng, src, wpk, out, add, g, stream);
+  return launch_tile<64, 16, 4, 1>(mode, ng, src, wpk, out, add, g, stream);
 }
 
 }  // namespace hpf

@@ -12,8 +12,11 @@ namespace {
 //   CONV_FWD  : W(tap,c,n) = w[tap][c][n]   (Cs = Cin,  N = Cout)
 //   CONV_DGRAD: W(tap,c,n) = w[tap][n][c]   (Cs = Cout, N = Cin)
 template <int MODE>
-__global__ __launch_bounds__(256) void k_conv_f32(const float* __restrict__ src, const float* __restrict__ w,
-                                                  float* out, const float* add, ConvGeom g) {
+__global__ __launch_bounds__(256) void k_conv_f32(PtrTab srcs, const float* __restrict__ w, PtrTab outs, PtrTab adds,
+                                                  ConvGeom g) {
+  const float* __restrict__ src = (const float*)srcs.p[blockIdx.z];
+  float* out = (float*)outs.p[blockIdx.z];
+  const float* add = (const float*)adds.p[blockIdx.z];
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)g.M * g.N) return;
   const int n = (int)(idx % g.N);
@@ -58,8 +61,9 @@ __global__ __launch_bounds__(256) void k_conv_f32(const float* __restrict__ src,
 }
 
 // dw[tap][c][n] += sum over this block's row slice of a[row(m,tap), c] * dy[m, n]
-__global__ __launch_bounds__(256) void k_wgrad_f32(const float* __restrict__ a, const float* __restrict__ dy,
-                                                   float* dw, WgradGeom g, int rows_per_slice) {
+__global__ __launch_bounds__(256) void k_wgrad_f32(PtrTab as, PtrTab dys, float* dw, WgradGeom g, int rows_per_slice) {
+  const float* __restrict__ a = (const float*)as.p[blockIdx.z];
+  const float* __restrict__ dy = (const float*)dys.p[blockIdx.z];
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t total = (size_t)g.R * g.R * g.c_valid * g.N;
   if (idx >= total) return;
@@ -83,10 +87,10 @@ __global__ __launch_bounds__(256) void k_wgrad_f32(const float* __restrict__ a, 
 
 }  // namespace
 
-hipError_t launch_conv_f32(int mode, const float* src, const float* w_hwio, float* out, const float* add,
+hipError_t launch_conv_f32(int mode, int ng, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& g, hipStream_t stream) {
   const size_t total = (size_t)g.M * g.N;
-  const unsigned grid = (unsigned)((total + 255) / 256);
+  const dim3 grid((unsigned)((total + 255) / 256), 1, (unsigned)ng);
   if (mode == CONV_FWD)
     k_conv_f32<CONV_FWD><<<grid, 256, 0, stream>>>(src, w_hwio, out, add, g);
   else
@@ -94,7 +98,7 @@ hipError_t launch_conv_f32(int mode, const float* src, const float* w_hwio, floa
   return hipGetLastError();
 }
 
-hipError_t launch_wgrad_f32(const float* a, const float* dy, float* dw, const WgradGeom& g, hipStream_t stream) {
+hipError_t launch_wgrad_f32(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
   const size_t total = (size_t)g.R * g.R * g.c_valid * g.N;
   const unsigned gx = (unsigned)((total + 255) / 256);
   int slices = (int)(1024 / (gx ? gx : 1));
@@ -103,7 +107,7 @@ hipError_t launch_wgrad_f32(const float* a, const float* dy, float* dw, const Wg
   if (slices > max_slices) slices = max_slices;
   const int rows = (g.M + slices - 1) / slices;
   slices = (g.M + rows - 1) / rows;
-  k_wgrad_f32<<<dim3(gx, (unsigned)slices), 256, 0, stream>>>(a, dy, dw, g, rows);
+  k_wgrad_f32<<<dim3(gx, (unsigned)slices, (unsigned)ng), 256, 0, stream>>>(a, dy, dw, g, rows);
   return hipGetLastError();
 }
 

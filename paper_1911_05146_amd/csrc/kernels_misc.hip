@@ -7,8 +7,9 @@ namespace hpf {
 namespace {
 
 // col[m, k] for k = (r*3+s)*Cin + c, zero for taps outside the image and for k >= 9*Cin.
-__global__ __launch_bounds__(256) void k_im2col3x3(const float* __restrict__ img, bf16_t* __restrict__ col, int b,
-                                                   int H, int W, int Cin, int Kc) {
+__global__ __launch_bounds__(256) void k_im2col3x3(PtrTab imgs, PtrTab cols, int b, int H, int W, int Cin, int Kc) {
+  const float* __restrict__ img = (const float*)imgs.p[blockIdx.z];
+  bf16_t* __restrict__ col = (bf16_t*)cols.p[blockIdx.z];
   const size_t total = (size_t)b * H * W * Kc;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int k = (int)(i % Kc);
@@ -48,10 +49,13 @@ __device__ __forceinline__ float block_reduce_sum(float v, float* sh) {
 
 // One block per sample.  Dynamic LDS: C + classes floats.
 template <class T>
-__global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ a, const float* __restrict__ wfc,
-                                                  const float* __restrict__ bfc, const int32_t* __restrict__ labels,
-                                                  float* __restrict__ g, float* __restrict__ dlogits,
-                                                  float* loss_accum, int hw, int C, int classes, float inv_div) {
+__global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __restrict__ wfc, const float* __restrict__ bfc,
+                                                  PtrTab labelss, PtrTab gs_, PtrTab dls, float* loss_accum, int hw, int C,
+                                                  int classes, float inv_div) {
+  const T* __restrict__ a = (const T*)as.p[blockIdx.z];
+  const int32_t* __restrict__ labels = (const int32_t*)labelss.p[blockIdx.z];
+  float* __restrict__ g = (float*)gs_.p[blockIdx.z];
+  float* __restrict__ dlogits = (float*)dls.p[blockIdx.z];
   extern __shared__ float dyn[];
   __shared__ float red[8];
   float* gs = dyn;
@@ -86,9 +90,11 @@ __global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ a, const
 
 // One block per sample: dWfc += g^T dlogits, dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw.
 template <class T>
-__global__ __launch_bounds__(256) void k_head_bwd(const float* __restrict__ g, const float* __restrict__ dlogits,
-                                                  const float* __restrict__ wfc, float* g_wfc, float* g_bfc,
-                                                  T* __restrict__ da, int hw, int C, int classes) {
+__global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const float* __restrict__ wfc, float* g_wfc,
+                                                  float* g_bfc, PtrTab das, int hw, int C, int classes) {
+  const float* __restrict__ g = (const float*)gs_.p[blockIdx.z];
+  const float* __restrict__ dlogits = (const float*)dls.p[blockIdx.z];
+  T* __restrict__ da = (T*)das.p[blockIdx.z];
   extern __shared__ float dyn[];
   float* dl = dyn;          // classes
   float* dg = dyn + classes;  // C
@@ -170,29 +176,32 @@ unsigned grid_for(size_t n, unsigned cap = 2048) {
 
 }  // namespace
 
-hipError_t launch_im2col3x3(const float* img, bf16_t* col, int b, int H, int W, int Cin, int Kc, hipStream_t stream) {
-  k_im2col3x3<<<grid_for((size_t)b * H * W * Kc), 256, 0, stream>>>(img, col, b, H, W, Cin, Kc);
+hipError_t launch_im2col3x3(int ng, const PtrTab& img, const PtrTab& col, int b, int H, int W, int Cin, int Kc,
+                            hipStream_t stream) {
+  k_im2col3x3<<<dim3(grid_for((size_t)b * H * W * Kc), 1, (unsigned)ng), 256, 0, stream>>>(img, col, b, H, W, Cin, Kc);
   return hipGetLastError();
 }
 
-hipError_t launch_head_fwd(int dt, const void* a, const float* wfc, const float* bfc, const int32_t* labels,
-                           float* g, float* dlogits, float* loss_accum, int b, int hw, int C, int classes,
-                           float divisor, hipStream_t stream) {
+hipError_t launch_head_fwd(int dt, int ng, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& labels,
+                           const PtrTab& gp, const PtrTab& dlogits, float* loss_accum, int b, int hw, int C,
+                           int classes, float divisor, hipStream_t stream) {
   const size_t lds = (size_t)(C + classes) * sizeof(float);
+  const dim3 grid((unsigned)b, 1, (unsigned)ng);
   if (dt == DT_BF16)
-    k_head_fwd<bf16_t><<<b, 256, lds, stream>>>((const bf16_t*)a, wfc, bfc, labels, g, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
+    k_head_fwd<bf16_t><<<grid, 256, lds, stream>>>(a, wfc, bfc, labels, gp, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
   else
-    k_head_fwd<float><<<b, 256, lds, stream>>>((const float*)a, wfc, bfc, labels, g, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
+    k_head_fwd<float><<<grid, 256, lds, stream>>>(a, wfc, bfc, labels, gp, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
   return hipGetLastError();
 }
 
-hipError_t launch_head_bwd(int dt, const float* g, const float* dlogits, const float* wfc, float* g_wfc,
-                           float* g_bfc, void* da, int b, int hw, int C, int classes, hipStream_t stream) {
+hipError_t launch_head_bwd(int dt, int ng, const PtrTab& gp, const PtrTab& dlogits, const float* wfc, float* g_wfc,
+                           float* g_bfc, const PtrTab& da, int b, int hw, int C, int classes, hipStream_t stream) {
   const size_t lds = (size_t)(C + classes) * sizeof(float);
+  const dim3 grid((unsigned)b, 1, (unsigned)ng);
   if (dt == DT_BF16)
-    k_head_bwd<bf16_t><<<b, 256, lds, stream>>>(g, dlogits, wfc, g_wfc, g_bfc, (bf16_t*)da, hw, C, classes);
+    k_head_bwd<bf16_t><<<grid, 256, lds, stream>>>(gp, dlogits, wfc, g_wfc, g_bfc, da, hw, C, classes);
   else
-    k_head_bwd<float><<<b, 256, lds, stream>>>(g, dlogits, wfc, g_wfc, g_bfc, (float*)da, hw, C, classes);
+    k_head_bwd<float><<<grid, 256, lds, stream>>>(gp, dlogits, wfc, g_wfc, g_bfc, da, hw, C, classes);
   return hipGetLastError();
 }
 

@@ -25,8 +25,9 @@ constexpr int MC = 128;         // pixel rows per step (32 per wave)
 constexpr int LSTR = MC + 8;    // LDS row stride in bf16 (272 bytes)
 
 template <int BC, int BN>
-__global__ __launch_bounds__(256) void k_wgrad_mfma(const bf16_t* __restrict__ a, const bf16_t* __restrict__ dy,
-                                                    float* dw, WgradGeom g, int rows_per_split) {
+__global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float* dw, WgradGeom g, int rows_per_split) {
+  const bf16_t* __restrict__ a = (const bf16_t*)as.p[blockIdx.z];
+  const bf16_t* __restrict__ dy = (const bf16_t*)dys.p[blockIdx.z];
   constexpr int CTL = BC / 16, NTL = BN / 16;
   constexpr int A_UNITS = (64 * (BC / 8) + 255) / 256;
   constexpr int D_UNITS = (64 * (BN / 8) + 255) / 256;
@@ -156,33 +157,33 @@ __global__ __launch_bounds__(256) void k_wgrad_mfma(const bf16_t* __restrict__ a
 }
 
 template <int BC, int BN>
-hipError_t launch_tile(const bf16_t* a, const bf16_t* dy, float* dw, const WgradGeom& g, hipStream_t stream) {
+hipError_t launch_tile(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
   const int tiles = g.R * g.R * (g.Cin / BC) * (g.N / BN);
   const int max_splits = (g.M + MC - 1) / MC;
-  int splits = (512 + tiles - 1) / tiles;
+  int splits = (512 + tiles * ng - 1) / (tiles * ng);
   if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;
   int rows = (g.M + splits - 1) / splits;
   rows = (rows + MC - 1) / MC * MC;
   splits = (g.M + rows - 1) / rows;
-  k_wgrad_mfma<BC, BN><<<dim3((unsigned)splits, (unsigned)tiles), 256, 0, stream>>>(a, dy, dw, g, rows);
+  k_wgrad_mfma<BC, BN><<<dim3((unsigned)splits, (unsigned)tiles, (unsigned)ng), 256, 0, stream>>>(a, dy, dw, g, rows);
   return hipGetLastError();
 }
 
 template <int BC>
-hipError_t pick_bn(const bf16_t* a, const bf16_t* dy, float* dw, const WgradGeom& g, hipStream_t stream) {
-  if (g.N % 64 == 0) return launch_tile<BC, 64>(a, dy, dw, g, stream);
-  if (g.N % 32 == 0) return launch_tile<BC, 32>(a, dy, dw, g, stream);
-  return launch_tile<BC, 16>(a, dy, dw, g, stream);
+hipError_t pick_bn(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
+  if (g.N % 64 == 0) return launch_tile<BC, 64>(ng, a, dy, dw, g, stream);
+  if (g.N % 32 == 0) return launch_tile<BC, 32>(ng, a, dy, dw, g, stream);
+  return launch_tile<BC, 16>(ng, a, dy, dw, g, stream);
 }
 
 }  // namespace
 
-hipError_t launch_wgrad_mfma(const bf16_t* a, const bf16_t* dy, float* dw, const WgradGeom& g, hipStream_t stream) {
-  if (g.Cin % 16 != 0 || g.N % 16 != 0) return hipErrorInvalidValue;
-  if (g.Cin % 64 == 0) return pick_bn<64>(a, dy, dw, g, stream);
-  if (g.Cin % 32 == 0) return pick_bn<32>(a, dy, dw, g, stream);
-  return pick_bn<16>(a, dy, dw, g, stream);
+hipError_t launch_wgrad_mfma(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
+  if (ng < 1 || ng > MAX_GROUP || g.Cin % 16 != 0 || g.N % 16 != 0) return hipErrorInvalidValue;
+  if (g.Cin % 64 == 0) return pick_bn<64>(ng, a, dy, dw, g, stream);
+  if (g.Cin % 32 == 0) return pick_bn<32>(ng, a, dy, dw, g, stream);
+  return pick_bn<16>(ng, a, dy, dw, g, stream);
 }
 
 }  // namespace hpf

@@ -57,6 +57,8 @@ def _load():
     L.hpf_partition_create.argtypes = [C.POINTER(hpf_partition_desc), vp, sz, vp, C.POINTER(vp)]
     L.hpf_forward_microbatch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.hpf_backward_microbatch.argtypes = [vp, i32, vp, vp, vp]
+    L.hpf_forward_microbatches.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    L.hpf_backward_microbatches.argtypes = [vp, i32, i32, vp, vp, vp]
     L.hpf_grad_accum_read.argtypes = [vp, vp, sz, i32, vp]
     L.hpf_grad_accum_zero.argtypes = [vp, vp]
     L.hpf_sgd_step.argtypes = [vp, C.c_float, C.c_float, vp]
@@ -77,6 +79,7 @@ def _load():
 lib = _load()
 
 EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatch", "hpf_backward_microbatch",
+           "hpf_forward_microbatches", "hpf_backward_microbatches",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
            "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
@@ -126,6 +129,24 @@ def hpf_forward_microbatch(handle, mb, act_in, labels, act_out, loss_accum, stre
 
 def hpf_backward_microbatch(handle, mb, err_in, err_out, stream=0):
     _check(lib.hpf_backward_microbatch(handle, mb, err_in or None, err_out or None, stream or None))
+
+
+def _ptr_array(ptrs):
+    """(host) array of device pointers from a list of ints; None -> NULL array."""
+    if ptrs is None:
+        return None
+    return (C.c_void_p * len(ptrs))(*[p or None for p in ptrs])
+
+
+def hpf_forward_microbatches(handle, mb_first, act_in, labels, act_out, loss_accum, stream=0):
+    """act_in / labels / act_out: lists of device addresses (labels or act_out may be None)."""
+    a, l, o = _ptr_array(act_in), _ptr_array(labels), _ptr_array(act_out)
+    _check(lib.hpf_forward_microbatches(handle, mb_first, len(act_in), a, l, o, loss_accum or None, stream or None))
+
+
+def hpf_backward_microbatches(handle, mb_first, count, err_in, err_out, stream=0):
+    e, o = _ptr_array(err_in), _ptr_array(err_out)
+    _check(lib.hpf_backward_microbatches(handle, mb_first, count, e, o, stream or None))
 
 
 def hpf_grad_accum_read(handle, dst, n_floats, dst_is_device, stream=0):
@@ -325,6 +346,40 @@ class Partition:
             assert tuple(err_out.shape) == self.in_shape and err_out.dtype == self.tdtype and err_out.is_contiguous()
         hpf_backward_microbatch(self.handle, mb, err_in.data_ptr() if err_in is not None else 0,
                                 err_out.data_ptr() if err_out is not None else 0, self._stream_or_current(stream))
+        return err_out
+
+    def forward_microbatches(self, mb_first, act_in, labels=None, act_out=None, stream=None):
+        """Group call: lists of tensors for micro-batches mb_first, mb_first+1, ..."""
+        n = len(act_in)
+        for t in act_in:
+            assert tuple(t.shape) == self.in_shape and t.dtype == self.in_dtype and t.is_contiguous()
+        if self.spec.has_head:
+            assert labels is not None and len(labels) == n
+        else:
+            if act_out is None:
+                act_out = [self.torch.empty(self.out_shape, dtype=self.tdtype, device=self.device) for _ in range(n)]
+            for t in act_out:
+                assert tuple(t.shape) == self.out_shape and t.dtype == self.tdtype and t.is_contiguous()
+        hpf_forward_microbatches(self.handle, mb_first, [t.data_ptr() for t in act_in],
+                                 [t.data_ptr() for t in labels] if labels is not None else None,
+                                 [t.data_ptr() for t in act_out] if act_out is not None else None,
+                                 self.loss.data_ptr() if self.spec.has_head else 0, self._stream_or_current(stream))
+        return act_out
+
+    def backward_microbatches(self, mb_first, count, err_in=None, err_out=None, stream=None):
+        if not self.spec.has_head:
+            assert len(err_in) == count
+            for t in err_in:
+                assert tuple(t.shape) == self.out_shape and t.dtype == self.tdtype and t.is_contiguous()
+        if not self.spec.has_stem:
+            if err_out is None:
+                err_out = [self.torch.empty(self.in_shape, dtype=self.tdtype, device=self.device) for _ in range(count)]
+            for t in err_out:
+                assert tuple(t.shape) == self.in_shape and t.dtype == self.tdtype and t.is_contiguous()
+        hpf_backward_microbatches(self.handle, mb_first, count,
+                                  [t.data_ptr() for t in err_in] if err_in is not None else None,
+                                  [t.data_ptr() for t in err_out] if err_out is not None else None,
+                                  self._stream_or_current(stream))
         return err_out
 
     def grad_accum_read(self, out=None, stream=None):

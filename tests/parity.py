@@ -32,7 +32,7 @@ def device_inputs(spec, inp: W.StepInputs, mode: str):
     return seen, t
 
 
-def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=None, part=None, keep=False):
+def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=None, part=None, keep=False, grouped=False):
     import torch
     from paper_1911_05146_amd import hpf
     seen, t = device_inputs(spec, inp, mode)
@@ -45,11 +45,17 @@ def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=Non
     part.loss.zero_()
     torch.cuda.synchronize()
     outs, errs = [], []
-    for i in range(m):
-        outs.append(part.forward_microbatch(i, t["act_in"][i], t["labels"][i] if t["labels"] else None,
-                                            stream=streams[i]))
-    for i in range(m):
-        errs.append(part.backward_microbatch(i, t["err_in"][i] if t["err_in"] else None, stream=streams[i]))
+    if grouped:          # all micro-batches of the batch in one call per direction
+        gs = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        outs = part.forward_microbatches(0, t["act_in"], t["labels"], stream=gs) or [None] * m
+        errs = part.backward_microbatches(0, m, t["err_in"], stream=gs) or [None] * m
+    else:
+        for i in range(m):
+            outs.append(part.forward_microbatch(i, t["act_in"][i], t["labels"][i] if t["labels"] else None,
+                                                stream=streams[i]))
+        for i in range(m):
+            errs.append(part.backward_microbatch(i, t["err_in"][i] if t["err_in"] else None, stream=streams[i]))
     grad = part.grad_accum_read()
     torch.cuda.synchronize()
     res = {

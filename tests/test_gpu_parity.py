@@ -26,7 +26,7 @@ def to64(inp):
 
 
 def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=True, strict=False, beta_shift=0.0,
-          seeds=1):
+          seeds=1, grouped=False):
     """GPU batch vs the oracle in the same precision reading (criterion A), falling back -- unless
     strict -- to the sensitivity-limited criterion B against the oracle in double (see parity.compare).
     seeds > 1 (strict bf16 cases only): a pre-activation within bf16 rounding of 0 may fall on either
@@ -36,14 +36,14 @@ def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=Tru
     for attempt in range(seeds):
         try:
             return check_once(oracle, replace(spec, seed=spec.seed + 1000 * attempt), mode, multi_stream, sgd,
-                              randomize_affine, strict, beta_shift)
+                              randomize_affine, strict, beta_shift, grouped)
         except AssertionError as e:
             if attempt == seeds - 1:
                 raise
             print(f"[retry] {spec.name}: {str(e)[:200]}", flush=True)
 
 
-def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift):
+def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False):
     from parity import compare, fmt, run_gpu_step
     print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream} seed={spec.seed}", flush=True)
     inp = W.make_inputs(spec, randomize_affine=randomize_affine)
@@ -51,7 +51,7 @@ def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, 
         for e in W.param_layout(spec):
             if e.kind == "beta":
                 inp.params[e.offset:e.offset + e.size] += beta_shift
-    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd)
+    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd, grouped=grouped)
     yard = oracle.run_step(spec, seen, np.float32, sgd=sgd, storage="bf16" if mode == "bf16" else "none")
     rep = compare(spec, res, yard, mode, ref64=lambda: oracle.run_step(spec, to64(seen), np.float64, sgd=sgd), strict=strict)
     print(f"[parity] {spec.name} {mode}: " + fmt(rep), flush=True)
@@ -133,8 +133,29 @@ def test_resnet1001_partition_two_microbatches(gpu, oracle, mode):
 
 
 def test_resnet1001_partition_full_batch_on_streams(gpu, oracle):
-    """The benchmark's launch configuration: 8 micro-batches of 32, one stream each."""
+    """8 micro-batches of 32, one stream each."""
     check(oracle, W.config(3), "bf16", multi_stream=True, randomize_affine=False)
+
+
+def test_resnet1001_partition_full_batch_grouped(gpu, oracle):
+    """The benchmark's launch configuration: the 8 micro-batches of 32 issued as one group."""
+    check(oracle, W.config(3), "bf16", grouped=True, randomize_affine=False)
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_grouped_calls_equal_single_calls(gpu, oracle, mode):
+    """A group call is the same work as single calls: bit-identical activations and errors."""
+    from parity import rel_err, run_gpu_step
+    for spec in (W.resnet20(microbatch=4, num_microbatches=3), W.resnet110_partition(p=2, microbatch=4, num_microbatches=8),
+                 W.resnet110_partition(p=1, microbatch=2, num_microbatches=11)):     # 11 > 8: two groups
+        inp = W.make_inputs(spec, randomize_affine=True)
+        _, a = run_gpu_step(spec, inp, mode)
+        _, b = run_gpu_step(spec, inp, mode, grouped=True)
+        for x, y in zip(a["act_out"] + a["err_out"], b["act_out"] + b["err_out"]):
+            assert (x is None and y is None) or np.array_equal(x, y)
+        assert abs(a["loss"] - b["loss"]) <= 1e-6 * abs(a["loss"]) + 1e-12
+        assert rel_err(b["grad"], a["grad"]) < 1e-5
+    check(oracle, W.resnet20(microbatch=4, num_microbatches=2), mode, grouped=True, sgd=(0.1, 0.9), strict=(mode == "f32"))
 
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
