@@ -158,6 +158,11 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
  * stream that is itself being captured by the caller always get plain launches. */
 hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
 
+/* bf16 mode computes the BatchNorm reductions (forward statistics, backward dbeta/dgamma sums) in
+ * the epilogue of the convolution that produces the tensor, instead of separate passes over it.
+ * enable == 0 switches to the separate kernels (same arithmetic, other summation order); default on. */
+hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable);
+
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
 

@@ -54,9 +54,26 @@ struct PackDesc {
   int T, Cin, Cout, Kf, Kd;
 };
 
+// Optional reduction fused into the convolution epilogue (the output tile is still in registers):
+//   EPI_STATS : statistics partial records {K, S1, S2, n} of the stored output, one record row per
+//               pixel-row tile and channel, for the BatchNorm that consumes this output;
+//   EPI_BNBWD : the output is the gradient da w.r.t. a BN+ReLU output: it is masked with the ReLU
+//               decision recomputed from the BN input x (dz = da*[z>0], stored instead of da) and the
+//               partial sums {sum dz, sum dz*xhat} are written, one row per pixel-row tile.
+enum : int { EPI_NONE = 0, EPI_STATS = 1, EPI_BNBWD = 2 };
+struct ConvEpi {
+  int kind = EPI_NONE;
+  PtrTab partials{};        // EPI_STATS: 4 floats, EPI_BNBWD: 2 floats per (tile row, channel)
+  PtrTab x{};               // EPI_BNBWD: BN input [M, N] bf16
+  PtrTab stats{};           // EPI_BNBWD: {mean(N), invstd(N)} float
+  const float* gamma = nullptr;
+  const float* beta = nullptr;
+};
+int conv_mfma_tile_rows(int g, const ConvGeom& geom);   // pixel rows per tile the launcher will use
+
 // g = number of group members (grid z); tables hold g valid pointers.  `add` tables may be all-null.
 hipError_t launch_conv_mfma(int mode, int g, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                            const ConvGeom& geom, hipStream_t stream);
+                            const ConvGeom& geom, hipStream_t stream, const ConvEpi& epi = ConvEpi());
 hipError_t launch_wgrad_mfma(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);
 
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
@@ -70,6 +87,11 @@ hipError_t launch_wgrad_f32(int g, const PtrTab& a, const PtrTab& dy, float* dw,
 size_t bn_partials_floats(int C);
 hipError_t launch_bn_stats(int dt, int g, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
                            const PtrTab& partials, hipStream_t stream);
+// Finalize steps alone, for partial records written by a convolution epilogue (nrows record rows).
+hipError_t launch_bn_stats_finalize(int g, int M, int C, int nrows, float eps, const PtrTab& partials, const PtrTab& stats,
+                                    hipStream_t stream);
+hipError_t launch_bn_bwd_finalize(int g, int C, int nrows, const PtrTab& partials, const PtrTab& sums, float* g_gamma,
+                                  float* g_beta, hipStream_t stream);
 hipError_t launch_bn_apply_relu(int dt, int g, const PtrTab& x, const PtrTab& a, const float* gamma, const float* beta,
                                 const PtrTab& stats, int M, int C, hipStream_t stream);
 // sums of each micro-batch; also atomically added into g_gamma / g_beta (fp32 gradient buffer).

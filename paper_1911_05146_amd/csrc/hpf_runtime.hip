@@ -187,7 +187,13 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   const size_t b_ = (size_t)d.microbatch;
   auto alloc = [&](size_t bytes) { Loc l; l.kind = IN_MB; l.off = mo; mo += align_up(bytes); return l; };
   auto tensor = [&](size_t elems) { if (elems > max_elems) max_elems = elems; return alloc(elems * P.esz); };
-  auto stats = [&](BnPlan& bn) { bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(double)).off; if (bn.C > max_c) max_c = bn.C; };
+  size_t max_tile_part = 0;   // floats: partial records written by convolution epilogues (64-row tiles)
+  auto stats = [&](BnPlan& bn, size_t M) {
+    bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(double)).off;
+    if (bn.C > max_c) max_c = bn.C;
+    const size_t need = ((M + 63) / 64) * (size_t)bn.C * 4;
+    if (need > max_tile_part) max_tile_part = need;
+  };
 
   P.act_in_elems = b_ * d.in_h * d.in_w * d.in_c;
   P.act_out_elems = d.has_head ? 0 : b_ * P.out_h * P.out_w * P.out_c;
@@ -206,10 +212,10 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
     p.x_in = cur;
-    stats(p.bn[0]); p.a[0] = tensor(M_in * p.d.c_in);
+    stats(p.bn[0], M_in); p.a[0] = tensor(M_in * p.d.c_in);
     for (int j = 1; j < p.nconv; ++j) {
       p.c[j - 1] = tensor(M_out * p.cv[j - 1].cout);
-      stats(p.bn[j]); p.a[j] = tensor(M_out * p.cv[j].cin);
+      stats(p.bn[j], M_out); p.a[j] = tensor(M_out * p.cv[j].cin);
     }
     const bool last = (i == d.n_blocks - 1);
     if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
@@ -218,7 +224,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   }
   if (d.has_head) {
     P.head_x = cur;
-    stats(P.head_bn);
+    stats(P.head_bn, b_ * P.out_h * P.out_w);
     P.head_a = tensor(b_ * P.out_h * P.out_w * P.out_c);
     P.head_g = alloc(b_ * P.out_c * sizeof(float));
     P.head_dl = alloc(b_ * d.num_classes * sizeof(float));
@@ -227,7 +233,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.max_elems = max_elems; P.max_c = max_c;
   if (max_c > 0) {
     P.sums_off = alloc(2 * (size_t)max_c * sizeof(double)).off;
-    P.partials_off = alloc(bn_partials_floats(max_c) * sizeof(float)).off;
+    const size_t pf = bn_partials_floats(max_c) > max_tile_part ? bn_partials_floats(max_c) : max_tile_part;
+    P.partials_off = alloc(pf * sizeof(float)).off;
   }
   P.tickets_off = alloc(64 * sizeof(unsigned)).off;
   for (int i = 0; i < 4; ++i) P.scratch_off[i] = alloc(max_elems * P.esz).off;
@@ -257,6 +264,7 @@ struct GraphSlot {
 struct hpf_partition {
   Plan P;
   bool use_graphs = true;
+  bool fuse = true;   // bf16 mode: BN reductions in the convolution epilogues
   std::vector<GraphSlot> g_fwd, g_bwd;
   char* arena = nullptr;
   std::vector<unsigned char> fwd_done, bwd_done;
@@ -302,21 +310,33 @@ struct Ctx {
   static PtrTab none() { return PtrTab{}; }
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
 
-  void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M) {
+  bool fused() const { return h->fuse && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
+
+  // part_rows > 0: the producing convolution already wrote that many statistics partial rows.
+  void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M, int part_rows = 0) {
     const Plan& P = h->P;
     const PtrTab st = mbp(bn.stats_off);
-    if (P.d.bn_mode == 0)
-      chk(launch_bn_stats(P.dt, g, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), s), "bn_stats");
-    else
+    if (P.d.bn_mode != 0)
       chk(launch_bn_frozen_stats(P.dt, g, st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
+    else if (part_rows > 0)
+      chk(launch_bn_stats_finalize(g, (int)M, bn.C, part_rows, P.d.bn_eps, mbp(P.partials_off), st, s), "bn_stats_finalize");
+    else
+      chk(launch_bn_stats(P.dt, g, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), s), "bn_stats");
     chk(launch_bn_apply_relu(P.dt, g, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
   }
-  void bn_bwd(const BnPlan& bn, const PtrTab& x, const PtrTab& da, const PtrTab& skip, const PtrTab& dx, size_t M) {
+  // part_rows > 0: `da` already holds dz and the producing data-gradient wrote that many partial rows.
+  void bn_bwd(const BnPlan& bn, const PtrTab& x, const PtrTab& da, const PtrTab& skip, const PtrTab& dx, size_t M,
+              int part_rows = 0) {
     const Plan& P = h->P;
     const PtrTab st = mbp(bn.stats_off);
-    chk(launch_bn_bwd_reduce(P.dt, g, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbp(P.sums_off),
-                             h->grads() + bn.g_off, h->grads() + bn.b_off, mbp(P.partials_off), s),
-        "bn_bwd_reduce");
+    if (part_rows > 0)
+      chk(launch_bn_bwd_finalize(g, bn.C, part_rows, mbp(P.partials_off), mbp(P.sums_off), h->grads() + bn.g_off,
+                                 h->grads() + bn.b_off, s),
+          "bn_bwd_finalize");
+    else
+      chk(launch_bn_bwd_reduce(P.dt, g, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, mbp(P.sums_off),
+                               h->grads() + bn.g_off, h->grads() + bn.b_off, mbp(P.partials_off), s),
+          "bn_bwd_reduce");
     chk(launch_bn_bwd_apply(P.dt, g, x, da, h->params() + bn.g_off, h->params() + bn.b_off, st, mbp(P.sums_off), skip, dx, (int)M,
                             bn.C, P.d.bn_mode, s),
         "bn_bwd_apply");
@@ -333,19 +353,41 @@ struct Ctx {
     q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cout; q.Kpad = cv.Kd;
     return q;
   }
-  void conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add) {
+  // want_stats: the output feeds a BatchNorm; returns the number of partial rows written (0 = none).
+  int conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add, bool want_stats = false) {
     const ConvGeom q = geom_fwd(cv);
-    if (h->P.dt == DT_BF16)
-      chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s), "conv_fwd");
-    else
-      chk(launch_conv_f32(CONV_FWD, g, x, h->params() + cv.w_off, y, add, q, s), "conv_fwd_f32");
+    if (h->P.dt == DT_BF16) {
+      ConvEpi epi;
+      int rows = 0;
+      if (want_stats && fused()) {
+        epi.kind = EPI_STATS; epi.partials = mbp(h->P.partials_off);
+        const int bm = conv_mfma_tile_rows(g, q);
+        rows = (q.M + bm - 1) / bm;
+      }
+      chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi), "conv_fwd");
+      return rows;
+    }
+    chk(launch_conv_f32(CONV_FWD, g, x, h->params() + cv.w_off, y, add, q, s), "conv_fwd_f32");
+    return 0;
   }
-  void conv_dgrad(const ConvPlan& cv, const PtrTab& dy, const PtrTab& dx, const PtrTab& add) {
+  // bn / bn_x: the BatchNorm (and its stashed input) whose backward consumes dx; returns partial rows.
+  int conv_dgrad(const ConvPlan& cv, const PtrTab& dy, const PtrTab& dx, const PtrTab& add, const BnPlan* bn = nullptr,
+                 const PtrTab* bn_x = nullptr) {
     const ConvGeom q = geom_dgrad(cv);
-    if (h->P.dt == DT_BF16)
-      chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s), "conv_dgrad");
-    else
-      chk(launch_conv_f32(CONV_DGRAD, g, dy, h->params() + cv.w_off, dx, add, q, s), "conv_dgrad_f32");
+    if (h->P.dt == DT_BF16) {
+      ConvEpi epi;
+      int rows = 0;
+      if (bn && fused()) {
+        epi.kind = EPI_BNBWD; epi.partials = mbp(h->P.partials_off); epi.x = *bn_x; epi.stats = mbp(bn->stats_off);
+        epi.gamma = h->params() + bn->g_off; epi.beta = h->params() + bn->b_off;
+        const int bm = conv_mfma_tile_rows(g, q);
+        rows = (q.M + bm - 1) / bm;
+      }
+      chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s, epi), "conv_dgrad");
+      return rows;
+    }
+    chk(launch_conv_f32(CONV_DGRAD, g, dy, h->params() + cv.w_off, dx, add, q, s), "conv_dgrad_f32");
+    return 0;
   }
   void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {
     WgradGeom q{};
@@ -361,35 +403,37 @@ struct Ctx {
 void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
+  int part_rows = 0;   // statistics partial rows pending for the next BatchNorm (written by the last conv)
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
+    const bool feeds_bn = !P.bp.empty() || P.d.has_head;
     if (P.dt == DT_BF16) {
       const PtrTab col = c.tab(P.stem_col);
       c.chk(launch_im2col3x3(c.g, c.tab(in), col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
-      ConvPlan cv = P.stem; cv.R = 1; cv.cin = P.stem_kc;
-      ConvGeom q = c.geom_fwd(cv);
-      q.Ktot = P.stem_kc; q.Kpad = P.stem.Kf;
-      c.chk(launch_conv_mfma(CONV_FWD, c.g, col, c.h->packed() + P.stem.wf_off, c.tab(P.stem_out), Ctx::none(), q, c.s), "stem_conv");
+      ConvPlan cv = P.stem; cv.R = 1; cv.cin = P.stem_kc;   // 1x1 convolution over the im2col columns
+      part_rows = c.conv_fwd(cv, col, c.tab(P.stem_out), Ctx::none(), feeds_bn);
     } else {
       c.conv_fwd(P.stem, c.tab(in), c.tab(P.stem_out), Ctx::none());
     }
   }
-  for (const BlockPlan& p : P.bp) {
+  for (size_t bi = 0; bi < P.bp.size(); ++bi) {
+    const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
-    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in);
+    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows);
     if (p.proj) c.conv_fwd(p.pj, c.tab(p.a[0]), y, Ctx::none());
     const PtrTab shortcut = p.proj ? y : x;
     for (int j = 0; j < p.nconv; ++j) {
       const bool last = (j == p.nconv - 1);
       const PtrTab out = last ? y : c.tab(p.c[j]);
-      c.conv_fwd(p.cv[j], c.tab(p.a[j]), out, last ? shortcut : Ctx::none());
-      if (!last) c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out);
+      const bool feeds_bn = !last || bi + 1 < P.bp.size() || P.d.has_head;
+      part_rows = c.conv_fwd(p.cv[j], c.tab(p.a[j]), out, last ? shortcut : Ctx::none(), feeds_bn);
+      if (!last) c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows);
     }
   }
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
-    c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M);
+    c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M, part_rows);
     c.chk(launch_head_fwd(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
                           c.tab(P.head_g), c.tab(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes,
                           (float)P.d.loss_divisor, c.s),
@@ -420,21 +464,23 @@ void run_backward(Ctx& c) {
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     PtrTab dr = dy;
     for (int j = p.nconv - 1; j >= 1; --j) {
+      const PtrTab xj = c.tab(p.c[j - 1]);
       c.conv_wgrad(p.cv[j], c.tab(p.a[j]), dr);
-      c.conv_dgrad(p.cv[j], dr, tA, Ctx::none());
-      c.bn_bwd(p.bn[j], c.tab(p.c[j - 1]), tA, Ctx::none(), tB, M_out);
+      const int rows = c.conv_dgrad(p.cv[j], dr, tA, Ctx::none(), &p.bn[j], &xj);
+      c.bn_bwd(p.bn[j], xj, tA, Ctx::none(), tB, M_out, rows);
       dr = tB;
     }
+    const PtrTab x0 = c.tab(p.x_in);
     c.conv_wgrad(p.cv[0], c.tab(p.a[0]), dr);
-    c.conv_dgrad(p.cv[0], dr, tA, Ctx::none());
-    if (p.proj) {
+    if (p.proj) {   // a = relu(bn1(x)) feeds the branch and the projection: the two data-gradients add
       c.conv_wgrad(p.pj, c.tab(p.a[0]), dy);
-      c.conv_dgrad(p.pj, dy, tA, tA);
+      c.conv_dgrad(p.pj, dy, tA, Ctx::none());
     }
+    const int rows0 = c.conv_dgrad(p.cv[0], dr, tA, p.proj ? tA : Ctx::none(), &p.bn[0], &x0);
     PtrTab dx; int nxt;
     if (ii == 0 && !P.d.has_stem) { dx = c.tab(lout); nxt = -1; }
     else { nxt = (cur == 0) ? 1 : 0; dx = c.scratch(nxt); }
-    c.bn_bwd(p.bn[0], c.tab(p.x_in), tA, p.proj ? Ctx::none() : dy, dx, M_in);
+    c.bn_bwd(p.bn[0], x0, tA, p.proj ? Ctx::none() : dy, dx, M_in, rows0);
     dy = dx; cur = nxt;
   }
   if (P.d.has_stem) {
@@ -721,6 +767,16 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
 hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   p->use_graphs = enable != 0;
+  return HPF_OK;
+}
+
+hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (p->fuse != (enable != 0)) {   // cached graphs hold the other kernel sequence
+    for (GraphSlot& g : p->g_fwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+    for (GraphSlot& g : p->g_bwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+  }
+  p->fuse = enable != 0;
   return HPF_OK;
 }
 

@@ -120,6 +120,7 @@ __device__ __forceinline__ bool reduce_partials(const A* partials, int C, unsign
   A a1 = 0, a2 = 0;
   if (j < jn) {
     const A* p = partials + ((size_t)(c_base + cl)) * 2;
+#pragma unroll 8
     for (unsigned bx = j; bx < nblocks; bx += jn) {
       a1 += p[(size_t)bx * C * 2];
       a2 += p[(size_t)bx * C * 2 + 1];
@@ -134,20 +135,24 @@ __device__ __forceinline__ bool reduce_partials(const A* partials, int C, unsign
   return true;
 }
 
+// Statistics partial of one block of rows (or one convolution output tile), per channel:
+// {K, S1 = sum(v - K), S2 = sum((v - K)^2), n} with the shift K = the block's first row.  The
+// shifted sums avoid the cancellation of the plain sum-of-squares form; blocks with different
+// shifts are merged exactly (pairwise update of count / mean / sum of squared deviations).
 template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(PtrTab xs, int M, int C, int rows_per_block, PtrTab parts) {
   const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
   A* __restrict__ partials = (A*)parts.p[blockIdx.z];
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
-  A s[16];
+  A s[16], k[8];
 #pragma unroll
   for (int j = 0; j < 16; ++j) s[j] = 0;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(M, r0 + rows_per_block);
   if (m.active) {
-    A k[8], v[8];
-    load8t(x + m.c0, k);  // shift: first row
-    const int r0 = blockIdx.x * rows_per_block;
-    const int r1 = min(M, r0 + rows_per_block);
+    A v[8];
+    load8t(x + (size_t)r0 * C + m.c0, k);  // shift: first row of this block
     for (int r = r0 + m.rl; r < r1; r += m.rpp) {
       load8t(x + (size_t)r * C + m.c0, v);
 #pragma unroll
@@ -160,30 +165,55 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(PtrTab xs, int M, int C
   }
   block_reduce16(s, m, C, sh);
   if (m.active && m.rl == 0) {
-    A* p = partials + ((size_t)blockIdx.x * C + m.c0) * 2;
+    A* p = partials + ((size_t)blockIdx.x * C + m.c0) * 4;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { p[2 * j] = s[j]; p[2 * j + 1] = s[8 + j]; }
+    for (int j = 0; j < 8; ++j) { p[4 * j] = k[j]; p[4 * j + 1] = s[j]; p[4 * j + 2] = s[8 + j]; p[4 * j + 3] = (A)(r1 - r0); }
   }
 }
 
-// grid (1, ceil(C/256)): statistics from the nblocks partials.
-template <class T, class A>
-__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(PtrTab xs, int M, int C, unsigned nblocks, float eps,
-                                                                  PtrTab parts, PtrTab statss) {
-  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
+template <class A>
+struct Moments { A n, mean, m2; };
+
+template <class A>
+__device__ __forceinline__ void merge_moments(Moments<A>& a, A nb, A meanb, A m2b) {
+  if (nb <= 0) return;
+  if (a.n <= 0) { a.n = nb; a.mean = meanb; a.m2 = m2b; return; }
+  const A n = a.n + nb, d = meanb - a.mean;
+  a.mean += d * (nb / n);
+  a.m2 += m2b + d * d * (a.n * nb / n);
+  a.n = n;
+}
+
+// grid (1, ceil(C/256), g): statistics from the nblocks partial records, merged in a fixed order.
+template <class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(int M, int C, unsigned nblocks, float eps, PtrTab parts,
+                                                                  PtrTab statss) {
   const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
   A* __restrict__ stats = (A*)statss.p[blockIdx.z];
-  __shared__ A sh[2][BN_THREADS];
-  A s1, s2;
-  if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    const A inv_m = (A)1 / (A)M;
-    const A d = s1 * inv_m;
-    A var = s2 * inv_m - d * d;
-    var = var > 0 ? var : 0;
-    stats[c] = (A)to_f32(x[c]) + d;
-    stats[C + c] = rsqrt_exact(var + (A)eps);
+  __shared__ A sh[3][BN_THREADS];
+  const int c_base = blockIdx.y * 256;
+  const int cw = min(256, C - c_base);
+  const int jn = BN_THREADS / cw;
+  const int cl = threadIdx.x % cw, j = threadIdx.x / cw;
+  Moments<A> mo{0, 0, 0};
+  if (j < jn) {
+    const A* p = partials + ((size_t)(c_base + cl)) * 4;
+#pragma unroll 4
+    for (unsigned bx = j; bx < nblocks; bx += jn) {
+      const A* q = p + (size_t)bx * C * 4;
+      const A k = q[0], s1 = q[1], s2 = q[2], n = q[3];
+      if (n > 0) merge_moments(mo, n, k + s1 / n, s2 - s1 * s1 / n);
+    }
   }
+  sh[0][threadIdx.x] = mo.n; sh[1][threadIdx.x] = mo.mean; sh[2][threadIdx.x] = mo.m2;
+  __syncthreads();
+  if (j != 0) return;
+  for (int r = 1; r < jn; ++r) merge_moments(mo, sh[0][cl + r * cw], sh[1][cl + r * cw], sh[2][cl + r * cw]);
+  const int c = c_base + cl;
+  A var = mo.m2 / (A)M;
+  var = var > 0 ? var : 0;
+  stats[c] = mo.mean;
+  stats[C + c] = rsqrt_exact(var + (A)eps);
 }
 
 template <class T, class A>
@@ -329,7 +359,7 @@ dim3 apply_grid(int M, int C) {
 
 }  // namespace
 
-size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 2 * 2; }  // sized for double
+size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 4 * 2; }  // 4 values, sized for double
 
 hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
                            const PtrTab& partials, hipStream_t stream) {
@@ -337,11 +367,27 @@ hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float 
   const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin(1, g.grid.y, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bn_stats<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
-    k_bn_stats_finalize<bf16_t, float><<<fin, BN_THREADS, 0, stream>>>(x, M, C, g.grid.x, eps, partials, stats);
+    k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
   } else {
     k_bn_stats<float, double><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
-    k_bn_stats_finalize<float, double><<<fin, BN_THREADS, 0, stream>>>(x, M, C, g.grid.x, eps, partials, stats);
+    k_bn_stats_finalize<double><<<fin, BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
   }
+  return hipGetLastError();
+}
+
+// Finalize only: the partial records were written by a convolution epilogue (one record row per
+// pixel-row tile).  float arithmetic (bf16 mode).
+hipError_t launch_bn_stats_finalize(int ng, int M, int C, int nrows, float eps, const PtrTab& partials, const PtrTab& stats,
+                                    hipStream_t stream) {
+  const dim3 fin(1, (unsigned)((C + 255) / 256), (unsigned)ng);
+  k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, (unsigned)nrows, eps, partials, stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_bwd_finalize(int ng, int C, int nrows, const PtrTab& partials, const PtrTab& sums, float* g_gamma,
+                                  float* g_beta, hipStream_t stream) {
+  const dim3 fin(1, (unsigned)((C + 255) / 256), (unsigned)ng);
+  k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, (unsigned)nrows, partials, sums, g_gamma, g_beta);
   return hipGetLastError();
 }
 

@@ -28,9 +28,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int KC = 32;          // reduction elements per step
 constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-free 16-byte reads)
 
-template <int BM, int BN, int WR, int WC, int MODE>
+template <int BM, int BN, int WR, int WC, int MODE, int EPI>
 __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds,
-                                                   ConvGeom g) {
+                                                   ConvGeom g, ConvEpi epi) {
   const bf16_t* __restrict__ src = (const bf16_t*)srcs.p[blockIdx.z];
   bf16_t* out = (bf16_t*)outs.p[blockIdx.z];
   const bf16_t* add = (const bf16_t*)adds.p[blockIdx.z];
@@ -138,54 +138,184 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
   }
 
   // acc[i][j][v]: channel = ch0 + wc*WCH + i*16 + (lane>>4)*4 + v, pixel row = row0 + wr*WPX + j*16 + (lane&15)
+  // Epilogue scratch in the (now idle) staging LDS: shift per channel and per-wave-row sums.
+  float* sK = reinterpret_cast<float*>(&sA[0][0]);        // [BN]
+  float* sS = sK + BN;                                     // [WR][BN][2]
+  static_assert((BN + WR * BN * 2) * 4 <= (int)sizeof(sA), "epilogue scratch fits the staging buffer");
+  float s1[CT][4], s2[CT][4];
+#pragma unroll
+  for (int i = 0; i < CT; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { s1[i][v] = 0.f; s2[i][v] = 0.f; }
+
 #pragma unroll
   for (int j = 0; j < PT; ++j) {
     const int m = row0 + wr * WPX + j * 16 + (lane & 15);
-    if (m >= g.M) continue;
+    const bool mv = m < g.M;
 #pragma unroll
     for (int i = 0; i < CT; ++i) {
-      const int ch = ch0 + wc * WCH + i * 16 + (lane >> 4) * 4;
-      const size_t o = (size_t)m * g.N + ch;
-      float v0 = acc[i][j][0], v1 = acc[i][j][1], v2 = acc[i][j][2], v3 = acc[i][j][3];
-      if (add) {
+      const int chl = wc * WCH + i * 16 + (lane >> 4) * 4;
+      const int ch = ch0 + chl;
+      const size_t o = (size_t)(mv ? m : 0) * g.N + ch;
+      float vv[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+      if (add && mv) {
         const uint2 t = *reinterpret_cast<const uint2*>(add + o);
-        v0 += __uint_as_float(t.x << 16); v1 += __uint_as_float(t.x & 0xffff0000u);
-        v2 += __uint_as_float(t.y << 16); v3 += __uint_as_float(t.y & 0xffff0000u);
+        vv[0] += __uint_as_float(t.x << 16); vv[1] += __uint_as_float(t.x & 0xffff0000u);
+        vv[2] += __uint_as_float(t.y << 16); vv[3] += __uint_as_float(t.y & 0xffff0000u);
       }
       uint2 st;
-      st.x = pack_bf16x2(v0, v1);
-      st.y = pack_bf16x2(v2, v3);
-      *reinterpret_cast<uint2*>(out + o) = st;
+      st.x = pack_bf16x2(vv[0], vv[1]);
+      st.y = pack_bf16x2(vv[2], vv[3]);
+      if (EPI != EPI_NONE) {   // continue with the values as stored
+        vv[0] = __uint_as_float(st.x << 16); vv[1] = __uint_as_float(st.x & 0xffff0000u);
+        vv[2] = __uint_as_float(st.y << 16); vv[3] = __uint_as_float(st.y & 0xffff0000u);
+      }
+      if (EPI == EPI_BNBWD) {
+        if (mv) {
+          const bf16_t* xt = (const bf16_t*)epi.x.p[blockIdx.z];
+          const float* stt = (const float*)epi.stats.p[blockIdx.z];
+          const uint2 xr = *reinterpret_cast<const uint2*>(xt + o);
+          const float xv[4] = {__uint_as_float(xr.x << 16), __uint_as_float(xr.x & 0xffff0000u),
+                               __uint_as_float(xr.y << 16), __uint_as_float(xr.y & 0xffff0000u)};
+          const float4 mu = *reinterpret_cast<const float4*>(stt + ch);
+          const float4 is = *reinterpret_cast<const float4*>(stt + g.N + ch);
+          const float4 ga = *reinterpret_cast<const float4*>(epi.gamma + ch);
+          const float4 be = *reinterpret_cast<const float4*>(epi.beta + ch);
+          const float mu_[4] = {mu.x, mu.y, mu.z, mu.w}, is_[4] = {is.x, is.y, is.z, is.w};
+          const float ga_[4] = {ga.x, ga.y, ga.z, ga.w}, be_[4] = {be.x, be.y, be.z, be.w};
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float xh = (xv[v] - mu_[v]) * is_[v];
+            const float z = ga_[v] * xh + be_[v];
+            const float dz = z > 0.f ? vv[v] : 0.f;
+            vv[v] = dz;
+            s1[i][v] += dz;
+            s2[i][v] += dz * xh;
+          }
+          st.x = pack_bf16x2(vv[0], vv[1]);   // exact: dz is a stored value or 0
+          st.y = pack_bf16x2(vv[2], vv[3]);
+        }
+      }
+      if (EPI == EPI_STATS) {
+        if (j == 0 && wr == 0 && (lane & 15) == 0) {   // the tile's first row gives the shift
+#pragma unroll
+          for (int v = 0; v < 4; ++v) sK[chl + v] = vv[v];
+        }
+        // keep the stored values for the second pass over the registers
+        acc[i][j][0] = vv[0]; acc[i][j][1] = vv[1]; acc[i][j][2] = vv[2]; acc[i][j][3] = vv[3];
+      }
+      if (mv) *reinterpret_cast<uint2*>(out + o) = st;
+    }
+  }
+  if (EPI == EPI_NONE) return;
+
+  if (EPI == EPI_STATS) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+      const int chl = wc * WCH + i * 16 + (lane >> 4) * 4;
+      const float4 k4 = *reinterpret_cast<const float4*>(sK + chl);
+      const float k_[4] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+      for (int j = 0; j < PT; ++j) {
+        const int m = row0 + wr * WPX + j * 16 + (lane & 15);
+        if (m < g.M) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float d = acc[i][j][v] - k_[v];
+            s1[i][v] += d;
+            s2[i][v] += d * d;
+          }
+        }
+      }
+    }
+  }
+  // sum over the 16 pixel lanes of each lane group, then over the wave rows through LDS (fixed order)
+#pragma unroll
+  for (int i = 0; i < CT; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) {
+        s1[i][v] += __shfl_xor(s1[i][v], o);
+        s2[i][v] += __shfl_xor(s2[i][v], o);
+      }
+    }
+  if ((lane & 15) == 0) {
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+      const int chl = wc * WCH + i * 16 + (lane >> 4) * 4;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        sS[(wr * BN + chl + v) * 2] = s1[i][v];
+        sS[(wr * BN + chl + v) * 2 + 1] = s2[i][v];
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < BN) {
+    float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+    for (int w = 0; w < WR; ++w) { a1 += sS[(w * BN + tid) * 2]; a2 += sS[(w * BN + tid) * 2 + 1]; }
+    float* part = (float*)epi.partials.p[blockIdx.z];
+    if (EPI == EPI_STATS) {
+      const int nrows = min(BM, g.M - row0);
+      *reinterpret_cast<float4*>(part + ((size_t)blockIdx.x * g.N + ch0 + tid) * 4) = make_float4(sK[tid], a1, a2, (float)nrows);
+    } else {
+      *reinterpret_cast<float2*>(part + ((size_t)blockIdx.x * g.N + ch0 + tid) * 2) = make_float2(a1, a2);
     }
   }
 }
 
 template <int BM, int BN, int WR, int WC>
 hipError_t launch_tile(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                       const ConvGeom& g, hipStream_t stream) {
+                       const ConvGeom& g, hipStream_t stream, const ConvEpi& epi) {
   const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN), (unsigned)ng);
-  if (mode == CONV_FWD)
-    k_conv_mfma<BM, BN, WR, WC, CONV_FWD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g);
-  else
-    k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g);
+  if (mode == CONV_FWD) {
+    if (epi.kind == EPI_STATS)
+      k_conv_mfma<BM, BN, WR, WC, CONV_FWD, EPI_STATS><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
+    else if (epi.kind == EPI_NONE)
+      k_conv_mfma<BM, BN, WR, WC, CONV_FWD, EPI_NONE><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
+    else
+      return hipErrorInvalidValue;
+  } else {
+    if (epi.kind == EPI_BNBWD)
+      k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD, EPI_BNBWD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
+    else if (epi.kind == EPI_NONE)
+      k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD, EPI_NONE><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
+    else
+      return hipErrorInvalidValue;
+  }
   return hipGetLastError();
+}
+
+// 0: 128x128, 1: 64x64, 2: 64x32, 3: 64x16
+int pick_tile(int ng, const ConvGeom& g) {
+  if (g.N % 128 == 0) {
+    const long wgs = (long)((g.M + 127) / 128) * (g.N / 128) * ng;
+    if (wgs >= 192) return 0;
+  }
+  if (g.N % 64 == 0) return 1;
+  if (g.N % 32 == 0) return 2;
+  return 3;
 }
 
 }  // namespace
 
+int conv_mfma_tile_rows(int ng, const ConvGeom& g) { return pick_tile(ng, g) == 0 ? 128 : 64; }
+
 // Tile choice: the widest channel tile that divides N, then the pixel tile that still gives the
 // chip (256 CUs) enough work-groups.
 hipError_t launch_conv_mfma(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                            const ConvGeom& g, hipStream_t stream) {
+                            const ConvGeom& g, hipStream_t stream, const ConvEpi& epi) {
   if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
   if (g.N % 16 != 0 || g.Cs % 8 != 0 || g.Kpad % KC != 0 || (g.stride != 1 && g.stride != 2)) return hipErrorInvalidValue;
-  if (g.N % 128 == 0) {
-    const long wgs = (long)((g.M + 127) / 128) * (g.N / 128) * ng;
-    if (wgs >= 192) return launch_tile<128, 128, 2, 2>(mode, ng, src, wpk, out, add, g, stream);
+  switch (pick_tile(ng, g)) {
+    case 0: return launch_tile<128, 128, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi);
+    case 1: return launch_tile<64, 64, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi);
+    case 2: return launch_tile<64, 32, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi);
+    default: return launch_tile<64, 16, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi);
   }
-  if (g.N % 64 == 0) return launch_tile<64, 64, 2, 2>(mode, ng, src, wpk, out, add, g, stream);
-  if (g.N % 32 == 0) return launch_tile<64, 32, 4, 1>(mode, ng, src, wpk, out, add, g, stream);
-  return launch_tile<64, 16, 4, 1>(mode, ng, src, wpk, out, add, g, stream);
 }
 
 }  // namespace hpf

@@ -66,6 +66,7 @@ def _load():
     L.hpf_partition_destroy.argtypes = [vp]
     L.hpf_partition_destroy.restype = None
     L.hpf_partition_set_graphs.argtypes = [vp, i32]
+    L.hpf_partition_set_fusion.argtypes = [vp, i32]
     L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
     L.hpf_op_workspace_bytes.restype = sz
     L.hpf_op_conv_forward.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, i32, vp]
@@ -81,7 +82,8 @@ lib = _load()
 EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatch", "hpf_backward_microbatch",
            "hpf_forward_microbatches", "hpf_backward_microbatches",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
-           "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
+           "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_partition_set_fusion",
+           "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
 
 
@@ -167,6 +169,10 @@ def hpf_params_read(handle, host_dst, n_floats):
 
 def hpf_partition_set_graphs(handle, enable):
     _check(lib.hpf_partition_set_graphs(handle, int(enable)))
+
+
+def hpf_partition_set_fusion(handle, enable):
+    _check(lib.hpf_partition_set_fusion(handle, int(enable)))
 
 
 def hpf_partition_destroy(handle):
@@ -401,6 +407,9 @@ class Partition:
 
     def set_graphs(self, enable):
         hpf_partition_set_graphs(self.handle, enable)
+
+    def set_fusion(self, enable):
+        hpf_partition_set_fusion(self.handle, enable)
 
     def params_read(self):
         import numpy as np

