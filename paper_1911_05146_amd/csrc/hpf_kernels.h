@@ -76,6 +76,23 @@ hipError_t launch_conv_mfma(int mode, int g, const PtrTab& src, const bf16_t* wp
                             const ConvGeom& geom, hipStream_t stream, const ConvEpi& epi = ConvEpi());
 hipError_t launch_wgrad_mfma(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);
 
+// All weight gradients of a backward pass in one launch per tile class.  An item is one (convolution,
+// filter tap, BC x BN output tile, slice of pixel rows); the work-group that takes it loops over the
+// group's micro-batches, so one atomic add per output element and item reaches the gradient buffer.
+// a / dy live at byte offsets in each member's arena region (dy_off == WGRAD_DY_CALLER: the caller's
+// err_in buffer of that member).
+constexpr unsigned long long WGRAD_DY_CALLER = ~0ull;
+struct WgradItem {
+  unsigned long long a_off, dy_off, dw_off;   // bytes, bytes, floats
+  WgradGeom g;
+  int tap, c0, n0, m_begin, m_end;
+};
+// tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}
+int wgrad_tile_class(int cin, int cout);
+void wgrad_tile_dims(int tile_class, int* bc, int* bn);
+hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
+                                const PtrTab& caller_dy, float* grads, hipStream_t stream);
+
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);
 hipError_t launch_wgrad_f32(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);

@@ -53,6 +53,8 @@ struct BlockPlan {
   bool proj = false;
   BnPlan bn[3]; ConvPlan cv[3]; ConvPlan pj;
   Loc x_in, a[3], c[2], y;
+  Loc gy;      // gradient w.r.t. the block output (kept until the deferred weight-gradient pass)
+  Loc dc[2];   // gradient w.r.t. c[j], the output of conv j (j < nconv-1)
 };
 
 struct Plan {
@@ -74,6 +76,9 @@ struct Plan {
   // global regions (bytes from arena base)
   size_t params_off = 0, grads_off = 0, mom_off = 0, packed_off = 0, table_off = 0, mb_off = 0;
   size_t packed_elems = 0; int n_convs = 0;
+  Loc g_stem;                          // gradient w.r.t. the stem output
+  std::vector<WgradItem> items[9];     // deferred weight-gradient work, per tile class (bf16 mode)
+  size_t items_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
   std::vector<PackDesc> table;
@@ -229,6 +234,19 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     P.head_g = alloc(b_ * P.out_c * sizeof(float));
     P.head_dl = alloc(b_ * d.num_classes * sizeof(float));
   }
+  // gradient tensors: every gradient that a weight-gradient consumes keeps its own buffer, so that all
+  // weight gradients of the pass can run as one grouped launch after the data-gradient chain
+  if (d.has_stem) {
+    if (d.n_blocks > 0 || d.has_head) P.g_stem = tensor(b_ * d.in_h * d.in_w * d.stem_c_out);
+    else P.g_stem.kind = CALLER_ERR_IN;
+  }
+  for (int i = 0; i < d.n_blocks; ++i) {
+    BlockPlan& p = P.bp[i];
+    const size_t M_out = b_ * p.h_out * p.w_out;
+    const bool last = (i == d.n_blocks - 1);
+    if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
+    for (int j = 0; j + 1 < p.nconv; ++j) p.dc[j] = tensor(M_out * p.cv[j].cout);
+  }
   P.stash_bytes_per_mb = mo;
   P.max_elems = max_elems; P.max_c = max_c;
   if (max_c > 0) {
@@ -240,6 +258,41 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   for (int i = 0; i < 4; ++i) P.scratch_off[i] = alloc(max_elems * P.esz).off;
   P.mb_bytes = mo;
 
+  // ---- deferred weight-gradient items (bf16 mode)
+  if (P.dt == DT_BF16) {
+    auto add_items = [&](const ConvPlan& cv, int cin_run, int c_valid, int R, const Loc& a, const Loc& dy) {
+      WgradGeom q{};
+      q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
+      q.R = R; q.stride = cv.stride; q.pad = (R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = c_valid;
+      const int cls = wgrad_tile_class(cin_run, cv.cout);
+      int bc, bn;
+      wgrad_tile_dims(cls, &bc, &bn);
+      const int rows_target = 2048;
+      int splits = (q.M + rows_target - 1) / rows_target;
+      int rows = ((q.M + splits - 1) / splits + 127) / 128 * 128;
+      splits = (q.M + rows - 1) / rows;
+      for (int tap = 0; tap < R * R; ++tap)
+        for (int c0 = 0; c0 < cin_run; c0 += bc)
+          for (int n0 = 0; n0 < cv.cout; n0 += bn)
+            for (int sp = 0; sp < splits; ++sp) {
+              WgradItem it{};
+              it.a_off = a.off;
+              it.dy_off = dy.kind == IN_MB ? dy.off : WGRAD_DY_CALLER;
+              it.dw_off = cv.w_off;
+              it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
+              it.m_begin = sp * rows; it.m_end = (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M;
+              P.items[cls].push_back(it);
+            }
+    };
+    if (d.has_stem) add_items(P.stem, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem);
+    for (int i = 0; i < d.n_blocks; ++i) {
+      const BlockPlan& p = P.bp[i];
+      for (int j = 0; j < p.nconv; ++j)
+        add_items(p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.a[j], j == p.nconv - 1 ? p.gy : p.dc[j]);
+      if (p.proj) add_items(p.pj, p.pj.cin, p.pj.cin, 1, p.a[0], p.gy);
+    }
+  }
+
   // ---- global regions
   size_t g = 0;
   P.params_off = g; g += align_up(P.n_params * sizeof(float));
@@ -247,6 +300,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.mom_off = g;    g += align_up(P.n_params * sizeof(float));
   P.packed_off = g; g += align_up(P.packed_elems * 2);
   P.table_off = g;  g += align_up(P.table.size() * sizeof(PackDesc));
+  for (int k = 0; k < 9; ++k) { P.items_off[k] = g; g += align_up(P.items[k].size() * sizeof(WgradItem)); }
   P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
   P.arena_bytes = g;
   return HPF_OK;
@@ -444,58 +498,56 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
 void run_backward(Ctx& c) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
-  const PtrTab tA = c.scratch(2), tB = c.scratch(3);
-  Loc lin; lin.kind = CALLER_ERR_IN;
+  const bool deferred = (P.dt == DT_BF16);   // weight gradients after the data-gradient chain, one grouped launch
+  const PtrTab tA = c.scratch(2);
   Loc lout; lout.kind = CALLER_ERR_OUT;
-  PtrTab dy = c.tab(lin);
-  int cur = -1;  // which ping-pong scratch holds dy: -1 = a caller buffer
+  // where the gradient w.r.t. the input of block `i` (= output of block i-1 / the stem) goes
+  auto grad_in_loc = [&](size_t i) -> Loc {
+    if (i > 0) return P.bp[i - 1].gy;
+    return P.d.has_stem ? P.g_stem : lout;
+  };
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
     c.chk(launch_head_bwd(P.dt, c.g, c.tab(P.head_g), c.tab(P.head_dl), c.h->params() + P.wfc_off, c.h->grads() + P.wfc_off,
                           c.h->grads() + P.bfc_off, tA, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes, c.s),
           "head_bwd");
-    const bool to_caller = (P.bp.empty() && !P.d.has_stem);
-    const PtrTab dx = to_caller ? c.tab(lout) : c.scratch(0);
-    c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), dx, M);
-    dy = dx; cur = to_caller ? -1 : 0;
+    c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
+    const PtrTab dy = c.tab(p.gy);
     PtrTab dr = dy;
     for (int j = p.nconv - 1; j >= 1; --j) {
       const PtrTab xj = c.tab(p.c[j - 1]);
-      c.conv_wgrad(p.cv[j], c.tab(p.a[j]), dr);
+      if (!deferred) c.conv_wgrad(p.cv[j], c.tab(p.a[j]), dr);
       const int rows = c.conv_dgrad(p.cv[j], dr, tA, Ctx::none(), &p.bn[j], &xj);
-      c.bn_bwd(p.bn[j], xj, tA, Ctx::none(), tB, M_out, rows);
-      dr = tB;
+      const PtrTab dcj = c.tab(p.dc[j - 1]);
+      c.bn_bwd(p.bn[j], xj, tA, Ctx::none(), dcj, M_out, rows);
+      dr = dcj;
     }
     const PtrTab x0 = c.tab(p.x_in);
-    c.conv_wgrad(p.cv[0], c.tab(p.a[0]), dr);
+    if (!deferred) c.conv_wgrad(p.cv[0], c.tab(p.a[0]), dr);
     if (p.proj) {   // a = relu(bn1(x)) feeds the branch and the projection: the two data-gradients add
-      c.conv_wgrad(p.pj, c.tab(p.a[0]), dy);
+      if (!deferred) c.conv_wgrad(p.pj, c.tab(p.a[0]), dy);
       c.conv_dgrad(p.pj, dy, tA, Ctx::none());
     }
     const int rows0 = c.conv_dgrad(p.cv[0], dr, tA, p.proj ? tA : Ctx::none(), &p.bn[0], &x0);
-    PtrTab dx; int nxt;
-    if (ii == 0 && !P.d.has_stem) { dx = c.tab(lout); nxt = -1; }
-    else { nxt = (cur == 0) ? 1 : 0; dx = c.scratch(nxt); }
-    c.bn_bwd(p.bn[0], x0, tA, p.proj ? Ctx::none() : dy, dx, M_in, rows0);
-    dy = dx; cur = nxt;
+    c.bn_bwd(p.bn[0], x0, tA, p.proj ? Ctx::none() : dy, c.tab(grad_in_loc(ii)), M_in, rows0);
   }
-  if (P.d.has_stem) {
-    if (P.dt == DT_BF16) {
-      WgradGeom q{};
-      q.b = (int)b; q.H = P.d.in_h; q.W = P.d.in_w; q.Cin = P.stem_kc; q.Ho = q.H; q.Wo = q.W; q.N = P.d.stem_c_out;
-      q.R = 1; q.stride = 1; q.pad = 0; q.M = q.b * q.H * q.W; q.c_valid = 9 * P.d.in_c;
-      c.chk(launch_wgrad_mfma(c.g, c.tab(P.stem_col), dy, c.h->grads() + P.stem.w_off, q, c.s), "stem_wgrad");
-    } else {
-      Loc in; in.kind = CALLER_ACT_IN;
-      c.conv_wgrad(P.stem, c.tab(in), dy);
-    }
+  if (P.d.has_stem && !deferred) {
+    Loc in; in.kind = CALLER_ACT_IN;
+    c.conv_wgrad(P.stem, c.tab(in), c.tab(P.g_stem));
+  }
+  if (deferred) {
+    PtrTab bases{}, caller{};
+    for (int i = 0; i < c.g; ++i) { bases.p[i] = c.h->mb_base(c.mb0 + i); caller.p[i] = const_cast<void*>(c.err_in[i]); }
+    for (int k = 0; k < 9; ++k)
+      c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + P.items_off[k]), (int)P.items[k].size(), bases, caller,
+                                 c.h->grads(), c.s),
+            "wgrad_grouped");
   }
 }
-
 
 bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_microbatches; }
 
@@ -593,6 +645,9 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     ok(hipMemcpy(p->arena + P.table_off, P.table.data(), P.table.size() * sizeof(PackDesc), hipMemcpyHostToDevice));
     ok(launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, nullptr));
   }
+  for (int k = 0; k < 9; ++k)
+    if (!P.items[k].empty())
+      ok(hipMemcpy(p->arena + P.items_off[k], P.items[k].data(), P.items[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
   p->ev_fwd.resize(m); p->ev_bwd.resize(m);
   for (int i = 0; i < m; ++i) {
     ok(hipEventCreateWithFlags(&p->ev_fwd[i], hipEventDisableTiming));

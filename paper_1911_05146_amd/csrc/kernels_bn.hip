@@ -107,34 +107,6 @@ __device__ __forceinline__ void block_reduce16(A (&s)[16], const BnMap& m, int C
   }
 }
 
-// Sum of the per-block partials of channel `c` (this slice's channels are c_base .. c_base+255):
-// the 256 threads split into (channel, row-group) pairs, every pair adds a strided subset of the
-// blocks' partials, then the row-groups of a channel are added in order through LDS.  The order of
-// the additions is fixed.
-template <class A>
-__device__ __forceinline__ bool reduce_partials(const A* partials, int C, unsigned nblocks, A (*sh)[BN_THREADS], A& s1, A& s2) {
-  const int c_base = blockIdx.y * 256;
-  const int cw = min(256, C - c_base);          // channels in this slice
-  int jn = BN_THREADS / cw;                     // row-groups
-  const int cl = threadIdx.x % cw, j = threadIdx.x / cw;
-  A a1 = 0, a2 = 0;
-  if (j < jn) {
-    const A* p = partials + ((size_t)(c_base + cl)) * 2;
-#pragma unroll 8
-    for (unsigned bx = j; bx < nblocks; bx += jn) {
-      a1 += p[(size_t)bx * C * 2];
-      a2 += p[(size_t)bx * C * 2 + 1];
-    }
-  }
-  sh[0][threadIdx.x] = a1;
-  sh[1][threadIdx.x] = a2;
-  __syncthreads();
-  if (j != 0) return false;
-  s1 = a1; s2 = a2;
-  for (int r = 1; r < jn; ++r) { s1 += sh[0][cl + r * cw]; s2 += sh[1][cl + r * cw]; }
-  return true;
-}
-
 // Statistics partial of one block of rows (or one convolution output tile), per channel:
 // {K, S1 = sum(v - K), S2 = sum((v - K)^2), n} with the shift K = the block's first row.  The
 // shifted sums avoid the cancellation of the plain sum-of-squares form; blocks with different
@@ -171,49 +143,62 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(PtrTab xs, int M, int C
   }
 }
 
-template <class A>
-struct Moments { A n, mean, m2; };
+// Finalize: block = 32 channels x 8 row-groups, grid (ceil(C/32), 1, g).  Two passes over the records
+// (the second hits the cache): first the mean from the tile sums, then the sum of squared deviations
+// about that mean, M2 = sum_t [S2_t - S1_t^2/n_t + n_t (mean_t - mean)^2].  All additions are
+// independent (no serial merge chain) and their order is fixed: strided partial sums per row-group,
+// then the 8 row-groups in order through LDS.
+constexpr int FIN_CH = 32, FIN_RG = BN_THREADS / FIN_CH;
 
 template <class A>
-__device__ __forceinline__ void merge_moments(Moments<A>& a, A nb, A meanb, A m2b) {
-  if (nb <= 0) return;
-  if (a.n <= 0) { a.n = nb; a.mean = meanb; a.m2 = m2b; return; }
-  const A n = a.n + nb, d = meanb - a.mean;
-  a.mean += d * (nb / n);
-  a.m2 += m2b + d * d * (a.n * nb / n);
-  a.n = n;
+__device__ __forceinline__ A fin_sum(A v, A (*sh)[FIN_CH], int cl, int j) {
+  __syncthreads();
+  sh[j][cl] = v;
+  __syncthreads();
+  A t = sh[0][cl];
+#pragma unroll
+  for (int r = 1; r < FIN_RG; ++r) t += sh[r][cl];
+  return t;
 }
 
-// grid (1, ceil(C/256), g): statistics from the nblocks partial records, merged in a fixed order.
 template <class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(int M, int C, unsigned nblocks, float eps, PtrTab parts,
                                                                   PtrTab statss) {
   const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
   A* __restrict__ stats = (A*)statss.p[blockIdx.z];
-  __shared__ A sh[3][BN_THREADS];
-  const int c_base = blockIdx.y * 256;
-  const int cw = min(256, C - c_base);
-  const int jn = BN_THREADS / cw;
-  const int cl = threadIdx.x % cw, j = threadIdx.x / cw;
-  Moments<A> mo{0, 0, 0};
-  if (j < jn) {
-    const A* p = partials + ((size_t)(c_base + cl)) * 4;
+  __shared__ A sh[FIN_RG][FIN_CH];
+  const int cl = threadIdx.x % FIN_CH, j = threadIdx.x / FIN_CH;
+  const int c = blockIdx.x * FIN_CH + cl;
+  const bool cv = c < C;
+  const A* p = partials + (size_t)(cv ? c : 0) * 4;
+  A tot = 0;
+  if (cv) {
 #pragma unroll 4
-    for (unsigned bx = j; bx < nblocks; bx += jn) {
+    for (unsigned bx = j; bx < nblocks; bx += FIN_RG) {
       const A* q = p + (size_t)bx * C * 4;
-      const A k = q[0], s1 = q[1], s2 = q[2], n = q[3];
-      if (n > 0) merge_moments(mo, n, k + s1 / n, s2 - s1 * s1 / n);
+      tot += q[3] * q[0] + q[1];                 // n*K + S1 = sum of the tile's values
     }
   }
-  sh[0][threadIdx.x] = mo.n; sh[1][threadIdx.x] = mo.mean; sh[2][threadIdx.x] = mo.m2;
-  __syncthreads();
-  if (j != 0) return;
-  for (int r = 1; r < jn; ++r) merge_moments(mo, sh[0][cl + r * cw], sh[1][cl + r * cw], sh[2][cl + r * cw]);
-  const int c = c_base + cl;
-  A var = mo.m2 / (A)M;
-  var = var > 0 ? var : 0;
-  stats[c] = mo.mean;
-  stats[C + c] = rsqrt_exact(var + (A)eps);
+  const A mean = fin_sum(tot, sh, cl, j) / (A)M;
+  A m2 = 0;
+  if (cv) {
+#pragma unroll 4
+    for (unsigned bx = j; bx < nblocks; bx += FIN_RG) {
+      const A* q = p + (size_t)bx * C * 4;
+      const A n = q[3];
+      if (n > 0) {
+        const A s1n = q[1] / n, d = q[0] + s1n - mean;
+        m2 += q[2] - q[1] * s1n + n * d * d;
+      }
+    }
+  }
+  m2 = fin_sum(m2, sh, cl, j);
+  if (cv && j == 0) {
+    A var = m2 / (A)M;
+    var = var > 0 ? var : 0;
+    stats[c] = mean;
+    stats[C + c] = rsqrt_exact(var + (A)eps);
+  }
 }
 
 template <class T, class A>
@@ -277,21 +262,33 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(PtrTab xs, PtrTab 
   }
 }
 
-// grid (1, ceil(C/256)): dbeta / dgamma of this micro-batch from the partials; also added into the
+// grid (ceil(C/32), 1, g): dbeta / dgamma of each micro-batch from the partials; also added into the
 // gradient buffer shared by all micro-batches.
 template <class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned nblocks, PtrTab parts, PtrTab sumss,
                                                                 float* g_gamma, float* g_beta) {
   const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
   A* __restrict__ sums = (A*)sumss.p[blockIdx.z];
-  __shared__ A sh[2][BN_THREADS];
-  A s1, s2;
-  if (reduce_partials(partials, C, nblocks, sh, s1, s2)) {
-    const int c = blockIdx.y * 256 + threadIdx.x;
-    sums[c] = s1;
-    sums[C + c] = s2;
-    atomicAdd(&g_beta[c], (float)s1);
-    atomicAdd(&g_gamma[c], (float)s2);
+  __shared__ A sh[FIN_RG][FIN_CH];
+  const int cl = threadIdx.x % FIN_CH, j = threadIdx.x / FIN_CH;
+  const int c = blockIdx.x * FIN_CH + cl;
+  const bool cv = c < C;
+  const A* p = partials + (size_t)(cv ? c : 0) * 2;
+  A a1 = 0, a2 = 0;
+  if (cv) {
+#pragma unroll 8
+    for (unsigned bx = j; bx < nblocks; bx += FIN_RG) {
+      a1 += p[(size_t)bx * C * 2];
+      a2 += p[(size_t)bx * C * 2 + 1];
+    }
+  }
+  a1 = fin_sum(a1, sh, cl, j);
+  a2 = fin_sum(a2, sh, cl, j);
+  if (cv && j == 0) {
+    sums[c] = a1;
+    sums[C + c] = a2;
+    atomicAdd(&g_beta[c], (float)a1);
+    atomicAdd(&g_gamma[c], (float)a2);
   }
 }
 
@@ -364,7 +361,7 @@ size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 4 * 2;
 hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
                            const PtrTab& partials, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin(1, g.grid.y, (unsigned)ng);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bn_stats<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
     k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
@@ -379,14 +376,14 @@ hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float 
 // pixel-row tile).  float arithmetic (bf16 mode).
 hipError_t launch_bn_stats_finalize(int ng, int M, int C, int nrows, float eps, const PtrTab& partials, const PtrTab& stats,
                                     hipStream_t stream) {
-  const dim3 fin(1, (unsigned)((C + 255) / 256), (unsigned)ng);
+  const dim3 fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, (unsigned)nrows, eps, partials, stats);
   return hipGetLastError();
 }
 
 hipError_t launch_bn_bwd_finalize(int ng, int C, int nrows, const PtrTab& partials, const PtrTab& sums, float* g_gamma,
                                   float* g_beta, hipStream_t stream) {
-  const dim3 fin(1, (unsigned)((C + 255) / 256), (unsigned)ng);
+  const dim3 fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, (unsigned)nrows, partials, sums, g_gamma, g_beta);
   return hipGetLastError();
 }
@@ -406,7 +403,7 @@ hipError_t launch_bn_bwd_reduce(int dt, int ng, const PtrTab& x, const PtrTab& d
                                 const PtrTab& stats, int M, int C, const PtrTab& sums, float* g_gamma, float* g_beta,
                                 const PtrTab& partials, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
-  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin(1, g.grid.y, (unsigned)ng);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bn_bwd_reduce<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, M, C, g.rows_per_block, partials);
     k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);

@@ -148,6 +148,24 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
 #pragma unroll
     for (int v = 0; v < 4; ++v) { s1[i][v] = 0.f; s2[i][v] = 0.f; }
 
+  // per-channel BN constants of this lane's channels (EPI_BNBWD), loaded once
+  float mu_[CT][4], is_[CT][4], ga_[CT][4], be_[CT][4];
+  if (EPI == EPI_BNBWD) {
+    const float* stt = (const float*)epi.stats.p[blockIdx.z];
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+      const int ch = ch0 + wc * WCH + i * 16 + (lane >> 4) * 4;
+      const float4 mu = *reinterpret_cast<const float4*>(stt + ch);
+      const float4 is = *reinterpret_cast<const float4*>(stt + g.N + ch);
+      const float4 ga = *reinterpret_cast<const float4*>(epi.gamma + ch);
+      const float4 be = *reinterpret_cast<const float4*>(epi.beta + ch);
+      mu_[i][0] = mu.x; mu_[i][1] = mu.y; mu_[i][2] = mu.z; mu_[i][3] = mu.w;
+      is_[i][0] = is.x; is_[i][1] = is.y; is_[i][2] = is.z; is_[i][3] = is.w;
+      ga_[i][0] = ga.x; ga_[i][1] = ga.y; ga_[i][2] = ga.z; ga_[i][3] = ga.w;
+      be_[i][0] = be.x; be_[i][1] = be.y; be_[i][2] = be.z; be_[i][3] = be.w;
+    }
+  }
+
 #pragma unroll
   for (int j = 0; j < PT; ++j) {
     const int m = row0 + wr * WPX + j * 16 + (lane & 15);
@@ -173,20 +191,13 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
       if (EPI == EPI_BNBWD) {
         if (mv) {
           const bf16_t* xt = (const bf16_t*)epi.x.p[blockIdx.z];
-          const float* stt = (const float*)epi.stats.p[blockIdx.z];
           const uint2 xr = *reinterpret_cast<const uint2*>(xt + o);
           const float xv[4] = {__uint_as_float(xr.x << 16), __uint_as_float(xr.x & 0xffff0000u),
                                __uint_as_float(xr.y << 16), __uint_as_float(xr.y & 0xffff0000u)};
-          const float4 mu = *reinterpret_cast<const float4*>(stt + ch);
-          const float4 is = *reinterpret_cast<const float4*>(stt + g.N + ch);
-          const float4 ga = *reinterpret_cast<const float4*>(epi.gamma + ch);
-          const float4 be = *reinterpret_cast<const float4*>(epi.beta + ch);
-          const float mu_[4] = {mu.x, mu.y, mu.z, mu.w}, is_[4] = {is.x, is.y, is.z, is.w};
-          const float ga_[4] = {ga.x, ga.y, ga.z, ga.w}, be_[4] = {be.x, be.y, be.z, be.w};
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const float xh = (xv[v] - mu_[v]) * is_[v];
-            const float z = ga_[v] * xh + be_[v];
+            const float xh = (xv[v] - mu_[i][v]) * is_[i][v];
+            const float z = ga_[i][v] * xh + be_[i][v];
             const float dz = z > 0.f ? vv[v] : 0.f;
             vv[v] = dz;
             s1[i][v] += dz;

@@ -25,37 +25,27 @@ constexpr int MC = 128;         // pixel rows per step (32 per wave)
 constexpr int LSTR = MC + 8;    // LDS row stride in bf16 (272 bytes)
 
 template <int BC, int BN>
-__global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float* dw, WgradGeom g, int rows_per_split) {
-  const bf16_t* __restrict__ a = (const bf16_t*)as.p[blockIdx.z];
-  const bf16_t* __restrict__ dy = (const bf16_t*)dys.p[blockIdx.z];
-  constexpr int CTL = BC / 16, NTL = BN / 16;
-  constexpr int A_UNITS = (64 * (BC / 8) + 255) / 256;
-  constexpr int D_UNITS = (64 * (BN / 8) + 255) / 256;
-  constexpr int LDS_A = BC * LSTR, LDS_D = BN * LSTR;
-  constexpr int RED_BYTES = BC * BN * 4;
-  constexpr int OP_BYTES = (LDS_A + LDS_D) * 2;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[OP_BYTES > RED_BYTES ? OP_BYTES : RED_BYTES];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* sD = sA + LDS_A;
-  float* red = reinterpret_cast<float*>(smem);
+struct WgradTile {
+  static constexpr int CTL = BC / 16, NTL = BN / 16;
+  static constexpr int A_UNITS = (64 * (BC / 8) + 255) / 256;
+  static constexpr int D_UNITS = (64 * (BN / 8) + 255) / 256;
+  static constexpr int LDS_A = BC * LSTR, LDS_D = BN * LSTR;
+  static constexpr int RED_BYTES = BC * BN * 4;
+  static constexpr int OP_BYTES = (LDS_A + LDS_D) * 2;
+  static constexpr int SMEM_BYTES = OP_BYTES > RED_BYTES ? OP_BYTES : RED_BYTES;
+};
 
+// Adds sum over rows [m_begin, m_end) of a[row(m,tap), c0..c0+BC) (x) dy[m, n0..n0+BN) into acc
+// (each of the 4 waves holds the sum over its 32-row slices).
+template <int BC, int BN>
+__device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, const bf16_t* __restrict__ dy, const WgradGeom& g,
+                                                 int tap, int c0, int n0, int m_begin, int m_end, bf16_t* sA, bf16_t* sD,
+                                                 floatx4 (&acc)[BC / 16][BN / 16]) {
+  typedef WgradTile<BC, BN> TT;
+  constexpr int CTL = TT::CTL, NTL = TT::NTL, A_UNITS = TT::A_UNITS, D_UNITS = TT::D_UNITS;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n_ct = g.Cin / BC, n_nt = g.N / BN;
-  int tile = blockIdx.y;
-  const int nt = tile % n_nt; tile /= n_nt;
-  const int ct = tile % n_ct; tile /= n_ct;
-  const int tap = tile;
   const int r = tap / g.R, s = tap - r * g.R;
-  const int c0 = ct * BC, n0 = nt * BN;
-  const int m_begin = blockIdx.x * rows_per_split;
-  const int m_end = min(g.M, m_begin + rows_per_split);
   const int HoWo = g.Ho * g.Wo;
-
-  floatx4 acc[CTL][NTL];
-#pragma unroll
-  for (int i = 0; i < CTL; ++i)
-#pragma unroll
-    for (int j = 0; j < NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   uint4 ra[A_UNITS][2], rd[D_UNITS][2];
 
@@ -135,8 +125,14 @@ __global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float
       for (int j = 0; j < NTL; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fd[j], acc[i][j], 0, 0, 0);
   }
+}
 
-  // sum the four waves through LDS, then one atomic per output element
+// Sums the four waves' accumulators through LDS and adds the tile into dw with one atomic per element.
+template <int BC, int BN>
+__device__ __forceinline__ void wgrad_flush(floatx4 (&acc)[BC / 16][BN / 16], float* red, float* dw, const WgradGeom& g, int tap,
+                                            int c0, int n0) {
+  constexpr int CTL = BC / 16, NTL = BN / 16;
+  const int tid = threadIdx.x, lane = tid & 63;
   __syncthreads();
   for (int i = tid; i < BC * BN; i += 256) red[i] = 0.f;
   __syncthreads();
@@ -154,6 +150,52 @@ __global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float
     const int c = c0 + i / BN, n = n0 + i % BN;
     if (c < g.c_valid) atomicAdd(&dw[((size_t)tap * g.c_valid + c) * g.N + n], red[i]);
   }
+}
+
+template <int BC, int BN>
+__global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float* dw, WgradGeom g, int rows_per_split) {
+  typedef WgradTile<BC, BN> TT;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[TT::SMEM_BYTES];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* sD = sA + TT::LDS_A;
+  const int n_ct = g.Cin / BC, n_nt = g.N / BN;
+  int tile = blockIdx.y;
+  const int nt = tile % n_nt; tile /= n_nt;
+  const int ct = tile % n_ct; tile /= n_ct;
+  const int tap = tile;
+  const int m_begin = blockIdx.x * rows_per_split;
+  const int m_end = min(g.M, m_begin + rows_per_split);
+  floatx4 acc[TT::CTL][TT::NTL];
+#pragma unroll
+  for (int i = 0; i < TT::CTL; ++i)
+#pragma unroll
+    for (int j = 0; j < TT::NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  wgrad_accumulate<BC, BN>((const bf16_t*)as.p[blockIdx.z], (const bf16_t*)dys.p[blockIdx.z], g, tap, ct * BC, nt * BN, m_begin,
+                           m_end, sA, sD, acc);
+  wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), dw, g, tap, ct * BC, nt * BN);
+}
+
+// One work-group per item; the micro-batches of the group are accumulated in registers.
+template <int BC, int BN>
+__global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restrict__ items, int ng, PtrTab bases, PtrTab caller_dy,
+                                                       float* grads) {
+  typedef WgradTile<BC, BN> TT;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[TT::SMEM_BYTES];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* sD = sA + TT::LDS_A;
+  const WgradItem it = items[blockIdx.x];
+  floatx4 acc[TT::CTL][TT::NTL];
+#pragma unroll
+  for (int i = 0; i < TT::CTL; ++i)
+#pragma unroll
+    for (int j = 0; j < TT::NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < ng; ++z) {
+    const char* base = (const char*)bases.p[z];
+    const bf16_t* a = (const bf16_t*)(base + it.a_off);
+    const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)caller_dy.p[z] : (const bf16_t*)(base + it.dy_off);
+    wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
+  }
+  wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0);
 }
 
 template <int BC, int BN>
@@ -184,6 +226,40 @@ hipError_t launch_wgrad_mfma(int ng, const PtrTab& a, const PtrTab& dy, float* d
   if (g.Cin % 64 == 0) return pick_bn<64>(ng, a, dy, dw, g, stream);
   if (g.Cin % 32 == 0) return pick_bn<32>(ng, a, dy, dw, g, stream);
   return pick_bn<16>(ng, a, dy, dw, g, stream);
+}
+
+namespace {
+int tile_index(int c) { return c % 64 == 0 ? 2 : (c % 32 == 0 ? 1 : 0); }
+}  // namespace
+
+int wgrad_tile_class(int cin, int cout) { return tile_index(cin) * 3 + tile_index(cout); }
+
+void wgrad_tile_dims(int tile_class, int* bc, int* bn) {
+  static const int sz[3] = {16, 32, 64};
+  *bc = sz[tile_class / 3];
+  *bn = sz[tile_class % 3];
+}
+
+hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
+                                const PtrTab& caller_dy, float* grads, hipStream_t stream) {
+  if (n_items <= 0) return hipSuccess;
+  if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)n_items);
+#define HPF_WG(BC, BN) k_wgrad_grouped<BC, BN><<<grid, 256, 0, stream>>>(items_dev, ng, region_base, caller_dy, grads)
+  switch (tile_class) {
+    case 0: HPF_WG(16, 16); break;
+    case 1: HPF_WG(16, 32); break;
+    case 2: HPF_WG(16, 64); break;
+    case 3: HPF_WG(32, 16); break;
+    case 4: HPF_WG(32, 32); break;
+    case 5: HPF_WG(32, 64); break;
+    case 6: HPF_WG(64, 16); break;
+    case 7: HPF_WG(64, 32); break;
+    case 8: HPF_WG(64, 64); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef HPF_WG
+  return hipGetLastError();
 }
 
 }  // namespace hpf
