@@ -4,6 +4,15 @@
 
 namespace hpf {
 
+// Member z of a pointer table passed by value in the kernel arguments.  A chain of scalar selects:
+// indexing the argument struct with a run-time index would make the compiler copy it to scratch memory.
+__device__ __forceinline__ void* pick(const PtrTab& t, unsigned z) {
+  void* r = t.p[0];
+#pragma unroll
+  for (int i = 1; i < MAX_GROUP; ++i) r = (z == (unsigned)i) ? t.p[i] : r;
+  return r;
+}
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // round-to-nearest-even; NaN stays NaN

@@ -260,36 +260,51 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
   // ---- deferred weight-gradient items (bf16 mode)
   if (P.dt == DT_BF16) {
-    auto add_items = [&](const ConvPlan& cv, int cin_run, int c_valid, int R, const Loc& a, const Loc& dy) {
-      WgradGeom q{};
-      q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
-      q.R = R; q.stride = cv.stride; q.pad = (R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = c_valid;
-      const int cls = wgrad_tile_class(cin_run, cv.cout);
+    struct WConv { const ConvPlan* cv; int cin_run, c_valid, R; Loc a, dy; };
+    std::vector<WConv> wc;
+    ConvPlan stem1x1 = P.stem;
+    if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem});
+    for (int i = 0; i < d.n_blocks; ++i) {
+      const BlockPlan& p = P.bp[i];
+      for (int j = 0; j < p.nconv; ++j)
+        wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.a[j], j == p.nconv - 1 ? p.gy : p.dc[j]});
+      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.a[0], p.gy});
+    }
+    // output tiles per class: the pixel rows are split so that every class launches roughly 1500 work-groups
+    // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
+    long tiles_in_class[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (const WConv& w : wc) {
+      const int cls = wgrad_tile_class(w.cin_run, w.cv->cout);
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
-      const int rows_target = 2048;
-      int splits = (q.M + rows_target - 1) / rows_target;
-      int rows = ((q.M + splits - 1) / splits + 127) / 128 * 128;
+      tiles_in_class[cls] += (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
+    }
+    for (const WConv& w : wc) {
+      const ConvPlan& cv = *w.cv;
+      WgradGeom q{};
+      q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = w.cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
+      q.R = w.R; q.stride = cv.stride; q.pad = (w.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = w.c_valid;
+      const int cls = wgrad_tile_class(w.cin_run, cv.cout);
+      int bc, bn;
+      wgrad_tile_dims(cls, &bc, &bn);
+      int splits = (int)((1536 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
+      const int max_splits = (q.M + 127) / 128;
+      if (splits > max_splits) splits = max_splits;
+      if (splits < 1) splits = 1;
+      const int rows = ((q.M + splits - 1) / splits + 127) / 128 * 128;
       splits = (q.M + rows - 1) / rows;
-      for (int tap = 0; tap < R * R; ++tap)
-        for (int c0 = 0; c0 < cin_run; c0 += bc)
+      for (int tap = 0; tap < w.R * w.R; ++tap)
+        for (int c0 = 0; c0 < w.cin_run; c0 += bc)
           for (int n0 = 0; n0 < cv.cout; n0 += bn)
             for (int sp = 0; sp < splits; ++sp) {
               WgradItem it{};
-              it.a_off = a.off;
-              it.dy_off = dy.kind == IN_MB ? dy.off : WGRAD_DY_CALLER;
+              it.a_off = w.a.off;
+              it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
               it.dw_off = cv.w_off;
               it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
               it.m_begin = sp * rows; it.m_end = (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M;
               P.items[cls].push_back(it);
             }
-    };
-    if (d.has_stem) add_items(P.stem, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem);
-    for (int i = 0; i < d.n_blocks; ++i) {
-      const BlockPlan& p = P.bp[i];
-      for (int j = 0; j < p.nconv; ++j)
-        add_items(p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.a[j], j == p.nconv - 1 ? p.gy : p.dc[j]);
-      if (p.proj) add_items(p.pj, p.pj.cin, p.pj.cin, 1, p.a[0], p.gy);
     }
   }
 

@@ -113,8 +113,8 @@ __device__ __forceinline__ void block_reduce16(A (&s)[16], const BnMap& m, int C
 // shifts are merged exactly (pairwise update of count / mean / sum of squared deviations).
 template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_stats(PtrTab xs, int M, int C, int rows_per_block, PtrTab parts) {
-  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
-  A* __restrict__ partials = (A*)parts.p[blockIdx.z];
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  A* __restrict__ partials = (A*)pick(parts, blockIdx.z);
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16], k[8];
@@ -164,8 +164,8 @@ __device__ __forceinline__ A fin_sum(A v, A (*sh)[FIN_CH], int cl, int j) {
 template <class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(int M, int C, unsigned nblocks, float eps, PtrTab parts,
                                                                   PtrTab statss) {
-  const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
-  A* __restrict__ stats = (A*)statss.p[blockIdx.z];
+  const A* __restrict__ partials = (const A*)pick(parts, blockIdx.z);
+  A* __restrict__ stats = (A*)pick(statss, blockIdx.z);
   __shared__ A sh[FIN_RG][FIN_CH];
   const int cl = threadIdx.x % FIN_CH, j = threadIdx.x / FIN_CH;
   const int c = blockIdx.x * FIN_CH + cl;
@@ -205,9 +205,9 @@ template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_apply_relu(PtrTab xs, PtrTab as, const float* __restrict__ gamma,
                                                               const float* __restrict__ beta, PtrTab statss, int M,
                                                               int C) {
-  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
-  T* __restrict__ a = (T*)as.p[blockIdx.z];
-  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  T* __restrict__ a = (T*)pick(as, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
   const BnMap m = bn_map(C);
   if (!m.active) return;
   A mu[8], is[8], g[8], bt[8], v[8];
@@ -227,10 +227,10 @@ template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(PtrTab xs, PtrTab das, const float* __restrict__ gamma,
                                                               const float* __restrict__ beta, PtrTab statss, int M,
                                                               int C, int rows_per_block, PtrTab parts) {
-  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
-  const T* __restrict__ da = (const T*)das.p[blockIdx.z];
-  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
-  A* __restrict__ partials = (A*)parts.p[blockIdx.z];
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ da = (const T*)pick(das, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
+  A* __restrict__ partials = (A*)pick(parts, blockIdx.z);
   __shared__ A sh[16][BN_THREADS];
   const BnMap m = bn_map(C);
   A s[16];
@@ -267,8 +267,8 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_reduce(PtrTab xs, PtrTab 
 template <class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned nblocks, PtrTab parts, PtrTab sumss,
                                                                 float* g_gamma, float* g_beta) {
-  const A* __restrict__ partials = (const A*)parts.p[blockIdx.z];
-  A* __restrict__ sums = (A*)sumss.p[blockIdx.z];
+  const A* __restrict__ partials = (const A*)pick(parts, blockIdx.z);
+  A* __restrict__ sums = (A*)pick(sumss, blockIdx.z);
   __shared__ A sh[FIN_RG][FIN_CH];
   const int cl = threadIdx.x % FIN_CH, j = threadIdx.x / FIN_CH;
   const int c = blockIdx.x * FIN_CH + cl;
@@ -296,12 +296,12 @@ template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_apply(PtrTab xs, PtrTab das, const float* __restrict__ gamma,
                                                              const float* __restrict__ beta, PtrTab statss, PtrTab sumss,
                                                              PtrTab skips, PtrTab dxs, int M, int C, int frozen) {
-  const T* __restrict__ x = (const T*)xs.p[blockIdx.z];
-  const T* __restrict__ da = (const T*)das.p[blockIdx.z];
-  const A* __restrict__ stats = (const A*)statss.p[blockIdx.z];
-  const A* __restrict__ sums = (const A*)sumss.p[blockIdx.z];
-  const T* skip = (const T*)skips.p[blockIdx.z];
-  T* dx = (T*)dxs.p[blockIdx.z];
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ da = (const T*)pick(das, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
+  const A* __restrict__ sums = (const A*)pick(sumss, blockIdx.z);
+  const T* skip = (const T*)pick(skips, blockIdx.z);
+  T* dx = (T*)pick(dxs, blockIdx.z);
   const BnMap m = bn_map(C);
   if (!m.active) return;
   A mu[8], is[8], g[8], bt[8], sb[8], sg[8], v[8], d[8], k[8];
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_apply(PtrTab xs, PtrTab d
 
 template <class A>
 __global__ void k_bn_frozen_stats(PtrTab statss, int C, float eps) {
-  A* stats = (A*)statss.p[blockIdx.z];
+  A* stats = (A*)pick(statss, blockIdx.z);
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c < C) { stats[c] = 0; stats[C + c] = rsqrt_exact((A)1 + (A)eps); }
 }

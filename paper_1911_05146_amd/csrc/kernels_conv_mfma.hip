@@ -31,9 +31,9 @@ constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-fr
 template <int BM, int BN, int WR, int WC, int MODE, int EPI>
 __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds,
                                                    ConvGeom g, ConvEpi epi) {
-  const bf16_t* __restrict__ src = (const bf16_t*)srcs.p[blockIdx.z];
-  bf16_t* out = (bf16_t*)outs.p[blockIdx.z];
-  const bf16_t* add = (const bf16_t*)adds.p[blockIdx.z];
+  const bf16_t* __restrict__ src = (const bf16_t*)pick(srcs, blockIdx.z);
+  bf16_t* out = (bf16_t*)pick(outs, blockIdx.z);
+  const bf16_t* add = (const bf16_t*)pick(adds, blockIdx.z);
   static_assert(WR * WC == 4, "4 waves");
   constexpr int WPX = BM / WR, WCH = BN / WC, PT = WPX / 16, CT = WCH / 16;
   static_assert(PT >= 1 && CT >= 1, "tile too small");
@@ -66,9 +66,15 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
     else { a_h[u] = p + g.pad; a_w[u] = q + g.pad; }
   }
 
-  uint4 ra[A_UNITS], rw[W_UNITS];
+  // NPRE chunks are kept in flight in registers: at these sizes a work-group lives for a handful of
+  // K steps only, so what matters is how many global loads are outstanding, not the MFMA rate.
+  constexpr int NPRE = 4;
+  struct Slot { uint4 a[A_UNITS]; uint4 w[W_UNITS]; };
+  Slot sl0, sl1, sl2, sl3;   // named, not an array: they must stay in registers
 
-  auto load_chunk = [&](int kc) {
+  auto load_chunk = [&](int kc, Slot& q) {
+    uint4 (&qa)[A_UNITS] = q.a;
+    uint4 (&qw)[W_UNITS] = q.w;
     const int k = kc * KC + grp * 8;
     const int tap = k / g.Cs;
     const int c = k - tap * g.Cs;
@@ -86,24 +92,26 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
         hs = th >> sshift; ws = tw >> sshift;
       }
       v = v && (unsigned)hs < (unsigned)g.Hs && (unsigned)ws < (unsigned)g.Ws;
-      ra[u] = v ? *reinterpret_cast<const uint4*>(src + (size_t)(a_img[u] + hs * g.Ws + ws) * g.Cs + c)
+      qa[u] = v ? *reinterpret_cast<const uint4*>(src + (size_t)(a_img[u] + hs * g.Ws + ws) * g.Cs + c)
                 : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int u = 0; u < W_UNITS; ++u) {
       const int unit = tid + u * 256;
       if (unit < BN * 4)
-        rw[u] = *reinterpret_cast<const uint4*>(wpk + (size_t)(ch0 + (unit >> 2)) * g.Kpad + kc * KC + (unit & 3) * 8);
+        qw[u] = *reinterpret_cast<const uint4*>(wpk + (size_t)(ch0 + (unit >> 2)) * g.Kpad + kc * KC + (unit & 3) * 8);
     }
   };
-  auto store_chunk = [&](int buf) {
+  auto store_chunk = [&](int buf, const Slot& q) {
+    const uint4 (&qa)[A_UNITS] = q.a;
+    const uint4 (&qw)[W_UNITS] = q.w;
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u)
-      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + u * 64) * LSTR + grp * 8]) = ra[u];
+      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + u * 64) * LSTR + grp * 8]) = qa[u];
 #pragma unroll
     for (int u = 0; u < W_UNITS; ++u) {
       const int unit = tid + u * 256;
-      if (unit < BN * 4) *reinterpret_cast<uint4*>(&sW[buf][(unit >> 2) * LSTR + (unit & 3) * 8]) = rw[u];
+      if (unit < BN * 4) *reinterpret_cast<uint4*>(&sW[buf][(unit >> 2) * LSTR + (unit & 3) * 8]) = qw[u];
     }
   };
 
@@ -114,13 +122,18 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
     for (int j = 0; j < PT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   const int nk = g.Kpad / KC;
-  load_chunk(0);
-  store_chunk(0);
+  load_chunk(0, sl0);
+  if (1 < nk) load_chunk(1, sl1);
+  if (2 < nk) load_chunk(2, sl2);
+  if (3 < nk) load_chunk(3, sl3);
+  store_chunk(0, sl0);
   __syncthreads();
   const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
-  for (int kc = 0; kc < nk; ++kc) {
+  // one K step: chunk kc is in LDS buffer kc&1 and its register slot `cur` is free again
+  auto step = [&](int kc, Slot& cur, const Slot& nxt) {
+    if (kc >= nk) return;
     const int buf = kc & 1;
-    if (kc + 1 < nk) load_chunk(kc + 1);
+    if (kc + NPRE < nk) load_chunk(kc + NPRE, cur);
     bf16x8 fa[PT], fw[CT];
 #pragma unroll
     for (int j = 0; j < PT; ++j)
@@ -133,8 +146,14 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
 #pragma unroll
       for (int j = 0; j < PT; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-    if (kc + 1 < nk) store_chunk(buf ^ 1);
+    if (kc + 1 < nk) store_chunk(buf ^ 1, nxt);
     __syncthreads();
+  };
+  for (int kc0 = 0; kc0 < nk; kc0 += NPRE) {
+    step(kc0, sl0, sl1);
+    step(kc0 + 1, sl1, sl2);
+    step(kc0 + 2, sl2, sl3);
+    step(kc0 + 3, sl3, sl0);
   }
 
   // acc[i][j][v]: channel = ch0 + wc*WCH + i*16 + (lane>>4)*4 + v, pixel row = row0 + wr*WPX + j*16 + (lane&15)
@@ -151,7 +170,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
   // per-channel BN constants of this lane's channels (EPI_BNBWD), loaded once
   float mu_[CT][4], is_[CT][4], ga_[CT][4], be_[CT][4];
   if (EPI == EPI_BNBWD) {
-    const float* stt = (const float*)epi.stats.p[blockIdx.z];
+    const float* stt = (const float*)pick(epi.stats, blockIdx.z);
 #pragma unroll
     for (int i = 0; i < CT; ++i) {
       const int ch = ch0 + wc * WCH + i * 16 + (lane >> 4) * 4;
@@ -190,7 +209,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
       }
       if (EPI == EPI_BNBWD) {
         if (mv) {
-          const bf16_t* xt = (const bf16_t*)epi.x.p[blockIdx.z];
+          const bf16_t* xt = (const bf16_t*)pick(epi.x, blockIdx.z);
           const uint2 xr = *reinterpret_cast<const uint2*>(xt + o);
           const float xv[4] = {__uint_as_float(xr.x << 16), __uint_as_float(xr.x & 0xffff0000u),
                                __uint_as_float(xr.y << 16), __uint_as_float(xr.y & 0xffff0000u)};
@@ -268,7 +287,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
     float a1 = 0.f, a2 = 0.f;
 #pragma unroll
     for (int w = 0; w < WR; ++w) { a1 += sS[(w * BN + tid) * 2]; a2 += sS[(w * BN + tid) * 2 + 1]; }
-    float* part = (float*)epi.partials.p[blockIdx.z];
+    float* part = (float*)pick(epi.partials, blockIdx.z);
     if (EPI == EPI_STATS) {
       const int nrows = min(BM, g.M - row0);
       *reinterpret_cast<float4*>(part + ((size_t)blockIdx.x * g.N + ch0 + tid) * 4) = make_float4(sK[tid], a1, a2, (float)nrows);

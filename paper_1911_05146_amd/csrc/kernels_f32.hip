@@ -14,9 +14,9 @@ namespace {
 template <int MODE>
 __global__ __launch_bounds__(256) void k_conv_f32(PtrTab srcs, const float* __restrict__ w, PtrTab outs, PtrTab adds,
                                                   ConvGeom g) {
-  const float* __restrict__ src = (const float*)srcs.p[blockIdx.z];
-  float* out = (float*)outs.p[blockIdx.z];
-  const float* add = (const float*)adds.p[blockIdx.z];
+  const float* __restrict__ src = (const float*)pick(srcs, blockIdx.z);
+  float* out = (float*)pick(outs, blockIdx.z);
+  const float* add = (const float*)pick(adds, blockIdx.z);
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (size_t)g.M * g.N) return;
   const int n = (int)(idx % g.N);
@@ -62,8 +62,8 @@ __global__ __launch_bounds__(256) void k_conv_f32(PtrTab srcs, const float* __re
 
 // dw[tap][c][n] += sum over this block's row slice of a[row(m,tap), c] * dy[m, n]
 __global__ __launch_bounds__(256) void k_wgrad_f32(PtrTab as, PtrTab dys, float* dw, WgradGeom g, int rows_per_slice) {
-  const float* __restrict__ a = (const float*)as.p[blockIdx.z];
-  const float* __restrict__ dy = (const float*)dys.p[blockIdx.z];
+  const float* __restrict__ a = (const float*)pick(as, blockIdx.z);
+  const float* __restrict__ dy = (const float*)pick(dys, blockIdx.z);
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t total = (size_t)g.R * g.R * g.c_valid * g.N;
   if (idx >= total) return;

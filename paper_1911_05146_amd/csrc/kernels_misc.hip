@@ -8,8 +8,8 @@ namespace {
 
 // col[m, k] for k = (r*3+s)*Cin + c, zero for taps outside the image and for k >= 9*Cin.
 __global__ __launch_bounds__(256) void k_im2col3x3(PtrTab imgs, PtrTab cols, int b, int H, int W, int Cin, int Kc) {
-  const float* __restrict__ img = (const float*)imgs.p[blockIdx.z];
-  bf16_t* __restrict__ col = (bf16_t*)cols.p[blockIdx.z];
+  const float* __restrict__ img = (const float*)pick(imgs, blockIdx.z);
+  bf16_t* __restrict__ col = (bf16_t*)pick(cols, blockIdx.z);
   const size_t total = (size_t)b * H * W * Kc;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int k = (int)(i % Kc);
@@ -52,10 +52,10 @@ template <class T>
 __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __restrict__ wfc, const float* __restrict__ bfc,
                                                   PtrTab labelss, PtrTab gs_, PtrTab dls, float* loss_accum, int hw, int C,
                                                   int classes, float inv_div) {
-  const T* __restrict__ a = (const T*)as.p[blockIdx.z];
-  const int32_t* __restrict__ labels = (const int32_t*)labelss.p[blockIdx.z];
-  float* __restrict__ g = (float*)gs_.p[blockIdx.z];
-  float* __restrict__ dlogits = (float*)dls.p[blockIdx.z];
+  const T* __restrict__ a = (const T*)pick(as, blockIdx.z);
+  const int32_t* __restrict__ labels = (const int32_t*)pick(labelss, blockIdx.z);
+  float* __restrict__ g = (float*)pick(gs_, blockIdx.z);
+  float* __restrict__ dlogits = (float*)pick(dls, blockIdx.z);
   extern __shared__ float dyn[];
   __shared__ float red[8];
   float* gs = dyn;
@@ -92,9 +92,9 @@ __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __rest
 template <class T>
 __global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const float* __restrict__ wfc, float* g_wfc,
                                                   float* g_bfc, PtrTab das, int hw, int C, int classes) {
-  const float* __restrict__ g = (const float*)gs_.p[blockIdx.z];
-  const float* __restrict__ dlogits = (const float*)dls.p[blockIdx.z];
-  T* __restrict__ da = (T*)das.p[blockIdx.z];
+  const float* __restrict__ g = (const float*)pick(gs_, blockIdx.z);
+  const float* __restrict__ dlogits = (const float*)pick(dls, blockIdx.z);
+  T* __restrict__ da = (T*)pick(das, blockIdx.z);
   extern __shared__ float dyn[];
   float* dl = dyn;          // classes
   float* dg = dyn + classes;  // C

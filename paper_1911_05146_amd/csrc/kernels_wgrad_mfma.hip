@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float
   for (int i = 0; i < TT::CTL; ++i)
 #pragma unroll
     for (int j = 0; j < TT::NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-  wgrad_accumulate<BC, BN>((const bf16_t*)as.p[blockIdx.z], (const bf16_t*)dys.p[blockIdx.z], g, tap, ct * BC, nt * BN, m_begin,
+  wgrad_accumulate<BC, BN>((const bf16_t*)pick(as, blockIdx.z), (const bf16_t*)pick(dys, blockIdx.z), g, tap, ct * BC, nt * BN, m_begin,
                            m_end, sA, sD, acc);
   wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), dw, g, tap, ct * BC, nt * BN);
 }
@@ -190,9 +190,9 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restri
 #pragma unroll
     for (int j = 0; j < TT::NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int z = 0; z < ng; ++z) {
-    const char* base = (const char*)bases.p[z];
+    const char* base = (const char*)pick(bases, z);
     const bf16_t* a = (const bf16_t*)(base + it.a_off);
-    const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)caller_dy.p[z] : (const bf16_t*)(base + it.dy_off);
+    const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_dy, z) : (const bf16_t*)(base + it.dy_off);
     wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
   }
   wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0);
