@@ -152,6 +152,9 @@ def main():
     ap.add_argument("--no-graphs", action="store_true", help="plain kernel launches instead of HIP graph replay")
     ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel probes")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one partition on ONE GPU; --gpus must be 1 "
@@ -204,6 +207,13 @@ def main():
         part.grad_accum_read(out=gbuf, stream=main_stream) if sgd is None else None
         torch.cuda.synchronize()
 
+    if args.calib_copy_mb > 0:
+        src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     gbuf = torch.empty(part.n_params, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     for _ in range(args.warmup):

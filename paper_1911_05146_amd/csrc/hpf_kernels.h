@@ -69,11 +69,21 @@ struct ConvEpi {
   const float* gamma = nullptr;
   const float* beta = nullptr;
 };
+// Optional BatchNorm + ReLU applied to the source tensor while it is staged (forward convolutions):
+// the source is the BatchNorm input x and the operand becomes bf16(max(gamma*((x-mean)*invstd)+beta, 0)),
+// so the normalised activation is never written to memory.  Padding stays zero.
+struct ConvPro {
+  int on = 0;
+  PtrTab stats{};            // {mean(Cs), invstd(Cs)} float, per member
+  const float* gamma = nullptr;
+  const float* beta = nullptr;
+};
 int conv_mfma_tile_rows(int g, const ConvGeom& geom);   // pixel rows per tile the launcher will use
 
 // g = number of group members (grid z); tables hold g valid pointers.  `add` tables may be all-null.
 hipError_t launch_conv_mfma(int mode, int g, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                            const ConvGeom& geom, hipStream_t stream, const ConvEpi& epi = ConvEpi());
+                            const ConvGeom& geom, hipStream_t stream, const ConvEpi& epi = ConvEpi(),
+                            const ConvPro& pro = ConvPro());
 hipError_t launch_wgrad_mfma(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);
 
 // All weight gradients of a backward pass in one launch per tile class.  An item is one (convolution,
@@ -82,8 +92,11 @@ hipError_t launch_wgrad_mfma(int g, const PtrTab& a, const PtrTab& dy, float* dw
 // a / dy live at byte offsets in each member's arena region (dy_off == WGRAD_DY_CALLER: the caller's
 // err_in buffer of that member).
 constexpr unsigned long long WGRAD_DY_CALLER = ~0ull;
+constexpr unsigned long long WGRAD_NO_BN = ~0ull;
 struct WgradItem {
-  unsigned long long a_off, dy_off, dw_off;   // bytes, bytes, floats
+  unsigned long long a_off, dy_off, dw_off;   // bytes, bytes, floats; a_off == WGRAD_DY_CALLER: the caller's act_in
+  unsigned long long stats_off;               // bytes; != WGRAD_NO_BN: `a` is a BatchNorm input and the operand is
+  unsigned long long gamma_off, beta_off;     //   relu(bn(a)) recomputed while staging (floats into the parameters)
   WgradGeom g;
   int tap, c0, n0, m_begin, m_end;
 };
@@ -91,7 +104,8 @@ struct WgradItem {
 int wgrad_tile_class(int cin, int cout);
 void wgrad_tile_dims(int tile_class, int* bc, int* bn);
 hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
-                                const PtrTab& caller_dy, float* grads, hipStream_t stream);
+                                const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
+                                hipStream_t stream);
 
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);

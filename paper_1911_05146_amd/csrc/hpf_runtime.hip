@@ -107,6 +107,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   // ---- shape chain + validation
   int h = d.in_h, w = d.in_w, c = d.has_stem ? d.stem_c_out : d.in_c;
   if (c % cmul) return fail(HPF_EUNSUPPORTED, "channel count %d is not a multiple of %d", c, cmul);
+  const int cmax = 1024;   // bf16 mode keeps a per-channel table of the source tensor in LDS
+  if (P.dt == DT_BF16 && c > cmax) return fail(HPF_EUNSUPPORTED, "more than %d channels", cmax);
   for (int i = 0; i < d.n_blocks; ++i) {
     const hpf_block_desc& b = P.blocks[i];
     if (b.kind != 0 && b.kind != 1) return fail(HPF_EINVAL, "block %d: kind %d", i, b.kind);
@@ -116,6 +118,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     if (b.stride != 1 && b.stride != 2) return fail(HPF_EINVAL, "block %d: stride %d", i, b.stride);
     if (h % b.stride || w % b.stride) return fail(HPF_EINVAL, "block %d: %dx%d not divisible by stride", i, h, w);
     if (b.c_mid % cmul || b.c_out % cmul) return fail(HPF_EUNSUPPORTED, "block %d: channel counts must be multiples of %d", i, cmul);
+    if (P.dt == DT_BF16 && (b.c_mid > cmax || b.c_out > cmax)) return fail(HPF_EUNSUPPORTED, "block %d: more than %d channels", i, cmax);
     h /= b.stride; w /= b.stride; c = b.c_out;
   }
   P.out_h = h; P.out_w = w; P.out_c = c;
@@ -217,10 +220,12 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
     p.x_in = cur;
-    stats(p.bn[0], M_in); p.a[0] = tensor(M_in * p.d.c_in);
+    // bf16 mode never materialises a = relu(bn(x)): the convolutions apply it while staging x
+    const bool keep_a = (P.dt != DT_BF16);
+    stats(p.bn[0], M_in); if (keep_a) p.a[0] = tensor(M_in * p.d.c_in);
     for (int j = 1; j < p.nconv; ++j) {
       p.c[j - 1] = tensor(M_out * p.cv[j - 1].cout);
-      stats(p.bn[j], M_out); p.a[j] = tensor(M_out * p.cv[j].cin);
+      stats(p.bn[j], M_out); if (keep_a) p.a[j] = tensor(M_out * p.cv[j].cin);
     }
     const bool last = (i == d.n_blocks - 1);
     if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
@@ -260,15 +265,17 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
   // ---- deferred weight-gradient items (bf16 mode)
   if (P.dt == DT_BF16) {
-    struct WConv { const ConvPlan* cv; int cin_run, c_valid, R; Loc a, dy; };
+    // the operand of a block convolution is relu(bn(x)) recomputed from the BatchNorm input x
+    struct WConv { const ConvPlan* cv; int cin_run, c_valid, R; Loc a, dy; const BnPlan* bn; };
     std::vector<WConv> wc;
     ConvPlan stem1x1 = P.stem;
-    if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem});
+    if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr});
     for (int i = 0; i < d.n_blocks; ++i) {
       const BlockPlan& p = P.bp[i];
       for (int j = 0; j < p.nconv; ++j)
-        wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.a[j], j == p.nconv - 1 ? p.gy : p.dc[j]});
-      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.a[0], p.gy});
+        wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, j == 0 ? p.x_in : p.c[j - 1],
+                           j == p.nconv - 1 ? p.gy : p.dc[j], &p.bn[j]});
+      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.gy, &p.bn[0]});
     }
     // output tiles per class: the pixel rows are split so that every class launches roughly 1500 work-groups
     // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
@@ -298,9 +305,12 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
           for (int n0 = 0; n0 < cv.cout; n0 += bn)
             for (int sp = 0; sp < splits; ++sp) {
               WgradItem it{};
-              it.a_off = w.a.off;
+              it.a_off = w.a.kind == IN_MB ? w.a.off : WGRAD_DY_CALLER;
               it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
               it.dw_off = cv.w_off;
+              it.stats_off = w.bn ? w.bn->stats_off : WGRAD_NO_BN;
+              it.gamma_off = w.bn ? w.bn->g_off : 0;
+              it.beta_off = w.bn ? w.bn->b_off : 0;
               it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
               it.m_begin = sp * rows; it.m_end = (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M;
               P.items[cls].push_back(it);
@@ -382,7 +392,8 @@ struct Ctx {
   bool fused() const { return h->fuse && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
 
   // part_rows > 0: the producing convolution already wrote that many statistics partial rows.
-  void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M, int part_rows = 0) {
+  // apply == false: only the statistics (the consuming convolutions normalise while staging)
+  void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M, int part_rows = 0, bool apply = true) {
     const Plan& P = h->P;
     const PtrTab st = mbp(bn.stats_off);
     if (P.d.bn_mode != 0)
@@ -391,7 +402,8 @@ struct Ctx {
       chk(launch_bn_stats_finalize(g, (int)M, bn.C, part_rows, P.d.bn_eps, mbp(P.partials_off), st, s), "bn_stats_finalize");
     else
       chk(launch_bn_stats(P.dt, g, x, (int)M, bn.C, P.d.bn_eps, st, mbp(P.partials_off), s), "bn_stats");
-    chk(launch_bn_apply_relu(P.dt, g, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
+    if (apply)
+      chk(launch_bn_apply_relu(P.dt, g, x, a, h->params() + bn.g_off, h->params() + bn.b_off, st, (int)M, bn.C, s), "bn_apply_relu");
   }
   // part_rows > 0: `da` already holds dz and the producing data-gradient wrote that many partial rows.
   void bn_bwd(const BnPlan& bn, const PtrTab& x, const PtrTab& da, const PtrTab& skip, const PtrTab& dx, size_t M,
@@ -423,17 +435,24 @@ struct Ctx {
     return q;
   }
   // want_stats: the output feeds a BatchNorm; returns the number of partial rows written (0 = none).
-  int conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add, bool want_stats = false) {
+  // pro_bn (bf16 mode): x is the input of that BatchNorm and the convolution normalises it while staging.
+  int conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add, bool want_stats = false,
+               const BnPlan* pro_bn = nullptr) {
     const ConvGeom q = geom_fwd(cv);
     if (h->P.dt == DT_BF16) {
       ConvEpi epi;
+      ConvPro pro;
+      if (pro_bn) {
+        pro.on = 1; pro.stats = mbp(pro_bn->stats_off);
+        pro.gamma = h->params() + pro_bn->g_off; pro.beta = h->params() + pro_bn->b_off;
+      }
       int rows = 0;
       if (want_stats && fused()) {
         epi.kind = EPI_STATS; epi.partials = mbp(h->P.partials_off);
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
-      chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi), "conv_fwd");
+      chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi, pro), "conv_fwd");
       return rows;
     }
     chk(launch_conv_f32(CONV_FWD, g, x, h->params() + cv.w_off, y, add, q, s), "conv_fwd_f32");
@@ -489,15 +508,20 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
-    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows);
-    if (p.proj) c.conv_fwd(p.pj, c.tab(p.a[0]), y, Ctx::none());
+    const bool pro = (P.dt == DT_BF16);   // bf16: BN + ReLU applied inside the consuming convolutions
+    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows, !pro);
+    if (p.proj) c.conv_fwd(p.pj, pro ? x : c.tab(p.a[0]), y, Ctx::none(), false, pro ? &p.bn[0] : nullptr);
     const PtrTab shortcut = p.proj ? y : x;
+    PtrTab src = pro ? x : c.tab(p.a[0]);
     for (int j = 0; j < p.nconv; ++j) {
       const bool last = (j == p.nconv - 1);
       const PtrTab out = last ? y : c.tab(p.c[j]);
       const bool feeds_bn = !last || bi + 1 < P.bp.size() || P.d.has_head;
-      part_rows = c.conv_fwd(p.cv[j], c.tab(p.a[j]), out, last ? shortcut : Ctx::none(), feeds_bn);
-      if (!last) c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows);
+      part_rows = c.conv_fwd(p.cv[j], src, out, last ? shortcut : Ctx::none(), feeds_bn, pro ? &p.bn[j] : nullptr);
+      if (!last) {
+        c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows, !pro);
+        src = pro ? out : c.tab(p.a[j + 1]);
+      }
     }
   }
   if (P.d.has_head) {
@@ -555,11 +579,15 @@ void run_backward(Ctx& c) {
     c.conv_wgrad(P.stem, c.tab(in), c.tab(P.g_stem));
   }
   if (deferred) {
-    PtrTab bases{}, caller{};
-    for (int i = 0; i < c.g; ++i) { bases.p[i] = c.h->mb_base(c.mb0 + i); caller.p[i] = const_cast<void*>(c.err_in[i]); }
+    PtrTab bases{}, caller_dy{}, caller_a{};
+    for (int i = 0; i < c.g; ++i) {
+      bases.p[i] = c.h->mb_base(c.mb0 + i);
+      caller_dy.p[i] = const_cast<void*>(c.err_in[i]);
+      caller_a.p[i] = const_cast<void*>(c.act_in[i]);
+    }
     for (int k = 0; k < 9; ++k)
-      c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + P.items_off[k]), (int)P.items[k].size(), bases, caller,
-                                 c.h->grads(), c.s),
+      c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + P.items_off[k]), (int)P.items[k].size(), bases, caller_dy,
+                                 caller_a, c.h->params(), c.h->grads(), c.s),
             "wgrad_grouped");
   }
 }

@@ -28,9 +28,25 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int KC = 32;          // reduction elements per step
 constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-free 16-byte reads)
 
-template <int BM, int BN, int WR, int WC, int MODE, int EPI>
+// relu(bn(x)) of the 8 bf16 values in q, channels c..c+7, constants {mean, invstd, gamma, beta} per channel
+__device__ __forceinline__ uint4 bn_relu_unit(const uint4& q, const float4* coef, int c) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  uint32_t r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 k0 = coef[c + 2 * i], k1 = coef[c + 2 * i + 1];
+    const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
+    const float z0 = k0.z * ((x0 - k0.x) * k0.y) + k0.w;
+    const float z1 = k1.z * ((x1 - k1.x) * k1.y) + k1.w;
+    r[i] = pack_bf16x2(z0 > 0.f ? z0 : 0.f, z1 > 0.f ? z1 : 0.f);
+  }
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+template <int BM, int BN, int WR, int WC, int MODE, int EPI, int PRO>
 __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds,
-                                                   ConvGeom g, ConvEpi epi) {
+                                                   ConvGeom g, ConvEpi epi, ConvPro pro) {
+  extern __shared__ float4 coef[];   // PRO: per source channel {mean, invstd, gamma, beta}
   const bf16_t* __restrict__ src = (const bf16_t*)pick(srcs, blockIdx.z);
   bf16_t* out = (bf16_t*)pick(outs, blockIdx.z);
   const bf16_t* add = (const bf16_t*)pick(adds, blockIdx.z);
@@ -69,8 +85,13 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
   // NPRE chunks are kept in flight in registers: at these sizes a work-group lives for a handful of
   // K steps only, so what matters is how many global loads are outstanding, not the MFMA rate.
   constexpr int NPRE = 4;
-  struct Slot { uint4 a[A_UNITS]; uint4 w[W_UNITS]; };
+  struct Slot { uint4 a[A_UNITS]; uint4 w[W_UNITS]; int c; bool av[A_UNITS]; };
   Slot sl0, sl1, sl2, sl3;   // named, not an array: they must stay in registers
+  if (PRO) {
+    const float* stt = (const float*)pick(pro.stats, blockIdx.z);
+    for (int c = tid; c < g.Cs; c += 256) coef[c] = make_float4(stt[c], stt[g.Cs + c], pro.gamma[c], pro.beta[c]);
+    __syncthreads();
+  }
 
   auto load_chunk = [&](int kc, Slot& q) {
     uint4 (&qa)[A_UNITS] = q.a;
@@ -80,6 +101,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
     const int c = k - tap * g.Cs;
     const int r = tap / g.R, s = tap - r * g.R;
     const bool kvalid = k < g.Ktot;
+    q.c = c;
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
       int hs, ws;
@@ -92,6 +114,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
         hs = th >> sshift; ws = tw >> sshift;
       }
       v = v && (unsigned)hs < (unsigned)g.Hs && (unsigned)ws < (unsigned)g.Ws;
+      q.av[u] = v;
       qa[u] = v ? *reinterpret_cast<const uint4*>(src + (size_t)(a_img[u] + hs * g.Ws + ws) * g.Cs + c)
                 : make_uint4(0u, 0u, 0u, 0u);
     }
@@ -106,8 +129,11 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
     const uint4 (&qa)[A_UNITS] = q.a;
     const uint4 (&qw)[W_UNITS] = q.w;
 #pragma unroll
-    for (int u = 0; u < A_UNITS; ++u)
-      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + u * 64) * LSTR + grp * 8]) = qa[u];
+    for (int u = 0; u < A_UNITS; ++u) {
+      uint4 val = qa[u];
+      if (PRO) { if (q.av[u]) val = bn_relu_unit(val, coef, q.c); }
+      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + u * 64) * LSTR + grp * 8]) = val;
+    }
 #pragma unroll
     for (int u = 0; u < W_UNITS; ++u) {
       const int unit = tid + u * 256;
@@ -299,29 +325,30 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
 
 template <int BM, int BN, int WR, int WC>
 hipError_t launch_tile(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                       const ConvGeom& g, hipStream_t stream, const ConvEpi& epi) {
+                       const ConvGeom& g, hipStream_t stream, const ConvEpi& epi, const ConvPro& pro) {
   const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN), (unsigned)ng);
+  const size_t dyn = pro.on ? (size_t)g.Cs * sizeof(float4) : 0;
+#define HPF_CONV(MODE_, EPI_, PRO_) \
+  k_conv_mfma<BM, BN, WR, WC, MODE_, EPI_, PRO_><<<grid, 256, dyn, stream>>>(src, wpk, out, add, g, epi, pro)
   if (mode == CONV_FWD) {
-    if (epi.kind == EPI_STATS)
-      k_conv_mfma<BM, BN, WR, WC, CONV_FWD, EPI_STATS><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
-    else if (epi.kind == EPI_NONE)
-      k_conv_mfma<BM, BN, WR, WC, CONV_FWD, EPI_NONE><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
-    else
-      return hipErrorInvalidValue;
+    if (epi.kind == EPI_STATS) { if (pro.on) HPF_CONV(CONV_FWD, EPI_STATS, 1); else HPF_CONV(CONV_FWD, EPI_STATS, 0); }
+    else if (epi.kind == EPI_NONE) { if (pro.on) HPF_CONV(CONV_FWD, EPI_NONE, 1); else HPF_CONV(CONV_FWD, EPI_NONE, 0); }
+    else return hipErrorInvalidValue;
   } else {
-    if (epi.kind == EPI_BNBWD)
-      k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD, EPI_BNBWD><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
-    else if (epi.kind == EPI_NONE)
-      k_conv_mfma<BM, BN, WR, WC, CONV_DGRAD, EPI_NONE><<<grid, 256, 0, stream>>>(src, wpk, out, add, g, epi);
-    else
-      return hipErrorInvalidValue;
+    if (pro.on) return hipErrorInvalidValue;
+    if (epi.kind == EPI_BNBWD) HPF_CONV(CONV_DGRAD, EPI_BNBWD, 0);
+    else if (epi.kind == EPI_NONE) HPF_CONV(CONV_DGRAD, EPI_NONE, 0);
+    else return hipErrorInvalidValue;
   }
+#undef HPF_CONV
   return hipGetLastError();
 }
 
 // 0: 128x128, 1: 64x64, 2: 64x32, 3: 64x16
 int pick_tile(int ng, const ConvGeom& g) {
-  if (g.N % 128 == 0) {
+  // the 128x128 tile pays off through operand reuse over a long reduction; short reductions are
+  // latency bound and want many small work-groups
+  if (g.N % 128 == 0 && g.Kpad >= 512) {
     const long wgs = (long)((g.M + 127) / 128) * (g.N / 128) * ng;
     if (wgs >= 192) return 0;
   }
@@ -337,14 +364,14 @@ int conv_mfma_tile_rows(int ng, const ConvGeom& g) { return pick_tile(ng, g) == 
 // Tile choice: the widest channel tile that divides N, then the pixel tile that still gives the
 // chip (256 CUs) enough work-groups.
 hipError_t launch_conv_mfma(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
-                            const ConvGeom& g, hipStream_t stream, const ConvEpi& epi) {
+                            const ConvGeom& g, hipStream_t stream, const ConvEpi& epi, const ConvPro& pro) {
   if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
   if (g.N % 16 != 0 || g.Cs % 8 != 0 || g.Kpad % KC != 0 || (g.stride != 1 && g.stride != 2)) return hipErrorInvalidValue;
   switch (pick_tile(ng, g)) {
-    case 0: return launch_tile<128, 128, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi);
-    case 1: return launch_tile<64, 64, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi);
-    case 2: return launch_tile<64, 32, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi);
-    default: return launch_tile<64, 16, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi);
+    case 0: return launch_tile<128, 128, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi, pro);
+    case 1: return launch_tile<64, 64, 2, 2>(mode, ng, src, wpk, out, add, g, stream, epi, pro);
+    case 2: return launch_tile<64, 32, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi, pro);
+    default: return launch_tile<64, 16, 4, 1>(mode, ng, src, wpk, out, add, g, stream, epi, pro);
   }
 }
 

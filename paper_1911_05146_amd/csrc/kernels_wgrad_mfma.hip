@@ -37,10 +37,14 @@ struct WgradTile {
 
 // Adds sum over rows [m_begin, m_end) of a[row(m,tap), c0..c0+BC) (x) dy[m, n0..n0+BN) into acc
 // (each of the 4 waves holds the sum over its 32-row slices).
+// bn_stats != nullptr: `a` is the input of a BatchNorm and the operand is relu(bn(a)), recomputed while
+// staging from {mean, invstd} = bn_stats[0..Cin), [Cin..2Cin) and gamma / beta (the normalised
+// activation is not kept in memory); rows outside the image stay zero.
 template <int BC, int BN>
 __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, const bf16_t* __restrict__ dy, const WgradGeom& g,
                                                  int tap, int c0, int n0, int m_begin, int m_end, bf16_t* sA, bf16_t* sD,
-                                                 floatx4 (&acc)[BC / 16][BN / 16]) {
+                                                 floatx4 (&acc)[BC / 16][BN / 16], const float* bn_stats = nullptr,
+                                                 const float* gamma = nullptr, const float* beta = nullptr) {
   typedef WgradTile<BC, BN> TT;
   constexpr int CTL = TT::CTL, NTL = TT::NTL, A_UNITS = TT::A_UNITS, D_UNITS = TT::D_UNITS;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -48,6 +52,31 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
   const int HoWo = g.Ho * g.Wo;
 
   uint4 ra[A_UNITS][2], rd[D_UNITS][2];
+  bool rv[A_UNITS][2];
+  float4 cf[A_UNITS][8];   // {mean, invstd, gamma, beta} of this thread's 8 channels (fixed over the steps)
+  if (bn_stats) {
+#pragma unroll
+    for (int u = 0; u < A_UNITS; ++u) {
+      const int unit = tid + u * 256;
+      if (unit < 64 * (BC / 8)) {
+        const int c = c0 + (unit >> 6) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cf[u][i] = make_float4(bn_stats[c + i], bn_stats[g.Cin + c + i], gamma[c + i], beta[c + i]);
+      }
+    }
+  }
+  auto bn_relu8 = [&](const uint4& q, const float4 (&k)[8]) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    uint32_t r_[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
+      const float z0 = k[2 * i].z * ((x0 - k[2 * i].x) * k[2 * i].y) + k[2 * i].w;
+      const float z1 = k[2 * i + 1].z * ((x1 - k[2 * i + 1].x) * k[2 * i + 1].y) + k[2 * i + 1].w;
+      r_[i] = pack_bf16x2(z0 > 0.f ? z0 : 0.f, z1 > 0.f ? z1 : 0.f);
+    }
+    return make_uint4(r_[0], r_[1], r_[2], r_[3]);
+  };
 
   auto load_step = [&](int m0) {
 #pragma unroll
@@ -67,6 +96,7 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
           v = (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
           off = ((size_t)(img * g.H + hi) * g.W + wi) * g.Cin + c0 + cg * 8;
         }
+        rv[u][e] = v;
         ra[u][e] = v ? *reinterpret_cast<const uint4*>(a + off) : make_uint4(0u, 0u, 0u, 0u);
       }
     }
@@ -98,7 +128,13 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
       const int unit = tid + u * 256;
-      if (unit < 64 * (BC / 8)) store_pairs(sA, unit, ra[u][0], ra[u][1]);
+      if (unit < 64 * (BC / 8)) {
+        if (bn_stats) {
+          if (rv[u][0]) ra[u][0] = bn_relu8(ra[u][0], cf[u]);
+          if (rv[u][1]) ra[u][1] = bn_relu8(ra[u][1], cf[u]);
+        }
+        store_pairs(sA, unit, ra[u][0], ra[u][1]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < D_UNITS; ++u) {
@@ -178,7 +214,7 @@ __global__ __launch_bounds__(256) void k_wgrad_mfma(PtrTab as, PtrTab dys, float
 // One work-group per item; the micro-batches of the group are accumulated in registers.
 template <int BC, int BN>
 __global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restrict__ items, int ng, PtrTab bases, PtrTab caller_dy,
-                                                       float* grads) {
+                                                       PtrTab caller_a, const float* __restrict__ params, float* grads) {
   typedef WgradTile<BC, BN> TT;
   __shared__ __attribute__((aligned(16))) unsigned char smem[TT::SMEM_BYTES];
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem);
@@ -191,9 +227,13 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restri
     for (int j = 0; j < TT::NTL; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int z = 0; z < ng; ++z) {
     const char* base = (const char*)pick(bases, z);
-    const bf16_t* a = (const bf16_t*)(base + it.a_off);
+    const bf16_t* a = it.a_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_a, z) : (const bf16_t*)(base + it.a_off);
     const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_dy, z) : (const bf16_t*)(base + it.dy_off);
-    wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
+    if (it.stats_off != WGRAD_NO_BN)
+      wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc,
+                               (const float*)(base + it.stats_off), params + it.gamma_off, params + it.beta_off);
+    else
+      wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
   }
   wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0);
 }
@@ -241,11 +281,13 @@ void wgrad_tile_dims(int tile_class, int* bc, int* bn) {
 }
 
 hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
-                                const PtrTab& caller_dy, float* grads, hipStream_t stream) {
+                                const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
+                                hipStream_t stream) {
   if (n_items <= 0) return hipSuccess;
   if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_items);
-#define HPF_WG(BC, BN) k_wgrad_grouped<BC, BN><<<grid, 256, 0, stream>>>(items_dev, ng, region_base, caller_dy, grads)
+#define HPF_WG(BC, BN) \
+  k_wgrad_grouped<BC, BN><<<grid, 256, 0, stream>>>(items_dev, ng, region_base, caller_dy, caller_a, params, grads)
   switch (tile_class) {
     case 0: HPF_WG(16, 16); break;
     case 1: HPF_WG(16, 32); break;
