@@ -15,17 +15,14 @@ __device__ __forceinline__ void* pick(const PtrTab& t, unsigned z) {
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-
+// float -> bfloat16, round-to-nearest-even, two at a time: one v_cvt_pk_bf16_f32 on gfx950
+typedef __bf16 hpf_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hpf_floatx2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  const hpf_floatx2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, hpf_bf16x2));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // 8 consecutive elements <-> 8 floats
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {

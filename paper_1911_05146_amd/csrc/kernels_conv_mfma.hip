@@ -28,17 +28,17 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int KC = 32;          // reduction elements per step
 constexpr int LSTR = KC + 8;    // LDS row stride in bf16 (80 bytes: conflict-free 16-byte reads)
 
-// relu(bn(x)) of the 8 bf16 values in q, channels c..c+7, constants {mean, invstd, gamma, beta} per channel
-__device__ __forceinline__ uint4 bn_relu_unit(const uint4& q, const float4* coef, int c) {
+// relu(bn(x)) of the 8 bf16 values in q, channels c..c+7 (c a multiple of 8); coef holds per channel
+// {scale = gamma*invstd, shift = beta - mean*scale}, so the operand is max(x*scale + shift, 0).
+__device__ __forceinline__ uint4 bn_relu_unit(const uint4& q, const float2* coef, int c) {
   const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  const float4* cf = reinterpret_cast<const float4*>(coef + c);   // two channels per 16-byte read
   uint32_t r[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const float4 k0 = coef[c + 2 * i], k1 = coef[c + 2 * i + 1];
+    const float4 k = cf[i];
     const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
-    const float z0 = k0.z * ((x0 - k0.x) * k0.y) + k0.w;
-    const float z1 = k1.z * ((x1 - k1.x) * k1.y) + k1.w;
-    r[i] = pack_bf16x2(z0 > 0.f ? z0 : 0.f, z1 > 0.f ? z1 : 0.f);
+    r[i] = pack_bf16x2(fmaxf(fmaf(x0, k.x, k.y), 0.f), fmaxf(fmaf(x1, k.z, k.w), 0.f));
   }
   return make_uint4(r[0], r[1], r[2], r[3]);
 }
@@ -46,7 +46,7 @@ __device__ __forceinline__ uint4 bn_relu_unit(const uint4& q, const float4* coef
 template <int BM, int BN, int WR, int WC, int MODE, int EPI, int PRO>
 __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds,
                                                    ConvGeom g, ConvEpi epi, ConvPro pro) {
-  extern __shared__ float4 coef[];   // PRO: per source channel {mean, invstd, gamma, beta}
+  extern __shared__ float2 coef[];   // PRO: per source channel {scale, shift}
   const bf16_t* __restrict__ src = (const bf16_t*)pick(srcs, blockIdx.z);
   bf16_t* out = (bf16_t*)pick(outs, blockIdx.z);
   const bf16_t* add = (const bf16_t*)pick(adds, blockIdx.z);
@@ -89,18 +89,29 @@ __global__ __launch_bounds__(256) void k_conv_mfma(PtrTab srcs, const bf16_t* __
   Slot sl0, sl1, sl2, sl3;   // named, not an array: they must stay in registers
   if (PRO) {
     const float* stt = (const float*)pick(pro.stats, blockIdx.z);
-    for (int c = tid; c < g.Cs; c += 256) coef[c] = make_float4(stt[c], stt[g.Cs + c], pro.gamma[c], pro.beta[c]);
+    for (int c = tid; c < g.Cs; c += 256) {
+      const float sc = pro.gamma[c] * stt[g.Cs + c];
+      coef[c] = make_float2(sc, pro.beta[c] - stt[c] * sc);
+    }
     __syncthreads();
   }
 
+  // (filter tap row, tap column, channel) of this thread's 16-byte unit in the chunk that is loaded
+  // next; chunks are loaded in order, so the position advances by KC channels per load (no divisions)
+  int lk = grp * 8, lr, ls, lc;
+  {
+    const int tap = lk / g.Cs;
+    lc = lk - tap * g.Cs;
+    lr = tap / g.R;
+    ls = tap - lr * g.R;
+  }
   auto load_chunk = [&](int kc, Slot& q) {
     uint4 (&qa)[A_UNITS] = q.a;
     uint4 (&qw)[W_UNITS] = q.w;
-    const int k = kc * KC + grp * 8;
-    const int tap = k / g.Cs;
-    const int c = k - tap * g.Cs;
-    const int r = tap / g.R, s = tap - r * g.R;
-    const bool kvalid = k < g.Ktot;
+    const int c = lc, r = lr, s = ls;
+    const bool kvalid = lk < g.Ktot;
+    lk += KC; lc += KC;
+    while (lc >= g.Cs) { lc -= g.Cs; if (++ls == g.R) { ls = 0; ++lr; } }
     q.c = c;
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
@@ -327,7 +338,7 @@ template <int BM, int BN, int WR, int WC>
 hipError_t launch_tile(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,
                        const ConvGeom& g, hipStream_t stream, const ConvEpi& epi, const ConvPro& pro) {
   const dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)(g.N / BN), (unsigned)ng);
-  const size_t dyn = pro.on ? (size_t)g.Cs * sizeof(float4) : 0;
+  const size_t dyn = pro.on ? (size_t)g.Cs * sizeof(float2) : 0;
 #define HPF_CONV(MODE_, EPI_, PRO_) \
   k_conv_mfma<BM, BN, WR, WC, MODE_, EPI_, PRO_><<<grid, 256, dyn, stream>>>(src, wpk, out, add, g, epi, pro)
   if (mode == CONV_FWD) {

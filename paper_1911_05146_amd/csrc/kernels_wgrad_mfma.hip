@@ -53,7 +53,7 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 
   uint4 ra[A_UNITS][2], rd[D_UNITS][2];
   bool rv[A_UNITS][2];
-  float4 cf[A_UNITS][8];   // {mean, invstd, gamma, beta} of this thread's 8 channels (fixed over the steps)
+  float2 cf[A_UNITS][8];   // {scale, shift} of this thread's 8 channels (fixed over the steps)
   if (bn_stats) {
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
@@ -61,19 +61,20 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
       if (unit < 64 * (BC / 8)) {
         const int c = c0 + (unit >> 6) * 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) cf[u][i] = make_float4(bn_stats[c + i], bn_stats[g.Cin + c + i], gamma[c + i], beta[c + i]);
+        for (int i = 0; i < 8; ++i) {
+          const float sc = gamma[c + i] * bn_stats[g.Cin + c + i];
+          cf[u][i] = make_float2(sc, beta[c + i] - bn_stats[c + i] * sc);
+        }
       }
     }
   }
-  auto bn_relu8 = [&](const uint4& q, const float4 (&k)[8]) {
+  auto bn_relu8 = [&](const uint4& q, const float2 (&k)[8]) {
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
     uint32_t r_[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
-      const float z0 = k[2 * i].z * ((x0 - k[2 * i].x) * k[2 * i].y) + k[2 * i].w;
-      const float z1 = k[2 * i + 1].z * ((x1 - k[2 * i + 1].x) * k[2 * i + 1].y) + k[2 * i + 1].w;
-      r_[i] = pack_bf16x2(z0 > 0.f ? z0 : 0.f, z1 > 0.f ? z1 : 0.f);
+      r_[i] = pack_bf16x2(fmaxf(fmaf(x0, k[2 * i].x, k[2 * i].y), 0.f), fmaxf(fmaf(x1, k[2 * i + 1].x, k[2 * i + 1].y), 0.f));
     }
     return make_uint4(r_[0], r_[1], r_[2], r_[3]);
   };
