@@ -158,10 +158,22 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
  * stream that is itself being captured by the caller always get plain launches. */
 hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
 
-/* bf16 mode computes the BatchNorm reductions (forward statistics, backward dbeta/dgamma sums) in
- * the epilogue of the convolution that produces the tensor, instead of separate passes over it.
- * enable == 0 switches to the separate kernels (same arithmetic, other summation order); default on. */
-hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable);
+/* How far bf16 mode fuses the kernel schedule; the arithmetic is the same at every level, summation
+ * orders and the points where intermediate gradients are rounded to bf16 differ.
+ *   0  every step a kernel of its own (convolution, BatchNorm statistics, normalise + ReLU, ...);
+ *   1  BatchNorm reductions (forward statistics, backward dbeta/dgamma sums) in the epilogue of the
+ *      convolution that produces the tensor, normalise + ReLU while the consuming convolution and
+ *      weight gradient stage their operand;
+ *   2  (default) additionally, runs of consecutive bottleneck blocks with stride 1 and identity
+ *      shortcut (128->32->32->128 channels at up to 256 pixels, 256->64->64->256 at up to 128) run
+ *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per
+ *      image, all of them on the chip together.  Needs microbatch <= number of CUs; a group call
+ *      then processes floor(CUs / microbatch) micro-batches (at most 8) per launch, and launches
+ *      of this kind from all streams and partitions of the process are serialised.  If a launch
+ *      ever waits in vain for its partner work-groups it gives up after about a second and the
+ *      next hpf_grad_accum_read to host memory or hpf_params_read returns HPF_EDEVICE.
+ * Not allowed while a micro-batch is between forward and backward (HPF_ESTATE). */
+hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
 
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);

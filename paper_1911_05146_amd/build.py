@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhpf.so")
 SOURCES = ["hpf_runtime.hip", "kernels_bn.hip", "kernels_misc.hip", "kernels_f32.hip",
-           "kernels_conv_mfma.hip", "kernels_wgrad_mfma.hip"]
+           "kernels_conv_mfma.hip", "kernels_wgrad_mfma.hip", "kernels_resident.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -107,6 +107,49 @@ hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_de
                                 const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
                                 hipStream_t stream);
 
+// ---- image-resident runs of identity bottleneck blocks (bf16 mode, BatchNorm on micro-batch statistics)
+// A run is a sequence of consecutive bottleneck blocks with stride 1 and identity shortcut.  One
+// work-group owns one image for the whole run: the residual stream of the image stays in LDS from block
+// to block, all three convolutions of a block run from LDS, and only what the backward pass and the
+// weight gradients read later goes to memory.  The one cross-image dependency, the BatchNorm reductions
+// over the micro-batch, is an all-gather of small per-image records between the work-groups of a
+// micro-batch, so all of them must be resident on the chip together (checked by the launchers).
+// tensor locations outside the micro-batch region: the caller's buffers of the member
+constexpr unsigned long long RES_ACT_IN = ~0ull, RES_ACT_OUT = ~1ull, RES_ERR_IN = ~2ull, RES_ERR_OUT = ~3ull;
+struct ResBlock {
+  // byte offsets into a micro-batch region (or RES_*): block input, conv1 / conv2 outputs, block output
+  unsigned long long x_off, c1_off, c2_off, y_off;
+  // gradients w.r.t. the block output, c1, c2, and where the gradient w.r.t. the block input goes
+  unsigned long long gy_off, dc1_off, dc2_off, gx_off;
+  unsigned long long stats_off[3];           // {mean, invstd} floats of the three BatchNorms (bytes)
+  unsigned long long wf_off[3], wd_off[3];   // packed bf16 weights (elements)
+  unsigned long long gamma_off[3], beta_off[3];   // floats into the parameter / gradient vectors
+};
+struct ResArgs {
+  const ResBlock* blocks;   // device table of the run
+  int nblk;
+  int nmem;                 // images per micro-batch = work-groups per exchange group (grid x)
+  int H, W;
+  float eps;
+  PtrTab base;              // micro-batch regions of the group members (grid z)
+  PtrTab act_in, act_out, err_in, err_out;   // caller buffers per member (null where the pass does not use them)
+  const float* params;
+  const bf16_t* packed;
+  float* grads;
+  unsigned long long xchg_off;   // bytes into the region: exchange words, resident_xchg_bytes()
+  unsigned long long tag_off;    // bytes into the region: phase tag counter (one unsigned, starts at 0)
+  int* abort_flag;          // set when an exchange timed out (the pass is then invalid)
+};
+// Shapes this path covers (a property of the shapes alone).
+bool resident_shape_ok(int C, int MID, int H, int W, int nmem);
+// Largest number of micro-batches of nmem images one launch may hold on the current device (0: none):
+// every work-group takes a CU of its own and all of them must be resident together.
+int resident_max_group(int nmem);
+size_t resident_xchg_bytes(int C, int nmem);
+hipError_t resident_prepare();   // once per process, outside stream capture: raises the kernels' LDS limits
+hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);
 hipError_t launch_wgrad_f32(int g, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& geom, hipStream_t stream);

@@ -12,6 +12,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -82,6 +83,14 @@ struct Plan {
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
   std::vector<PackDesc> table;
+  // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
+  struct ResRun { int first = 0, count = 0, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
+  std::vector<ResRun> runs;
+  std::vector<int> run_at;             // per block: index of the run that starts (forward) at this block, else -1
+  std::vector<int> run_end_at;         // per block: index of the run that ends at this block, else -1
+  std::vector<ResBlock> res_blocks;
+  size_t res_off = 0, abort_off = 0;   // global regions
+  size_t xchg_off = 0, tag_off = 0;    // per-micro-batch region
 };
 
 hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
@@ -261,6 +270,58 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   }
   P.tickets_off = alloc(64 * sizeof(unsigned)).off;
   for (int i = 0; i < 4; ++i) P.scratch_off[i] = alloc(max_elems * P.esz).off;
+
+  // ---- image-resident runs: maximal sequences of identity bottleneck blocks of one shape
+  P.run_at.assign(d.n_blocks, -1);
+  P.run_end_at.assign(d.n_blocks, -1);
+  if (P.dt == DT_BF16 && d.bn_mode == 0) {
+    auto eligible = [&](int i) {
+      const BlockPlan& p = P.bp[i];
+      return p.d.kind == 1 && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
+    };
+    int cmax_run = 0;
+    for (int i = 0; i < d.n_blocks;) {
+      if (!eligible(i)) { ++i; continue; }
+      int j = i + 1;
+      while (j < d.n_blocks && eligible(j) && P.bp[j].d.c_in == P.bp[i].d.c_in && P.bp[j].d.c_mid == P.bp[i].d.c_mid) ++j;
+      Plan::ResRun r;
+      r.first = i; r.count = j - i; r.C = P.bp[i].d.c_in; r.MID = P.bp[i].d.c_mid;
+      r.table_off = P.res_blocks.size() * sizeof(ResBlock);   // made absolute below
+      auto res_loc = [](const Loc& l) -> unsigned long long {
+        switch (l.kind) {
+          case IN_MB: return l.off;
+          case CALLER_ACT_IN: return RES_ACT_IN;
+          case CALLER_ACT_OUT: return RES_ACT_OUT;
+          case CALLER_ERR_IN: return RES_ERR_IN;
+          default: return RES_ERR_OUT;
+        }
+      };
+      for (int k = i; k < j; ++k) {
+        const BlockPlan& p = P.bp[k];
+        ResBlock rb{};
+        rb.x_off = res_loc(p.x_in); rb.c1_off = res_loc(p.c[0]); rb.c2_off = res_loc(p.c[1]); rb.y_off = res_loc(p.y);
+        rb.gy_off = res_loc(p.gy); rb.dc1_off = res_loc(p.dc[0]); rb.dc2_off = res_loc(p.dc[1]);
+        Loc gx; gx.kind = CALLER_ERR_OUT;
+        if (k > 0) gx = P.bp[k - 1].gy; else if (d.has_stem) gx = P.g_stem;
+        rb.gx_off = res_loc(gx);
+        for (int q = 0; q < 3; ++q) {
+          rb.stats_off[q] = p.bn[q].stats_off;
+          rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off;
+          rb.gamma_off[q] = p.bn[q].g_off; rb.beta_off[q] = p.bn[q].b_off;
+        }
+        P.res_blocks.push_back(rb);
+      }
+      P.run_at[i] = (int)P.runs.size();
+      P.run_end_at[j - 1] = (int)P.runs.size();
+      P.runs.push_back(r);
+      if (r.C > cmax_run) cmax_run = r.C;
+      i = j;
+    }
+    if (!P.runs.empty()) {
+      P.xchg_off = alloc(resident_xchg_bytes(cmax_run, d.microbatch)).off;
+      P.tag_off = alloc(sizeof(unsigned)).off;
+    }
+  }
   P.mb_bytes = mo;
 
   // ---- deferred weight-gradient items (bf16 mode)
@@ -326,6 +387,9 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.packed_off = g; g += align_up(P.packed_elems * 2);
   P.table_off = g;  g += align_up(P.table.size() * sizeof(PackDesc));
   for (int k = 0; k < 9; ++k) { P.items_off[k] = g; g += align_up(P.items[k].size() * sizeof(WgradItem)); }
+  P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
+  for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
+  P.abort_off = g;  g += align_up(sizeof(int));
   P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
   P.arena_bytes = g;
   return HPF_OK;
@@ -343,7 +407,11 @@ struct GraphSlot {
 struct hpf_partition {
   Plan P;
   bool use_graphs = true;
-  bool fuse = true;   // bf16 mode: BN reductions in the convolution epilogues
+  // bf16 mode: 0 = every BatchNorm step a kernel of its own, 1 = BN reductions in the convolution epilogues and
+  // normalisation in the consuming convolutions, 2 = additionally image-resident kernels for runs of identity
+  // bottleneck blocks
+  int fuse = 2;
+  int res_group = 0;   // micro-batches one image-resident launch may hold on this device (0: path unavailable)
   std::vector<GraphSlot> g_fwd, g_bwd;
   char* arena = nullptr;
   std::vector<unsigned char> fwd_done, bwd_done;
@@ -358,6 +426,9 @@ struct hpf_partition {
   float* mom() const { return (float*)(arena + P.mom_off); }
   bf16_t* packed() const { return (bf16_t*)(arena + P.packed_off); }
   char* mb_base(int mb) const { return arena + P.mb_off + (size_t)mb * P.mb_bytes; }
+  int* abort_flag() const { return (int*)(arena + P.abort_off); }
+  bool resident() const { return fuse >= 2 && res_group >= 1 && !P.runs.empty(); }
+  int group_limit() const { return resident() ? res_group : MAX_GROUP; }
 };
 
 namespace {
@@ -389,7 +460,7 @@ struct Ctx {
   static PtrTab none() { return PtrTab{}; }
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
 
-  bool fused() const { return h->fuse && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
+  bool fused() const { return h->fuse >= 1 && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
 
   // part_rows > 0: the producing convolution already wrote that many statistics partial rows.
   // apply == false: only the statistics (the consuming convolutions normalise while staging)
@@ -477,6 +548,23 @@ struct Ctx {
     chk(launch_conv_f32(CONV_DGRAD, g, dy, h->params() + cv.w_off, dx, add, q, s), "conv_dgrad_f32");
     return 0;
   }
+  ResArgs res_args(const Plan::ResRun& r) const {
+    const Plan& P = h->P;
+    const BlockPlan& p0 = P.bp[r.first];
+    ResArgs a{};
+    a.blocks = (const ResBlock*)(h->arena + r.table_off);
+    a.nblk = r.count; a.nmem = P.d.microbatch; a.H = p0.h_in; a.W = p0.w_in; a.eps = P.d.bn_eps;
+    for (int i = 0; i < g; ++i) {
+      a.base.p[i] = h->mb_base(mb0 + i);
+      a.act_in.p[i] = const_cast<void*>(act_in[i]); a.act_out.p[i] = act_out[i];
+      a.err_in.p[i] = const_cast<void*>(err_in[i]); a.err_out.p[i] = err_out[i];
+    }
+    a.params = h->params(); a.packed = h->packed(); a.grads = h->grads();
+    a.xchg_off = P.xchg_off; a.tag_off = P.tag_off; a.abort_flag = h->abort_flag();
+    return a;
+  }
+  void res_forward(const Plan::ResRun& r) { chk(launch_resident_forward(g, r.C, r.MID, res_args(r), s), "resident_forward"); }
+  void res_backward(const Plan::ResRun& r) { chk(launch_resident_backward(g, r.C, r.MID, res_args(r), s), "resident_backward"); }
   void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {
     WgradGeom q{};
     q.b = h->P.d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cv.cin; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
@@ -492,9 +580,10 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
   int part_rows = 0;   // statistics partial rows pending for the next BatchNorm (written by the last conv)
+  const bool resident = c.h->resident();
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
-    const bool feeds_bn = !P.bp.empty() || P.d.has_head;
+    const bool feeds_bn = (!P.bp.empty() && !(resident && P.run_at[0] >= 0)) || (P.bp.empty() && P.d.has_head);
     if (P.dt == DT_BF16) {
       const PtrTab col = c.tab(P.stem_col);
       c.chk(launch_im2col3x3(c.g, c.tab(in), col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
@@ -505,6 +594,13 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     }
   }
   for (size_t bi = 0; bi < P.bp.size(); ++bi) {
+    if (resident && P.run_at[bi] >= 0) {   // the whole run in one launch; it takes its own statistics
+      const Plan::ResRun& r = P.runs[P.run_at[bi]];
+      c.res_forward(r);
+      bi += r.count - 1;
+      part_rows = 0;
+      continue;
+    }
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
@@ -516,7 +612,8 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     for (int j = 0; j < p.nconv; ++j) {
       const bool last = (j == p.nconv - 1);
       const PtrTab out = last ? y : c.tab(p.c[j]);
-      const bool feeds_bn = !last || bi + 1 < P.bp.size() || P.d.has_head;
+      const bool next_resident = resident && bi + 1 < P.bp.size() && P.run_at[bi + 1] >= 0;
+      const bool feeds_bn = !last || (bi + 1 < P.bp.size() && !next_resident) || (bi + 1 == P.bp.size() && P.d.has_head);
       part_rows = c.conv_fwd(p.cv[j], src, out, last ? shortcut : Ctx::none(), feeds_bn, pro ? &p.bn[j] : nullptr);
       if (!last) {
         c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows, !pro);
@@ -553,6 +650,12 @@ void run_backward(Ctx& c) {
     c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
+    if (c.h->resident() && P.run_end_at[ii] >= 0) {
+      const Plan::ResRun& r = P.runs[P.run_end_at[ii]];
+      c.res_backward(r);
+      ii = (size_t)r.first;
+      continue;
+    }
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab dy = c.tab(p.gy);
@@ -631,6 +734,39 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<cons
   return HPF_OK;
 }
 
+// Image-resident kernels need every work-group of a launch on the chip at once and take a CU each, so two
+// of them must never share the device: launches of this process are chained through one event.
+std::mutex g_res_mu;
+hipEvent_t g_res_ev = nullptr;
+bool g_res_recorded = false;
+
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  return s != nullptr && hipStreamIsCapturing(s, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+}
+hpf_status resident_enter(hpf_partition* p, hipStream_t s) {
+  if (!p->resident() || stream_is_capturing(s)) return HPF_OK;
+  std::lock_guard<std::mutex> lk(g_res_mu);
+  if (g_res_recorded && hipStreamWaitEvent(s, g_res_ev, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  return HPF_OK;
+}
+hpf_status resident_leave(hpf_partition* p, hipStream_t s) {
+  if (!p->resident() || stream_is_capturing(s)) return HPF_OK;
+  std::lock_guard<std::mutex> lk(g_res_mu);
+  if (!g_res_ev && hipEventCreateWithFlags(&g_res_ev, hipEventDisableTiming) != hipSuccess) return fail(HPF_EDEVICE, "hipEventCreate failed");
+  if (hipEventRecord(g_res_ev, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+  g_res_recorded = true;
+  return HPF_OK;
+}
+// An exchange between the work-groups of an image-resident launch timed out: the batch is invalid.
+hpf_status check_abort_flag(hpf_partition* p) {
+  if (p->P.runs.empty()) return HPF_OK;
+  int flag = 0;
+  if (hipMemcpy(&flag, p->abort_flag(), sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return fail(HPF_EDEVICE, "device-to-host copy failed");
+  if (flag) return fail(HPF_EDEVICE, "an image-resident launch timed out waiting for its partner work-groups");
+  return HPF_OK;
+}
+
 void begin_next_batch(hpf_partition* p, hipStream_t s) {
   std::fill(p->fwd_done.begin(), p->fwd_done.end(), 0);
   std::fill(p->bwd_done.begin(), p->bwd_done.end(), 0);
@@ -691,6 +827,16 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   for (int k = 0; k < 9; ++k)
     if (!P.items[k].empty())
       ok(hipMemcpy(p->arena + P.items_off[k], P.items[k].data(), P.items[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
+  if (!P.runs.empty()) {
+    ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
+    ok(hipMemset(p->abort_flag(), 0, sizeof(int)));
+    for (int i = 0; i < m; ++i) {
+      ok(hipMemset(p->mb_base(i) + P.xchg_off, 0, P.tag_off - P.xchg_off));
+      ok(hipMemset(p->mb_base(i) + P.tag_off, 0, sizeof(unsigned)));
+    }
+    p->res_group = resident_max_group(P.d.microbatch);
+    if (p->res_group >= 1) ok(resident_prepare());
+  }
   p->ev_fwd.resize(m); p->ev_bwd.resize(m);
   for (int i = 0; i < m; ++i) {
     ok(hipEventCreateWithFlags(&p->ev_fwd[i], hipEventDisableTiming));
@@ -735,8 +881,13 @@ hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t 
   }
   hipStream_t s = (hipStream_t)hip_stream;
   if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  for (int c0 = 0; c0 < count; c0 += MAX_GROUP) {
-    const int g = count - c0 < MAX_GROUP ? count - c0 : MAX_GROUP;
+  const int gmax = p->group_limit();
+  {
+    const hpf_status st = resident_enter(p, s);
+    if (st != HPF_OK) return st;
+  }
+  for (int c0 = 0; c0 < count; c0 += gmax) {
+    const int g = count - c0 < gmax ? count - c0 : gmax;
     Ctx c{p, mb_first + c0, g, s};
     PtrTab lab{};
     std::vector<const void*> key;
@@ -758,7 +909,7 @@ hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t 
       p->fwd_done[mb] = 1;
     }
   }
-  return HPF_OK;
+  return resident_leave(p, s);
 }
 
 hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in,
@@ -780,8 +931,13 @@ hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t
   hipStream_t s = (hipStream_t)hip_stream;
   for (int i = 0; i < count; ++i)
     if (hipStreamWaitEvent(s, p->ev_fwd[mb_first + i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  for (int c0 = 0; c0 < count; c0 += MAX_GROUP) {
-    const int g = count - c0 < MAX_GROUP ? count - c0 : MAX_GROUP;
+  const int gmax = p->group_limit();
+  {
+    const hpf_status st = resident_enter(p, s);
+    if (st != HPF_OK) return st;
+  }
+  for (int c0 = 0; c0 < count; c0 += gmax) {
+    const int g = count - c0 < gmax ? count - c0 : gmax;
     Ctx c{p, mb_first + c0, g, s};
     std::vector<const void*> key;
     key.push_back((const void*)(intptr_t)g);
@@ -801,7 +957,7 @@ hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t
       ++p->n_bwd;
     }
   }
-  return HPF_OK;
+  return resident_leave(p, s);
 }
 
 hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels, void* act_out,
@@ -833,7 +989,7 @@ hpf_status hpf_grad_accum_read(hpf_partition* p, float* dst, size_t n_floats, in
   if (hipMemcpyAsync(dst, p->grads(), n_floats * sizeof(float), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
     return fail(HPF_EDEVICE, "device-to-host copy failed: %s", hipGetErrorString(hipGetLastError()));
-  return HPF_OK;
+  return check_abort_flag(p);
 }
 
 hpf_status hpf_grad_accum_zero(hpf_partition* p, void* hip_stream) {
@@ -870,11 +1026,14 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable) {
 
 hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
   if (!p) return fail(HPF_EINVAL, "null handle");
-  if (p->fuse != (enable != 0)) {   // cached graphs hold the other kernel sequence
+  if (enable < 0 || enable > 2) return fail(HPF_EINVAL, "fusion level %d (0, 1 or 2)", enable);
+  for (int i = 0; i < p->P.d.num_microbatches; ++i)
+    if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
+  if (p->fuse != enable) {   // cached graphs hold the other kernel sequence
     for (GraphSlot& g : p->g_fwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
     for (GraphSlot& g : p->g_bwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
   }
-  p->fuse = enable != 0;
+  p->fuse = enable;
   return HPF_OK;
 }
 
@@ -884,7 +1043,7 @@ hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {
   if (hipDeviceSynchronize() != hipSuccess ||
       hipMemcpy(host_dst, p->params(), n_floats * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
     return fail(HPF_EDEVICE, "device-to-host copy failed");
-  return HPF_OK;
+  return check_abort_flag(p);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -1,0 +1,734 @@
+// Image-resident forward and backward kernels for runs of identity bottleneck blocks (bf16 mode).
+//
+// A partition of a deep pre-activation ResNet (paper Section "Model Generator" / Table of models:
+// ResNet-110 ... ResNet-1001) is mostly a long run of identical blocks at one resolution.  At CIFAR
+// resolutions a whole image of the residual stream fits in one CU's LDS (16x16x128 bf16 = 64 KiB), so
+// one work-group keeps "its" image resident for the whole run: per block it only reads the weights and
+// writes what back-propagation needs later (the BatchNorm inputs c1, c2, y).  The backward kernel walks
+// the run in reverse with the gradient of the residual stream resident instead.
+//
+// BatchNorm uses the statistics of the micro-batch, so the work-groups of one micro-batch exchange small
+// per-image records three times per block and direction.  The exchange is an all-gather through device
+// memory in which every float travels in one 8-byte word together with the tag of its phase: the words
+// are written and polled with single-copy-atomic device-scope accesses, so a reader that sees the tag
+// has the value, and no cache write-back or invalidate is needed.  Merges run in a fixed order in every
+// work-group, so all of them derive bit-identical statistics.
+//
+// All work-groups of a micro-batch must be on the chip together; the launchers check the grid against
+// the number of CUs, and a bounded spin turns a missing partner into an error flag instead of a hang.
+#include <hip/hip_runtime.h>
+
+#include "hpf_device.h"
+
+namespace hpf {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+constexpr int RES_NT = 512;            // threads per work-group (8 waves)
+constexpr int RES_NWV = RES_NT / 64;
+constexpr unsigned RES_SPIN_LIMIT = 1u << 19;
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// {scale, shift} of a BatchNorm channel: bn(x) = x*scale + shift
+__device__ __forceinline__ float2 bn_scale_shift(float mean, float invstd, float gamma, float beta) {
+  const float sc = gamma * invstd;
+  return make_float2(sc, fmaf(-mean, sc, beta));
+}
+
+// ---- tiles: a [P][Cc] bf16 image in LDS has row stride Cc + 8 (16-byte reads of 16 consecutive rows hit distinct banks)
+template <int Cc>
+__device__ __forceinline__ void tile_load(bf16_t* s, const bf16_t* g, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    *reinterpret_cast<uint4*>(s + row * (Cc + 8) + col * 8) = *reinterpret_cast<const uint4*>(g + (size_t)u * 8);
+  }
+}
+template <int Cc>
+__device__ __forceinline__ void tile_store(bf16_t* g, const bf16_t* s, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    *reinterpret_cast<uint4*>(g + (size_t)u * 8) = *reinterpret_cast<const uint4*>(s + row * (Cc + 8) + col * 8);
+  }
+}
+// in place: s = relu(s*scale + shift)
+template <int Cc>
+__device__ __forceinline__ void tile_bn_relu(bf16_t* s, const float2* coef, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    uint4* q = reinterpret_cast<uint4*>(s + row * (Cc + 8) + col * 8);
+    const uint4 v = *q;
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const float4* cf = reinterpret_cast<const float4*>(coef + col * 8);
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 k = cf[i];
+      r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(w[i]), k.z, k.w), 0.f));
+    }
+    *q = make_uint4(r[0], r[1], r[2], r[3]);
+  }
+}
+// Per-channel {mean, M2} of this image's tile -> mine[0..Cc) = mean, mine[Cc..2Cc) = M2.  Sums are taken
+// about the first pixel's value, so a large common offset does not cancel.  Ends with a barrier.
+template <int Cc>
+__device__ __forceinline__ void tile_stats(const bf16_t* s, int P, float* red, float* mine) {
+  constexpr int T = RES_NT / Cc;
+  const int c = threadIdx.x % Cc, q = threadIdx.x / Cc;
+  const float K = bf16_to_f32(s[c]);
+  float s1 = 0.f, s2 = 0.f;
+  for (int p = q; p < P; p += T) {
+    const float d = bf16_to_f32(s[p * (Cc + 8) + c]) - K;
+    s1 += d;
+    s2 = fmaf(d, d, s2);
+  }
+  red[q * Cc + c] = s1;
+  red[RES_NT + q * Cc + c] = s2;
+  __syncthreads();
+  if (threadIdx.x < Cc) {
+    float S1 = 0.f, S2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < T; ++i) { S1 += red[i * Cc + c]; S2 += red[RES_NT + i * Cc + c]; }
+    const float inv = 1.f / (float)P;
+    mine[c] = K + S1 * inv;
+    mine[Cc + c] = fmaxf(S2 - S1 * S1 * inv, 0.f);
+  }
+  __syncthreads();
+}
+
+// All `nmem` work-groups of a micro-batch publish `nw` floats (mine, in LDS) and collect everybody's in
+// gath[m*nw + w] (LDS).  Returns false, uniformly over the work-group, when a partner did not show up.
+__device__ __forceinline__ bool exchange(u64* slot, int me, int nmem, int nw, const float* mine, unsigned tag, float* gath,
+                                         int* abort_flag) {
+  for (int w = threadIdx.x; w < nw; w += RES_NT)
+    __hip_atomic_store(slot + (size_t)me * nw + w, ((u64)tag << 32) | (u64)__float_as_uint(mine[w]), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  const int total = nmem * nw;
+  int timed_out = 0;
+  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * 8) {
+    u64 v[8];
+    unsigned pending = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (i0 + i * RES_NT < total) pending |= 1u << i;
+    unsigned spins = 0;
+    while (pending) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (pending >> i & 1u) v[i] = __hip_atomic_load(slot + i0 + i * RES_NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if ((pending >> i & 1u) && (unsigned)(v[i] >> 32) == tag) {
+          pending &= ~(1u << i);
+          gath[i0 + i * RES_NT] = __uint_as_float((unsigned)v[i]);
+        }
+      if (pending && ++spins > RES_SPIN_LIMIT) { timed_out = 1; pending = 0; }
+    }
+  }
+  const int any = __syncthreads_or(timed_out);
+  if (any && threadIdx.x == 0) atomicExch(abort_flag, 1);
+  return any == 0;
+}
+
+// Gathered per-image {mean, M2} (equal pixel counts) -> micro-batch mean / invstd -> coef[c] = {scale, shift}.
+// The same arithmetic in the same order in every work-group; stats_out (member 0 only) receives
+// {mean(Cc), invstd(Cc)} for the backward pass and the weight gradients.  Ends with a barrier.
+template <int Cc>
+__device__ __forceinline__ void merge_stats(const float* gath, int nmem, int P, float eps, const float* gamma, const float* beta,
+                                            float2* coef, float* stats_out, float* red) {
+  constexpr int T = RES_NT / Cc;
+  const int c = threadIdx.x % Cc, q = threadIdx.x / Cc;
+  float s = 0.f;
+  for (int m = q; m < nmem; m += T) s += gath[m * 2 * Cc + c];
+  red[q * Cc + c] = s;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < T; ++i) tot += red[i * Cc + c];
+  const float mean = tot / (float)nmem;
+  float s2 = 0.f;
+  for (int m = q; m < nmem; m += T) {
+    const float d = gath[m * 2 * Cc + c] - mean;
+    s2 += gath[m * 2 * Cc + Cc + c] + (float)P * d * d;
+  }
+  red[RES_NT + q * Cc + c] = s2;
+  __syncthreads();
+  if (threadIdx.x < Cc) {
+    float m2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < T; ++i) m2 += red[RES_NT + i * Cc + c];
+    const float var = m2 / ((float)nmem * (float)P);
+    const float is = 1.0f / sqrtf(var + eps);
+    coef[c] = bn_scale_shift(mean, is, gamma[c], beta[c]);
+    if (stats_out) { stats_out[c] = mean; stats_out[Cc + c] = is; }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ bf16x8 frag_bn_relu(const uint4& q, const float2 (&cf)[8]) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  uint32_t r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), cf[2 * i].x, cf[2 * i].y), 0.f),
+                       fmaxf(fmaf(bf_hi(w[i]), cf[2 * i + 1].x, cf[2 * i + 1].y), 0.f));
+  return __builtin_bit_cast(bf16x8, make_uint4(r[0], r[1], r[2], r[3]));
+}
+__device__ __forceinline__ bf16x8 frag_zero() { return __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, 0u, 0u)); }
+__device__ __forceinline__ uint2 pack4(const floatx4& v) { return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])); }
+__device__ __forceinline__ float elem4(const uint2& q, int e) {
+  return e == 0 ? bf_lo(q.x) : e == 1 ? bf_hi(q.x) : e == 2 ? bf_lo(q.y) : bf_hi(q.y);
+}
+__device__ __forceinline__ float sum16(float v) {   // over the 16 lanes that hold the 16 pixels of a tile
+  v += __shfl_xor(v, 1);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 8);
+  return v;
+}
+
+struct ResCtx {
+  char* base; void* act_in; void* act_out; void* err_in; void* err_out;
+  __device__ __forceinline__ bf16_t* tensor(unsigned long long off) const {
+    void* p = base + off;
+    p = off == RES_ACT_IN ? act_in : p;
+    p = off == RES_ACT_OUT ? act_out : p;
+    p = off == RES_ERR_IN ? err_in : p;
+    p = off == RES_ERR_OUT ? err_out : p;
+    return (bf16_t*)p;
+  }
+};
+
+// 3x3 convolution (stride 1, zero padding) of a [P][MID] tile in LDS, both directions:
+//   forward : out(p,q) += src(p+r-1, q+s-1) * W[r][s]       weights [MID][9*MID], k = tap*MID + c
+//   backward: out(p,q) += src(p+1-r, q+1-s) * W[r][s]^T     weights [MID][9*MID], k = tap*MID + n
+template <int MID, int PTW, bool BACKWARD>
+__device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const bf16_t* w, int H, int W, int npt, int wave, int fr, int fk,
+                                             floatx4 (&acc)[PTW][MID / 16]) {
+  constexpr int MS = MID + 8, K2 = 9 * MID;
+  int py[PTW], px[PTW];
+#pragma unroll
+  for (int j = 0; j < PTW; ++j) {
+    const int p = (wave + j * RES_NWV) * 16 + fr;
+    py[j] = p / W;
+    px[j] = p - py[j] * W;
+  }
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap) {
+    const int r = tap / 3, s = tap % 3;
+    const int dh = BACKWARD ? 1 - r : r - 1, dw = BACKWARD ? 1 - s : s - 1;
+#pragma unroll
+    for (int ks = 0; ks < MID / 32; ++ks) {
+      bf16x8 wf[MID / 16];
+#pragma unroll
+      for (int nt = 0; nt < MID / 16; ++nt)
+        wf[nt] = *reinterpret_cast<const bf16x8*>(w + (size_t)(nt * 16 + fr) * K2 + tap * MID + ks * 32 + fk);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        if (wave + j * RES_NWV < npt) {
+          const int hs = py[j] + dh, ws = px[j] + dw;
+          const bool ok = (unsigned)hs < (unsigned)H && (unsigned)ws < (unsigned)W;
+          const int row = ok ? hs * W + ws : 0;
+          bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(src + row * MS + ks * 32 + fk);
+          if (!ok) bfrag = frag_zero();
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], bfrag, acc[j][nt], 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ forward
+// PTW: pixel tiles (16 pixels) per wave, i.e. images of up to 16*PTW*RES_NWV pixels
+template <int C, int MID, int PTW>
+__global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8, MS = MID + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int me = blockIdx.x, z = blockIdx.z;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sx = reinterpret_cast<bf16_t*>(smem);           // residual stream of the image, [P][XS]
+  bf16_t* smA = sx + (size_t)P * XS;                      // c1, then relu(bn2(c1))
+  bf16_t* smB = smA + (size_t)P * MS;                     // c2, then relu(bn3(c2))
+  float2* coefC = reinterpret_cast<float2*>(smB + (size_t)P * MS);
+  float2* coefM = coefC + C;
+  float* red = reinterpret_cast<float*>(coefM + MID);     // 2*RES_NT floats
+  float* mine = red + 2 * RES_NT;                         // 2*C floats
+  float* own = mine + 2 * C;                              // gather area of its own when the tiles are too small
+  float* gathA = gath_own ? own : reinterpret_cast<float*>(smA);
+  float* gathB = gath_own ? own : reinterpret_cast<float*>(smB);
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+
+  {
+    const ResBlock B0 = a.blocks[0];
+    tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
+    __syncthreads();
+    tile_stats<C>(sx, P, red, mine);
+    if (!exchange(slot(), me, a.nmem, 2 * C, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    ++phase;
+    merge_stats<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
+                   me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr, red);
+  }
+
+  for (int bi = 0; bi < a.nblk; ++bi) {
+    const ResBlock B = a.blocks[bi];
+    // ---- conv1 (1x1, C -> MID) on relu(bn1(x)), normalised while the operand is read from LDS
+    {
+      const bf16_t* w1 = a.packed + B.wf_off[0];   // [MID][C]
+      floatx4 acc[PTW][MID / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < C / 32; ++ks) {
+        float2 cf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cf[i] = coefC[ks * 32 + fk + i];
+        bf16x8 wf[MID / 16];
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(nt * 16 + fr) * C + ks * 32 + fk);
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+          if (pt < npt) {
+            const uint4 xv = *reinterpret_cast<const uint4*>(sx + (pt * 16 + fr) * XS + ks * 32 + fk);
+            const bf16x8 bfrag = frag_bn_relu(xv, cf);
+#pragma unroll
+            for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], bfrag, acc[j][nt], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt)
+            *reinterpret_cast<uint2*>(smA + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+      }
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);
+    tile_stats<MID>(smA, P, red, mine);
+    if (!exchange(slot(), me, a.nmem, 2 * MID, mine, tag0 + 1u + phase, gathB, a.abort_flag)) return;
+    ++phase;
+    merge_stats<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
+                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr, red);
+    tile_bn_relu<MID>(smA, coefM, P);
+    __syncthreads();
+    // ---- conv2 (3x3, MID -> MID)
+    {
+      floatx4 acc[PTW][MID / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<MID, PTW, false>(smA, a.packed + B.wf_off[1], a.H, a.W, npt, wave, fr, fk, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt)
+            *reinterpret_cast<uint2*>(smB + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+      }
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
+    tile_stats<MID>(smB, P, red, mine);
+    if (!exchange(slot(), me, a.nmem, 2 * MID, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    ++phase;
+    merge_stats<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
+                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr, red);
+    tile_bn_relu<MID>(smB, coefM, P);
+    __syncthreads();
+    // ---- conv3 (1x1, MID -> C) + residual: y = x + branch, written over x in LDS
+    {
+      const bf16_t* w3 = a.packed + B.wf_off[2];   // [C][MID]
+      bf16x8 bfrag[PTW][MID / 32];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+#pragma unroll
+        for (int ks = 0; ks < MID / 32; ++ks)
+          bfrag[j][ks] = pt < npt ? *reinterpret_cast<const bf16x8*>(smB + (pt * 16 + fr) * MS + ks * 32 + fk) : frag_zero();
+      }
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt) {
+        bf16x8 wf[MID / 32];
+#pragma unroll
+        for (int ks = 0; ks < MID / 32; ++ks) wf[ks] = *reinterpret_cast<const bf16x8*>(w3 + (size_t)(nt * 16 + fr) * MID + ks * 32 + fk);
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+          if (pt < npt) {
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < MID / 32; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], bfrag[j][ks], acc, 0, 0, 0);
+            uint2* q = reinterpret_cast<uint2*>(sx + (pt * 16 + fr) * XS + nt * 16 + fq * 4);
+            const uint2 xr = *q;
+            acc[0] += bf_lo(xr.x); acc[1] += bf_hi(xr.x); acc[2] += bf_lo(xr.y); acc[3] += bf_hi(xr.y);
+            *q = pack4(acc);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+    if (bi + 1 < a.nblk) {
+      const ResBlock Bn = a.blocks[bi + 1];
+      tile_stats<C>(sx, P, red, mine);
+      if (!exchange(slot(), me, a.nmem, 2 * C, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+      ++phase;
+      merge_stats<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
+                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr, red);
+    }
+  }
+  // every member has read the counter before it took part in the first exchange, which member 0 has left
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
+// ------------------------------------------------------------------------------------------ backward
+// BatchNorm + ReLU backward on a gradient tile held in accumulator layout (lane: 4 channels of one pixel).
+//   dz = da * [z > 0];  sums over the micro-batch {sum dz, sum dz*xhat} (all-gather);
+//   out = scale * (dz - sum_dz/M - xhat * sum_dzxhat/M)
+// cf[c] = {scale, shift, invstd, -mean*invstd}; xin = the BatchNorm input at the same positions.
+// On return dz holds `out`.  Member 0 adds the sums into the gradients of beta and gamma.
+template <int Cc, int PTW>
+__device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf,
+                                                int npt, int wave, int fr, int fq, float* red, float* mine, float* sums, float* gath,
+                                                u64* slot, int me, int nmem, int P, unsigned tag, float* g_gamma, float* g_beta,
+                                                int* abort_flag) {
+  constexpr int NTL = Cc / 16;
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) {
+    float sb[4] = {0.f, 0.f, 0.f, 0.f}, sg[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      if (wave + j * RES_NWV < npt) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float4 k = cf[nt * 16 + fq * 4 + e];
+          const float v = elem4(xin[j][nt], e);
+          const float d = fmaf(v, k.x, k.y) > 0.f ? dz[j][nt][e] : 0.f;
+          dz[j][nt][e] = d;
+          sb[e] += d;
+          sg[e] = fmaf(d, fmaf(v, k.z, k.w), sg[e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float b = sum16(sb[e]), g = sum16(sg[e]);
+      if (fr == 0) {
+        red[wave * 2 * Cc + nt * 16 + fq * 4 + e] = b;
+        red[wave * 2 * Cc + Cc + nt * 16 + fq * 4 + e] = g;
+      }
+    }
+  }
+  __syncthreads();
+  for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RES_NWV; ++i) s += red[i * 2 * Cc + w];
+    mine[w] = s;
+  }
+  __syncthreads();
+  if (!exchange(slot, me, nmem, 2 * Cc, mine, tag, gath, abort_flag)) return false;
+  for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
+    float s = 0.f;
+    for (int m = 0; m < nmem; ++m) s += gath[m * 2 * Cc + w];
+    sums[w] = s;
+    if (me == 0) atomicAdd(w < Cc ? g_beta + w : g_gamma + (w - Cc), s);
+  }
+  __syncthreads();
+  const float invM = 1.f / ((float)nmem * (float)P);
+#pragma unroll
+  for (int j = 0; j < PTW; ++j) {
+    if (wave + j * RES_NWV < npt) {
+#pragma unroll
+      for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int c = nt * 16 + fq * 4 + e;
+          const float4 k = cf[c];
+          const float xh = fmaf(elem4(xin[j][nt], e), k.z, k.w);
+          dz[j][nt][e] = k.x * (dz[j][nt][e] - sums[c] * invM - xh * sums[Cc + c] * invM);
+        }
+    }
+  }
+  return true;
+}
+
+template <int Cc>
+__device__ __forceinline__ void load_bn_table(float4* cf, const float* stats, const float* gamma, const float* beta) {
+  for (int c = threadIdx.x; c < Cc; c += RES_NT) {
+    const float mean = stats[c], is = stats[Cc + c];
+    const float2 ss = bn_scale_shift(mean, is, gamma[c], beta[c]);
+    cf[c] = make_float4(ss.x, ss.y, is, -mean * is);
+  }
+}
+
+template <int C, int MID, int PTW>
+__global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8, MS = MID + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int me = blockIdx.x, z = blockIdx.z;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream, [P][XS]
+  bf16_t* sm1 = sdy + (size_t)P * XS;                     // c1
+  bf16_t* sm2 = sm1 + (size_t)P * MS;                     // c2, later dc1
+  bf16_t* sdc = sm2 + (size_t)P * MS;                     // dc2
+  float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * MS);
+  float4* cf2 = cf1 + C;
+  float4* cf3 = cf2 + MID;
+  float* red = reinterpret_cast<float*>(cf3 + MID);       // RES_NWV * 2*C floats
+  float* mine = red + RES_NWV * 2 * C;                    // 2*C
+  float* sums = mine + 2 * C;                             // 2*C
+  float* own = sums + 2 * C;
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+
+  {
+    const ResBlock BL = a.blocks[a.nblk - 1];
+    tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+  }
+  for (int bi = a.nblk - 1; bi >= 0; --bi) {
+    const ResBlock B = a.blocks[bi];
+    tile_load<MID>(sm2, cx.tensor(B.c2_off) + (size_t)me * P * MID, P);
+    tile_load<MID>(sm1, cx.tensor(B.c1_off) + (size_t)me * P * MID, P);
+    load_bn_table<C>(cf1, reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0], a.params + B.beta_off[0]);
+    load_bn_table<MID>(cf2, reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1], a.params + B.beta_off[1]);
+    load_bn_table<MID>(cf3, reinterpret_cast<const float*>(cx.base + B.stats_off[2]), a.params + B.gamma_off[2], a.params + B.beta_off[2]);
+    __syncthreads();
+    // ---- conv3 data gradient: da3[p][c] = sum_n dy[p][n] * W3[c][n]; then BN3 + ReLU backward -> dc2
+    {
+      const bf16_t* w3 = a.packed + B.wd_off[2];   // [MID][C]
+      floatx4 acc[PTW][MID / 16];
+      uint2 xin[PTW][MID / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < C / 32; ++ks) {
+        bf16x8 wf[MID / 16];
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(w3 + (size_t)(nt * 16 + fr) * C + ks * 32 + fk);
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+          if (pt < npt) {
+            const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(sdy + (pt * 16 + fr) * XS + ks * 32 + fk);
+#pragma unroll
+            for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], bfrag, acc[j][nt], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt)
+          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+      }
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
+      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag))
+        return;
+      ++phase;
+      __syncthreads();   // the gather area overlaps the tile written next
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt)
+            *reinterpret_cast<uint2*>(sdc + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+      }
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, sdc, P);
+    // ---- conv2 data gradient, BN2 + ReLU backward -> dc1 (into the tile that held c2)
+    {
+      floatx4 acc[PTW][MID / 16];
+      uint2 xin[PTW][MID / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<MID, PTW, true>(sdc, a.packed + B.wd_off[1], a.H, a.W, npt, wave, fr, fk, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt)
+          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+      }
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
+      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag))
+        return;
+      ++phase;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt)
+            *reinterpret_cast<uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+      }
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.dc1_off) + (size_t)me * P * MID, sm2, P);
+    // ---- conv1 data gradient, BN1 + ReLU backward, plus the shortcut: dx = bn1_bwd(...) + dy, written over dy
+    {
+      const bf16_t* w1 = a.packed + B.wd_off[0];   // [C][MID]
+      const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
+      floatx4 acc[PTW][C / 16];
+      uint2 xin[PTW][C / 16];
+      bf16x8 bfrag[PTW][MID / 32];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt)
+          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(xg + (size_t)(pt * 16 + fr) * C + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+#pragma unroll
+        for (int ks = 0; ks < MID / 32; ++ks)
+          bfrag[j][ks] = pt < npt ? *reinterpret_cast<const bf16x8*>(sm2 + (pt * 16 + fr) * MS + ks * 32 + fk) : frag_zero();
+      }
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt) {
+        bf16x8 wf[MID / 32];
+#pragma unroll
+        for (int ks = 0; ks < MID / 32; ++ks) wf[ks] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(nt * 16 + fr) * MID + ks * 32 + fk);
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < MID / 32; ++ks) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], bfrag[j][ks], acc[j][nt], 0, 0, 0);
+        }
+      }
+      __syncthreads();   // all waves are done with the small tiles: they become the gather area
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sm1);
+      if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                              a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag))
+        return;
+      ++phase;
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt) {
+            uint2* q = reinterpret_cast<uint2*>(sdy + (pt * 16 + fr) * XS + nt * 16 + fq * 4);
+            const uint2 d = *q;
+            floatx4 v = acc[j][nt];
+            v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
+            *q = pack4(v);
+          }
+      }
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
+// LDS bytes of the two kernels; *own = 1 when the gather area cannot overlay the small tiles
+size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
+  const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
+  const size_t fixed = (size_t)(C + MID) * 8 + 2 * RES_NT * 4 + 2 * (size_t)C * 4;
+  const size_t one_tile = (size_t)P * (MID + 8) * 2;
+  *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
+  return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
+}
+size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
+  const size_t tiles = (size_t)P * (C + 8) * 2 + 3 * (size_t)P * (MID + 8) * 2;
+  const size_t fixed = (size_t)(C + 2 * MID) * 16 + (size_t)RES_NWV * 2 * C * 4 + 4 * (size_t)C * 4;
+  const size_t one_tile = (size_t)P * (MID + 8) * 2;
+  *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
+  return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
+}
+
+constexpr size_t RES_LDS_BYTES = 160 * 1024 - 1024;   // LDS of a gfx950 CU, less room for the kernels' static allocations
+
+template <class K>
+hipError_t launch_res(K kernel, size_t lds, int own, int g, const ResArgs& a, hipStream_t stream) {
+  kernel<<<dim3((unsigned)a.nmem, 1, (unsigned)g), RES_NT, lds, stream>>>(a, own);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t resident_xchg_bytes(int C, int nmem) { return 2 * (size_t)nmem * 2 * C * sizeof(u64); }
+
+bool resident_shape_ok(int C, int MID, int H, int W, int nmem) {
+  if (!((C == 128 && MID == 32) || (C == 256 && MID == 64))) return false;
+  const int P = H * W;
+  if (H <= 0 || W <= 0 || P % 16 || P > 16 * (C == 128 ? 2 : 1) * RES_NWV) return false;
+  if (nmem < 1 || nmem > 1024) return false;
+  int own = 0;
+  return fwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES && bwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES;
+}
+
+int resident_max_group(int nmem) {
+  int dev = 0, cus = 0;
+  if (nmem < 1 || hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return 0;
+  const int g = cus / nmem;
+  return g > MAX_GROUP ? MAX_GROUP : g;
+}
+
+hipError_t resident_prepare() {
+  const int lds = (int)RES_LDS_BYTES;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<128, 32, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  return e;
+}
+
+hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
+  int own = 0;
+  const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
+  if (C == 128) return launch_res(k_res_forward<128, 32, 2>, lds, own, g, a, stream);
+  return launch_res(k_res_forward<256, 64, 1>, lds, own, g, a, stream);
+}
+
+hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
+  int own = 0;
+  const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
+  if (C == 128) return launch_res(k_res_backward<128, 32, 2>, lds, own, g, a, stream);
+  return launch_res(k_res_backward<256, 64, 1>, lds, own, g, a, stream);
+}
+
+}  // namespace hpf

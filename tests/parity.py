@@ -33,7 +33,7 @@ def device_inputs(spec, inp: W.StepInputs, mode: str):
 
 
 def run_gpu_step(spec, inp: W.StepInputs, mode: str, multi_stream=False, sgd=None, part=None, keep=False, grouped=False,
-                 fusion=True):
+                 fusion=2):
     import torch
     from paper_1911_05146_amd import hpf
     seen, t = device_inputs(spec, inp, mode)

@@ -26,7 +26,7 @@ def to64(inp):
 
 
 def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=True, strict=False, beta_shift=0.0,
-          seeds=1, grouped=False, fusion=True):
+          seeds=1, grouped=False, fusion=2):
     """GPU batch vs the oracle in the same precision reading (criterion A), falling back -- unless
     strict -- to the sensitivity-limited criterion B against the oracle in double (see parity.compare).
     seeds > 1 (strict bf16 cases only): a pre-activation within bf16 rounding of 0 may fall on either
@@ -43,9 +43,10 @@ def check(oracle, spec, mode, multi_stream=False, sgd=None, randomize_affine=Tru
             print(f"[retry] {spec.name}: {str(e)[:200]}", flush=True)
 
 
-def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False, fusion=True):
+def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False, fusion=2):
     from parity import compare, fmt, run_gpu_step
-    print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream} seed={spec.seed}", flush=True)
+    print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream} "
+          f"grouped={grouped} fusion={int(fusion)} seed={spec.seed}", flush=True)
     inp = W.make_inputs(spec, randomize_affine=randomize_affine)
     if beta_shift:
         for e in W.param_layout(spec):
@@ -87,6 +88,50 @@ def test_separate_bn_reduction_kernels_bf16(gpu, oracle):
     blk = W.Block(W.BOTTLENECK, 64, 32, 128, 2)
     spec = W.PartitionSpec(name="entry-unfused", in_h=16, in_w=16, in_c=64, blocks=(blk,), microbatch=2, num_microbatches=2, seed=21)
     check(oracle, spec, "bf16", strict=True, seeds=5, fusion=False)
+
+
+def _bottleneck_run(name, c, mid, hw, n, b, m, seed=31, **kw):
+    blk = W.Block(W.BOTTLENECK, c, mid, c, 1)
+    return W.PartitionSpec(name=name, in_h=hw, in_w=hw, in_c=c, blocks=(blk,) * n, microbatch=b, num_microbatches=m, seed=seed, **kw)
+
+
+def test_image_resident_runs_small(gpu, oracle):
+    """Runs of identity bottleneck blocks in the image-resident kernels (fusion level 2), in every shape class
+    the path covers.  With every pre-activation above 0 (beta + 6) no ReLU decision can differ and the run must
+    agree element by element; with ReLUs in play one block at a tiny micro-batch still must (a few seeds: see
+    check), longer runs fall under the same criteria as every other partition."""
+    cases = [
+        (_bottleneck_run("resident-128x32-16x16", 128, 32, 16, 2, 2, 2), False),
+        (_bottleneck_run("resident-128x32-8x8", 128, 32, 8, 2, 3, 2), False),
+        (_bottleneck_run("resident-128x32-8x8-grouped", 128, 32, 8, 3, 2, 3, seed=33), True),
+        (_bottleneck_run("resident-256x64-8x8", 256, 64, 8, 2, 2, 2), False),
+        (replace(_bottleneck_run("resident-128x32-8x16", 128, 32, 16, 2, 2, 2, seed=35), in_h=8), True),
+    ]
+    for spec, grouped in cases:
+        check(oracle, spec, "bf16", strict=True, beta_shift=6.0, grouped=grouped)
+        check(oracle, replace(spec, blocks=spec.blocks[:1], microbatch=1), "bf16", strict=True, seeds=5, grouped=grouped)
+        check(oracle, spec, "bf16", grouped=grouped)
+
+
+def test_image_resident_runs_deep_and_mixed(gpu, oracle):
+    """Deep runs (ReLU always active: element-wise; otherwise the sensitivity-limited criterion), runs between
+    other units (stem, projection blocks, head), runs split by a shape change, and groups of micro-batches."""
+    check(oracle, _bottleneck_run("resident-deep-active", 128, 32, 16, 21, 8, 2), "bf16", beta_shift=6.0, grouped=True)
+    check(oracle, _bottleneck_run("resident-deep", 128, 32, 16, 21, 8, 3), "bf16", grouped=True)
+    blocks = (W.Block(W.BOTTLENECK, 64, 32, 128, 2),) + (W.Block(W.BOTTLENECK, 128, 32, 128, 1),) * 3 + \
+             (W.Block(W.BOTTLENECK, 128, 64, 256, 2),) + (W.Block(W.BOTTLENECK, 256, 64, 256, 1),) * 2
+    mixed = W.PartitionSpec(name="resident-mixed-stem-head", in_h=32, in_w=32, in_c=3, has_stem=True, stem_c_out=64, blocks=blocks,
+                            has_head=True, num_classes=10, microbatch=4, num_microbatches=3, seed=37)
+    check(oracle, mixed, "bf16", sgd=(0.1, 0.9))
+    check(oracle, mixed, "bf16", grouped=True)
+    check(oracle, replace(mixed, name="resident-mixed-level1"), "bf16", fusion=1)
+
+
+def test_fusion_levels_agree_on_the_benchmark_partition(gpu, oracle):
+    """The three kernel schedules are three bf16 evaluations of the same batch."""
+    spec = W.with_microbatching(W.config(3), 32, 2, loss_divisor=256)
+    for level in (0, 1, 2):
+        check(oracle, spec, "bf16", fusion=level, grouped=(level == 2))
 
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
