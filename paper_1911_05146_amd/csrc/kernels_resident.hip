@@ -40,6 +40,23 @@ __device__ __forceinline__ float2 bn_scale_shift(float mean, float invstd, float
   return make_float2(sc, fmaf(-mean, sc, beta));
 }
 
+// Sums within a row of 16 lanes by DPP row rotations (one VALU instruction per step, no LDS round trip).
+// row_sum<N>(v): every lane gets the sum over the lanes of its row that are congruent to it modulo N.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int N>
+__device__ __forceinline__ float row_sum(float v) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "N divides 16");
+  if (N <= 8) v += dpp_mov<0x128>(v);   // row_ror:8
+  if (N <= 4) v += dpp_mov<0x124>(v);   // row_ror:4
+  if (N <= 2) v += dpp_mov<0x122>(v);   // row_ror:2
+  if (N <= 1) v += dpp_mov<0x121>(v);   // row_ror:1
+  return v;
+}
+__device__ __forceinline__ float sum16(float v) { return row_sum<1>(v); }   // over the 16 pixels of a tile
+
 // ---- tiles: a [P][Cc] bf16 image in LDS has row stride Cc + 8 (16-byte reads of 16 consecutive rows hit distinct banks)
 template <int Cc>
 __device__ __forceinline__ void tile_load(bf16_t* s, const bf16_t* g, int P) {
@@ -57,59 +74,13 @@ __device__ __forceinline__ void tile_store(bf16_t* g, const bf16_t* s, int P) {
     *reinterpret_cast<uint4*>(g + (size_t)u * 8) = *reinterpret_cast<const uint4*>(s + row * (Cc + 8) + col * 8);
   }
 }
-// in place: s = relu(s*scale + shift)
-template <int Cc>
-__device__ __forceinline__ void tile_bn_relu(bf16_t* s, const float2* coef, int P) {
-  constexpr int U = Cc / 8;
-  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
-    const int row = u / U, col = u - row * U;
-    uint4* q = reinterpret_cast<uint4*>(s + row * (Cc + 8) + col * 8);
-    const uint4 v = *q;
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    const float4* cf = reinterpret_cast<const float4*>(coef + col * 8);
-    uint32_t r[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float4 k = cf[i];
-      r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(w[i]), k.z, k.w), 0.f));
-    }
-    *q = make_uint4(r[0], r[1], r[2], r[3]);
-  }
+// All `nmem` work-groups of a micro-batch publish `nw` floats each and collect everybody's in
+// gath[m*nw + w] (LDS).  The two halves are separate so that independent work can fill the flight time.
+__device__ __forceinline__ void publish_word(u64* slot, int me, int nw, int w, float v, unsigned tag) {
+  __hip_atomic_store(slot + (size_t)me * nw + w, ((u64)tag << 32) | (u64)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Per-channel {mean, M2} of this image's tile -> mine[0..Cc) = mean, mine[Cc..2Cc) = M2.  Sums are taken
-// about the first pixel's value, so a large common offset does not cancel.  Ends with a barrier.
-template <int Cc>
-__device__ __forceinline__ void tile_stats(const bf16_t* s, int P, float* red, float* mine) {
-  constexpr int T = RES_NT / Cc;
-  const int c = threadIdx.x % Cc, q = threadIdx.x / Cc;
-  const float K = bf16_to_f32(s[c]);
-  float s1 = 0.f, s2 = 0.f;
-  for (int p = q; p < P; p += T) {
-    const float d = bf16_to_f32(s[p * (Cc + 8) + c]) - K;
-    s1 += d;
-    s2 = fmaf(d, d, s2);
-  }
-  red[q * Cc + c] = s1;
-  red[RES_NT + q * Cc + c] = s2;
-  __syncthreads();
-  if (threadIdx.x < Cc) {
-    float S1 = 0.f, S2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < T; ++i) { S1 += red[i * Cc + c]; S2 += red[RES_NT + i * Cc + c]; }
-    const float inv = 1.f / (float)P;
-    mine[c] = K + S1 * inv;
-    mine[Cc + c] = fmaxf(S2 - S1 * S1 * inv, 0.f);
-  }
-  __syncthreads();
-}
-
-// All `nmem` work-groups of a micro-batch publish `nw` floats (mine, in LDS) and collect everybody's in
-// gath[m*nw + w] (LDS).  Returns false, uniformly over the work-group, when a partner did not show up.
-__device__ __forceinline__ bool exchange(u64* slot, int me, int nmem, int nw, const float* mine, unsigned tag, float* gath,
-                                         int* abort_flag) {
-  for (int w = threadIdx.x; w < nw; w += RES_NT)
-    __hip_atomic_store(slot + (size_t)me * nw + w, ((u64)tag << 32) | (u64)__float_as_uint(mine[w]), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
+// Returns false, uniformly over the work-group, when a partner did not show up.  Ends with a barrier.
+__device__ __forceinline__ bool collect(const u64* slot, int nmem, int nw, unsigned tag, float* gath, int* abort_flag) {
   const int total = nmem * nw;
   int timed_out = 0;
   for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * 8) {
@@ -136,37 +107,39 @@ __device__ __forceinline__ bool exchange(u64* slot, int me, int nmem, int nw, co
   if (any && threadIdx.x == 0) atomicExch(abort_flag, 1);
   return any == 0;
 }
+__device__ __forceinline__ bool exchange(u64* slot, int me, int nmem, int nw, const float* mine, unsigned tag, float* gath,
+                                         int* abort_flag) {
+  for (int w = threadIdx.x; w < nw; w += RES_NT) publish_word(slot, me, nw, w, mine[w], tag);
+  return collect(slot, nmem, nw, tag, gath, abort_flag);
+}
 
 // Gathered per-image {mean, M2} (equal pixel counts) -> micro-batch mean / invstd -> coef[c] = {scale, shift}.
-// The same arithmetic in the same order in every work-group; stats_out (member 0 only) receives
-// {mean(Cc), invstd(Cc)} for the backward pass and the weight gradients.  Ends with a barrier.
+// The 32 rows of 16 lanes of the work-group take Cc/32 channels each, the lanes of a row split the members
+// and combine by row rotations: the same arithmetic in the same order in every work-group.  stats_out
+// (member 0 only) receives {mean(Cc), invstd(Cc)} for the backward pass and the weight gradients.
+// Ends with a barrier.
 template <int Cc>
-__device__ __forceinline__ void merge_stats(const float* gath, int nmem, int P, float eps, const float* gamma, const float* beta,
-                                            float2* coef, float* stats_out, float* red) {
-  constexpr int T = RES_NT / Cc;
-  const int c = threadIdx.x % Cc, q = threadIdx.x / Cc;
+__device__ __forceinline__ void merge_coef(const float* gath, int nmem, int P, float eps, const float* gamma, const float* beta,
+                                           float2* coef, float* stats_out) {
+  constexpr int CR = Cc / 32;        // channels per row
+  constexpr int MP = 16 / CR;        // member subsets per row
+  const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+  const int c = row * CR + l16 % CR, part = l16 / CR;
+  const float g = gamma[c], b = beta[c];
   float s = 0.f;
-  for (int m = q; m < nmem; m += T) s += gath[m * 2 * Cc + c];
-  red[q * Cc + c] = s;
-  __syncthreads();
-  float tot = 0.f;
-#pragma unroll
-  for (int i = 0; i < T; ++i) tot += red[i * Cc + c];
-  const float mean = tot / (float)nmem;
+  for (int m = part; m < nmem; m += MP) s += gath[m * 2 * Cc + c];
+  s = row_sum<CR>(s);
+  const float mean = s / (float)nmem;
   float s2 = 0.f;
-  for (int m = q; m < nmem; m += T) {
+  for (int m = part; m < nmem; m += MP) {
     const float d = gath[m * 2 * Cc + c] - mean;
     s2 += gath[m * 2 * Cc + Cc + c] + (float)P * d * d;
   }
-  red[RES_NT + q * Cc + c] = s2;
-  __syncthreads();
-  if (threadIdx.x < Cc) {
-    float m2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < T; ++i) m2 += red[RES_NT + i * Cc + c];
-    const float var = m2 / ((float)nmem * (float)P);
+  s2 = row_sum<CR>(s2);
+  if (part == 0) {
+    const float var = s2 / ((float)nmem * (float)P);
     const float is = 1.0f / sqrtf(var + eps);
-    coef[c] = bn_scale_shift(mean, is, gamma[c], beta[c]);
+    coef[c] = bn_scale_shift(mean, is, g, b);
     if (stats_out) { stats_out[c] = mean; stats_out[Cc + c] = is; }
   }
   __syncthreads();
@@ -186,14 +159,6 @@ __device__ __forceinline__ uint2 pack4(const floatx4& v) { return make_uint2(pac
 __device__ __forceinline__ float elem4(const uint2& q, int e) {
   return e == 0 ? bf_lo(q.x) : e == 1 ? bf_hi(q.x) : e == 2 ? bf_lo(q.y) : bf_hi(q.y);
 }
-__device__ __forceinline__ float sum16(float v) {   // over the 16 lanes that hold the 16 pixels of a tile
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
-  return v;
-}
-
 struct ResCtx {
   char* base; void* act_in; void* act_out; void* err_in; void* err_out;
   __device__ __forceinline__ bf16_t* tensor(unsigned long long off) const {
@@ -206,13 +171,39 @@ struct ResCtx {
   }
 };
 
+// Weight fragments of one GEMM as the first MFMA operand: fragment (kt, nt) holds rows nt*16..+15 and
+// k = kt*32..+31 of a row-major [rows][ld] bf16 matrix.  PRE = true keeps all fragments in registers, loaded
+// where load() is called (ahead of an exchange, so the memory latency hides behind the wait); PRE = false
+// fetches each fragment where it is used.
+template <int KT, int NT, bool PRE>
+struct WFrags;
+template <int KT, int NT>
+struct WFrags<KT, NT, true> {
+  bf16x8 r[KT][NT];
+  __device__ __forceinline__ void load(const bf16_t* w, int ld, int fr, int fk) {
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) r[kt][nt] = *reinterpret_cast<const bf16x8*>(w + (size_t)(nt * 16 + fr) * ld + kt * 32 + fk);
+  }
+  __device__ __forceinline__ bf16x8 get(int kt, int nt) const { return r[kt][nt]; }
+};
+template <int KT, int NT>
+struct WFrags<KT, NT, false> {
+  const bf16_t* w; int ld, fr, fk;
+  __device__ __forceinline__ void load(const bf16_t* w_, int ld_, int fr_, int fk_) { w = w_; ld = ld_; fr = fr_; fk = fk_; }
+  __device__ __forceinline__ bf16x8 get(int kt, int nt) const {
+    return *reinterpret_cast<const bf16x8*>(w + (size_t)(nt * 16 + fr) * ld + kt * 32 + fk);
+  }
+};
+
 // 3x3 convolution (stride 1, zero padding) of a [P][MID] tile in LDS, both directions:
 //   forward : out(p,q) += src(p+r-1, q+s-1) * W[r][s]       weights [MID][9*MID], k = tap*MID + c
 //   backward: out(p,q) += src(p+1-r, q+1-s) * W[r][s]^T     weights [MID][9*MID], k = tap*MID + n
-template <int MID, int PTW, bool BACKWARD>
-__device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const bf16_t* w, int H, int W, int npt, int wave, int fr, int fk,
+template <int MID, int PTW, bool BACKWARD, class WF>
+__device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const WF& wfr, int H, int W, int npt, int wave, int fr, int fk,
                                              floatx4 (&acc)[PTW][MID / 16]) {
-  constexpr int MS = MID + 8, K2 = 9 * MID;
+  constexpr int MS = MID + 8;
   int py[PTW], px[PTW];
 #pragma unroll
   for (int j = 0; j < PTW; ++j) {
@@ -228,8 +219,7 @@ __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const bf16_t* w,
     for (int ks = 0; ks < MID / 32; ++ks) {
       bf16x8 wf[MID / 16];
 #pragma unroll
-      for (int nt = 0; nt < MID / 16; ++nt)
-        wf[nt] = *reinterpret_cast<const bf16x8*>(w + (size_t)(nt * 16 + fr) * K2 + tap * MID + ks * 32 + fk);
+      for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = wfr.get(tap * (MID / 32) + ks, nt);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         if (wave + j * RES_NWV < npt) {
@@ -246,9 +236,76 @@ __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const bf16_t* w,
   }
 }
 
+// Per-channel {mean, M2} of this image's [P][Cc] tile, published as the work-group's record (words c and
+// Cc + c).  Sums are taken about the first pixel's value, so a large common offset does not cancel.
+// A row of 16 lanes reads one 16-byte unit (8 channels) of 16 consecutive pixels at a time and sums by row
+// rotations; the 32 rows of the work-group cover the U units of a pixel times 32/U pixel groups.
+template <int Cc>
+__device__ __forceinline__ void stats_publish(const bf16_t* s, int P, float* red, u64* slot, int me, unsigned tag) {
+  constexpr int U = Cc / 8;          // 16-byte units per pixel
+  constexpr int NG = 32 / U;         // pixel groups (of 16 pixels per step)
+  static_assert(U <= 32 && 32 % U == 0, "unit count");
+  const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+  const int unit = row % U, grp = row / U;
+  float K[8], s1[8], s2[8];
+  load8(s + unit * 8, K);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { s1[i] = 0.f; s2[i] = 0.f; }
+  for (int p = grp * 16 + l16; p < P; p += NG * 16) {
+    float v[8];
+    load8(s + p * (Cc + 8) + unit * 8, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float d = v[i] - K[i];
+      s1[i] += d;
+      s2[i] = fmaf(d, d, s2[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { s1[i] = row_sum<1>(s1[i]); s2[i] = row_sum<1>(s2[i]); }
+  if (l16 == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      red[grp * 2 * Cc + unit * 8 + i] = s1[i];
+      red[grp * 2 * Cc + Cc + unit * 8 + i] = s2[i];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < Cc) {
+    const int c = threadIdx.x;
+    float S1 = 0.f, S2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) { S1 += red[i * 2 * Cc + c]; S2 += red[i * 2 * Cc + Cc + c]; }
+    const float inv = 1.f / (float)P;
+    publish_word(slot, me, 2 * Cc, c, bf16_to_f32(s[c]) + S1 * inv, tag);
+    publish_word(slot, me, 2 * Cc, Cc + c, fmaxf(S2 - S1 * S1 * inv, 0.f), tag);
+  }
+}
+
+// in place: s = relu(s*scale + shift)
+template <int Cc>
+__device__ __forceinline__ void tile_bn_relu(bf16_t* s, const float2* coef, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    uint4* q = reinterpret_cast<uint4*>(s + row * (Cc + 8) + col * 8);
+    const uint4 v = *q;
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const float4* cf = reinterpret_cast<const float4*>(coef + col * 8);
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 k = cf[i];
+      r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(w[i]), k.z, k.w), 0.f));
+    }
+    *q = make_uint4(r[0], r[1], r[2], r[3]);
+  }
+}
+
 // ------------------------------------------------------------------------------------------ forward
-// PTW: pixel tiles (16 pixels) per wave, i.e. images of up to 16*PTW*RES_NWV pixels
-template <int C, int MID, int PTW>
+// PTW: pixel tiles (16 pixels) per wave, i.e. images of up to 16*PTW*RES_NWV pixels.
+// PRE: weight fragments are preloaded into registers ahead of the exchanges (needs the register room).
+template <int C, int MID, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -267,29 +324,33 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   bf16_t* smB = smA + (size_t)P * MS;                     // c2, then relu(bn3(c2))
   float2* coefC = reinterpret_cast<float2*>(smB + (size_t)P * MS);
   float2* coefM = coefC + C;
-  float* red = reinterpret_cast<float*>(coefM + MID);     // 2*RES_NT floats
-  float* mine = red + 2 * RES_NT;                         // 2*C floats
+  float* red = reinterpret_cast<float*>(coefM + MID);     // RES_NWV * 2*C floats
+  float* mine = red + RES_NWV * 2 * C;                    // 2*C floats
   float* own = mine + 2 * C;                              // gather area of its own when the tiles are too small
   float* gathA = gath_own ? own : reinterpret_cast<float*>(smA);
   float* gathB = gath_own ? own : reinterpret_cast<float*>(smB);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
+  WFrags<C / 32, MID / 16, PRE> w1;        // conv1 [MID][C]
+  WFrags<9 * MID / 32, MID / 16, PRE> w2;  // conv2 [MID][9*MID]
+  WFrags<MID / 32, C / 16, PRE> w3;        // conv3 [C][MID]
+
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
+    w1.load(a.packed + B0.wf_off[0], C, fr, fk);
     __syncthreads();
-    tile_stats<C>(sx, P, red, mine);
-    if (!exchange(slot(), me, a.nmem, 2 * C, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
+    if (!collect(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
     ++phase;
-    merge_stats<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
-                   me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr, red);
+    merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
+                  me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
   }
 
   for (int bi = 0; bi < a.nblk; ++bi) {
     const ResBlock B = a.blocks[bi];
     // ---- conv1 (1x1, C -> MID) on relu(bn1(x)), normalised while the operand is read from LDS
     {
-      const bf16_t* w1 = a.packed + B.wf_off[0];   // [MID][C]
       floatx4 acc[PTW][MID / 16];
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
@@ -302,7 +363,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
         for (int i = 0; i < 8; ++i) cf[i] = coefC[ks * 32 + fk + i];
         bf16x8 wf[MID / 16];
 #pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(nt * 16 + fr) * C + ks * 32 + fk);
+        for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = w1.get(ks, nt);
 #pragma unroll
         for (int j = 0; j < PTW; ++j) {
           const int pt = wave + j * RES_NWV;
@@ -323,14 +384,15 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
             *reinterpret_cast<uint2*>(smA + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
       }
     }
+    w2.load(a.packed + B.wf_off[1], 9 * MID, fr, fk);
     __syncthreads();
-    tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);
-    tile_stats<MID>(smA, P, red, mine);
-    if (!exchange(slot(), me, a.nmem, 2 * MID, mine, tag0 + 1u + phase, gathB, a.abort_flag)) return;
+    stats_publish<MID>(smA, P, red, slot(), me, tag0 + 1u + phase);
+    tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // while the records travel
+    if (!collect(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
     ++phase;
-    merge_stats<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
-                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr, red);
-    tile_bn_relu<MID>(smA, coefM, P);
+    merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    tile_bn_relu<MID>(smA, coefM, P);   // once, not per filter tap
     __syncthreads();
     // ---- conv2 (3x3, MID -> MID)
     {
@@ -339,7 +401,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<MID, PTW, false>(smA, a.packed + B.wf_off[1], a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<MID, PTW, false>(smA, w2, a.H, a.W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -349,38 +411,37 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
             *reinterpret_cast<uint2*>(smB + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
       }
     }
+    w3.load(a.packed + B.wf_off[2], MID, fr, fk);
     __syncthreads();
+    stats_publish<MID>(smB, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
-    tile_stats<MID>(smB, P, red, mine);
-    if (!exchange(slot(), me, a.nmem, 2 * MID, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    if (!collect(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
     ++phase;
-    merge_stats<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
-                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr, red);
-    tile_bn_relu<MID>(smB, coefM, P);
-    __syncthreads();
-    // ---- conv3 (1x1, MID -> C) + residual: y = x + branch, written over x in LDS
+    merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
+    // ---- conv3 (1x1, MID -> C) on relu(bn3(c2)) + residual: y = x + branch, written over x in LDS
     {
-      const bf16_t* w3 = a.packed + B.wf_off[2];   // [C][MID]
       bf16x8 bfrag[PTW][MID / 32];
 #pragma unroll
-      for (int j = 0; j < PTW; ++j) {
-        const int pt = wave + j * RES_NWV;
+      for (int ks = 0; ks < MID / 32; ++ks) {
+        float2 cf[8];
 #pragma unroll
-        for (int ks = 0; ks < MID / 32; ++ks)
-          bfrag[j][ks] = pt < npt ? *reinterpret_cast<const bf16x8*>(smB + (pt * 16 + fr) * MS + ks * 32 + fk) : frag_zero();
+        for (int i = 0; i < 8; ++i) cf[i] = coefM[ks * 32 + fk + i];
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+          bfrag[j][ks] = pt < npt ? frag_bn_relu(*reinterpret_cast<const uint4*>(smB + (pt * 16 + fr) * MS + ks * 32 + fk), cf) : frag_zero();
+        }
       }
 #pragma unroll
       for (int nt = 0; nt < C / 16; ++nt) {
-        bf16x8 wf[MID / 32];
-#pragma unroll
-        for (int ks = 0; ks < MID / 32; ++ks) wf[ks] = *reinterpret_cast<const bf16x8*>(w3 + (size_t)(nt * 16 + fr) * MID + ks * 32 + fk);
 #pragma unroll
         for (int j = 0; j < PTW; ++j) {
           const int pt = wave + j * RES_NWV;
           if (pt < npt) {
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < MID / 32; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], bfrag[j][ks], acc, 0, 0, 0);
+            for (int ks = 0; ks < MID / 32; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(ks, nt), bfrag[j][ks], acc, 0, 0, 0);
             uint2* q = reinterpret_cast<uint2*>(sx + (pt * 16 + fr) * XS + nt * 16 + fq * 4);
             const uint2 xr = *q;
             acc[0] += bf_lo(xr.x); acc[1] += bf_hi(xr.x); acc[2] += bf_lo(xr.y); acc[3] += bf_hi(xr.y);
@@ -389,15 +450,17 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
         }
       }
     }
+    const bool more = bi + 1 < a.nblk;
+    const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
+    if (more) w1.load(a.packed + Bn.wf_off[0], C, fr, fk);
     __syncthreads();
+    if (more) stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
-    if (bi + 1 < a.nblk) {
-      const ResBlock Bn = a.blocks[bi + 1];
-      tile_stats<C>(sx, P, red, mine);
-      if (!exchange(slot(), me, a.nmem, 2 * C, mine, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    if (more) {
+      if (!collect(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
-      merge_stats<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
-                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr, red);
+      merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
     }
   }
   // every member has read the counter before it took part in the first exchange, which member 0 has left
@@ -409,12 +472,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
 //   dz = da * [z > 0];  sums over the micro-batch {sum dz, sum dz*xhat} (all-gather);
 //   out = scale * (dz - sum_dz/M - xhat * sum_dzxhat/M)
 // cf[c] = {scale, shift, invstd, -mean*invstd}; xin = the BatchNorm input at the same positions.
-// On return dz holds `out`.  Member 0 adds the sums into the gradients of beta and gamma.
-template <int Cc, int PTW>
+// mid() runs once the gather area is free again (all sums taken), before the second pass; fin(j, nt, out)
+// receives the result tile by tile.  Member 0 adds the sums into the gradients of beta and gamma.
+template <int Cc, int PTW, class Mid, class Fin>
 __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf,
                                                 int npt, int wave, int fr, int fq, float* red, float* mine, float* sums, float* gath,
                                                 u64* slot, int me, int nmem, int P, unsigned tag, float* g_gamma, float* g_beta,
-                                                int* abort_flag) {
+                                                int* abort_flag, Mid&& mid, Fin&& fin) {
   constexpr int NTL = Cc / 16;
 #pragma unroll
   for (int nt = 0; nt < NTL; ++nt) {
@@ -441,6 +505,7 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
         red[wave * 2 * Cc + Cc + nt * 16 + fq * 4 + e] = g;
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // keeps the table reads of later tiles from piling up in registers
   }
   __syncthreads();
   for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
@@ -458,34 +523,81 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
     if (me == 0) atomicAdd(w < Cc ? g_beta + w : g_gamma + (w - Cc), s);
   }
   __syncthreads();
+  mid();
   const float invM = 1.f / ((float)nmem * (float)P);
 #pragma unroll
   for (int j = 0; j < PTW; ++j) {
     if (wave + j * RES_NWV < npt) {
 #pragma unroll
-      for (int nt = 0; nt < NTL; ++nt)
+      for (int nt = 0; nt < NTL; ++nt) {
+        floatx4 out;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int c = nt * 16 + fq * 4 + e;
           const float4 k = cf[c];
           const float xh = fmaf(elem4(xin[j][nt], e), k.z, k.w);
-          dz[j][nt][e] = k.x * (dz[j][nt][e] - sums[c] * invM - xh * sums[Cc + c] * invM);
+          out[e] = k.x * (dz[j][nt][e] - sums[c] * invM - xh * sums[Cc + c] * invM);
         }
+        fin(j, nt, out);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
   return true;
 }
 
-template <int Cc>
-__device__ __forceinline__ void load_bn_table(float4* cf, const float* stats, const float* gamma, const float* beta) {
-  for (int c = threadIdx.x; c < Cc; c += RES_NT) {
+// What the backward pass of one block reads from memory besides the weights, fetched into registers ahead
+// of use: the stashed c1 / c2 tiles and the BatchNorm tables.
+template <int C, int MID>
+struct BwdLoads {
+  static constexpr int NU = (256 * MID / 8 + RES_NT - 1) / RES_NT;   // 16-byte units per thread and tile, up to 256 pixels
+  uint4 c1[NU], c2[NU];
+  float4 t1, t2, t3;
+  __device__ __forceinline__ void issue(const ResBlock& B, const ResCtx& cx, const float* params, int me, int P) {
+    const bf16_t* g1 = cx.tensor(B.c1_off) + (size_t)me * P * MID;
+    const bf16_t* g2 = cx.tensor(B.c2_off) + (size_t)me * P * MID;
+    const int units = P * (MID / 8);
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      if (u < units) {
+        c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)u * 8);
+        c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)u * 8);
+      }
+    }
+    const int c = threadIdx.x;
+    if (c < C) t1 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), params + B.gamma_off[0], params + B.beta_off[0], c, C);
+    if (c < MID) {
+      t2 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), params + B.gamma_off[1], params + B.beta_off[1], c, MID);
+      t3 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[2]), params + B.gamma_off[2], params + B.beta_off[2], c, MID);
+    }
+  }
+  static __device__ __forceinline__ float4 table(const float* stats, const float* gamma, const float* beta, int c, int Cc) {
     const float mean = stats[c], is = stats[Cc + c];
     const float2 ss = bn_scale_shift(mean, is, gamma[c], beta[c]);
-    cf[c] = make_float4(ss.x, ss.y, is, -mean * is);
+    return make_float4(ss.x, ss.y, is, -mean * is);
   }
-}
+  __device__ __forceinline__ void commit_tiles(bf16_t* sm1, bf16_t* sm2, int P) const {
+    constexpr int U = MID / 8;
+    const int units = P * U;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      if (u < units) {
+        const int row = u / U, col = u - row * U;
+        *reinterpret_cast<uint4*>(sm1 + row * (MID + 8) + col * 8) = c1[i];
+        *reinterpret_cast<uint4*>(sm2 + row * (MID + 8) + col * 8) = c2[i];
+      }
+    }
+  }
+  __device__ __forceinline__ void commit_tables(float4* cf1, float4* cf2, float4* cf3) const {
+    const int c = threadIdx.x;
+    if (c < C) cf1[c] = t1;
+    if (c < MID) { cf2[c] = t2; cf3[c] = t3; }
+  }
+};
 
-template <int C, int MID, int PTW>
+template <int C, int MID, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -512,21 +624,25 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   float* own = sums + 2 * C;
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
+  WFrags<C / 32, MID / 16, PRE> w3;        // conv3 data gradient [MID][C]
+  WFrags<9 * MID / 32, MID / 16, PRE> w2;  // conv2 data gradient [MID][9*MID]
+  WFrags<MID / 32, C / 16, PRE> w1;        // conv1 data gradient [C][MID]
   {
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
   }
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
-    tile_load<MID>(sm2, cx.tensor(B.c2_off) + (size_t)me * P * MID, P);
-    tile_load<MID>(sm1, cx.tensor(B.c1_off) + (size_t)me * P * MID, P);
-    load_bn_table<C>(cf1, reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0], a.params + B.beta_off[0]);
-    load_bn_table<MID>(cf2, reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1], a.params + B.beta_off[1]);
-    load_bn_table<MID>(cf3, reinterpret_cast<const float*>(cx.base + B.stats_off[2]), a.params + B.gamma_off[2], a.params + B.beta_off[2]);
+    {   // one round trip to memory for everything the block reads up front
+      BwdLoads<C, MID> ld;
+      ld.issue(B, cx, a.params, me, P);
+      w3.load(a.packed + B.wd_off[2], C, fr, fk);
+      ld.commit_tiles(sm1, sm2, P);
+      ld.commit_tables(cf1, cf2, cf3);
+    }
     __syncthreads();
     // ---- conv3 data gradient: da3[p][c] = sum_n dy[p][n] * W3[c][n]; then BN3 + ReLU backward -> dc2
     {
-      const bf16_t* w3 = a.packed + B.wd_off[2];   // [MID][C]
       floatx4 acc[PTW][MID / 16];
       uint2 xin[PTW][MID / 16];
 #pragma unroll
@@ -535,16 +651,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < C / 32; ++ks) {
-        bf16x8 wf[MID / 16];
-#pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(w3 + (size_t)(nt * 16 + fr) * C + ks * 32 + fk);
 #pragma unroll
         for (int j = 0; j < PTW; ++j) {
           const int pt = wave + j * RES_NWV;
           if (pt < npt) {
             const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(sdy + (pt * 16 + fr) * XS + ks * 32 + fk);
 #pragma unroll
-            for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], bfrag, acc[j][nt], 0, 0, 0);
+            for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(ks, nt), bfrag, acc[j][nt], 0, 0, 0);
           }
         }
       }
@@ -555,24 +668,20 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         for (int nt = 0; nt < MID / 16; ++nt)
           xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
       }
+      w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag))
+                                     a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag, [] {},
+                                     [&](int j, int nt, const floatx4& out) {
+                                       *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
+                                     }))
         return;
       ++phase;
-      __syncthreads();   // the gather area overlaps the tile written next
-#pragma unroll
-      for (int j = 0; j < PTW; ++j) {
-        const int pt = wave + j * RES_NWV;
-        if (pt < npt)
-#pragma unroll
-          for (int nt = 0; nt < MID / 16; ++nt)
-            *reinterpret_cast<uint2*>(sdc + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
-      }
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, sdc, P);
     // ---- conv2 data gradient, BN2 + ReLU backward -> dc1 (into the tile that held c2)
+    uint2 x1[PTW][C / 16];   // the block input at this lane's positions, for the BN1 backward below
     {
       floatx4 acc[PTW][MID / 16];
       uint2 xin[PTW][MID / 16];
@@ -580,7 +689,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<MID, PTW, true>(sdc, a.packed + B.wd_off[1], a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<MID, PTW, true>(sdc, w2, a.H, a.W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -588,73 +697,63 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         for (int nt = 0; nt < MID / 16; ++nt)
           xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
       }
+      w1.load(a.packed + B.wd_off[0], MID, fr, fk);
+      {
+        const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt)
+            x1[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(xg + (size_t)(pt * 16 + fr) * C + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+        }
+      }
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag))
+                                     a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag, [] {},
+                                     [&](int j, int nt, const floatx4& out) {
+                                       *reinterpret_cast<uint2*>(sm2 + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
+                                     }))
         return;
       ++phase;
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < PTW; ++j) {
-        const int pt = wave + j * RES_NWV;
-        if (pt < npt)
-#pragma unroll
-          for (int nt = 0; nt < MID / 16; ++nt)
-            *reinterpret_cast<uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
-      }
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc1_off) + (size_t)me * P * MID, sm2, P);
     // ---- conv1 data gradient, BN1 + ReLU backward, plus the shortcut: dx = bn1_bwd(...) + dy, written over dy
     {
-      const bf16_t* w1 = a.packed + B.wd_off[0];   // [C][MID]
-      const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
       floatx4 acc[PTW][C / 16];
-      uint2 xin[PTW][C / 16];
       bf16x8 bfrag[PTW][MID / 32];
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
-#pragma unroll
-        for (int nt = 0; nt < C / 16; ++nt)
-          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(xg + (size_t)(pt * 16 + fr) * C + nt * 16 + fq * 4) : make_uint2(0u, 0u);
 #pragma unroll
         for (int ks = 0; ks < MID / 32; ++ks)
           bfrag[j][ks] = pt < npt ? *reinterpret_cast<const bf16x8*>(sm2 + (pt * 16 + fr) * MS + ks * 32 + fk) : frag_zero();
       }
 #pragma unroll
       for (int nt = 0; nt < C / 16; ++nt) {
-        bf16x8 wf[MID / 32];
-#pragma unroll
-        for (int ks = 0; ks < MID / 32; ++ks) wf[ks] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(nt * 16 + fr) * MID + ks * 32 + fk);
 #pragma unroll
         for (int j = 0; j < PTW; ++j) {
           acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ks = 0; ks < MID / 32; ++ks) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks], bfrag[j][ks], acc[j][nt], 0, 0, 0);
+          for (int ks = 0; ks < MID / 32; ++ks) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1.get(ks, nt), bfrag[j][ks], acc[j][nt], 0, 0, 0);
         }
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm1);
-      if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                              a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag))
+      if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag, [] {},
+                                   [&](int j, int nt, const floatx4& out) {
+                                     uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
+                                     const uint2 d = *q;
+                                     floatx4 v = out;
+                                     v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
+                                     *q = pack4(v);
+                                   }))
         return;
       ++phase;
-#pragma unroll
-      for (int j = 0; j < PTW; ++j) {
-        const int pt = wave + j * RES_NWV;
-        if (pt < npt)
-#pragma unroll
-          for (int nt = 0; nt < C / 16; ++nt) {
-            uint2* q = reinterpret_cast<uint2*>(sdy + (pt * 16 + fr) * XS + nt * 16 + fq * 4);
-            const uint2 d = *q;
-            floatx4 v = acc[j][nt];
-            v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
-            *q = pack4(v);
-          }
-      }
     }
-    __syncthreads();
+    __syncthreads();   // dx is complete; the BN tables and the small tiles of this block are no longer read
     tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
   }
   if (me == 0 && tid == 0) *tagp = tag0 + phase;
@@ -663,7 +762,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
 // LDS bytes of the two kernels; *own = 1 when the gather area cannot overlay the small tiles
 size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
-  const size_t fixed = (size_t)(C + MID) * 8 + 2 * RES_NT * 4 + 2 * (size_t)C * 4;
+  const size_t fixed = (size_t)(C + MID) * 8 + (size_t)RES_NWV * 2 * C * 4 + 2 * (size_t)C * 4;
   const size_t one_tile = (size_t)P * (MID + 8) * 2;
   *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
   return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
@@ -708,10 +807,10 @@ int resident_max_group(int nmem) {
 
 hipError_t resident_prepare() {
   const int lds = (int)RES_LDS_BYTES;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<128, 32, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
@@ -719,16 +818,16 @@ hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipS
   if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
-  if (C == 128) return launch_res(k_res_forward<128, 32, 2>, lds, own, g, a, stream);
-  return launch_res(k_res_forward<256, 64, 1>, lds, own, g, a, stream);
+  if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
+  return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
 hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
   if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
-  if (C == 128) return launch_res(k_res_backward<128, 32, 2>, lds, own, g, a, stream);
-  return launch_res(k_res_backward<256, 64, 1>, lds, own, g, a, stream);
+  if (C == 128) return launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
+  return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
 }  // namespace hpf
