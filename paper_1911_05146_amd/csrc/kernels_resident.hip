@@ -83,36 +83,28 @@ __device__ __forceinline__ void publish_word(u64* slot, int me, int nw, int w, f
 __device__ __forceinline__ bool collect(const u64* slot, int nmem, int nw, unsigned tag, float* gath, int* abort_flag) {
   const int total = nmem * nw;
   int timed_out = 0;
-  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * 8) {
+  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * 8) {   // up to 8 words in flight per thread
     u64 v[8];
-    unsigned pending = 0;
+    unsigned spins = 0;
+    for (;;) {
+      bool all = true;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (i0 + i * RES_NT < total) v[i] = __hip_atomic_load(slot + i0 + i * RES_NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (i0 + i * RES_NT < total) all = all && (unsigned)(v[i] >> 32) == tag;
+      if (all) break;
+      if (++spins > RES_SPIN_LIMIT) { timed_out = 1; break; }
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      if (i0 + i * RES_NT < total) pending |= 1u << i;
-    unsigned spins = 0;
-    while (pending) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (pending >> i & 1u) v[i] = __hip_atomic_load(slot + i0 + i * RES_NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if ((pending >> i & 1u) && (unsigned)(v[i] >> 32) == tag) {
-          pending &= ~(1u << i);
-          gath[i0 + i * RES_NT] = __uint_as_float((unsigned)v[i]);
-        }
-      if (pending && ++spins > RES_SPIN_LIMIT) { timed_out = 1; pending = 0; }
-    }
+      if (i0 + i * RES_NT < total) gath[i0 + i * RES_NT] = __uint_as_float((unsigned)v[i]);
   }
   const int any = __syncthreads_or(timed_out);
   if (any && threadIdx.x == 0) atomicExch(abort_flag, 1);
   return any == 0;
 }
-__device__ __forceinline__ bool exchange(u64* slot, int me, int nmem, int nw, const float* mine, unsigned tag, float* gath,
-                                         int* abort_flag) {
-  for (int w = threadIdx.x; w < nw; w += RES_NT) publish_word(slot, me, nw, w, mine[w], tag);
-  return collect(slot, nmem, nw, tag, gath, abort_flag);
-}
-
 // Gathered per-image {mean, M2} (equal pixel counts) -> micro-batch mean / invstd -> coef[c] = {scale, shift}.
 // The 32 rows of 16 lanes of the work-group take Cc/32 channels each, the lanes of a row split the members
 // and combine by row rotations: the same arithmetic in the same order in every work-group.  stats_out
@@ -470,76 +462,74 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
 // ------------------------------------------------------------------------------------------ backward
 // BatchNorm + ReLU backward on a gradient tile held in accumulator layout (lane: 4 channels of one pixel).
 //   dz = da * [z > 0];  sums over the micro-batch {sum dz, sum dz*xhat} (all-gather);
-//   out = scale * (dz - sum_dz/M - xhat * sum_dzxhat/M)
-// cf[c] = {scale, shift, invstd, -mean*invstd}; xin = the BatchNorm input at the same positions.
-// mid() runs once the gather area is free again (all sums taken), before the second pass; fin(j, nt, out)
-// receives the result tile by tile.  Member 0 adds the sums into the gradients of beta and gamma.
-template <int Cc, int PTW, class Mid, class Fin>
-__device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf,
-                                                int npt, int wave, int fr, int fq, float* red, float* mine, float* sums, float* gath,
+//   out = scale * (dz - sum_dz/M - xhat * sum_dzxhat/M)  =  a1*dz + a2*x + a3  with per-channel a1..a3
+// cf[c] = {scale, shift, invstd, -mean*invstd}; xin = the BatchNorm input at the same positions; tab = Cc
+// float4 of LDS for {a1, a2, a3}.  fin(j, nt, out) receives the result tile by tile.  Member 0 adds the sums
+// into the gradients of beta and gamma.
+template <int Cc, int PTW, class Fin>
+__device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf_,
+                                                int npt, int wave, int fr, int fq, float* red, float4* tab_, float* gath,
                                                 u64* slot, int me, int nmem, int P, unsigned tag, float* g_gamma, float* g_beta,
-                                                int* abort_flag, Mid&& mid, Fin&& fin) {
+                                                int* abort_flag, Fin&& fin) {
   constexpr int NTL = Cc / 16;
+  const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(cf_, 16));
+  float4* tab = reinterpret_cast<float4*>(__builtin_assume_aligned(tab_, 16));
 #pragma unroll
   for (int nt = 0; nt < NTL; ++nt) {
+    float4 k[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) k[e] = cf[nt * 16 + fq * 4 + e];
     float sb[4] = {0.f, 0.f, 0.f, 0.f}, sg[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < PTW; ++j) {
       if (wave + j * RES_NWV < npt) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float4 k = cf[nt * 16 + fq * 4 + e];
           const float v = elem4(xin[j][nt], e);
-          const float d = fmaf(v, k.x, k.y) > 0.f ? dz[j][nt][e] : 0.f;
+          const float d = fmaf(v, k[e].x, k[e].y) > 0.f ? dz[j][nt][e] : 0.f;
           dz[j][nt][e] = d;
           sb[e] += d;
-          sg[e] = fmaf(d, fmaf(v, k.z, k.w), sg[e]);
+          sg[e] = fmaf(d, fmaf(v, k[e].z, k[e].w), sg[e]);
         }
       }
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float b = sum16(sb[e]), g = sum16(sg[e]);
-      if (fr == 0) {
-        red[wave * 2 * Cc + nt * 16 + fq * 4 + e] = b;
-        red[wave * 2 * Cc + Cc + nt * 16 + fq * 4 + e] = g;
-      }
+    for (int e = 0; e < 4; ++e) { sb[e] = sum16(sb[e]); sg[e] = sum16(sg[e]); }
+    if (fr == 0) {
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + nt * 16 + fq * 4) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + Cc + nt * 16 + fq * 4) = make_float4(sg[0], sg[1], sg[2], sg[3]);
     }
-    __builtin_amdgcn_sched_barrier(0);   // keeps the table reads of later tiles from piling up in registers
   }
   __syncthreads();
   for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < RES_NWV; ++i) s += red[i * 2 * Cc + w];
-    mine[w] = s;
+    publish_word(slot, me, 2 * Cc, w, s, tag);
   }
-  __syncthreads();
-  if (!exchange(slot, me, nmem, 2 * Cc, mine, tag, gath, abort_flag)) return false;
-  for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
-    float s = 0.f;
-    for (int m = 0; m < nmem; ++m) s += gath[m * 2 * Cc + w];
-    sums[w] = s;
-    if (me == 0) atomicAdd(w < Cc ? g_beta + w : g_gamma + (w - Cc), s);
-  }
-  __syncthreads();
-  mid();
+  if (!collect(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
   const float invM = 1.f / ((float)nmem * (float)P);
+  for (int c = threadIdx.x; c < Cc; c += RES_NT) {
+    float sb = 0.f, sg = 0.f;
+    for (int m = 0; m < nmem; ++m) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
+    if (me == 0) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
+    const float4 k = cf[c];
+    // scale*(dz - sb/M - (x*is + nm)*sg/M)
+    tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
+  }
+  __syncthreads();
 #pragma unroll
-  for (int j = 0; j < PTW; ++j) {
-    if (wave + j * RES_NWV < npt) {
+  for (int nt = 0; nt < NTL; ++nt) {
+    float4 t[4];
 #pragma unroll
-      for (int nt = 0; nt < NTL; ++nt) {
+    for (int e = 0; e < 4; ++e) t[e] = tab[nt * 16 + fq * 4 + e];
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      if (wave + j * RES_NWV < npt) {
         floatx4 out;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int c = nt * 16 + fq * 4 + e;
-          const float4 k = cf[c];
-          const float xh = fmaf(elem4(xin[j][nt], e), k.z, k.w);
-          out[e] = k.x * (dz[j][nt][e] - sums[c] * invM - xh * sums[Cc + c] * invM);
-        }
+        for (int e = 0; e < 4; ++e) out[e] = fmaf(t[e].x, dz[j][nt][e], fmaf(t[e].y, elem4(xin[j][nt], e), t[e].z));
         fin(j, nt, out);
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -560,17 +550,14 @@ struct BwdLoads {
 #pragma unroll
     for (int i = 0; i < NU; ++i) {
       const int u = threadIdx.x + i * RES_NT;
-      if (u < units) {
-        c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)u * 8);
-        c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)u * 8);
-      }
+      const int uc = u < units ? u : 0;   // always a valid address; commit_tiles drops the surplus
+      c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
+      c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)uc * 8);
     }
     const int c = threadIdx.x;
-    if (c < C) t1 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), params + B.gamma_off[0], params + B.beta_off[0], c, C);
-    if (c < MID) {
-      t2 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), params + B.gamma_off[1], params + B.beta_off[1], c, MID);
-      t3 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[2]), params + B.gamma_off[2], params + B.beta_off[2], c, MID);
-    }
+    t1 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), params + B.gamma_off[0], params + B.beta_off[0], c < C ? c : 0, C);
+    t2 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), params + B.gamma_off[1], params + B.beta_off[1], c < MID ? c : 0, MID);
+    t3 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[2]), params + B.gamma_off[2], params + B.beta_off[2], c < MID ? c : 0, MID);
   }
   static __device__ __forceinline__ float4 table(const float* stats, const float* gamma, const float* beta, int c, int Cc) {
     const float mean = stats[c], is = stats[Cc + c];
@@ -619,9 +606,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   float4* cf2 = cf1 + C;
   float4* cf3 = cf2 + MID;
   float* red = reinterpret_cast<float*>(cf3 + MID);       // RES_NWV * 2*C floats
-  float* mine = red + RES_NWV * 2 * C;                    // 2*C
-  float* sums = mine + 2 * C;                             // 2*C
-  float* own = sums + 2 * C;
+  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);   // C float4: per-channel coefficients of a BN backward
+  float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
   WFrags<C / 32, MID / 16, PRE> w3;        // conv3 data gradient [MID][C]
@@ -670,8 +656,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       }
       w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
-      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                     a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag, [] {},
+      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                     a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag,
                                      [&](int j, int nt, const floatx4& out) {
                                        *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
                                      }))
@@ -709,8 +695,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         }
       }
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
-      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                     a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag, [] {},
+      if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                     a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag,
                                      [&](int j, int nt, const floatx4& out) {
                                        *reinterpret_cast<uint2*>(sm2 + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
                                      }))
@@ -741,8 +727,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm1);
-      if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, mine, sums, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag, [] {},
+      if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
                                      const uint2 d = *q;
