@@ -7,10 +7,11 @@ HBM: clear the gradient buffer, forward of all micro-batches, backward of all mi
 
     python bench.py [--steps K] [--warmup W] [--config 3]
 
-Prints ONE JSON line.  `roofline` describes the kernel that takes the largest share of the step
-(per-launch duration measured with HIP events on the launching stream, at the workload's shape,
-through the single-kernel entry points); `kernels` lists every kernel class of the step the same
-way; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line.  `roofline` describes the kernel class that takes the largest share of the
+step: its per-launch duration is measured with HIP events on the launching stream, in the launch
+configuration that was timed, by the library's profiling mode (ten more steps after the timed
+region); `kernels` lists every kernel class of the step the same way; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -27,99 +28,27 @@ PEAK_MFMA_BF16 = 2.5e15   # dense bf16 MFMA flop/s, MI355X
 PEAK_HBM = 8.0e12         # bytes/s
 
 
-def kernel_classes(spec):
-    """The step's kernel launches per micro-batch, grouped by (kind, shape): {key: count}.
-    Mirrors the library's schedule: per block bn-relu before every conv; conv fwd / dgrad / wgrad."""
-    from collections import Counter
-    c = Counter()
-    b = spec.microbatch
-    h, w = spec.in_h, spec.in_w
-    for blk in spec.blocks:
-        ho, wo = h // blk.stride, w // blk.stride
-        if blk.kind == 0:
-            convs = [(blk.c_in, blk.c_mid, 3, blk.stride, h, w), (blk.c_mid, blk.c_out, 3, 1, ho, wo)]
-        else:
-            convs = [(blk.c_in, blk.c_mid, 1, blk.stride, h, w), (blk.c_mid, blk.c_mid, 3, 1, ho, wo),
-                     (blk.c_mid, blk.c_out, 1, 1, ho, wo)]
-        if blk.has_proj:
-            convs.append((blk.c_in, blk.c_out, 1, blk.stride, h, w))
-        for i, (ci, co, R, st, hi, wi) in enumerate(convs):
-            if i < (2 if blk.kind == 0 else 3):
-                c[("bn", b * hi * wi, ci)] += 1
-            c[("conv", b, hi, wi, ci, co, R, st)] += 1
-        h, w = ho, wo
-    return c
+# HBM bytes per launch from rocprofv3 counter runs of this same command (FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the counter reads for a plain device copy of known size); the summaries with the
+# commands are under profiles/.  Keyed by (kernel class, configuration).
+MEASURED_TRAFFIC = {}
 
 
-def time_launches(torch, fn, iters=50, reps=6):
-    """Average GPU time (s) of one fn() call: `iters` calls are captured into a graph on a side stream
-    (so no host launch cost is in the figure) and the replays are bracketed by HIP events recorded on
-    that same stream."""
-    st = torch.cuda.Stream()
+def profile_classes(torch, part, step, steps=10):
+    """Per-kernel-class GPU time of the step in the launch configuration that was just timed: the library
+    brackets every class with HIP events on the launching stream (plain launches instead of graph replay
+    while it does).  Returns the library's entries with per-launch averages added."""
+    part.set_profiling(True)
+    for _ in range(steps):
+        step()
     torch.cuda.synchronize()
-    with torch.cuda.stream(st):
-        fn()
-        st.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=st):
-            for _ in range(iters):
-                fn()
-        g.replay()
-        st.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(st)
-        for _ in range(reps):
-            g.replay()
-        e1.record(st)
-        st.synchronize()
-    return e0.elapsed_time(e1) * 1e-3 / (iters * reps)
-
-
-def probe_kernels(torch, hpf, spec, m):
-    """Per-launch time of every kernel class at the workload's shapes.  Returns a list of dicts with
-    algorithmic flops / bytes per launch and launches per step."""
-    import numpy as np
-    ops = hpf.Ops(hpf.HPF_BF16)
-    dev = torch.device("cuda:0")
-    out = []
-    s = 2  # bytes per element
-    for key, cnt in sorted(kernel_classes(spec).items(), key=str):
-        if key[0] == "bn":
-            _, M, C = key
-            x = torch.randn(M, C, device=dev).to(torch.bfloat16)
-            da = torch.randn(M, C, device=dev).to(torch.bfloat16)
-            g = torch.ones(C, device=dev)
-            bt = torch.zeros(C, device=dev)
-            a, stats = ops.bn_relu_forward(x, g, bt)
-            dx = torch.empty_like(x)
-            t_f = time_launches(torch, lambda: ops.bn_relu_forward(x, g, bt, out=a))
-            t_b = time_launches(torch, lambda: ops.bn_relu_backward(x, da, g, bt, stats, out=dx))
-            # one call = 1 fill + 2 kernels; bytes: fwd 3*s*M*C (stats read, apply read+write), bwd 5*s*M*C
-            out.append(dict(kernel="bn_relu_fwd(stats+apply)", shape=[M, C], launches_per_step=cnt * m, sec=t_f,
-                            bytes=3 * s * M * C, flops=0, bound="hbm"))
-            out.append(dict(kernel="bn_relu_bwd(reduce+apply)", shape=[M, C], launches_per_step=cnt * m, sec=t_b,
-                            bytes=5 * s * M * C, flops=0, bound="hbm"))
-        else:
-            _, b, h, w, ci, co, R, st = key
-            x = torch.randn(b, h, w, ci, device=dev).to(torch.bfloat16)
-            wt = (torch.randn(R, R, ci, co, device=dev) * (2.0 / (R * R * ci)) ** 0.5)
-            y = ops.conv_forward(x, wt, st)
-            dy = torch.randn_like(y.float()).to(torch.bfloat16)
-            dx = ops.conv_dgrad(dy, wt, (h, w), st)
-            dw = ops.conv_wgrad(x, dy, R, st)
-            M, K, N = b * (h // st) * (w // st), R * R * ci, co
-            flops = 2.0 * M * K * N
-            byt = s * (b * h * w * ci + K * N + M * N)
-            # repack=False: the packed weight copies of the calls above are reused, one kernel per call
-            t_f = time_launches(torch, lambda: ops.conv_forward(x, wt, st, out=y, repack=False))
-            t_d = time_launches(torch, lambda: ops.conv_dgrad(dy, wt, (h, w), st, out=dx, repack=False))
-            t_w = time_launches(torch, lambda: ops.conv_wgrad(x, dy, R, st, out=dw))
-            shape = [M, K, N]
-            out.append(dict(kernel="conv_fwd", shape=shape, launches_per_step=cnt * m, sec=t_f, bytes=byt, flops=flops, bound="mfma"))
-            out.append(dict(kernel="conv_dgrad", shape=shape, launches_per_step=cnt * m, sec=t_d, bytes=byt, flops=flops, bound="mfma"))
-            out.append(dict(kernel="conv_wgrad", shape=shape, launches_per_step=cnt * m, sec=t_w,
-                            bytes=s * (b * h * w * ci + M * N) + 8 * K * N, flops=flops, bound="mfma"))
-    return out
+    entries = part.profile_read()
+    part.set_profiling(False)
+    for e in entries:
+        e["avg_sec"] = e["total_ms"] * 1e-3 / e["launches"]
+        e["launches_per_step"] = e["launches"] / steps
+        e["sec_per_step"] = e["total_ms"] * 1e-3 / steps
+    return entries
 
 
 def cpu_baseline(spec, inputs, max_microbatches=4):
@@ -150,7 +79,7 @@ def main():
                     help="grouped: all micro-batches of the batch in one group call per direction (default); "
                          "streams: one call and one stream per micro-batch; single-stream: one call per micro-batch, one stream")
     ap.add_argument("--no-graphs", action="store_true", help="plain kernel launches instead of HIP graph replay")
-    ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel probes")
+    ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel-class timing")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
@@ -241,24 +170,30 @@ def main():
     }
 
     if not args.no_probe:
-        ks = probe_kernels(torch, hpf, spec, m)
-        for k in ks:
-            k["share_sec_per_step"] = k["sec"] * k["launches_per_step"]
-        dom = max(ks, key=lambda k: k["share_sec_per_step"])
-        if dom["bound"] == "mfma":
-            ach, peak, unit = dom["flops"] / dom["sec"] / 1e12, PEAK_MFMA_BF16 / 1e12, "TFLOP/s"
+        ks = profile_classes(torch, part, step)
+        if sgd is None:
+            drain()
+        dom = max(ks, key=lambda k: k["sec_per_step"])
+        gbs = dom["bytes_per_launch"] / dom["avg_sec"] / 1e9
+        tfl = dom["flops_per_launch"] / dom["avg_sec"] / 1e12
+        # the roof the kernel is closer to
+        if dom["bytes_per_launch"] > 0 and gbs / (PEAK_HBM / 1e9) >= tfl / (PEAK_MFMA_BF16 / 1e12):
+            bound, ach, peak, unit = "hbm", gbs, PEAK_HBM / 1e9, "GB/s"
         else:
-            ach, peak, unit = dom["bytes"] / dom["sec"] / 1e9, PEAK_HBM / 1e9, "GB/s"
-        result["roofline"] = {"bound": dom["bound"], "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                              "traffic": None, "kernel": dom["kernel"], "shape": dom["shape"],
-                              "avg_launch_us": dom["sec"] * 1e6,
-                              "hbm_frac_of_same_kernel": dom["bytes"] / dom["sec"] / PEAK_HBM}
+            bound, ach, peak, unit = "mfma", tfl, PEAK_MFMA_BF16 / 1e12, "TFLOP/s"
+        result["roofline"] = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+                              "traffic": MEASURED_TRAFFIC.get((dom["name"], args.config)), "kernel": dom["name"],
+                              "avg_launch_us": dom["avg_sec"] * 1e6, "launches_per_step": dom["launches_per_step"],
+                              "algorithmic_bytes_per_launch": dom["bytes_per_launch"],
+                              "algorithmic_flops_per_launch": dom["flops_per_launch"],
+                              "share_of_step_gpu_time": dom["sec_per_step"] / sum(k["sec_per_step"] for k in ks)}
         result["kernels"] = [
-            {"kernel": k["kernel"], "shape": k["shape"], "launches_per_step": k["launches_per_step"],
-             "avg_us": round(k["sec"] * 1e6, 2),
-             "TFLOP/s": round(k["flops"] / k["sec"] / 1e12, 2) if k["flops"] else None,
-             "mfma_frac": round(k["flops"] / k["sec"] / PEAK_MFMA_BF16, 4) if k["flops"] else None,
-             "GB/s": round(k["bytes"] / k["sec"] / 1e9, 1), "hbm_frac": round(k["bytes"] / k["sec"] / PEAK_HBM, 4)}
+            {"kernel": k["name"], "launches_per_step": k["launches_per_step"], "avg_us": round(k["avg_sec"] * 1e6, 2),
+             "us_per_step": round(k["sec_per_step"] * 1e6, 1),
+             "TFLOP/s": round(k["flops_per_launch"] / k["avg_sec"] / 1e12, 2) if k["flops_per_launch"] else None,
+             "mfma_frac": round(k["flops_per_launch"] / k["avg_sec"] / PEAK_MFMA_BF16, 4) if k["flops_per_launch"] else None,
+             "GB/s": round(k["bytes_per_launch"] / k["avg_sec"] / 1e9, 1) if k["bytes_per_launch"] else None,
+             "hbm_frac": round(k["bytes_per_launch"] / k["avg_sec"] / PEAK_HBM, 4) if k["bytes_per_launch"] else None}
             for k in ks]
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(spec, inputs)

@@ -175,6 +175,27 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  * Not allowed while a micro-batch is between forward and backward (HPF_ESTATE). */
 hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
 
+/* Per-kernel-class timing, measured with HIP events on the stream the kernels are launched on.
+ * While enabled the passes run as plain launches (no graph replay) with an event pair around every
+ * segment of consecutive launches of one class; the classes are
+ *   "resident_forward" / "resident_backward"  one launch per run of bottleneck blocks and group,
+ *   "wgrad_grouped"                           the deferred weight-gradient launches (one per tile class),
+ *   "other_forward" / "other_backward"        every other kernel of the pass.
+ * hpf_partition_profile_read waits for the device, adds the finished segments to the totals kept
+ * since profiling was enabled, and writes up to `capacity` entries (classes with no launch are
+ * skipped); *count receives the number written.  bytes / flops are the algorithmic figures of the
+ * class per launch (each stashed tensor read or written once per pass, 2*M*K*N per contraction;
+ * 0 where the library keeps no figure). */
+typedef struct hpf_profile_entry {
+  char name[32];
+  int64_t launches;
+  double total_ms;
+  double bytes_per_launch;
+  double flops_per_launch;
+} hpf_profile_entry;
+hpf_status hpf_partition_set_profiling(hpf_partition* p, int32_t enable);
+hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entries, int32_t capacity, int32_t* count);
+
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
 

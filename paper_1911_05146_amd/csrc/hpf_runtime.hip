@@ -80,6 +80,7 @@ struct Plan {
   Loc g_stem;                          // gradient w.r.t. the stem output
   std::vector<WgradItem> items[9];     // deferred weight-gradient work, per tile class (bf16 mode)
   size_t items_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  double wg_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, wg_flops[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};   // per micro-batch
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
   std::vector<PackDesc> table;
@@ -355,6 +356,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       const int cls = wgrad_tile_class(w.cin_run, cv.cout);
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
+      P.wg_bytes[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
+      P.wg_flops[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
       int splits = (int)((1536 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
       const int max_splits = (q.M + 127) / 128;
       if (splits > max_splits) splits = max_splits;
@@ -397,6 +400,9 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
 }  // namespace
 
+enum ProfCat { PROF_NONE = -1, PROF_RES_FWD = 0, PROF_RES_BWD, PROF_WGRAD, PROF_OTHER_FWD, PROF_OTHER_BWD, PROF_N };
+const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward", "wgrad_grouped", "other_forward", "other_backward"};
+
 // One captured HIP graph of a micro-batch's forward or backward kernel sequence, valid for the caller
 // pointers it was captured with.
 struct GraphSlot {
@@ -412,6 +418,18 @@ struct hpf_partition {
   // bottleneck blocks
   int fuse = 2;
   int res_group = 0;   // micro-batches one image-resident launch may hold on this device (0: path unavailable)
+  // per-kernel-class timing
+  bool profiling = false;
+  struct ProfSeg { int cat; hipEvent_t e0, e1; int launches; double bytes, flops; };
+  std::vector<ProfSeg> prof_pending;
+  std::vector<hipEvent_t> ev_pool;
+  double prof_ms[PROF_N] = {}, prof_bytes[PROF_N] = {}, prof_flops[PROF_N] = {};
+  long long prof_launches[PROF_N] = {};
+  hipEvent_t prof_event() {
+    hipEvent_t e = nullptr;
+    if (!ev_pool.empty()) { e = ev_pool.back(); ev_pool.pop_back(); return e; }
+    return hipEventCreate(&e) == hipSuccess ? e : nullptr;
+  }
   std::vector<GraphSlot> g_fwd, g_bwd;
   char* arena = nullptr;
   std::vector<unsigned char> fwd_done, bwd_done;
@@ -440,6 +458,23 @@ struct Ctx {
   const void* act_in[MAX_GROUP]; void* act_out[MAX_GROUP]; const void* err_in[MAX_GROUP]; void* err_out[MAX_GROUP];
   hipError_t err = hipSuccess;
   const char* where = "";
+  hpf_partition::ProfSeg cur{PROF_NONE, nullptr, nullptr, 0, 0, 0};
+
+  // Profiling: launches from here on belong to class `cat` (a new segment starts even if the class repeats)
+  void seg(int cat, double bytes = 0, double flops = 0) {
+    if (!h->profiling) return;
+    seg_end();
+    cur = hpf_partition::ProfSeg{cat, h->prof_event(), h->prof_event(), 0, bytes, flops};
+    if (cur.e0) (void)hipEventRecord(cur.e0, s);
+  }
+  void seg_same(int cat) { if (h->profiling && cur.cat != cat) seg(cat); }
+  void seg_end() {
+    if (cur.cat == PROF_NONE) return;
+    if (cur.e1) (void)hipEventRecord(cur.e1, s);
+    if (cur.e0 && cur.e1 && cur.launches > 0) h->prof_pending.push_back(cur);
+    else { if (cur.e0) h->ev_pool.push_back(cur.e0); if (cur.e1) h->ev_pool.push_back(cur.e1); }
+    cur.cat = PROF_NONE;
+  }
 
   PtrTab tab(const Loc& l) const {
     PtrTab t{};
@@ -458,7 +493,10 @@ struct Ctx {
   PtrTab mbp(size_t off) const { Loc l; l.kind = IN_MB; l.off = off; return tab(l); }
   PtrTab scratch(int i) const { return mbp(h->P.scratch_off[i]); }
   static PtrTab none() { return PtrTab{}; }
-  void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
+  void chk(hipError_t e, const char* w) {
+    if (err == hipSuccess && e != hipSuccess) { err = e; where = w; }
+    if (cur.cat != PROF_NONE) ++cur.launches;
+  }
 
   bool fused() const { return h->fuse >= 1 && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
 
@@ -563,8 +601,23 @@ struct Ctx {
     a.xchg_off = P.xchg_off; a.tag_off = P.tag_off; a.abort_flag = h->abort_flag();
     return a;
   }
-  void res_forward(const Plan::ResRun& r) { chk(launch_resident_forward(g, r.C, r.MID, res_args(r), s), "resident_forward"); }
-  void res_backward(const Plan::ResRun& r) { chk(launch_resident_backward(g, r.C, r.MID, res_args(r), s), "resident_backward"); }
+  // algorithmic figures of a run: every stashed tensor once, data contractions only
+  void res_forward(const Plan::ResRun& r) {
+    const BlockPlan& p0 = h->P.bp[r.first];
+    const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
+    seg(PROF_RES_FWD, img * 2.0 * px * (r.C + r.count * (2.0 * r.MID + r.C)),
+        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
+    chk(launch_resident_forward(g, r.C, r.MID, res_args(r), s), "resident_forward");
+    seg_end();
+  }
+  void res_backward(const Plan::ResRun& r) {
+    const BlockPlan& p0 = h->P.bp[r.first];
+    const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
+    seg(PROF_RES_BWD, img * 2.0 * px * (r.C + r.count * (4.0 * r.MID + 2.0 * r.C)),
+        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
+    chk(launch_resident_backward(g, r.C, r.MID, res_args(r), s), "resident_backward");
+    seg_end();
+  }
   void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {
     WgradGeom q{};
     q.b = h->P.d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cv.cin; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
@@ -581,6 +634,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const size_t b = (size_t)P.d.microbatch;
   int part_rows = 0;   // statistics partial rows pending for the next BatchNorm (written by the last conv)
   const bool resident = c.h->resident();
+  c.seg_same(PROF_OTHER_FWD);
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
     const bool feeds_bn = (!P.bp.empty() && !(resident && P.run_at[0] >= 0)) || (P.bp.empty() && P.d.has_head);
@@ -601,6 +655,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
       part_rows = 0;
       continue;
     }
+    c.seg_same(PROF_OTHER_FWD);
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
@@ -623,12 +678,14 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   }
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
+    c.seg_same(PROF_OTHER_FWD);
     c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M, part_rows);
     c.chk(launch_head_fwd(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
                           c.tab(P.head_g), c.tab(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes,
                           (float)P.d.loss_divisor, c.s),
           "head_fwd");
   }
+  c.seg_end();
 }
 
 void run_backward(Ctx& c) {
@@ -642,6 +699,7 @@ void run_backward(Ctx& c) {
     if (i > 0) return P.bp[i - 1].gy;
     return P.d.has_stem ? P.g_stem : lout;
   };
+  c.seg_same(PROF_OTHER_BWD);
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
     c.chk(launch_head_bwd(P.dt, c.g, c.tab(P.head_g), c.tab(P.head_dl), c.h->params() + P.wfc_off, c.h->grads() + P.wfc_off,
@@ -656,6 +714,7 @@ void run_backward(Ctx& c) {
       ii = (size_t)r.first;
       continue;
     }
+    c.seg_same(PROF_OTHER_BWD);
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab dy = c.tab(p.gy);
@@ -677,6 +736,7 @@ void run_backward(Ctx& c) {
     const int rows0 = c.conv_dgrad(p.cv[0], dr, tA, p.proj ? tA : Ctx::none(), &p.bn[0], &x0);
     c.bn_bwd(p.bn[0], x0, tA, p.proj ? Ctx::none() : dy, c.tab(grad_in_loc(ii)), M_in, rows0);
   }
+  c.seg_same(PROF_OTHER_BWD);
   if (P.d.has_stem && !deferred) {
     Loc in; in.kind = CALLER_ACT_IN;
     c.conv_wgrad(P.stem, c.tab(in), c.tab(P.g_stem));
@@ -688,11 +748,15 @@ void run_backward(Ctx& c) {
       caller_dy.p[i] = const_cast<void*>(c.err_in[i]);
       caller_a.p[i] = const_cast<void*>(c.act_in[i]);
     }
-    for (int k = 0; k < 9; ++k)
+    for (int k = 0; k < 9; ++k) {
+      if (P.items[k].empty()) continue;
+      c.seg(PROF_WGRAD, c.g * P.wg_bytes[k], c.g * P.wg_flops[k]);
       c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + P.items_off[k]), (int)P.items[k].size(), bases, caller_dy,
                                  caller_a, c.h->params(), c.h->grads(), c.s),
             "wgrad_grouped");
+    }
   }
+  c.seg_end();
 }
 
 bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_microbatches; }
@@ -710,7 +774,7 @@ template <class Body>
 hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<const void*>& key, hipStream_t s, Ctx& c, Body body) {
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   // the default (NULL) stream cannot be captured
-  if (!p->use_graphs || s == nullptr || hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+  if (!p->use_graphs || p->profiling || s == nullptr || hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
     body();
     return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
   }
@@ -859,6 +923,8 @@ void hpf_partition_destroy(hpf_partition* p) {
   for (hipEvent_t ev : p->ev_fwd) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : p->ev_bwd) if (ev) (void)hipEventDestroy(ev);
   if (p->ev_step) (void)hipEventDestroy(p->ev_step);
+  for (auto& sg : p->prof_pending) { (void)hipEventDestroy(sg.e0); (void)hipEventDestroy(sg.e1); }
+  for (hipEvent_t ev : p->ev_pool) (void)hipEventDestroy(ev);
   for (GraphSlot& g : p->g_fwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   for (GraphSlot& g : p->g_bwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete p;
@@ -1035,6 +1101,42 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
   }
   p->fuse = enable;
   return HPF_OK;
+}
+
+hpf_status hpf_partition_set_profiling(hpf_partition* p, int32_t enable) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (enable && !p->profiling) {
+    for (int i = 0; i < PROF_N; ++i) { p->prof_ms[i] = 0; p->prof_bytes[i] = 0; p->prof_flops[i] = 0; p->prof_launches[i] = 0; }
+  }
+  p->profiling = enable != 0;
+  return HPF_OK;
+}
+
+hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entries, int32_t capacity, int32_t* count) {
+  if (!p || !entries || !count || capacity < 0) return fail(HPF_EINVAL, "bad argument");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(HPF_EDEVICE, "synchronize failed");
+  for (auto& sg : p->prof_pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, sg.e0, sg.e1) == hipSuccess) {
+      p->prof_ms[sg.cat] += ms; p->prof_launches[sg.cat] += sg.launches;
+      p->prof_bytes[sg.cat] += sg.bytes; p->prof_flops[sg.cat] += sg.flops;
+    }
+    p->ev_pool.push_back(sg.e0); p->ev_pool.push_back(sg.e1);
+  }
+  p->prof_pending.clear();
+  int n = 0;
+  for (int i = 0; i < PROF_N && n < capacity; ++i) {
+    if (p->prof_launches[i] == 0) continue;
+    hpf_profile_entry& e = entries[n++];
+    std::memset(&e, 0, sizeof(e));
+    std::strncpy(e.name, kProfNames[i], sizeof(e.name) - 1);
+    e.launches = p->prof_launches[i];
+    e.total_ms = p->prof_ms[i];
+    e.bytes_per_launch = p->prof_bytes[i] / (double)p->prof_launches[i];
+    e.flops_per_launch = p->prof_flops[i] / (double)p->prof_launches[i];
+  }
+  *count = n;
+  return check_abort_flag(p);
 }
 
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {

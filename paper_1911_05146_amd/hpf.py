@@ -67,6 +67,8 @@ def _load():
     L.hpf_partition_destroy.restype = None
     L.hpf_partition_set_graphs.argtypes = [vp, i32]
     L.hpf_partition_set_fusion.argtypes = [vp, i32]
+    L.hpf_partition_set_profiling.argtypes = [vp, i32]
+    L.hpf_partition_profile_read.argtypes = [vp, vp, i32, vp]
     L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
     L.hpf_op_workspace_bytes.restype = sz
     L.hpf_op_conv_forward.argtypes = [C.c_int, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, i32, vp]
@@ -83,6 +85,7 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_forward_microbatches", "hpf_backward_microbatches",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
            "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_partition_set_fusion",
+           "hpf_partition_set_profiling", "hpf_partition_profile_read",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
 
@@ -171,8 +174,26 @@ def hpf_partition_set_graphs(handle, enable):
     _check(lib.hpf_partition_set_graphs(handle, int(enable)))
 
 
-def hpf_partition_set_fusion(handle, enable):
-    _check(lib.hpf_partition_set_fusion(handle, int(enable)))
+def hpf_partition_set_fusion(handle, level):
+    _check(lib.hpf_partition_set_fusion(handle, int(level)))
+
+
+class hpf_profile_entry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("bytes_per_launch", C.c_double), ("flops_per_launch", C.c_double)]
+
+
+def hpf_partition_set_profiling(handle, enable):
+    _check(lib.hpf_partition_set_profiling(handle, int(bool(enable))))
+
+
+def hpf_partition_profile_read(handle, capacity=16):
+    buf = (hpf_profile_entry * capacity)()
+    n = C.c_int32(0)
+    _check(lib.hpf_partition_profile_read(handle, buf, capacity, C.byref(n)))
+    return [dict(name=buf[i].name.decode(), launches=int(buf[i].launches), total_ms=float(buf[i].total_ms),
+                 bytes_per_launch=float(buf[i].bytes_per_launch), flops_per_launch=float(buf[i].flops_per_launch))
+            for i in range(n.value)]
 
 
 def hpf_partition_destroy(handle):
@@ -408,8 +429,15 @@ class Partition:
     def set_graphs(self, enable):
         hpf_partition_set_graphs(self.handle, enable)
 
-    def set_fusion(self, enable):
-        hpf_partition_set_fusion(self.handle, enable)
+    def set_fusion(self, level):
+        hpf_partition_set_fusion(self.handle, level)
+
+    def set_profiling(self, enable):
+        hpf_partition_set_profiling(self.handle, enable)
+
+    def profile_read(self):
+        """[{name, launches, total_ms, bytes_per_launch, flops_per_launch}] since profiling was enabled."""
+        return hpf_partition_profile_read(self.handle)
 
     def params_read(self):
         import numpy as np
