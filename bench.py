@@ -31,7 +31,7 @@ PEAK_HBM = 8.0e12         # bytes/s
 # HBM bytes per launch from rocprofv3 counter runs of this same command (FETCH_SIZE + WRITE_SIZE, each
 # scaled by what the counter reads for a plain device copy of known size); the summaries with the
 # commands are under profiles/.  Keyed by (kernel class, configuration).
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {("resident_backward", 3): 1.258e9}
 
 
 def profile_classes(torch, part, step, steps=10):
@@ -79,6 +79,8 @@ def main():
                     help="grouped: all micro-batches of the batch in one group call per direction (default); "
                          "streams: one call and one stream per micro-batch; single-stream: one call per micro-batch, one stream")
     ap.add_argument("--no-graphs", action="store_true", help="plain kernel launches instead of HIP graph replay")
+    ap.add_argument("--fusion", type=int, choices=[0, 1, 2], default=2,
+                    help="kernel schedule of the library (hpf_partition_set_fusion); default 2, the library's default")
     ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel-class timing")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
@@ -104,6 +106,8 @@ def main():
     part = hpf.Partition(spec, inputs.params, hpf.HPF_BF16)
     if args.no_graphs:
         part.set_graphs(False)
+    if args.fusion != 2:
+        part.set_fusion(args.fusion)
     tdt = torch.bfloat16
     act_in = [torch.from_numpy(a).to(dev, torch.float32 if spec.has_stem else tdt) for a in inputs.act_in]
     labels = [torch.from_numpy(l).to(dev) for l in inputs.labels] if inputs.labels else [None] * m
@@ -166,7 +170,7 @@ def main():
                                f"{m} micro-batches of {spec.microbatch} images"
                                + (", + SGD step" if sgd else ""),
                    "batch": spec.batch, "microbatch": spec.microbatch, "num_microbatches": m,
-                   "schedule": args.schedule, "hip_graphs": not args.no_graphs},
+                   "schedule": args.schedule, "hip_graphs": not args.no_graphs, "fusion_level": args.fusion},
     }
 
     if not args.no_probe:
