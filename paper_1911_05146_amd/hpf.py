@@ -50,6 +50,12 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1911_05146_amd.build` "
                           "(there is no fallback path)")
+    # PyTorch ships its own HIP runtime; whichever runtime is loaded first serves the whole process, and the
+    # device tensors handed to this library come from PyTorch's: load it first.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(LIB_PATH)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
     L.hpf_last_error.restype = C.c_char_p
