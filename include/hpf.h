@@ -165,7 +165,8 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *      convolution that produces the tensor, normalise + ReLU while the consuming convolution and
  *      weight gradient stage their operand;
  *   2  (default) additionally, runs of consecutive bottleneck blocks with stride 1 and identity
- *      shortcut (128->32->32->128 channels at up to 256 pixels, 256->64->64->256 at up to 128) run
+ *      shortcut (128->32->32->128 channels at up to 256 pixels, 256->64->64->256 at up to 128; image
+ *      width 8, 16 or 32, pixel count a multiple of 32) run
  *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per
  *      image, all of them on the chip together.  Needs microbatch <= number of CUs; a group call
  *      then processes floor(CUs / microbatch) micro-batches (at most 8) per launch, and launches
@@ -178,8 +179,9 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
 /* Per-kernel-class timing, measured with HIP events on the stream the kernels are launched on.
  * While enabled the passes run as plain launches (no graph replay) with an event pair around every
  * segment of consecutive launches of one class; the classes are
- *   "resident_forward" / "resident_backward"  one launch per run of bottleneck blocks and group,
- *   "wgrad_grouped"                           the deferred weight-gradient launches (one per tile class),
+ *   "resident_forward" / "resident_backward" / "resident_wgrad"
+ *                                             one launch each per run of bottleneck blocks and group,
+ *   "wgrad_grouped"                           the other deferred weight-gradient launches (one per tile class),
  *   "other_forward" / "other_backward"        every other kernel of the pass.
  * hpf_partition_profile_read waits for the device, adds the finished segments to the totals kept
  * since profiling was enabled, and writes up to `capacity` entries (classes with no launch are

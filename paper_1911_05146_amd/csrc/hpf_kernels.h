@@ -123,6 +123,7 @@ struct ResBlock {
   unsigned long long gy_off, dc1_off, dc2_off, gx_off;
   unsigned long long stats_off[3];           // {mean, invstd} floats of the three BatchNorms (bytes)
   unsigned long long wf_off[3], wd_off[3];   // packed bf16 weights (elements)
+  unsigned long long w_off[3];               // fp32 masters / gradients [tap][Cin][Cout] (floats)
   unsigned long long gamma_off[3], beta_off[3];   // floats into the parameter / gradient vectors
 };
 struct ResArgs {
@@ -149,6 +150,9 @@ size_t resident_xchg_bytes(int C, int nmem);
 hipError_t resident_prepare();   // once per process, outside stream capture: raises the kernels' LDS limits
 hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
 hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+// Weight gradients of all blocks of the run (after the backward launch): reads the stash and the gradient
+// tensors the backward launch wrote, adds into a.grads.
+hipError_t launch_resident_wgrad(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
 
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);

@@ -79,6 +79,9 @@ struct Plan {
   size_t packed_elems = 0; int n_convs = 0;
   Loc g_stem;                          // gradient w.r.t. the stem output
   std::vector<WgradItem> items[9];     // deferred weight-gradient work, per tile class (bf16 mode)
+  std::vector<WgradItem> items_nr[9];  // the same without the blocks of image-resident runs (those have a launch of their own)
+  size_t items_nr_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  double wg_nr_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, wg_nr_flops[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   size_t items_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
   double wg_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, wg_flops[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};   // per micro-batch
   size_t arena_bytes = 0;
@@ -307,7 +310,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         rb.gx_off = res_loc(gx);
         for (int q = 0; q < 3; ++q) {
           rb.stats_off[q] = p.bn[q].stats_off;
-          rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off;
+          rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off; rb.w_off[q] = p.cv[q].w_off;
           rb.gamma_off[q] = p.bn[q].g_off; rb.beta_off[q] = p.bn[q].b_off;
         }
         P.res_blocks.push_back(rb);
@@ -328,27 +331,33 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   // ---- deferred weight-gradient items (bf16 mode)
   if (P.dt == DT_BF16) {
     // the operand of a block convolution is relu(bn(x)) recomputed from the BatchNorm input x
-    struct WConv { const ConvPlan* cv; int cin_run, c_valid, R; Loc a, dy; const BnPlan* bn; };
+    struct WConv { const ConvPlan* cv; int cin_run, c_valid, R; Loc a, dy; const BnPlan* bn; bool in_run; };
     std::vector<WConv> wc;
     ConvPlan stem1x1 = P.stem;
-    if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr});
+    if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr, false});
     for (int i = 0; i < d.n_blocks; ++i) {
       const BlockPlan& p = P.bp[i];
+      bool in_run = false;
+      for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
       for (int j = 0; j < p.nconv; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, j == 0 ? p.x_in : p.c[j - 1],
-                           j == p.nconv - 1 ? p.gy : p.dc[j], &p.bn[j]});
-      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.gy, &p.bn[0]});
+                           j == p.nconv - 1 ? p.gy : p.dc[j], &p.bn[j], in_run});
+      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.gy, &p.bn[0], false});
     }
     // output tiles per class: the pixel rows are split so that every class launches roughly 1500 work-groups
     // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
+    for (int pass = 0; pass < 2; ++pass) {   // pass 1: without the convolutions of image-resident runs
+    if (pass == 1 && P.runs.empty()) break;
     long tiles_in_class[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (const WConv& w : wc) {
+      if (pass == 1 && w.in_run) continue;
       const int cls = wgrad_tile_class(w.cin_run, w.cv->cout);
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
       tiles_in_class[cls] += (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
     }
     for (const WConv& w : wc) {
+      if (pass == 1 && w.in_run) continue;
       const ConvPlan& cv = *w.cv;
       WgradGeom q{};
       q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = w.cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
@@ -356,8 +365,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       const int cls = wgrad_tile_class(w.cin_run, cv.cout);
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
-      P.wg_bytes[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
-      P.wg_flops[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
+      (pass ? P.wg_nr_bytes : P.wg_bytes)[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
+      (pass ? P.wg_nr_flops : P.wg_flops)[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
       int splits = (int)((1536 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
       const int max_splits = (q.M + 127) / 128;
       if (splits > max_splits) splits = max_splits;
@@ -377,8 +386,9 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
               it.beta_off = w.bn ? w.bn->b_off : 0;
               it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
               it.m_begin = sp * rows; it.m_end = (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M;
-              P.items[cls].push_back(it);
+              (pass ? P.items_nr : P.items)[cls].push_back(it);
             }
+    }
     }
   }
 
@@ -390,6 +400,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.packed_off = g; g += align_up(P.packed_elems * 2);
   P.table_off = g;  g += align_up(P.table.size() * sizeof(PackDesc));
   for (int k = 0; k < 9; ++k) { P.items_off[k] = g; g += align_up(P.items[k].size() * sizeof(WgradItem)); }
+  for (int k = 0; k < 9; ++k) { P.items_nr_off[k] = g; g += align_up(P.items_nr[k].size() * sizeof(WgradItem)); }
   P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
   for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
   P.abort_off = g;  g += align_up(sizeof(int));
@@ -400,8 +411,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
 }  // namespace
 
-enum ProfCat { PROF_NONE = -1, PROF_RES_FWD = 0, PROF_RES_BWD, PROF_WGRAD, PROF_OTHER_FWD, PROF_OTHER_BWD, PROF_N };
-const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward", "wgrad_grouped", "other_forward", "other_backward"};
+enum ProfCat { PROF_NONE = -1, PROF_RES_FWD = 0, PROF_RES_BWD, PROF_RES_WGRAD, PROF_WGRAD, PROF_OTHER_FWD, PROF_OTHER_BWD, PROF_N };
+const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward", "resident_wgrad", "wgrad_grouped", "other_forward", "other_backward"};
 
 // One captured HIP graph of a micro-batch's forward or backward kernel sequence, valid for the caller
 // pointers it was captured with.
@@ -618,6 +629,14 @@ struct Ctx {
     chk(launch_resident_backward(g, r.C, r.MID, res_args(r), s), "resident_backward");
     seg_end();
   }
+  void res_wgrad(const Plan::ResRun& r) {
+    const BlockPlan& p0 = h->P.bp[r.first];
+    const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
+    seg(PROF_RES_WGRAD, img * r.count * 2.0 * px * (4.0 * r.MID + 2.0 * r.C),
+        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
+    chk(launch_resident_wgrad(g, r.C, r.MID, res_args(r), s), "resident_wgrad");
+    seg_end();
+  }
   void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {
     WgradGeom q{};
     q.b = h->P.d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = cv.cin; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
@@ -748,11 +767,15 @@ void run_backward(Ctx& c) {
       caller_dy.p[i] = const_cast<void*>(c.err_in[i]);
       caller_a.p[i] = const_cast<void*>(c.act_in[i]);
     }
+    const bool res = c.h->resident();
+    if (res)
+      for (const Plan::ResRun& r : P.runs) c.res_wgrad(r);
     for (int k = 0; k < 9; ++k) {
-      if (P.items[k].empty()) continue;
-      c.seg(PROF_WGRAD, c.g * P.wg_bytes[k], c.g * P.wg_flops[k]);
-      c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + P.items_off[k]), (int)P.items[k].size(), bases, caller_dy,
-                                 caller_a, c.h->params(), c.h->grads(), c.s),
+      const std::vector<WgradItem>& items = res ? P.items_nr[k] : P.items[k];
+      if (items.empty()) continue;
+      c.seg(PROF_WGRAD, c.g * (res ? P.wg_nr_bytes : P.wg_bytes)[k], c.g * (res ? P.wg_nr_flops : P.wg_flops)[k]);
+      c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + (res ? P.items_nr_off : P.items_off)[k]), (int)items.size(),
+                                 bases, caller_dy, caller_a, c.h->params(), c.h->grads(), c.s),
             "wgrad_grouped");
     }
   }
@@ -891,6 +914,9 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   for (int k = 0; k < 9; ++k)
     if (!P.items[k].empty())
       ok(hipMemcpy(p->arena + P.items_off[k], P.items[k].data(), P.items[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
+  for (int k = 0; k < 9; ++k)
+    if (!P.items_nr[k].empty())
+      ok(hipMemcpy(p->arena + P.items_nr_off[k], P.items_nr[k].data(), P.items_nr[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
   if (!P.runs.empty()) {
     ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
     ok(hipMemset(p->abort_flag(), 0, sizeof(int)));

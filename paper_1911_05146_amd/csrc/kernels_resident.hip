@@ -745,6 +745,264 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   if (me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
+// ------------------------------------------------------------------------------------------ weight gradients
+// Weight gradients of the blocks of a run, one launch for all of them.  A work-group takes one (block,
+// convolution [, 64-channel chunk]) and a group of images of one micro-batch; per image it stages the two
+// operands ONCE, transposed (channel-major, so that every MFMA lane finds its 8 consecutive pixels with one
+// 16-byte LDS read), runs every filter tap and output tile from LDS, and keeps the sums in registers over its
+// images; one fp32 atomic add per output element and work-group then goes to the gradient buffer.
+//   dw[tap][c][n] += sum_p a[p + shift(tap)][c] * dy[p][n],   a = relu(bn(x)) recomputed while staging.
+// The 3x3 convolution keeps three copies of `a`, shifted by -1 / 0 / +1 pixel along the image row with the
+// wrapped column zeroed, on a canvas with one zero image row above and below: every tap is then an aligned
+// read at offset r*W.
+constexpr int RW_NT = 256;
+
+// Pixel pairs of an image tile in registers: channels [c0, c0+CH) of an image [P][CT];
+// unit -> (pair = unit % 128, channel group = unit / 128); v[u][e] = 8 channels of pixel 2*pair + e.
+template <int CH>
+struct PairRegs {
+  static constexpr int NU = (128 * (CH / 8) + RW_NT - 1) / RW_NT;
+  uint4 v[NU][2];
+  __device__ __forceinline__ void load(const bf16_t* img, int CT, int c0, int P) {
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const int unit = threadIdx.x + u * RW_NT;
+      const int pr = unit & 127, cg = unit >> 7;
+      const bool ok = cg < CH / 8 && 2 * pr < P;
+      const bf16_t* q = img + (size_t)(ok ? 2 * pr : 0) * CT + c0 + (ok ? cg : 0) * 8;   // always a valid address
+      v[u][0] = *reinterpret_cast<const uint4*>(q);
+      v[u][1] = *reinterpret_cast<const uint4*>(q + CT);
+    }
+  }
+};
+// two pixels' 8 channels -> 8 dwords {pixel at pos, pixel at pos+1} in the channel-major tile (pos even)
+__device__ __forceinline__ void store_pair(bf16_t* T, int PS, int ch0, int pos, const uint4& e0, const uint4& e1) {
+  uint32_t* dst = reinterpret_cast<uint32_t*>(T + (size_t)ch0 * PS + pos);
+  const int RS = PS >> 1;
+  const uint32_t a[4] = {e0.x, e0.y, e0.z, e0.w}, b[4] = {e1.x, e1.y, e1.z, e1.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    dst[(2 * i) * RS] = (a[i] & 0xffffu) | (b[i] << 16);
+    dst[(2 * i + 1) * RS] = (a[i] >> 16) | (b[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ uint4 bn_relu8(const uint4& q, const float2* coef) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(coef, 16));
+  uint32_t r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 k = cf[i];
+    r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(w[i]), k.z, k.w), 0.f));
+  }
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+template <int CTRL>
+__device__ __forceinline__ uint4 dpp_mov4(const uint4& v) {
+  return make_uint4((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.x, CTRL, 0xf, 0xf, true),
+                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.y, CTRL, 0xf, 0xf, true),
+                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.z, CTRL, 0xf, 0xf, true),
+                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.w, CTRL, 0xf, 0xf, true));
+}
+
+struct ResWgArgs {
+  const ResBlock* blocks;
+  int nmem, ipw, H, W;       // images per micro-batch, images per work-group (divides nmem), image shape
+  PtrTab base, act_in, err_in;
+  const float* params;
+  float* grads;
+};
+
+struct WgImage {   // where the work-group's image i lives
+  const ResWgArgs& a; int img0;
+  __device__ __forceinline__ ResCtx ctx(int i, int& me) const {
+    const int img = img0 + i, z = img / a.nmem;
+    me = img - z * a.nmem;
+    return ResCtx{(char*)pick(a.base, z), pick(a.act_in, z), nullptr, pick(a.err_in, z), nullptr};
+  }
+};
+
+// BN table of the `a` operand's channels [c0, c0+CA) -> LDS coef (the group's images share one micro-batch)
+template <int CA>
+__device__ __forceinline__ void wg_coef(float2* coef, const float* stats, const float* gamma, const float* beta, int c0, int CT) {
+  for (int c = threadIdx.x; c < CA; c += RW_NT)
+    coef[c] = bn_scale_shift(stats[c0 + c], stats[CT + c0 + c], gamma[c0 + c], beta[c0 + c]);
+}
+
+// 1x1 convolution: a channels [ca0, ca0+CA) of CTA, dy channels [nd0, nd0+ND) of CTD; dw is [CTA][CTD].
+template <int CA, int ND>
+__device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsigned long long a_off, int CTA, int ca0,
+                                              unsigned long long st_off, const float* gamma, const float* beta,
+                                              unsigned long long dy_off, int CTD, int nd0, float* dw, unsigned char* smem) {
+  const int P = a.H * a.W, PS = P + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  bf16_t* Ta = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* Td = Ta + (size_t)CA * PS;
+  float2* coef = reinterpret_cast<float2*>(Td + (size_t)ND * PS);
+  constexpr int NTD = ND / 16, TPW = (CA / 16) * NTD / 4;
+  floatx4 acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const WgImage wi{a, img0};
+  PairRegs<CA> ra;
+  PairRegs<ND> rd;
+  {
+    int me;
+    const ResCtx cx = wi.ctx(0, me);
+    wg_coef<CA>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, ca0, CTA);
+    ra.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
+    rd.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
+  }
+  for (int i = 0; i < a.ipw; ++i) {
+    __syncthreads();   // the previous image's fragments are read (and coef is written, first time)
+#pragma unroll
+    for (int u = 0; u < PairRegs<CA>::NU; ++u) {
+      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
+      if (cg < CA / 8 && 2 * pr < P)
+        store_pair(Ta, PS, cg * 8, 2 * pr, bn_relu8(ra.v[u][0], coef + cg * 8), bn_relu8(ra.v[u][1], coef + cg * 8));
+    }
+#pragma unroll
+    for (int u = 0; u < PairRegs<ND>::NU; ++u) {
+      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
+      if (cg < ND / 8 && 2 * pr < P) store_pair(Td, PS, cg * 8, 2 * pr, rd.v[u][0], rd.v[u][1]);
+    }
+    __syncthreads();
+    if (i + 1 < a.ipw) {
+      int me;
+      const ResCtx cx = wi.ctx(i + 1, me);
+      ra.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
+      rd.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
+    }
+    for (int ks = 0; ks < P / 32; ++ks) {
+#pragma unroll
+      for (int t = 0; t < TPW; ++t) {
+        const int tile = wave * TPW + t, ct = tile / NTD, nt = tile % NTD;
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(Ta + (size_t)(ct * 16 + fr) * PS + ks * 32 + fk);
+        const bf16x8 fd = *reinterpret_cast<const bf16x8*>(Td + (size_t)(nt * 16 + fr) * PS + ks * 32 + fk);
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fd, acc[t], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int tile = wave * TPW + t, ct = tile / NTD, nt = tile % NTD;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      atomicAdd(dw + (size_t)(ca0 + ct * 16 + fq * 4 + v) * CTD + nd0 + nt * 16 + fr, acc[t][v]);
+  }
+}
+
+// 3x3 convolution, MID -> MID channels, stride 1, zero padding; dw is [9][MID][MID].
+template <int MID>
+__device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsigned long long a_off, unsigned long long st_off,
+                                              const float* gamma, const float* beta, unsigned long long dy_off, float* dw,
+                                              unsigned char* smem) {
+  const int P = a.H * a.W, W = a.W, PS = P + 8, PSH = P + 2 * W + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  bf16_t* Tsh = reinterpret_cast<bf16_t*>(smem);          // [3][MID][PSH]: a shifted by s-1 pixels along the row
+  bf16_t* Td = Tsh + (size_t)3 * MID * PSH;               // [MID][PS]
+  float2* coef = reinterpret_cast<float2*>(Td + (size_t)MID * PS);
+  constexpr int NT = MID / 16, PPW = NT * NT / 4;         // (input tile, output tile) pairs per wave
+  floatx4 acc[PPW][9];
+#pragma unroll
+  for (int t = 0; t < PPW; ++t)
+#pragma unroll
+    for (int k = 0; k < 9; ++k) acc[t][k] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // the zero image rows above and below
+  for (int i = tid; i < 3 * MID * 2 * W; i += RW_NT) {
+    const int ch = i / (2 * W), j = i - ch * 2 * W;
+    Tsh[(size_t)ch * PSH + (j < W ? j : P + j)] = 0;
+  }
+  const WgImage wi{a, img0};
+  PairRegs<MID> ra, rd;
+  {
+    int me;
+    const ResCtx cx = wi.ctx(0, me);
+    wg_coef<MID>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
+    ra.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
+    rd.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
+  }
+  const int half_w = W >> 1;
+  for (int i = 0; i < a.ipw; ++i) {
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PairRegs<MID>::NU; ++u) {
+      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
+      const bool ok = cg < MID / 8 && 2 * pr < P;
+      const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+      const uint4 e0 = bn_relu8(ra.v[u][0], coef + (ok ? cg : 0) * 8), e1 = bn_relu8(ra.v[u][1], coef + (ok ? cg : 0) * 8);
+      // neighbours along the image row sit in the neighbouring lanes (pairs of one row share a DPP row)
+      uint4 left = dpp_mov4<0x111>(e1), right = dpp_mov4<0x101>(e0);   // row_shr:1 / row_shl:1
+      const int pc = pr % half_w;
+      if (pc == 0) left = zero;
+      if (pc == half_w - 1) right = zero;
+      if (ok) {
+        const int pos = 2 * pr + W;
+        store_pair(Tsh, PSH, cg * 8, pos, left, e0);                       // a[col-1]
+        store_pair(Tsh + (size_t)MID * PSH, PSH, cg * 8, pos, e0, e1);     // a[col]
+        store_pair(Tsh + (size_t)2 * MID * PSH, PSH, cg * 8, pos, e1, right);   // a[col+1]
+        store_pair(Td, PS, cg * 8, 2 * pr, rd.v[u][0], rd.v[u][1]);
+      }
+    }
+    __syncthreads();
+    if (i + 1 < a.ipw) {
+      int me;
+      const ResCtx cx = wi.ctx(i + 1, me);
+      ra.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
+      rd.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
+    }
+    for (int ks = 0; ks < P / 32; ++ks) {
+#pragma unroll
+      for (int t = 0; t < PPW; ++t) {
+        const int pair = wave * PPW + t, ct = pair / NT, nt = pair % NT;
+        const bf16x8 fd = *reinterpret_cast<const bf16x8*>(Td + (size_t)(nt * 16 + fr) * PS + ks * 32 + fk);
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+          const int r = tap / 3, s = tap % 3;
+          const bf16x8 fa = *reinterpret_cast<const bf16x8*>(Tsh + ((size_t)s * MID + ct * 16 + fr) * PSH + ks * 32 + fk + r * W);
+          acc[t][tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fd, acc[t][tap], 0, 0, 0);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < PPW; ++t) {
+    const int pair = wave * PPW + t, ct = pair / NT, nt = pair % NT;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        atomicAdd(dw + ((size_t)tap * MID + ct * 16 + fq * 4 + v) * MID + nt * 16 + fr, acc[t][tap][v]);
+  }
+}
+
+// grid: (image groups, 2*C/64 + 1 items, blocks of the run).  Items: conv1 in chunks of 64 input channels,
+// conv2, conv3 in chunks of 64 output channels.
+template <int C, int MID>
+__global__ void __launch_bounds__(RW_NT) k_res_wgrad(const ResWgArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ResBlock B = a.blocks[blockIdx.z];
+  const int img0 = blockIdx.x * a.ipw;
+  constexpr int NCH = C / 64;
+  const int item = blockIdx.y;
+  if (item < NCH)
+    res_wgrad_1x1<64, MID>(a, img0, B.x_off, C, item * 64, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0],
+                           B.dc1_off, MID, 0, a.grads + B.w_off[0], smem);
+  else if (item == NCH)
+    res_wgrad_3x3<MID>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.dc2_off,
+                       a.grads + B.w_off[1], smem);
+  else
+    res_wgrad_1x1<MID, 64>(a, img0, B.c2_off, MID, 0, B.stats_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2],
+                           B.gy_off, C, (item - NCH - 1) * 64, a.grads + B.w_off[2], smem);
+}
+
+size_t wgrad_lds(int C, int MID, int P, int W) {
+  const size_t one = (size_t)(64 + MID) * (P + 8) * 2 + 64 * 8;
+  const size_t three = (size_t)3 * MID * (P + 2 * W + 8) * 2 + (size_t)MID * (P + 8) * 2 + (size_t)MID * 8;
+  (void)C;
+  return one > three ? one : three;
+}
+
 // LDS bytes of the two kernels; *own = 1 when the gather area cannot overlay the small tiles
 size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
@@ -776,7 +1034,9 @@ size_t resident_xchg_bytes(int C, int nmem) { return 2 * (size_t)nmem * 2 * C * 
 bool resident_shape_ok(int C, int MID, int H, int W, int nmem) {
   if (!((C == 128 && MID == 32) || (C == 256 && MID == 64))) return false;
   const int P = H * W;
-  if (H <= 0 || W <= 0 || P % 16 || P > 16 * (C == 128 ? 2 : 1) * RES_NWV) return false;
+  // whole 32-pixel reduction steps in the weight gradients; image rows that keep 16-byte alignment under a row shift
+  // and whose pixel pairs fit the 16-lane rows used for neighbour exchange
+  if (H <= 0 || (W != 8 && W != 16 && W != 32) || P % 32 || P > 16 * (C == 128 ? 2 : 1) * RES_NWV) return false;
   if (nmem < 1 || nmem > 1024) return false;
   int own = 0;
   return fwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES && bwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES;
@@ -797,6 +1057,8 @@ hipError_t resident_prepare() {
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<128, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<256, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
@@ -806,6 +1068,21 @@ hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipS
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
   if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
+}
+
+hipError_t launch_resident_wgrad(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
+  ResWgArgs w{};
+  w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
+  w.ipw = 1;
+  for (int k = 8; k >= 1; k >>= 1)
+    if (a.nmem % k == 0) { w.ipw = k; break; }
+  w.base = a.base; w.act_in = a.act_in; w.err_in = a.err_in; w.params = a.params; w.grads = a.grads;
+  const size_t lds = wgrad_lds(C, MID, a.H * a.W, a.W);
+  const dim3 grid((unsigned)(g * a.nmem / w.ipw), (unsigned)(2 * (C / 64) + 1), (unsigned)a.nblk);
+  if (C == 128) k_res_wgrad<128, 32><<<grid, RW_NT, lds, stream>>>(w);
+  else k_res_wgrad<256, 64><<<grid, RW_NT, lds, stream>>>(w);
+  return hipGetLastError();
 }
 
 hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
