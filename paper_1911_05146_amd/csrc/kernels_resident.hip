@@ -757,19 +757,27 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
 // read at offset r*W.
 constexpr int RW_NT = 256;
 
-// Pixel pairs of an image tile in registers: channels [c0, c0+CH) of an image [P][CT];
-// unit -> (pair = unit % 128, channel group = unit / 128); v[u][e] = 8 channels of pixel 2*pair + e.
+// Pixel pairs of an image tile in registers: channels [c0, c0+CH) of an image [P][CT].  A unit is (pixel pair,
+// group of 8 channels); four neighbouring lanes take four consecutive channel groups of one pair (64
+// contiguous bytes), the 16 lane quads of a wave 16 consecutive pairs: global loads touch 16 lines per
+// instruction and the transposing LDS stores stay within a 2-way bank conflict.
 template <int CH>
 struct PairRegs {
-  static constexpr int NU = (128 * (CH / 8) + RW_NT - 1) / RW_NT;
+  static constexpr int G = CH / 8;                       // channel groups (4 or 8)
+  static constexpr int NU = 128 * G / RW_NT;
+  static_assert(G % 4 == 0 && (128 * G) % RW_NT == 0, "tile shape");
   uint4 v[NU][2];
+  static __device__ __forceinline__ void unit(int u, int& pr, int& cg) {
+    const int lane = threadIdx.x & 63, q = u * (RW_NT / 64) + (threadIdx.x >> 6);
+    cg = (q % (G / 4)) * 4 + (lane & 3);
+    pr = (q / (G / 4)) * 16 + (lane >> 2);
+  }
   __device__ __forceinline__ void load(const bf16_t* img, int CT, int c0, int P) {
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const int unit = threadIdx.x + u * RW_NT;
-      const int pr = unit & 127, cg = unit >> 7;
-      const bool ok = cg < CH / 8 && 2 * pr < P;
-      const bf16_t* q = img + (size_t)(ok ? 2 * pr : 0) * CT + c0 + (ok ? cg : 0) * 8;   // always a valid address
+      int pr, cg;
+      unit(u, pr, cg);
+      const bf16_t* q = img + (size_t)(2 * pr < P ? 2 * pr : 0) * CT + c0 + cg * 8;   // always a valid address
       v[u][0] = *reinterpret_cast<const uint4*>(q);
       v[u][1] = *reinterpret_cast<const uint4*>(q + CT);
     }
@@ -797,12 +805,12 @@ __device__ __forceinline__ uint4 bn_relu8(const uint4& q, const float2* coef) {
   }
   return make_uint4(r[0], r[1], r[2], r[3]);
 }
-template <int CTRL>
-__device__ __forceinline__ uint4 dpp_mov4(const uint4& v) {
-  return make_uint4((uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.x, CTRL, 0xf, 0xf, true),
-                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.y, CTRL, 0xf, 0xf, true),
-                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.z, CTRL, 0xf, 0xf, true),
-                    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v.w, CTRL, 0xf, 0xf, true));
+// value of the lane four below / above (same channel group, previous / next pixel pair)
+__device__ __forceinline__ uint4 lanes_up4(const uint4& v) {
+  return make_uint4(__shfl_up(v.x, 4), __shfl_up(v.y, 4), __shfl_up(v.z, 4), __shfl_up(v.w, 4));
+}
+__device__ __forceinline__ uint4 lanes_down4(const uint4& v) {
+  return make_uint4(__shfl_down(v.x, 4), __shfl_down(v.y, 4), __shfl_down(v.z, 4), __shfl_down(v.w, 4));
 }
 
 struct ResWgArgs {
@@ -844,35 +852,27 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
 #pragma unroll
   for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
   const WgImage wi{a, img0};
-  PairRegs<CA> ra;
-  PairRegs<ND> rd;
-  {
+  auto load_img = [&](int i, PairRegs<CA>& A, PairRegs<ND>& D) {
     int me;
-    const ResCtx cx = wi.ctx(0, me);
-    wg_coef<CA>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, ca0, CTA);
-    ra.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
-    rd.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
-  }
-  for (int i = 0; i < a.ipw; ++i) {
-    __syncthreads();   // the previous image's fragments are read (and coef is written, first time)
+    const ResCtx cx = wi.ctx(i, me);
+    A.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
+    D.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
+  };
+  auto stage = [&](const PairRegs<CA>& A, const PairRegs<ND>& D) {
 #pragma unroll
     for (int u = 0; u < PairRegs<CA>::NU; ++u) {
-      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
-      if (cg < CA / 8 && 2 * pr < P)
-        store_pair(Ta, PS, cg * 8, 2 * pr, bn_relu8(ra.v[u][0], coef + cg * 8), bn_relu8(ra.v[u][1], coef + cg * 8));
+      int pr, cg;
+      PairRegs<CA>::unit(u, pr, cg);
+      if (2 * pr < P) store_pair(Ta, PS, cg * 8, 2 * pr, bn_relu8(A.v[u][0], coef + cg * 8), bn_relu8(A.v[u][1], coef + cg * 8));
     }
 #pragma unroll
     for (int u = 0; u < PairRegs<ND>::NU; ++u) {
-      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
-      if (cg < ND / 8 && 2 * pr < P) store_pair(Td, PS, cg * 8, 2 * pr, rd.v[u][0], rd.v[u][1]);
+      int pr, cg;
+      PairRegs<ND>::unit(u, pr, cg);
+      if (2 * pr < P) store_pair(Td, PS, cg * 8, 2 * pr, D.v[u][0], D.v[u][1]);
     }
-    __syncthreads();
-    if (i + 1 < a.ipw) {
-      int me;
-      const ResCtx cx = wi.ctx(i + 1, me);
-      ra.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
-      rd.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
-    }
+  };
+  auto mma = [&]() {
     for (int ks = 0; ks < P / 32; ++ks) {
 #pragma unroll
       for (int t = 0; t < TPW; ++t) {
@@ -881,6 +881,29 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
         const bf16x8 fd = *reinterpret_cast<const bf16x8*>(Td + (size_t)(nt * 16 + fr) * PS + ks * 32 + fk);
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fd, acc[t], 0, 0, 0);
       }
+    }
+  };
+  // two register sets: an image's loads are issued a whole iteration before they are staged
+  PairRegs<CA> a0, a1;
+  PairRegs<ND> d0, d1;
+  {
+    int me;
+    const ResCtx cx = wi.ctx(0, me);
+    wg_coef<CA>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, ca0, CTA);
+  }
+  load_img(0, a0, d0);
+  for (int i = 0; i < a.ipw; i += 2) {
+    if (i + 1 < a.ipw) load_img(i + 1, a1, d1);
+    __syncthreads();   // the previous image's fragments are read (and coef is written, first time)
+    stage(a0, d0);
+    __syncthreads();
+    mma();
+    if (i + 1 < a.ipw) {
+      if (i + 2 < a.ipw) load_img(i + 2, a0, d0);
+      __syncthreads();
+      stage(a1, d1);
+      __syncthreads();
+      mma();
     }
   }
 #pragma unroll
@@ -914,25 +937,23 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
     Tsh[(size_t)ch * PSH + (j < W ? j : P + j)] = 0;
   }
   const WgImage wi{a, img0};
-  PairRegs<MID> ra, rd;
-  {
-    int me;
-    const ResCtx cx = wi.ctx(0, me);
-    wg_coef<MID>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
-    ra.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
-    rd.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
-  }
   const int half_w = W >> 1;
-  for (int i = 0; i < a.ipw; ++i) {
-    __syncthreads();
+  auto load_img = [&](int i, PairRegs<MID>& A, PairRegs<MID>& D) {
+    int me;
+    const ResCtx cx = wi.ctx(i, me);
+    A.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
+    D.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
+  };
+  auto stage = [&](const PairRegs<MID>& A, const PairRegs<MID>& D) {
 #pragma unroll
     for (int u = 0; u < PairRegs<MID>::NU; ++u) {
-      const int unit = tid + u * RW_NT, pr = unit & 127, cg = unit >> 7;
-      const bool ok = cg < MID / 8 && 2 * pr < P;
+      int pr, cg;
+      PairRegs<MID>::unit(u, pr, cg);
+      const bool ok = 2 * pr < P;
       const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-      const uint4 e0 = bn_relu8(ra.v[u][0], coef + (ok ? cg : 0) * 8), e1 = bn_relu8(ra.v[u][1], coef + (ok ? cg : 0) * 8);
-      // neighbours along the image row sit in the neighbouring lanes (pairs of one row share a DPP row)
-      uint4 left = dpp_mov4<0x111>(e1), right = dpp_mov4<0x101>(e0);   // row_shr:1 / row_shl:1
+      const uint4 e0 = bn_relu8(A.v[u][0], coef + cg * 8), e1 = bn_relu8(A.v[u][1], coef + cg * 8);
+      // the neighbouring pairs of the image row sit four lanes away (the 16 pairs of a wave hold whole rows)
+      uint4 left = lanes_up4(e1), right = lanes_down4(e0);
       const int pc = pr % half_w;
       if (pc == 0) left = zero;
       if (pc == half_w - 1) right = zero;
@@ -941,16 +962,11 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
         store_pair(Tsh, PSH, cg * 8, pos, left, e0);                       // a[col-1]
         store_pair(Tsh + (size_t)MID * PSH, PSH, cg * 8, pos, e0, e1);     // a[col]
         store_pair(Tsh + (size_t)2 * MID * PSH, PSH, cg * 8, pos, e1, right);   // a[col+1]
-        store_pair(Td, PS, cg * 8, 2 * pr, rd.v[u][0], rd.v[u][1]);
+        store_pair(Td, PS, cg * 8, 2 * pr, D.v[u][0], D.v[u][1]);
       }
     }
-    __syncthreads();
-    if (i + 1 < a.ipw) {
-      int me;
-      const ResCtx cx = wi.ctx(i + 1, me);
-      ra.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
-      rd.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
-    }
+  };
+  auto mma = [&]() {
     for (int ks = 0; ks < P / 32; ++ks) {
 #pragma unroll
       for (int t = 0; t < PPW; ++t) {
@@ -963,6 +979,27 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
           acc[t][tap] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fd, acc[t][tap], 0, 0, 0);
         }
       }
+    }
+  };
+  PairRegs<MID> a0, a1, d0, d1;
+  {
+    int me;
+    const ResCtx cx = wi.ctx(0, me);
+    wg_coef<MID>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
+  }
+  load_img(0, a0, d0);
+  for (int i = 0; i < a.ipw; i += 2) {
+    if (i + 1 < a.ipw) load_img(i + 1, a1, d1);
+    __syncthreads();
+    stage(a0, d0);
+    __syncthreads();
+    mma();
+    if (i + 1 < a.ipw) {
+      if (i + 2 < a.ipw) load_img(i + 2, a0, d0);
+      __syncthreads();
+      stage(a1, d1);
+      __syncthreads();
+      mma();
     }
   }
 #pragma unroll
