@@ -154,8 +154,9 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
 
 /* Forward and backward kernel sequences of a micro-batch are captured into HIP graphs on first use
  * and replayed while the caller passes the same buffers (a call with other pointers re-captures).
- * enable == 0 switches to plain launches; default is enabled.  The default (NULL) stream and a
- * stream that is itself being captured by the caller always get plain launches. */
+ * enable == 0 switches to plain launches; default is enabled.  The default (NULL) stream, a
+ * stream that is itself being captured by the caller, and sequences of fewer than 8 launches
+ * (cheaper to launch than a graph) always get plain launches. */
 hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
 
 /* How far bf16 mode fuses the kernel schedule; the arithmetic is the same at every level, summation

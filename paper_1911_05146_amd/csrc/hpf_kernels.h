@@ -129,7 +129,8 @@ struct ResBlock {
 struct ResArgs {
   const ResBlock* blocks;   // device table of the run
   int nblk;
-  int nmem;                 // images per micro-batch = work-groups per exchange group (grid x)
+  int nmem;                 // images per micro-batch = work-groups per exchange group
+  int ngroup;               // micro-batches in the launch (set by the launchers)
   int H, W;
   float eps;
   PtrTab base;              // micro-batch regions of the group members (grid z)

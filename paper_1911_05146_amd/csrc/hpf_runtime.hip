@@ -419,7 +419,9 @@ const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward",
 struct GraphSlot {
   hipGraphExec_t exec = nullptr;
   std::vector<const void*> key;
+  bool direct = false;   // the sequence is so short that plain launches are cheaper than a graph launch
 };
+constexpr int kMinGraphLaunches = 8;
 
 struct hpf_partition {
   Plan P;
@@ -504,9 +506,11 @@ struct Ctx {
   PtrTab mbp(size_t off) const { Loc l; l.kind = IN_MB; l.off = off; return tab(l); }
   PtrTab scratch(int i) const { return mbp(h->P.scratch_off[i]); }
   static PtrTab none() { return PtrTab{}; }
+  int n_launches = 0;
   void chk(hipError_t e, const char* w) {
     if (err == hipSuccess && e != hipSuccess) { err = e; where = w; }
     if (cur.cat != PROF_NONE) ++cur.launches;
+    ++n_launches;
   }
 
   bool fused() const { return h->fuse >= 1 && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
@@ -801,8 +805,13 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<cons
     body();
     return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
   }
+  if (slot.direct && slot.key == key) {
+    body();
+    return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
+  }
   const bool hit = slot.exec && slot.key == key;
   if (!hit) {
+    slot.direct = false;
     if (slot.exec) { (void)hipGraphExecDestroy(slot.exec); slot.exec = nullptr; }
     hipGraph_t graph = nullptr;
     if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamBeginCapture failed");
@@ -812,10 +821,17 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<cons
       if (graph) (void)hipGraphDestroy(graph);
       return fail(HPF_EDEVICE, "graph capture failed: %s: %s", c.where, hipGetErrorString(c.err != hipSuccess ? c.err : e));
     }
+    slot.key = key;
+    if (c.n_launches < kMinGraphLaunches) {   // capture recorded the launches without running them: run them now
+      (void)hipGraphDestroy(graph);
+      slot.direct = true;
+      c.n_launches = 0;
+      body();
+      return c.err == hipSuccess ? HPF_OK : fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
+    }
     const hipError_t ei = hipGraphInstantiate(&slot.exec, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
     if (ei != hipSuccess) { slot.exec = nullptr; return fail(HPF_EDEVICE, "hipGraphInstantiate: %s", hipGetErrorString(ei)); }
-    slot.key = key;
   }
   if (hipGraphLaunch(slot.exec, s) != hipSuccess) return fail(HPF_EDEVICE, "hipGraphLaunch failed");
   return HPF_OK;
@@ -1122,8 +1138,8 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
   for (int i = 0; i < p->P.d.num_microbatches; ++i)
     if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
   if (p->fuse != enable) {   // cached graphs hold the other kernel sequence
-    for (GraphSlot& g : p->g_fwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
-    for (GraphSlot& g : p->g_bwd) if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+    for (GraphSlot& g : p->g_fwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
+    for (GraphSlot& g : p->g_bwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
   }
   p->fuse = enable;
   return HPF_OK;

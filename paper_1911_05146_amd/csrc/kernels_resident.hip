@@ -303,7 +303,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
-  const int me = blockIdx.x, z = blockIdx.z;
+  // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
   unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
@@ -590,7 +591,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
-  const int me = blockIdx.x, z = blockIdx.z;
+  // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
   unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
@@ -667,7 +669,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, sdc, P);
     // ---- conv2 data gradient, BN2 + ReLU backward -> dc1 (into the tile that held c2)
-    uint2 x1[PTW][C / 16];   // the block input at this lane's positions, for the BN1 backward below
+    uint2 x1[PTW][C / 16];   // the block input at this lane's accumulator positions, for the BN1 backward below
     {
       floatx4 acc[PTW][MID / 16];
       uint2 xin[PTW][MID / 16];
@@ -675,6 +677,16 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      {   // issued ahead of the contraction: the latency passes behind it and the first BN pass
+        const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt)
+            x1[j][nt] = *reinterpret_cast<const uint2*>(xg + (size_t)((pt < npt ? pt : 0) * 16 + fr) * C + nt * 16 + fq * 4);
+        }
+      }
       conv3x3_tile<MID, PTW, true>(sdc, w2, a.H, a.W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
@@ -684,16 +696,6 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
           xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
       }
       w1.load(a.packed + B.wd_off[0], MID, fr, fk);
-      {
-        const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
-#pragma unroll
-        for (int j = 0; j < PTW; ++j) {
-          const int pt = wave + j * RES_NWV;
-#pragma unroll
-          for (int nt = 0; nt < C / 16; ++nt)
-            x1[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(xg + (size_t)(pt * 16 + fr) * C + nt * 16 + fq * 4) : make_uint2(0u, 0u);
-        }
-      }
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                      a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag,
@@ -1060,7 +1062,9 @@ constexpr size_t RES_LDS_BYTES = 160 * 1024 - 1024;   // LDS of a gfx950 CU, les
 
 template <class K>
 hipError_t launch_res(K kernel, size_t lds, int own, int g, const ResArgs& a, hipStream_t stream) {
-  kernel<<<dim3((unsigned)a.nmem, 1, (unsigned)g), RES_NT, lds, stream>>>(a, own);
+  ResArgs b = a;
+  b.ngroup = g;
+  kernel<<<dim3((unsigned)(a.nmem * g)), RES_NT, lds, stream>>>(b, own);
   return hipGetLastError();
 }
 
