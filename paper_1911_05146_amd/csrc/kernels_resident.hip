@@ -80,25 +80,28 @@ __device__ __forceinline__ void publish_word(u64* slot, int me, int nw, int w, f
   __hip_atomic_store(slot + (size_t)me * nw + w, ((u64)tag << 32) | (u64)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // Returns false, uniformly over the work-group, when a partner did not show up.  Ends with a barrier.
+// INFL: words in flight per thread and polling round (a micro-batch of 32 images exchanges 4 words per thread
+// for the narrow tensors, 16 for the wide ones: one round each).
+template <int INFL>
 __device__ __forceinline__ bool collect(const u64* slot, int nmem, int nw, unsigned tag, float* gath, int* abort_flag) {
   const int total = nmem * nw;
   int timed_out = 0;
-  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * 8) {   // up to 8 words in flight per thread
-    u64 v[8];
+  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * INFL) {
+    u64 v[INFL];
     unsigned spins = 0;
     for (;;) {
       bool all = true;
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < INFL; ++i)
         if (i0 + i * RES_NT < total) v[i] = __hip_atomic_load(slot + i0 + i * RES_NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < INFL; ++i)
         if (i0 + i * RES_NT < total) all = all && (unsigned)(v[i] >> 32) == tag;
       if (all) break;
       if (++spins > RES_SPIN_LIMIT) { timed_out = 1; break; }
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < INFL; ++i)
       if (i0 + i * RES_NT < total) gath[i0 + i * RES_NT] = __uint_as_float((unsigned)v[i]);
   }
   const int any = __syncthreads_or(timed_out);
@@ -121,7 +124,8 @@ __device__ __forceinline__ void merge_coef(const float* gath, int nmem, int P, f
   float s = 0.f;
   for (int m = part; m < nmem; m += MP) s += gath[m * 2 * Cc + c];
   s = row_sum<CR>(s);
-  const float mean = s / (float)nmem;
+  const float inv_n = 1.f / (float)nmem;
+  const float mean = s * inv_n;
   float s2 = 0.f;
   for (int m = part; m < nmem; m += MP) {
     const float d = gath[m * 2 * Cc + c] - mean;
@@ -129,7 +133,7 @@ __device__ __forceinline__ void merge_coef(const float* gath, int nmem, int P, f
   }
   s2 = row_sum<CR>(s2);
   if (part == 0) {
-    const float var = s2 / ((float)nmem * (float)P);
+    const float var = s2 * inv_n / (float)P;
     const float is = 1.0f / sqrtf(var + eps);
     coef[c] = bn_scale_shift(mean, is, g, b);
     if (stats_out) { stats_out[c] = mean; stats_out[Cc + c] = is; }
@@ -334,7 +338,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     w1.load(a.packed + B0.wf_off[0], C, fr, fk);
     __syncthreads();
     stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
-    if (!collect(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
     ++phase;
     merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
                   me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
@@ -381,7 +385,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     __syncthreads();
     stats_publish<MID>(smA, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // while the records travel
-    if (!collect(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
+    if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
     ++phase;
     merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
@@ -408,7 +412,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     __syncthreads();
     stats_publish<MID>(smB, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
-    if (!collect(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+    if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
     ++phase;
     merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
@@ -450,7 +454,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     if (more) stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
     if (more) {
-      if (!collect(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+      if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
@@ -508,15 +512,22 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
     for (int i = 0; i < RES_NWV; ++i) s += red[i * 2 * Cc + w];
     publish_word(slot, me, 2 * Cc, w, s, tag);
   }
-  if (!collect(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
+  if (!collect<(Cc >= 128 ? 16 : 4)>(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
   const float invM = 1.f / ((float)nmem * (float)P);
-  for (int c = threadIdx.x; c < Cc; c += RES_NT) {
+  {   // the 32 rows of 16 lanes take Cc/32 channels each; the lanes of a row split the members (fixed order)
+    constexpr int CR = Cc / 32, MP = 16 / CR;
+    const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const int c = row * CR + l16 % CR, part = l16 / CR;
     float sb = 0.f, sg = 0.f;
-    for (int m = 0; m < nmem; ++m) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
-    if (me == 0) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
-    const float4 k = cf[c];
-    // scale*(dz - sb/M - (x*is + nm)*sg/M)
-    tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
+    for (int m = part; m < nmem; m += MP) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
+    sb = row_sum<CR>(sb);
+    sg = row_sum<CR>(sg);
+    if (part == 0) {
+      if (me == 0) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
+      const float4 k = cf[c];
+      // scale*(dz - sb/M - (x*is + nm)*sg/M)
+      tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
+    }
   }
   __syncthreads();
 #pragma unroll
