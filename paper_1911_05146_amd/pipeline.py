@@ -1,0 +1,122 @@
+"""Several partitions of one model chained on ONE GPU, scheduled the way the paper pipelines a batch
+(Section "Exploiting Pipeline Stages within Each Minibatch"): the batch is cut into micro-batches, every
+partition forwards micro-batch i as soon as the partition before it has, the partial errors flow back the
+same way, and every partition accumulates its weight gradients over the micro-batches before the one
+update of the batch.  Here the "ranks" are HIP streams: one per partition, with events standing in for
+the send/recv pairs, so partition p works on micro-batch i while partition p+1 still works on i-1.
+
+Host logic only: every tensor operation is a call into the C-ABI library through `hpf.Partition`.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+from . import hpf
+from . import workloads as W
+
+
+def split_model(name: str, blocks: Sequence[W.Block], n_parts: int, in_hw: int, stem_c: int, classes: int,
+                microbatch: int, num_microbatches: int, seed: int) -> List[W.PartitionSpec]:
+    """A stem + blocks + head model cut into n_parts contiguous partitions at block boundaries."""
+    return [W.partition_of(f"{name}-part{p}of{n_parts}", list(blocks), n_parts, p, in_hw, blocks[0].c_in, stem_c, classes,
+                           microbatch, num_microbatches, seed) for p in range(n_parts)]
+
+
+class Pipeline:
+    """specs: the partitions in model order (the first holds the stem, the last the head); params: the flat
+    parameter vector of the whole model (canonical order = concatenation of the partitions' vectors).
+    group: micro-batches per library call (1: finest pipelining; more: fewer, larger launches per partition)."""
+
+    def __init__(self, specs: Sequence[W.PartitionSpec], params, compute_dtype=hpf.HPF_BF16, device="cuda:0", group: int = 1,
+                 fusion: Optional[int] = None):
+        import torch
+        self.torch = torch
+        self.specs = list(specs)
+        assert self.specs[0].has_stem and self.specs[-1].has_head, "first partition holds the stem, last the head"
+        self.m = self.specs[0].num_microbatches
+        assert all(s.num_microbatches == self.m and s.microbatch == self.specs[0].microbatch for s in self.specs)
+        assert group >= 1 and self.m % group == 0, "group must divide the number of micro-batches"
+        self.group = group
+        self.device = torch.device(device)
+        self.parts: List[hpf.Partition] = []
+        off = 0
+        for s in self.specs:
+            n = W.n_params(s)
+            self.parts.append(hpf.Partition(s, params[off:off + n], compute_dtype, device))
+            if fusion is not None:
+                self.parts[-1].set_fusion(fusion)
+            off += n
+        assert off == len(params), "parameter vector does not match the partitions"
+        self.streams = [torch.cuda.Stream(self.device) for _ in self.parts]
+        self._keep = []
+
+    @property
+    def loss(self):
+        return self.parts[-1].loss
+
+    def run_batch(self, act_in, labels):
+        """Forward and backward of one batch: act_in / labels are lists of m device tensors.  Returns when all work
+        is queued; the gradients are complete after `synchronize()` / `grad_accum_read()`."""
+        torch, P, g = self.torch, len(self.parts), self.group
+        units = [list(range(u, u + g)) for u in range(0, self.m, g)]
+        self.parts[-1].loss.zero_()
+        torch.cuda.synchronize(self.device)
+        fwd_done = [[torch.cuda.Event() for _ in units] for _ in range(P)]
+        bwd_done = [[torch.cuda.Event() for _ in units] for _ in range(P)]
+        acts = [[None] * self.m for _ in range(P)]   # acts[p][i]: output of partition p (input of p+1)
+        errs = [[None] * self.m for _ in range(P)]   # errs[p][i]: partial error leaving partition p (into p-1)
+        # ---- fill and drain, forward: unit u reaches partition p after it left p-1
+        for ui, unit in enumerate(units):
+            for p, part in enumerate(self.parts):
+                s = self.streams[p]
+                if p > 0:
+                    s.wait_event(fwd_done[p - 1][ui])
+                x = [act_in[i] for i in unit] if p == 0 else [acts[p - 1][i] for i in unit]
+                lab = [labels[i] for i in unit] if part.spec.has_head else None
+                if g == 1:
+                    out = [part.forward_microbatch(unit[0], x[0], lab[0] if lab else None, stream=s)]
+                else:
+                    out = part.forward_microbatches(unit[0], x, lab, stream=s) or [None] * g
+                for i, o in zip(unit, out):
+                    acts[p][i] = o
+                fwd_done[p][ui].record(s)
+        # ---- backward: the partial errors travel from the head to the stem
+        for ui, unit in enumerate(units):
+            for p in reversed(range(P)):
+                part, s = self.parts[p], self.streams[p]
+                if p < P - 1:
+                    s.wait_event(bwd_done[p + 1][ui])
+                e_in = None if part.spec.has_head else [errs[p + 1][i] for i in unit]
+                if g == 1:
+                    out = [part.backward_microbatch(unit[0], e_in[0] if e_in else None, stream=s)]
+                else:
+                    out = part.backward_microbatches(unit[0], g, e_in, stream=s) or [None] * g
+                for i, o in zip(unit, out):
+                    errs[p][i] = o
+                bwd_done[p][ui].record(s)
+        self._keep = [acts, errs, act_in, labels]   # the boundary tensors must outlive the queued work
+
+    def synchronize(self):
+        self.torch.cuda.synchronize(self.device)
+        self._keep = []
+
+    def grad_accum_read(self):
+        """The accumulated gradients of all partitions, concatenated in model order (numpy)."""
+        import numpy as np
+        out = np.concatenate([p.grad_accum_read() for p in self.parts])
+        self.synchronize()
+        return out
+
+    def sgd_step(self, lr, momentum):
+        for p, s in zip(self.parts, self.streams):
+            p.sgd_step(lr, momentum, stream=s)
+
+    def params_read(self):
+        import numpy as np
+        return np.concatenate([p.params_read() for p in self.parts])
+
+    def close(self):
+        self.synchronize()
+        for p in self.parts:
+            p.close()
+        self.parts = []
