@@ -127,6 +127,31 @@ def test_image_resident_runs_deep_and_mixed(gpu, oracle):
     check(oracle, replace(mixed, name="resident-mixed-level1"), "bf16", fusion=1)
 
 
+def test_image_resident_runs_edge_cases(gpu, oracle):
+    """One image per micro-batch (the all-gather has a single member), an odd micro-batch (weight-gradient groups of
+    one image), more images than CUs (the run falls back to the per-layer kernels), and the level switch between
+    batches of one handle."""
+    from parity import run_gpu_step, rel_err
+    check(oracle, _bottleneck_run("resident-single-image", 128, 32, 16, 2, 1, 3), "bf16", strict=True, beta_shift=6.0, grouped=True)
+    check(oracle, _bottleneck_run("resident-odd-microbatch", 128, 32, 8, 2, 5, 2), "bf16", strict=True, beta_shift=6.0)
+    check(oracle, _bottleneck_run("resident-more-images-than-cus", 128, 32, 8, 1, 260, 1), "bf16", strict=True, beta_shift=6.0)
+    spec = _bottleneck_run("resident-level-switch", 128, 32, 8, 2, 4, 2, seed=41)
+    inp = W.make_inputs(spec, randomize_affine=True)
+    _, r2 = run_gpu_step(spec, inp, "bf16", keep=True, fusion=2)
+    part = r2["part"]
+    part.grad_accum_zero()
+    part.set_fusion(1)
+    _, r1 = run_gpu_step(spec, inp, "bf16", part=part)
+    part.grad_accum_zero()
+    part.set_fusion(2)
+    _, r2b = run_gpu_step(spec, inp, "bf16", part=part)
+    part.close()
+    for x, y in zip(r2["act_out"] + r2["err_out"], r2b["act_out"] + r2b["err_out"]):
+        assert np.array_equal(x, y)                       # the same schedule twice: identical tensors
+    assert rel_err(r2b["grad"], r2["grad"]) < 1e-5         # fp32 atomics in another order
+    assert rel_err(r1["act_out"][0], r2["act_out"][0]) < 2e-2   # the other schedule: another bf16 evaluation
+
+
 def test_fusion_levels_agree_on_the_benchmark_partition(gpu, oracle):
     """The three kernel schedules are three bf16 evaluations of the same batch."""
     spec = W.with_microbatching(W.config(3), 32, 2, loss_divisor=256)
