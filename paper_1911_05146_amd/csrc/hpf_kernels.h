@@ -107,8 +107,9 @@ hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_de
                                 const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
                                 hipStream_t stream);
 
-// ---- image-resident runs of identity bottleneck blocks (bf16 mode, BatchNorm on micro-batch statistics)
-// A run is a sequence of consecutive bottleneck blocks with stride 1 and identity shortcut.  One
+// ---- image-resident runs of identity blocks (bf16 mode, BatchNorm on micro-batch statistics)
+// A run is a sequence of consecutive blocks of one kind and shape (bottleneck or basic) with stride 1 and identity
+// shortcut.  One
 // work-group owns one image for the whole run: the residual stream of the image stays in LDS from block
 // to block, all three convolutions of a block run from LDS, and only what the backward pass and the
 // weight gradients read later goes to memory.  The one cross-image dependency, the BatchNorm reductions
@@ -118,6 +119,7 @@ hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_de
 constexpr unsigned long long RES_ACT_IN = ~0ull, RES_ACT_OUT = ~1ull, RES_ERR_IN = ~2ull, RES_ERR_OUT = ~3ull;
 struct ResBlock {
   // byte offsets into a micro-batch region (or RES_*): block input, conv1 / conv2 outputs, block output
+  // (basic blocks have two convolutions: c2 / dc2 and entry 2 of the arrays are unused)
   unsigned long long x_off, c1_off, c2_off, y_off;
   // gradients w.r.t. the block output, c1, c2, and where the gradient w.r.t. the block input goes
   unsigned long long gy_off, dc1_off, dc2_off, gx_off;
@@ -143,17 +145,17 @@ struct ResArgs {
   int* abort_flag;          // set when an exchange timed out (the pass is then invalid)
 };
 // Shapes this path covers (a property of the shapes alone).
-bool resident_shape_ok(int C, int MID, int H, int W, int nmem);
+bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem);   // kind: 0 basic (MID == C), 1 bottleneck
 // Largest number of micro-batches of nmem images one launch may hold on the current device (0: none):
 // every work-group takes a CU of its own and all of them must be resident together.
 int resident_max_group(int nmem);
 size_t resident_xchg_bytes(int C, int nmem);
 hipError_t resident_prepare();   // once per process, outside stream capture: raises the kernels' LDS limits
-hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
-hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream);
 // Weight gradients of all blocks of the run (after the backward launch): reads the stash and the gradient
 // tensors the backward launch wrote, adds into a.grads.
-hipError_t launch_resident_wgrad(int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream);
 
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);

@@ -88,7 +88,7 @@ struct Plan {
   size_t act_in_elems = 0, act_out_elems = 0;
   std::vector<PackDesc> table;
   // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
-  struct ResRun { int first = 0, count = 0, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
+  struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
   std::vector<ResRun> runs;
   std::vector<int> run_at;             // per block: index of the run that starts (forward) at this block, else -1
   std::vector<int> run_end_at;         // per block: index of the run that ends at this block, else -1
@@ -281,15 +281,17 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (P.dt == DT_BF16 && d.bn_mode == 0) {
     auto eligible = [&](int i) {
       const BlockPlan& p = P.bp[i];
-      return p.d.kind == 1 && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
+      return p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
     };
     int cmax_run = 0;
     for (int i = 0; i < d.n_blocks;) {
       if (!eligible(i)) { ++i; continue; }
       int j = i + 1;
-      while (j < d.n_blocks && eligible(j) && P.bp[j].d.c_in == P.bp[i].d.c_in && P.bp[j].d.c_mid == P.bp[i].d.c_mid) ++j;
+      while (j < d.n_blocks && eligible(j) && P.bp[j].d.kind == P.bp[i].d.kind && P.bp[j].d.c_in == P.bp[i].d.c_in &&
+             P.bp[j].d.c_mid == P.bp[i].d.c_mid)
+        ++j;
       Plan::ResRun r;
-      r.first = i; r.count = j - i; r.C = P.bp[i].d.c_in; r.MID = P.bp[i].d.c_mid;
+      r.first = i; r.count = j - i; r.kind = P.bp[i].d.kind; r.C = P.bp[i].d.c_in; r.MID = P.bp[i].d.c_mid;
       r.table_off = P.res_blocks.size() * sizeof(ResBlock);   // made absolute below
       auto res_loc = [](const Loc& l) -> unsigned long long {
         switch (l.kind) {
@@ -303,12 +305,13 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       for (int k = i; k < j; ++k) {
         const BlockPlan& p = P.bp[k];
         ResBlock rb{};
-        rb.x_off = res_loc(p.x_in); rb.c1_off = res_loc(p.c[0]); rb.c2_off = res_loc(p.c[1]); rb.y_off = res_loc(p.y);
-        rb.gy_off = res_loc(p.gy); rb.dc1_off = res_loc(p.dc[0]); rb.dc2_off = res_loc(p.dc[1]);
+        rb.x_off = res_loc(p.x_in); rb.c1_off = res_loc(p.c[0]); rb.y_off = res_loc(p.y);
+        rb.gy_off = res_loc(p.gy); rb.dc1_off = res_loc(p.dc[0]);
+        if (p.nconv == 3) { rb.c2_off = res_loc(p.c[1]); rb.dc2_off = res_loc(p.dc[1]); }
         Loc gx; gx.kind = CALLER_ERR_OUT;
         if (k > 0) gx = P.bp[k - 1].gy; else if (d.has_stem) gx = P.g_stem;
         rb.gx_off = res_loc(gx);
-        for (int q = 0; q < 3; ++q) {
+        for (int q = 0; q < p.nconv; ++q) {
           rb.stats_off[q] = p.bn[q].stats_off;
           rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off; rb.w_off[q] = p.cv[q].w_off;
           rb.gamma_off[q] = p.bn[q].g_off; rb.beta_off[q] = p.bn[q].b_off;
@@ -616,29 +619,36 @@ struct Ctx {
     a.xchg_off = P.xchg_off; a.tag_off = P.tag_off; a.abort_flag = h->abort_flag();
     return a;
   }
-  // algorithmic figures of a run: every stashed tensor once, data contractions only
+  // algorithmic figures of a run per image: every stashed tensor once (elements), contraction flop of one direction
+  static void res_figures(const Plan::ResRun& r, double px, double* stash_elems, double* flops) {
+    if (r.kind == 0) { *stash_elems = px * 2.0 * r.C; *flops = 2.0 * px * 2.0 * 9.0 * r.C * r.C; }
+    else { *stash_elems = px * (2.0 * r.MID + r.C); *flops = 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID); }
+  }
   void res_forward(const Plan::ResRun& r) {
     const BlockPlan& p0 = h->P.bp[r.first];
     const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
-    seg(PROF_RES_FWD, img * 2.0 * px * (r.C + r.count * (2.0 * r.MID + r.C)),
-        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
-    chk(launch_resident_forward(g, r.C, r.MID, res_args(r), s), "resident_forward");
+    double st, fl;
+    res_figures(r, px, &st, &fl);
+    seg(PROF_RES_FWD, img * 2.0 * (px * r.C + r.count * st), img * r.count * fl);
+    chk(launch_resident_forward(r.kind, g, r.C, r.MID, res_args(r), s), "resident_forward");
     seg_end();
   }
   void res_backward(const Plan::ResRun& r) {
     const BlockPlan& p0 = h->P.bp[r.first];
     const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
-    seg(PROF_RES_BWD, img * 2.0 * px * (r.C + r.count * (4.0 * r.MID + 2.0 * r.C)),
-        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
-    chk(launch_resident_backward(g, r.C, r.MID, res_args(r), s), "resident_backward");
+    double st, fl;
+    res_figures(r, px, &st, &fl);
+    seg(PROF_RES_BWD, img * 2.0 * (px * r.C + r.count * 2.0 * st), img * r.count * fl);
+    chk(launch_resident_backward(r.kind, g, r.C, r.MID, res_args(r), s), "resident_backward");
     seg_end();
   }
   void res_wgrad(const Plan::ResRun& r) {
     const BlockPlan& p0 = h->P.bp[r.first];
     const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
-    seg(PROF_RES_WGRAD, img * r.count * 2.0 * px * (4.0 * r.MID + 2.0 * r.C),
-        img * r.count * 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID));
-    chk(launch_resident_wgrad(g, r.C, r.MID, res_args(r), s), "resident_wgrad");
+    double st, fl;
+    res_figures(r, px, &st, &fl);
+    seg(PROF_RES_WGRAD, img * r.count * 2.0 * 2.0 * st, img * r.count * fl);
+    chk(launch_resident_wgrad(r.kind, g, r.C, r.MID, res_args(r), s), "resident_wgrad");
     seg_end();
   }
   void conv_wgrad(const ConvPlan& cv, const PtrTab& a, const PtrTab& dy) {

@@ -1046,6 +1046,290 @@ __global__ void __launch_bounds__(RW_NT) k_res_wgrad(const ResWgArgs a) {
                            B.gy_off, C, (item - NCH - 1) * 64, a.grads + B.w_off[2], smem);
 }
 
+// ------------------------------------------------------------------------------------------ basic blocks
+// The same ownership for runs of basic blocks (two 3x3 convolutions of C channels, identity shortcut: the
+// ResNet-20 / ResNet-110 family):  a1 = relu(bn1(x)); c1 = conv1(a1); a2 = relu(bn2(c1)); y = x + conv2(a2).
+// Two exchanges per block and direction.  ResBlock fields used: x, c1, y, gy, dc1, gx and entries 0 / 1 of the
+// per-BatchNorm / per-convolution arrays.
+template <int Cc>
+struct TwoTiles {   // two [P][Cc] tiles fetched in one round trip
+  static constexpr int NU = (256 * Cc / 8 + RES_NT - 1) / RES_NT;   // images of up to 256 pixels
+  uint4 t0[NU], t1[NU];
+  __device__ __forceinline__ void issue(const bf16_t* g0, const bf16_t* g1, int P) {
+    const int units = P * (Cc / 8);
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT, uc = u < units ? u : 0;
+      t0[i] = *reinterpret_cast<const uint4*>(g0 + (size_t)uc * 8);
+      t1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
+    }
+  }
+  __device__ __forceinline__ void commit(bf16_t* s0, bf16_t* s1, int P) const {
+    constexpr int U = Cc / 8;
+    const int units = P * U;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      if (u < units) {
+        const int row = u / U, col = u - row * U;
+        *reinterpret_cast<uint4*>(s0 + row * (Cc + 8) + col * 8) = t0[i];
+        *reinterpret_cast<uint4*>(s1 + row * (Cc + 8) + col * 8) = t1[i];
+      }
+    }
+  }
+};
+// dst = relu(src*scale + shift), tile to tile
+template <int Cc>
+__device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, const float2* coef, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    const uint4 v = *reinterpret_cast<const uint4*>(src + row * (Cc + 8) + col * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const float4* cf = reinterpret_cast<const float4*>(coef + col * 8);
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 k = cf[i];
+      r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(w[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(w[i]), k.z, k.w), 0.f));
+    }
+    *reinterpret_cast<uint4*>(dst + row * (Cc + 8) + col * 8) = make_uint4(r[0], r[1], r[2], r[3]);
+  }
+}
+
+template <int C, int PTW, bool PRE>
+__global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sx = reinterpret_cast<bf16_t*>(smem);           // residual stream of the image, [P][XS]
+  bf16_t* sA = sx + (size_t)P * XS;                       // relu(bn1(x))
+  bf16_t* sB = sA + (size_t)P * XS;                       // c1, then relu(bn2(c1))
+  float2* coef = reinterpret_cast<float2*>(sB + (size_t)P * XS);
+  float* red = reinterpret_cast<float*>(coef + C);        // RES_NWV * 2*C floats
+  float* own = red + RES_NWV * 2 * C;
+  float* gath = gath_own ? own : reinterpret_cast<float*>(sA);
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+  WFrags<9 * C / 32, C / 16, PRE> w1, w2;
+
+  auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+      if (pt < npt)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt)
+          *reinterpret_cast<uint2*>(dst + (pt * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+    }
+  };
+  {
+    const ResBlock B0 = a.blocks[0];
+    tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
+    w1.load(a.packed + B0.wf_off[0], 9 * C, fr, fk);
+    __syncthreads();
+    stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
+    if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
+    ++phase;
+    merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coef,
+                  me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+  }
+  for (int bi = 0; bi < a.nblk; ++bi) {
+    const ResBlock B = a.blocks[bi];
+    tile_bn_relu_to<C>(sA, sx, coef, P);
+    __syncthreads();
+    {   // ---- conv1 (3x3) on relu(bn1(x))
+      floatx4 acc[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, false>(sA, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      store_acc(sB, acc);
+    }
+    w2.load(a.packed + B.wf_off[1], 9 * C, fr, fk);
+    __syncthreads();
+    stats_publish<C>(sB, P, red, slot(), me, tag0 + 1u + phase);
+    tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
+    if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;   // sA is free: conv1 is done
+    ++phase;
+    merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
+                  me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    tile_bn_relu<C>(sB, coef, P);
+    __syncthreads();
+    {   // ---- conv2 (3x3) on relu(bn2(c1)) + shortcut, written over x
+      floatx4 acc[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, false>(sB, w2, a.H, a.W, npt, wave, fr, fk, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt) {
+            uint2* q = reinterpret_cast<uint2*>(sx + (pt * 16 + fr) * XS + nt * 16 + fq * 4);
+            const uint2 xr = *q;
+            floatx4 v = acc[j][nt];
+            v[0] += bf_lo(xr.x); v[1] += bf_hi(xr.x); v[2] += bf_lo(xr.y); v[3] += bf_hi(xr.y);
+            *q = pack4(v);
+          }
+      }
+    }
+    const bool more = bi + 1 < a.nblk;
+    const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
+    if (more) w1.load(a.packed + Bn.wf_off[0], 9 * C, fr, fk);
+    __syncthreads();
+    if (more) stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
+    tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+    if (more) {
+      if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
+      ++phase;
+      merge_coef<C>(gath, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coef,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
+    }
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
+template <int C, int PTW, bool PRE>
+__global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream
+  bf16_t* s0 = sdy + (size_t)P * XS;                      // x   (BN1 input)
+  bf16_t* s1 = s0 + (size_t)P * XS;                       // c1  (BN2 input)
+  bf16_t* sdc = s1 + (size_t)P * XS;                      // dc1
+  float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * XS);
+  float4* cf2 = cf1 + C;
+  float* red = reinterpret_cast<float*>(cf2 + C);         // RES_NWV * 2*C floats
+  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);
+  float* own = reinterpret_cast<float*>(tab + C);
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+  WFrags<9 * C / 32, C / 16, PRE> w2, w1;   // data-gradient operands [C][9*C]
+
+  auto xin_from = [&](const bf16_t* t, uint2 (&xin)[PTW][C / 16]) {
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt)
+        xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(t + (pt * 16 + fr) * XS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+    }
+  };
+  {
+    const ResBlock BL = a.blocks[a.nblk - 1];
+    tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+  }
+  for (int bi = a.nblk - 1; bi >= 0; --bi) {
+    const ResBlock B = a.blocks[bi];
+    {   // one round trip to memory for everything the block reads up front
+      TwoTiles<C> ld;
+      ld.issue(cx.tensor(B.x_off) + (size_t)me * P * C, cx.tensor(B.c1_off) + (size_t)me * P * C, P);
+      const int c = tid < C ? tid : 0;
+      const float4 t1 = BwdLoads<C, C>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0],
+                                              a.params + B.beta_off[0], c, C);
+      const float4 t2 = BwdLoads<C, C>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
+                                              a.params + B.beta_off[1], c, C);
+      w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
+      ld.commit(s0, s1, P);
+      if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
+    }
+    __syncthreads();
+    {   // ---- conv2 data gradient, BN2 + ReLU backward -> dc1
+      floatx4 acc[PTW][C / 16];
+      uint2 xin[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, true>(sdy, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      xin_from(s1, xin);
+      w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
+      if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                   a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag,
+                                   [&](int j, int nt, const floatx4& out) {
+                                     *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(out);
+                                   }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.dc1_off) + (size_t)me * P * C, sdc, P);
+    {   // ---- conv1 data gradient, BN1 + ReLU backward, plus the shortcut: dx = bn1_bwd(...) + dy over dy
+      floatx4 acc[PTW][C / 16];
+      uint2 xin[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      xin_from(s0, xin);
+      float* gath = gath_own ? own : reinterpret_cast<float*>(s1);   // c1 is no longer read
+      if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
+                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
+                                   [&](int j, int nt, const floatx4& out) {
+                                     uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
+                                     const uint2 d = *q;
+                                     floatx4 v = out;
+                                     v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
+                                     *q = pack4(v);
+                                   }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
+// weight gradients of a run of basic blocks: grid (image groups, 2 convolutions, blocks)
+template <int C>
+__global__ void __launch_bounds__(RW_NT) k_bb_wgrad(const ResWgArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ResBlock B = a.blocks[blockIdx.z];
+  const int img0 = blockIdx.x * a.ipw;
+  if (blockIdx.y == 0)
+    res_wgrad_3x3<C>(a, img0, B.x_off, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0], B.dc1_off,
+                     a.grads + B.w_off[0], smem);
+  else
+    res_wgrad_3x3<C>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.gy_off,
+                     a.grads + B.w_off[1], smem);
+}
+
+size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
+  const size_t tile = (size_t)P * (C + 8) * 2;
+  const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16
+                                : (size_t)C * 8 + (size_t)RES_NWV * 2 * C * 4;
+  *own = (size_t)nmem * 2 * C * 4 > tile ? 1 : 0;
+  return (backward ? 4 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
+}
+size_t bb_wgrad_lds(int C, int P, int W) {
+  return (size_t)3 * C * (P + 2 * W + 8) * 2 + (size_t)C * (P + 8) * 2 + (size_t)C * 8;
+}
+
 size_t wgrad_lds(int C, int MID, int P, int W) {
   const size_t one = (size_t)(64 + MID) * (P + 8) * 2 + 64 * 8;
   const size_t three = (size_t)3 * MID * (P + 2 * W + 8) * 2 + (size_t)MID * (P + 8) * 2 + (size_t)MID * 8;
@@ -1083,14 +1367,19 @@ hipError_t launch_res(K kernel, size_t lds, int own, int g, const ResArgs& a, hi
 
 size_t resident_xchg_bytes(int C, int nmem) { return 2 * (size_t)nmem * 2 * C * sizeof(u64); }
 
-bool resident_shape_ok(int C, int MID, int H, int W, int nmem) {
-  if (!((C == 128 && MID == 32) || (C == 256 && MID == 64))) return false;
+bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   const int P = H * W;
   // whole 32-pixel reduction steps in the weight gradients; image rows that keep 16-byte alignment under a row shift
   // and whose pixel pairs fit the 16-lane rows used for neighbour exchange
-  if (H <= 0 || (W != 8 && W != 16 && W != 32) || P % 32 || P > 16 * (C == 128 ? 2 : 1) * RES_NWV) return false;
+  if (H <= 0 || (W != 8 && W != 16 && W != 32) || P % 32) return false;
   if (nmem < 1 || nmem > 1024) return false;
   int own = 0;
+  if (kind == 0) {   // basic blocks: C -> C -> C
+    if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
+    return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
+           bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES;
+  }
+  if (!((C == 128 && MID == 32 && P <= 256) || (C == 256 && MID == 64 && P <= 128))) return false;
   return fwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES && bwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES;
 }
 
@@ -1109,37 +1398,60 @@ hipError_t resident_prepare() {
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* bb[] = {reinterpret_cast<const void*>(k_bb_forward<32, 2, true>),  reinterpret_cast<const void*>(k_bb_forward<64, 1, false>),
+                      reinterpret_cast<const void*>(k_bb_backward<32, 2, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false>),
+                      reinterpret_cast<const void*>(k_bb_wgrad<32>),             reinterpret_cast<const void*>(k_bb_wgrad<64>)};
+  for (const void* f : bb)
+    if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<128, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<256, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
-hipError_t launch_resident_forward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
+hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
+  if (kind == 0) {
+    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 32) return launch_res(k_bb_forward<32, 2, true>, lds, own, g, a, stream);
+    return launch_res(k_bb_forward<64, 1, false>, lds, own, g, a, stream);
+  }
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
   if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
-hipError_t launch_resident_wgrad(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
+hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
   ResWgArgs w{};
   w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
   w.ipw = 1;
   for (int k = 8; k >= 1; k >>= 1)
     if (a.nmem % k == 0) { w.ipw = k; break; }
   w.base = a.base; w.act_in = a.act_in; w.err_in = a.err_in; w.params = a.params; w.grads = a.grads;
+  const unsigned groups = (unsigned)(g * a.nmem / w.ipw);
+  if (kind == 0) {
+    const size_t lds = bb_wgrad_lds(C, a.H * a.W, a.W);
+    const dim3 grid(groups, 2u, (unsigned)a.nblk);
+    if (C == 32) k_bb_wgrad<32><<<grid, RW_NT, lds, stream>>>(w);
+    else k_bb_wgrad<64><<<grid, RW_NT, lds, stream>>>(w);
+    return hipGetLastError();
+  }
   const size_t lds = wgrad_lds(C, MID, a.H * a.W, a.W);
-  const dim3 grid((unsigned)(g * a.nmem / w.ipw), (unsigned)(2 * (C / 64) + 1), (unsigned)a.nblk);
+  const dim3 grid(groups, (unsigned)(2 * (C / 64) + 1), (unsigned)a.nblk);
   if (C == 128) k_res_wgrad<128, 32><<<grid, RW_NT, lds, stream>>>(w);
   else k_res_wgrad<256, 64><<<grid, RW_NT, lds, stream>>>(w);
   return hipGetLastError();
 }
 
-hipError_t launch_resident_backward(int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (!resident_shape_ok(C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
+hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
+  if (kind == 0) {
+    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
+    if (C == 32) return launch_res(k_bb_backward<32, 2, true>, lds, own, g, a, stream);
+    return launch_res(k_bb_backward<64, 1, false>, lds, own, g, a, stream);
+  }
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
   if (C == 128) return launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);

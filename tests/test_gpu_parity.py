@@ -113,6 +113,21 @@ def test_image_resident_runs_small(gpu, oracle):
         check(oracle, spec, "bf16", grouped=grouped)
 
 
+def test_image_resident_runs_of_basic_blocks(gpu, oracle):
+    """The ResNet-20 / ResNet-110 family: runs of basic blocks (two 3x3 convolutions) in the image-resident kernels."""
+    def basic_run(name, c, hw, n, b, m, seed=43):
+        blk = W.Block(W.BASIC, c, c, c, 1)
+        return W.PartitionSpec(name=name, in_h=hw, in_w=hw, in_c=c, blocks=(blk,) * n, microbatch=b, num_microbatches=m, seed=seed)
+    for spec, grouped in ((basic_run("resident-basic-32x16x16", 32, 16, 2, 2, 2), False),
+                          (basic_run("resident-basic-64x8x8", 64, 8, 3, 3, 2), True),
+                          (replace(basic_run("resident-basic-32x8x16", 32, 16, 2, 2, 3, seed=45), in_h=8), True)):
+        check(oracle, spec, "bf16", strict=True, beta_shift=6.0, grouped=grouped)
+        check(oracle, replace(spec, blocks=spec.blocks[:1], microbatch=1), "bf16", strict=True, seeds=5, grouped=grouped)
+        check(oracle, spec, "bf16", grouped=grouped)
+    check(oracle, basic_run("resident-basic-deep", 32, 16, 9, 16, 2), "bf16", grouped=True)
+    check(oracle, basic_run("resident-basic-deep-active", 32, 16, 9, 16, 2), "bf16", beta_shift=6.0, grouped=True)
+
+
 def test_image_resident_runs_deep_and_mixed(gpu, oracle):
     """Deep runs (ReLU always active: element-wise; otherwise the sensitivity-limited criterion), runs between
     other units (stem, projection blocks, head), runs split by a shape change, and groups of micro-batches."""
