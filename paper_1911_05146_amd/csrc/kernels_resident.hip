@@ -322,8 +322,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   float2* coefC = reinterpret_cast<float2*>(smB + (size_t)P * MS);
   float2* coefM = coefC + C;
   float* red = reinterpret_cast<float*>(coefM + MID);     // RES_NWV * 2*C floats
-  float* mine = red + RES_NWV * 2 * C;                    // 2*C floats
-  float* own = mine + 2 * C;                              // gather area of its own when the tiles are too small
+  float* own = red + RES_NWV * 2 * C;                     // gather area of its own when the tiles are too small
   float* gathA = gath_own ? own : reinterpret_cast<float*>(smA);
   float* gathB = gath_own ? own : reinterpret_cast<float*>(smB);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
@@ -1340,7 +1339,7 @@ size_t wgrad_lds(int C, int MID, int P, int W) {
 // LDS bytes of the two kernels; *own = 1 when the gather area cannot overlay the small tiles
 size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
-  const size_t fixed = (size_t)(C + MID) * 8 + (size_t)RES_NWV * 2 * C * 4 + 2 * (size_t)C * 4;
+  const size_t fixed = (size_t)(C + MID) * 8 + (size_t)RES_NWV * 2 * C * 4;
   const size_t one_tile = (size_t)P * (MID + 8) * 2;
   *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
   return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
