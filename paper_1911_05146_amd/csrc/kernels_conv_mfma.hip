@@ -361,7 +361,7 @@ int pick_tile(int ng, const ConvGeom& g) {
   // latency bound and want many small work-groups
   if (g.N % 128 == 0 && g.Kpad >= 512) {
     const long wgs = (long)((g.M + 127) / 128) * (g.N / 128) * ng;
-    if (wgs >= 192) return 0;
+    if (wgs >= 512) return 0;   // at least two work-groups per CU, else the smaller tile hides latency better
   }
   if (g.N % 64 == 0) return 1;
   if (g.N % 32 == 0) return 2;
