@@ -24,6 +24,22 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int MC = 128;         // pixel rows per step (32 per wave)
 constexpr int LSTR = MC + 8;    // LDS row stride in bf16 (272 bytes)
 
+// A staging unit is (pixel pair of the 128-row step, group of 8 channels).  With at least 4 channel groups,
+// four neighbouring lanes take four consecutive groups of one pair (64 contiguous bytes of a pixel) and the
+// 16 lane quads of a wave 16 consecutive pairs: global loads touch 16 cache lines per instruction instead of
+// 64, and the transposing LDS stores stay within a 2-way bank conflict.  Narrow tiles keep one pair per lane.
+template <int G>
+__device__ __forceinline__ void unit_map(int unit, int& pr, int& grp) {
+  if (G >= 4) {
+    const int lane = unit & 63, q = unit >> 6;
+    grp = (q % (G / 4)) * 4 + (lane & 3);
+    pr = (q / (G / 4)) * 16 + (lane >> 2);
+  } else {
+    pr = unit & 63;
+    grp = unit >> 6;
+  }
+}
+
 template <int BC, int BN>
 struct WgradTile {
   static constexpr int CTL = BC / 16, NTL = BN / 16;
@@ -59,7 +75,9 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
     for (int u = 0; u < A_UNITS; ++u) {
       const int unit = tid + u * 256;
       if (unit < 64 * (BC / 8)) {
-        const int c = c0 + (unit >> 6) * 8;
+        int pr_, cg_;
+        unit_map<BC / 8>(unit, pr_, cg_);
+        const int c = c0 + cg_ * 8;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float sc = gamma[c + i] * bn_stats[g.Cin + c + i];
@@ -83,7 +101,8 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
       const int unit = tid + u * 256;
-      const int pr = unit & 63, cg = unit >> 6;
+      int pr, cg;
+      unit_map<BC / 8>(unit < 64 * (BC / 8) ? unit : 0, pr, cg);
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
@@ -104,7 +123,8 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 #pragma unroll
     for (int u = 0; u < D_UNITS; ++u) {
       const int unit = tid + u * 256;
-      const int pr = unit & 63, ng = unit >> 6;
+      int pr, ng;
+      unit_map<BN / 8>(unit < 64 * (BN / 8) ? unit : 0, pr, ng);
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
@@ -114,8 +134,7 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
     }
   };
   // {lo half of x = element 2i, hi half = element 2i+1}: interleave two rows into {row0, row1} dwords
-  auto store_pairs = [&](bf16_t* tile_base, int unit, const uint4& v0, const uint4& v1) {
-    const int pr = unit & 63, grp = unit >> 6;
+  auto store_pairs = [&](bf16_t* tile_base, int pr, int grp, const uint4& v0, const uint4& v1) {
     uint32_t* dst = reinterpret_cast<uint32_t*>(tile_base + (grp * 8) * LSTR + 2 * pr);
     constexpr int RS = LSTR / 2;  // dwords per LDS row
     const uint32_t e0[4] = {v0.x, v0.y, v0.z, v0.w}, e1[4] = {v1.x, v1.y, v1.z, v1.w};
@@ -134,13 +153,19 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
           if (rv[u][0]) ra[u][0] = bn_relu8(ra[u][0], cf[u]);
           if (rv[u][1]) ra[u][1] = bn_relu8(ra[u][1], cf[u]);
         }
-        store_pairs(sA, unit, ra[u][0], ra[u][1]);
+        int pr, cg;
+        unit_map<BC / 8>(unit, pr, cg);
+        store_pairs(sA, pr, cg, ra[u][0], ra[u][1]);
       }
     }
 #pragma unroll
     for (int u = 0; u < D_UNITS; ++u) {
       const int unit = tid + u * 256;
-      if (unit < 64 * (BN / 8)) store_pairs(sD, unit, rd[u][0], rd[u][1]);
+      if (unit < 64 * (BN / 8)) {
+        int pr, ng;
+        unit_map<BN / 8>(unit, pr, ng);
+        store_pairs(sD, pr, ng, rd[u][0], rd[u][1]);
+      }
     }
   };
 
