@@ -100,9 +100,12 @@ struct WgradItem {
   WgradGeom g;
   int tap, c0, n0, m_begin, m_end;
 };
-// tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}
+// tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}; 9 = 128 x 128 (both channel counts
+// multiples of 128: each wave owns a 64 x 64 quadrant of the tile over the whole reduction)
+constexpr int WGRAD_CLASSES = 10;
 int wgrad_tile_class(int cin, int cout);
 void wgrad_tile_dims(int tile_class, int* bc, int* bn);
+hipError_t wgrad_prepare();   // once per device before the first grouped launch
 hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
                                 const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
                                 hipStream_t stream);

@@ -78,12 +78,12 @@ struct Plan {
   size_t params_off = 0, grads_off = 0, mom_off = 0, packed_off = 0, table_off = 0, mb_off = 0;
   size_t packed_elems = 0; int n_convs = 0;
   Loc g_stem;                          // gradient w.r.t. the stem output
-  std::vector<WgradItem> items[9];     // deferred weight-gradient work, per tile class (bf16 mode)
-  std::vector<WgradItem> items_nr[9];  // the same without the blocks of image-resident runs (those have a launch of their own)
-  size_t items_nr_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-  double wg_nr_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, wg_nr_flops[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-  size_t items_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-  double wg_bytes[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0}, wg_flops[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};   // per micro-batch
+  std::vector<WgradItem> items[WGRAD_CLASSES];     // deferred weight-gradient work, per tile class (bf16 mode)
+  std::vector<WgradItem> items_nr[WGRAD_CLASSES];  // the same without the blocks of image-resident runs (those have a launch of their own)
+  size_t items_nr_off[WGRAD_CLASSES] = {};
+  double wg_nr_bytes[WGRAD_CLASSES] = {}, wg_nr_flops[WGRAD_CLASSES] = {};
+  size_t items_off[WGRAD_CLASSES] = {};
+  double wg_bytes[WGRAD_CLASSES] = {}, wg_flops[WGRAD_CLASSES] = {};   // per micro-batch
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
   std::vector<PackDesc> table;
@@ -351,7 +351,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
     for (int pass = 0; pass < 2; ++pass) {   // pass 1: without the convolutions of image-resident runs
     if (pass == 1 && P.runs.empty()) break;
-    long tiles_in_class[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    long tiles_in_class[WGRAD_CLASSES] = {};
     for (const WConv& w : wc) {
       if (pass == 1 && w.in_run) continue;
       const int cls = wgrad_tile_class(w.cin_run, w.cv->cout);
@@ -402,8 +402,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.mom_off = g;    g += align_up(P.n_params * sizeof(float));
   P.packed_off = g; g += align_up(P.packed_elems * 2);
   P.table_off = g;  g += align_up(P.table.size() * sizeof(PackDesc));
-  for (int k = 0; k < 9; ++k) { P.items_off[k] = g; g += align_up(P.items[k].size() * sizeof(WgradItem)); }
-  for (int k = 0; k < 9; ++k) { P.items_nr_off[k] = g; g += align_up(P.items_nr[k].size() * sizeof(WgradItem)); }
+  for (int k = 0; k < WGRAD_CLASSES; ++k) { P.items_off[k] = g; g += align_up(P.items[k].size() * sizeof(WgradItem)); }
+  for (int k = 0; k < WGRAD_CLASSES; ++k) { P.items_nr_off[k] = g; g += align_up(P.items_nr[k].size() * sizeof(WgradItem)); }
   P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
   for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
   P.abort_off = g;  g += align_up(sizeof(int));
@@ -784,7 +784,7 @@ void run_backward(Ctx& c) {
     const bool res = c.h->resident();
     if (res)
       for (const Plan::ResRun& r : P.runs) c.res_wgrad(r);
-    for (int k = 0; k < 9; ++k) {
+    for (int k = 0; k < WGRAD_CLASSES; ++k) {
       const std::vector<WgradItem>& items = res ? P.items_nr[k] : P.items[k];
       if (items.empty()) continue;
       c.seg(PROF_WGRAD, c.g * (res ? P.wg_nr_bytes : P.wg_bytes)[k], c.g * (res ? P.wg_nr_flops : P.wg_flops)[k]);
@@ -937,12 +937,13 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     ok(hipMemcpy(p->arena + P.table_off, P.table.data(), P.table.size() * sizeof(PackDesc), hipMemcpyHostToDevice));
     ok(launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, nullptr));
   }
-  for (int k = 0; k < 9; ++k)
+  for (int k = 0; k < WGRAD_CLASSES; ++k)
     if (!P.items[k].empty())
       ok(hipMemcpy(p->arena + P.items_off[k], P.items[k].data(), P.items[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
-  for (int k = 0; k < 9; ++k)
+  for (int k = 0; k < WGRAD_CLASSES; ++k)
     if (!P.items_nr[k].empty())
       ok(hipMemcpy(p->arena + P.items_nr_off[k], P.items_nr[k].data(), P.items_nr[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
+  if (!P.items[WGRAD_CLASSES - 1].empty()) ok(wgrad_prepare());
   if (!P.runs.empty()) {
     ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
     ok(hipMemset(p->abort_flag(), 0, sizeof(int)));

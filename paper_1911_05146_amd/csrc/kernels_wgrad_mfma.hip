@@ -21,8 +21,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int MC = 128;         // pixel rows per step (32 per wave)
-constexpr int LSTR = MC + 8;    // LDS row stride in bf16 (272 bytes)
+constexpr int MC = 128;         // pixel rows per step (32 per wave); the 128 x 128 class takes 64-row steps
 
 // A staging unit is (pixel pair of the 128-row step, group of 8 channels).  With at least 4 channel groups,
 // four neighbouring lanes take four consecutive groups of one pair (64 contiguous bytes of a pixel) and the
@@ -40,14 +39,17 @@ __device__ __forceinline__ void unit_map(int unit, int& pr, int& grp) {
   }
 }
 
-template <int BC, int BN>
+template <int BC, int BN, int ROWS = MC>
 struct WgradTile {
   static constexpr int CTL = BC / 16, NTL = BN / 16;
-  static constexpr int A_UNITS = (64 * (BC / 8) + 255) / 256;
-  static constexpr int D_UNITS = (64 * (BN / 8) + 255) / 256;
+  static constexpr int PAIRS = ROWS / 2;            // pixel pairs per step
+  static constexpr int LSTR = ROWS + 8;             // LDS row stride in bf16 (272 or 144 bytes: 16 rows hit 16 bank groups)
+  static constexpr int A_UNITS = (PAIRS * (BC / 8) + 255) / 256;
+  static constexpr int D_UNITS = (PAIRS * (BN / 8) + 255) / 256;
   static constexpr int LDS_A = BC * LSTR, LDS_D = BN * LSTR;
   static constexpr int RED_BYTES = BC * BN * 4;
   static constexpr int OP_BYTES = (LDS_A + LDS_D) * 2;
+  static constexpr int QUAD_BYTES = OP_BYTES + BC * 8;   // + {scale, shift} per tile channel
   static constexpr int SMEM_BYTES = OP_BYTES > RED_BYTES ? OP_BYTES : RED_BYTES;
 };
 
@@ -56,32 +58,49 @@ struct WgradTile {
 // bn_stats != nullptr: `a` is the input of a BatchNorm and the operand is relu(bn(a)), recomputed while
 // staging from {mean, invstd} = bn_stats[0..Cin), [Cin..2Cin) and gamma / beta (the normalised
 // activation is not kept in memory); rows outside the image stay zero.
-template <int BC, int BN>
+// QUAD = false: the four waves take 32-row slices of each step and all accumulate the whole BC x BN tile
+// (acc is [BC/16][BN/16], summed over the waves afterwards).  QUAD = true (large tiles): every wave takes all
+// rows of the step and owns one quadrant of the tile (acc is [BC/32][BN/32]): half the operand traffic per flop.
+template <int BC, int BN, bool QUAD = false>
 __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, const bf16_t* __restrict__ dy, const WgradGeom& g,
                                                  int tap, int c0, int n0, int m_begin, int m_end, bf16_t* sA, bf16_t* sD,
-                                                 floatx4 (&acc)[BC / 16][BN / 16], const float* bn_stats = nullptr,
-                                                 const float* gamma = nullptr, const float* beta = nullptr) {
-  typedef WgradTile<BC, BN> TT;
-  constexpr int CTL = TT::CTL, NTL = TT::NTL, A_UNITS = TT::A_UNITS, D_UNITS = TT::D_UNITS;
+                                                 floatx4 (&acc)[BC / (QUAD ? 32 : 16)][BN / (QUAD ? 32 : 16)],
+                                                 const float* bn_stats = nullptr, const float* gamma = nullptr,
+                                                 const float* beta = nullptr) {
+  constexpr int ROWS = QUAD ? 64 : MC;
+  typedef WgradTile<BC, BN, ROWS> TT;
+  constexpr int CTL = BC / (QUAD ? 32 : 16), NTL = BN / (QUAD ? 32 : 16), A_UNITS = TT::A_UNITS, D_UNITS = TT::D_UNITS;
+  constexpr int LSTR = TT::LSTR, A_N = TT::PAIRS * (BC / 8), D_N = TT::PAIRS * (BN / 8);   // staging units per step
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = tap / g.R, s = tap - r * g.R;
   const int HoWo = g.Ho * g.Wo;
 
   uint4 ra[A_UNITS][2], rd[D_UNITS][2];
   bool rv[A_UNITS][2];
-  float2 cf[A_UNITS][8];   // {scale, shift} of this thread's 8 channels (fixed over the steps)
+  // {scale, shift} of the BatchNorm: held per thread for its 8 channels (fixed over the steps), or -- for the
+  // large tiles, where registers are short -- per tile channel in LDS behind the operand tiles
+  float2 cf[QUAD ? 1 : A_UNITS][8];
+  float2* sCf = reinterpret_cast<float2*>(sD + TT::LDS_D);
   if (bn_stats) {
+    if (QUAD) {
+      if (tid < BC) {
+        const int c = c0 + tid;
+        const float sc = gamma[c] * bn_stats[g.Cin + c];
+        sCf[tid] = make_float2(sc, beta[c] - bn_stats[c] * sc);   // read after the first barrier of the step loop
+      }
+    } else {
 #pragma unroll
-    for (int u = 0; u < A_UNITS; ++u) {
-      const int unit = tid + u * 256;
-      if (unit < 64 * (BC / 8)) {
-        int pr_, cg_;
-        unit_map<BC / 8>(unit, pr_, cg_);
-        const int c = c0 + cg_ * 8;
+      for (int u = 0; u < A_UNITS; ++u) {
+        const int unit = tid + u * 256;
+        if (unit < A_N) {
+          int pr_, cg_;
+          unit_map<BC / 8>(unit, pr_, cg_);
+          const int c = c0 + cg_ * 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float sc = gamma[c + i] * bn_stats[g.Cin + c + i];
-          cf[u][i] = make_float2(sc, beta[c + i] - bn_stats[c + i] * sc);
+          for (int i = 0; i < 8; ++i) {
+            const float sc = gamma[c + i] * bn_stats[g.Cin + c + i];
+            cf[QUAD ? 0 : u][i] = make_float2(sc, beta[c + i] - bn_stats[c + i] * sc);
+          }
         }
       }
     }
@@ -102,11 +121,11 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
     for (int u = 0; u < A_UNITS; ++u) {
       const int unit = tid + u * 256;
       int pr, cg;
-      unit_map<BC / 8>(unit < 64 * (BC / 8) ? unit : 0, pr, cg);
+      unit_map<BC / 8>(unit < A_N ? unit : 0, pr, cg);
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
-        bool v = (unit < 64 * (BC / 8)) && m < m_end;
+        bool v = (unit < A_N) && m < m_end;
         size_t off = 0;
         if (v) {
           const int img = m / HoWo;
@@ -124,11 +143,11 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
     for (int u = 0; u < D_UNITS; ++u) {
       const int unit = tid + u * 256;
       int pr, ng;
-      unit_map<BN / 8>(unit < 64 * (BN / 8) ? unit : 0, pr, ng);
+      unit_map<BN / 8>(unit < D_N ? unit : 0, pr, ng);
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
-        const bool v = (unit < 64 * (BN / 8)) && m < m_end;
+        const bool v = (unit < D_N) && m < m_end;
         rd[u][e] = v ? *reinterpret_cast<const uint4*>(dy + (size_t)m * g.N + n0 + ng * 8) : make_uint4(0u, 0u, 0u, 0u);
       }
     }
@@ -148,20 +167,29 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
       const int unit = tid + u * 256;
-      if (unit < 64 * (BC / 8)) {
-        if (bn_stats) {
-          if (rv[u][0]) ra[u][0] = bn_relu8(ra[u][0], cf[u]);
-          if (rv[u][1]) ra[u][1] = bn_relu8(ra[u][1], cf[u]);
-        }
+      if (unit < A_N) {
         int pr, cg;
         unit_map<BC / 8>(unit, pr, cg);
+        if (bn_stats) {
+          if (QUAD) {
+            const float4* k4 = reinterpret_cast<const float4*>(sCf + cg * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float4 k = k4[i];
+              cf[0][2 * i] = make_float2(k.x, k.y);
+              cf[0][2 * i + 1] = make_float2(k.z, k.w);
+            }
+          }
+          if (rv[u][0]) ra[u][0] = bn_relu8(ra[u][0], cf[QUAD ? 0 : u]);
+          if (rv[u][1]) ra[u][1] = bn_relu8(ra[u][1], cf[QUAD ? 0 : u]);
+        }
         store_pairs(sA, pr, cg, ra[u][0], ra[u][1]);
       }
     }
 #pragma unroll
     for (int u = 0; u < D_UNITS; ++u) {
       const int unit = tid + u * 256;
-      if (unit < 64 * (BN / 8)) {
+      if (unit < D_N) {
         int pr, ng;
         unit_map<BN / 8>(unit, pr, ng);
         store_pairs(sD, pr, ng, rd[u][0], rd[u][1]);
@@ -171,21 +199,39 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 
   const int frag_row = lane & 15, frag_m = wave * 32 + (lane >> 4) * 8;
   if (m_begin < m_end) load_step(m_begin);
-  for (int m0 = m_begin; m0 < m_end; m0 += MC) {
+  for (int m0 = m_begin; m0 < m_end; m0 += ROWS) {
     __syncthreads();  // previous step's LDS reads are done
     store_step();
     __syncthreads();
-    if (m0 + MC < m_end) load_step(m0 + MC);
-    bf16x8 fa[CTL], fd[NTL];
+    if (m0 + ROWS < m_end) load_step(m0 + ROWS);
+    if (QUAD) {
+      const int qc = (wave >> 1) * (BC / 2), qn = (wave & 1) * (BN / 2);
 #pragma unroll
-    for (int i = 0; i < CTL; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sA[(i * 16 + frag_row) * LSTR + frag_m]);
+      for (int ks = 0; ks < ROWS / 32; ++ks) {
+        const int fm = ks * 32 + (lane >> 4) * 8;
+        bf16x8 fa[CTL], fd[NTL];
 #pragma unroll
-    for (int j = 0; j < NTL; ++j) fd[j] = *reinterpret_cast<const bf16x8*>(&sD[(j * 16 + frag_row) * LSTR + frag_m]);
+        for (int i = 0; i < CTL; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sA[(qc + i * 16 + frag_row) * LSTR + fm]);
 #pragma unroll
-    for (int i = 0; i < CTL; ++i)
+        for (int j = 0; j < NTL; ++j) fd[j] = *reinterpret_cast<const bf16x8*>(&sD[(qn + j * 16 + frag_row) * LSTR + fm]);
 #pragma unroll
-      for (int j = 0; j < NTL; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fd[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < CTL; ++i)
+#pragma unroll
+          for (int j = 0; j < NTL; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fd[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
+      bf16x8 fa[CTL], fd[NTL];
+#pragma unroll
+      for (int i = 0; i < CTL; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sA[(i * 16 + frag_row) * LSTR + frag_m]);
+#pragma unroll
+      for (int j = 0; j < NTL; ++j) fd[j] = *reinterpret_cast<const bf16x8*>(&sD[(j * 16 + frag_row) * LSTR + frag_m]);
+#pragma unroll
+      for (int i = 0; i < CTL; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fd[j], acc[i][j], 0, 0, 0);
+    }
   }
 }
 
@@ -264,6 +310,45 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restri
   wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0);
 }
 
+// The 128 x 128 class: every wave owns a 64 x 64 quadrant over the whole reduction, so the sums go straight
+// from the accumulators to the gradient buffer (one atomic per output element and work-group).
+__global__ __launch_bounds__(256, 2) void k_wgrad_grouped_quad(const WgradItem* __restrict__ items, int ng, PtrTab bases, PtrTab caller_dy,
+                                                            PtrTab caller_a, const float* __restrict__ params, float* grads) {
+  constexpr int BC = 128, BN = 128;
+  typedef WgradTile<BC, BN, 64> TT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_q[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_q);
+  bf16_t* sD = sA + TT::LDS_A;
+  const WgradItem it = items[blockIdx.x];
+  floatx4 acc[BC / 32][BN / 32];
+#pragma unroll
+  for (int i = 0; i < BC / 32; ++i)
+#pragma unroll
+    for (int j = 0; j < BN / 32; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < ng; ++z) {
+    const char* base = (const char*)pick(bases, z);
+    const bf16_t* a = it.a_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_a, z) : (const bf16_t*)(base + it.a_off);
+    const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_dy, z) : (const bf16_t*)(base + it.dy_off);
+    if (it.stats_off != WGRAD_NO_BN)
+      wgrad_accumulate<BC, BN, true>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc,
+                                     (const float*)(base + it.stats_off), params + it.gamma_off, params + it.beta_off);
+    else
+      wgrad_accumulate<BC, BN, true>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qc = it.c0 + (wave >> 1) * (BC / 2), qn = it.n0 + (wave & 1) * (BN / 2);
+  float* dw = grads + it.dw_off;
+#pragma unroll
+  for (int i = 0; i < BC / 32; ++i)
+#pragma unroll
+    for (int j = 0; j < BN / 32; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int c = qc + i * 16 + (lane >> 4) * 4 + v, n = qn + j * 16 + (lane & 15);
+        if (c < it.g.c_valid) atomicAdd(&dw[((size_t)it.tap * it.g.c_valid + c) * it.g.N + n], acc[i][j][v]);
+      }
+}
+
 template <int BC, int BN>
 hipError_t launch_tile(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
   const int tiles = g.R * g.R * (g.Cin / BC) * (g.N / BN);
@@ -298,12 +383,23 @@ namespace {
 int tile_index(int c) { return c % 64 == 0 ? 2 : (c % 32 == 0 ? 1 : 0); }
 }  // namespace
 
-int wgrad_tile_class(int cin, int cout) { return tile_index(cin) * 3 + tile_index(cout); }
+int wgrad_tile_class(int cin, int cout) {
+  if (cin % 128 == 0 && cout % 128 == 0) return 9;
+  return tile_index(cin) * 3 + tile_index(cout);
+}
 
 void wgrad_tile_dims(int tile_class, int* bc, int* bn) {
   static const int sz[3] = {16, 32, 64};
+  if (tile_class == 9) { *bc = 128; *bn = 128; return; }
   *bc = sz[tile_class / 3];
   *bn = sz[tile_class % 3];
+}
+
+// The 128 x 128 class takes its LDS (two operand tiles and the BatchNorm coefficients) as dynamic shared memory:
+// state the size once per device before the first launch (not a stream operation, so it stays out of captured graphs).
+hipError_t wgrad_prepare() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_grouped_quad), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             WgradTile<128, 128, 64>::QUAD_BYTES);
 }
 
 hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
@@ -324,6 +420,10 @@ hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_d
     case 6: HPF_WG(64, 16); break;
     case 7: HPF_WG(64, 32); break;
     case 8: HPF_WG(64, 64); break;
+    case 9:
+      k_wgrad_grouped_quad<<<grid, 256, WgradTile<128, 128, 64>::QUAD_BYTES, stream>>>(items_dev, ng, region_base, caller_dy, caller_a, params,
+                                                                                 grads);
+      break;
     default: return hipErrorInvalidValue;
   }
 #undef HPF_WG
