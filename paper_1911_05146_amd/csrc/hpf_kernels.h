@@ -79,6 +79,10 @@ struct ConvPro {
   const float* beta = nullptr;
 };
 int conv_mfma_tile_rows(int g, const ConvGeom& geom);   // pixel rows per tile the launcher will use
+hipError_t conv_prepare();                               // once per device before the first convolution launch
+// How often the bf16 convolution kernels stage each element of the source tensor (filter taps x channel tiles);
+// 0 for shapes that run on the narrow tiles.
+int conv_operand_reuse(int cin, int cout, int R);
 
 // g = number of group members (grid z); tables hold g valid pointers.  `add` tables may be all-null.
 hipError_t launch_conv_mfma(int mode, int g, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add,

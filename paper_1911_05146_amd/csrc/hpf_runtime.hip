@@ -54,6 +54,7 @@ struct BlockPlan {
   bool proj = false;
   BnPlan bn[3]; ConvPlan cv[3]; ConvPlan pj;
   Loc x_in, a[3], c[2], y;
+  bool mat[3] = {false, false, false};   // bf16 mode: a[j] = relu(bn_j(.)) is written to memory (else applied while staging)
   Loc gy;      // gradient w.r.t. the block output (kept until the deferred weight-gradient pass)
   Loc dc[2];   // gradient w.r.t. c[j], the output of conv j (j < nconv-1)
 };
@@ -233,12 +234,17 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
     p.x_in = cur;
-    // bf16 mode never materialises a = relu(bn(x)): the convolutions apply it while staging x
+    // bf16 mode: the convolutions apply a = relu(bn(x)) while staging x, so a is not written to memory -- except
+    // where the staged operand is re-read so often (filter taps x channel tiles) that one pass writing a is cheaper
     const bool keep_a = (P.dt != DT_BF16);
-    stats(p.bn[0], M_in); if (keep_a) p.a[0] = tensor(M_in * p.d.c_in);
+    if (P.dt == DT_BF16) {
+      for (int j = 0; j < p.nconv; ++j) p.mat[j] = conv_operand_reuse(p.cv[j].cin, p.cv[j].cout, p.cv[j].R) >= 4;
+      if (p.proj && conv_operand_reuse(p.pj.cin, p.pj.cout, p.pj.R) >= 4) p.mat[0] = true;
+    }
+    stats(p.bn[0], M_in); if (keep_a || p.mat[0]) p.a[0] = tensor(M_in * p.d.c_in);
     for (int j = 1; j < p.nconv; ++j) {
       p.c[j - 1] = tensor(M_out * p.cv[j - 1].cout);
-      stats(p.bn[j], M_out); if (keep_a) p.a[j] = tensor(M_out * p.cv[j].cin);
+      stats(p.bn[j], M_out); if (keep_a || p.mat[j]) p.a[j] = tensor(M_out * p.cv[j].cin);
     }
     const bool last = (i == d.n_blocks - 1);
     if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
@@ -343,9 +349,9 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       bool in_run = false;
       for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
       for (int j = 0; j < p.nconv; ++j)
-        wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, j == 0 ? p.x_in : p.c[j - 1],
-                           j == p.nconv - 1 ? p.gy : p.dc[j], &p.bn[j], in_run});
-      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.gy, &p.bn[0], false});
+        wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
+                           j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
+      if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.mat[0] ? p.a[0] : p.x_in, p.gy, p.mat[0] ? nullptr : &p.bn[0], false});
     }
     // output tiles per class: the pixel rows are split so that every class launches roughly 1500 work-groups
     // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
@@ -692,7 +698,8 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
-    const bool pro = (P.dt == DT_BF16);   // bf16: BN + ReLU applied inside the consuming convolutions
+    // bf16: BN + ReLU applied inside the consuming convolutions unless the plan writes the activation out
+    bool pro = (P.dt == DT_BF16) && !p.mat[0];
     c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows, !pro);
     if (p.proj) c.conv_fwd(p.pj, pro ? x : c.tab(p.a[0]), y, Ctx::none(), false, pro ? &p.bn[0] : nullptr);
     const PtrTab shortcut = p.proj ? y : x;
@@ -704,6 +711,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
       const bool feeds_bn = !last || (bi + 1 < P.bp.size() && !next_resident) || (bi + 1 == P.bp.size() && P.d.has_head);
       part_rows = c.conv_fwd(p.cv[j], src, out, last ? shortcut : Ctx::none(), feeds_bn, pro ? &p.bn[j] : nullptr);
       if (!last) {
+        pro = (P.dt == DT_BF16) && !p.mat[j + 1];
         c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows, !pro);
         src = pro ? out : c.tab(p.a[j + 1]);
       }
@@ -943,6 +951,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   for (int k = 0; k < WGRAD_CLASSES; ++k)
     if (!P.items_nr[k].empty())
       ok(hipMemcpy(p->arena + P.items_nr_off[k], P.items_nr[k].data(), P.items_nr[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
+  ok(conv_prepare());
   if (!P.items[WGRAD_CLASSES - 1].empty()) ok(wgrad_prepare());
   if (!P.runs.empty()) {
     ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
@@ -1252,6 +1261,7 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
     if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
   }
   const bf16_t* wp = (const bf16_t*)base + (mode == CONV_FWD ? pd.wf_off : pd.wd_off);
+  if (conv_prepare() != hipSuccess) return fail(HPF_EDEVICE, "kernel set-up failed");
   if (launch_conv_mfma(mode, 1, one_ptr(src), wp, one_ptr(out), one_ptr(add), g, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
 }
