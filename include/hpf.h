@@ -44,7 +44,7 @@
 extern "C" {
 #endif
 
-#define HPF_ABI_VERSION 1u
+#define HPF_ABI_VERSION 2u
 
 typedef struct hpf_partition hpf_partition; /* opaque, owned by the library */
 
@@ -86,6 +86,18 @@ typedef struct {
   hpf_dtype compute_dtype;        /* dtype of interior boundary tensors, stash and conv operands */
   float bn_eps;
   int32_t bn_mode;                /* 0: statistics of the micro-batch; 1: frozen mean 0, variance 1 */
+  /* Cuts at layer granularity (paper Section "Special Handling for Non-consecutive Models": a partition is a
+   * range of layers, and a skip connection whose ends fall into different partitions is exchanged between those
+   * two directly).  The partition holds convolutions [first_block_from_conv, n) of its first block and
+   * [0, last_block_to_conv) of its last block; 0 means the whole block.  A BatchNorm+ReLU goes with the
+   * convolution it feeds, the projection shortcut with convolution 0, the residual add with the last convolution.
+   * first_block_from_conv = j > 0: act_in is the output of convolution j-1 (block-output size, c_mid channels;
+   * in_h, in_w, in_c describe it), needs no stem; if the block also ends here, its shortcut value arrives as
+   * skip_in.  last_block_to_conv = j > 0 (j < n): act_out is the output of convolution j-1, needs no head; if
+   * the block also starts here, its shortcut value (the block input, or its projection) leaves as skip_out.
+   * Parameters: those of the layers held, in canonical order. */
+  int32_t first_block_from_conv;
+  int32_t last_block_to_conv;
 } hpf_partition_desc;
 
 typedef struct {
@@ -94,6 +106,8 @@ typedef struct {
   size_t stash_bytes;    /* part of arena_bytes: stashed activations of all micro-batches */
   size_t act_in_elems;   /* elements per micro-batch of act_in / err_out */
   size_t act_out_elems;  /* elements per micro-batch of act_out / err_in (0 if has_head) */
+  size_t skip_in_elems;  /* elements per micro-batch of skip_in / skip_err_out (0: none) */
+  size_t skip_out_elems; /* elements per micro-batch of skip_out / skip_err_in (0: none) */
 } hpf_sizes;
 
 /* Validates the description and reports sizes.  No device work. */
@@ -122,6 +136,22 @@ hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_
  * Adds this micro-batch's weight gradients into the fp32 gradient buffer. */
 hpf_status hpf_backward_microbatch(hpf_partition* p, int32_t mb, const void* err_in, void* err_out,
                                    void* hip_stream);
+
+/* The same two calls for partitions cut at layer granularity (paper Section "Special Handling for
+ * Non-consecutive Models"); they also accept partitions without cuts (all skip arguments NULL).
+ *  skip_in      (dev) [microbatch, out_h0, out_w0, c_out0] compute_dtype: shortcut value of the first block,
+ *               sent by the partition that holds the block's start; required iff skip_in_elems > 0.
+ *  skip_out     (dev) shortcut value of the last block, for the partition that holds the block's end;
+ *               required iff skip_out_elems > 0.
+ *  skip_err_in  (dev) gradient w.r.t. skip_out, returned by that partition; required iff skip_out_elems > 0.
+ *  skip_err_out (dev) gradient w.r.t. skip_in, for the partition that sent it; required iff skip_in_elems > 0.
+ * hpf_forward_microbatch / hpf_backward_microbatch and the group calls return HPF_EINVAL for a partition
+ * that needs one of these tensors. */
+hpf_status hpf_forward_microbatch_cut(hpf_partition* p, int32_t mb, const void* act_in, const void* skip_in,
+                                      const int32_t* labels, void* act_out, void* skip_out, float* loss_accum,
+                                      void* hip_stream);
+hpf_status hpf_backward_microbatch_cut(hpf_partition* p, int32_t mb, const void* err_in, const void* skip_err_in,
+                                       void* err_out, void* skip_err_out, void* hip_stream);
 
 /* Several consecutive micro-batches [mb_first, mb_first + count) in one call: the same work as `count`
  * single calls, but every layer is launched once for the whole group (the micro-batch is a grid

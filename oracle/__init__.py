@@ -43,6 +43,8 @@ def lib():
         L.oracle_n_params.argtypes = [C.c_void_p]
         L.oracle_forward_microbatch.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_backward_microbatch.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.oracle_forward_microbatch_cut.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 6
+        L.oracle_backward_microbatch_cut.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
         L.oracle_grad_accum_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.oracle_grad_accum_zero.argtypes = [C.c_void_p]
         L.oracle_sgd_step.argtypes = [C.c_void_p, C.c_double, C.c_double]
@@ -195,7 +197,8 @@ class OraclePartition:
                           dtype=np.int32).reshape(-1, 5)
         desc = np.array([spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
                          len(spec.blocks), int(spec.has_head), spec.num_classes, spec.microbatch,
-                         spec.num_microbatches, spec.divisor, spec.bn_mode, STORAGE[storage]], dtype=np.int32)
+                         spec.num_microbatches, spec.divisor, spec.bn_mode, STORAGE[storage],
+                         getattr(spec, "first_from", 0), getattr(spec, "last_to", 0)], dtype=np.int32)
         params = _c(params, self.dtype)
         self._h = lib().oracle_partition_create(_p(desc), float(spec.bn_eps), _p(blocks), _p(params),
                                                 int(self.dtype == np.float64))
@@ -207,6 +210,8 @@ class OraclePartition:
         oh, ow, oc = spec.out_shape()
         self.out_shape = (spec.microbatch, oh, ow, oc)
         self.in_shape = (spec.microbatch, spec.in_h, spec.in_w, spec.in_c)
+        self.skip_in_shape = (spec.microbatch,) + tuple(spec.skip_in_shape()) if getattr(spec, "has_skip_in", False) else None
+        self.skip_out_shape = (spec.microbatch,) + tuple(spec.skip_out_shape()) if getattr(spec, "has_skip_out", False) else None
         self.loss = np.zeros(1, np.float64)
 
     def close(self):
@@ -221,22 +226,30 @@ class OraclePartition:
         if rc != 0:
             raise RuntimeError(f"oracle {what}: status {rc}")
 
-    def forward(self, mb, act_in, labels=None):
+    def forward(self, mb, act_in, labels=None, skip_in=None):
+        """Returns act_out, or (act_out, skip_out) when the last block is cut before its end."""
         act_in = _c(act_in, self.dtype)
         assert act_in.shape == self.in_shape, (act_in.shape, self.in_shape)
         out = None if self.spec.has_head else np.empty(self.out_shape, self.dtype)
         lab = _c(labels, np.int32) if labels is not None else None
-        self._check(lib().oracle_forward_microbatch(self._h, mb, _p(act_in), _p(lab), _p(out), _p(self.loss)),
-                    "forward")
-        return out
+        sk = _c(skip_in, self.dtype) if skip_in is not None else None
+        assert (sk is None) == (self.skip_in_shape is None) and (sk is None or sk.shape == self.skip_in_shape)
+        sko = np.empty(self.skip_out_shape, self.dtype) if self.skip_out_shape else None
+        self._check(lib().oracle_forward_microbatch_cut(self._h, mb, _p(act_in), _p(sk), _p(lab), _p(out), _p(sko),
+                                                        _p(self.loss)), "forward")
+        return (out, sko) if sko is not None else out
 
-    def backward(self, mb, err_in=None, want_err_out=True):
+    def backward(self, mb, err_in=None, want_err_out=True, skip_err_in=None):
+        """Returns err_out, or (err_out, skip_err_out) when the first block is cut after its start."""
         e = _c(err_in, self.dtype) if err_in is not None else None
         if e is not None:
             assert e.shape == self.out_shape
+        se = _c(skip_err_in, self.dtype) if skip_err_in is not None else None
+        assert (se is None) == (self.skip_out_shape is None) and (se is None or se.shape == self.skip_out_shape)
         out = np.empty(self.in_shape, self.dtype) if want_err_out else None
-        self._check(lib().oracle_backward_microbatch(self._h, mb, _p(e), _p(out)), "backward")
-        return out
+        seo = np.empty(self.skip_in_shape, self.dtype) if self.skip_in_shape else None
+        self._check(lib().oracle_backward_microbatch_cut(self._h, mb, _p(e), _p(se), _p(out), _p(seo)), "backward")
+        return (out, seo) if seo is not None else out
 
     def grad(self):
         g = np.empty(self.n_params, self.dtype)
@@ -266,14 +279,27 @@ def run_step(spec, inputs, dtype=np.float32, sgd=None, storage="none"):
     per-micro-batch act_out / err_out, the loss, the accumulated gradient and, when `sgd` =
     (lr, momentum) is given, the parameters after the step."""
     part = OraclePartition(spec, inputs.params, dtype, storage)
-    outs, errs = [], []
+    outs, errs, skip_outs, skip_errs = [], [], [], []
+    skip_in = getattr(inputs, "skip_in", None)
+    skip_err_in = getattr(inputs, "skip_err_in", None)
     for i in range(spec.num_microbatches):
-        outs.append(part.forward(i, inputs.act_in[i], inputs.labels[i] if inputs.labels else None))
+        o = part.forward(i, inputs.act_in[i], inputs.labels[i] if inputs.labels else None,
+                         skip_in[i] if skip_in else None)
+        if isinstance(o, tuple):
+            skip_outs.append(o[1]); o = o[0]
+        outs.append(o)
     loss = float(part.loss[0])
     for i in range(spec.num_microbatches):
-        errs.append(part.backward(i, inputs.err_in[i] if inputs.err_in else None,
-                                  want_err_out=not spec.has_stem))
+        e = part.backward(i, inputs.err_in[i] if inputs.err_in else None, want_err_out=not spec.has_stem,
+                          skip_err_in=skip_err_in[i] if skip_err_in else None)
+        if isinstance(e, tuple):
+            skip_errs.append(e[1]); e = e[0]
+        errs.append(e)
     res = {"act_out": outs, "err_out": errs, "loss": loss, "grad": part.grad()}
+    if skip_outs:
+        res["skip_out"] = skip_outs
+    if skip_errs:
+        res["skip_err_out"] = skip_errs
     if sgd is not None:
         part.sgd_step(*sgd)
         res["params"] = part.params()

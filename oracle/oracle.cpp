@@ -289,6 +289,12 @@ struct Desc {
   int in_h, in_w, in_c, has_stem, stem_c_out, n_blocks, has_head, num_classes;
   int microbatch, num_microbatches, loss_divisor, bn_mode;
   int storage = 0;   // 0: nothing rounded; 1: stored tensors and conv weight operands are bfloat16
+  // Cuts at layer granularity (Section "Special Handling for Non-consecutive Models"): the partition holds
+  // convolutions [first_from, nconv) of its first block and [0, last_to) of its last block (0 = the whole block;
+  // a BatchNorm+ReLU goes with the convolution it feeds, the projection with convolution 0, the residual add
+  // with the last convolution).  A block cut this way sends its shortcut value (x, or the projection of
+  // relu(bn1(x))) straight from the partition that holds its start to the one that holds its end.
+  int first_from = 0, last_to = 0;
   double bn_eps;
   std::vector<BlockDesc> blocks;
 };
@@ -298,6 +304,7 @@ struct BnP { size_t g, b; int c; };
 struct BlockP {
   BlockDesc d; int h_in, w_in, h_out, w_out; bool proj;
   BnP bn[3]; ConvP cv[3]; ConvP pj; int nconv;
+  int j0, j1;   // convolutions [j0, j1) of the block belong to this partition
 };
 
 template <class T>
@@ -309,6 +316,7 @@ struct BlockStash { BnSave<T> bn[3]; std::vector<T> a[3]; };
 template <class T>
 struct MbStash {
   std::vector<T> stem_in;
+  std::vector<T> skip_in;   // shortcut value received for a first block that starts after its convolution 0
   std::vector<BlockStash<T>> blk;
   BnSave<T> head_bn; std::vector<T> head_a, g, dlogits;
   bool fwd_done = false, bwd_done = false;
@@ -332,24 +340,31 @@ struct Partition {
     int h = d.in_h, w = d.in_w, c = d.in_c;
     if (d.has_stem) { stem_w = off; off += (size_t)9 * d.in_c * d.stem_c_out; c = d.stem_c_out; }
     c0 = c;
-    for (auto& b : d.blocks) {
-      BlockP p{}; p.d = b; p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride;
+    for (size_t bi = 0; bi < d.blocks.size(); ++bi) {
+      const BlockDesc& b = d.blocks[bi];
+      BlockP p{}; p.d = b;
+      p.nconv = b.kind == 0 ? 2 : 3;
+      p.j0 = (bi == 0) ? d.first_from : 0;
+      p.j1 = (bi + 1 == d.blocks.size() && d.last_to > 0) ? d.last_to : p.nconv;
+      if (p.j0 == 0) { p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride; }
+      else { p.h_in = h * b.stride; p.w_in = w * b.stride; p.h_out = h; p.w_out = w; }   // the input is already at the block's output size
       p.proj = (b.stride != 1 || b.c_in != b.c_out);
       auto bn = [&](int ch) { BnP r{off, off + (size_t)ch, ch}; off += 2 * (size_t)ch; return r; };
       auto cv = [&](int ci, int co, int R, int s) { ConvP r{off, ci, co, R, s}; off += (size_t)R * R * ci * co; return r; };
-      if (b.kind == 0) {
-        p.nconv = 2;
-        p.bn[0] = bn(b.c_in);  p.cv[0] = cv(b.c_in, b.c_mid, 3, b.stride);
-        p.bn[1] = bn(b.c_mid); p.cv[1] = cv(b.c_mid, b.c_out, 3, 1);
-      } else {
-        p.nconv = 3;
-        p.bn[0] = bn(b.c_in);  p.cv[0] = cv(b.c_in, b.c_mid, 1, b.stride);
-        p.bn[1] = bn(b.c_mid); p.cv[1] = cv(b.c_mid, b.c_mid, 3, 1);
-        p.bn[2] = bn(b.c_mid); p.cv[2] = cv(b.c_mid, b.c_out, 1, 1);
+      const int cin[3] = {b.c_in, b.c_mid, b.c_mid};
+      const int cout[3] = {b.c_mid, b.kind == 0 ? b.c_out : b.c_mid, b.c_out};
+      const int R[3] = {b.kind == 0 ? 3 : 1, 3, 1};
+      for (int j = 0; j < p.nconv; ++j) {
+        const ConvP shape{0, cin[j], cout[j], R[j], j == 0 ? b.stride : 1};
+        p.cv[j] = shape; p.bn[j] = BnP{0, 0, cin[j]};
+        if (j >= p.j0 && j < p.j1) {     // parameters only of the layers held here, in canonical order
+          p.bn[j] = bn(cin[j]);
+          p.cv[j] = cv(cin[j], cout[j], R[j], shape.st);
+        }
       }
-      if (p.proj) p.pj = cv(b.c_in, b.c_out, 1, b.stride);
+      if (p.proj) { p.pj = ConvP{0, b.c_in, b.c_out, 1, b.stride}; if (p.j0 == 0) p.pj = cv(b.c_in, b.c_out, 1, b.stride); }
       bp.push_back(p);
-      h = p.h_out; w = p.w_out; c = b.c_out;
+      h = p.h_out; w = p.w_out; c = p.j1 == p.nconv ? b.c_out : cout[p.j1 - 1];
     }
     out_h = h; out_w = w; out_c = c;
     if (d.has_head) {
@@ -368,7 +383,8 @@ struct Partition {
     st.resize(d.num_microbatches);
   }
 
-  int forward(int mb, const T* act_in, const int32_t* labels, T* act_out, double* loss_accum) {
+  // skip_in / skip_out: shortcut value of a first block that starts, or a last block that ends, inside the block
+  int forward(int mb, const T* act_in, const T* skip_in, const int32_t* labels, T* act_out, T* skip_out, double* loss_accum) {
     if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
     MbStash<T>& S = st[mb];
     if (S.fwd_done) return E_STATE;
@@ -394,23 +410,37 @@ struct Partition {
         bn_relu_fwd(in.data(), P + p.bn[j].g, P + p.bn[j].b, B.a[j].data(), B.bn[j].mean.data(),
                     B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode, bf);
       };
-      bnrelu(0, x);                                        // a = relu(bn1(x))
       std::vector<T> sc;                                   // shortcut: x, or the 1x1 projection of a
-      if (p.proj) {
-        sc.resize(M_out * p.d.c_out);
-        conv_fwd(B.a[0].data(), P + p.pj.w, sc.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st,
-                 (const T*)nullptr, bf);
-      } else {
-        sc = x;
-      }
       std::vector<T> r;
-      for (int j = 0; j < p.nconv; ++j) {
+      if (p.j0 == 0) {
+        bnrelu(0, x);                                      // a = relu(bn1(x))
+        if (p.proj) {
+          sc.resize(M_out * p.d.c_out);
+          conv_fwd(B.a[0].data(), P + p.pj.w, sc.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st,
+                   (const T*)nullptr, bf);
+        } else {
+          sc = x;
+        }
+      } else {                                             // x is the output of convolution j0-1
+        r = x;
+        if (p.j1 == p.nconv) {
+          if (!skip_in) return E_INVAL;
+          S.skip_in.assign(skip_in, skip_in + M_out * p.d.c_out);
+          for (auto& v : S.skip_in) v = rnd(v, bf);
+          sc = S.skip_in;
+        }
+      }
+      for (int j = p.j0; j < p.j1; ++j) {
         const bool last = (j == p.nconv - 1);
         if (j > 0) bnrelu(j, r);
         std::vector<T> r2(M_out * p.cv[j].cout);
         conv_fwd(B.a[j].data(), P + p.cv[j].w, r2.data(), b, j == 0 ? p.h_in : p.h_out, j == 0 ? p.w_in : p.w_out,
                  p.cv[j].cin, p.cv[j].cout, p.cv[j].R, p.cv[j].st, last ? sc.data() : (const T*)nullptr, bf);
         r.swap(r2);                                        // after the last conv: y = shortcut + branch
+      }
+      if (p.j1 < p.nconv && p.j0 == 0) {                   // the block ends elsewhere: its shortcut value leaves too
+        if (!skip_out) return E_INVAL;
+        std::memcpy(skip_out, sc.data(), sc.size() * sizeof(T));
       }
       x.swap(r);
     }
@@ -431,7 +461,8 @@ struct Partition {
     return OK;
   }
 
-  int backward(int mb, const T* err_in, T* err_out) {
+  // skip_err_in: gradient w.r.t. skip_out; skip_err_out: gradient w.r.t. skip_in
+  int backward(int mb, const T* err_in, const T* skip_err_in, T* err_out, T* skip_err_out) {
     if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
     MbStash<T>& S = st[mb];
     if (!S.fwd_done || S.bwd_done) return E_STATE;
@@ -448,14 +479,23 @@ struct Partition {
       bn_relu_bwd(S.head_bn.x.data(), da.data(), P + head_bn.g, P + head_bn.b, S.head_bn.mean.data(),
                   S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode, none, bf);
     } else {
+      if (!err_in) return E_INVAL;
       dy.assign(err_in, err_in + (size_t)b * out_h * out_w * out_c);
     }
     for (size_t ii = bp.size(); ii-- > 0;) {
       const BlockP& p = bp[ii]; BlockStash<T>& B = S.blk[ii];
       const size_t M_in = (size_t)b * p.h_in * p.w_in, M_out = (size_t)b * p.h_out * p.w_out;
-      // residual branch, last conv to first
+      // residual branch, last conv held here to first; dsc: gradient w.r.t. the shortcut value
       std::vector<T> dr = dy;
-      for (int j = p.nconv - 1; j >= 1; --j) {
+      std::vector<T> dsc;
+      if (p.j1 == p.nconv) {
+        dsc = dy;                                          // y = shortcut + branch
+      } else if (p.j0 == 0) {
+        if (!skip_err_in) return E_INVAL;
+        dsc.assign(skip_err_in, skip_err_in + M_out * p.d.c_out);
+        for (auto& v : dsc) v = rnd(v, bf);
+      }
+      for (int j = p.j1 - 1; j >= std::max(p.j0, 1); --j) {
         conv_wgrad(B.a[j].data(), dr.data(), G + p.cv[j].w, b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1);
         std::vector<T> da(M_out * p.cv[j].cin);
         conv_dgrad(dr.data(), P + p.cv[j].w, da.data(), b, p.h_out, p.w_out, p.cv[j].cin, p.cv[j].cout, p.cv[j].R, 1, none, bf);
@@ -464,17 +504,25 @@ struct Partition {
                     B.bn[j].invstd.data(), dx.data(), G + p.bn[j].g, G + p.bn[j].b, M_out, p.bn[j].c, d.bn_mode, none, bf);
         dr.swap(dx);
       }
+      if (p.j0 > 0) {                                      // dr is the gradient w.r.t. the partition's input
+        if (p.j1 == p.nconv) {
+          if (!skip_err_out) return E_INVAL;
+          std::memcpy(skip_err_out, dsc.data(), dsc.size() * sizeof(T));
+        }
+        dy.swap(dr);
+        continue;
+      }
       conv_wgrad(B.a[0].data(), dr.data(), G + p.cv[0].w, b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st);
       std::vector<T> da(M_in * p.d.c_in);
       conv_dgrad(dr.data(), P + p.cv[0].w, da.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, p.cv[0].R, p.cv[0].st, none, bf);
       if (p.proj) {   // a = relu(bn1(x)) feeds both the branch and the projection: their gradients add
-        conv_wgrad(B.a[0].data(), dy.data(), G + p.pj.w, b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
-        conv_dgrad(dy.data(), P + p.pj.w, da.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st, da.data(), bf);
+        conv_wgrad(B.a[0].data(), dsc.data(), G + p.pj.w, b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+        conv_dgrad(dsc.data(), P + p.pj.w, da.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st, da.data(), bf);
       }
-      std::vector<T> dx(da.size());  // identity shortcut: x also feeds the output directly, so dy is added
+      std::vector<T> dx(da.size());  // identity shortcut: x also feeds the output directly, so dsc is added
       bn_relu_bwd(B.bn[0].x.data(), da.data(), P + p.bn[0].g, P + p.bn[0].b, B.bn[0].mean.data(),
                   B.bn[0].invstd.data(), dx.data(), G + p.bn[0].g, G + p.bn[0].b, M_in, p.bn[0].c, d.bn_mode,
-                  p.proj ? none : dy.data(), bf);
+                  p.proj ? none : dsc.data(), bf);
       dy.swap(dx);
     }
     if (d.has_stem) {
@@ -525,13 +573,26 @@ bool valid(const Desc& d) {
   if (!d.has_stem && !d.has_head && d.n_blocks == 0) return false;
   int h = d.in_h, w = d.in_w, c = d.has_stem ? d.stem_c_out : d.in_c;
   if (d.has_stem && d.stem_c_out <= 0) return false;
-  for (auto& b : d.blocks) {
+  const int nb = (int)d.blocks.size();
+  if (d.first_from < 0 || d.last_to < 0) return false;
+  if (d.first_from > 0 && (nb == 0 || d.has_stem)) return false;
+  if (d.last_to > 0 && (nb == 0 || d.has_head)) return false;
+  for (int i = 0; i < nb; ++i) {
+    const BlockDesc& b = d.blocks[i];
     if (b.kind != 0 && b.kind != 1) return false;
-    if (b.c_in != c || b.c_mid <= 0 || b.c_out <= 0) return false;
+    const int nconv = b.kind == 0 ? 2 : 3;
+    const int j0 = i == 0 ? d.first_from : 0, j1 = (i == nb - 1 && d.last_to > 0) ? d.last_to : nconv;
+    if (j0 >= j1 || j1 > nconv || (i == nb - 1 && d.last_to >= nconv)) return false;
+    if (b.c_mid <= 0 || b.c_out <= 0) return false;
+    if (b.c_in != c && j0 == 0) return false;
+    if (j0 > 0 && c != b.c_mid) return false;      // the input is the output of convolution j0-1
     if (b.kind == 0 && b.c_mid != b.c_out) return false;
     if (b.stride != 1 && b.stride != 2) return false;
-    if (h % b.stride || w % b.stride) return false;
-    h /= b.stride; w /= b.stride; c = b.c_out;
+    if (j0 == 0) {
+      if (h % b.stride || w % b.stride) return false;
+      h /= b.stride; w /= b.stride;
+    }
+    c = j1 == nconv ? b.c_out : b.c_mid;
   }
   if (d.has_head && d.num_classes <= 0) return false;
   if (d.storage != 0 && d.storage != 1) return false;
@@ -543,14 +604,14 @@ bool valid(const Desc& d) {
 extern "C" {
 
 // desc_i: in_h,in_w,in_c,has_stem,stem_c_out,n_blocks,has_head,num_classes,microbatch,
-//         num_microbatches,loss_divisor,bn_mode,storage ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
+//         num_microbatches,loss_divisor,bn_mode,storage,first_from,last_to ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
 void* oracle_partition_create(const int32_t* desc_i, double bn_eps, const int32_t* blocks,
                               const void* host_params, int is_f64) {
   Desc d;
   d.in_h = desc_i[0]; d.in_w = desc_i[1]; d.in_c = desc_i[2]; d.has_stem = desc_i[3];
   d.stem_c_out = desc_i[4]; d.n_blocks = desc_i[5]; d.has_head = desc_i[6]; d.num_classes = desc_i[7];
   d.microbatch = desc_i[8]; d.num_microbatches = desc_i[9]; d.loss_divisor = desc_i[10]; d.bn_mode = desc_i[11];
-  d.storage = desc_i[12];
+  d.storage = desc_i[12]; d.first_from = desc_i[13]; d.last_to = desc_i[14];
   d.bn_eps = bn_eps;
   for (int i = 0; i < d.n_blocks; ++i)
     d.blocks.push_back(BlockDesc{blocks[5 * i], blocks[5 * i + 1], blocks[5 * i + 2], blocks[5 * i + 3], blocks[5 * i + 4]});
@@ -569,17 +630,27 @@ size_t oracle_n_params(void* hp) {
   return h->f64 ? h->pd->params.size() : h->pf->params.size();
 }
 
+int oracle_forward_microbatch_cut(void* hp, int mb, const void* act_in, const void* skip_in, const int32_t* labels,
+                                  void* act_out, void* skip_out, double* loss_accum) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->forward(mb, (const double*)act_in, (const double*)skip_in, labels, (double*)act_out, (double*)skip_out, loss_accum)
+                : h->pf->forward(mb, (const float*)act_in, (const float*)skip_in, labels, (float*)act_out, (float*)skip_out, loss_accum);
+}
+
 int oracle_forward_microbatch(void* hp, int mb, const void* act_in, const int32_t* labels, void* act_out,
                               double* loss_accum) {
+  return oracle_forward_microbatch_cut(hp, mb, act_in, nullptr, labels, act_out, nullptr, loss_accum);
+}
+
+int oracle_backward_microbatch_cut(void* hp, int mb, const void* err_in, const void* skip_err_in, void* err_out,
+                                   void* skip_err_out) {
   Handle* h = (Handle*)hp;
-  return h->f64 ? h->pd->forward(mb, (const double*)act_in, labels, (double*)act_out, loss_accum)
-                : h->pf->forward(mb, (const float*)act_in, labels, (float*)act_out, loss_accum);
+  return h->f64 ? h->pd->backward(mb, (const double*)err_in, (const double*)skip_err_in, (double*)err_out, (double*)skip_err_out)
+                : h->pf->backward(mb, (const float*)err_in, (const float*)skip_err_in, (float*)err_out, (float*)skip_err_out);
 }
 
 int oracle_backward_microbatch(void* hp, int mb, const void* err_in, void* err_out) {
-  Handle* h = (Handle*)hp;
-  return h->f64 ? h->pd->backward(mb, (const double*)err_in, (double*)err_out)
-                : h->pf->backward(mb, (const float*)err_in, (float*)err_out);
+  return oracle_backward_microbatch_cut(hp, mb, err_in, nullptr, err_out, nullptr);
 }
 
 int oracle_grad_accum_read(void* hp, void* dst, size_t n) {

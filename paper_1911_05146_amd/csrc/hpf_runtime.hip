@@ -38,7 +38,8 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 int round_up32(int v) { return (v + 31) / 32 * 32; }
 
 // Where a tensor lives: inside this micro-batch's arena region, or in a caller buffer.
-enum LocKind { IN_MB = 0, CALLER_ACT_IN, CALLER_ACT_OUT, CALLER_ERR_IN, CALLER_ERR_OUT, NOWHERE };
+enum LocKind { IN_MB = 0, CALLER_ACT_IN, CALLER_ACT_OUT, CALLER_ERR_IN, CALLER_ERR_OUT,
+               CALLER_SKIP_IN, CALLER_SKIP_OUT, CALLER_SKIP_ERR_IN, CALLER_SKIP_ERR_OUT, NOWHERE };
 struct Loc { LocKind kind = NOWHERE; size_t off = 0; };
 
 struct ConvPlan {
@@ -52,6 +53,8 @@ struct BlockPlan {
   hpf_block_desc d{};
   int h_in = 0, w_in = 0, h_out = 0, w_out = 0, nconv = 0;
   bool proj = false;
+  int j0 = 0, j1 = 0;   // the partition holds convolutions [j0, j1) of the block (cuts at layer granularity)
+  bool whole() const { return j0 == 0 && j1 == nconv; }
   BnPlan bn[3]; ConvPlan cv[3]; ConvPlan pj;
   Loc x_in, a[3], c[2], y;
   bool mat[3] = {false, false, false};   // bf16 mode: a[j] = relu(bn_j(.)) is written to memory (else applied while staging)
@@ -87,6 +90,7 @@ struct Plan {
   double wg_bytes[WGRAD_CLASSES] = {}, wg_flops[WGRAD_CLASSES] = {};   // per micro-batch
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
+  size_t skip_in_elems = 0, skip_out_elems = 0;   // shortcut value of a first / last block that is cut (0: none)
   std::vector<PackDesc> table;
   // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
   struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
@@ -123,17 +127,27 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (c % cmul) return fail(HPF_EUNSUPPORTED, "channel count %d is not a multiple of %d", c, cmul);
   const int cmax = 1024;   // bf16 mode keeps a per-channel table of the source tensor in LDS
   if (P.dt == DT_BF16 && c > cmax) return fail(HPF_EUNSUPPORTED, "more than %d channels", cmax);
+  if (d.first_block_from_conv < 0 || d.last_block_to_conv < 0) return fail(HPF_EINVAL, "negative layer cut");
+  if (d.first_block_from_conv > 0 && (d.n_blocks == 0 || d.has_stem)) return fail(HPF_EINVAL, "first_block_from_conv needs a first block and no stem");
+  if (d.last_block_to_conv > 0 && (d.n_blocks == 0 || d.has_head)) return fail(HPF_EINVAL, "last_block_to_conv needs a last block and no head");
   for (int i = 0; i < d.n_blocks; ++i) {
     const hpf_block_desc& b = P.blocks[i];
     if (b.kind != 0 && b.kind != 1) return fail(HPF_EINVAL, "block %d: kind %d", i, b.kind);
-    if (b.c_in != c) return fail(HPF_EINVAL, "block %d: c_in %d does not continue the chain (%d)", i, b.c_in, c);
+    const int nconv = b.kind == 0 ? 2 : 3;
+    const int j0 = i == 0 ? d.first_block_from_conv : 0;
+    const int j1 = (i == d.n_blocks - 1 && d.last_block_to_conv > 0) ? d.last_block_to_conv : nconv;
+    if (j0 >= j1 || j1 > nconv || (i == d.n_blocks - 1 && d.last_block_to_conv >= nconv))
+      return fail(HPF_EINVAL, "block %d: convolutions [%d, %d) of %d", i, j0, j1, nconv);
     if (b.c_mid <= 0 || b.c_out <= 0) return fail(HPF_EINVAL, "block %d: channel counts must be positive", i);
+    if (j0 == 0 && b.c_in != c) return fail(HPF_EINVAL, "block %d: c_in %d does not continue the chain (%d)", i, b.c_in, c);
+    if (j0 > 0 && b.c_mid != c) return fail(HPF_EINVAL, "block %d: c_mid %d does not continue the chain (%d)", i, b.c_mid, c);
     if (b.kind == 0 && b.c_mid != b.c_out) return fail(HPF_EINVAL, "block %d: a basic block needs c_mid == c_out", i);
     if (b.stride != 1 && b.stride != 2) return fail(HPF_EINVAL, "block %d: stride %d", i, b.stride);
-    if (h % b.stride || w % b.stride) return fail(HPF_EINVAL, "block %d: %dx%d not divisible by stride", i, h, w);
-    if (b.c_mid % cmul || b.c_out % cmul) return fail(HPF_EUNSUPPORTED, "block %d: channel counts must be multiples of %d", i, cmul);
-    if (P.dt == DT_BF16 && (b.c_mid > cmax || b.c_out > cmax)) return fail(HPF_EUNSUPPORTED, "block %d: more than %d channels", i, cmax);
-    h /= b.stride; w /= b.stride; c = b.c_out;
+    if (j0 == 0 && (h % b.stride || w % b.stride)) return fail(HPF_EINVAL, "block %d: %dx%d not divisible by stride", i, h, w);
+    if (b.c_in % cmul || b.c_mid % cmul || b.c_out % cmul) return fail(HPF_EUNSUPPORTED, "block %d: channel counts must be multiples of %d", i, cmul);
+    if (P.dt == DT_BF16 && (b.c_in > cmax || b.c_mid > cmax || b.c_out > cmax)) return fail(HPF_EUNSUPPORTED, "block %d: more than %d channels", i, cmax);
+    if (j0 == 0) { h /= b.stride; w /= b.stride; }   // else the input already has the block's output size
+    c = j1 == nconv ? b.c_out : b.c_mid;
   }
   P.out_h = h; P.out_w = w; P.out_c = c;
   if ((size_t)d.microbatch * d.in_h * d.in_w >= (1u << 30)) return fail(HPF_EUNSUPPORTED, "micro-batch too large");
@@ -177,20 +191,23 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   for (int i = 0; i < d.n_blocks; ++i) {
     BlockPlan& p = P.bp[i];
     const hpf_block_desc& b = P.blocks[i];
-    p.d = b; p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride;
+    p.d = b;
+    p.nconv = b.kind == 0 ? 2 : 3;
+    p.j0 = i == 0 ? d.first_block_from_conv : 0;
+    p.j1 = (i == d.n_blocks - 1 && d.last_block_to_conv > 0) ? d.last_block_to_conv : p.nconv;
+    if (p.j0 == 0) { p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride; }
+    else { p.h_in = h * b.stride; p.w_in = w * b.stride; p.h_out = h; p.w_out = w; }
     p.proj = (b.stride != 1 || b.c_in != b.c_out);
-    if (b.kind == 0) {
-      p.nconv = 2;
-      p.bn[0] = mk_bn(b.c_in);  p.cv[0] = mk_conv(b.c_in, b.c_mid, 3, b.stride, h, w);
-      p.bn[1] = mk_bn(b.c_mid); p.cv[1] = mk_conv(b.c_mid, b.c_out, 3, 1, p.h_out, p.w_out);
-    } else {
-      p.nconv = 3;
-      p.bn[0] = mk_bn(b.c_in);  p.cv[0] = mk_conv(b.c_in, b.c_mid, 1, b.stride, h, w);
-      p.bn[1] = mk_bn(b.c_mid); p.cv[1] = mk_conv(b.c_mid, b.c_mid, 3, 1, p.h_out, p.w_out);
-      p.bn[2] = mk_bn(b.c_mid); p.cv[2] = mk_conv(b.c_mid, b.c_out, 1, 1, p.h_out, p.w_out);
+    const int cin[3] = {b.c_in, b.c_mid, b.c_mid};
+    const int cout[3] = {b.c_mid, b.kind == 0 ? b.c_out : b.c_mid, b.c_out};
+    const int R[3] = {b.kind == 0 ? 3 : 1, 3, 1};
+    for (int j = p.j0; j < p.j1; ++j) {   // parameters only of the layers held here, in canonical order
+      p.bn[j] = mk_bn(cin[j]);
+      p.cv[j] = j == 0 ? mk_conv(cin[0], cout[0], R[0], b.stride, p.h_in, p.w_in) : mk_conv(cin[j], cout[j], R[j], 1, p.h_out, p.w_out);
     }
-    if (p.proj) p.pj = mk_conv(b.c_in, b.c_out, 1, b.stride, h, w);
-    for (int j = 0; j < p.nconv; ++j) add_pack(p.cv[j], p.cv[j].cin, true);
+    if (p.proj && p.j0 == 0) p.pj = mk_conv(b.c_in, b.c_out, 1, b.stride, p.h_in, p.w_in);
+    else p.proj = p.proj && p.j0 == 0;    // the projection lives with convolution 0
+    for (int j = p.j0; j < p.j1; ++j) add_pack(p.cv[j], p.cv[j].cin, true);
     if (p.proj) add_pack(p.pj, p.pj.cin, true);
     h = p.h_out; w = p.w_out;
   }
@@ -218,7 +235,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   };
 
   P.act_in_elems = b_ * d.in_h * d.in_w * d.in_c;
-  P.act_out_elems = d.has_head ? 0 : b_ * P.out_h * P.out_w * P.out_c;
+  P.act_out_elems = d.has_head ? 0 : b_ * P.out_h * P.out_w * P.out_c;   // out_c: c_mid if the last block is cut
   Loc cur; cur.kind = CALLER_ACT_IN;
   if (d.has_stem) {
     const size_t Mst = b_ * d.in_h * d.in_w;
@@ -233,23 +250,32 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   for (int i = 0; i < d.n_blocks; ++i) {
     BlockPlan& p = P.bp[i];
     const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
-    p.x_in = cur;
+    if (p.j0 == 0) p.x_in = cur; else p.c[p.j0 - 1] = cur;   // a block cut after its start takes convolution j0-1's output
     // bf16 mode: the convolutions apply a = relu(bn(x)) while staging x, so a is not written to memory -- except
     // where the staged operand is re-read so often (filter taps x channel tiles) that one pass writing a is cheaper
     const bool keep_a = (P.dt != DT_BF16);
     if (P.dt == DT_BF16) {
-      for (int j = 0; j < p.nconv; ++j) p.mat[j] = conv_operand_reuse(p.cv[j].cin, p.cv[j].cout, p.cv[j].R) >= 4;
+      for (int j = p.j0; j < p.j1; ++j) p.mat[j] = conv_operand_reuse(p.cv[j].cin, p.cv[j].cout, p.cv[j].R) >= 4;
       if (p.proj && conv_operand_reuse(p.pj.cin, p.pj.cout, p.pj.R) >= 4) p.mat[0] = true;
     }
-    stats(p.bn[0], M_in); if (keep_a || p.mat[0]) p.a[0] = tensor(M_in * p.d.c_in);
-    for (int j = 1; j < p.nconv; ++j) {
-      p.c[j - 1] = tensor(M_out * p.cv[j - 1].cout);
-      stats(p.bn[j], M_out); if (keep_a || p.mat[j]) p.a[j] = tensor(M_out * p.cv[j].cin);
+    for (int j = p.j0; j < p.j1; ++j) {
+      const size_t Mj = j == 0 ? M_in : M_out;
+      stats(p.bn[j], Mj);
+      if (keep_a || p.mat[j]) p.a[j] = tensor(Mj * p.cv[j].cin);
+      if (j + 1 < p.j1) p.c[j] = tensor(M_out * p.cv[j].cout);
     }
     const bool last = (i == d.n_blocks - 1);
-    if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
-    else p.y = tensor(M_out * p.d.c_out);
-    cur = p.y;
+    if (p.j1 == p.nconv) {
+      if (last && !d.has_head) { p.y.kind = CALLER_ACT_OUT; if (M_out * p.d.c_out > max_elems) max_elems = M_out * p.d.c_out; }
+      else p.y = tensor(M_out * p.d.c_out);
+      cur = p.y;
+      if (p.j0 > 0) P.skip_in_elems = M_out * p.d.c_out;
+    } else {   // the block ends in a later partition: convolution j1-1's output and the shortcut value leave
+      p.c[p.j1 - 1].kind = CALLER_ACT_OUT;
+      if (M_out * p.cv[p.j1 - 1].cout > max_elems) max_elems = M_out * p.cv[p.j1 - 1].cout;
+      if (p.j0 == 0) { P.skip_out_elems = M_out * p.d.c_out; if (P.skip_out_elems > max_elems) max_elems = P.skip_out_elems; }
+      cur = p.c[p.j1 - 1];
+    }
   }
   if (d.has_head) {
     P.head_x = cur;
@@ -268,8 +294,16 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const size_t M_out = b_ * p.h_out * p.w_out;
     const bool last = (i == d.n_blocks - 1);
-    if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
-    for (int j = 0; j + 1 < p.nconv; ++j) p.dc[j] = tensor(M_out * p.cv[j].cout);
+    if (p.j1 == p.nconv) {
+      if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
+    } else {
+      p.dc[p.j1 - 1].kind = CALLER_ERR_IN;                 // gradient w.r.t. the output that left
+      if (p.j0 == 0) p.gy = tensor(M_out * p.d.c_out);     // the gradient w.r.t. the shortcut value is copied here
+    }
+    for (int j = p.j0 > 0 ? p.j0 - 1 : 0; j + 1 < p.j1; ++j) {
+      if (j == p.j0 - 1) p.dc[j].kind = CALLER_ERR_OUT;    // gradient w.r.t. the partition's input
+      else p.dc[j] = tensor(M_out * p.cv[j].cout);
+    }
   }
   P.stash_bytes_per_mb = mo;
   P.max_elems = max_elems; P.max_c = max_c;
@@ -287,7 +321,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (P.dt == DT_BF16 && d.bn_mode == 0) {
     auto eligible = [&](int i) {
       const BlockPlan& p = P.bp[i];
-      return p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
+      return p.whole() && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
     };
     int cmax_run = 0;
     for (int i = 0; i < d.n_blocks;) {
@@ -348,7 +382,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       const BlockPlan& p = P.bp[i];
       bool in_run = false;
       for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
-      for (int j = 0; j < p.nconv; ++j)
+      for (int j = p.j0; j < p.j1; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
                            j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
       if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.mat[0] ? p.a[0] : p.x_in, p.gy, p.mat[0] ? nullptr : &p.bn[0], false});
@@ -478,6 +512,8 @@ namespace {
 struct Ctx {
   hpf_partition* h; int mb0; int g; hipStream_t s;
   const void* act_in[MAX_GROUP]; void* act_out[MAX_GROUP]; const void* err_in[MAX_GROUP]; void* err_out[MAX_GROUP];
+  // shortcut value of a cut block: received / sent in forward, its gradient sent back / received in backward
+  const void* skip_in[MAX_GROUP] = {}; void* skip_out[MAX_GROUP] = {}; const void* skip_err_in[MAX_GROUP] = {}; void* skip_err_out[MAX_GROUP] = {};
   hipError_t err = hipSuccess;
   const char* where = "";
   hpf_partition::ProfSeg cur{PROF_NONE, nullptr, nullptr, 0, 0, 0};
@@ -507,6 +543,10 @@ struct Ctx {
         case CALLER_ACT_OUT: t.p[i] = act_out[i]; break;
         case CALLER_ERR_IN: t.p[i] = const_cast<void*>(err_in[i]); break;
         case CALLER_ERR_OUT: t.p[i] = err_out[i]; break;
+        case CALLER_SKIP_IN: t.p[i] = const_cast<void*>(skip_in[i]); break;
+        case CALLER_SKIP_OUT: t.p[i] = skip_out[i]; break;
+        case CALLER_SKIP_ERR_IN: t.p[i] = const_cast<void*>(skip_err_in[i]); break;
+        case CALLER_SKIP_ERR_OUT: t.p[i] = skip_err_out[i]; break;
         default: t.p[i] = nullptr;
       }
     }
@@ -523,6 +563,9 @@ struct Ctx {
   }
 
   bool fused() const { return h->fuse >= 1 && h->P.dt == DT_BF16 && h->P.d.bn_mode == 0; }
+  void copy(const PtrTab& dst, const PtrTab& src, size_t bytes) {
+    for (int i = 0; i < g; ++i) chk(launch_copy_bytes(dst.p[i], src.p[i], bytes, s), "copy");
+  }
 
   // part_rows > 0: the producing convolution already wrote that many statistics partial rows.
   // apply == false: only the statistics (the consuming convolutions normalise while staging)
@@ -697,21 +740,37 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     c.seg_same(PROF_OTHER_FWD);
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
-    const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
+    const bool bf = (P.dt == DT_BF16);
     // bf16: BN + ReLU applied inside the consuming convolutions unless the plan writes the activation out
-    bool pro = (P.dt == DT_BF16) && !p.mat[0];
-    c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows, !pro);
-    if (p.proj) c.conv_fwd(p.pj, pro ? x : c.tab(p.a[0]), y, Ctx::none(), false, pro ? &p.bn[0] : nullptr);
-    const PtrTab shortcut = p.proj ? y : x;
-    PtrTab src = pro ? x : c.tab(p.a[0]);
-    for (int j = 0; j < p.nconv; ++j) {
+    PtrTab shortcut{}, src{};
+    bool pro = false;
+    Loc lskip_in; lskip_in.kind = CALLER_SKIP_IN;
+    Loc lskip_out; lskip_out.kind = CALLER_SKIP_OUT;
+    if (p.j0 == 0) {
+      const PtrTab x = c.tab(p.x_in);
+      pro = bf && !p.mat[0];
+      c.bn_fwd(p.bn[0], x, c.tab(p.a[0]), M_in, part_rows, !pro);
+      // the shortcut value: x, or the projection of relu(bn1(x)); it leaves the partition if the block ends elsewhere
+      const PtrTab sc_dst = p.j1 == p.nconv ? c.tab(p.y) : c.tab(lskip_out);
+      if (p.proj) c.conv_fwd(p.pj, pro ? x : c.tab(p.a[0]), sc_dst, Ctx::none(), false, pro ? &p.bn[0] : nullptr);
+      else if (p.j1 < p.nconv) c.copy(sc_dst, x, M_out * p.d.c_out * P.esz);
+      shortcut = p.proj ? sc_dst : x;
+      src = pro ? x : c.tab(p.a[0]);
+    } else {
+      const PtrTab in = c.tab(p.c[p.j0 - 1]);
+      pro = bf && !p.mat[p.j0];
+      c.bn_fwd(p.bn[p.j0], in, c.tab(p.a[p.j0]), M_out, 0, !pro);
+      shortcut = c.tab(lskip_in);
+      src = pro ? in : c.tab(p.a[p.j0]);
+    }
+    for (int j = p.j0; j < p.j1; ++j) {
       const bool last = (j == p.nconv - 1);
-      const PtrTab out = last ? y : c.tab(p.c[j]);
+      const PtrTab out = last ? c.tab(p.y) : c.tab(p.c[j]);
       const bool next_resident = resident && bi + 1 < P.bp.size() && P.run_at[bi + 1] >= 0;
-      const bool feeds_bn = !last || (bi + 1 < P.bp.size() && !next_resident) || (bi + 1 == P.bp.size() && P.d.has_head);
+      const bool feeds_bn = (!last && j + 1 < p.j1) || (last && ((bi + 1 < P.bp.size() && !next_resident) || (bi + 1 == P.bp.size() && P.d.has_head)));
       part_rows = c.conv_fwd(p.cv[j], src, out, last ? shortcut : Ctx::none(), feeds_bn, pro ? &p.bn[j] : nullptr);
-      if (!last) {
-        pro = (P.dt == DT_BF16) && !p.mat[j + 1];
+      if (j + 1 < p.j1) {
+        pro = bf && !p.mat[j + 1];
         c.bn_fwd(p.bn[j + 1], out, c.tab(p.a[j + 1]), M_out, part_rows, !pro);
         src = pro ? out : c.tab(p.a[j + 1]);
       }
@@ -758,15 +817,25 @@ void run_backward(Ctx& c) {
     c.seg_same(PROF_OTHER_BWD);
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
+    Loc lskip_err_in; lskip_err_in.kind = CALLER_SKIP_ERR_IN;
+    Loc lskip_err_out; lskip_err_out.kind = CALLER_SKIP_ERR_OUT;
+    // dy: gradient w.r.t. the block output, which is also the gradient w.r.t. the shortcut value.  A block that
+    // ends in a later partition receives the latter from there (copied into the arena: the deferred weight
+    // gradient of the projection reads it) and starts from the gradient w.r.t. the output that left.
     const PtrTab dy = c.tab(p.gy);
-    PtrTab dr = dy;
-    for (int j = p.nconv - 1; j >= 1; --j) {
+    if (p.j1 < p.nconv && p.j0 == 0) c.copy(dy, c.tab(lskip_err_in), M_out * p.d.c_out * P.esz);
+    PtrTab dr = p.j1 == p.nconv ? dy : c.tab(p.dc[p.j1 - 1]);
+    for (int j = p.j1 - 1; j >= (p.j0 > 1 ? p.j0 : 1); --j) {
       const PtrTab xj = c.tab(p.c[j - 1]);
       if (!deferred) c.conv_wgrad(p.cv[j], c.tab(p.a[j]), dr);
       const int rows = c.conv_dgrad(p.cv[j], dr, tA, Ctx::none(), &p.bn[j], &xj);
       const PtrTab dcj = c.tab(p.dc[j - 1]);
       c.bn_bwd(p.bn[j], xj, tA, Ctx::none(), dcj, M_out, rows);
       dr = dcj;
+    }
+    if (p.j0 > 0) {   // the block started in an earlier partition: the gradient w.r.t. its shortcut value goes back there
+      if (p.j1 == p.nconv) c.copy(c.tab(lskip_err_out), dy, M_out * p.d.c_out * P.esz);
+      continue;
     }
     const PtrTab x0 = c.tab(p.x_in);
     if (!deferred) c.conv_wgrad(p.cv[0], c.tab(p.a[0]), dr);
@@ -912,6 +981,8 @@ hpf_status hpf_partition_sizes(const hpf_partition_desc* desc, hpf_sizes* out) {
   out->stash_bytes = P.stash_bytes_per_mb * (size_t)P.d.num_microbatches;
   out->act_in_elems = P.act_in_elems;
   out->act_out_elems = P.act_out_elems;
+  out->skip_in_elems = P.skip_in_elems;
+  out->skip_out_elems = P.skip_out_elems;
   return HPF_OK;
 }
 
@@ -992,10 +1063,22 @@ void hpf_partition_destroy(hpf_partition* p) {
   delete p;
 }
 
-hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* act_in,
-                                   const int32_t* const* labels, void* const* act_out, float* loss_accum, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// skip_in / skip_out: arrays like act_in / act_out for the shortcut value of a cut block, or NULL
+hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* act_in, const void* const* skip_in,
+                         const int32_t* const* labels, void* const* act_out, void* const* skip_out, float* loss_accum,
+                         void* hip_stream) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   const Plan& P = p->P;
+  if (P.skip_in_elems && !skip_in) return fail(HPF_EINVAL, "the first block starts after its first convolution: skip_in is required (hpf_forward_microbatch_cut)");
+  if (P.skip_out_elems && !skip_out) return fail(HPF_EINVAL, "the last block ends in a later partition: skip_out is required (hpf_forward_microbatch_cut)");
+  for (int i = 0; i < count && count >= 1; ++i) {
+    if (P.skip_in_elems && !skip_in[i]) return fail(HPF_EINVAL, "skip_in[%d] is null", i);
+    if (P.skip_out_elems && !skip_out[i]) return fail(HPF_EINVAL, "skip_out[%d] is null", i);
+  }
   if (count < 1 || mb_first < 0 || mb_first + count > P.d.num_microbatches)
     return fail(HPF_EINVAL, "micro-batches [%d, %d) out of range", mb_first, mb_first + count);
   if (!act_in) return fail(HPF_EINVAL, "act_in is required");
@@ -1026,7 +1109,10 @@ hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t 
       c.act_out[i] = P.d.has_head ? nullptr : act_out[c0 + i];
       c.err_in[i] = nullptr; c.err_out[i] = nullptr;
       lab.p[i] = P.d.has_head ? const_cast<int32_t*>(labels[c0 + i]) : nullptr;
+      c.skip_in[i] = P.skip_in_elems ? skip_in[c0 + i] : nullptr;
+      c.skip_out[i] = P.skip_out_elems ? skip_out[c0 + i] : nullptr;
       key.push_back(c.act_in[i]); key.push_back(c.act_out[i]); key.push_back(lab.p[i]);
+      key.push_back(c.skip_in[i]); key.push_back(c.skip_out[i]);
     }
     const hpf_status st = run_graphed(p, p->g_fwd[mb_first + c0], key, s, c, [&] { run_forward(c, lab, loss_accum); });
     if (st != HPF_OK) return st;
@@ -1040,10 +1126,17 @@ hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t 
   return resident_leave(p, s);
 }
 
-hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in,
-                                    void* const* err_out, void* hip_stream) {
+// skip_err_in: gradient w.r.t. skip_out (from the partition that took it); skip_err_out: gradient w.r.t. skip_in
+hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in, const void* const* skip_err_in,
+                          void* const* err_out, void* const* skip_err_out, void* hip_stream) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   const Plan& P = p->P;
+  if (P.skip_out_elems && !skip_err_in) return fail(HPF_EINVAL, "the last block ends in a later partition: skip_err_in is required (hpf_backward_microbatch_cut)");
+  if (P.skip_in_elems && !skip_err_out) return fail(HPF_EINVAL, "the first block starts after its first convolution: skip_err_out is required (hpf_backward_microbatch_cut)");
+  for (int i = 0; i < count && count >= 1; ++i) {
+    if (P.skip_out_elems && !skip_err_in[i]) return fail(HPF_EINVAL, "skip_err_in[%d] is null", i);
+    if (P.skip_in_elems && !skip_err_out[i]) return fail(HPF_EINVAL, "skip_err_out[%d] is null", i);
+  }
   if (count < 1 || mb_first < 0 || mb_first + count > P.d.num_microbatches)
     return fail(HPF_EINVAL, "micro-batches [%d, %d) out of range", mb_first, mb_first + count);
   if (!P.d.has_head && !err_in) return fail(HPF_EINVAL, "err_in is required without a head");
@@ -1074,7 +1167,10 @@ hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t
       c.act_out[i] = nullptr;
       c.err_in[i] = P.d.has_head ? nullptr : err_in[c0 + i];
       c.err_out[i] = P.d.has_stem ? nullptr : err_out[c0 + i];
+      c.skip_err_in[i] = P.skip_out_elems ? skip_err_in[c0 + i] : nullptr;
+      c.skip_err_out[i] = P.skip_in_elems ? skip_err_out[c0 + i] : nullptr;
       key.push_back(c.act_in[i]); key.push_back(c.err_in[i]); key.push_back(c.err_out[i]);
+      key.push_back(c.skip_err_in[i]); key.push_back(c.skip_err_out[i]);
     }
     const hpf_status st = run_graphed(p, p->g_bwd[mb_first + c0], key, s, c, [&] { run_backward(c); });
     if (st != HPF_OK) return st;
@@ -1086,6 +1182,40 @@ hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t
     }
   }
   return resident_leave(p, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+hpf_status hpf_forward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* act_in,
+                                   const int32_t* const* labels, void* const* act_out, float* loss_accum, void* hip_stream) {
+  return forward_group(p, mb_first, count, act_in, nullptr, labels, act_out, nullptr, loss_accum, hip_stream);
+}
+
+hpf_status hpf_backward_microbatches(hpf_partition* p, int32_t mb_first, int32_t count, const void* const* err_in,
+                                    void* const* err_out, void* hip_stream) {
+  return backward_group(p, mb_first, count, err_in, nullptr, err_out, nullptr, hip_stream);
+}
+
+hpf_status hpf_forward_microbatch_cut(hpf_partition* p, int32_t mb, const void* act_in, const void* skip_in, const int32_t* labels,
+                                      void* act_out, void* skip_out, float* loss_accum, void* hip_stream) {
+  if (p && p->P.d.has_head && !labels) return fail(HPF_EINVAL, "labels and loss_accum are required with a head");
+  if (p && !p->P.d.has_head && !act_out) return fail(HPF_EINVAL, "act_out is required without a head");
+  if (!act_in) return fail(HPF_EINVAL, "act_in is required");
+  if (p && !p->P.skip_in_elems && skip_in) return fail(HPF_EINVAL, "skip_in given, but the first block starts at its first convolution");
+  if (p && !p->P.skip_out_elems && skip_out) return fail(HPF_EINVAL, "skip_out given, but the last block ends here");
+  return forward_group(p, mb, 1, &act_in, &skip_in, &labels, &act_out, &skip_out, loss_accum, hip_stream);
+}
+
+hpf_status hpf_backward_microbatch_cut(hpf_partition* p, int32_t mb, const void* err_in, const void* skip_err_in, void* err_out,
+                                       void* skip_err_out, void* hip_stream) {
+  if (p && !p->P.d.has_head && !err_in) return fail(HPF_EINVAL, "err_in is required without a head");
+  if (p && !p->P.d.has_stem && !err_out) return fail(HPF_EINVAL, "err_out is required");
+  if (p && p->P.d.has_stem && err_out) return fail(HPF_EINVAL, "err_out must be NULL for the partition that holds the stem");
+  if (p && !p->P.skip_out_elems && skip_err_in) return fail(HPF_EINVAL, "skip_err_in given, but the last block ends here");
+  if (p && !p->P.skip_in_elems && skip_err_out) return fail(HPF_EINVAL, "skip_err_out given, but the first block starts at its first convolution");
+  return backward_group(p, mb, 1, &err_in, &skip_err_in, &err_out, &skip_err_out, hip_stream);
 }
 
 hpf_status hpf_forward_microbatch(hpf_partition* p, int32_t mb, const void* act_in, const int32_t* labels, void* act_out,

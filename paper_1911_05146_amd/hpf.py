@@ -15,7 +15,7 @@ from typing import Optional
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libhpf.so")
 
-HPF_ABI_VERSION = 1
+HPF_ABI_VERSION = 2
 HPF_OK, HPF_EINVAL, HPF_ESTATE, HPF_ENOMEM, HPF_EDEVICE, HPF_EUNSUPPORTED = range(6)
 HPF_F32, HPF_BF16 = 0, 1
 STATUS_NAMES = {0: "HPF_OK", 1: "HPF_EINVAL", 2: "HPF_ESTATE", 3: "HPF_ENOMEM", 4: "HPF_EDEVICE",
@@ -32,12 +32,14 @@ class hpf_partition_desc(C.Structure):
                 ("has_stem", C.c_int32), ("stem_c_out", C.c_int32), ("n_blocks", C.c_int32),
                 ("blocks", C.POINTER(hpf_block_desc)), ("has_head", C.c_int32), ("num_classes", C.c_int32),
                 ("microbatch", C.c_int32), ("num_microbatches", C.c_int32), ("loss_divisor", C.c_int32),
-                ("compute_dtype", C.c_int), ("bn_eps", C.c_float), ("bn_mode", C.c_int32)]
+                ("compute_dtype", C.c_int), ("bn_eps", C.c_float), ("bn_mode", C.c_int32),
+                ("first_block_from_conv", C.c_int32), ("last_block_to_conv", C.c_int32)]
 
 
 class hpf_sizes(C.Structure):
     _fields_ = [("n_params", C.c_size_t), ("arena_bytes", C.c_size_t), ("stash_bytes", C.c_size_t),
-                ("act_in_elems", C.c_size_t), ("act_out_elems", C.c_size_t)]
+                ("act_in_elems", C.c_size_t), ("act_out_elems", C.c_size_t),
+                ("skip_in_elems", C.c_size_t), ("skip_out_elems", C.c_size_t)]
 
 
 class HpfError(RuntimeError):
@@ -63,6 +65,8 @@ def _load():
     L.hpf_partition_create.argtypes = [C.POINTER(hpf_partition_desc), vp, sz, vp, C.POINTER(vp)]
     L.hpf_forward_microbatch.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.hpf_backward_microbatch.argtypes = [vp, i32, vp, vp, vp]
+    L.hpf_forward_microbatch_cut.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.hpf_backward_microbatch_cut.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.hpf_forward_microbatches.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     L.hpf_backward_microbatches.argtypes = [vp, i32, i32, vp, vp, vp]
     L.hpf_grad_accum_read.argtypes = [vp, vp, sz, i32, vp]
@@ -88,6 +92,7 @@ def _load():
 lib = _load()
 
 EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatch", "hpf_backward_microbatch",
+           "hpf_forward_microbatch_cut", "hpf_backward_microbatch_cut",
            "hpf_forward_microbatches", "hpf_backward_microbatches",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
            "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_partition_set_fusion",
@@ -115,7 +120,7 @@ def make_desc(spec, compute_dtype=HPF_BF16):
     d = hpf_partition_desc(HPF_ABI_VERSION, spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
                            n, C.cast(arr, C.POINTER(hpf_block_desc)), int(spec.has_head), spec.num_classes,
                            spec.microbatch, spec.num_microbatches, spec.divisor, compute_dtype,
-                           float(spec.bn_eps), spec.bn_mode)
+                           float(spec.bn_eps), spec.bn_mode, getattr(spec, "first_from", 0), getattr(spec, "last_to", 0))
     return d, arr
 
 
@@ -140,6 +145,16 @@ def hpf_forward_microbatch(handle, mb, act_in, labels, act_out, loss_accum, stre
 
 def hpf_backward_microbatch(handle, mb, err_in, err_out, stream=0):
     _check(lib.hpf_backward_microbatch(handle, mb, err_in or None, err_out or None, stream or None))
+
+
+def hpf_forward_microbatch_cut(handle, mb, act_in, skip_in, labels, act_out, skip_out, loss_accum, stream=0):
+    _check(lib.hpf_forward_microbatch_cut(handle, mb, act_in, skip_in or None, labels or None, act_out or None,
+                                          skip_out or None, loss_accum or None, stream or None))
+
+
+def hpf_backward_microbatch_cut(handle, mb, err_in, skip_err_in, err_out, skip_err_out, stream=0):
+    _check(lib.hpf_backward_microbatch_cut(handle, mb, err_in or None, skip_err_in or None, err_out or None,
+                                           skip_err_out or None, stream or None))
 
 
 def _ptr_array(ptrs):
@@ -333,6 +348,8 @@ class Partition:
         self.in_shape = (spec.microbatch, spec.in_h, spec.in_w, spec.in_c)
         self.out_shape = (spec.microbatch, oh, ow, oc)
         self.in_dtype = torch.float32 if spec.has_stem else self.tdtype
+        self.skip_in_shape = (spec.microbatch,) + tuple(spec.skip_in_shape()) if getattr(spec, "has_skip_in", False) else None
+        self.skip_out_shape = (spec.microbatch,) + tuple(spec.skip_out_shape()) if getattr(spec, "has_skip_out", False) else None
         self.loss = torch.zeros(1, dtype=torch.float32, device=self.device)
 
     def close(self):
@@ -380,6 +397,44 @@ class Partition:
         hpf_backward_microbatch(self.handle, mb, err_in.data_ptr() if err_in is not None else 0,
                                 err_out.data_ptr() if err_out is not None else 0, self._stream_or_current(stream))
         return err_out
+
+    def _skip_ok(self, t, shape):
+        return t is not None and tuple(t.shape) == shape and t.dtype == self.tdtype and t.is_contiguous()
+
+    def forward_microbatch_cut(self, mb, act_in, skip_in=None, labels=None, act_out=None, skip_out=None, stream=None):
+        """Forward of a partition cut at layer granularity: returns (act_out, skip_out)."""
+        assert tuple(act_in.shape) == self.in_shape and act_in.dtype == self.in_dtype and act_in.is_contiguous()
+        if not self.spec.has_head and act_out is None:
+            act_out = self.torch.empty(self.out_shape, dtype=self.tdtype, device=self.device)
+        if self.skip_in_shape:
+            assert self._skip_ok(skip_in, self.skip_in_shape)
+        if self.skip_out_shape:
+            if skip_out is None:
+                skip_out = self.torch.empty(self.skip_out_shape, dtype=self.tdtype, device=self.device)
+            assert self._skip_ok(skip_out, self.skip_out_shape)
+        hpf_forward_microbatch_cut(self.handle, mb, act_in.data_ptr(), skip_in.data_ptr() if skip_in is not None else 0,
+                                   labels.data_ptr() if labels is not None else 0,
+                                   act_out.data_ptr() if act_out is not None else 0,
+                                   skip_out.data_ptr() if skip_out is not None else 0,
+                                   self.loss.data_ptr() if self.spec.has_head else 0, self._stream_or_current(stream))
+        return act_out, skip_out
+
+    def backward_microbatch_cut(self, mb, err_in=None, skip_err_in=None, err_out=None, skip_err_out=None, stream=None):
+        """Backward of a partition cut at layer granularity: returns (err_out, skip_err_out)."""
+        if not self.spec.has_stem and err_out is None:
+            err_out = self.torch.empty(self.in_shape, dtype=self.tdtype, device=self.device)
+        if self.skip_out_shape:
+            assert self._skip_ok(skip_err_in, self.skip_out_shape)
+        if self.skip_in_shape:
+            if skip_err_out is None:
+                skip_err_out = self.torch.empty(self.skip_in_shape, dtype=self.tdtype, device=self.device)
+            assert self._skip_ok(skip_err_out, self.skip_in_shape)
+        hpf_backward_microbatch_cut(self.handle, mb, err_in.data_ptr() if err_in is not None else 0,
+                                    skip_err_in.data_ptr() if skip_err_in is not None else 0,
+                                    err_out.data_ptr() if err_out is not None else 0,
+                                    skip_err_out.data_ptr() if skip_err_out is not None else 0,
+                                    self._stream_or_current(stream))
+        return err_out, skip_err_out
 
     def forward_microbatches(self, mb_first, act_in, labels=None, act_out=None, stream=None):
         """Group call: lists of tensors for micro-batches mb_first, mb_first+1, ..."""

@@ -66,6 +66,12 @@ class PartitionSpec:
     bn_eps: float = 1e-5
     bn_mode: int = 0               # 0: statistics of the micro-batch, 1: frozen mean 0 / var 1
     seed: int = SEED_BASE
+    # Cuts at layer granularity: the partition holds convolutions [first_from, n) of its first block and
+    # [0, last_to) of its last block (0 = the whole block).  A BatchNorm+ReLU belongs to the convolution it
+    # feeds, the projection to convolution 0, the residual add to the last convolution.  With first_from > 0,
+    # (in_h, in_w, in_c) is the output of convolution first_from-1 (block-output size, c_mid channels).
+    first_from: int = 0
+    last_to: int = 0
 
     @property
     def batch(self) -> int:
@@ -75,14 +81,45 @@ class PartitionSpec:
     def divisor(self) -> int:
         return self.loss_divisor if self.loss_divisor > 0 else self.batch
 
+    def conv_range(self, i: int) -> Tuple[int, int]:
+        """[j0, j1): the convolutions of block i that this partition holds."""
+        n = 2 if self.blocks[i].kind == BASIC else 3
+        j0 = self.first_from if i == 0 else 0
+        j1 = self.last_to if (i == len(self.blocks) - 1 and self.last_to > 0) else n
+        return j0, j1
+
     def out_shape(self) -> Tuple[int, int, int]:
-        """(H, W, C) of the tensor leaving the last residual block."""
+        """(H, W, C) of the tensor leaving the partition's last layer (before the head)."""
         h, w = self.in_h, self.in_w
         c = self.stem_c_out if self.has_stem else self.in_c
-        for b in self.blocks:
-            assert b.c_in == c, (self.name, b, c)
-            h, w, c = h // b.stride, w // b.stride, b.c_out
+        for i, b in enumerate(self.blocks):
+            j0, j1 = self.conv_range(i)
+            n = 2 if b.kind == BASIC else 3
+            if j0 == 0:
+                assert b.c_in == c, (self.name, b, c)
+                h, w = h // b.stride, w // b.stride
+            else:
+                assert b.c_mid == c, (self.name, b, c)
+            c = b.c_out if j1 == n else b.c_mid
         return h, w, c
+
+    @property
+    def has_skip_in(self) -> bool:
+        """The first block starts after its convolution 0 and ends here: its shortcut value comes from the
+        partition that holds its start."""
+        return self.first_from > 0 and self.conv_range(0)[1] == (2 if self.blocks[0].kind == BASIC else 3)
+
+    @property
+    def has_skip_out(self) -> bool:
+        """The last block starts here and ends in a later partition: its shortcut value leaves directly."""
+        return self.last_to > 0 and self.conv_range(len(self.blocks) - 1)[0] == 0
+
+    def skip_in_shape(self) -> Tuple[int, int, int]:
+        return self.in_h, self.in_w, self.blocks[0].c_out
+
+    def skip_out_shape(self) -> Tuple[int, int, int]:
+        h, w, _ = self.out_shape()
+        return h, w, self.blocks[-1].c_out
 
 
 # ----------------------------------------------------------------------------
@@ -213,22 +250,15 @@ def param_layout(spec: PartitionSpec) -> List[ParamEntry]:
         add("stem.W", (3, 3, spec.in_c, spec.stem_c_out), "conv")
     for i, b in enumerate(spec.blocks):
         p = f"block{i}."
-        add(p + "bn1.gamma", (b.c_in,), "gamma")
-        add(p + "bn1.beta", (b.c_in,), "beta")
-        if b.kind == BASIC:
-            add(p + "W1", (3, 3, b.c_in, b.c_mid), "conv")
-            add(p + "bn2.gamma", (b.c_mid,), "gamma")
-            add(p + "bn2.beta", (b.c_mid,), "beta")
-            add(p + "W2", (3, 3, b.c_mid, b.c_out), "conv")
-        else:
-            add(p + "W1", (1, 1, b.c_in, b.c_mid), "conv")
-            add(p + "bn2.gamma", (b.c_mid,), "gamma")
-            add(p + "bn2.beta", (b.c_mid,), "beta")
-            add(p + "W2", (3, 3, b.c_mid, b.c_mid), "conv")
-            add(p + "bn3.gamma", (b.c_mid,), "gamma")
-            add(p + "bn3.beta", (b.c_mid,), "beta")
-            add(p + "W3", (1, 1, b.c_mid, b.c_out), "conv")
-        if b.has_proj:
+        j0, j1 = spec.conv_range(i)
+        cin = (b.c_in, b.c_mid, b.c_mid)
+        cout = (b.c_mid, b.c_out, None) if b.kind == BASIC else (b.c_mid, b.c_mid, b.c_out)
+        R = (3, 3, None) if b.kind == BASIC else (1, 3, 1)
+        for j in range(j0, j1):        # only the layers held here, in canonical order
+            add(p + f"bn{j + 1}.gamma", (cin[j],), "gamma")
+            add(p + f"bn{j + 1}.beta", (cin[j],), "beta")
+            add(p + f"W{j + 1}", (R[j], R[j], cin[j], cout[j]), "conv")
+        if b.has_proj and j0 == 0:
             add(p + "Wproj", (1, 1, b.c_in, b.c_out), "conv")
     if spec.has_head:
         c = spec.out_shape()[2]
@@ -253,6 +283,8 @@ class StepInputs:
     act_in: List[np.ndarray]                 # per micro-batch [b,H,W,C] float32
     labels: Optional[List[np.ndarray]]       # per micro-batch [b] int32 (head only)
     err_in: Optional[List[np.ndarray]]       # per micro-batch [b,H',W',C'] float32 (no head)
+    skip_in: Optional[List[np.ndarray]] = None       # shortcut value for a first block cut after its start
+    skip_err_in: Optional[List[np.ndarray]] = None   # gradient w.r.t. skip_out of a last block cut before its end
 
 
 def make_params(spec: PartitionSpec, rng: np.random.Generator,
@@ -281,12 +313,16 @@ def make_inputs(spec: PartitionSpec, randomize_affine: bool = False) -> StepInpu
     params = make_params(spec, rng, randomize_affine)
     b = spec.microbatch
     oh, ow, oc = spec.out_shape()
-    act_in, labels, err_in = [], [], []
+    act_in, labels, err_in, skip_in, skip_err_in = [], [], [], [], []
     for _ in range(spec.num_microbatches):
         act_in.append(rng.standard_normal((b, spec.in_h, spec.in_w, spec.in_c), dtype=np.float32))
         if spec.has_head:
             labels.append(rng.integers(0, spec.num_classes, size=b, dtype=np.int32))
         else:
             err_in.append((0.1 * rng.standard_normal((b, oh, ow, oc), dtype=np.float32)))
+        if spec.has_skip_in:
+            skip_in.append(rng.standard_normal((b,) + spec.skip_in_shape(), dtype=np.float32))
+        if spec.has_skip_out:
+            skip_err_in.append(0.1 * rng.standard_normal((b,) + spec.skip_out_shape(), dtype=np.float32))
     return StepInputs(params, act_in, labels if spec.has_head else None,
-                      None if spec.has_head else err_in)
+                      None if spec.has_head else err_in, skip_in or None, skip_err_in or None)

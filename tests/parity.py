@@ -92,7 +92,7 @@ def rel_l2(got, ref):
 
 def _tensors(res, spec):
     out = {}
-    for k in ("act_out", "err_out"):
+    for k in ("act_out", "err_out", "skip_out", "skip_err_out"):
         v = [t for t in res.get(k, []) if t is not None]
         if v:
             out[k] = np.concatenate([np.asarray(t, np.float64).ravel() for t in v])
