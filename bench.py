@@ -69,6 +69,47 @@ def cpu_baseline(spec, inputs, max_microbatches=4):
             "sample": f"{n} of {spec.num_microbatches} micro-batches ({sub.batch} images) forward+backward, {dt:.1f} s"}
 
 
+def bench_pipeline(args, torch, dev):
+    """Whole ResNet-110 (54 basic blocks, 32x32x3 inputs, 8 micro-batches of 16) as P chained partitions."""
+    from paper_1911_05146_amd import hpf, layer_cuts, workloads as W
+    from paper_1911_05146_amd.pipeline import Pipeline, split_model
+    blocks, b, m, seed = W.basic_resnet_blocks(18), 16, 8, W.SEED_BASE + 6
+    if args.cuts == "layers":
+        cm = layer_cuts.split_at_layers("resnet110", blocks, layer_cuts.even_layer_cuts(blocks, args.pipeline), 32, 16, 10, b, m, seed)
+        specs, whole = cm.specs, cm.whole
+    else:
+        cm = None
+        specs = split_model("resnet110", blocks, args.pipeline, 32, 16, 10, b, m, seed)
+        whole = W.partition_of("resnet110", blocks, 1, 0, 32, 16, 16, 10, b, m, seed)
+    inp = W.make_inputs(whole)
+    pipe = Pipeline(specs, inp.params, hpf.HPF_BF16, group=1, cut_model=cm)
+    x = [torch.from_numpy(a).to(dev) for a in inp.act_in]
+    lab = [torch.from_numpy(l).to(dev) for l in inp.labels]
+
+    def step():
+        for part, s in zip(pipe.parts, pipe.streams):
+            part.grad_accum_zero(stream=s)
+        pipe.run_batch(x, lab)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_skip = sum(1 for msg in cm.messages if msg.tensor == "skip") if cm else 0
+    pipe.close()
+    print(json.dumps({
+        "metric": "images/sec through the chained partitions fwd+bwd at 1 MI355X", "value": b * m * args.steps / elapsed,
+        "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResNet-110 whole model, {args.pipeline} partitions cut at {args.cuts}, "
+                               f"{m} micro-batches of {b} images, one stream per partition",
+                   "partitions": args.pipeline, "cuts": args.cuts, "skip_tensors_crossing_partitions": n_skip}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +124,12 @@ def main():
                     help="kernel schedule of the library (hpf_partition_set_fusion); default 2, the library's default")
     ap.add_argument("--no-probe", action="store_true", help="skip the per-kernel-class timing")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--pipeline", type=int, default=0, metavar="P",
+                    help="instead of one partition: the whole ResNet-110 (CIFAR shape) cut into P partitions chained on "
+                         "the GPU, one stream per partition (paper: pipelined model parallelism); see --cuts")
+    ap.add_argument("--cuts", choices=["blocks", "layers"], default="blocks",
+                    help="with --pipeline: cut at residual-block boundaries, or evenly over the convolution layers "
+                         "(cuts inside blocks; shortcut values cross partitions)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -98,6 +145,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.pipeline > 0:
+        return bench_pipeline(args, torch, dev)
     spec = W.config(args.config)
     inputs = W.make_inputs(spec)
     m = spec.num_microbatches

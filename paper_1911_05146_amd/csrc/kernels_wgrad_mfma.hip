@@ -116,6 +116,24 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
     return make_uint4(r_[0], r_[1], r_[2], r_[3]);
   };
 
+  // (image, output row, output column) of every pixel row this thread stages: decoded once with divisions for
+  // the first step, then advanced by ROWS rows per step with carries (ROWS = dimg*HoWo + dp*Wo + dq)
+  const int dimg = ROWS / HoWo, drem = ROWS - dimg * HoWo, dp = drem / g.Wo, dq = drem - dp * g.Wo;
+  int pi[A_UNITS], pp[A_UNITS], pq[A_UNITS];   // of the even row of each pair; the odd row follows it
+#pragma unroll
+  for (int u = 0; u < A_UNITS; ++u) {
+    const int unit = tid + u * 256;
+    int pr, cg;
+    unit_map<BC / 8>(unit < A_N ? unit : 0, pr, cg);
+    const int m = m_begin + 2 * pr;
+    pi[u] = m / HoWo;
+    const int rem = m - pi[u] * HoWo;
+    pp[u] = rem / g.Wo;
+    pq[u] = rem - pp[u] * g.Wo;
+  }
+  // All loads are issued unconditionally (rows past the end or outside the image read a clamped address and are
+  // zeroed when they are stored to LDS), so the count of outstanding loads is known at every wait.
+  bool dv[D_UNITS][2];
   auto load_step = [&](int m0) {
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
@@ -125,19 +143,20 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
-        bool v = (unit < A_N) && m < m_end;
-        size_t off = 0;
-        if (v) {
-          const int img = m / HoWo;
-          const int rem = m - img * HoWo;
-          const int p = rem / g.Wo, q = rem - p * g.Wo;
-          const int hi = p * g.stride + r - g.pad, wi = q * g.stride + s - g.pad;
-          v = (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
-          off = ((size_t)(img * g.H + hi) * g.W + wi) * g.Cin + c0 + cg * 8;
-        }
+        int im = pi[u], p = pp[u], q = pq[u] + e;
+        if (q >= g.Wo) { q = 0; if (++p >= g.Ho) { p = 0; ++im; } }
+        const int hi = p * g.stride + r - g.pad, wi = q * g.stride + s - g.pad;
+        const bool v = (unit < A_N) && m < m_end && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
+        const size_t off = v ? ((size_t)(im * g.H + hi) * g.W + wi) * g.Cin + c0 + cg * 8 : (size_t)0;
         rv[u][e] = v;
-        ra[u][e] = v ? *reinterpret_cast<const uint4*>(a + off) : make_uint4(0u, 0u, 0u, 0u);
+        ra[u][e] = *reinterpret_cast<const uint4*>(a + off);
       }
+      // next step's rows
+      pq[u] += dq;
+      if (pq[u] >= g.Wo) { pq[u] -= g.Wo; ++pp[u]; }
+      pp[u] += dp;
+      if (pp[u] >= g.Ho) { pp[u] -= g.Ho; ++pi[u]; }
+      pi[u] += dimg;
     }
 #pragma unroll
     for (int u = 0; u < D_UNITS; ++u) {
@@ -148,7 +167,8 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
       for (int e = 0; e < 2; ++e) {
         const int m = m0 + 2 * pr + e;
         const bool v = (unit < D_N) && m < m_end;
-        rd[u][e] = v ? *reinterpret_cast<const uint4*>(dy + (size_t)m * g.N + n0 + ng * 8) : make_uint4(0u, 0u, 0u, 0u);
+        dv[u][e] = v;
+        rd[u][e] = *reinterpret_cast<const uint4*>(dy + (v ? (size_t)m * g.N + n0 + ng * 8 : (size_t)0));
       }
     }
   };
@@ -180,10 +200,11 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
               cf[0][2 * i + 1] = make_float2(k.z, k.w);
             }
           }
-          if (rv[u][0]) ra[u][0] = bn_relu8(ra[u][0], cf[QUAD ? 0 : u]);
-          if (rv[u][1]) ra[u][1] = bn_relu8(ra[u][1], cf[QUAD ? 0 : u]);
+          ra[u][0] = bn_relu8(ra[u][0], cf[QUAD ? 0 : u]);
+          ra[u][1] = bn_relu8(ra[u][1], cf[QUAD ? 0 : u]);
         }
-        store_pairs(sA, pr, cg, ra[u][0], ra[u][1]);
+        const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+        store_pairs(sA, pr, cg, rv[u][0] ? ra[u][0] : zero, rv[u][1] ? ra[u][1] : zero);
       }
     }
 #pragma unroll
@@ -192,7 +213,8 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
       if (unit < D_N) {
         int pr, ng;
         unit_map<BN / 8>(unit, pr, ng);
-        store_pairs(sD, pr, ng, rd[u][0], rd[u][1]);
+        const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+        store_pairs(sD, pr, ng, dv[u][0] ? rd[u][0] : zero, dv[u][1] ? rd[u][1] : zero);
       }
     }
   };
