@@ -82,7 +82,7 @@ def bench_pipeline(args, torch, dev):
         specs = split_model("resnet110", blocks, args.pipeline, 32, 16, 10, b, m, seed)
         whole = W.partition_of("resnet110", blocks, 1, 0, 32, 16, 16, 10, b, m, seed)
     inp = W.make_inputs(whole)
-    pipe = Pipeline(specs, inp.params, hpf.HPF_BF16, group=1, cut_model=cm)
+    pipe = Pipeline(specs, inp.params, hpf.HPF_BF16, group=1 if cm else args.group, cut_model=cm)
     x = [torch.from_numpy(a).to(dev) for a in inp.act_in]
     lab = [torch.from_numpy(l).to(dev) for l in inp.labels]
 
@@ -106,7 +106,8 @@ def bench_pipeline(args, torch, dev):
         "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"ResNet-110 whole model, {args.pipeline} partitions cut at {args.cuts}, "
-                               f"{m} micro-batches of {b} images, one stream per partition",
+                               f"{m} micro-batches of {b} images, one stream per partition, "
+                               f"{1 if cm else args.group} micro-batch(es) per call",
                    "partitions": args.pipeline, "cuts": args.cuts, "skip_tensors_crossing_partitions": n_skip}}))
 
 
@@ -127,6 +128,8 @@ def main():
     ap.add_argument("--pipeline", type=int, default=0, metavar="P",
                     help="instead of one partition: the whole ResNet-110 (CIFAR shape) cut into P partitions chained on "
                          "the GPU, one stream per partition (paper: pipelined model parallelism); see --cuts")
+    ap.add_argument("--group", type=int, default=1,
+                    help="with --pipeline and --cuts blocks: micro-batches per library call (1, 2, 4 or 8)")
     ap.add_argument("--cuts", choices=["blocks", "layers"], default="blocks",
                     help="with --pipeline: cut at residual-block boundaries, or evenly over the convolution layers "
                          "(cuts inside blocks; shortcut values cross partitions)")
