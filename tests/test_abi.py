@@ -83,3 +83,36 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_layer_cut_descriptions_sizes_and_validation(hpf):
+    """Partitions cut inside residual blocks (paper Section "Special Handling for Non-consecutive Models"): the
+    library and the host-side splitter agree on parameter counts and tensor sizes; bad cuts are rejected."""
+    from paper_1911_05146_amd import layer_cuts as LC
+    blocks = W.bottleneck_resnet_blocks([2, 2], (16, 32), (64, 128), 16) + [W.Block(W.BASIC, 128, 128, 128, 1)]
+    cm = LC.split_at_layers("m", blocks, [1, 2, 4, 8, 13], 16, 16, 10, 4, 2, 3)
+    total = 0
+    for spec in cm.specs:
+        z = hpf.hpf_partition_sizes(hpf.make_desc(spec)[0])
+        assert z.n_params == W.n_params(spec)
+        total += z.n_params
+        b = spec.microbatch
+        oh, ow, oc = spec.out_shape()
+        assert z.act_in_elems == b * spec.in_h * spec.in_w * spec.in_c
+        assert z.act_out_elems == (0 if spec.has_head else b * oh * ow * oc)
+        assert z.skip_in_elems == (b * int(__import__("numpy").prod(spec.skip_in_shape())) if spec.has_skip_in else 0)
+        assert z.skip_out_elems == (b * int(__import__("numpy").prod(spec.skip_out_shape())) if spec.has_skip_out else 0)
+    assert total == W.n_params(cm.whole)
+    r = dataclasses.replace
+    tail = cm.specs[2]                       # starts after the first two convolutions of block 0
+    assert tail.first_from == 2 and status_of(hpf, tail) == hpf.HPF_OK
+    assert status_of(hpf, r(tail, first_from=3)) == hpf.HPF_EINVAL           # a bottleneck has three convolutions
+    assert status_of(hpf, r(tail, first_from=-1)) == hpf.HPF_EINVAL
+    assert status_of(hpf, r(tail, in_c=64)) == hpf.HPF_EINVAL                # the input must have c_mid channels
+    assert status_of(hpf, r(tail, has_stem=True, stem_c_out=16)) == hpf.HPF_EINVAL
+    head = cm.specs[0]
+    assert head.last_to == 1 and head.has_stem
+    assert status_of(hpf, r(head, last_to=3)) == hpf.HPF_EINVAL              # the whole block is last_to = 0
+    assert status_of(hpf, r(head, has_head=True, num_classes=10)) == hpf.HPF_EINVAL
+    one = r(tail, blocks=tail.blocks[:1], first_from=1, last_to=1)
+    assert status_of(hpf, one) == hpf.HPF_EINVAL                             # empty range of convolutions
