@@ -116,7 +116,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..5 (default 3: ResNet-1001 partition)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..6 (default 3: ResNet-1001 partition; 6: the same cut of the 30 M-parameter variant)")
     ap.add_argument("--schedule", choices=["grouped", "streams", "single-stream"], default="grouped",
                     help="grouped: all micro-batches of the batch in one group call per direction (default); "
                          "streams: one call and one stream per micro-batch; single-stream: one call per micro-batch, one stream")

@@ -206,10 +206,29 @@ def resnet152_stage3(n_blocks=36, microbatch=16, num_microbatches=4,
                          num_microbatches=num_microbatches, seed=seed)
 
 
+def resnet1001_wide_blocks() -> List[Block]:
+    """The wider ResNet-1001-v2 with about 30 M parameters (the size the paper quotes for its ResNet-1001):
+    333 bottleneck blocks whose inner width is the width of the stage's input, i.e. 16 -> 64 in stage 1,
+    64 -> 128 in stage 2 and 128 -> 256 in stage 3 (inner widths 16 / 64 / 128)."""
+    blocks, c = [], 16
+    for s, (mid, out) in enumerate(((16, 64), (64, 128), (128, 256))):
+        for i in range(111):
+            blocks.append(Block(BOTTLENECK, c, mid, out, 2 if (s > 0 and i == 0) else 1))
+            c = out
+    return blocks
+
+
+def resnet1001_wide_partition(p=7, n_parts=16, microbatch=32, num_microbatches=8,
+                              seed=SEED_BASE + 6) -> PartitionSpec:
+    """Partition 7 of 16 of the 30 M-parameter variant: 21 identity blocks 128-64-64-128 at 16x16."""
+    return partition_of(f"resnet1001wide-part{p}of{n_parts}", resnet1001_wide_blocks(), n_parts, p,
+                        32, 16, 16, 10, microbatch, num_microbatches, seed)
+
+
 def config(index: int) -> PartitionSpec:
-    """The five benchmark configurations, numbered 1..5."""
+    """The five benchmark configurations, numbered 1..5, and 6: the same cut of the wider ResNet-1001."""
     return {1: resnet20, 2: resnet110_partition, 3: resnet1001_partition,
-            4: resnet1001_whole, 5: resnet152_stage3}[index]()
+            4: resnet1001_whole, 5: resnet152_stage3, 6: resnet1001_wide_partition}[index]()
 
 
 def with_microbatching(spec: PartitionSpec, microbatch: int, num_microbatches: int,

@@ -227,6 +227,12 @@ def test_resnet1001_partition_two_microbatches(gpu, oracle, mode):
     check(oracle, W.with_microbatching(W.config(3), 32, 2, loss_divisor=256), mode)
 
 
+@pytest.mark.parametrize("mode", ["f32", "bf16"])
+def test_resnet1001_wide_partition_two_microbatches(gpu, oracle, mode):
+    """The 30 M-parameter variant (inner widths 16 / 64 / 128): 21 blocks 128-64-64-128 at 16x16."""
+    check(oracle, W.with_microbatching(W.config(6), 8, 2, loss_divisor=64), mode)
+
+
 def test_resnet1001_partition_full_batch_on_streams(gpu, oracle):
     """8 micro-batches of 32, one stream each."""
     check(oracle, W.config(3), "bf16", multi_stream=True, randomize_affine=False)

@@ -286,6 +286,10 @@ def test_parameter_counts_of_the_benchmark_partitions():
     assert [W.n_params(W.config(i)) for i in range(1, 6)] == [272282, 446528, 373632, 10327706, 40610816]
     # ResNet-1001 = 9*111 + 2 weighted layers
     assert len(W.resnet1001_blocks()) * 3 + 2 == 1001
+    # the wider variant has the size the paper quotes for its ResNet-1001 ("approximately 30 million parameters")
+    wide = W.partition_of("w", W.resnet1001_wide_blocks(), 1, 0, 32, 16, 16, 10, 1, 1, 0)
+    assert len(wide.blocks) * 3 + 2 == 1001 and 29.5e6 < W.n_params(wide) < 30.5e6
+    assert W.n_params(W.config(6)) == 21 * (2 * 128 + 128 * 64 + 2 * 64 + 9 * 64 * 64 + 2 * 64 + 64 * 128)
 
 
 def test_bf16_storage_reading_keeps_the_premise_and_stays_near_the_plain_reference(oracle):
