@@ -46,6 +46,13 @@ def lib():
         L.oracle_forward_microbatch_cut.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 6
         L.oracle_backward_microbatch_cut.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
         L.oracle_grad_accum_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+        L.oracle_forward_inference.argtypes = [C.c_void_p] * 5
+        L.oracle_set_bn_momentum.argtypes = [C.c_void_p, C.c_double]
+        L.oracle_set_bn_momentum.restype = None
+        L.oracle_n_bn_running.argtypes = [C.c_void_p]
+        L.oracle_n_bn_running.restype = C.c_size_t
+        L.oracle_bn_running_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+        L.oracle_bn_running_write.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.oracle_grad_accum_zero.argtypes = [C.c_void_p]
         L.oracle_sgd_step.argtypes = [C.c_void_p, C.c_double, C.c_double]
         L.oracle_params_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
@@ -250,6 +257,31 @@ class OraclePartition:
         seo = np.empty(self.skip_in_shape, self.dtype) if self.skip_in_shape else None
         self._check(lib().oracle_backward_microbatch_cut(self._h, mb, _p(e), _p(se), _p(out), _p(seo)), "backward")
         return (out, seo) if seo is not None else out
+
+    def set_bn_momentum(self, momentum):
+        """Training forwards move the running statistics: r <- momentum*r + (1-momentum)*batch (1: never)."""
+        lib().oracle_set_bn_momentum(self._h, float(momentum))
+
+    def bn_running(self):
+        """Running statistics (float64): per BatchNorm in model order mean[c] then variance[c]."""
+        r = np.empty(lib().oracle_n_bn_running(self._h), np.float64)
+        self._check(lib().oracle_bn_running_read(self._h, _p(r), r.size), "bn_running_read")
+        return r
+
+    def set_bn_running(self, r):
+        r = _c(r, np.float64)
+        self._check(lib().oracle_bn_running_write(self._h, _p(r), r.size), "bn_running_write")
+
+    def infer(self, act_in, skip_in=None):
+        """Inference forward (BatchNorm by running statistics): logits [b, classes] with a head, else act_out
+        (or (act_out, skip_out))."""
+        act_in = _c(act_in, self.dtype)
+        assert act_in.shape == self.in_shape
+        out = np.empty((self.spec.microbatch, self.spec.num_classes) if self.spec.has_head else self.out_shape, self.dtype)
+        sk = _c(skip_in, self.dtype) if skip_in is not None else None
+        sko = np.empty(self.skip_out_shape, self.dtype) if self.skip_out_shape else None
+        self._check(lib().oracle_forward_inference(self._h, _p(act_in), _p(sk), _p(out), _p(sko)), "forward_inference")
+        return (out, sko) if sko is not None else out
 
     def grad(self):
         g = np.empty(self.n_params, self.dtype)

@@ -175,13 +175,17 @@ void conv_wgrad(const T* x, const T* dy, double* dw, int n, int h, int wd, int c
 // mode 0: mean = mean(x), var = mean((x-mean)^2) (biased); mode 1: frozen mean 0, var 1.
 // xhat = (x-mean)/sqrt(var+eps); z = gamma*xhat + beta; a = max(z, 0).
 // ------------------------------------------------------------------------------------------
+// given_mean / given_var (both or neither): use these statistics instead (inference with running statistics).
 template <class T>
 void bn_relu_fwd(const T* x, const T* gamma, const T* beta, T* a, double* mean, double* invstd,
-                 size_t M, int C, double eps, int mode, int bf = 0) {
+                 size_t M, int C, double eps, int mode, int bf = 0, const double* given_mean = nullptr,
+                 const double* given_var = nullptr) {
 #pragma omp parallel for schedule(static)
   for (int c = 0; c < C; ++c) {
     double mu = 0.0, var = 1.0;
-    if (mode == 0) {
+    if (given_mean) {
+      mu = given_mean[c]; var = given_var[c];
+    } else if (mode == 0) {
       double s = 0.0;
       for (size_t m = 0; m < M; ++m) s += (double)x[m * C + c];
       mu = s / (double)M;
@@ -300,7 +304,7 @@ struct Desc {
 };
 
 struct ConvP { size_t w; int cin, cout, R, st; };
-struct BnP { size_t g, b; int c; };
+struct BnP { size_t g, b; int c; size_t run = 0; /* running mean at run, running variance at run + c */ };
 struct BlockP {
   BlockDesc d; int h_in, w_in, h_out, w_out; bool proj;
   BnP bn[3]; ConvP cv[3]; ConvP pj; int nconv;
@@ -334,7 +338,14 @@ struct Partition {
   int out_h, out_w, out_c, c0;
   std::vector<MbStash<T>> st;
   int n_bwd_done = 0;
+  // Running statistics of every BatchNorm held here, in model order: mean[c] then variance[c]; start at 0 / 1.
+  // A training forward with momentum < 1 moves them towards the statistics of its micro-batch (biased variance):
+  // r <- bn_momentum*r + (1-bn_momentum)*batch.  The paper trains Keras models; it says nothing about these buffers
+  // beyond using the framework's layers, so this is the framework's moving-average rule.
+  std::vector<double> running;
+  double bn_momentum = 1.0;   // 1: never updated
 
+  size_t n_running = 0;
   size_t plan() {
     size_t off = 0;
     int h = d.in_h, w = d.in_w, c = d.in_c;
@@ -349,7 +360,7 @@ struct Partition {
       if (p.j0 == 0) { p.h_in = h; p.w_in = w; p.h_out = h / b.stride; p.w_out = w / b.stride; }
       else { p.h_in = h * b.stride; p.w_in = w * b.stride; p.h_out = h; p.w_out = w; }   // the input is already at the block's output size
       p.proj = (b.stride != 1 || b.c_in != b.c_out);
-      auto bn = [&](int ch) { BnP r{off, off + (size_t)ch, ch}; off += 2 * (size_t)ch; return r; };
+      auto bn = [&](int ch) { BnP r{off, off + (size_t)ch, ch, n_running}; off += 2 * (size_t)ch; n_running += 2 * (size_t)ch; return r; };
       auto cv = [&](int ci, int co, int R, int s) { ConvP r{off, ci, co, R, s}; off += (size_t)R * R * ci * co; return r; };
       const int cin[3] = {b.c_in, b.c_mid, b.c_mid};
       const int cout[3] = {b.c_mid, b.kind == 0 ? b.c_out : b.c_mid, b.c_out};
@@ -368,7 +379,7 @@ struct Partition {
     }
     out_h = h; out_w = w; out_c = c;
     if (d.has_head) {
-      head_bn = BnP{off, off + (size_t)c, c}; off += 2 * (size_t)c;
+      head_bn = BnP{off, off + (size_t)c, c, n_running}; off += 2 * (size_t)c; n_running += 2 * (size_t)c;
       wfc = off; off += (size_t)c * d.num_classes;
       bfc = off; off += d.num_classes;
     }
@@ -381,6 +392,19 @@ struct Partition {
     momentum.assign(P, (T)0);
     grad.assign(P, 0.0);
     st.resize(d.num_microbatches);
+    running.assign(n_running, 0.0);
+    auto init = [&](const BnP& b) { for (int c = 0; c < b.c; ++c) running[b.run + b.c + c] = 1.0; };
+    for (auto& p : bp) for (int j = p.j0; j < p.j1; ++j) init(p.bn[j]);
+    if (d.has_head) init(head_bn);
+  }
+
+  void update_running(const BnP& b, const double* mean, const double* invstd) {
+    if (!(bn_momentum < 1.0) || d.bn_mode != 0) return;
+    for (int c = 0; c < b.c; ++c) {
+      const double var = 1.0 / (invstd[c] * invstd[c]) - d.bn_eps;
+      running[b.run + c] = bn_momentum * running[b.run + c] + (1.0 - bn_momentum) * mean[c];
+      running[b.run + b.c + c] = bn_momentum * running[b.run + b.c + c] + (1.0 - bn_momentum) * var;
+    }
   }
 
   // skip_in / skip_out: shortcut value of a first block that starts, or a last block that ends, inside the block
@@ -388,6 +412,20 @@ struct Partition {
     if (mb < 0 || mb >= d.num_microbatches) return E_INVAL;
     MbStash<T>& S = st[mb];
     if (S.fwd_done) return E_STATE;
+    const int rc = forward_impl(S, false, act_in, skip_in, labels, act_out, skip_out, loss_accum);
+    if (rc == OK) S.fwd_done = true;
+    return rc;
+  }
+
+  // Inference: the same layers with every BatchNorm normalising by its running statistics; nothing is kept for
+  // a backward pass.  `out`: logits [microbatch, classes] if the partition holds the head, else act_out.
+  int infer(const T* act_in, const T* skip_in, T* out, T* skip_out) {
+    MbStash<T> S;
+    return forward_impl(S, true, act_in, skip_in, nullptr, out, skip_out, nullptr);
+  }
+
+  int forward_impl(MbStash<T>& S, bool inference, const T* act_in, const T* skip_in, const int32_t* labels, T* act_out,
+                   T* skip_out, double* loss_accum) {
     const int b = d.microbatch, bf = d.storage;
     const T* P = params.data();
     std::vector<T> x;
@@ -407,8 +445,11 @@ struct Partition {
       auto bnrelu = [&](int j, std::vector<T>& in) {
         B.bn[j].x = in; B.bn[j].mean.resize(p.bn[j].c); B.bn[j].invstd.resize(p.bn[j].c);
         B.a[j].resize(in.size());
+        const double* rm = inference ? running.data() + p.bn[j].run : nullptr;
         bn_relu_fwd(in.data(), P + p.bn[j].g, P + p.bn[j].b, B.a[j].data(), B.bn[j].mean.data(),
-                    B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode, bf);
+                    B.bn[j].invstd.data(), in.size() / p.bn[j].c, p.bn[j].c, d.bn_eps, d.bn_mode, bf, rm,
+                    rm ? rm + p.bn[j].c : nullptr);
+        if (!inference) update_running(p.bn[j], B.bn[j].mean.data(), B.bn[j].invstd.data());
       };
       std::vector<T> sc;                                   // shortcut: x, or the 1x1 projection of a
       std::vector<T> r;
@@ -448,16 +489,33 @@ struct Partition {
       const int C = out_c, hw = out_h * out_w;
       S.head_bn.x = x; S.head_bn.mean.resize(C); S.head_bn.invstd.resize(C);
       S.head_a.resize(x.size());
+      const double* rm = inference ? running.data() + head_bn.run : nullptr;
       bn_relu_fwd(x.data(), P + head_bn.g, P + head_bn.b, S.head_a.data(), S.head_bn.mean.data(),
-                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode, bf);
+                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode, bf, rm, rm ? rm + C : nullptr);
+      if (!inference) update_running(head_bn, S.head_bn.mean.data(), S.head_bn.invstd.data());
       S.g.resize((size_t)b * C); S.dlogits.resize((size_t)b * d.num_classes);
+      if (inference) {   // logits = mean_{h,w}(a) * Wfc + bfc
+        if (!act_out) return E_INVAL;
+        for (int n = 0; n < b; ++n)
+          for (int j = 0; j < d.num_classes; ++j) {
+            double sum = (double)P[bfc + j];
+            for (int c = 0; c < C; ++c) {
+              double g = 0.0;
+              for (int i = 0; i < hw; ++i) g += (double)S.head_a[((size_t)n * hw + i) * C + c];
+              sum += (double)(T)(g / (double)hw) * (double)P[wfc + (size_t)c * d.num_classes + j];
+            }
+            act_out[(size_t)n * d.num_classes + j] = (T)sum;
+          }
+        return OK;
+      }
+      if (!labels) return E_INVAL;
       const double l = head_fwd(S.head_a.data(), P + wfc, P + bfc, labels, S.g.data(), S.dlogits.data(),
                                 b, hw, C, d.num_classes, (double)d.loss_divisor);
       if (loss_accum) *loss_accum += l;
     } else {
+      if (!act_out) return E_INVAL;
       std::memcpy(act_out, x.data(), x.size() * sizeof(T));
     }
-    S.fwd_done = true;
     return OK;
   }
 
@@ -651,6 +709,40 @@ int oracle_backward_microbatch_cut(void* hp, int mb, const void* err_in, const v
 
 int oracle_backward_microbatch(void* hp, int mb, const void* err_in, void* err_out) {
   return oracle_backward_microbatch_cut(hp, mb, err_in, nullptr, err_out, nullptr);
+}
+
+// out: logits [microbatch, classes] with a head, else act_out; BatchNorm uses the running statistics
+int oracle_forward_inference(void* hp, const void* act_in, const void* skip_in, void* out, void* skip_out) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->infer((const double*)act_in, (const double*)skip_in, (double*)out, (double*)skip_out)
+                : h->pf->infer((const float*)act_in, (const float*)skip_in, (float*)out, (float*)skip_out);
+}
+
+void oracle_set_bn_momentum(void* hp, double momentum) {
+  Handle* h = (Handle*)hp;
+  if (h->f64) h->pd->bn_momentum = momentum; else h->pf->bn_momentum = momentum;
+}
+
+size_t oracle_n_bn_running(void* hp) {
+  Handle* h = (Handle*)hp;
+  return h->f64 ? h->pd->running.size() : h->pf->running.size();
+}
+
+// running statistics as doubles: per BatchNorm in model order mean[c] then variance[c]
+int oracle_bn_running_read(void* hp, double* dst, size_t n) {
+  Handle* h = (Handle*)hp;
+  const std::vector<double>& r = h->f64 ? h->pd->running : h->pf->running;
+  if (n != r.size()) return E_INVAL;
+  std::memcpy(dst, r.data(), n * sizeof(double));
+  return OK;
+}
+
+int oracle_bn_running_write(void* hp, const double* src, size_t n) {
+  Handle* h = (Handle*)hp;
+  std::vector<double>& r = h->f64 ? h->pd->running : h->pf->running;
+  if (n != r.size()) return E_INVAL;
+  std::memcpy(r.data(), src, n * sizeof(double));
+  return OK;
 }
 
 int oracle_grad_accum_read(void* hp, void* dst, size_t n) {
