@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--cuts", choices=["blocks", "layers"], default="blocks",
                     help="with --pipeline: cut at residual-block boundaries, or evenly over the convolution layers "
                          "(cuts inside blocks; shortcut values cross partitions)")
+    ap.add_argument("--inference", action="store_true",
+                    help="instead of training steps: inference forwards (BatchNorm by running statistics) of the "
+                         "configuration's micro-batches, one call each")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -191,6 +194,28 @@ def main():
         # the last step's backward work sits on the micro-batch streams: join them
         part.grad_accum_read(out=gbuf, stream=main_stream) if sgd is None else None
         torch.cuda.synchronize()
+
+    if args.inference:
+        xs = act_in
+        skips = None
+        for _ in range(args.warmup):
+            for x in xs:
+                part.forward_inference(x, stream=main_stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            for x in xs:
+                part.forward_inference(x, stream=main_stream)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        part.close()
+        print(json.dumps({
+            "metric": "images/sec through partition inference forward at 1 MI355X", "value": spec.batch * args.steps / elapsed,
+            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"config {args.config}: {spec.name}, inference forward of {m} micro-batches of "
+                                   f"{spec.microbatch} images, one call each"}}))
+        return
 
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)

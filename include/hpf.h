@@ -108,6 +108,7 @@ typedef struct {
   size_t act_out_elems;  /* elements per micro-batch of act_out / err_in (0 if has_head) */
   size_t skip_in_elems;  /* elements per micro-batch of skip_in / skip_err_out (0: none) */
   size_t skip_out_elems; /* elements per micro-batch of skip_out / skip_err_in (0: none) */
+  size_t n_bn_running;   /* floats of BatchNorm running statistics (hpf_bn_running_read / _write) */
 } hpf_sizes;
 
 /* Validates the description and reports sizes.  No device work. */
@@ -207,6 +208,30 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *      next hpf_grad_accum_read to host memory or hpf_params_read returns HPF_EDEVICE.
  * Not allowed while a micro-batch is between forward and backward (HPF_ESTATE). */
 hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
+
+/* BatchNorm running statistics and inference.  The paper trains the framework's layers and reports test
+ * accuracy (Section "Verifying the Correctness of HyPar-Flow"); evaluating a trained partition needs the
+ * inference form of BatchNorm, i.e. moving averages of the micro-batch statistics.  Every BatchNorm of the
+ * partition keeps a running mean (start 0) and a running variance (start 1) in the arena.
+ *
+ * hpf_partition_set_bn_momentum: with momentum m < 1 every training forward moves them,
+ *   r <- m*r + (1-m)*(mean | biased variance of the micro-batch), once per micro-batch, in micro-batch order
+ *   within a group call and in stream order between calls -- forwards of one batch issued on several streams
+ *   at once would race on these buffers, so issue them on one stream (or as group calls) when m < 1.
+ *   m = 1 (the default) never touches them; bn_mode 1 neither.  [0, 1] else HPF_EINVAL; HPF_ESTATE while a
+ *   micro-batch is between forward and backward.
+ * hpf_bn_running_read / _write: (host) n_bn_running floats: per BatchNorm in model order mean[C], variance[C].
+ *   Synchronise the device.  Variances must be >= 0.
+ * hpf_forward_inference: the partition's layers on one micro-batch with every BatchNorm normalising by its
+ *   running statistics; nothing is kept for a backward pass, no state of the batch in progress changes.
+ *   act_in / skip_in / skip_out as in hpf_forward_microbatch_cut; out (dev): act_out, or with has_head the
+ *   logits [microbatch, num_classes] fp32.  Works in the region of micro-batch 0: HPF_ESTATE while any
+ *   micro-batch is between forward and backward. */
+hpf_status hpf_partition_set_bn_momentum(hpf_partition* p, float momentum);
+hpf_status hpf_bn_running_read(hpf_partition* p, float* host_dst, size_t n_floats);
+hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t n_floats);
+hpf_status hpf_forward_inference(hpf_partition* p, const void* act_in, const void* skip_in, void* out, void* skip_out,
+                                 void* hip_stream);
 
 /* Per-kernel-class timing, measured with HIP events on the stream the kernels are launched on.
  * While enabled the passes run as plain launches (no graph replay) with an event pair around every

@@ -191,12 +191,23 @@ hipError_t launch_bn_bwd_apply(int dt, int g, const PtrTab& x, const PtrTab& da,
                                const PtrTab& stats, const PtrTab& sums, const PtrTab& skip, const PtrTab& dx, int M,
                                int C, int frozen, hipStream_t stream);
 hipError_t launch_bn_frozen_stats(int dt, int g, const PtrTab& stats, int C, float eps, hipStream_t stream);
+// Running statistics (fp32): per BatchNorm mean[C] then variance[C] at run_off floats into `running`.
+struct BnRunDesc { unsigned long long stats_off; int C; int run_off; };   // stats_off: bytes into a member's region
+// After a training forward: for the group's members in order, r <- momentum*r + (1-momentum)*{mean, 1/invstd^2 - eps}.
+hipError_t launch_bn_running_update(int dt, int g, const PtrTab& bases, const BnRunDesc* table_dev, int n_bn, float* running,
+                                    float momentum, float eps, hipStream_t stream);
+// Inference: stats = {running mean, 1/sqrt(running variance + eps)}.
+hipError_t launch_bn_running_stats(int dt, int g, const PtrTab& stats, const float* running_mean_var, int C, float eps,
+                                   hipStream_t stream);
 
 // Stem: fp32 image [b,H,W,Cin] -> bf16 im2col columns [b*H*W, Kc], k = (r*3+s)*Cin + c, zero padded.
 hipError_t launch_im2col3x3(int g, const PtrTab& img, const PtrTab& col, int b, int H, int W, int Cin, int Kc,
                             hipStream_t stream);
 
 // Head: a [b,hw,C] (dtype dt) -> g [b,C] fp32, dlogits [b,classes] fp32, loss_accum += sum CE / divisor.
+// Inference head: logits[b, classes] (fp32) = mean_{h,w}(a) * Wfc + bfc.
+hipError_t launch_head_logits(int dt, int g, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& logits, int b,
+                              int hw, int C, int classes, hipStream_t stream);
 hipError_t launch_head_fwd(int dt, int g, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& labels,
                            const PtrTab& gp, const PtrTab& dlogits, float* loss_accum, int b, int hw, int C,
                            int classes, float divisor, hipStream_t stream);

@@ -48,7 +48,7 @@ struct ConvPlan {
   size_t wf_off = 0, wd_off = 0;    // packed bf16 offsets (elements)
   int Kf = 0, Kd = 0;
 };
-struct BnPlan { int C = 0; size_t g_off = 0, b_off = 0; size_t stats_off = 0; /* bytes in mb region */ };
+struct BnPlan { int C = 0; size_t g_off = 0, b_off = 0; size_t stats_off = 0; /* bytes in mb region */ size_t run_off = 0; /* floats: running mean, then variance */ };
 struct BlockPlan {
   hpf_block_desc d{};
   int h_in = 0, w_in = 0, h_out = 0, w_out = 0, nconv = 0;
@@ -91,6 +91,8 @@ struct Plan {
   size_t arena_bytes = 0;
   size_t act_in_elems = 0, act_out_elems = 0;
   size_t skip_in_elems = 0, skip_out_elems = 0;   // shortcut value of a first / last block that is cut (0: none)
+  size_t n_running = 0, running_off = 0, bn_table_off = 0;   // BatchNorm running statistics (fp32) and their table
+  std::vector<BnRunDesc> bn_table;
   std::vector<PackDesc> table;
   // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
   struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
@@ -174,7 +176,11 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     cv.h_out = hi / st; cv.w_out = wi / st; cv.w_off = off; off += (size_t)R * R * ci * co;
     return cv;
   };
-  auto mk_bn = [&](int ch) { BnPlan b; b.C = ch; b.g_off = off; b.b_off = off + ch; off += 2 * (size_t)ch; return b; };
+  auto mk_bn = [&](int ch) {
+    BnPlan b; b.C = ch; b.g_off = off; b.b_off = off + ch; off += 2 * (size_t)ch;
+    b.run_off = P.n_running; P.n_running += 2 * (size_t)ch;
+    return b;
+  };
 
   h = d.in_h; w = d.in_w;
   if (d.has_stem) {
@@ -229,6 +235,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   size_t max_tile_part = 0;   // floats: partial records written by convolution epilogues (64-row tiles)
   auto stats = [&](BnPlan& bn, size_t M) {
     bn.stats_off = alloc(2 * (size_t)bn.C * sizeof(double)).off;
+    P.bn_table.push_back(BnRunDesc{bn.stats_off, bn.C, (int)bn.run_off});
     if (bn.C > max_c) max_c = bn.C;
     const size_t need = ((M + 63) / 64) * (size_t)bn.C * 4;
     if (need > max_tile_part) max_tile_part = need;
@@ -447,6 +454,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
   for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
   P.abort_off = g;  g += align_up(sizeof(int));
+  P.running_off = g; g += align_up(P.n_running * sizeof(float));
+  P.bn_table_off = g; g += align_up(P.bn_table.size() * sizeof(BnRunDesc));
   P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
   P.arena_bytes = g;
   return HPF_OK;
@@ -474,6 +483,7 @@ struct hpf_partition {
   // bottleneck blocks
   int fuse = 2;
   int res_group = 0;   // micro-batches one image-resident launch may hold on this device (0: path unavailable)
+  float bn_momentum = 1.f;   // running statistics: r <- m*r + (1-m)*batch after every training forward; 1: never
   // per-kernel-class timing
   bool profiling = false;
   struct ProfSeg { int cat; hipEvent_t e0, e1; int launches; double bytes, flops; };
@@ -501,6 +511,7 @@ struct hpf_partition {
   bf16_t* packed() const { return (bf16_t*)(arena + P.packed_off); }
   char* mb_base(int mb) const { return arena + P.mb_off + (size_t)mb * P.mb_bytes; }
   int* abort_flag() const { return (int*)(arena + P.abort_off); }
+  float* running() const { return (float*)(arena + P.running_off); }
   bool resident() const { return fuse >= 2 && res_group >= 1 && !P.runs.empty(); }
   int group_limit() const { return resident() ? res_group : MAX_GROUP; }
 };
@@ -514,6 +525,7 @@ struct Ctx {
   const void* act_in[MAX_GROUP]; void* act_out[MAX_GROUP]; const void* err_in[MAX_GROUP]; void* err_out[MAX_GROUP];
   // shortcut value of a cut block: received / sent in forward, its gradient sent back / received in backward
   const void* skip_in[MAX_GROUP] = {}; void* skip_out[MAX_GROUP] = {}; const void* skip_err_in[MAX_GROUP] = {}; void* skip_err_out[MAX_GROUP] = {};
+  bool inference = false;   // BatchNorm by running statistics, nothing kept for a backward pass, logits instead of the loss
   hipError_t err = hipSuccess;
   const char* where = "";
   hpf_partition::ProfSeg cur{PROF_NONE, nullptr, nullptr, 0, 0, 0};
@@ -572,7 +584,9 @@ struct Ctx {
   void bn_fwd(const BnPlan& bn, const PtrTab& x, const PtrTab& a, size_t M, int part_rows = 0, bool apply = true) {
     const Plan& P = h->P;
     const PtrTab st = mbp(bn.stats_off);
-    if (P.d.bn_mode != 0)
+    if (inference)
+      chk(launch_bn_running_stats(P.dt, g, st, h->running() + bn.run_off, bn.C, P.d.bn_eps, s), "bn_running_stats");
+    else if (P.d.bn_mode != 0)
       chk(launch_bn_frozen_stats(P.dt, g, st, bn.C, P.d.bn_eps, s), "bn_frozen_stats");
     else if (part_rows > 0)
       chk(launch_bn_stats_finalize(g, (int)M, bn.C, part_rows, P.d.bn_eps, mbp(P.partials_off), st, s), "bn_stats_finalize");
@@ -623,7 +637,7 @@ struct Ctx {
         pro.gamma = h->params() + pro_bn->g_off; pro.beta = h->params() + pro_bn->b_off;
       }
       int rows = 0;
-      if (want_stats && fused()) {
+      if (want_stats && fused() && !inference) {
         epi.kind = EPI_STATS; epi.partials = mbp(h->P.partials_off);
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
@@ -715,7 +729,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
   int part_rows = 0;   // statistics partial rows pending for the next BatchNorm (written by the last conv)
-  const bool resident = c.h->resident();
+  const bool resident = c.h->resident() && !c.inference;
   c.seg_same(PROF_OTHER_FWD);
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
@@ -780,10 +794,24 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     const size_t M = b * P.out_h * P.out_w;
     c.seg_same(PROF_OTHER_FWD);
     c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M, part_rows);
-    c.chk(launch_head_fwd(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
-                          c.tab(P.head_g), c.tab(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes,
-                          (float)P.d.loss_divisor, c.s),
-          "head_fwd");
+    if (c.inference) {
+      Loc lo; lo.kind = CALLER_ACT_OUT;   // logits
+      c.chk(launch_head_logits(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, c.tab(lo), (int)b,
+                               P.out_h * P.out_w, P.out_c, P.d.num_classes, c.s),
+            "head_logits");
+    } else {
+      c.chk(launch_head_fwd(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, labels,
+                            c.tab(P.head_g), c.tab(P.head_dl), loss_accum, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes,
+                            (float)P.d.loss_divisor, c.s),
+            "head_fwd");
+    }
+  }
+  if (!c.inference && c.h->bn_momentum < 1.f && P.d.bn_mode == 0 && !P.bn_table.empty()) {
+    PtrTab bases{};
+    for (int i = 0; i < c.g; ++i) bases.p[i] = c.h->mb_base(c.mb0 + i);
+    c.chk(launch_bn_running_update(P.dt, c.g, bases, (const BnRunDesc*)(c.h->arena + P.bn_table_off), (int)P.bn_table.size(),
+                                   c.h->running(), c.h->bn_momentum, P.d.bn_eps, c.s),
+          "bn_running_update");
   }
   c.seg_end();
 }
@@ -983,6 +1011,7 @@ hpf_status hpf_partition_sizes(const hpf_partition_desc* desc, hpf_sizes* out) {
   out->act_out_elems = P.act_out_elems;
   out->skip_in_elems = P.skip_in_elems;
   out->skip_out_elems = P.skip_out_elems;
+  out->n_bn_running = P.n_running;
   return HPF_OK;
 }
 
@@ -1023,6 +1052,12 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     if (!P.items_nr[k].empty())
       ok(hipMemcpy(p->arena + P.items_nr_off[k], P.items_nr[k].data(), P.items_nr[k].size() * sizeof(WgradItem), hipMemcpyHostToDevice));
   ok(conv_prepare());
+  if (P.n_running) {
+    std::vector<float> r0(P.n_running, 0.f);
+    for (const BnRunDesc& d : P.bn_table) for (int c = 0; c < d.C; ++c) r0[(size_t)d.run_off + d.C + c] = 1.f;
+    ok(hipMemcpy(p->running(), r0.data(), P.n_running * sizeof(float), hipMemcpyHostToDevice));
+    ok(hipMemcpy(p->arena + P.bn_table_off, P.bn_table.data(), P.bn_table.size() * sizeof(BnRunDesc), hipMemcpyHostToDevice));
+  }
   if (!P.items[WGRAD_CLASSES - 1].empty()) ok(wgrad_prepare());
   if (!P.runs.empty()) {
     ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
@@ -1292,6 +1327,63 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
     for (GraphSlot& g : p->g_bwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
   }
   p->fuse = enable;
+  return HPF_OK;
+}
+
+hpf_status hpf_partition_set_bn_momentum(hpf_partition* p, float momentum) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (!(momentum >= 0.f && momentum <= 1.f)) return fail(HPF_EINVAL, "momentum %g outside [0, 1]", (double)momentum);
+  for (int i = 0; i < p->P.d.num_microbatches; ++i)
+    if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
+  if (p->bn_momentum != momentum) {   // cached graphs hold the other kernel sequence / the old factor
+    for (GraphSlot& g : p->g_fwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
+  }
+  p->bn_momentum = momentum;
+  return HPF_OK;
+}
+
+hpf_status hpf_bn_running_read(hpf_partition* p, float* host_dst, size_t n_floats) {
+  if (!p || (!host_dst && n_floats)) return fail(HPF_EINVAL, "null argument");
+  if (n_floats != p->P.n_running) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_running);
+  if (hipDeviceSynchronize() != hipSuccess) return fail(HPF_EDEVICE, "synchronize failed");
+  if (n_floats && hipMemcpy(host_dst, p->running(), n_floats * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(HPF_EDEVICE, "device-to-host copy failed");
+  return check_abort_flag(p);
+}
+
+hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t n_floats) {
+  if (!p || (!host_src && n_floats)) return fail(HPF_EINVAL, "null argument");
+  if (n_floats != p->P.n_running) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_running);
+  for (const BnRunDesc& d : p->P.bn_table)
+    for (int c = 0; c < d.C; ++c)
+      if (!(host_src[(size_t)d.run_off + d.C + c] >= 0.f)) return fail(HPF_EINVAL, "negative running variance");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(HPF_EDEVICE, "synchronize failed");
+  if (n_floats && hipMemcpy(p->running(), host_src, n_floats * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+    return fail(HPF_EDEVICE, "host-to-device copy failed");
+  return HPF_OK;
+}
+
+hpf_status hpf_forward_inference(hpf_partition* p, const void* act_in, const void* skip_in, void* out, void* skip_out,
+                                 void* hip_stream) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  const Plan& P = p->P;
+  if (!act_in || !out) return fail(HPF_EINVAL, "act_in and out are required");
+  if ((P.skip_in_elems != 0) != (skip_in != nullptr)) return fail(HPF_EINVAL, "skip_in is required exactly when the first block starts after its first convolution");
+  if ((P.skip_out_elems != 0) != (skip_out != nullptr)) return fail(HPF_EINVAL, "skip_out is required exactly when the last block ends in a later partition");
+  for (int i = 0; i < P.d.num_microbatches; ++i)   // the pass works in the region of micro-batch 0
+    if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  const hpf_status st = wait_all_backward(p, s);
+  if (st != HPF_OK) return st;
+  Ctx c{p, 0, 1, s};
+  c.inference = true;
+  c.act_in[0] = act_in; c.act_out[0] = out; c.err_in[0] = nullptr; c.err_out[0] = nullptr;
+  c.skip_in[0] = skip_in; c.skip_out[0] = skip_out;
+  run_forward(c, PtrTab{}, nullptr);
+  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
+  if (hipEventRecord(p->ev_step, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");   // later forwards reuse the region
+  p->step_recorded = true;
   return HPF_OK;
 }
 

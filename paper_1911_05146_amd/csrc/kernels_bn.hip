@@ -335,6 +335,33 @@ __global__ void k_bn_frozen_stats(PtrTab statss, int C, float eps) {
   if (c < C) { stats[c] = 0; stats[C + c] = rsqrt_exact((A)1 + (A)eps); }
 }
 
+// One block per BatchNorm; a thread walks its channels and, per channel, the group's members in order.
+template <class A>
+__global__ __launch_bounds__(256) void k_bn_running_update(PtrTab bases, const BnRunDesc* __restrict__ table, float* running, int ng,
+                                                           float momentum, float eps) {
+  const BnRunDesc d = table[blockIdx.x];
+  float* rm = running + d.run_off;
+  float* rv = rm + d.C;
+  for (int c = threadIdx.x; c < d.C; c += blockDim.x) {
+    A m = (A)rm[c], v = (A)rv[c];
+    for (int i = 0; i < ng; ++i) {
+      const A* st = (const A*)((const char*)pick(bases, i) + d.stats_off);
+      const A is = st[d.C + c];
+      const A var = (A)1 / (is * is) - (A)eps;
+      m = (A)momentum * m + ((A)1 - (A)momentum) * st[c];
+      v = (A)momentum * v + ((A)1 - (A)momentum) * var;
+    }
+    rm[c] = (float)m; rv[c] = (float)v;
+  }
+}
+
+template <class A>
+__global__ void k_bn_running_stats(PtrTab statss, const float* __restrict__ running, int C, float eps) {
+  A* stats = (A*)pick(statss, blockIdx.z);
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < C) { stats[c] = (A)running[c]; stats[C + c] = rsqrt_exact((A)running[C + c] + (A)eps); }
+}
+
 struct BnGrid { dim3 grid; int rows_per_block; };
 
 BnGrid reduce_grid(int M, int C) {
@@ -430,6 +457,22 @@ hipError_t launch_bn_frozen_stats(int dt, int ng, const PtrTab& stats, int C, fl
   const dim3 grid((unsigned)((C + 255) / 256), 1, (unsigned)ng);
   if (dt == DT_BF16) k_bn_frozen_stats<float><<<grid, 256, 0, stream>>>(stats, C, eps);
   else k_bn_frozen_stats<double><<<grid, 256, 0, stream>>>(stats, C, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_running_update(int dt, int ng, const PtrTab& bases, const BnRunDesc* table_dev, int n_bn, float* running,
+                                    float momentum, float eps, hipStream_t stream) {
+  if (n_bn <= 0) return hipSuccess;
+  if (dt == DT_BF16) k_bn_running_update<float><<<n_bn, 256, 0, stream>>>(bases, table_dev, running, ng, momentum, eps);
+  else k_bn_running_update<double><<<n_bn, 256, 0, stream>>>(bases, table_dev, running, ng, momentum, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_running_stats(int dt, int ng, const PtrTab& stats, const float* running_mean_var, int C, float eps,
+                                   hipStream_t stream) {
+  const dim3 grid((unsigned)((C + 255) / 256), 1, (unsigned)ng);
+  if (dt == DT_BF16) k_bn_running_stats<float><<<grid, 256, 0, stream>>>(stats, running_mean_var, C, eps);
+  else k_bn_running_stats<double><<<grid, 256, 0, stream>>>(stats, running_mean_var, C, eps);
   return hipGetLastError();
 }
 

@@ -88,6 +88,30 @@ __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __rest
   if (threadIdx.x == 0) atomicAdd(loss_accum, -(lg[y] - mx - logf(den)) * inv_div);
 }
 
+// Inference head, one block per sample: logits = mean_{h,w}(a) * Wfc + bfc.
+template <class T>
+__global__ __launch_bounds__(256) void k_head_logits(PtrTab as, const float* __restrict__ wfc, const float* __restrict__ bfc,
+                                                     PtrTab outs, int hw, int C, int classes) {
+  const T* __restrict__ a = (const T*)pick(as, blockIdx.z);
+  float* __restrict__ out = (float*)pick(outs, blockIdx.z);
+  extern __shared__ float dyn[];
+  float* gs = dyn;
+  const int n = blockIdx.x;
+  const T* an = a + (size_t)n * hw * C;
+  const float inv_hw = 1.0f / (float)hw;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int i = 0; i < hw; ++i) s += to_f32(an[(size_t)i * C + c]);
+    gs[c] = s * inv_hw;
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    float s = bfc[j];
+    for (int c = 0; c < C; ++c) s = fmaf(gs[c], wfc[(size_t)c * classes + j], s);
+    out[(size_t)n * classes + j] = s;
+  }
+}
+
 // One block per sample: dWfc += g^T dlogits, dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw.
 template <class T>
 __global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const float* __restrict__ wfc, float* g_wfc,
@@ -191,6 +215,15 @@ hipError_t launch_head_fwd(int dt, int ng, const PtrTab& a, const float* wfc, co
     k_head_fwd<bf16_t><<<grid, 256, lds, stream>>>(a, wfc, bfc, labels, gp, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
   else
     k_head_fwd<float><<<grid, 256, lds, stream>>>(a, wfc, bfc, labels, gp, dlogits, loss_accum, hw, C, classes, 1.0f / divisor);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_logits(int dt, int ng, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& logits, int b,
+                              int hw, int C, int classes, hipStream_t stream) {
+  const size_t lds = (size_t)C * sizeof(float);
+  const dim3 grid((unsigned)b, 1, (unsigned)ng);
+  if (dt == DT_BF16) k_head_logits<bf16_t><<<grid, 256, lds, stream>>>(a, wfc, bfc, logits, hw, C, classes);
+  else k_head_logits<float><<<grid, 256, lds, stream>>>(a, wfc, bfc, logits, hw, C, classes);
   return hipGetLastError();
 }
 

@@ -39,7 +39,7 @@ class hpf_partition_desc(C.Structure):
 class hpf_sizes(C.Structure):
     _fields_ = [("n_params", C.c_size_t), ("arena_bytes", C.c_size_t), ("stash_bytes", C.c_size_t),
                 ("act_in_elems", C.c_size_t), ("act_out_elems", C.c_size_t),
-                ("skip_in_elems", C.c_size_t), ("skip_out_elems", C.c_size_t)]
+                ("skip_in_elems", C.c_size_t), ("skip_out_elems", C.c_size_t), ("n_bn_running", C.c_size_t)]
 
 
 class HpfError(RuntimeError):
@@ -77,6 +77,10 @@ def _load():
     L.hpf_partition_destroy.restype = None
     L.hpf_partition_set_graphs.argtypes = [vp, i32]
     L.hpf_partition_set_fusion.argtypes = [vp, i32]
+    L.hpf_partition_set_bn_momentum.argtypes = [vp, C.c_float]
+    L.hpf_bn_running_read.argtypes = [vp, vp, sz]
+    L.hpf_bn_running_write.argtypes = [vp, vp, sz]
+    L.hpf_forward_inference.argtypes = [vp, vp, vp, vp, vp, vp]
     L.hpf_partition_set_profiling.argtypes = [vp, i32]
     L.hpf_partition_profile_read.argtypes = [vp, vp, i32, vp]
     L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
@@ -96,7 +100,8 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_forward_microbatches", "hpf_backward_microbatches",
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
            "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_partition_set_fusion",
-           "hpf_partition_set_profiling", "hpf_partition_profile_read",
+           "hpf_partition_set_profiling", "hpf_partition_profile_read", "hpf_partition_set_bn_momentum",
+           "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
 
@@ -197,6 +202,22 @@ def hpf_partition_set_graphs(handle, enable):
 
 def hpf_partition_set_fusion(handle, level):
     _check(lib.hpf_partition_set_fusion(handle, int(level)))
+
+
+def hpf_partition_set_bn_momentum(handle, momentum):
+    _check(lib.hpf_partition_set_bn_momentum(handle, float(momentum)))
+
+
+def hpf_bn_running_read(handle, host_dst, n_floats):
+    _check(lib.hpf_bn_running_read(handle, host_dst, n_floats))
+
+
+def hpf_bn_running_write(handle, host_src, n_floats):
+    _check(lib.hpf_bn_running_write(handle, host_src, n_floats))
+
+
+def hpf_forward_inference(handle, act_in, skip_in, out, skip_out, stream=0):
+    _check(lib.hpf_forward_inference(handle, act_in, skip_in or None, out, skip_out or None, stream or None))
 
 
 class hpf_profile_entry(C.Structure):
@@ -495,6 +516,35 @@ class Partition:
 
     def set_profiling(self, enable):
         hpf_partition_set_profiling(self.handle, enable)
+
+    def set_bn_momentum(self, momentum):
+        hpf_partition_set_bn_momentum(self.handle, momentum)
+
+    def bn_running_read(self):
+        import numpy as np
+        r = np.empty(int(self.sizes.n_bn_running), np.float32)
+        hpf_bn_running_read(self.handle, r.ctypes.data, r.size)
+        return r
+
+    def bn_running_write(self, r):
+        import numpy as np
+        r = np.ascontiguousarray(r, np.float32)
+        hpf_bn_running_write(self.handle, r.ctypes.data, r.size)
+
+    def forward_inference(self, act_in, skip_in=None, stream=None):
+        """Inference forward: logits [b, classes] fp32 with a head, else act_out (or (act_out, skip_out))."""
+        torch = self.torch
+        assert tuple(act_in.shape) == self.in_shape and act_in.dtype == self.in_dtype and act_in.is_contiguous()
+        if self.spec.has_head:
+            out = torch.empty((self.spec.microbatch, self.spec.num_classes), dtype=torch.float32, device=self.device)
+        else:
+            out = torch.empty(self.out_shape, dtype=self.tdtype, device=self.device)
+        skip_out = torch.empty(self.skip_out_shape, dtype=self.tdtype, device=self.device) if self.skip_out_shape else None
+        if self.skip_in_shape:
+            assert self._skip_ok(skip_in, self.skip_in_shape)
+        hpf_forward_inference(self.handle, act_in.data_ptr(), skip_in.data_ptr() if skip_in is not None else 0, out.data_ptr(),
+                              skip_out.data_ptr() if skip_out is not None else 0, self._stream_or_current(stream))
+        return (out, skip_out) if skip_out is not None else out
 
     def profile_read(self):
         """[{name, launches, total_ms, bytes_per_launch, flops_per_launch}] since profiling was enabled."""
