@@ -198,14 +198,23 @@ def main():
     if args.inference:
         xs = act_in
         skips = None
+        oshape = (spec.microbatch, spec.num_classes) if spec.has_head else part.out_shape
+        outs = [torch.empty(oshape, dtype=torch.float32 if spec.has_head else tdt, device=dev) for _ in xs]
+
+        def infer_all():
+            if args.schedule == "grouped":
+                for i in range(0, len(xs), 8):
+                    part.forward_inference_group(xs[i:i + 8], stream=main_stream, out=outs[i:i + 8])
+            else:
+                for x, o in zip(xs, outs):
+                    part.forward_inference(x, stream=main_stream, out=o)
+
         for _ in range(args.warmup):
-            for x in xs:
-                part.forward_inference(x, stream=main_stream)
+            infer_all()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            for x in xs:
-                part.forward_inference(x, stream=main_stream)
+            infer_all()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         part.close()
@@ -214,7 +223,7 @@ def main():
             "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": f"config {args.config}: {spec.name}, inference forward of {m} micro-batches of "
-                                   f"{spec.microbatch} images, one call each"}}))
+                                   f"{spec.microbatch} images, " + ("one group call" if args.schedule == "grouped" else "one call each")}}))
         return
 
     if args.calib_copy_mb > 0:

@@ -226,12 +226,18 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
  *   running statistics; nothing is kept for a backward pass, no state of the batch in progress changes.
  *   act_in / skip_in / skip_out as in hpf_forward_microbatch_cut; out (dev): act_out, or with has_head the
  *   logits [microbatch, num_classes] fp32.  Works in the region of micro-batch 0: HPF_ESTATE while any
- *   micro-batch is between forward and backward. */
+ *   micro-batch is between forward and backward.
+ * hpf_forward_inference_group: the same for `count` micro-batches (1 .. min(num_microbatches, 8)) in one call,
+ *   every layer launched once for all of them; arguments are (host) arrays of `count` (dev) pointers, the skip
+ *   arrays NULL exactly when the single-call arguments would be. */
 hpf_status hpf_partition_set_bn_momentum(hpf_partition* p, float momentum);
 hpf_status hpf_bn_running_read(hpf_partition* p, float* host_dst, size_t n_floats);
 hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t n_floats);
 hpf_status hpf_forward_inference(hpf_partition* p, const void* act_in, const void* skip_in, void* out, void* skip_out,
                                  void* hip_stream);
+hpf_status hpf_forward_inference_group(hpf_partition* p, int32_t count, const void* const* act_in,
+                                       const void* const* skip_in, void* const* out, void* const* skip_out,
+                                       void* hip_stream);
 
 /* Per-kernel-class timing, measured with HIP events on the stream the kernels are launched on.
  * While enabled the passes run as plain launches (no graph replay) with an event pair around every

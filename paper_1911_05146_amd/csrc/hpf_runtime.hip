@@ -497,6 +497,8 @@ struct hpf_partition {
     return hipEventCreate(&e) == hipSuccess ? e : nullptr;
   }
   std::vector<GraphSlot> g_fwd, g_bwd;
+  GraphSlot g_inf[8];   // inference forward: graphs of the last 8 distinct argument sets
+  int g_inf_next = 0;
   char* arena = nullptr;
   std::vector<unsigned char> fwd_done, bwd_done;
   std::vector<const void*> act_in;
@@ -1095,6 +1097,7 @@ void hpf_partition_destroy(hpf_partition* p) {
   for (hipEvent_t ev : p->ev_pool) (void)hipEventDestroy(ev);
   for (GraphSlot& g : p->g_fwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   for (GraphSlot& g : p->g_bwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  for (GraphSlot& g : p->g_inf) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete p;
 }
 
@@ -1325,6 +1328,7 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t enable) {
   if (p->fuse != enable) {   // cached graphs hold the other kernel sequence
     for (GraphSlot& g : p->g_fwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
     for (GraphSlot& g : p->g_bwd) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
+    for (GraphSlot& g : p->g_inf) { if (g.exec) (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; g.direct = false; g.key.clear(); }
   }
   p->fuse = enable;
   return HPF_OK;
@@ -1363,28 +1367,47 @@ hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t 
   return HPF_OK;
 }
 
-hpf_status hpf_forward_inference(hpf_partition* p, const void* act_in, const void* skip_in, void* out, void* skip_out,
-                                 void* hip_stream) {
+hpf_status hpf_forward_inference_group(hpf_partition* p, int32_t count, const void* const* act_in, const void* const* skip_in,
+                                       void* const* out, void* const* skip_out, void* hip_stream) {
   if (!p) return fail(HPF_EINVAL, "null handle");
   const Plan& P = p->P;
+  const int cmax = P.d.num_microbatches < MAX_GROUP ? P.d.num_microbatches : MAX_GROUP;
+  if (count < 1 || count > cmax) return fail(HPF_EINVAL, "count %d outside [1, %d]", count, cmax);
   if (!act_in || !out) return fail(HPF_EINVAL, "act_in and out are required");
   if ((P.skip_in_elems != 0) != (skip_in != nullptr)) return fail(HPF_EINVAL, "skip_in is required exactly when the first block starts after its first convolution");
   if ((P.skip_out_elems != 0) != (skip_out != nullptr)) return fail(HPF_EINVAL, "skip_out is required exactly when the last block ends in a later partition");
-  for (int i = 0; i < P.d.num_microbatches; ++i)   // the pass works in the region of micro-batch 0
+  for (int i = 0; i < count; ++i)
+    if (!act_in[i] || !out[i] || (skip_in && !skip_in[i]) || (skip_out && !skip_out[i])) return fail(HPF_EINVAL, "null tensor for member %d", i);
+  for (int i = 0; i < P.d.num_microbatches; ++i)   // the pass works in the regions of micro-batches 0 .. count-1
     if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
   hipStream_t s = (hipStream_t)hip_stream;
   if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  const hpf_status st = wait_all_backward(p, s);
+  hpf_status st = wait_all_backward(p, s);
   if (st != HPF_OK) return st;
-  Ctx c{p, 0, 1, s};
+  Ctx c{p, 0, count, s};
   c.inference = true;
-  c.act_in[0] = act_in; c.act_out[0] = out; c.err_in[0] = nullptr; c.err_out[0] = nullptr;
-  c.skip_in[0] = skip_in; c.skip_out[0] = skip_out;
-  run_forward(c, PtrTab{}, nullptr);
-  if (c.err != hipSuccess) return fail(HPF_EDEVICE, "%s: %s", c.where, hipGetErrorString(c.err));
-  if (hipEventRecord(p->ev_step, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");   // later forwards reuse the region
+  std::vector<const void*> key;
+  key.push_back((const void*)(intptr_t)count);
+  for (int i = 0; i < count; ++i) {
+    c.act_in[i] = act_in[i]; c.act_out[i] = out[i]; c.err_in[i] = nullptr; c.err_out[i] = nullptr;
+    c.skip_in[i] = skip_in ? skip_in[i] : nullptr; c.skip_out[i] = skip_out ? skip_out[i] : nullptr;
+    key.push_back(c.act_in[i]); key.push_back(c.act_out[i]); key.push_back(c.skip_in[i]); key.push_back(c.skip_out[i]);
+  }
+  GraphSlot* slot = nullptr;
+  for (GraphSlot& g : p->g_inf) if (g.key == key) slot = &g;
+  if (!slot) { slot = &p->g_inf[p->g_inf_next]; p->g_inf_next = (p->g_inf_next + 1) % 8; }
+  st = run_graphed(p, *slot, key, s, c, [&] { run_forward(c, PtrTab{}, nullptr); });
+  if (st != HPF_OK) return st;
+  if (hipEventRecord(p->ev_step, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");   // later forwards reuse the regions
   p->step_recorded = true;
   return HPF_OK;
+}
+
+hpf_status hpf_forward_inference(hpf_partition* p, const void* act_in, const void* skip_in, void* out, void* skip_out,
+                                 void* hip_stream) {
+  if (p && (p->P.skip_in_elems != 0) != (skip_in != nullptr)) return fail(HPF_EINVAL, "skip_in is required exactly when the first block starts after its first convolution");
+  if (p && (p->P.skip_out_elems != 0) != (skip_out != nullptr)) return fail(HPF_EINVAL, "skip_out is required exactly when the last block ends in a later partition");
+  return hpf_forward_inference_group(p, 1, &act_in, skip_in ? &skip_in : nullptr, &out, skip_out ? &skip_out : nullptr, hip_stream);
 }
 
 hpf_status hpf_partition_set_profiling(hpf_partition* p, int32_t enable) {

@@ -81,6 +81,7 @@ def _load():
     L.hpf_bn_running_read.argtypes = [vp, vp, sz]
     L.hpf_bn_running_write.argtypes = [vp, vp, sz]
     L.hpf_forward_inference.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.hpf_forward_inference_group.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.hpf_partition_set_profiling.argtypes = [vp, i32]
     L.hpf_partition_profile_read.argtypes = [vp, vp, i32, vp]
     L.hpf_op_workspace_bytes.argtypes = [i32, i32, i32]
@@ -101,7 +102,7 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_grad_accum_read", "hpf_grad_accum_zero", "hpf_sgd_step", "hpf_params_read",
            "hpf_partition_destroy", "hpf_partition_set_graphs", "hpf_partition_set_fusion",
            "hpf_partition_set_profiling", "hpf_partition_profile_read", "hpf_partition_set_bn_momentum",
-           "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference",
+           "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference", "hpf_forward_inference_group",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
 
@@ -214,6 +215,12 @@ def hpf_bn_running_read(handle, host_dst, n_floats):
 
 def hpf_bn_running_write(handle, host_src, n_floats):
     _check(lib.hpf_bn_running_write(handle, host_src, n_floats))
+
+
+def hpf_forward_inference_group(handle, act_in, skip_in, out, skip_out, stream=0):
+    """Lists of device addresses (skip lists may be None)."""
+    _check(lib.hpf_forward_inference_group(handle, len(act_in), _ptr_array(act_in), _ptr_array(skip_in), _ptr_array(out),
+                                           _ptr_array(skip_out), stream or None))
 
 
 def hpf_forward_inference(handle, act_in, skip_in, out, skip_out, stream=0):
@@ -531,11 +538,14 @@ class Partition:
         r = np.ascontiguousarray(r, np.float32)
         hpf_bn_running_write(self.handle, r.ctypes.data, r.size)
 
-    def forward_inference(self, act_in, skip_in=None, stream=None):
+    def forward_inference(self, act_in, skip_in=None, stream=None, out=None):
         """Inference forward: logits [b, classes] fp32 with a head, else act_out (or (act_out, skip_out))."""
         torch = self.torch
         assert tuple(act_in.shape) == self.in_shape and act_in.dtype == self.in_dtype and act_in.is_contiguous()
-        if self.spec.has_head:
+        if out is not None:
+            assert out.is_contiguous() and out.numel() == (self.spec.microbatch * self.spec.num_classes if self.spec.has_head
+                                                           else int(self.sizes.act_out_elems))
+        elif self.spec.has_head:
             out = torch.empty((self.spec.microbatch, self.spec.num_classes), dtype=torch.float32, device=self.device)
         else:
             out = torch.empty(self.out_shape, dtype=self.tdtype, device=self.device)
@@ -545,6 +555,27 @@ class Partition:
         hpf_forward_inference(self.handle, act_in.data_ptr(), skip_in.data_ptr() if skip_in is not None else 0, out.data_ptr(),
                               skip_out.data_ptr() if skip_out is not None else 0, self._stream_or_current(stream))
         return (out, skip_out) if skip_out is not None else out
+
+    def forward_inference_group(self, act_in, skip_in=None, stream=None, out=None):
+        """Inference forward of several micro-batches in one call: list of outputs (or of (act_out, skip_out)).
+        out: optional list of output tensors to write into (the same tensors every call let the library replay
+        one HIP graph)."""
+        torch = self.torch
+        n = len(act_in)
+        for t in act_in:
+            assert tuple(t.shape) == self.in_shape and t.dtype == self.in_dtype and t.is_contiguous()
+        shape = (self.spec.microbatch, self.spec.num_classes) if self.spec.has_head else self.out_shape
+        dt = torch.float32 if self.spec.has_head else self.tdtype
+        outs = out if out is not None else [torch.empty(shape, dtype=dt, device=self.device) for _ in range(n)]
+        assert len(outs) == n and all(tuple(t.shape) == shape and t.dtype == dt and t.is_contiguous() for t in outs)
+        skos = [torch.empty(self.skip_out_shape, dtype=self.tdtype, device=self.device) for _ in range(n)] if self.skip_out_shape else None
+        if self.skip_in_shape:
+            assert skip_in is not None and all(self._skip_ok(t, self.skip_in_shape) for t in skip_in)
+        hpf_forward_inference_group(self.handle, [t.data_ptr() for t in act_in],
+                                    [t.data_ptr() for t in skip_in] if skip_in is not None else None,
+                                    [t.data_ptr() for t in outs], [t.data_ptr() for t in skos] if skos else None,
+                                    self._stream_or_current(stream))
+        return list(zip(outs, skos)) if skos else outs
 
     def profile_read(self):
         """[{name, launches, total_ms, bytes_per_launch, flops_per_launch}] since profiling was enabled."""

@@ -94,6 +94,14 @@ def test_running_statistics_and_inference_against_oracle(gpu, oracle, name, grou
     errs = [parity.rel_err(g.float().cpu().numpy(), r) for g, r in zip(gl, rl)]
     print(f"[parity] running statistics {e:.2e}; inference outputs {['%.2e' % v for v in errs]}", flush=True)
     assert len(gl) == len(rl) and max(errs) <= tol
+    # the group call gives what the single calls give (twice: the second call replays the captured launches)
+    outs = None
+    for _ in range(2):
+        grp = part.forward_inference_group(t["act_in"], t["skip_in"], out=outs)
+        outs = [g[0] if isinstance(g, tuple) else g for g in grp]
+        torch.cuda.synchronize()
+        g1 = grp[1][0] if isinstance(grp[1], tuple) else grp[1]
+        assert torch.equal(g1, gl[0])
     part.close()
     opart.close()
 
