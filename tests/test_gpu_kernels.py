@@ -50,6 +50,12 @@ CONV_SHAPES = [
     (3, 14, 14, 256, 256, 3, 1),     # 588 rows: ragged tile
     (1, 14, 14, 256, 1024, 1, 1),    # wide channel tile
     (1, 8, 8, 64, 64, 3, 1),
+    # wide tensors (8-wave 128x128x64 kernels): step counts 16, 18, 9, 7, 11 exercise every tail of the unrolled loop
+    (2, 14, 14, 1024, 256, 1, 1),    # ResNet-152 stage-3 conv1: 16 steps; data gradient 4 steps into 1024 channels
+    (1, 28, 28, 128, 128, 3, 2),     # 3x3 stride 2 on the wide kernel: 18 steps, stride holes in the data gradient
+    (5, 7, 7, 64, 128, 3, 1),        # 9 steps, 245 rows (ragged second tile)
+    (1, 8, 8, 448, 128, 1, 1),       # 7 steps
+    (1, 8, 8, 704, 128, 1, 1),       # 11 steps
 ]
 
 
