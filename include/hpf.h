@@ -216,8 +216,9 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
  *
  * hpf_partition_set_bn_momentum: with momentum m < 1 every training forward moves them,
  *   r <- m*r + (1-m)*(mean | biased variance of the micro-batch), once per micro-batch, in micro-batch order
- *   within a group call and in stream order between calls -- forwards of one batch issued on several streams
- *   at once would race on these buffers, so issue them on one stream (or as group calls) when m < 1.
+ *   within a group call and in call order between calls (with m < 1 the library chains forward calls issued on
+ *   different streams through an event, so they no longer overlap each other; a caller that captures the calls
+ *   into a graph of its own must keep them on one stream).
  *   m = 1 (the default) never touches them; bn_mode 1 neither.  [0, 1] else HPF_EINVAL; HPF_ESTATE while a
  *   micro-batch is between forward and backward.
  * hpf_bn_running_read / _write: (host) n_bn_running floats: per BatchNorm in model order mean[C], variance[C].

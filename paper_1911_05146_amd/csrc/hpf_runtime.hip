@@ -506,6 +506,8 @@ struct hpf_partition {
   std::vector<hipEvent_t> ev_fwd, ev_bwd;
   hipEvent_t ev_step = nullptr;
   bool step_recorded = false;
+  hipEvent_t ev_run = nullptr;   // last forward that moved the BatchNorm running statistics
+  bool run_recorded = false;
 
   float* params() const { return (float*)(arena + P.params_off); }
   float* grads() const { return (float*)(arena + P.grads_off); }
@@ -1077,6 +1079,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     ok(hipEventCreateWithFlags(&p->ev_bwd[i], hipEventDisableTiming));
   }
   ok(hipEventCreateWithFlags(&p->ev_step, hipEventDisableTiming));
+  ok(hipEventCreateWithFlags(&p->ev_run, hipEventDisableTiming));
   ok(hipDeviceSynchronize());
   if (e != hipSuccess) {
     st = fail(HPF_EDEVICE, "create: %s", hipGetErrorString(e));
@@ -1093,6 +1096,7 @@ void hpf_partition_destroy(hpf_partition* p) {
   for (hipEvent_t ev : p->ev_fwd) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : p->ev_bwd) if (ev) (void)hipEventDestroy(ev);
   if (p->ev_step) (void)hipEventDestroy(p->ev_step);
+  if (p->ev_run) (void)hipEventDestroy(p->ev_run);
   for (auto& sg : p->prof_pending) { (void)hipEventDestroy(sg.e0); (void)hipEventDestroy(sg.e1); }
   for (hipEvent_t ev : p->ev_pool) (void)hipEventDestroy(ev);
   for (GraphSlot& g : p->g_fwd) if (g.exec) (void)hipGraphExecDestroy(g.exec);
@@ -1152,8 +1156,16 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
       key.push_back(c.act_in[i]); key.push_back(c.act_out[i]); key.push_back(lab.p[i]);
       key.push_back(c.skip_in[i]); key.push_back(c.skip_out[i]);
     }
+    // forwards that move the running statistics read and write the same buffers: chain them in call order
+    const bool moves_running = p->bn_momentum < 1.f && P.d.bn_mode == 0 && P.n_running > 0 && !stream_is_capturing(s);
+    if (moves_running && p->run_recorded && hipStreamWaitEvent(s, p->ev_run, 0) != hipSuccess)
+      return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
     const hpf_status st = run_graphed(p, p->g_fwd[mb_first + c0], key, s, c, [&] { run_forward(c, lab, loss_accum); });
     if (st != HPF_OK) return st;
+    if (moves_running) {
+      if (hipEventRecord(p->ev_run, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+      p->run_recorded = true;
+    }
     for (int i = 0; i < g; ++i) {
       const int mb = mb_first + c0 + i;
       if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");

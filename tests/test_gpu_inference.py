@@ -155,3 +155,33 @@ def test_momentum_one_and_frozen_mode_never_touch_the_running_statistics(gpu):
         with pytest.raises(hpf.HpfError):
             part.bn_running_write(-np.ones_like(r0))
         part.close()
+
+
+def test_running_statistics_with_one_stream_per_microbatch(gpu, oracle):
+    """Forward calls on different streams are chained by the library while they move the running statistics:
+    the result is that of the calls in call order."""
+    import torch
+    hpf = gpu
+    spec = small_specs()["bottleneck_run"]
+    inp = W.make_inputs(spec, randomize_affine=True)
+    dev = torch.device("cuda:0")
+    act = [parity.bf16_round(a) for a in inp.act_in]
+    x = [torch.from_numpy(a).to(dev, torch.bfloat16) for a in act]
+    e = [torch.from_numpy(parity.bf16_round(a)).to(dev, torch.bfloat16) for a in inp.err_in]
+    part = hpf.Partition(spec, inp.params, hpf.HPF_BF16)
+    opart = oracle.OraclePartition(spec, inp.params, np.float32, storage="bf16")
+    part.set_bn_momentum(0.5)
+    opart.set_bn_momentum(0.5)
+    streams = [torch.cuda.Stream() for _ in x]
+    torch.cuda.synchronize()
+    for i, s in enumerate(streams):
+        part.forward_microbatch(i, x[i], stream=s)
+    for i, s in enumerate(streams):
+        part.backward_microbatch(i, e[i], stream=s)
+    for i in range(spec.num_microbatches):
+        opart.forward(i, act[i])
+    err = parity.rel_err(part.bn_running_read().astype(np.float64), opart.bn_running())
+    print(f"[parity] running statistics over streams {err:.2e}", flush=True)
+    assert err <= 2e-2
+    part.close()
+    opart.close()
