@@ -197,7 +197,7 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *      convolution that produces the tensor, normalise + ReLU while the consuming convolution and
  *      weight gradient stage their operand;
  *   2  (default) additionally, runs of consecutive blocks of one shape with stride 1 and identity
- *      shortcut -- bottleneck 128->32->32->128 channels at up to 256 pixels or 256->64->64->256 at
+ *      shortcut -- bottleneck 128->32->32->128 or 128->64->64->128 channels at up to 256 pixels or 256->64->64->256 at
  *      up to 128; basic (two 3x3 convolutions) with 32 channels at up to 256 pixels or 64 at up to
  *      128; image width 8, 16 or 32, pixel count a multiple of 32 -- run
  *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per

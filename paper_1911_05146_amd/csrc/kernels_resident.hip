@@ -549,21 +549,43 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
 
 // What the backward pass of one block reads from memory besides the weights, fetched into registers ahead
 // of use: the stashed c1 / c2 tiles and the BatchNorm tables.
+// XD (the three MID-wide tiles of the backward pass do not fit LDS next to the gradient stream: 128-64 blocks at 256
+// pixels): c1 / c2 are only needed at the accumulator positions of the BatchNorm backward, so they are read there
+// straight from memory (8 bytes per lane) instead of being staged as whole tiles.
 template <int C, int MID>
+constexpr bool res_bwd_direct() { return C == 128 && MID == 64; }
+
+template <int C, int MID, int PTW>
 struct BwdLoads {
-  static constexpr int NU = (256 * MID / 8 + RES_NT - 1) / RES_NT;   // 16-byte units per thread and tile, up to 256 pixels
+  static constexpr bool XD = res_bwd_direct<C, MID>();
+  static constexpr int NU = XD ? 1 : (256 * MID / 8 + RES_NT - 1) / RES_NT;   // 16-byte units per thread and tile, up to 256 pixels
   uint4 c1[NU], c2[NU];
+  uint2 x1[XD ? PTW : 1][MID / 16], x2[XD ? PTW : 1][MID / 16];   // XD: c1 / c2 at this lane's accumulator positions
   float4 t1, t2, t3;
-  __device__ __forceinline__ void issue(const ResBlock& B, const ResCtx& cx, const float* params, int me, int P) {
+  __device__ __forceinline__ void issue(const ResBlock& B, const ResCtx& cx, const float* params, int me, int P, int npt, int wave,
+                                        int fr, int fq) {
     const bf16_t* g1 = cx.tensor(B.c1_off) + (size_t)me * P * MID;
     const bf16_t* g2 = cx.tensor(B.c2_off) + (size_t)me * P * MID;
-    const int units = P * (MID / 8);
+    if (XD) {
 #pragma unroll
-    for (int i = 0; i < NU; ++i) {
-      const int u = threadIdx.x + i * RES_NT;
-      const int uc = u < units ? u : 0;   // always a valid address; commit_tiles drops the surplus
-      c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
-      c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)uc * 8);
+      for (int j = 0; j < (XD ? PTW : 1); ++j) {
+        const int pt = wave + j * RES_NWV;
+        const size_t row = (size_t)((pt < npt ? pt : 0) * 16 + fr) * MID + fq * 4;   // always a valid address
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) {
+          x1[j][nt] = *reinterpret_cast<const uint2*>(g1 + row + nt * 16);
+          x2[j][nt] = *reinterpret_cast<const uint2*>(g2 + row + nt * 16);
+        }
+      }
+    } else {
+      const int units = P * (MID / 8);
+#pragma unroll
+      for (int i = 0; i < NU; ++i) {
+        const int u = threadIdx.x + i * RES_NT;
+        const int uc = u < units ? u : 0;   // always a valid address; commit_tiles drops the surplus
+        c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
+        c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)uc * 8);
+      }
     }
     const int c = threadIdx.x;
     t1 = table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), params + B.gamma_off[0], params + B.beta_off[0], c < C ? c : 0, C);
@@ -576,6 +598,7 @@ struct BwdLoads {
     return make_float4(ss.x, ss.y, is, -mean * is);
   }
   __device__ __forceinline__ void commit_tiles(bf16_t* sm1, bf16_t* sm2, int P) const {
+    if (XD) return;
     constexpr int U = MID / 8;
     const int units = P * U;
 #pragma unroll
@@ -610,9 +633,10 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   unsigned phase = 0;
 
   extern __shared__ __align__(16) unsigned char smem[];
+  constexpr bool XD = res_bwd_direct<C, MID>();           // c1 / c2 are not staged as tiles
   bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream, [P][XS]
-  bf16_t* sm1 = sdy + (size_t)P * XS;                     // c1
-  bf16_t* sm2 = sm1 + (size_t)P * MS;                     // c2, later dc1
+  bf16_t* sm1 = sdy + (size_t)P * XS;                     // c1 (XD: no such tile)
+  bf16_t* sm2 = XD ? sm1 : sm1 + (size_t)P * MS;          // c2, later dc1
   bf16_t* sdc = sm2 + (size_t)P * MS;                     // dc2
   float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * MS);
   float4* cf2 = cf1 + C;
@@ -631,12 +655,19 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   }
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
+    uint2 xc1[XD ? PTW : 1][MID / 16], xc2[XD ? PTW : 1][MID / 16];   // XD: c1 / c2 at this lane's accumulator positions
     {   // one round trip to memory for everything the block reads up front
-      BwdLoads<C, MID> ld;
-      ld.issue(B, cx, a.params, me, P);
+      BwdLoads<C, MID, PTW> ld;
+      ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
       w3.load(a.packed + B.wd_off[2], C, fr, fk);
       ld.commit_tiles(sm1, sm2, P);
       ld.commit_tables(cf1, cf2, cf3);
+      if (XD) {
+#pragma unroll
+        for (int j = 0; j < (XD ? PTW : 1); ++j)
+#pragma unroll
+          for (int nt = 0; nt < MID / 16; ++nt) { xc1[j][nt] = ld.x1[j][nt]; xc2[j][nt] = ld.x2[j][nt]; }
+      }
     }
     __syncthreads();
     // ---- conv3 data gradient: da3[p][c] = sum_n dy[p][n] * W3[c][n]; then BN3 + ReLU backward -> dc2
@@ -663,8 +694,10 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
 #pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt)
-          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+        for (int nt = 0; nt < MID / 16; ++nt) {
+          if (XD) xin[j][nt] = pt < npt ? xc2[XD ? j : 0][nt] : make_uint2(0u, 0u);
+          else xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+        }
       }
       w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
@@ -702,8 +735,10 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
 #pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt)
-          xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+        for (int nt = 0; nt < MID / 16; ++nt) {
+          if (XD) xin[j][nt] = pt < npt ? xc1[XD ? j : 0][nt] : make_uint2(0u, 0u);
+          else xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+        }
       }
       w1.load(a.packed + B.wd_off[0], MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
@@ -738,7 +773,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         }
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
-      float* gath = gath_own ? own : reinterpret_cast<float*>(sm1);
+      float* gath = gath_own ? own : reinterpret_cast<float*>(XD ? sm2 : sm1);   // XD: dc1 left the tile above
       if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                    a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
@@ -1246,9 +1281,9 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       TwoTiles<C> ld;
       ld.issue(cx.tensor(B.x_off) + (size_t)me * P * C, cx.tensor(B.c1_off) + (size_t)me * P * C, P);
       const int c = tid < C ? tid : 0;
-      const float4 t1 = BwdLoads<C, C>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0],
+      const float4 t1 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0],
                                               a.params + B.beta_off[0], c, C);
-      const float4 t2 = BwdLoads<C, C>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
+      const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
       w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
       ld.commit(s0, s1, P);
@@ -1345,7 +1380,7 @@ size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
 size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
-  const size_t tiles = (size_t)P * (C + 8) * 2 + 3 * (size_t)P * (MID + 8) * 2;
+  const size_t tiles = (size_t)P * (C + 8) * 2 + (C == 128 && MID == 64 ? 2 : 3) * (size_t)P * (MID + 8) * 2;
   const size_t fixed = (size_t)(C + 2 * MID) * 16 + (size_t)RES_NWV * 2 * C * 4 + 4 * (size_t)C * 4;
   const size_t one_tile = (size_t)P * (MID + 8) * 2;
   *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
@@ -1378,7 +1413,7 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
     return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
            bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES;
   }
-  if (!((C == 128 && MID == 32 && P <= 256) || (C == 256 && MID == 64 && P <= 128))) return false;
+  if (!((C == 128 && (MID == 32 || MID == 64) && P <= 256) || (C == 256 && MID == 64 && P <= 128))) return false;
   return fwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES && bwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES;
 }
 
@@ -1404,6 +1439,10 @@ hipError_t resident_prepare() {
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<128, 32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_wgrad<256, 64>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* wide[] = {reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false>), reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false>),
+                        reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
+  for (const void* f : wide)
+    if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
@@ -1416,6 +1455,7 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
     return launch_res(k_bb_forward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
+  if (C == 128 && MID == 64) return launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
@@ -1438,7 +1478,8 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
   }
   const size_t lds = wgrad_lds(C, MID, a.H * a.W, a.W);
   const dim3 grid(groups, (unsigned)(2 * (C / 64) + 1), (unsigned)a.nblk);
-  if (C == 128) k_res_wgrad<128, 32><<<grid, RW_NT, lds, stream>>>(w);
+  if (C == 128 && MID == 64) k_res_wgrad<128, 64><<<grid, RW_NT, lds, stream>>>(w);
+  else if (C == 128) k_res_wgrad<128, 32><<<grid, RW_NT, lds, stream>>>(w);
   else k_res_wgrad<256, 64><<<grid, RW_NT, lds, stream>>>(w);
   return hipGetLastError();
 }
@@ -1452,6 +1493,7 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
     return launch_res(k_bb_backward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
+  if (C == 128 && MID == 64) return launch_res(k_res_backward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128) return launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);
 }

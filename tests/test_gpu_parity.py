@@ -113,6 +113,22 @@ def test_image_resident_runs_small(gpu, oracle):
         check(oracle, spec, "bf16", grouped=grouped)
 
 
+def test_image_resident_runs_of_wide_bottlenecks(gpu, oracle):
+    """128-64-64-128 blocks (the 30 M-parameter ResNet-1001): at 256 pixels the backward kernel reads c1 / c2 at the
+    accumulator positions instead of staging them as tiles."""
+    cases = [
+        (_bottleneck_run("resident-128x64-16x16", 128, 64, 16, 2, 2, 2, seed=51), False),
+        (_bottleneck_run("resident-128x64-8x8-grouped", 128, 64, 8, 3, 3, 2, seed=52), True),
+        (replace(_bottleneck_run("resident-128x64-8x16", 128, 64, 16, 2, 2, 3, seed=53), in_h=8), True),
+    ]
+    for spec, grouped in cases:
+        check(oracle, spec, "bf16", strict=True, beta_shift=6.0, grouped=grouped)
+        check(oracle, replace(spec, blocks=spec.blocks[:1], microbatch=1), "bf16", strict=True, seeds=5, grouped=grouped)
+        check(oracle, spec, "bf16", grouped=grouped)
+    check(oracle, _bottleneck_run("resident-128x64-deep-active", 128, 64, 16, 21, 8, 2, seed=54), "bf16", beta_shift=6.0, grouped=True)
+    check(oracle, _bottleneck_run("resident-128x64-deep", 128, 64, 16, 21, 8, 2, seed=55), "bf16", grouped=True)
+
+
 def test_image_resident_runs_of_basic_blocks(gpu, oracle):
     """The ResNet-20 / ResNet-110 family: runs of basic blocks (two 3x3 convolutions) in the image-resident kernels."""
     def basic_run(name, c, hw, n, b, m, seed=43):
