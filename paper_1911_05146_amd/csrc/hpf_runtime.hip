@@ -504,6 +504,8 @@ struct hpf_partition {
   std::vector<const void*> act_in;
   int n_bwd = 0;
   std::vector<hipEvent_t> ev_fwd, ev_bwd;
+  // the members of one launch share its first member's event: fwd_ev[mb] / bwd_ev[mb] say whose event covers mb
+  std::vector<int> fwd_ev, bwd_ev;
   hipEvent_t ev_step = nullptr;
   bool step_recorded = false;
   hipEvent_t ev_run = nullptr;   // last forward that moved the BatchNorm running statistics
@@ -909,7 +911,7 @@ bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_m
 
 hpf_status wait_all_backward(hpf_partition* p, hipStream_t s) {
   for (int i = 0; i < p->P.d.num_microbatches; ++i)
-    if (p->bwd_done[i] && hipStreamWaitEvent(s, p->ev_bwd[i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+    if (p->bwd_done[i] && p->bwd_ev[i] == i && hipStreamWaitEvent(s, p->ev_bwd[i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
   return HPF_OK;
 }
 
@@ -1074,6 +1076,8 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     if (p->res_group >= 1) ok(resident_prepare());
   }
   p->ev_fwd.resize(m); p->ev_bwd.resize(m);
+  p->fwd_ev.assign(m, 0); p->bwd_ev.assign(m, 0);
+  for (int i = 0; i < m; ++i) { p->fwd_ev[i] = i; p->bwd_ev[i] = i; }
   for (int i = 0; i < m; ++i) {
     ok(hipEventCreateWithFlags(&p->ev_fwd[i], hipEventDisableTiming));
     ok(hipEventCreateWithFlags(&p->ev_bwd[i], hipEventDisableTiming));
@@ -1166,9 +1170,10 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
       if (hipEventRecord(p->ev_run, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
       p->run_recorded = true;
     }
+    if (hipEventRecord(p->ev_fwd[mb_first + c0], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
     for (int i = 0; i < g; ++i) {
       const int mb = mb_first + c0 + i;
-      if (hipEventRecord(p->ev_fwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+      p->fwd_ev[mb] = mb_first + c0;
       p->act_in[mb] = c.act_in[i];
       p->fwd_done[mb] = 1;
     }
@@ -1201,7 +1206,9 @@ hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, con
   }
   hipStream_t s = (hipStream_t)hip_stream;
   for (int i = 0; i < count; ++i)
-    if (hipStreamWaitEvent(s, p->ev_fwd[mb_first + i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+    if ((i == 0 || p->fwd_ev[mb_first + i] != p->fwd_ev[mb_first + i - 1]) &&
+        hipStreamWaitEvent(s, p->ev_fwd[p->fwd_ev[mb_first + i]], 0) != hipSuccess)
+      return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
   const int gmax = p->group_limit();
   {
     const hpf_status st = resident_enter(p, s);
@@ -1224,9 +1231,10 @@ hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, con
     }
     const hpf_status st = run_graphed(p, p->g_bwd[mb_first + c0], key, s, c, [&] { run_backward(c); });
     if (st != HPF_OK) return st;
+    if (hipEventRecord(p->ev_bwd[mb_first + c0], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
     for (int i = 0; i < g; ++i) {
       const int mb = mb_first + c0 + i;
-      if (hipEventRecord(p->ev_bwd[mb], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
+      p->bwd_ev[mb] = mb_first + c0;
       p->bwd_done[mb] = 1;
       ++p->n_bwd;
     }
