@@ -506,8 +506,10 @@ struct hpf_partition {
   std::vector<hipEvent_t> ev_fwd, ev_bwd;
   // the members of one launch share its first member's event: fwd_ev[mb] / bwd_ev[mb] say whose event covers mb
   std::vector<int> fwd_ev, bwd_ev;
+  std::vector<hipStream_t> fwd_stream, bwd_stream;   // the stream each leader's event was last recorded on
   hipEvent_t ev_step = nullptr;
   bool step_recorded = false;
+  hipStream_t step_stream = nullptr, run_stream = nullptr;
   hipEvent_t ev_run = nullptr;   // last forward that moved the BatchNorm running statistics
   bool run_recorded = false;
 
@@ -909,9 +911,24 @@ void run_backward(Ctx& c) {
 
 bool all_backward_done(const hpf_partition* p) { return p->n_bwd == p->P.d.num_microbatches; }
 
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  return s != nullptr && hipStreamIsCapturing(s, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+}
+// Work queued on one stream runs in the order of the calls, so only a wait across streams needs a marker in
+// the queue (each costs a few microseconds of stream time).  A stream under capture always gets the wait.
+hpf_status wait_for(hipStream_t s, hipEvent_t ev, hipStream_t recorded_on) {
+  if (recorded_on == s && !stream_is_capturing(s)) return HPF_OK;
+  if (hipStreamWaitEvent(s, ev, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  return HPF_OK;
+}
+
 hpf_status wait_all_backward(hpf_partition* p, hipStream_t s) {
   for (int i = 0; i < p->P.d.num_microbatches; ++i)
-    if (p->bwd_done[i] && p->bwd_ev[i] == i && hipStreamWaitEvent(s, p->ev_bwd[i], 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+    if (p->bwd_done[i] && p->bwd_ev[i] == i) {
+      const hpf_status st = wait_for(s, p->ev_bwd[i], p->bwd_stream[i]);
+      if (st != HPF_OK) return st;
+    }
   return HPF_OK;
 }
 
@@ -960,27 +977,25 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<cons
 
 // Image-resident kernels need every work-group of a launch on the chip at once and take a CU each, so two
 // of them must never share the device: launches of this process are chained through one event.
+// The link of the chain is the completion event the last such call recorded anyway (its owner re-records it
+// only after a later launch of its own, so waiting on it never waits for too little).
 std::mutex g_res_mu;
-hipEvent_t g_res_ev = nullptr;
-bool g_res_recorded = false;
+struct ResidentLink { hipEvent_t ev = nullptr; hipStream_t stream = nullptr; const hpf_partition* owner = nullptr; } g_res;
 
-bool stream_is_capturing(hipStream_t s) {
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  return s != nullptr && hipStreamIsCapturing(s, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
-}
 hpf_status resident_enter(hpf_partition* p, hipStream_t s) {
   if (!p->resident() || stream_is_capturing(s)) return HPF_OK;
   std::lock_guard<std::mutex> lk(g_res_mu);
-  if (g_res_recorded && hipStreamWaitEvent(s, g_res_ev, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
-  return HPF_OK;
+  return g_res.owner ? wait_for(s, g_res.ev, g_res.stream) : HPF_OK;
 }
-hpf_status resident_leave(hpf_partition* p, hipStream_t s) {
-  if (!p->resident() || stream_is_capturing(s)) return HPF_OK;
+// done: the event recorded on s after the call's last launch
+void resident_leave(hpf_partition* p, hipStream_t s, hipEvent_t done) {
+  if (!p->resident() || stream_is_capturing(s)) return;
   std::lock_guard<std::mutex> lk(g_res_mu);
-  if (!g_res_ev && hipEventCreateWithFlags(&g_res_ev, hipEventDisableTiming) != hipSuccess) return fail(HPF_EDEVICE, "hipEventCreate failed");
-  if (hipEventRecord(g_res_ev, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
-  g_res_recorded = true;
-  return HPF_OK;
+  g_res.ev = done; g_res.stream = s; g_res.owner = p;
+}
+void resident_forget(const hpf_partition* p) {   // the partition's events are about to be destroyed (device idle)
+  std::lock_guard<std::mutex> lk(g_res_mu);
+  if (g_res.owner == p) g_res = ResidentLink{};
 }
 // An exchange between the work-groups of an image-resident launch timed out: the batch is invalid.
 hpf_status check_abort_flag(hpf_partition* p) {
@@ -997,6 +1012,7 @@ void begin_next_batch(hpf_partition* p, hipStream_t s) {
   p->n_bwd = 0;
   (void)hipEventRecord(p->ev_step, s);
   p->step_recorded = true;
+  p->step_stream = s;
 }
 
 }  // namespace
@@ -1077,6 +1093,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   }
   p->ev_fwd.resize(m); p->ev_bwd.resize(m);
   p->fwd_ev.assign(m, 0); p->bwd_ev.assign(m, 0);
+  p->fwd_stream.assign(m, nullptr); p->bwd_stream.assign(m, nullptr);
   for (int i = 0; i < m; ++i) { p->fwd_ev[i] = i; p->bwd_ev[i] = i; }
   for (int i = 0; i < m; ++i) {
     ok(hipEventCreateWithFlags(&p->ev_fwd[i], hipEventDisableTiming));
@@ -1097,6 +1114,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
 void hpf_partition_destroy(hpf_partition* p) {
   if (!p) return;
   (void)hipDeviceSynchronize();
+  resident_forget(p);
   for (hipEvent_t ev : p->ev_fwd) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : p->ev_bwd) if (ev) (void)hipEventDestroy(ev);
   if (p->ev_step) (void)hipEventDestroy(p->ev_step);
@@ -1137,7 +1155,10 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
     if (p->fwd_done[mb_first + i]) return fail(HPF_ESTATE, "forward(%d) already ran in this batch", mb_first + i);
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  if (p->step_recorded) {
+    const hpf_status st = wait_for(s, p->ev_step, p->step_stream);
+    if (st != HPF_OK) return st;
+  }
   const int gmax = p->group_limit();
   {
     const hpf_status st = resident_enter(p, s);
@@ -1162,13 +1183,16 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
     }
     // forwards that move the running statistics read and write the same buffers: chain them in call order
     const bool moves_running = p->bn_momentum < 1.f && P.d.bn_mode == 0 && P.n_running > 0 && !stream_is_capturing(s);
-    if (moves_running && p->run_recorded && hipStreamWaitEvent(s, p->ev_run, 0) != hipSuccess)
-      return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+    if (moves_running && p->run_recorded) {
+      const hpf_status st = wait_for(s, p->ev_run, p->run_stream);
+      if (st != HPF_OK) return st;
+    }
     const hpf_status st = run_graphed(p, p->g_fwd[mb_first + c0], key, s, c, [&] { run_forward(c, lab, loss_accum); });
     if (st != HPF_OK) return st;
     if (moves_running) {
       if (hipEventRecord(p->ev_run, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
       p->run_recorded = true;
+      p->run_stream = s;
     }
     if (hipEventRecord(p->ev_fwd[mb_first + c0], s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");
     for (int i = 0; i < g; ++i) {
@@ -1177,8 +1201,10 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
       p->act_in[mb] = c.act_in[i];
       p->fwd_done[mb] = 1;
     }
+    p->fwd_stream[mb_first + c0] = s;
+    resident_leave(p, s, p->ev_fwd[mb_first + c0]);
   }
-  return resident_leave(p, s);
+  return HPF_OK;
 }
 
 // skip_err_in: gradient w.r.t. skip_out (from the partition that took it); skip_err_out: gradient w.r.t. skip_in
@@ -1206,9 +1232,11 @@ hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, con
   }
   hipStream_t s = (hipStream_t)hip_stream;
   for (int i = 0; i < count; ++i)
-    if ((i == 0 || p->fwd_ev[mb_first + i] != p->fwd_ev[mb_first + i - 1]) &&
-        hipStreamWaitEvent(s, p->ev_fwd[p->fwd_ev[mb_first + i]], 0) != hipSuccess)
-      return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+    if (i == 0 || p->fwd_ev[mb_first + i] != p->fwd_ev[mb_first + i - 1]) {
+      const int lead = p->fwd_ev[mb_first + i];
+      const hpf_status st = wait_for(s, p->ev_fwd[lead], p->fwd_stream[lead]);
+      if (st != HPF_OK) return st;
+    }
   const int gmax = p->group_limit();
   {
     const hpf_status st = resident_enter(p, s);
@@ -1238,8 +1266,10 @@ hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, con
       p->bwd_done[mb] = 1;
       ++p->n_bwd;
     }
+    p->bwd_stream[mb_first + c0] = s;
+    resident_leave(p, s, p->ev_bwd[mb_first + c0]);
   }
-  return resident_leave(p, s);
+  return HPF_OK;
 }
 
 }  // namespace
@@ -1401,7 +1431,10 @@ hpf_status hpf_forward_inference_group(hpf_partition* p, int32_t count, const vo
   for (int i = 0; i < P.d.num_microbatches; ++i)   // the pass works in the regions of micro-batches 0 .. count-1
     if (p->fwd_done[i] && !p->bwd_done[i]) return fail(HPF_ESTATE, "micro-batch %d is between forward and backward", i);
   hipStream_t s = (hipStream_t)hip_stream;
-  if (p->step_recorded && hipStreamWaitEvent(s, p->ev_step, 0) != hipSuccess) return fail(HPF_EDEVICE, "hipStreamWaitEvent failed");
+  if (p->step_recorded) {
+    const hpf_status st = wait_for(s, p->ev_step, p->step_stream);
+    if (st != HPF_OK) return st;
+  }
   hpf_status st = wait_all_backward(p, s);
   if (st != HPF_OK) return st;
   Ctx c{p, 0, count, s};
@@ -1420,6 +1453,7 @@ hpf_status hpf_forward_inference_group(hpf_partition* p, int32_t count, const vo
   if (st != HPF_OK) return st;
   if (hipEventRecord(p->ev_step, s) != hipSuccess) return fail(HPF_EDEVICE, "hipEventRecord failed");   // later forwards reuse the regions
   p->step_recorded = true;
+  p->step_stream = s;
   return HPF_OK;
 }
 
