@@ -51,11 +51,49 @@ def profile_classes(torch, part, step, steps=10):
     return entries
 
 
-def cpu_baseline(spec, inputs, max_microbatches=4):
-    """The oracle (fp32 storage, double sums, OpenMP) on the first micro-batches of the same workload."""
+def measured_ceilings(torch, dev):
+    """What this chip achieves on a plain copy and on a register-only MFMA loop (the library's two probe kernels),
+    timed with events on the launch stream: the ceilings to read the kernel rates against next to the data-sheet ones."""
+    from paper_1911_05146_amd import hpf
+    stream = torch.cuda.current_stream(dev)
+    nbytes = 1 << 30
+    src = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    wgs, iters = 4096, 2048
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    t_copy = timed(lambda: hpf.hpf_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream), 10)
+    flops = float(wgs) * 4 * iters * 131072
+    t_mfma = {shape: timed(lambda: hpf.hpf_probe_mfma_bf16(sink.data_ptr(), wgs, iters, wide, stream.cuda_stream), 5)
+              for shape, wide in (("16x16x32", False), ("32x32x16", True))}
+    best = min(t_mfma, key=t_mfma.get)
+    del src, dst, sink
+    return {"copy_GB/s": 2 * nbytes / t_copy / 1e9, "copy": "1 GiB read + 1 GiB written per launch",
+            "mfma_bf16_TFLOP/s": flops / t_mfma[best] / 1e12,
+            "mfma": f"{wgs} work-groups x 4 waves x {iters} rounds of 131072 flop, v_mfma_f32_{best}_bf16 "
+                    f"(16x16x32: {flops / t_mfma['16x16x32'] / 1e12:.0f}, 32x32x16: {flops / t_mfma['32x32x16'] / 1e12:.0f} TFLOP/s)"}
+
+
+def cpu_baseline(spec, inputs, max_microbatches=4, threads=None):
+    """The oracle (fp32 storage, double sums, OpenMP) on the first micro-batches of the same workload.
+    threads: ask the OpenMP runtime for this many threads first (the oracle itself has no such setting)."""
     import numpy as np
     import oracle
     from paper_1911_05146_amd import workloads as W
+    if threads is not None:
+        import ctypes
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(threads))
     n = min(spec.num_microbatches, max_microbatches)
     sub = W.with_microbatching(spec, spec.microbatch, n, loss_divisor=spec.divisor)
     sub_inp = W.StepInputs(inputs.params, inputs.act_in[:n], inputs.labels[:n] if inputs.labels else None,
@@ -64,7 +102,7 @@ def cpu_baseline(spec, inputs, max_microbatches=4):
     t0 = time.perf_counter()
     oracle.run_step(sub, sub_inp, np.float32)
     dt = time.perf_counter() - t0
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cores = int(threads) if threads is not None else int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": sub.batch / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
             "sample": f"{n} of {spec.num_microbatches} micro-batches ({sub.batch} images) forward+backward, {dt:.1f} s"}
 
@@ -136,6 +174,8 @@ def main():
     ap.add_argument("--inference", action="store_true",
                     help="instead of training steps: inference forwards (BatchNorm by running statistics) of the "
                          "configuration's micro-batches, one call each")
+    ap.add_argument("--cpu-one-core", action="store_true",
+                    help="also time the oracle on one thread, on one micro-batch (adds its run time)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -285,8 +325,15 @@ def main():
              "GB/s": round(k["bytes_per_launch"] / k["avg_sec"] / 1e9, 1) if k["bytes_per_launch"] else None,
              "hbm_frac": round(k["bytes_per_launch"] / k["avg_sec"] / PEAK_HBM, 4) if k["bytes_per_launch"] else None}
             for k in ks]
+    if not args.no_probe:
+        ceil = measured_ceilings(torch, dev)
+        result["measured_ceilings"] = ceil
+        r = result["roofline"]
+        r["frac_of_measured_ceiling"] = r["achieved"] / (ceil["copy_GB/s"] if r["bound"] == "hbm" else ceil["mfma_bf16_TFLOP/s"])
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(spec, inputs)
+        if args.cpu_one_core:   # after the all-thread run: the thread count stays at 1 from here on
+            result["cpu_baseline"]["one_core"] = cpu_baseline(spec, inputs, max_microbatches=1, threads=1)
     part.close()
     print(json.dumps(result))
 

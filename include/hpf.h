@@ -304,6 +304,18 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
                                    float* dgamma, float* dbeta, int32_t M, int32_t C, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
 
+/* ---- Measurement aids ------------------------------------------------------------------------
+ * Not steps of the method: two plain kernels that say what this chip achieves, so that kernel rates can be
+ * quoted against a measured ceiling next to the data-sheet one.
+ * hpf_probe_copy: dst[0..bytes) = src[0..bytes) (dev, dev; no overlap) with the library's 16-byte grid-stride
+ * copy kernel: 2*bytes of HBM traffic per call.
+ * hpf_probe_mfma_bf16: `workgroups` work-groups of 4 waves each run `iters` rounds of independent MFMA on
+ * registers: 8 x v_mfma_f32_16x16x32_bf16 per round (wide == 0) or 4 x v_mfma_f32_32x32x16_bf16 (wide != 0):
+ * flops = workgroups * 4 * iters * 131072 either way.  sink (dev) receives workgroups*256 floats (each
+ * lane's sum of its accumulators).  1 <= workgroups <= 65536, 1 <= iters <= 2^20.  Both enqueue on hip_stream. */
+hpf_status hpf_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+hpf_status hpf_probe_mfma_bf16(float* sink, int32_t workgroups, int32_t iters, int32_t wide, void* hip_stream);
+
 /* Message for the last non-OK status on this thread (static storage, never NULL). */
 const char* hpf_last_error(void);
 

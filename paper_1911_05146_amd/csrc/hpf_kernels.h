@@ -219,5 +219,8 @@ hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream);
 hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
                                hipStream_t stream);
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
+// iters rounds of 131 072 flop of bf16 MFMA per wave (8 x 16x16x32, or 4 x 32x32x16 when wide), 4 waves per
+// work-group; sink: workgroups*256 floats
+hipError_t launch_probe_mfma_bf16(float* sink, int workgroups, int iters, bool wide, hipStream_t stream);
 
 }  // namespace hpf

@@ -1622,4 +1622,19 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
   return HPF_OK;
 }
 
+hpf_status hpf_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src) return fail(HPF_EINVAL, "null pointer");
+  const char* d = (const char*)dst; const char* s0 = (const char*)src;
+  if (d < s0 + bytes && s0 < d + bytes) return fail(HPF_EINVAL, "source and destination overlap");
+  if (bytes && launch_copy_bytes(dst, src, bytes, (hipStream_t)hip_stream) != hipSuccess) return fail(HPF_EDEVICE, "copy launch failed");
+  return HPF_OK;
+}
+
+hpf_status hpf_probe_mfma_bf16(float* sink, int32_t workgroups, int32_t iters, int32_t wide, void* hip_stream) {
+  if (!sink) return fail(HPF_EINVAL, "null sink");
+  if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return fail(HPF_EINVAL, "workgroups in [1, 65536], iters in [1, 2^20]");
+  if (launch_probe_mfma_bf16(sink, workgroups, iters, wide != 0, (hipStream_t)hip_stream) != hipSuccess) return fail(HPF_EDEVICE, "probe launch failed");
+  return HPF_OK;
+}
+
 }  // extern "C"

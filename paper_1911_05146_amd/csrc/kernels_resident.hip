@@ -26,6 +26,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int RES_NT = 512;            // threads per work-group (8 waves)
 constexpr int RES_NWV = RES_NT / 64;
@@ -71,7 +72,8 @@ __device__ __forceinline__ void tile_store(bf16_t* g, const bf16_t* s, int P) {
   constexpr int U = Cc / 8;
   for (int u = threadIdx.x; u < P * U; u += RES_NT) {
     const int row = u / U, col = u - row * U;
-    *reinterpret_cast<uint4*>(g + (size_t)u * 8) = *reinterpret_cast<const uint4*>(s + row * (Cc + 8) + col * 8);
+    // streaming store: the tensor is read again only by the backward pass, long after it has left the caches
+    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(s + row * (Cc + 8) + col * 8), reinterpret_cast<u32x4*>(g + (size_t)u * 8));
   }
 }
 // All `nmem` work-groups of a micro-batch publish `nw` floats each and collect everybody's in
@@ -802,20 +804,22 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
 // The 3x3 convolution keeps three copies of `a`, shifted by -1 / 0 / +1 pixel along the image row with the
 // wrapped column zeroed, on a canvas with one zero image row above and below: every tap is then an aligned
 // read at offset r*W.
-constexpr int RW_NT = 256;
+// Threads per work-group: 4 waves for the 32-wide tensors; 8 for the 64-wide ones, whose 3x3 item fills the LDS
+// of a CU on its own (one work-group per CU) and whose sums would otherwise take 200 registers per lane.
+constexpr int rw_threads(int mid) { return mid >= 64 ? 512 : 256; }
 
 // Pixel pairs of an image tile in registers: channels [c0, c0+CH) of an image [P][CT].  A unit is (pixel pair,
 // group of 8 channels); four neighbouring lanes take four consecutive channel groups of one pair (64
 // contiguous bytes), the 16 lane quads of a wave 16 consecutive pairs: global loads touch 16 lines per
 // instruction and the transposing LDS stores stay within a 2-way bank conflict.
-template <int CH>
+template <int CH, int NTH>
 struct PairRegs {
   static constexpr int G = CH / 8;                       // channel groups (4 or 8)
-  static constexpr int NU = 128 * G / RW_NT;
-  static_assert(G % 4 == 0 && (128 * G) % RW_NT == 0, "tile shape");
+  static constexpr int NU = 128 * G / NTH;
+  static_assert(G % 4 == 0 && (128 * G) % NTH == 0, "tile shape");
   uint4 v[NU][2];
   static __device__ __forceinline__ void unit(int u, int& pr, int& cg) {
-    const int lane = threadIdx.x & 63, q = u * (RW_NT / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, q = u * (NTH / 64) + (threadIdx.x >> 6);
     cg = (q % (G / 4)) * 4 + (lane & 3);
     pr = (q / (G / 4)) * 16 + (lane >> 2);
   }
@@ -878,14 +882,14 @@ struct WgImage {   // where the work-group's image i lives
 };
 
 // BN table of the `a` operand's channels [c0, c0+CA) -> LDS coef (the group's images share one micro-batch)
-template <int CA>
+template <int CA, int NTH>
 __device__ __forceinline__ void wg_coef(float2* coef, const float* stats, const float* gamma, const float* beta, int c0, int CT) {
-  for (int c = threadIdx.x; c < CA; c += RW_NT)
+  for (int c = threadIdx.x; c < CA; c += NTH)
     coef[c] = bn_scale_shift(stats[c0 + c], stats[CT + c0 + c], gamma[c0 + c], beta[c0 + c]);
 }
 
 // 1x1 convolution: a channels [ca0, ca0+CA) of CTA, dy channels [nd0, nd0+ND) of CTD; dw is [CTA][CTD].
-template <int CA, int ND>
+template <int CA, int ND, int NTH>
 __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsigned long long a_off, int CTA, int ca0,
                                               unsigned long long st_off, const float* gamma, const float* beta,
                                               unsigned long long dy_off, int CTD, int nd0, float* dw, unsigned char* smem) {
@@ -894,28 +898,29 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
   bf16_t* Ta = reinterpret_cast<bf16_t*>(smem);
   bf16_t* Td = Ta + (size_t)CA * PS;
   float2* coef = reinterpret_cast<float2*>(Td + (size_t)ND * PS);
-  constexpr int NTD = ND / 16, TPW = (CA / 16) * NTD / 4;
+  constexpr int NTD = ND / 16, TPW = (CA / 16) * NTD / (NTH / 64);
+  static_assert((CA / 16) * NTD % (NTH / 64) == 0, "output tiles per wave");
   floatx4 acc[TPW];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
   const WgImage wi{a, img0};
-  auto load_img = [&](int i, PairRegs<CA>& A, PairRegs<ND>& D) {
+  auto load_img = [&](int i, PairRegs<CA, NTH>& A, PairRegs<ND, NTH>& D) {
     int me;
     const ResCtx cx = wi.ctx(i, me);
     A.load(cx.tensor(a_off) + (size_t)me * P * CTA, CTA, ca0, P);
     D.load(cx.tensor(dy_off) + (size_t)me * P * CTD, CTD, nd0, P);
   };
-  auto stage = [&](const PairRegs<CA>& A, const PairRegs<ND>& D) {
+  auto stage = [&](const PairRegs<CA, NTH>& A, const PairRegs<ND, NTH>& D) {
 #pragma unroll
-    for (int u = 0; u < PairRegs<CA>::NU; ++u) {
+    for (int u = 0; u < PairRegs<CA, NTH>::NU; ++u) {
       int pr, cg;
-      PairRegs<CA>::unit(u, pr, cg);
+      PairRegs<CA, NTH>::unit(u, pr, cg);
       if (2 * pr < P) store_pair(Ta, PS, cg * 8, 2 * pr, bn_relu8(A.v[u][0], coef + cg * 8), bn_relu8(A.v[u][1], coef + cg * 8));
     }
 #pragma unroll
-    for (int u = 0; u < PairRegs<ND>::NU; ++u) {
+    for (int u = 0; u < PairRegs<ND, NTH>::NU; ++u) {
       int pr, cg;
-      PairRegs<ND>::unit(u, pr, cg);
+      PairRegs<ND, NTH>::unit(u, pr, cg);
       if (2 * pr < P) store_pair(Td, PS, cg * 8, 2 * pr, D.v[u][0], D.v[u][1]);
     }
   };
@@ -931,12 +936,12 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
     }
   };
   // two register sets: an image's loads are issued a whole iteration before they are staged
-  PairRegs<CA> a0, a1;
-  PairRegs<ND> d0, d1;
+  PairRegs<CA, NTH> a0, a1;
+  PairRegs<ND, NTH> d0, d1;
   {
     int me;
     const ResCtx cx = wi.ctx(0, me);
-    wg_coef<CA>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, ca0, CTA);
+    wg_coef<CA, NTH>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, ca0, CTA);
   }
   load_img(0, a0, d0);
   for (int i = 0; i < a.ipw; i += 2) {
@@ -963,7 +968,7 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
 }
 
 // 3x3 convolution, MID -> MID channels, stride 1, zero padding; dw is [9][MID][MID].
-template <int MID>
+template <int MID, int NTH>
 __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsigned long long a_off, unsigned long long st_off,
                                               const float* gamma, const float* beta, unsigned long long dy_off, float* dw,
                                               unsigned char* smem) {
@@ -972,30 +977,31 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
   bf16_t* Tsh = reinterpret_cast<bf16_t*>(smem);          // [3][MID][PSH]: a shifted by s-1 pixels along the row
   bf16_t* Td = Tsh + (size_t)3 * MID * PSH;               // [MID][PS]
   float2* coef = reinterpret_cast<float2*>(Td + (size_t)MID * PS);
-  constexpr int NT = MID / 16, PPW = NT * NT / 4;         // (input tile, output tile) pairs per wave
+  constexpr int NT = MID / 16, PPW = NT * NT / (NTH / 64);
+  static_assert(NT * NT % (NTH / 64) == 0, "tile pairs per wave");         // (input tile, output tile) pairs per wave
   floatx4 acc[PPW][9];
 #pragma unroll
   for (int t = 0; t < PPW; ++t)
 #pragma unroll
     for (int k = 0; k < 9; ++k) acc[t][k] = floatx4{0.f, 0.f, 0.f, 0.f};
   // the zero image rows above and below
-  for (int i = tid; i < 3 * MID * 2 * W; i += RW_NT) {
+  for (int i = tid; i < 3 * MID * 2 * W; i += NTH) {
     const int ch = i / (2 * W), j = i - ch * 2 * W;
     Tsh[(size_t)ch * PSH + (j < W ? j : P + j)] = 0;
   }
   const WgImage wi{a, img0};
   const int half_w = W >> 1;
-  auto load_img = [&](int i, PairRegs<MID>& A, PairRegs<MID>& D) {
+  auto load_img = [&](int i, PairRegs<MID, NTH>& A, PairRegs<MID, NTH>& D) {
     int me;
     const ResCtx cx = wi.ctx(i, me);
     A.load(cx.tensor(a_off) + (size_t)me * P * MID, MID, 0, P);
     D.load(cx.tensor(dy_off) + (size_t)me * P * MID, MID, 0, P);
   };
-  auto stage = [&](const PairRegs<MID>& A, const PairRegs<MID>& D) {
+  auto stage = [&](const PairRegs<MID, NTH>& A, const PairRegs<MID, NTH>& D) {
 #pragma unroll
-    for (int u = 0; u < PairRegs<MID>::NU; ++u) {
+    for (int u = 0; u < PairRegs<MID, NTH>::NU; ++u) {
       int pr, cg;
-      PairRegs<MID>::unit(u, pr, cg);
+      PairRegs<MID, NTH>::unit(u, pr, cg);
       const bool ok = 2 * pr < P;
       const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
       const uint4 e0 = bn_relu8(A.v[u][0], coef + cg * 8), e1 = bn_relu8(A.v[u][1], coef + cg * 8);
@@ -1028,11 +1034,11 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
       }
     }
   };
-  PairRegs<MID> a0, a1, d0, d1;
+  PairRegs<MID, NTH> a0, a1, d0, d1;
   {
     int me;
     const ResCtx cx = wi.ctx(0, me);
-    wg_coef<MID>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
+    wg_coef<MID, NTH>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
   }
   load_img(0, a0, d0);
   for (int i = 0; i < a.ipw; i += 2) {
@@ -1063,20 +1069,21 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
 // grid: (image groups, 2*C/64 + 1 items, blocks of the run).  Items: conv1 in chunks of 64 input channels,
 // conv2, conv3 in chunks of 64 output channels.
 template <int C, int MID>
-__global__ void __launch_bounds__(RW_NT) k_res_wgrad(const ResWgArgs a) {
+__global__ void __launch_bounds__(rw_threads(MID)) k_res_wgrad(const ResWgArgs a) {
+  constexpr int NTH = rw_threads(MID);
   extern __shared__ __align__(16) unsigned char smem[];
   const ResBlock B = a.blocks[blockIdx.z];
   const int img0 = blockIdx.x * a.ipw;
   constexpr int NCH = C / 64;
   const int item = blockIdx.y;
   if (item < NCH)
-    res_wgrad_1x1<64, MID>(a, img0, B.x_off, C, item * 64, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0],
+    res_wgrad_1x1<64, MID, NTH>(a, img0, B.x_off, C, item * 64, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0],
                            B.dc1_off, MID, 0, a.grads + B.w_off[0], smem);
   else if (item == NCH)
-    res_wgrad_3x3<MID>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.dc2_off,
+    res_wgrad_3x3<MID, NTH>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.dc2_off,
                        a.grads + B.w_off[1], smem);
   else
-    res_wgrad_1x1<MID, 64>(a, img0, B.c2_off, MID, 0, B.stats_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2],
+    res_wgrad_1x1<MID, 64, NTH>(a, img0, B.c2_off, MID, 0, B.stats_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2],
                            B.gy_off, C, (item - NCH - 1) * 64, a.grads + B.w_off[2], smem);
 }
 
@@ -1341,15 +1348,16 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
 
 // weight gradients of a run of basic blocks: grid (image groups, 2 convolutions, blocks)
 template <int C>
-__global__ void __launch_bounds__(RW_NT) k_bb_wgrad(const ResWgArgs a) {
+__global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
+  constexpr int NTH = rw_threads(C);
   extern __shared__ __align__(16) unsigned char smem[];
   const ResBlock B = a.blocks[blockIdx.z];
   const int img0 = blockIdx.x * a.ipw;
   if (blockIdx.y == 0)
-    res_wgrad_3x3<C>(a, img0, B.x_off, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0], B.dc1_off,
+    res_wgrad_3x3<C, NTH>(a, img0, B.x_off, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0], B.dc1_off,
                      a.grads + B.w_off[0], smem);
   else
-    res_wgrad_3x3<C>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.gy_off,
+    res_wgrad_3x3<C, NTH>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.gy_off,
                      a.grads + B.w_off[1], smem);
 }
 
@@ -1472,15 +1480,15 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
   if (kind == 0) {
     const size_t lds = bb_wgrad_lds(C, a.H * a.W, a.W);
     const dim3 grid(groups, 2u, (unsigned)a.nblk);
-    if (C == 32) k_bb_wgrad<32><<<grid, RW_NT, lds, stream>>>(w);
-    else k_bb_wgrad<64><<<grid, RW_NT, lds, stream>>>(w);
+    if (C == 32) k_bb_wgrad<32><<<grid, rw_threads(32), lds, stream>>>(w);
+    else k_bb_wgrad<64><<<grid, rw_threads(64), lds, stream>>>(w);
     return hipGetLastError();
   }
   const size_t lds = wgrad_lds(C, MID, a.H * a.W, a.W);
   const dim3 grid(groups, (unsigned)(2 * (C / 64) + 1), (unsigned)a.nblk);
-  if (C == 128 && MID == 64) k_res_wgrad<128, 64><<<grid, RW_NT, lds, stream>>>(w);
-  else if (C == 128) k_res_wgrad<128, 32><<<grid, RW_NT, lds, stream>>>(w);
-  else k_res_wgrad<256, 64><<<grid, RW_NT, lds, stream>>>(w);
+  if (C == 128 && MID == 64) k_res_wgrad<128, 64><<<grid, rw_threads(64), lds, stream>>>(w);
+  else if (C == 128) k_res_wgrad<128, 32><<<grid, rw_threads(32), lds, stream>>>(w);
+  else k_res_wgrad<256, 64><<<grid, rw_threads(64), lds, stream>>>(w);
   return hipGetLastError();
 }
 

@@ -91,6 +91,8 @@ def _load():
     L.hpf_op_conv_wgrad.argtypes = [C.c_int, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     L.hpf_op_bn_relu_forward.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]
     L.hpf_op_bn_relu_backward.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    L.hpf_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.hpf_probe_mfma_bf16.argtypes = [vp, i32, i32, i32, vp]
     return L
 
 
@@ -104,7 +106,8 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_partition_set_profiling", "hpf_partition_profile_read", "hpf_partition_set_bn_momentum",
            "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference", "hpf_forward_inference_group",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
-           "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward"]
+           "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward",
+           "hpf_probe_copy", "hpf_probe_mfma_bf16"]
 
 
 def hpf_last_error() -> str:
@@ -278,6 +281,16 @@ def hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip, dx, dgamma, 
                             workspace_bytes, stream=0):
     _check(lib.hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip or None, dx, dgamma, dbeta, M, Cc,
                                        workspace, workspace_bytes, stream or None))
+
+
+def hpf_probe_copy(dst, src, nbytes, stream=0):
+    _check(lib.hpf_probe_copy(dst, src, nbytes, stream))
+
+
+def hpf_probe_mfma_bf16(sink, workgroups, iters, wide=False, stream=0):
+    """Returns the flops the launch performs."""
+    _check(lib.hpf_probe_mfma_bf16(sink, workgroups, iters, int(wide), stream))
+    return float(workgroups) * 4 * iters * 131072
 
 
 class Ops:

@@ -134,3 +134,60 @@ def test_bn_relu_forward_backward(env, oracle, mode, shape):
     assert e_mean < 1e-5 and e_inv < 1e-5
     tol = TOL[mode]
     assert e_a <= tol and e_dx <= tol and e_dg <= tol and e_db <= tol
+
+
+# ---------------------------------------------------------------------------------------------
+# the two measurement aids: results are checked, rates are bench.py's business
+# ---------------------------------------------------------------------------------------------
+def test_probe_copy_copies_and_rejects_overlap(env):
+    hpf, torch = env
+    n = (1 << 20) + 13                                   # ragged tail behind the 16-byte units
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n + 16, dtype=torch.uint8, device="cuda")
+    hpf.hpf_probe_copy(dst.data_ptr(), src.data_ptr(), n)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
+    with pytest.raises(hpf.HpfError):
+        hpf.hpf_probe_copy(src.data_ptr() + 16, src.data_ptr(), 64)
+
+
+@pytest.mark.parametrize("wide", [False, True], ids=["16x16x32", "32x32x16"])
+def test_probe_mfma_loop_computes_the_product_it_claims(env, wide):
+    """The register-only MFMA loops: every lane's result against the product of the operands the kernel builds.
+    16x16x32: lane l feeds row / column l%16 with k = 8*(l/16)..+7 and holds rows 4*(l/16)..+3 of column l%16;
+    32x32x16: lane l feeds row / column l%32 with k = 8*(l/32)..+7 and holds rows 8g + 4*(l/32) + v (g, v < 4)."""
+    hpf, torch = env
+    wgs, iters = 3, 3
+    sink = torch.full((wgs * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    flops = hpf.hpf_probe_mfma_bf16(sink.data_ptr(), wgs, iters, wide)
+    torch.cuda.synchronize()
+    assert flops == wgs * 4 * iters * 131072
+
+    def bf16_pairs(words):                               # uint32 words -> the bf16 values they pack, low half first
+        w = np.asarray(words, np.uint32)
+        lo = (w << np.uint32(16)).view(np.float32)
+        hi = (w & np.uint32(0xffff0000)).view(np.float32)
+        return np.stack([lo, hi], -1).reshape(-1)
+
+    n = 32 if wide else 16
+    A = np.zeros((n, 512 // n)); B = np.zeros((512 // n, n))
+    for lane in range(64):
+        seed = np.uint32(0x3f803f80 + ((lane & 7) << 16))
+        a = bf16_pairs([seed, seed ^ np.uint32(0x00010000), seed, seed ^ np.uint32(0x00000001)])
+        b = bf16_pairs([seed ^ np.uint32(0x80000000), seed, seed ^ np.uint32(0x00008000), seed])
+        k0 = (lane // n) * 8
+        A[lane % n, k0:k0 + 8] = a
+        B[k0:k0 + 8, lane % n] = b
+    D = A @ B
+    if wide:
+        rows = lambda l: [8 * g + 4 * (l // 32) + v for g in range(4) for v in range(4)]
+        tiles = 4
+    else:
+        rows = lambda l: [4 * (l // 16) + v for v in range(4)]
+        tiles = 8
+    want = np.array([tiles * iters * D[rows(l), l % n].sum() for l in range(64)])
+    got = sink.cpu().numpy().reshape(wgs * 4, 64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= 1e-6 * np.abs(want).max()
+    with pytest.raises(hpf.HpfError):
+        hpf.hpf_probe_mfma_bf16(sink.data_ptr(), 0, 1)
