@@ -32,6 +32,10 @@ constexpr int RES_NT = 512;            // threads per work-group (8 waves)
 constexpr int RES_NWV = RES_NT / 64;
 constexpr unsigned RES_SPIN_LIMIT = 1u << 19;
 
+// The wave's index within the work-group as a scalar: conditions on it become scalar branches instead of
+// compare / exec-mask sequences.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -306,7 +310,7 @@ __device__ __forceinline__ void tile_bn_relu(bf16_t* s, const float2* coef, int 
 template <int C, int MID, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
   // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
@@ -623,7 +627,7 @@ struct BwdLoads {
 template <int C, int MID, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
   // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
@@ -894,7 +898,7 @@ __device__ __forceinline__ void res_wgrad_1x1(const ResWgArgs& a, int img0, unsi
                                               unsigned long long st_off, const float* gamma, const float* beta,
                                               unsigned long long dy_off, int CTD, int nd0, float* dw, unsigned char* smem) {
   const int P = a.H * a.W, PS = P + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index(), fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   bf16_t* Ta = reinterpret_cast<bf16_t*>(smem);
   bf16_t* Td = Ta + (size_t)CA * PS;
   float2* coef = reinterpret_cast<float2*>(Td + (size_t)ND * PS);
@@ -973,7 +977,7 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
                                               const float* gamma, const float* beta, unsigned long long dy_off, float* dw,
                                               unsigned char* smem) {
   const int P = a.H * a.W, W = a.W, PS = P + 8, PSH = P + 2 * W + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index(), fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   bf16_t* Tsh = reinterpret_cast<bf16_t*>(smem);          // [3][MID][PSH]: a shifted by s-1 pixels along the row
   bf16_t* Td = Tsh + (size_t)3 * MID * PSH;               // [MID][PS]
   float2* coef = reinterpret_cast<float2*>(Td + (size_t)MID * PS);
@@ -1141,7 +1145,7 @@ __device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, 
 template <int C, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
@@ -1246,7 +1250,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
 template <int C, int PTW, bool PRE>
 __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   const int P = a.H * a.W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
