@@ -554,43 +554,26 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
 }
 
 // What the backward pass of one block reads from memory besides the weights, fetched into registers ahead
-// of use: the stashed c1 / c2 tiles and the BatchNorm tables.
-// XD (the three MID-wide tiles of the backward pass do not fit LDS next to the gradient stream: 128-64 blocks at 256
-// pixels): c1 / c2 are only needed at the accumulator positions of the BatchNorm backward, so they are read there
-// straight from memory (8 bytes per lane) instead of being staged as whole tiles.
-template <int C, int MID>
-constexpr bool res_bwd_direct() { return C == 128 && MID == 64; }
-
+// of use: c1 / c2 and the BatchNorm tables.  c1 / c2 are only needed at the accumulator positions of the
+// BatchNorm backward, so they are read there straight from memory (8 bytes per lane) instead of being staged
+// as whole tiles: two MID-wide tiles in LDS instead of four (128-64 blocks at 256 pixels would not fit
+// otherwise), no tile stores, and 4 % less time per launch on 128-32 blocks.
 template <int C, int MID, int PTW>
 struct BwdLoads {
-  static constexpr bool XD = res_bwd_direct<C, MID>();
-  static constexpr int NU = XD ? 1 : (256 * MID / 8 + RES_NT - 1) / RES_NT;   // 16-byte units per thread and tile, up to 256 pixels
-  uint4 c1[NU], c2[NU];
-  uint2 x1[XD ? PTW : 1][MID / 16], x2[XD ? PTW : 1][MID / 16];   // XD: c1 / c2 at this lane's accumulator positions
+  uint2 x1[PTW][MID / 16], x2[PTW][MID / 16];   // c1 / c2 at this lane's accumulator positions
   float4 t1, t2, t3;
   __device__ __forceinline__ void issue(const ResBlock& B, const ResCtx& cx, const float* params, int me, int P, int npt, int wave,
                                         int fr, int fq) {
     const bf16_t* g1 = cx.tensor(B.c1_off) + (size_t)me * P * MID;
     const bf16_t* g2 = cx.tensor(B.c2_off) + (size_t)me * P * MID;
-    if (XD) {
 #pragma unroll
-      for (int j = 0; j < (XD ? PTW : 1); ++j) {
-        const int pt = wave + j * RES_NWV;
-        const size_t row = (size_t)((pt < npt ? pt : 0) * 16 + fr) * MID + fq * 4;   // always a valid address
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+      const size_t row = (size_t)((pt < npt ? pt : 0) * 16 + fr) * MID + fq * 4;   // always a valid address
 #pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt) {
-          x1[j][nt] = *reinterpret_cast<const uint2*>(g1 + row + nt * 16);
-          x2[j][nt] = *reinterpret_cast<const uint2*>(g2 + row + nt * 16);
-        }
-      }
-    } else {
-      const int units = P * (MID / 8);
-#pragma unroll
-      for (int i = 0; i < NU; ++i) {
-        const int u = threadIdx.x + i * RES_NT;
-        const int uc = u < units ? u : 0;   // always a valid address; commit_tiles drops the surplus
-        c1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
-        c2[i] = *reinterpret_cast<const uint4*>(g2 + (size_t)uc * 8);
+      for (int nt = 0; nt < MID / 16; ++nt) {
+        x1[j][nt] = *reinterpret_cast<const uint2*>(g1 + row + nt * 16);
+        x2[j][nt] = *reinterpret_cast<const uint2*>(g2 + row + nt * 16);
       }
     }
     const int c = threadIdx.x;
@@ -602,20 +585,6 @@ struct BwdLoads {
     const float mean = stats[c], is = stats[Cc + c];
     const float2 ss = bn_scale_shift(mean, is, gamma[c], beta[c]);
     return make_float4(ss.x, ss.y, is, -mean * is);
-  }
-  __device__ __forceinline__ void commit_tiles(bf16_t* sm1, bf16_t* sm2, int P) const {
-    if (XD) return;
-    constexpr int U = MID / 8;
-    const int units = P * U;
-#pragma unroll
-    for (int i = 0; i < NU; ++i) {
-      const int u = threadIdx.x + i * RES_NT;
-      if (u < units) {
-        const int row = u / U, col = u - row * U;
-        *reinterpret_cast<uint4*>(sm1 + row * (MID + 8) + col * 8) = c1[i];
-        *reinterpret_cast<uint4*>(sm2 + row * (MID + 8) + col * 8) = c2[i];
-      }
-    }
   }
   __device__ __forceinline__ void commit_tables(float4* cf1, float4* cf2, float4* cf3) const {
     const int c = threadIdx.x;
@@ -639,10 +608,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   unsigned phase = 0;
 
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr bool XD = res_bwd_direct<C, MID>();           // c1 / c2 are not staged as tiles
   bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream, [P][XS]
-  bf16_t* sm1 = sdy + (size_t)P * XS;                     // c1 (XD: no such tile)
-  bf16_t* sm2 = XD ? sm1 : sm1 + (size_t)P * MS;          // c2, later dc1
+  bf16_t* sm2 = sdy + (size_t)P * XS;                     // dc1
   bf16_t* sdc = sm2 + (size_t)P * MS;                     // dc2
   float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * MS);
   float4* cf2 = cf1 + C;
@@ -661,19 +628,16 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   }
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
-    uint2 xc1[XD ? PTW : 1][MID / 16], xc2[XD ? PTW : 1][MID / 16];   // XD: c1 / c2 at this lane's accumulator positions
+    uint2 xc1[PTW][MID / 16], xc2[PTW][MID / 16];   // c1 / c2 at this lane's accumulator positions
     {   // one round trip to memory for everything the block reads up front
       BwdLoads<C, MID, PTW> ld;
       ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
       w3.load(a.packed + B.wd_off[2], C, fr, fk);
-      ld.commit_tiles(sm1, sm2, P);
       ld.commit_tables(cf1, cf2, cf3);
-      if (XD) {
 #pragma unroll
-        for (int j = 0; j < (XD ? PTW : 1); ++j)
+      for (int j = 0; j < PTW; ++j)
 #pragma unroll
-          for (int nt = 0; nt < MID / 16; ++nt) { xc1[j][nt] = ld.x1[j][nt]; xc2[j][nt] = ld.x2[j][nt]; }
-      }
+        for (int nt = 0; nt < MID / 16; ++nt) { xc1[j][nt] = ld.x1[j][nt]; xc2[j][nt] = ld.x2[j][nt]; }
     }
     __syncthreads();
     // ---- conv3 data gradient: da3[p][c] = sum_n dy[p][n] * W3[c][n]; then BN3 + ReLU backward -> dc2
@@ -701,8 +665,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         const int pt = wave + j * RES_NWV;
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) {
-          if (XD) xin[j][nt] = pt < npt ? xc2[XD ? j : 0][nt] : make_uint2(0u, 0u);
-          else xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm2 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+          xin[j][nt] = pt < npt ? xc2[j][nt] : make_uint2(0u, 0u);
         }
       }
       w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
@@ -742,8 +705,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         const int pt = wave + j * RES_NWV;
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) {
-          if (XD) xin[j][nt] = pt < npt ? xc1[XD ? j : 0][nt] : make_uint2(0u, 0u);
-          else xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(sm1 + (pt * 16 + fr) * MS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+          xin[j][nt] = pt < npt ? xc1[j][nt] : make_uint2(0u, 0u);
         }
       }
       w1.load(a.packed + B.wd_off[0], MID, fr, fk);
@@ -779,7 +741,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         }
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
-      float* gath = gath_own ? own : reinterpret_cast<float*>(XD ? sm2 : sm1);   // XD: dc1 left the tile above
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);   // dc1 left the tile above
       if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                    a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
@@ -1096,33 +1058,6 @@ __global__ void __launch_bounds__(rw_threads(MID)) k_res_wgrad(const ResWgArgs a
 // ResNet-20 / ResNet-110 family):  a1 = relu(bn1(x)); c1 = conv1(a1); a2 = relu(bn2(c1)); y = x + conv2(a2).
 // Two exchanges per block and direction.  ResBlock fields used: x, c1, y, gy, dc1, gx and entries 0 / 1 of the
 // per-BatchNorm / per-convolution arrays.
-template <int Cc>
-struct TwoTiles {   // two [P][Cc] tiles fetched in one round trip
-  static constexpr int NU = (256 * Cc / 8 + RES_NT - 1) / RES_NT;   // images of up to 256 pixels
-  uint4 t0[NU], t1[NU];
-  __device__ __forceinline__ void issue(const bf16_t* g0, const bf16_t* g1, int P) {
-    const int units = P * (Cc / 8);
-#pragma unroll
-    for (int i = 0; i < NU; ++i) {
-      const int u = threadIdx.x + i * RES_NT, uc = u < units ? u : 0;
-      t0[i] = *reinterpret_cast<const uint4*>(g0 + (size_t)uc * 8);
-      t1[i] = *reinterpret_cast<const uint4*>(g1 + (size_t)uc * 8);
-    }
-  }
-  __device__ __forceinline__ void commit(bf16_t* s0, bf16_t* s1, int P) const {
-    constexpr int U = Cc / 8;
-    const int units = P * U;
-#pragma unroll
-    for (int i = 0; i < NU; ++i) {
-      const int u = threadIdx.x + i * RES_NT;
-      if (u < units) {
-        const int row = u / U, col = u - row * U;
-        *reinterpret_cast<uint4*>(s0 + row * (Cc + 8) + col * 8) = t0[i];
-        *reinterpret_cast<uint4*>(s1 + row * (Cc + 8) + col * 8) = t1[i];
-      }
-    }
-  }
-};
 // dst = relu(src*scale + shift), tile to tile
 template <int Cc>
 __device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, const float2* coef, int P) {
@@ -1262,9 +1197,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
 
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream
-  bf16_t* s0 = sdy + (size_t)P * XS;                      // x   (BN1 input)
-  bf16_t* s1 = s0 + (size_t)P * XS;                       // c1  (BN2 input)
-  bf16_t* sdc = s1 + (size_t)P * XS;                      // dc1
+  bf16_t* sdc = sdy + (size_t)P * XS;                     // dc1
   float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * XS);
   float4* cf2 = cf1 + C;
   float* red = reinterpret_cast<float*>(cf2 + C);         // RES_NWV * 2*C floats
@@ -1273,13 +1206,14 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
   WFrags<9 * C / 32, C / 16, PRE> w2, w1;   // data-gradient operands [C][9*C]
 
-  auto xin_from = [&](const bf16_t* t, uint2 (&xin)[PTW][C / 16]) {
+  // x / c1 (the BatchNorm inputs) are needed only at this lane's accumulator positions: read there from memory
+  auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
 #pragma unroll
     for (int j = 0; j < PTW; ++j) {
       const int pt = wave + j * RES_NWV;
+      const size_t row = (size_t)((pt < npt ? pt : 0) * 16 + fr) * C + fq * 4;   // always a valid address
 #pragma unroll
-      for (int nt = 0; nt < C / 16; ++nt)
-        xin[j][nt] = pt < npt ? *reinterpret_cast<const uint2*>(t + (pt * 16 + fr) * XS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+      for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = *reinterpret_cast<const uint2*>(g + row + nt * 16);
     }
   };
   {
@@ -1288,16 +1222,16 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
   }
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
+    uint2 xc0[PTW][C / 16], xc1[PTW][C / 16];
     {   // one round trip to memory for everything the block reads up front
-      TwoTiles<C> ld;
-      ld.issue(cx.tensor(B.x_off) + (size_t)me * P * C, cx.tensor(B.c1_off) + (size_t)me * P * C, P);
+      at_acc(cx.tensor(B.c1_off) + (size_t)me * P * C, xc1);
+      at_acc(cx.tensor(B.x_off) + (size_t)me * P * C, xc0);
       const int c = tid < C ? tid : 0;
       const float4 t1 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0],
                                               a.params + B.beta_off[0], c, C);
       const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
       w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
-      ld.commit(s0, s1, P);
       if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
     }
     __syncthreads();
@@ -1309,7 +1243,10 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
       conv3x3_tile<C, PTW, true>(sdy, w2, a.H, a.W, npt, wave, fr, fk, acc);
-      xin_from(s1, xin);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
       w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
@@ -1330,8 +1267,13 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
       conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
-      xin_from(s0, xin);
-      float* gath = gath_own ? own : reinterpret_cast<float*>(s1);   // c1 is no longer read
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc0[j][nt] : make_uint2(0u, 0u);
+      // dc1 is read for the last time by the contraction above; the barrier inside the BatchNorm backward lies
+      // between that and the first write of the gathered words
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                    a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
@@ -1370,7 +1312,7 @@ size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
   const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16
                                 : (size_t)C * 8 + (size_t)RES_NWV * 2 * C * 4;
   *own = (size_t)nmem * 2 * C * 4 > tile ? 1 : 0;
-  return (backward ? 4 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
+  return (backward ? 2 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
 size_t bb_wgrad_lds(int C, int P, int W) {
   return (size_t)3 * C * (P + 2 * W + 8) * 2 + (size_t)C * (P + 8) * 2 + (size_t)C * 8;
@@ -1392,7 +1334,7 @@ size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
 size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
-  const size_t tiles = (size_t)P * (C + 8) * 2 + (C == 128 && MID == 64 ? 2 : 3) * (size_t)P * (MID + 8) * 2;
+  const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
   const size_t fixed = (size_t)(C + 2 * MID) * 16 + (size_t)RES_NWV * 2 * C * 4 + 4 * (size_t)C * 4;
   const size_t one_tile = (size_t)P * (MID + 8) * 2;
   *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
