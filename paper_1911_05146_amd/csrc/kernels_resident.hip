@@ -626,28 +626,22 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
   }
+  __syncthreads();   // the first contraction reads the tile right away
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
     uint2 xc1[PTW][MID / 16], xc2[PTW][MID / 16];   // c1 / c2 at this lane's accumulator positions
-    {   // one round trip to memory for everything the block reads up front
-      BwdLoads<C, MID, PTW> ld;
-      ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
-      w3.load(a.packed + B.wd_off[2], C, fr, fk);
-      ld.commit_tables(cf1, cf2, cf3);
-#pragma unroll
-      for (int j = 0; j < PTW; ++j)
-#pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt) { xc1[j][nt] = ld.x1[j][nt]; xc2[j][nt] = ld.x2[j][nt]; }
-    }
-    __syncthreads();
     // ---- conv3 data gradient: da3[p][c] = sum_n dy[p][n] * W3[c][n]; then BN3 + ReLU backward -> dc2
+    // One round trip to memory for everything the block reads up front; the weights are asked for first and the
+    // contraction, which needs nothing else, runs while the stashed tensors and the tables are on their way.
+    floatx4 acc3[PTW][MID / 16];
     {
-      floatx4 acc[PTW][MID / 16];
-      uint2 xin[PTW][MID / 16];
+      BwdLoads<C, MID, PTW> ld;
+      w3.load(a.packed + B.wd_off[2], C, fr, fk);
+      ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
-        for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < MID / 16; ++nt) acc3[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < C / 32; ++ks) {
 #pragma unroll
@@ -656,10 +650,20 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
           if (pt < npt) {
             const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(sdy + (pt * 16 + fr) * XS + ks * 32 + fk);
 #pragma unroll
-            for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(ks, nt), bfrag, acc[j][nt], 0, 0, 0);
+            for (int nt = 0; nt < MID / 16; ++nt) acc3[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(ks, nt), bfrag, acc3[j][nt], 0, 0, 0);
           }
         }
       }
+      ld.commit_tables(cf1, cf2, cf3);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < MID / 16; ++nt) { xc1[j][nt] = ld.x1[j][nt]; xc2[j][nt] = ld.x2[j][nt]; }
+    }
+    __syncthreads();
+    {
+      floatx4 (&acc)[PTW][MID / 16] = acc3;
+      uint2 xin[PTW][MID / 16];
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
