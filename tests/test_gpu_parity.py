@@ -311,6 +311,32 @@ def test_streams_give_the_same_result_as_one_stream(gpu, oracle):
     assert rel_err(b["grad"], a["grad"]) < 1e-5          # gradient sums: fp32 atomics, order may differ
 
 
+def test_directions_on_different_streams_wait_for_each_other(gpu, oracle):
+    """Forward group on one stream, backward group on a second, the clearing of the gradient buffer on a third:
+    the library's events order them (waits are only skipped between calls on one and the same stream)."""
+    import torch
+    from parity import device_inputs, run_gpu_step, rel_err
+    from paper_1911_05146_amd import hpf
+    spec = W.with_microbatching(W.config(3), 8, 4, loss_divisor=32)
+    inp = W.make_inputs(spec)
+    _, ref = run_gpu_step(spec, inp, "bf16", grouped=True)
+    _, t = device_inputs(spec, inp, "bf16")
+    part = hpf.Partition(spec, inp.params, hpf.HPF_BF16)
+    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):                                   # several batches: events are re-recorded on changing streams
+        part.grad_accum_zero(stream=sc)
+        outs = part.forward_microbatches(0, t["act_in"], None, stream=sa)
+        errs = part.backward_microbatches(0, 4, t["err_in"], stream=sb)
+        sa, sb, sc = sb, sc, sa
+    grad = part.grad_accum_read()
+    torch.cuda.synchronize()
+    for x, y in zip(outs + errs, ref["act_out"] + ref["err_out"]):
+        assert np.array_equal(x.float().cpu().numpy(), y)
+    assert rel_err(grad, ref["grad"]) < 1e-5             # one batch's sums: the buffer was cleared before each
+    part.close()
+
+
 def test_two_batches_accumulate_zero_and_step(gpu, oracle):
     """Gradient buffer life cycle over consecutive batches on one handle."""
     from parity import run_gpu_step, rel_err
