@@ -134,6 +134,9 @@ struct ResBlock {
   unsigned long long wf_off[3], wd_off[3];   // packed bf16 weights (elements)
   unsigned long long w_off[3];               // fp32 masters / gradients [tap][Cin][Cout] (floats)
   unsigned long long gamma_off[3], beta_off[3];   // floats into the parameter / gradient vectors
+  // {sum dz (C floats), sum dz*xhat (C floats)} of the three BatchNorms over the micro-batch (bytes into its region):
+  // written by the backward launch, added into the gradients of beta and gamma by the weight-gradient launch
+  unsigned long long dgb_off[3];
 };
 struct ResArgs {
   const ResBlock* blocks;   // device table of the run

@@ -362,6 +362,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
           rb.stats_off[q] = p.bn[q].stats_off;
           rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off; rb.w_off[q] = p.cv[q].w_off;
           rb.gamma_off[q] = p.bn[q].g_off; rb.beta_off[q] = p.bn[q].b_off;
+          rb.dgb_off[q] = alloc(2 * (size_t)p.bn[q].C * sizeof(float)).off;
         }
         P.res_blocks.push_back(rb);
       }

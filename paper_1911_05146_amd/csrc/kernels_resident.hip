@@ -474,12 +474,14 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
 //   dz = da * [z > 0];  sums over the micro-batch {sum dz, sum dz*xhat} (all-gather);
 //   out = scale * (dz - sum_dz/M - xhat * sum_dzxhat/M)  =  a1*dz + a2*x + a3  with per-channel a1..a3
 // cf[c] = {scale, shift, invstd, -mean*invstd}; xin = the BatchNorm input at the same positions; tab = Cc
-// float4 of LDS for {a1, a2, a3}.  fin(j, nt, out) receives the result tile by tile.  Member 0 adds the sums
-// into the gradients of beta and gamma.
+// float4 of LDS for {a1, a2, a3}.  fin(j, nt, out) receives the result tile by tile.  dgb (member 0 only,
+// else null) receives the micro-batch sums {sum dz (Cc), sum dz*xhat (Cc)}: the gradients of beta and gamma, which
+// the weight-gradient launch adds into the gradient buffer (as atomics here they cost member 0, and with it every
+// exchange of its micro-batch, 13 us per launch of 21 blocks).
 template <int Cc, int PTW, class Fin>
 __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf_,
                                                 int npt, int wave, int fr, int fq, float* red, float4* tab_, float* gath,
-                                                u64* slot, int me, int nmem, int P, unsigned tag, float* g_gamma, float* g_beta,
+                                                u64* slot, int me, int nmem, int P, unsigned tag, float* dgb,
                                                 int* abort_flag, Fin&& fin) {
   constexpr int NTL = Cc / 16;
   const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(cf_, 16));
@@ -528,7 +530,7 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
     sb = row_sum<CR>(sb);
     sg = row_sum<CR>(sg);
     if (part == 0) {
-      if (me == 0) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
+      if (dgb) { dgb[c] = sb; dgb[Cc + c] = sg; }
       const float4 k = cf[c];
       // scale*(dz - sb/M - (x*is + nm)*sg/M)
       tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
@@ -675,7 +677,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                     a.grads + B.gamma_off[2], a.grads + B.beta_off[2], a.abort_flag,
+                                     me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[2]) : nullptr, a.abort_flag,
                                      [&](int j, int nt, const floatx4& out) {
                                        *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
                                      }))
@@ -715,7 +717,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       w1.load(a.packed + B.wd_off[0], MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                     a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag,
+                                     me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
                                      [&](int j, int nt, const floatx4& out) {
                                        *reinterpret_cast<uint2*>(sm2 + ((wave + j * RES_NWV) * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(out);
                                      }))
@@ -747,7 +749,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);   // dc1 left the tile above
       if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
+                                   me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[0]) : nullptr, a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
                                      const uint2 d = *q;
@@ -839,6 +841,7 @@ __device__ __forceinline__ uint4 lanes_down4(const uint4& v) {
 struct ResWgArgs {
   const ResBlock* blocks;
   int nmem, ipw, H, W;       // images per micro-batch, images per work-group (divides nmem), image shape
+  int ngroup;                // micro-batches in the launch
   PtrTab base, act_in, err_in;
   const float* params;
   float* grads;
@@ -1042,6 +1045,23 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
   }
 }
 
+// Gradients of beta and gamma of one BatchNorm (Cc channels) of a block: the backward launch left {sum dz,
+// sum dz*xhat} per micro-batch at dgb_off; one work-group per block adds them up over the micro-batches of the
+// launch.  The loads of a lane are issued before the first use: one trip to memory.
+template <int NTH>
+__device__ __forceinline__ void add_bn_param_grads(const ResWgArgs& a, unsigned long long dgb_off, float* g_beta, float* g_gamma, int Cc) {
+  for (int c = threadIdx.x; c < 2 * Cc; c += NTH) {
+    float v[MAX_GROUP];
+#pragma unroll
+    for (int z = 0; z < MAX_GROUP; ++z)
+      v[z] = z < a.ngroup ? reinterpret_cast<const float*>((const char*)pick(a.base, z) + dgb_off)[c] : 0.f;
+    float s = 0.f;
+#pragma unroll
+    for (int z = 0; z < MAX_GROUP; ++z) s += v[z];
+    atomicAdd(c < Cc ? g_beta + c : g_gamma + (c - Cc), s);
+  }
+}
+
 // grid: (image groups, 2*C/64 + 1 items, blocks of the run).  Items: conv1 in chunks of 64 input channels,
 // conv2, conv3 in chunks of 64 output channels.
 template <int C, int MID>
@@ -1055,10 +1075,15 @@ __global__ void __launch_bounds__(rw_threads(MID)) k_res_wgrad(const ResWgArgs a
   if (item < NCH)
     res_wgrad_1x1<64, MID, NTH>(a, img0, B.x_off, C, item * 64, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0],
                            B.dc1_off, MID, 0, a.grads + B.w_off[0], smem);
-  else if (item == NCH)
+  else if (item == NCH) {
     res_wgrad_3x3<MID, NTH>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.dc2_off,
                        a.grads + B.w_off[1], smem);
-  else
+    if (blockIdx.x == 0) {
+      add_bn_param_grads<NTH>(a, B.dgb_off[0], a.grads + B.beta_off[0], a.grads + B.gamma_off[0], C);
+      add_bn_param_grads<NTH>(a, B.dgb_off[1], a.grads + B.beta_off[1], a.grads + B.gamma_off[1], MID);
+      add_bn_param_grads<NTH>(a, B.dgb_off[2], a.grads + B.beta_off[2], a.grads + B.gamma_off[2], MID);
+    }
+  } else
     res_wgrad_1x1<MID, 64, NTH>(a, img0, B.c2_off, MID, 0, B.stats_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2],
                            B.gy_off, C, (item - NCH - 1) * 64, a.grads + B.w_off[2], smem);
 }
@@ -1260,7 +1285,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   a.grads + B.gamma_off[1], a.grads + B.beta_off[1], a.abort_flag,
+                                   me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(out);
                                    }))
@@ -1285,7 +1310,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       // between that and the first write of the gathered words
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   a.grads + B.gamma_off[0], a.grads + B.beta_off[0], a.abort_flag,
+                                   me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[0]) : nullptr, a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
                                      const uint2 d = *q;
@@ -1309,10 +1334,14 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ResBlock B = a.blocks[blockIdx.z];
   const int img0 = blockIdx.x * a.ipw;
-  if (blockIdx.y == 0)
+  if (blockIdx.y == 0) {
     res_wgrad_3x3<C, NTH>(a, img0, B.x_off, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0], B.dc1_off,
                      a.grads + B.w_off[0], smem);
-  else
+    if (blockIdx.x == 0) {
+      add_bn_param_grads<NTH>(a, B.dgb_off[0], a.grads + B.beta_off[0], a.grads + B.gamma_off[0], C);
+      add_bn_param_grads<NTH>(a, B.dgb_off[1], a.grads + B.beta_off[1], a.grads + B.gamma_off[1], C);
+    }
+  } else
     res_wgrad_3x3<C, NTH>(a, img0, B.c1_off, B.stats_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], B.gy_off,
                      a.grads + B.w_off[1], smem);
 }
@@ -1432,6 +1461,7 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
   for (int k = 8; k >= 1; k >>= 1)
     if (a.nmem % k == 0) { w.ipw = k; break; }
   w.base = a.base; w.act_in = a.act_in; w.err_in = a.err_in; w.params = a.params; w.grads = a.grads;
+  w.ngroup = g;
   const unsigned groups = (unsigned)(g * a.nmem / w.ipw);
   if (kind == 0) {
     const size_t lds = bb_wgrad_lds(C, a.H * a.W, a.W);
