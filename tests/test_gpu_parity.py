@@ -166,6 +166,13 @@ def test_image_resident_runs_edge_cases(gpu, oracle):
     check(oracle, _bottleneck_run("resident-single-image", 128, 32, 16, 2, 1, 3), "bf16", strict=True, beta_shift=6.0, grouped=True)
     check(oracle, _bottleneck_run("resident-odd-microbatch", 128, 32, 8, 2, 5, 2), "bf16", strict=True, beta_shift=6.0)
     check(oracle, _bottleneck_run("resident-more-images-than-cus", 128, 32, 8, 1, 260, 1), "bf16", strict=True, beta_shift=6.0)
+    # 7 micro-batches of 48 images in one group call: at most 5 fit the chip at once, so the call runs as launches of
+    # 5 and 2 micro-batches; weight-gradient groups of 8 images
+    check(oracle, _bottleneck_run("resident-chunked-group-call", 128, 32, 8, 2, 48, 7, seed=47), "bf16", strict=True, beta_shift=6.0,
+          grouped=True)
+    # 12 images per micro-batch: weight-gradient groups of 4 images, 3 members per channel subset in the merges
+    check(oracle, _bottleneck_run("resident-microbatch-12", 128, 64, 8, 2, 12, 3, seed=48), "bf16", strict=True, beta_shift=6.0,
+          grouped=True)
     spec = _bottleneck_run("resident-level-switch", 128, 32, 8, 2, 4, 2, seed=41)
     inp = W.make_inputs(spec, randomize_affine=True)
     _, r2 = run_gpu_step(spec, inp, "bf16", keep=True, fusion=2)
