@@ -230,7 +230,9 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
  *   micro-batch is between forward and backward.
  * hpf_forward_inference_group: the same for `count` micro-batches (1 .. min(num_microbatches, 8)) in one call,
  *   every layer launched once for all of them; arguments are (host) arrays of `count` (dev) pointers, the skip
- *   arrays NULL exactly when the single-call arguments would be. */
+ *   arrays NULL exactly when the single-call arguments would be.
+ *   At fusion level 2 the runs of blocks described there go through inference variants of the same kernels
+ *   (one work-group per image; nothing is exchanged, so these launches are not serialised). */
 hpf_status hpf_partition_set_bn_momentum(hpf_partition* p, float momentum);
 hpf_status hpf_bn_running_read(hpf_partition* p, float* host_dst, size_t n_floats);
 hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t n_floats);

@@ -137,6 +137,7 @@ struct ResBlock {
   // {sum dz (C floats), sum dz*xhat (C floats)} of the three BatchNorms over the micro-batch (bytes into its region):
   // written by the backward launch, added into the gradients of beta and gamma by the weight-gradient launch
   unsigned long long dgb_off[3];
+  unsigned long long run_off[3];             // running {mean(C), variance(C)} of the three BatchNorms (floats)
 };
 struct ResArgs {
   const ResBlock* blocks;   // device table of the run
@@ -148,6 +149,7 @@ struct ResArgs {
   PtrTab base;              // micro-batch regions of the group members (grid z)
   PtrTab act_in, act_out, err_in, err_out;   // caller buffers per member (null where the pass does not use them)
   const float* params;
+  const float* running;     // running BatchNorm statistics (inference launches)
   const bf16_t* packed;
   float* grads;
   unsigned long long xchg_off;   // bytes into the region: exchange words, resident_xchg_bytes()
@@ -166,6 +168,9 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
 // Weight gradients of all blocks of the run (after the backward launch): reads the stash and the gradient
 // tensors the backward launch wrote, adds into a.grads.
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream);
+// Inference forward of a run (BatchNorm by the running statistics in a.running): only the output of the last block
+// is written; no exchange, so there is no limit on the work-groups of a launch (g <= MAX_GROUP micro-batches).
+hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream);
 
 hipError_t launch_conv_f32(int mode, int g, const PtrTab& src, const float* w_hwio, const PtrTab& out, const PtrTab& add,
                            const ConvGeom& geom, hipStream_t stream);

@@ -363,6 +363,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
           rb.wf_off[q] = p.cv[q].wf_off; rb.wd_off[q] = p.cv[q].wd_off; rb.w_off[q] = p.cv[q].w_off;
           rb.gamma_off[q] = p.bn[q].g_off; rb.beta_off[q] = p.bn[q].b_off;
           rb.dgb_off[q] = alloc(2 * (size_t)p.bn[q].C * sizeof(float)).off;
+          rb.run_off[q] = p.bn[q].run_off;
         }
         P.res_blocks.push_back(rb);
       }
@@ -687,7 +688,7 @@ struct Ctx {
       a.act_in.p[i] = const_cast<void*>(act_in[i]); a.act_out.p[i] = act_out[i];
       a.err_in.p[i] = const_cast<void*>(err_in[i]); a.err_out.p[i] = err_out[i];
     }
-    a.params = h->params(); a.packed = h->packed(); a.grads = h->grads();
+    a.params = h->params(); a.running = h->running(); a.packed = h->packed(); a.grads = h->grads();
     a.xchg_off = P.xchg_off; a.tag_off = P.tag_off; a.abort_flag = h->abort_flag();
     return a;
   }
@@ -703,6 +704,15 @@ struct Ctx {
     res_figures(r, px, &st, &fl);
     seg(PROF_RES_FWD, img * 2.0 * (px * r.C + r.count * st), img * r.count * fl);
     chk(launch_resident_forward(r.kind, g, r.C, r.MID, res_args(r), s), "resident_forward");
+    seg_end();
+  }
+  void res_inference(const Plan::ResRun& r) {
+    const BlockPlan& p0 = h->P.bp[r.first];
+    const double img = (double)g * h->P.d.microbatch, px = (double)p0.h_in * p0.w_in;
+    double st, fl;
+    res_figures(r, px, &st, &fl);
+    seg(PROF_RES_FWD, img * 2.0 * 2.0 * px * r.C, img * r.count * fl);   // run input read, run output written
+    chk(launch_resident_inference(r.kind, g, r.C, r.MID, res_args(r), s), "resident_inference");
     seg_end();
   }
   void res_backward(const Plan::ResRun& r) {
@@ -738,7 +748,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
   int part_rows = 0;   // statistics partial rows pending for the next BatchNorm (written by the last conv)
-  const bool resident = c.h->resident() && !c.inference;
+  const bool resident = c.h->resident();
   c.seg_same(PROF_OTHER_FWD);
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
@@ -755,7 +765,8 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   for (size_t bi = 0; bi < P.bp.size(); ++bi) {
     if (resident && P.run_at[bi] >= 0) {   // the whole run in one launch; it takes its own statistics
       const Plan::ResRun& r = P.runs[P.run_at[bi]];
-      c.res_forward(r);
+      if (c.inference) c.res_inference(r);
+      else c.res_forward(r);
       bi += r.count - 1;
       part_rows = 0;
       continue;

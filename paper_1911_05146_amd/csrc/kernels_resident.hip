@@ -324,10 +324,20 @@ __device__ __forceinline__ void tile_bn_relu(bf16_t* s, const float2* coef, int 
   }
 }
 
+// Inference: a BatchNorm is the fixed map of its running statistics run = {mean(Cc), variance(Cc)}: no
+// statistics are taken and nothing is exchanged.  Ends with a barrier.
+template <int Cc>
+__device__ __forceinline__ void running_coef(float2* coef, const float* run, const float* gamma, const float* beta, float eps) {
+  for (int c = threadIdx.x; c < Cc; c += RES_NT) coef[c] = bn_scale_shift(run[c], 1.0f / sqrtf(run[Cc + c] + eps), gamma[c], beta[c]);
+  __syncthreads();
+}
+
 // ------------------------------------------------------------------------------------------ forward
 // PTW: pixel tiles (16 pixels) per wave, i.e. images of up to 16*PTW*RES_NWV pixels.
 // PRE: weight fragments are preloaded into registers ahead of the exchanges (needs the register room).
-template <int C, int MID, int PTW, bool PRE>
+// INFER: inference forward (BatchNorm by running statistics): the images are independent, nothing is stashed and
+// only the output of the last block is written.
+template <int C, int MID, int PTW, bool PRE, bool INFER = false>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
@@ -362,11 +372,15 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
     w1.load(a.packed + B0.wf_off[0], C, fr, fk);
     __syncthreads();
-    stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
-    if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
-    ++phase;
-    merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
-                  me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+    if (INFER) {
+      running_coef<C>(coefC, a.running + B0.run_off[0], a.params + B0.gamma_off[0], a.params + B0.beta_off[0], a.eps);
+    } else {
+      stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
+      if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+      ++phase;
+      merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+    }
   }
 
   for (int bi = 0; bi < a.nblk; ++bi) {
@@ -408,12 +422,16 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     }
     w2.load(a.packed + B.wf_off[1], 9 * MID, fr, fk);
     __syncthreads();
-    stats_publish<MID>(smA, P, red, slot(), me, tag0 + 1u + phase);
-    if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
-    tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // after the polls (measured: 2 % faster than before them)
-    ++phase;
-    merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
-                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    if (INFER) {
+      running_coef<MID>(coefM, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
+    } else {
+      stats_publish<MID>(smA, P, red, slot(), me, tag0 + 1u + phase);
+      if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
+      tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // after the polls (measured: 2 % faster than before them)
+      ++phase;
+      merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
+                      me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    }
     tile_bn_relu<MID>(smA, coefM, P);   // once, not per filter tap
     __syncthreads();
     // ---- conv2 (3x3, MID -> MID)
@@ -435,12 +453,16 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     }
     w3.load(a.packed + B.wf_off[2], MID, fr, fk);
     __syncthreads();
-    stats_publish<MID>(smB, P, red, slot(), me, tag0 + 1u + phase);
-    if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
-    tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
-    ++phase;
-    merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
-                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
+    if (INFER) {
+      running_coef<MID>(coefM, a.running + B.run_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2], a.eps);
+    } else {
+      stats_publish<MID>(smB, P, red, slot(), me, tag0 + 1u + phase);
+      if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
+      tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
+      ++phase;
+      merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
+                      me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
+    }
     // ---- conv3 (1x1, MID -> C) on relu(bn3(c2)) + residual: y = x + branch, written over x in LDS
     {
       bf16x8 bfrag[PTW][MID / 32];
@@ -476,6 +498,11 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
     if (more) w1.load(a.packed + Bn.wf_off[0], C, fr, fk);
     __syncthreads();
+    if (INFER) {
+      if (more) running_coef<C>(coefC, a.running + Bn.run_off[0], a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], a.eps);
+      else tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+      continue;
+    }
     if (more) stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);   // while the records travel (measured: better before the polls)
     if (more) {
@@ -486,7 +513,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     }
   }
   // every member has read the counter before it took part in the first exchange, which member 0 has left
-  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+  if (!INFER && me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
 // ------------------------------------------------------------------------------------------ backward
@@ -1132,7 +1159,7 @@ __device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, 
   }
 }
 
-template <int C, int PTW, bool PRE>
+template <int C, int PTW, bool PRE, bool INFER = false>
 __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
@@ -1171,11 +1198,15 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
     w1.load(a.packed + B0.wf_off[0], 9 * C, fr, fk);
     __syncthreads();
-    stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
-    if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
-    ++phase;
-    merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coef,
-                  me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+    if (INFER) {
+      running_coef<C>(coef, a.running + B0.run_off[0], a.params + B0.gamma_off[0], a.params + B0.beta_off[0], a.eps);
+    } else {
+      stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
+      if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
+      ++phase;
+      merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coef,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+    }
   }
   for (int bi = 0; bi < a.nblk; ++bi) {
     const ResBlock B = a.blocks[bi];
@@ -1192,12 +1223,16 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     }
     w2.load(a.packed + B.wf_off[1], 9 * C, fr, fk);
     __syncthreads();
-    stats_publish<C>(sB, P, red, slot(), me, tag0 + 1u + phase);
-    tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
-    if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;   // sA is free: conv1 is done
-    ++phase;
-    merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
-                  me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    if (INFER) {
+      running_coef<C>(coef, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
+    } else {
+      stats_publish<C>(sB, P, red, slot(), me, tag0 + 1u + phase);
+      tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
+      if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;   // sA is free: conv1 is done
+      ++phase;
+      merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    }
     tile_bn_relu<C>(sB, coef, P);
     __syncthreads();
     {   // ---- conv2 (3x3) on relu(bn2(c1)) + shortcut, written over x
@@ -1225,6 +1260,11 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
     if (more) w1.load(a.packed + Bn.wf_off[0], 9 * C, fr, fk);
     __syncthreads();
+    if (INFER) {
+      if (more) running_coef<C>(coef, a.running + Bn.run_off[0], a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], a.eps);
+      else tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+      continue;
+    }
     if (more) stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
     tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
     if (more) {
@@ -1234,7 +1274,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
     }
   }
-  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+  if (!INFER && me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
 template <int C, int PTW, bool PRE>
@@ -1456,6 +1496,11 @@ hipError_t resident_prepare() {
                         reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* infer[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, true>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, true>),
+                         reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, true>), reinterpret_cast<const void*>(k_bb_forward<32, 2, true, true>),
+                         reinterpret_cast<const void*>(k_bb_forward<64, 1, false, true>)};
+  for (const void* f : infer)
+    if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   return e;
 }
 
@@ -1471,6 +1516,21 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   if (C == 128 && MID == 64) return launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
+}
+
+// Inference forward of a run: the images are independent (no exchange), so any number of work-groups may queue.
+hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP || !a.running) return hipErrorInvalidValue;
+  int own = 0;
+  if (kind == 0) {
+    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 32) return launch_res(k_bb_forward<32, 2, true, true>, lds, 0, g, a, stream);
+    return launch_res(k_bb_forward<64, 1, false, true>, lds, 0, g, a, stream);
+  }
+  const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
+  if (C == 128 && MID == 64) return launch_res(k_res_forward<128, 64, 2, false, true>, lds, 0, g, a, stream);
+  if (C == 128) return launch_res(k_res_forward<128, 32, 2, true, true>, lds, 0, g, a, stream);
+  return launch_res(k_res_forward<256, 64, 1, false, true>, lds, 0, g, a, stream);
 }
 
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {

@@ -27,7 +27,11 @@ def small_specs():
     cut = W.PartitionSpec(name="cut", in_h=8, in_w=8, in_c=32,                              # tail of one block, head of the next
                           blocks=(W.Block(W.BOTTLENECK, 64, 32, 128, 2), W.Block(W.BOTTLENECK, 128, 32, 128, 1)),
                           microbatch=3, num_microbatches=2, seed=10, first_from=2, last_to=2)
-    return {"resnet20": r20, "bottleneck_run": bott, "cut_partition": cut}
+    wide = W.PartitionSpec(name="wide", in_h=16, in_w=16, in_c=128,                        # resident runs of the two other shapes
+                           blocks=(W.Block(W.BOTTLENECK, 128, 64, 128, 1),) * 2 + (W.Block(W.BOTTLENECK, 128, 64, 256, 2),) +
+                                  (W.Block(W.BOTTLENECK, 256, 64, 256, 1),) * 2,
+                           microbatch=3, num_microbatches=2, seed=11)
+    return {"resnet20": r20, "bottleneck_run": bott, "cut_partition": cut, "wide_runs": wide}
 
 
 def train_batch(part, spec, t, grouped):
@@ -46,7 +50,7 @@ def train_batch(part, spec, t, grouped):
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
 @pytest.mark.parametrize("grouped", [False, True])
-@pytest.mark.parametrize("name", ["resnet20", "bottleneck_run", "cut_partition"])
+@pytest.mark.parametrize("name", ["resnet20", "bottleneck_run", "cut_partition", "wide_runs"])
 def test_running_statistics_and_inference_against_oracle(gpu, oracle, name, grouped, mode):
     import torch
     hpf = gpu
