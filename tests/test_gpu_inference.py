@@ -189,3 +189,36 @@ def test_running_statistics_with_one_stream_per_microbatch(gpu, oracle):
     assert err <= 2e-2
     part.close()
     opart.close()
+
+
+def test_inference_group_larger_than_the_chip(gpu, oracle):
+    """8 micro-batches of 48 images in one inference call: 384 work-groups of the image-resident kernel on 256
+    CUs.  The images are independent at inference, so the work-groups simply queue (a training launch of that size
+    is split); the group call equals the single calls, and one micro-batch is checked against the oracle."""
+    import torch
+    hpf = gpu
+    blk = W.Block(W.BOTTLENECK, 128, 32, 128, 1)
+    spec = W.PartitionSpec(name="infer-large-group", in_h=8, in_w=8, in_c=128, blocks=(blk,) * 3, microbatch=48,
+                           num_microbatches=8, seed=12)
+    inp = W.make_inputs(spec, randomize_affine=True)
+    dev = torch.device("cuda:0")
+    act = [parity.bf16_round(a) for a in inp.act_in]
+    xs = [torch.from_numpy(a).to(dev, torch.bfloat16) for a in act]
+    part = hpf.Partition(spec, inp.params, hpf.HPF_BF16)
+    opart = oracle.OraclePartition(spec, inp.params, np.float32, storage="bf16")
+    rng = np.random.default_rng(5)
+    run = rng.uniform(0.5, 1.5, opart.bn_running().size)                             # means and variances in [0.5, 1.5]
+    opart.set_bn_running(run)
+    part.bn_running_write(run)
+    grp = part.forward_inference_group(xs, None)
+    torch.cuda.synchronize()
+    for i in (0, 5, 7):
+        single = part.forward_inference(xs[i], None)
+        torch.cuda.synchronize()
+        assert torch.equal(single, grp[i])
+    ref = opart.infer(act[5], None)
+    e = parity.rel_err(grp[5].float().cpu().numpy(), ref)
+    print(f"[parity] inference output {e:.2e}", flush=True)
+    assert e <= 2e-2
+    part.close()
+    opart.close()
