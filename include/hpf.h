@@ -25,7 +25,9 @@
  *    Wfc [C][classes], bfc.
  *  - forward / backward / grad_accum_zero / sgd_step only enqueue work and return; ordering
  *    between calls issued on different streams (micro-batches may each use their own stream) is
- *    handled inside the library with events.  grad_accum_read to host memory blocks until done.
+ *    handled inside the library with events (two calls on one and the same stream rely on the
+ *    stream's own order).  A stream handed to a call must stay alive until the work of the batch
+ *    it took part in has completed.  grad_accum_read to host memory blocks until done.
  *  - Every call returns a status; nothing throws or aborts.  A call that returns HPF_EINVAL,
  *    HPF_ESTATE or HPF_EUNSUPPORTED has had no effect.  hpf_last_error() gives a message.
  *  - Call order per batch (else HPF_ESTATE): forward(mb) once, then backward(mb) once, for every
