@@ -269,6 +269,38 @@ hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entri
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
 
+/* Test and debugging aid: reads one of the tensors that back-propagation keeps per micro-batch (paper Section
+ * "Implementing Distributed Back-Propagation": the layer inputs of the forward pass and the partial errors of
+ * Eq. 5-7 that the weight gradients are formed from), so that every layer of a deep partition can be checked on
+ * its own.  Valid after backward(mb) and before the next batch's forward(mb) overwrites the region.
+ *  unit    -1: the stem; 0 .. n_blocks-1: a residual block; n_blocks: the head.
+ *  tensor  one of hpf_tensor_id; tensors of compute_dtype are copied as stored (bf16 bits or fp32), HPF_T_STATS*
+ *          as 2*C values {mean[C], invstd[C]} of the BatchNorm in front of convolution 0 / 1 / 2 (of the head's
+ *          BatchNorm: HPF_T_STATS0), float in bf16 mode and double in the fp32 check mode.
+ *          stem: HPF_T_Y (its output), HPF_T_GY (gradient w.r.t. it); head: HPF_T_X (its input), HPF_T_GX
+ *          (gradient w.r.t. its input), HPF_T_STATS0.
+ *  host_dst / bytes  (host) destination and its exact size (else HPF_EINVAL).  host_dst == NULL asks only for
+ *          the size and the place: *bytes_needed (if non-NULL) and *where are set, nothing is copied.
+ *  where   receives 0 when the tensor was copied; when the tensor lives in a caller buffer of that micro-batch
+ *          nothing is copied and it receives 1: act_in, 2: act_out, 3: err_in, 4: err_out, 5: skip_in,
+ *          6: skip_out, 7: skip_err_in, 8: skip_err_out.
+ * HPF_EINVAL for a tensor the partition does not keep (a layer it does not hold, an activation that the
+ * convolutions recompute instead of storing).  Synchronises the device. */
+typedef enum {
+  HPF_T_X = 0,    /* block input (BatchNorm-1 input) */
+  HPF_T_C1 = 1,   /* output of convolution 0 */
+  HPF_T_C2 = 2,   /* output of convolution 1 (bottleneck) */
+  HPF_T_Y = 3,    /* block output */
+  HPF_T_GY = 4,   /* gradient w.r.t. the block output */
+  HPF_T_DC1 = 5,  /* gradient w.r.t. c1 */
+  HPF_T_DC2 = 6,  /* gradient w.r.t. c2 */
+  HPF_T_GX = 7,   /* gradient w.r.t. the block input */
+  HPF_T_STATS0 = 8, HPF_T_STATS1 = 9, HPF_T_STATS2 = 10,
+  HPF_T_A0 = 11, HPF_T_A1 = 12, HPF_T_A2 = 13   /* relu(bn_j(.)) where the partition stores it */
+} hpf_tensor_id;
+hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t tensor, void* host_dst, size_t bytes,
+                          size_t* bytes_needed, int32_t* where);
+
 /* Frees the host-side handle (after synchronising the device).  The arena is the caller's. */
 void hpf_partition_destroy(hpf_partition* p);
 
@@ -307,6 +339,15 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
                                    const float* beta, const void* stats, const void* skip, void* dx,
                                    float* dgamma, float* dbeta, int32_t M, int32_t C, void* workspace,
                                    size_t workspace_bytes, void* hip_stream);
+
+/* hpf_op_bn_relu_forward for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results; the reduction
+ * partials go to an array built into the library (4 MiB per GPU the library runs on, held until the process
+ * ends) instead of a caller workspace, so the call allocates nothing.  Limit: C <= 1024 (else HPF_EUNSUPPORTED).
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or threads)
+ * race; calls on one stream, or otherwise ordered, are safe.  Nothing in the array needs clearing between calls. */
+hpf_status hpf_op_bn_relu_forward_noalloc(hpf_dtype dtype, const void* x, const float* gamma, const float* beta,
+                                          float eps, void* a, void* stats, int32_t M, int32_t C, void* hip_stream);
 
 /* ---- Measurement aids ------------------------------------------------------------------------
  * Not steps of the method: two plain kernels that say what this chip achieves, so that kernel rates can be

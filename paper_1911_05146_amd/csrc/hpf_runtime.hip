@@ -1512,6 +1512,68 @@ hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entri
   return check_abort_flag(p);
 }
 
+hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t tensor, void* host_dst, size_t bytes,
+                          size_t* bytes_needed, int32_t* where) {
+  if (!p || !where) return fail(HPF_EINVAL, "null argument");
+  const Plan& P = p->P;
+  const int nb = (int)P.bp.size();
+  if (mb < 0 || mb >= P.d.num_microbatches) return fail(HPF_EINVAL, "micro-batch %d out of range", mb);
+  if (unit < -1 || unit > nb) return fail(HPF_EINVAL, "unit %d out of range", unit);
+  const size_t b = (size_t)P.d.microbatch;
+  const size_t asz = P.dt == DT_BF16 ? sizeof(float) : sizeof(double);
+  Loc loc;          // NOWHERE until resolved
+  size_t need = 0;
+  Loc lout; lout.kind = CALLER_ERR_OUT;
+  auto grad_in = [&](int i) -> Loc { return i > 0 ? P.bp[i - 1].gy : (P.d.has_stem ? P.g_stem : lout); };
+  auto stats_of = [&](const BnPlan& bn) { loc.kind = IN_MB; loc.off = bn.stats_off; need = 2 * (size_t)bn.C * asz; };
+  if (unit == -1) {
+    if (!P.d.has_stem) return fail(HPF_EINVAL, "the partition has no stem");
+    const size_t n = b * P.d.in_h * P.d.in_w * P.d.stem_c_out * P.esz;
+    if (tensor == HPF_T_Y) { loc = P.stem_out; need = n; }
+    else if (tensor == HPF_T_GY) { loc = P.g_stem; need = n; }
+  } else if (unit == nb) {
+    if (!P.d.has_head) return fail(HPF_EINVAL, "the partition has no head");
+    const size_t n = b * P.out_h * P.out_w * P.out_c * P.esz;
+    if (tensor == HPF_T_X) { loc = P.head_x; need = n; }
+    else if (tensor == HPF_T_A0) { loc = P.head_a; need = n; }
+    else if (tensor == HPF_T_GX) { loc = grad_in(nb); need = n; }
+    else if (tensor == HPF_T_STATS0) stats_of(P.head_bn);
+  } else {
+    const BlockPlan& q = P.bp[unit];
+    const size_t M_in = b * q.h_in * q.w_in, M_out = b * q.h_out * q.w_out;
+    auto held = [&](int j) { return j >= q.j0 && j < q.j1; };
+    switch (tensor) {
+      case HPF_T_X: if (q.j0 == 0) { loc = q.x_in; need = M_in * q.d.c_in * P.esz; } break;
+      case HPF_T_C1: if (held(0) || q.j0 == 1) { loc = q.c[0]; need = M_out * q.d.c_mid * P.esz; } break;
+      case HPF_T_C2: if (q.nconv == 3 && (held(1) || q.j0 == 2)) { loc = q.c[1]; need = M_out * q.d.c_mid * P.esz; } break;
+      case HPF_T_Y: if (q.j1 == q.nconv) { loc = q.y; need = M_out * q.d.c_out * P.esz; } break;
+      case HPF_T_GY: if (q.j1 == q.nconv || q.j0 == 0) { loc = q.gy; need = M_out * q.d.c_out * P.esz; } break;
+      case HPF_T_DC1: if (held(0) || q.j0 == 1) { loc = q.dc[0]; need = M_out * q.d.c_mid * P.esz; } break;
+      case HPF_T_DC2: if (q.nconv == 3 && (held(1) || q.j0 == 2)) { loc = q.dc[1]; need = M_out * q.d.c_mid * P.esz; } break;
+      case HPF_T_GX: if (q.j0 == 0) { loc = grad_in(unit); need = M_in * q.d.c_in * P.esz; } break;
+      case HPF_T_STATS0: case HPF_T_STATS1: case HPF_T_STATS2:
+        if (tensor - HPF_T_STATS0 < q.nconv && held(tensor - HPF_T_STATS0)) stats_of(q.bn[tensor - HPF_T_STATS0]);
+        break;
+      case HPF_T_A0: case HPF_T_A1: case HPF_T_A2: {
+        const int j = tensor - HPF_T_A0;
+        if (j < q.nconv && held(j) && q.a[j].kind != NOWHERE) { loc = q.a[j]; need = (j == 0 ? M_in : M_out) * q.cv[j].cin * P.esz; }
+        break;
+      }
+      default: break;
+    }
+  }
+  if (loc.kind == NOWHERE || need == 0) return fail(HPF_EINVAL, "unit %d does not keep tensor %d", unit, tensor);
+  if (bytes_needed) *bytes_needed = need;
+  if (loc.kind != IN_MB) { *where = (int32_t)loc.kind; return HPF_OK; }   // CALLER_ACT_IN = 1 ... CALLER_SKIP_ERR_OUT = 8
+  *where = 0;
+  if (!host_dst) return HPF_OK;   // a query for the size and the place
+  if (bytes != need) return fail(HPF_EINVAL, "destination has %zu bytes, the tensor %zu", bytes, need);
+  if (hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(host_dst, p->mb_base(mb) + loc.off, need, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(HPF_EDEVICE, "device-to-host copy failed");
+  return HPF_OK;
+}
+
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {
   if (!p || !host_dst) return fail(HPF_EINVAL, "null argument");
   if (n_floats != p->P.n_params) return fail(HPF_EINVAL, "n_floats %zu, expected %zu", n_floats, p->P.n_params);
@@ -1631,6 +1693,51 @@ hpf_status hpf_op_bn_relu_backward(hpf_dtype dtype, const void* x, const void* d
     return fail(HPF_EDEVICE, "launch failed");
   if (launch_bn_bwd_apply(dt, 1, one_ptr(x), one_ptr(da), gamma, beta, one_ptr(stats), one_ptr(sums), one_ptr(skip), one_ptr(dx), M, C, 0, s) != hipSuccess)
     return fail(HPF_EDEVICE, "launch failed");
+  return HPF_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// hpf_op_bn_relu_forward for callers that cannot allocate: the reduction partials live in a file-scope device
+// array instead of a caller workspace.  Every GPU holds its own copy of the array at its own address, looked up
+// once per device; all calls on one GPU share it.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStaticBnMaxC = 1024;
+constexpr size_t kStaticBnFloats = (size_t)128 * kStaticBnMaxC * 4 * 2;   // = bn_partials_floats(kStaticBnMaxC): 4 MiB
+static __device__ __align__(256) float scratch[kStaticBnFloats];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static hpf_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(HPF_EDEVICE, "no current device");
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(HPF_EDEVICE, "hipGetSymbolAddress: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return HPF_OK;
+}
+
+hpf_status hpf_op_bn_relu_forward_noalloc(hpf_dtype dtype, const void* x, const float* gamma, const float* beta, float eps,
+                                          void* a, void* stats, int32_t M, int32_t C, void* hip_stream) {
+  if (!x || !gamma || !beta || !a || !stats) return fail(HPF_EINVAL, "null tensor");
+  if (dtype != HPF_BF16 && dtype != HPF_F32) return fail(HPF_EINVAL, "unknown dtype");
+  if (M <= 0 || C <= 0 || C % 8) return fail(HPF_EUNSUPPORTED, "C must be a positive multiple of 8");
+  if (C > kStaticBnMaxC) return fail(HPF_EUNSUPPORTED, "C = %d exceeds the %d channels the built-in scratch array is sized for", C, kStaticBnMaxC);
+  if (bn_partials_floats(C) > kStaticBnFloats) return fail(HPF_EUNSUPPORTED, "reduction partials do not fit the built-in scratch array");
+  void* partials = nullptr;
+  const hpf_status st = static_scratch(&partials);
+  if (st != HPF_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int dt = dtype == HPF_BF16 ? DT_BF16 : DT_F32;
+  // every partial record the finalize step reads is written by the statistics kernel of the same call: nothing in
+  // the array has to start at zero
+  if (launch_bn_stats(dt, 1, one_ptr(x), M, C, eps, one_ptr(stats), one_ptr(partials), s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
+  if (launch_bn_apply_relu(dt, 1, one_ptr(x), one_ptr(a), gamma, beta, one_ptr(stats), M, C, s) != hipSuccess) return fail(HPF_EDEVICE, "launch failed");
   return HPF_OK;
 }
 

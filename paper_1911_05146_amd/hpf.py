@@ -91,6 +91,8 @@ def _load():
     L.hpf_op_conv_wgrad.argtypes = [C.c_int, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     L.hpf_op_bn_relu_forward.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]
     L.hpf_op_bn_relu_backward.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    L.hpf_op_bn_relu_forward_noalloc.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp]
+    L.hpf_stash_read.argtypes = [vp, i32, i32, i32, vp, sz, C.POINTER(sz), C.POINTER(i32)]
     L.hpf_probe_copy.argtypes = [vp, vp, sz, vp]
     L.hpf_probe_mfma_bf16.argtypes = [vp, i32, i32, i32, vp]
     return L
@@ -107,7 +109,7 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference", "hpf_forward_inference_group",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward",
-           "hpf_probe_copy", "hpf_probe_mfma_bf16"]
+           "hpf_stash_read", "hpf_op_bn_relu_forward_noalloc", "hpf_probe_copy", "hpf_probe_mfma_bf16"]
 
 
 def hpf_last_error() -> str:
@@ -248,6 +250,20 @@ def hpf_partition_profile_read(handle, capacity=16):
             for i in range(n.value)]
 
 
+# hpf_tensor_id
+(HPF_T_X, HPF_T_C1, HPF_T_C2, HPF_T_Y, HPF_T_GY, HPF_T_DC1, HPF_T_DC2, HPF_T_GX, HPF_T_STATS0, HPF_T_STATS1,
+ HPF_T_STATS2, HPF_T_A0, HPF_T_A1, HPF_T_A2) = range(14)
+STASH_WHERE = {1: "act_in", 2: "act_out", 3: "err_in", 4: "err_out", 5: "skip_in", 6: "skip_out", 7: "skip_err_in",
+               8: "skip_err_out"}
+
+
+def hpf_stash_read(handle, mb, unit, tensor, host_dst, nbytes):
+    """Returns (where, bytes_needed); where == 0: copied into host_dst."""
+    need, where = C.c_size_t(0), C.c_int32(-1)
+    _check(lib.hpf_stash_read(handle, mb, unit, tensor, host_dst, nbytes, C.byref(need), C.byref(where)))
+    return where.value, need.value
+
+
 def hpf_partition_destroy(handle):
     lib.hpf_partition_destroy(handle)
 
@@ -281,6 +297,10 @@ def hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip, dx, dgamma, 
                             workspace_bytes, stream=0):
     _check(lib.hpf_op_bn_relu_backward(dtype, x, da, gamma, beta, stats, skip or None, dx, dgamma, dbeta, M, Cc,
                                        workspace, workspace_bytes, stream or None))
+
+
+def hpf_op_bn_relu_forward_noalloc(dtype, x, gamma, beta, eps, a, stats, M, Cc, stream=0):
+    _check(lib.hpf_op_bn_relu_forward_noalloc(dtype, x, gamma, beta, eps, a, stats, M, Cc, stream))
 
 
 def hpf_probe_copy(dst, src, nbytes, stream=0):
@@ -593,6 +613,22 @@ class Partition:
     def profile_read(self):
         """[{name, launches, total_ms, bytes_per_launch, flops_per_launch}] since profiling was enabled."""
         return hpf_partition_profile_read(self.handle)
+
+    def stash_read(self, mb, unit, tensor):
+        """One stashed tensor of micro-batch mb as a flat float32 array (statistics: float64), or the name of the
+        caller buffer that holds it ("act_in", "err_out", ...)."""
+        import numpy as np
+        torch = self.torch
+        where, need = hpf_stash_read(self.handle, mb, unit, tensor, None, 0)
+        if where != 0:
+            return STASH_WHERE[where]
+        raw = np.empty(need, np.uint8)
+        hpf_stash_read(self.handle, mb, unit, tensor, raw.ctypes.data, need)
+        if HPF_T_STATS0 <= tensor <= HPF_T_STATS2:
+            return raw.view(np.float32 if self.compute_dtype == HPF_BF16 else np.float64).astype(np.float64)
+        if self.compute_dtype == HPF_BF16:
+            return torch.from_numpy(raw.view(np.int16)).view(torch.bfloat16).float().numpy()
+        return raw.view(np.float32).copy()
 
     def params_read(self):
         import numpy as np

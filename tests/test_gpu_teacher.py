@@ -1,0 +1,97 @@
+"""GPU parity, layer by layer, at full size: every tensor the device keeps for back-propagation, for every block
+and micro-batch of the benchmark configurations, against the plain CPU oracle fed the device's own layer inputs
+(tests/teacher.py).  Element-wise, 2e-2 (bf16 operands) / 1e-4 (fp32 check mode), in the launch configuration
+bench.py times (all micro-batches of the batch in one group call per direction)."""
+import time
+
+import numpy as np
+import pytest
+
+from paper_1911_05146_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: these tests need a real MI355X")
+    from paper_1911_05146_amd import hpf
+    return hpf
+
+
+def layerwise(oracle, spec, mode, grouped=True, fusion=2, randomize_affine=True):
+    from parity import run_gpu_step
+    from teacher import layerwise_check
+    print(f"\n[case] layer-wise {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} grouped={grouped} "
+          f"fusion={fusion} seed={spec.seed}", flush=True)
+    inp = W.make_inputs(spec, randomize_affine=randomize_affine)
+    t0 = time.time()
+    seen, res = run_gpu_step(spec, inp, mode, grouped=grouped, fusion=fusion, keep=True)
+    part = res.pop("part")
+    try:
+        rep = layerwise_check(oracle, part, spec, seen, res, mode)
+    finally:
+        part.close()
+    print(f"[layer-wise] {spec.name} {mode}: {rep.summary()} ({time.time() - t0:.0f} s)", flush=True)
+    return rep
+
+
+@pytest.mark.parametrize("mode", ["bf16", "f32"])
+def test_single_blocks_layerwise(gpu, oracle, mode):
+    """Every block kind at its full micro-batch, first seed, no retries."""
+    cases = {
+        "bottleneck-identity-r1001-stage2": (W.Block(W.BOTTLENECK, 128, 32, 128, 1), 16, 32),
+        "bottleneck-entry-stride2-proj": (W.Block(W.BOTTLENECK, 64, 32, 128, 2), 16, 8),
+        "bottleneck-widen-proj-stride1": (W.Block(W.BOTTLENECK, 16, 16, 64, 1), 32, 8),
+        "bottleneck-wide-identity": (W.Block(W.BOTTLENECK, 128, 64, 128, 1), 16, 8),
+        "basic-identity": (W.Block(W.BASIC, 32, 32, 32, 1), 16, 16),
+        "basic-identity-64": (W.Block(W.BASIC, 64, 64, 64, 1), 8, 16),
+        "basic-entry-stride2-proj": (W.Block(W.BASIC, 32, 64, 64, 2), 16, 16),
+        "bottleneck-r152-stage3": (W.Block(W.BOTTLENECK, 1024, 256, 1024, 1), 14, 4),
+        "bottleneck-r152-entry": (W.Block(W.BOTTLENECK, 512, 256, 1024, 2), 28, 2),
+    }
+    for name, (blk, hw, b) in cases.items():
+        spec = W.PartitionSpec(name=name, in_h=hw, in_w=hw, in_c=blk.c_in, blocks=(blk,), microbatch=b,
+                               num_microbatches=2, seed=21)
+        layerwise(oracle, spec, mode)
+
+
+def test_config1_resnet20_layerwise(gpu, oracle):
+    for mode in ("bf16", "f32"):
+        layerwise(oracle, W.config(1), mode, grouped=False)
+        layerwise(oracle, W.config(1), mode, grouped=True)
+
+
+def test_config2_resnet110_partition_full_size_layerwise(gpu, oracle):
+    layerwise(oracle, W.config(2), "bf16")
+    layerwise(oracle, W.config(2), "bf16", fusion=1)
+    layerwise(oracle, W.config(2), "f32")
+
+
+def test_config3_resnet1001_partition_full_size_layerwise(gpu, oracle):
+    """The benchmark configuration: 21 blocks x 8 micro-batches x 32 images through the image-resident kernels."""
+    layerwise(oracle, W.config(3), "bf16")
+
+
+def test_config3_other_schedules_layerwise(gpu, oracle):
+    spec = W.with_microbatching(W.config(3), 32, 2, loss_divisor=256)
+    layerwise(oracle, spec, "bf16", fusion=1)
+    layerwise(oracle, spec, "bf16", fusion=0)
+    layerwise(oracle, spec, "bf16", grouped=False)
+    layerwise(oracle, W.with_microbatching(W.config(3), 8, 2, loss_divisor=256), "f32")
+
+
+def test_config6_wide_resnet1001_partition_full_size_layerwise(gpu, oracle):
+    layerwise(oracle, W.config(6), "bf16")
+
+
+def test_config4_resnet1001_whole_full_size_layerwise(gpu, oracle):
+    """333 blocks + stem + head, 8 micro-batches of 8 images."""
+    layerwise(oracle, W.config(4), "bf16")
+
+
+def test_config5_resnet152_stage3_full_size_layerwise(gpu, oracle):
+    """36 blocks at 14x14x1024, 4 micro-batches of 16 images (3 TFLOP per oracle pass)."""
+    layerwise(oracle, W.config(5), "bf16")
