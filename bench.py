@@ -32,6 +32,8 @@ PEAK_HBM = 8.0e12         # bytes/s
 # scaled by what the counter reads for a plain device copy of known size); the summaries with the
 # commands are under profiles/.  Keyed by (kernel class, configuration).
 MEASURED_TRAFFIC = {("resident_backward", 3): 1.125e9}
+TRAFFIC_SOURCE = ("constant taken from profiles/mfma_and_bn_counters_resnet1001_partition.md (two rocprofv3 --pmc runs of this "
+                  "command), not measured in this run")
 
 
 def profile_classes(torch, part, step, steps=10):
@@ -85,8 +87,9 @@ def measured_ceilings(torch, dev):
                     f"(16x16x32: {flops / t_mfma['16x16x32'] / 1e12:.0f}, 32x32x16: {flops / t_mfma['32x32x16'] / 1e12:.0f} TFLOP/s)"}
 
 
-def cpu_baseline(spec, inputs, max_microbatches=4, threads=None):
-    """The oracle (fp32 storage, double sums, OpenMP) on the first micro-batches of the same workload.
+def cpu_baseline(spec, inputs, max_microbatches=None, threads=None, repeats=3):
+    """The oracle as it stands (fp32 storage, double sums, OpenMP) on the same workload: the full step on all
+    threads, best of `repeats`; or, with max_microbatches, on the first micro-batches only.
     threads: ask the OpenMP runtime for this many threads first (the oracle itself has no such setting)."""
     import numpy as np
     import oracle
@@ -94,17 +97,21 @@ def cpu_baseline(spec, inputs, max_microbatches=4, threads=None):
     if threads is not None:
         import ctypes
         ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(threads))
-    n = min(spec.num_microbatches, max_microbatches)
+    n = min(spec.num_microbatches, max_microbatches or spec.num_microbatches)
     sub = W.with_microbatching(spec, spec.microbatch, n, loss_divisor=spec.divisor)
     sub_inp = W.StepInputs(inputs.params, inputs.act_in[:n], inputs.labels[:n] if inputs.labels else None,
                            inputs.err_in[:n] if inputs.err_in else None)
     oracle.lib()
-    t0 = time.perf_counter()
-    oracle.run_step(sub, sub_inp, np.float32)
-    dt = time.perf_counter() - t0
+    times = []
+    for _ in range(max(1, repeats)):
+        t0 = time.perf_counter()
+        oracle.run_step(sub, sub_inp, np.float32)
+        times.append(time.perf_counter() - t0)
+    dt = min(times)
     cores = int(threads) if threads is not None else int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    what = "the full step" if n == spec.num_microbatches else f"{n} of {spec.num_microbatches} micro-batches"
     return {"value": sub.batch / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n} of {spec.num_microbatches} micro-batches ({sub.batch} images) forward+backward, {dt:.1f} s"}
+            "sample": f"{what} ({sub.batch} images) forward+backward, best of {len(times)}: {dt:.1f} s"}
 
 
 def bench_pipeline(args, torch, dev):
@@ -174,8 +181,11 @@ def main():
     ap.add_argument("--inference", action="store_true",
                     help="instead of training steps: inference forwards (BatchNorm by running statistics) of the "
                          "configuration's micro-batches, one call each")
-    ap.add_argument("--cpu-one-core", action="store_true",
-                    help="also time the oracle on one thread, on one micro-batch (adds its run time)")
+    ap.add_argument("--no-cpu-one-core", action="store_true",
+                    help="skip the oracle timing on one thread (one micro-batch; a few seconds)")
+    ap.add_argument("--cpu-repeats", type=int, default=3, help="the all-thread oracle timing is the best of this many full steps")
+    ap.add_argument("--no-others", dest="others", action="store_false",
+                    help="skip the short runs of the other configurations that follow the headline one")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -193,10 +203,36 @@ def main():
     dev = torch.device("cuda:0")
     if args.pipeline > 0:
         return bench_pipeline(args, torch, dev)
-    spec = W.config(args.config)
+    result = run_config(args, torch, dev, args.config, args.steps, args.warmup, probe=not args.no_probe, cpu=not args.no_cpu)
+    if result is None:
+        return
+    if args.others:
+        # the other configurations, after the timed region of the headline one: shorter runs, same launch configuration
+        result["other_configs"] = []
+        for cfg in (1, 2, 4, 5, 6):
+            if cfg == args.config:
+                continue
+            r = run_config(args, torch, dev, cfg, max(5, args.steps // 3), 3, probe=not args.no_probe, cpu=False, ceilings=False)
+            entry = {"config": cfg, "workload": r["config"]["workload"], "ms_per_step": r["ms_per_step"], "images/s": r["value"],
+                     "steps": r["steps"], "warmup": r["warmup"]}
+            if "roofline" in r:
+                rf = r["roofline"]
+                entry["dominant_kernel_class"] = rf["kernel"]
+                entry["roofline"] = {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us", "launches_per_step",
+                                                        "share_of_step_gpu_time")}
+                entry["kernels"] = r["kernels"]
+            result["other_configs"].append(entry)
+    print(json.dumps(result))
+
+
+def run_config(args, torch, dev, config, steps, warmup, probe=True, cpu=True, ceilings=True):
+    """Times `steps` steps of one configuration; returns the result dictionary (None: a mode that printed its own line)."""
+    import numpy as np  # noqa: F401
+    from paper_1911_05146_amd import hpf, workloads as W
+    spec = W.config(config)
     inputs = W.make_inputs(spec)
     m = spec.num_microbatches
-    sgd = (0.1, 0.9) if args.config == 4 else None
+    sgd = (0.1, 0.9) if config == 4 else None
 
     part = hpf.Partition(spec, inputs.params, hpf.HPF_BF16)
     if args.no_graphs:
@@ -249,22 +285,22 @@ def main():
                 for x, o in zip(xs, outs):
                     part.forward_inference(x, stream=main_stream, out=o)
 
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             infer_all()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             infer_all()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         part.close()
         print(json.dumps({
-            "metric": "images/sec through partition inference forward at 1 MI355X", "value": spec.batch * args.steps / elapsed,
-            "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+            "metric": "images/sec through partition inference forward at 1 MI355X", "value": spec.batch * steps / elapsed,
+            "unit": "images/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"config {args.config}: {spec.name}, inference forward of {m} micro-batches of "
+            "config": {"workload": f"config {config}: {spec.name}, inference forward of {m} micro-batches of "
                                    f"{spec.microbatch} images, " + ("one group call" if args.schedule == "grouped" else "one call each")}}))
-        return
+        return None
 
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
@@ -275,31 +311,32 @@ def main():
         del src, dst
     gbuf = torch.empty(part.n_params, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     if sgd is None:
         drain()
-    img_s = spec.batch * args.steps / elapsed
+    part.check()   # a resident launch that gave up waiting would have left invalid gradients: fail loudly
+    img_s = spec.batch * steps / elapsed
 
     result = {
         "metric": "images/sec through partition fwd+bwd at 1 MI355X",
-        "value": img_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "value": img_s, "unit": "images/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {spec.name}, {len(spec.blocks)} blocks, "
+        "config": {"workload": f"config {config}: {spec.name}, {len(spec.blocks)} blocks, "
                                f"{m} micro-batches of {spec.microbatch} images"
                                + (", + SGD step" if sgd else ""),
                    "batch": spec.batch, "microbatch": spec.microbatch, "num_microbatches": m,
                    "schedule": args.schedule, "hip_graphs": not args.no_graphs, "fusion_level": args.fusion},
     }
 
-    if not args.no_probe:
+    if probe:
         ks = profile_classes(torch, part, step)
         if sgd is None:
             drain()
@@ -312,7 +349,9 @@ def main():
         else:
             bound, ach, peak, unit = "mfma", tfl, PEAK_MFMA_BF16 / 1e12, "TFLOP/s"
         result["roofline"] = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                              "traffic": MEASURED_TRAFFIC.get((dom["name"], args.config)), "kernel": dom["name"],
+                              "traffic": MEASURED_TRAFFIC.get((dom["name"], config)),
+                              "traffic_source": TRAFFIC_SOURCE if (dom["name"], config) in MEASURED_TRAFFIC else None,
+                              "kernel": dom["name"],
                               "avg_launch_us": dom["avg_sec"] * 1e6, "launches_per_step": dom["launches_per_step"],
                               "algorithmic_bytes_per_launch": dom["bytes_per_launch"],
                               "algorithmic_flops_per_launch": dom["flops_per_launch"],
@@ -325,17 +364,17 @@ def main():
              "GB/s": round(k["bytes_per_launch"] / k["avg_sec"] / 1e9, 1) if k["bytes_per_launch"] else None,
              "hbm_frac": round(k["bytes_per_launch"] / k["avg_sec"] / PEAK_HBM, 4) if k["bytes_per_launch"] else None}
             for k in ks]
-    if not args.no_probe:
+    if probe and ceilings:
         ceil = measured_ceilings(torch, dev)
         result["measured_ceilings"] = ceil
         r = result["roofline"]
         r["frac_of_measured_ceiling"] = r["achieved"] / (ceil["copy_GB/s"] if r["bound"] == "hbm" else ceil["mfma_bf16_TFLOP/s"])
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(spec, inputs)
-        if args.cpu_one_core:   # after the all-thread run: the thread count stays at 1 from here on
-            result["cpu_baseline"]["one_core"] = cpu_baseline(spec, inputs, max_microbatches=1, threads=1)
+    if cpu:
+        result["cpu_baseline"] = cpu_baseline(spec, inputs, repeats=args.cpu_repeats)
+        if not args.no_cpu_one_core:   # after the all-thread run: the thread count stays at 1 from here on
+            result["cpu_baseline"]["one_core"] = cpu_baseline(spec, inputs, max_microbatches=1, threads=1, repeats=1)
     part.close()
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":

@@ -91,6 +91,8 @@ def rel_l2(got, ref):
 
 
 def _tensors(res, spec):
+    """The compared tensors of one batch: boundary tensors over all micro-batches, the loss, and the accumulated
+    gradient / the parameters after the step split into the parameter tensors of the canonical layout."""
     out = {}
     for k in ("act_out", "err_out", "skip_out", "skip_err_out"):
         v = [t for t in res.get(k, []) if t is not None]
@@ -100,44 +102,53 @@ def _tensors(res, spec):
         out["loss"] = np.array([res["loss"]], np.float64)
     for k in ("grad", "params"):
         if k in res:
-            out[k] = np.asarray(res[k], np.float64)
+            flat = np.asarray(res[k], np.float64)
+            out[k] = flat
+            for e in W.param_layout(spec):
+                out[f"{k}:{e.name}"] = flat[e.offset:e.offset + e.size]
     return out
 
 
-KAPPA = 2.0
+KAPPA = 1.1
+FLOOR = {"bf16": 5e-3, "f32": 5e-3}
+NOT_A_TEST = 0.5
 
 
-FLOOR = {"bf16": 2e-2, "f32": 1e-2}
+def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None, plain=None):
+    """Parity of one batch, tensor by tensor (the gradient and the parameters also per parameter tensor).
 
-
-def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None):
-    """Parity of one batch.
-
-    yard : the oracle run in the device's precision reading on the same inputs (float storage;
-           in bf16 mode with the tensors the device keeps as bfloat16 rounded at the same points).
-    Criterion A (strict): max|gpu - yard| / max|yard| <= tol for every tensor (2e-2 bf16, 1e-4 fp32).
-    Criterion B (sensitivity-limited), only for tensors that fail A and only if strict is False:
-           a ReLU network's backward pass is discontinuous where a pre-activation is within rounding
-           of 0, so two correct implementations of the same precision reading scatter around the
-           exact result by an amount the oracle itself can measure: with ref64 the oracle in double
-           and nothing rounded,  relL2(gpu, ref64) <= KAPPA * relL2(yard, ref64) + FLOOR.  The floor
-           covers the case where the yardstick run happens to contain no such tie while the device
-           run does: in the fp32 check mode both sides agree to the last bit until the first 1-ulp
-           difference appears (about 2e-8 per stored element), after which ulp-level noise spreads
-           and a handful of ReLU decisions may differ; each moves relL2 by about 1e-3.
-    ref64 may be a callable that computes it on demand.  Returns {tensor: (criterion, error)}.
+    yard : the oracle run in the device's precision reading on the same inputs (float storage; in bf16 mode with
+           the tensors the device keeps as bfloat16 rounded at the same points).
+    plain: optionally the plain fp32 oracle (nothing rounded); the error against it is reported next to the other.
+    Criterion A: max|gpu - yard| / max|yard| <= tol for the tensor (2e-2 bf16, 1e-4 fp32).  strict: A is required.
+    Criterion B (sensitivity-limited), only for tensors that fail A and only if strict is False: a deep ReLU
+           network's backward pass is discontinuous where a pre-activation is within rounding of 0, so two correct
+           implementations of one precision reading scatter around the exact result by an amount the oracle
+           itself can measure.  With ref64 the oracle in double and nothing rounded,
+               relL2(gpu, ref64) <= (KAPPA + 3 / sqrt(2 n)) * relL2(yard, ref64) + FLOOR
+           per tensor of n elements (KAPPA = 1.1: the two distances were measured equal to within 2 %; the second
+           term is three standard deviations of a norm estimated from n samples, which matters for the
+           per-channel tensors of 16 ... 128 elements).  A tensor for which the yardstick itself is at
+           relL2 >= 0.5 of the exact result says nothing either way and fails the case as "not a test":
+           such configurations are covered layer by layer instead (tests/teacher.py).
+    A tensor the oracle returns and the device does not is a failure.  Returns {tensor: (criterion, error, ...)}.
     """
     tol = TOL[mode] if tol is None else tol
     g, y = _tensors(res, spec), _tensors(yard, spec)
+    pl = _tensors(plain, spec) if plain is not None else None
     report, bad = {}, {}
     r64 = None
     for k in y:
         if k not in g:
+            bad[k] = ("missing",)
             continue
         e = rel_err(g[k], y[k])
         if e <= tol:
-            report[k] = ("A", e)
+            if ":" not in k:      # the per-parameter-tensor entries are only listed when they need criterion B
+                report[k] = ("A", e) + ((rel_err(g[k], pl[k]),) if pl is not None else ())
             continue
+        if k in ("grad", "params"):
+            continue              # judged per parameter tensor below
         if strict or ref64 is None:
             bad[k] = ("A", e)
             continue
@@ -145,17 +156,26 @@ def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None):
             r64 = _tensors(ref64() if callable(ref64) else ref64, spec)
         eg, ey = rel_l2(g[k], r64[k]), rel_l2(y[k], r64[k])
         report[k] = ("B", e, eg, ey)
-        if not eg <= KAPPA * ey + FLOOR[mode]:
+        if ey >= NOT_A_TEST:
+            bad[k] = ("not a test: the yardstick is itself at relL2", ey)
+        elif not eg <= (KAPPA + 3.0 / np.sqrt(2.0 * g[k].size)) * ey + FLOOR[mode]:
             bad[k] = ("B", e, eg, ey)
     assert not bad, f"{spec.name} [{mode}] parity failed: {bad} (passed: {report})"
     return report
 
 
 def fmt(report):
-    out = []
+    out, nb, worst = [], 0, None
     for k, v in report.items():
         if v[0] == "A":
-            out.append(f"{k}: max-norm {v[1]:.2e}")
+            out.append(f"{k}: max-norm {v[1]:.2e}" + (f" (vs the plain fp32 oracle {v[2]:.2e})" if len(v) > 2 else ""))
+        elif ":" in k:
+            nb += 1
+            if worst is None or v[2] / max(v[3], 1e-30) > worst[1][2] / max(worst[1][3], 1e-30):
+                worst = (k, v)
         else:
             out.append(f"{k}: max-norm {v[1]:.2e} -> sensitivity-limited, relL2 gpu {v[2]:.2e} vs oracle-in-same-precision {v[3]:.2e}")
+    if nb:
+        k, v = worst
+        out.append(f"{nb} parameter tensors sensitivity-limited, largest gpu/yardstick ratio at {k}: relL2 {v[2]:.2e} vs {v[3]:.2e}")
     return "; ".join(out)

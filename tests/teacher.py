@@ -106,12 +106,22 @@ def layerwise_check(oracle, part, spec, seen, res, mode, eps=None, check_grad=Tr
         rep.cmp("bn.invstd", where, st[C:], invstd, tol=STATS_TOL[mode])
         return a, mean, invstd, g, bt
 
+    Gabs = {}   # BatchNorm parameter gradients: sum of the absolute values of the terms (the scale of their rounding error)
+
     def bn_bwd(x, da, g, bt, mean, invstd, skip, gname, bname):
         dx, dg, db = oracle.bn_relu_bwd(x, da, g, bt, mean, invstd, skip=skip)
         G[gname] += dg
         G[bname] += db
         tie = _tie_mask(x, g, bt, mean, invstd, mode)
         rep.n_ties += int(tie.sum())
+        xh = (x - mean) * invstd
+        dz = np.abs(da) * (g * xh + bt > 0)
+        ax = tuple(range(x.ndim - 1))
+        Gabs[bname] = Gabs.get(bname, 0.0) + dz.sum(axis=ax)
+        Gabs[gname] = Gabs.get(gname, 0.0) + (dz * np.abs(xh)).sum(axis=ax)
+        # a tie that falls the other way on the device moves these sums by up to its |da|
+        Gabs[bname + ".tie"] = Gabs.get(bname + ".tie", 0.0) + (np.abs(da) * tie).sum(axis=ax)
+        Gabs[gname + ".tie"] = Gabs.get(gname + ".tie", 0.0) + (np.abs(da * xh) * tie).sum(axis=ax)
         return dx, tie
 
     loss = 0.0
@@ -184,9 +194,173 @@ def layerwise_check(oracle, part, spec, seen, res, mode, eps=None, check_grad=Tr
     if check_grad:
         gdev = np.asarray(res["grad"], np.float64)
         for name, e in lay.items():
-            rep.cmp("G." + name.split(".", 1)[1] if name.startswith("block") else "G." + name, name,
-                    gdev[e.offset:e.offset + e.size], G[name])
+            kind = "G." + name.split(".", 1)[1] if name.startswith("block") else "G." + name
+            got, ref = gdev[e.offset:e.offset + e.size], G[name].ravel()
+            if name in Gabs and not np.abs(got - ref).max() <= rep.tol * (np.abs(ref).max() or 1.0):
+                # A sum over M terms of both signs can come out far smaller than its terms; what rounding can do
+                # to it scales with the sum of the terms' magnitudes, not with the result.  Such a slice passes if
+                # every element is within that bound: one bf16 rounding per term (2^-8), plus the ties.
+                bound = 2.0 ** -8 * Gabs[name] + Gabs[name + ".tie"]
+                ok = bool((np.abs(got - ref) <= bound).all())
+                print(f"[note] {spec.name} {name}: max-norm {np.abs(got - ref).max() / (np.abs(ref).max() or 1.0):.3e} over {ref.size} "
+                      f"channels; |err| / (2^-8 sum|terms| + ties) <= {float((np.abs(got - ref) / bound).max()):.3f}; "
+                      f"max|ref| {np.abs(ref).max():.3e}, sum|terms| {Gabs[name].max():.3e}, ties {Gabs[name + '.tie'].max():.3e}", flush=True)
+                rep.cmp(kind + ".cancelling", name, got, ref, tol=np.inf if ok else 0.0)
+                continue
+            rep.cmp(kind, name, got, ref)
     total = max(rep.n_elems, 1)
     assert rep.n_ties <= 1e-4 * total + 10, f"{rep.n_ties} ReLU ties among {total} elements"
     assert not rep.bad, f"{spec.name} [{mode}] layer-wise parity failed ({len(rep.bad)} tensors), first: {rep.bad[:8]}; {rep.summary()}"
+    return rep
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Block by block: one block of cascade, with an explicit mask of the ReLU decisions that differ
+# ---------------------------------------------------------------------------------------------------------
+def _spread(oracle, pix, R, stride, in_hw):
+    """Pixels of a convolution's input that receive gradient from the marked output pixels (the oracle's own
+    data-gradient geometry applied to an indicator)."""
+    if not pix.any():
+        return np.zeros((pix.shape[0],) + tuple(in_hw), bool)
+    ind = np.ascontiguousarray(pix[..., None], np.float64)
+    return oracle.conv_dgrad(ind, np.ones((R, R, 1, 1)), in_hw, stride)[..., 0] > 0
+
+
+def blockwise_check(oracle, part, spec, seen, res, mode, frac_ok=0.999):
+    """Every block from the device's block input x_k and incoming gradient gy_k alone: the plain oracle (float64,
+    nothing rounded) runs the whole block -- its own c1, c2, its own ReLU decisions -- and every tensor of the
+    block is compared element by element.  Inside one block the device's c1 / c2 differ from the oracle's by
+    bf16 rounding, so a few ReLU decisions of BatchNorm 2 / 3 fall the other way; these are found explicitly
+    (decision from the device's stored tensor vs decision of the oracle, both evaluated in double; the forward
+    comparison bounds how far from zero such a pre-activation can be), and only the gradient elements that such a decision can
+    reach through the block's own layers are left out.  Every other element must be within tolerance; in
+    addition, of ALL elements of a tensor at least frac_ok must be, and its relative L2 error must be."""
+    from paper_1911_05146_amd import hpf
+    assert spec.first_from == 0 and spec.last_to == 0 and spec.bn_mode == 0
+    rep = Report(mode)
+    tol = rep.tol
+    lay = {e.name: e for e in W.param_layout(spec)}
+    params = _f64(seen.params)
+    b, m = spec.microbatch, spec.num_microbatches
+    P = lambda name: params[lay[name].offset:lay[name].offset + lay[name].size].reshape(lay[name].shape)
+    G = {name: np.zeros(e.shape, np.float64) for name, e in lay.items() if name.startswith("block")}
+    caller = lambda mb: {"act_in": seen.act_in[mb], "act_out": res["act_out"][mb],
+                         "err_in": seen.err_in[mb] if seen.err_in else None, "err_out": res["err_out"][mb]}
+
+    def rd(mb, unit, tensor, shape):
+        t = part.stash_read(mb, unit, tensor)
+        if isinstance(t, str):
+            t = caller(mb)[t]
+        return _f64(t).reshape(shape)
+
+    n_flips = n_masked = 0
+    worst_frac, worst_l2 = 1.0, 0.0
+
+    def cmp_masked(kind, where, got, ref, taint):
+        nonlocal n_masked, worst_frac, worst_l2
+        rep.cmp(kind, where, got, ref, mask=taint)                 # every element no differing decision can reach
+        den = float(np.abs(ref).max()) or 1.0
+        frac = float((np.abs(got - ref) <= tol * den).mean())      # ... and nearly all elements altogether
+        l2 = float(np.linalg.norm((got - ref).ravel()) / (np.linalg.norm(ref.ravel()) or 1.0))
+        worst_frac, worst_l2 = min(worst_frac, frac), max(worst_l2, l2)
+        n_masked += int(taint.sum()) if taint is not None else 0
+        if frac < frac_ok or l2 > tol:
+            rep.bad.append((kind + ".all", where, (frac, l2)))
+
+    for mb in range(m):
+        h, w = spec.in_h, spec.in_w
+        for i, blk in enumerate(spec.blocks):
+            pre, tag = f"block{i}.", f"mb{mb} block{i}"
+            ho, wo = h // blk.stride, w // blk.stride
+            nconv = 2 if blk.kind == W.BASIC else 3
+            R = (3, 3) if blk.kind == W.BASIC else (1, 3, 1)
+            x = rd(mb, i, hpf.HPF_T_X, (b, h, w, blk.c_in))
+            gy = rd(mb, i, hpf.HPF_T_GY, (b, ho, wo, blk.c_out))
+            ins, a, st, flips = [x], [], [], []
+            for j in range(nconv):
+                g, bt = P(pre + f"bn{j + 1}.gamma"), P(pre + f"bn{j + 1}.beta")
+                aj, mean, invstd = oracle.bn_relu_fwd(ins[j], g, bt, spec.bn_eps)
+                a.append(aj)
+                st.append((mean, invstd, g, bt))
+                if j == 0:
+                    flips.append(np.zeros(x.shape, bool))      # same x on both sides
+                else:                                          # the device decides on its own stored c_j and statistics
+                    cdev = rd(mb, i, hpf.HPF_T_C1 + j - 1, ins[j].shape)
+                    sd = part.stash_read(mb, i, hpf.HPF_T_STATS0 + j)
+                    C = g.size
+                    z_ref = g * ((ins[j] - mean) * invstd) + bt
+                    z_dev = g * ((cdev - sd[:C]) * sd[C:]) + bt
+                    f = (z_ref > 0) != (z_dev > 0)
+                    # (a decision can only differ where |z_ref| <= |z_ref - z_dev|, and the forward comparison just
+                    # below bounds that difference: every differing decision is a near-tie by construction)
+                    flips.append(f)
+                    n_flips += int(f.sum())
+                    rep.cmp(f"fwd.c{j}", tag, cdev, ins[j])
+                if j + 1 < nconv:
+                    ins.append(oracle.conv_fwd(aj, P(pre + f"W{j + 1}"), blk.stride if j == 0 else 1))
+            shortcut = oracle.conv_fwd(a[0], P(pre + "Wproj"), blk.stride) if blk.has_proj else x
+            y = oracle.conv_fwd(a[-1], P(pre + f"W{nconv}"), blk.stride if nconv == 1 else 1, add=shortcut)
+            rep.cmp("fwd.y", tag, rd(mb, i, hpf.HPF_T_Y, y.shape), y)
+            # backward from gy with the oracle's own intermediates
+            d = gy
+            taint_pix = np.zeros((b, ho, wo), bool)            # pixels of the current gradient tensor a flip can reach
+            for j in range(nconv - 1, -1, -1):
+                stride = blk.stride if j == 0 else 1
+                G[pre + f"W{j + 1}"] += oracle.conv_wgrad(a[j], d, R[j], stride)
+                da = oracle.conv_dgrad(d, P(pre + f"W{j + 1}"), ins[j].shape[1:3], stride)
+                taint_pix = _spread(oracle, taint_pix, R[j], stride, ins[j].shape[1:3])
+                skip = None
+                if j == 0:
+                    if blk.has_proj:
+                        G[pre + "Wproj"] += oracle.conv_wgrad(a[0], gy, 1, blk.stride)
+                        da = da + oracle.conv_dgrad(gy, P(pre + "Wproj"), x.shape[1:3], blk.stride)
+                    else:
+                        skip = gy
+                mean, invstd, g, bt = st[j]
+                dx, dg, db = oracle.bn_relu_bwd(ins[j], da, g, bt, mean, invstd, skip=skip)
+                G[pre + f"bn{j + 1}.gamma"] += dg
+                G[pre + f"bn{j + 1}.beta"] += db
+                taint = taint_pix[..., None] | flips[j] | _tie_mask(ins[j], g, bt, mean, invstd, mode)
+                dev = rd(mb, i, hpf.HPF_T_GX if j == 0 else hpf.HPF_T_DC1 + j - 1, dx.shape)
+                cmp_masked("bwd.gx" if j == 0 else f"bwd.dc{j}", tag, dev, dx, taint)
+                taint_pix = taint.any(axis=-1)
+                d = dx
+            h, w = ho, wo
+    gdev = np.asarray(res["grad"], np.float64)
+    for name in G:
+        e = lay[name]
+        got, ref = gdev[e.offset:e.offset + e.size], G[name].ravel()
+        l2 = float(np.linalg.norm(got - ref) / (np.linalg.norm(ref) or 1.0))
+        worst_l2 = max(worst_l2, l2)
+        rep.worst["G.relL2"] = max(rep.worst.get("G.relL2", (0.0, "")), (l2, name))
+        if l2 > tol:
+            rep.bad.append(("G.relL2", name, l2))
+    rep.n_ties = n_flips
+    rep.extra = (f"{n_flips} differing ReLU decisions (all near-ties), {n_masked} gradient elements within their reach left out; "
+                 f"over ALL elements: >= {worst_frac:.5f} of every tensor within tolerance, worst relative L2 {worst_l2:.2e}")
+    assert not rep.bad, f"{spec.name} [{mode}] block-wise parity failed ({len(rep.bad)}), first: {rep.bad[:8]}; {rep.summary()}; {rep.extra}"
+    return rep
+
+
+def run_and_check(oracle, spec, mode, grouped=False, fusion=2, multi_stream=False, randomize_affine=True, blockwise=True,
+                  beta_shift=0.0):
+    """One batch on the device, then the layer-wise and (optionally) the block-wise check.  For a partition of a
+    single block the block-wise check IS the end-to-end comparison of err_out and G against the plain oracle, with
+    the differing ReLU decisions found explicitly instead of re-drawing the inputs until none occurs."""
+    from parity import run_gpu_step
+    inp = W.make_inputs(spec, randomize_affine=randomize_affine)
+    if beta_shift:
+        for e in W.param_layout(spec):
+            if e.kind == "beta":
+                inp.params[e.offset:e.offset + e.size] += beta_shift
+    seen, res = run_gpu_step(spec, inp, mode, grouped=grouped, fusion=fusion, multi_stream=multi_stream, keep=True)
+    part = res.pop("part")
+    try:
+        rep = layerwise_check(oracle, part, spec, seen, res, mode)
+        print(f"[layer-wise] {spec.name} {mode}: {rep.summary()}", flush=True)
+        if blockwise:
+            rb = blockwise_check(oracle, part, spec, seen, res, mode)
+            print(f"[block-wise] {spec.name} {mode}: {rb.summary()}; {rb.extra}", flush=True)
+    finally:
+        part.close()
     return rep

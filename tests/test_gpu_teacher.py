@@ -1,7 +1,8 @@
-"""GPU parity, layer by layer, at full size: every tensor the device keeps for back-propagation, for every block
-and micro-batch of the benchmark configurations, against the plain CPU oracle fed the device's own layer inputs
-(tests/teacher.py).  Element-wise, 2e-2 (bf16 operands) / 1e-4 (fp32 check mode), in the launch configuration
-bench.py times (all micro-batches of the batch in one group call per direction)."""
+"""GPU parity, layer by layer and block by block, at full size: every tensor the device keeps for
+back-propagation, for every block and micro-batch of the benchmark configurations, against the plain CPU oracle
+(float64, nothing rounded) fed the device's own layer inputs / block inputs (tests/teacher.py).  Element-wise,
+2e-2 (bf16 operands) / 1e-4 (fp32 check mode), in the launch configuration bench.py times (all micro-batches of
+the batch in one group call per direction)."""
 import time
 
 import numpy as np
@@ -21,9 +22,9 @@ def gpu():
     return hpf
 
 
-def layerwise(oracle, spec, mode, grouped=True, fusion=2, randomize_affine=True):
+def layerwise(oracle, spec, mode, grouped=True, fusion=2, randomize_affine=True, blockwise=True):
     from parity import run_gpu_step
-    from teacher import layerwise_check
+    from teacher import blockwise_check, layerwise_check
     print(f"\n[case] layer-wise {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} grouped={grouped} "
           f"fusion={fusion} seed={spec.seed}", flush=True)
     inp = W.make_inputs(spec, randomize_affine=randomize_affine)
@@ -32,9 +33,13 @@ def layerwise(oracle, spec, mode, grouped=True, fusion=2, randomize_affine=True)
     part = res.pop("part")
     try:
         rep = layerwise_check(oracle, part, spec, seen, res, mode)
+        print(f"[layer-wise] {spec.name} {mode}: {rep.summary()} ({time.time() - t0:.0f} s)", flush=True)
+        if blockwise:
+            t0 = time.time()
+            rb = blockwise_check(oracle, part, spec, seen, res, mode)
+            print(f"[block-wise] {spec.name} {mode}: {rb.summary()}; {rb.extra} ({time.time() - t0:.0f} s)", flush=True)
     finally:
         part.close()
-    print(f"[layer-wise] {spec.name} {mode}: {rep.summary()} ({time.time() - t0:.0f} s)", flush=True)
     return rep
 
 
