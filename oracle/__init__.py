@@ -69,7 +69,14 @@ def lib():
             getattr(L, f"oracle_head_fwd_{suf}").argtypes = [p, p, p, p, p, p, i, i, i, i, d]
             getattr(L, f"oracle_head_fwd_{suf}").restype = d
             getattr(L, f"oracle_head_bwd_{suf}").argtypes = [p, p, p, p, p, p, i, i, i, i]
-            for nm in ("conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd", "bn_relu_bwd", "head_bwd"):
+            getattr(L, f"oracle_bias_act_fwd_{suf}").argtypes = [p, p, p, z, i, i]
+            getattr(L, f"oracle_bias_act_bwd_{suf}").argtypes = [p, p, p, p, z, i, i]
+            getattr(L, f"oracle_maxpool2_fwd_{suf}").argtypes = [p, p, i, i, i, i]
+            getattr(L, f"oracle_maxpool2_bwd_{suf}").argtypes = [p, p, p, i, i, i, i]
+            getattr(L, f"oracle_bn_add_relu_fwd_{suf}").argtypes = [p, p, p, p, p, p, p, z, i, d, i]
+            getattr(L, f"oracle_bn_add_relu_bwd_{suf}").argtypes = [p, p, p, p, p, p, p, p, p, p, z, i, i]
+            for nm in ("conv_fwd", "conv_dgrad", "conv_wgrad", "bn_relu_fwd", "bn_relu_bwd", "head_bwd", "bias_act_fwd",
+                       "bias_act_bwd", "maxpool2_fwd", "maxpool2_bwd", "bn_add_relu_fwd", "bn_add_relu_bwd"):
                 getattr(L, f"oracle_{nm}_{suf}").restype = None
     return _lib
 
@@ -190,6 +197,69 @@ def head_bwd(g, dlogits, wfc, hw):
     return dwfc, dbfc, da
 
 
+def bias_act_fwd(x, bias, relu=True):
+    """y = x + bias[c], then max(., 0) if relu."""
+    dt = x.dtype
+    x, bias = _c(x, dt), _c(bias, dt)
+    Cc = x.shape[-1]
+    y = np.empty_like(x)
+    getattr(lib(), f"oracle_bias_act_fwd_{_suf(dt)}")(_p(x), _p(bias), _p(y), x.size // Cc, Cc, int(relu))
+    return y
+
+
+def bias_act_bwd(y, dy, relu=True):
+    """Returns dx = dy*[y>0] (or dy) and dbias = sum over rows of dx."""
+    dt = y.dtype
+    y, dy = _c(y, dt), _c(dy, dt)
+    Cc = y.shape[-1]
+    dx, db = np.empty_like(y), np.zeros(Cc)
+    getattr(lib(), f"oracle_bias_act_bwd_{_suf(dt)}")(_p(y), _p(dy), _p(dx), _p(db), y.size // Cc, Cc, int(relu))
+    return dx, db
+
+
+def maxpool2_fwd(x):
+    dt = x.dtype
+    x = _c(x, dt)
+    n, h, w, Cc = x.shape
+    y = np.empty((n, h // 2, w // 2, Cc), dt)
+    getattr(lib(), f"oracle_maxpool2_fwd_{_suf(dt)}")(_p(x), _p(y), n, h, w, Cc)
+    return y
+
+
+def maxpool2_bwd(x, dy):
+    dt = x.dtype
+    x, dy = _c(x, dt), _c(dy, dt)
+    n, h, w, Cc = x.shape
+    dx = np.empty_like(x)
+    getattr(lib(), f"oracle_maxpool2_bwd_{_suf(dt)}")(_p(x), _p(dy), _p(dx), n, h, w, Cc)
+    return dx
+
+
+def bn_add_relu_fwd(x, gamma, beta, add, eps=1e-5, mode=0):
+    """y = relu(bn(x) + add); returns y, mean, invstd."""
+    dt = x.dtype
+    x, gamma, beta, add = _c(x, dt), _c(gamma, dt), _c(beta, dt), _c(add, dt)
+    Cc = x.shape[-1]
+    y = np.empty_like(x)
+    mean, invstd = np.empty(Cc), np.empty(Cc)
+    getattr(lib(), f"oracle_bn_add_relu_fwd_{_suf(dt)}")(_p(x), _p(gamma), _p(beta), _p(add), _p(y), _p(mean), _p(invstd),
+                                                         x.size // Cc, Cc, eps, mode)
+    return y, mean, invstd
+
+
+def bn_add_relu_bwd(x, y, dy, gamma, mean, invstd, mode=0):
+    """Returns dx (through the BatchNorm), dadd = dy*[y>0], dgamma, dbeta."""
+    dt = x.dtype
+    x, y, dy, gamma = _c(x, dt), _c(y, dt), _c(dy, dt), _c(gamma, dt)
+    mean, invstd = _c(mean, np.float64), _c(invstd, np.float64)
+    Cc = x.shape[-1]
+    dx, dadd = np.empty_like(x), np.empty_like(x)
+    dg, db = np.zeros(Cc), np.zeros(Cc)
+    getattr(lib(), f"oracle_bn_add_relu_bwd_{_suf(dt)}")(_p(x), _p(y), _p(dy), _p(gamma), _p(mean), _p(invstd), _p(dx), _p(dadd),
+                                                         _p(dg), _p(db), x.size // Cc, Cc, mode)
+    return dx, dadd, dg, db
+
+
 # ---------------------------------------------------------------------------
 # the partition
 # ---------------------------------------------------------------------------
@@ -205,7 +275,8 @@ class OraclePartition:
         desc = np.array([spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
                          len(spec.blocks), int(spec.has_head), spec.num_classes, spec.microbatch,
                          spec.num_microbatches, spec.divisor, spec.bn_mode, STORAGE[storage],
-                         getattr(spec, "first_from", 0), getattr(spec, "last_to", 0)], dtype=np.int32)
+                         getattr(spec, "first_from", 0), getattr(spec, "last_to", 0),
+                         int(getattr(spec, "head_bn", True))], dtype=np.int32)
         params = _c(params, self.dtype)
         self._h = lib().oracle_partition_create(_p(desc), float(spec.bn_eps), _p(blocks), _p(params),
                                                 int(self.dtype == np.float64))

@@ -283,6 +283,124 @@ void head_bwd(const T* g, const T* dlogits, const T* wfc, double* dwfc, double* 
 }
 
 // ------------------------------------------------------------------------------------------
+// The layers of the paper's two other models (Section "Model-Parallelism on a Single Node": VGG-16 and the
+// post-activation ResNet-110-v1), each the textbook definition.
+// ------------------------------------------------------------------------------------------
+// y = x + bias[c], followed by max(., 0) when relu.
+template <class T>
+void bias_act_fwd(const T* x, const T* bias, T* y, size_t M, int C, int relu, int bf = 0) {
+#pragma omp parallel for schedule(static)
+  for (size_t m = 0; m < M; ++m)
+    for (int c = 0; c < C; ++c) {
+      const double v = (double)x[m * C + c] + (double)bias[c];
+      y[m * C + c] = rnd((T)(relu && !(v > 0.0) ? 0.0 : v), bf);
+    }
+}
+// dz = dy * [y > 0] (relu) or dy; dbias += sum_m dz; dx = dz.
+template <class T>
+void bias_act_bwd(const T* y, const T* dy, T* dx, double* dbias, size_t M, int C, int relu, int bf = 0) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    double s = 0.0;
+    for (size_t m = 0; m < M; ++m) {
+      const double dz = (!relu || (double)y[m * C + c] > 0.0) ? (double)dy[m * C + c] : 0.0;
+      s += dz;
+      dx[m * C + c] = rnd((T)dz, bf);
+    }
+    dbias[c] += s;
+  }
+}
+// 2x2 max-pool, stride 2 (h, w even): y[n,p,q,c] = max over the window.
+template <class T>
+void maxpool2_fwd(const T* x, T* y, int n, int h, int w, int C) {
+  const int ho = h / 2, wo = w / 2;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int in = 0; in < n; ++in)
+    for (int p = 0; p < ho; ++p)
+      for (int q = 0; q < wo; ++q)
+        for (int c = 0; c < C; ++c) {
+          T best = x[((size_t)(in * h + 2 * p) * w + 2 * q) * C + c];
+          for (int r = 0; r < 2; ++r)
+            for (int s = 0; s < 2; ++s) {
+              const T v = x[((size_t)(in * h + 2 * p + r) * w + 2 * q + s) * C + c];
+              if (v > best) best = v;
+            }
+          y[((size_t)(in * ho + p) * wo + q) * C + c] = best;
+        }
+}
+// The gradient of a window goes to its maximum; among equal maxima to the first in row-major order.
+template <class T>
+void maxpool2_bwd(const T* x, const T* dy, T* dx, int n, int h, int w, int C) {
+  const int ho = h / 2, wo = w / 2;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int in = 0; in < n; ++in)
+    for (int p = 0; p < ho; ++p)
+      for (int q = 0; q < wo; ++q)
+        for (int c = 0; c < C; ++c) {
+          int br = 0, bs = 0;
+          T best = x[((size_t)(in * h + 2 * p) * w + 2 * q) * C + c];
+          for (int r = 0; r < 2; ++r)
+            for (int s = 0; s < 2; ++s) {
+              const T v = x[((size_t)(in * h + 2 * p + r) * w + 2 * q + s) * C + c];
+              if (v > best) { best = v; br = r; bs = s; }
+            }
+          for (int r = 0; r < 2; ++r)
+            for (int s = 0; s < 2; ++s)
+              dx[((size_t)(in * h + 2 * p + r) * w + 2 * q + s) * C + c] =
+                  (r == br && s == bs) ? dy[((size_t)(in * ho + p) * wo + q) * C + c] : (T)0;
+        }
+}
+// Post-activation residual join: y = max(gamma*xhat + beta + add, 0), statistics as in bn_relu_fwd.
+template <class T>
+void bn_add_relu_fwd(const T* x, const T* gamma, const T* beta, const T* add, T* y, double* mean, double* invstd,
+                     size_t M, int C, double eps, int mode, int bf = 0, const double* given_mean = nullptr,
+                     const double* given_var = nullptr) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    double mu = 0.0, var = 1.0;
+    if (given_mean) {
+      mu = given_mean[c]; var = given_var[c];
+    } else if (mode == 0) {
+      double s = 0.0;
+      for (size_t m = 0; m < M; ++m) s += (double)x[m * C + c];
+      mu = s / (double)M;
+      double v = 0.0;
+      for (size_t m = 0; m < M; ++m) { const double d = (double)x[m * C + c] - mu; v += d * d; }
+      var = v / (double)M;
+    }
+    const double is = 1.0 / std::sqrt(var + eps);
+    mean[c] = mu; invstd[c] = is;
+    for (size_t m = 0; m < M; ++m) {
+      const double z = (double)gamma[c] * (((double)x[m * C + c] - mu) * is) + (double)beta[c] + (double)add[m * C + c];
+      y[m * C + c] = rnd((T)(z > 0.0 ? z : 0.0), bf);
+    }
+  }
+}
+// dz = dy * [y > 0]; dadd = dz; dbeta += sum dz; dgamma += sum dz*xhat;
+// mode 0: dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M); mode 1: dx = gamma*invstd*dz.
+template <class T>
+void bn_add_relu_bwd(const T* x, const T* y, const T* dy, const T* gamma, const double* mean, const double* invstd,
+                     T* dx, T* dadd, double* dgamma, double* dbeta, size_t M, int C, int mode, int bf = 0) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    const double mu = mean[c], is = invstd[c], g = gamma[c];
+    double sb = 0.0, sg = 0.0;
+    for (size_t m = 0; m < M; ++m) {
+      const double dz = (double)y[m * C + c] > 0.0 ? (double)dy[m * C + c] : 0.0;
+      sb += dz; sg += dz * (((double)x[m * C + c] - mu) * is);
+    }
+    dbeta[c] += sb; dgamma[c] += sg;
+    for (size_t m = 0; m < M; ++m) {
+      const double dz = (double)y[m * C + c] > 0.0 ? (double)dy[m * C + c] : 0.0;
+      const double xh = ((double)x[m * C + c] - mu) * is;
+      const double v = mode == 0 ? (dz - sb / (double)M - xh * sg / (double)M) : dz;
+      dx[m * C + c] = rnd((T)(g * is * v), bf);
+      dadd[m * C + c] = rnd((T)dz, bf);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // The partition: stem? + residual blocks + head?, canonical flat parameter order
 //   stem W; per block bn1.g, bn1.b, W1, bn2.g, bn2.b, W2, [bn3.g, bn3.b, W3], [Wproj];
 //   head bn.g, bn.b, Wfc, bfc.
@@ -299,9 +417,14 @@ struct Desc {
   // with the last convolution).  A block cut this way sends its shortcut value (x, or the projection of
   // relu(bn1(x))) straight from the partition that holds its start to the one that holds its end.
   int first_from = 0, last_to = 0;
+  int head_bn = 1;   // the head starts with BatchNorm + relu; 0: global average pool - FC only (ResNet-v1, VGG)
   double bn_eps;
   std::vector<BlockDesc> blocks;
 };
+// Unit kinds: 0 / 1 pre-activation basic / bottleneck block; 2 post-activation basic block (ResNet-v1);
+// 3 conv3x3 + bias + relu (+ 2x2 max-pool iff stride == 2); 4 flatten - dense + bias (+ relu iff c_mid != 0);
+// 5 BatchNorm + relu; 6 bias + relu.
+enum { K_BASIC = 0, K_BOTTLENECK = 1, K_POSTACT = 2, K_CONV_RELU = 3, K_DENSE = 4, K_BN_RELU = 5, K_BIAS_RELU = 6 };
 
 struct ConvP { size_t w; int cin, cout, R, st; };
 struct BnP { size_t g, b; int c; size_t run = 0; /* running mean at run, running variance at run + c */ };
@@ -309,13 +432,17 @@ struct BlockP {
   BlockDesc d; int h_in, w_in, h_out, w_out; bool proj;
   BnP bn[3]; ConvP cv[3]; ConvP pj; int nconv;
   int j0, j1;   // convolutions [j0, j1) of the block belong to this partition
+  size_t bias = 0;   // kinds 3, 4, 6
 };
 
 template <class T>
 struct BnSave { std::vector<T> x; std::vector<double> mean, invstd; };
 
 template <class T>
-struct BlockStash { BnSave<T> bn[3]; std::vector<T> a[3]; };
+struct BlockStash {
+  BnSave<T> bn[3]; std::vector<T> a[3];
+  std::vector<T> x, y, y0;   // kinds 2 ... 6: unit input, output (after the relu), output before the pool
+};
 
 template <class T>
 struct MbStash {
@@ -354,6 +481,32 @@ struct Partition {
     for (size_t bi = 0; bi < d.blocks.size(); ++bi) {
       const BlockDesc& b = d.blocks[bi];
       BlockP p{}; p.d = b;
+      if (b.kind >= K_POSTACT) {   // the other models' units: no cuts inside them
+        auto bn2 = [&](int ch) { BnP r{off, off + (size_t)ch, ch, n_running}; off += 2 * (size_t)ch; n_running += 2 * (size_t)ch; return r; };
+        auto cv2 = [&](int ci, int co, int R, int s) { ConvP r{off, ci, co, R, s}; off += (size_t)R * R * ci * co; return r; };
+        p.h_in = h; p.w_in = w; p.j0 = 0;
+        if (b.kind == K_POSTACT) {
+          p.nconv = 2; p.h_out = h / b.stride; p.w_out = w / b.stride;
+          p.proj = (b.stride != 1 || b.c_in != b.c_out);
+          p.cv[0] = cv2(b.c_in, b.c_mid, 3, b.stride); p.bn[0] = bn2(b.c_mid);
+          p.cv[1] = cv2(b.c_mid, b.c_out, 3, 1);       p.bn[1] = bn2(b.c_out);
+          if (p.proj) p.pj = cv2(b.c_in, b.c_out, 1, b.stride);
+        } else if (b.kind == K_CONV_RELU) {
+          p.nconv = 1; p.h_out = h / b.stride; p.w_out = w / b.stride;
+          p.cv[0] = cv2(b.c_in, b.c_out, 3, 1); p.bias = off; off += b.c_out;
+        } else if (b.kind == K_DENSE) {
+          p.nconv = 1; p.h_out = 1; p.w_out = 1;
+          p.cv[0] = cv2(h * w * b.c_in, b.c_out, 1, 1); p.bias = off; off += b.c_out;
+        } else if (b.kind == K_BN_RELU) {
+          p.nconv = 0; p.h_out = h; p.w_out = w; p.bn[0] = bn2(b.c_in);
+        } else {
+          p.nconv = 0; p.h_out = h; p.w_out = w; p.bias = off; off += b.c_in;
+        }
+        p.j1 = p.nconv;
+        bp.push_back(p);
+        h = p.h_out; w = p.w_out; c = b.c_out;
+        continue;
+      }
       p.nconv = b.kind == 0 ? 2 : 3;
       p.j0 = (bi == 0) ? d.first_from : 0;
       p.j1 = (bi + 1 == d.blocks.size() && d.last_to > 0) ? d.last_to : p.nconv;
@@ -379,7 +532,7 @@ struct Partition {
     }
     out_h = h; out_w = w; out_c = c;
     if (d.has_head) {
-      head_bn = BnP{off, off + (size_t)c, c, n_running}; off += 2 * (size_t)c; n_running += 2 * (size_t)c;
+      if (d.head_bn) { head_bn = BnP{off, off + (size_t)c, c, n_running}; off += 2 * (size_t)c; n_running += 2 * (size_t)c; }
       wfc = off; off += (size_t)c * d.num_classes;
       bfc = off; off += d.num_classes;
     }
@@ -394,8 +547,11 @@ struct Partition {
     st.resize(d.num_microbatches);
     running.assign(n_running, 0.0);
     auto init = [&](const BnP& b) { for (int c = 0; c < b.c; ++c) running[b.run + b.c + c] = 1.0; };
-    for (auto& p : bp) for (int j = p.j0; j < p.j1; ++j) init(p.bn[j]);
-    if (d.has_head) init(head_bn);
+    for (auto& p : bp) {
+      if (p.d.kind == K_BN_RELU) init(p.bn[0]);
+      else if (p.d.kind <= K_POSTACT) for (int j = p.j0; j < p.j1; ++j) init(p.bn[j]);
+    }
+    if (d.has_head && d.head_bn) init(head_bn);
   }
 
   void update_running(const BnP& b, const double* mean, const double* invstd) {
@@ -451,6 +607,58 @@ struct Partition {
                     rm ? rm + p.bn[j].c : nullptr);
         if (!inference) update_running(p.bn[j], B.bn[j].mean.data(), B.bn[j].invstd.data());
       };
+      if (p.d.kind >= K_POSTACT) {
+        const size_t M_in = (size_t)b * p.h_in * p.w_in;
+        const double* none_d = nullptr;
+        auto run_of = [&](const BnP& q) { return inference ? running.data() + q.run : none_d; };
+        B.x = x;
+        if (p.d.kind == K_POSTACT) {
+          // c1 = conv1(x); a1 = relu(bn1(c1)); c2 = conv2(a1); y = relu(bn2(c2) + shortcut)
+          std::vector<T> c1(M_out * p.d.c_mid), c2(M_out * p.d.c_out), sc2, y(M_out * p.d.c_out);
+          conv_fwd(x.data(), P + p.cv[0].w, c1.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, p.cv[0].st, (const T*)nullptr, bf);
+          bnrelu(0, c1);
+          conv_fwd(B.a[0].data(), P + p.cv[1].w, c2.data(), b, p.h_out, p.w_out, p.cv[1].cin, p.cv[1].cout, 3, 1, (const T*)nullptr, bf);
+          if (p.proj) {
+            sc2.resize(M_out * p.d.c_out);
+            conv_fwd(x.data(), P + p.pj.w, sc2.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st, (const T*)nullptr, bf);
+          } else {
+            sc2 = x;
+          }
+          B.bn[1].x = c2; B.bn[1].mean.resize(p.bn[1].c); B.bn[1].invstd.resize(p.bn[1].c);
+          const double* rm = run_of(p.bn[1]);
+          bn_add_relu_fwd(c2.data(), P + p.bn[1].g, P + p.bn[1].b, sc2.data(), y.data(), B.bn[1].mean.data(), B.bn[1].invstd.data(),
+                          M_out, p.bn[1].c, d.bn_eps, d.bn_mode, bf, rm, rm ? rm + p.bn[1].c : nullptr);
+          if (!inference) update_running(p.bn[1], B.bn[1].mean.data(), B.bn[1].invstd.data());
+          B.y = y;
+          x.swap(y);
+        } else if (p.d.kind == K_CONV_RELU) {
+          std::vector<T> cc(M_in * p.d.c_out);
+          conv_fwd(x.data(), P + p.cv[0].w, cc.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, 1, (const T*)nullptr, bf);
+          B.y0.resize(cc.size());
+          bias_act_fwd(cc.data(), P + p.bias, B.y0.data(), M_in, p.d.c_out, 1, bf);
+          if (p.d.stride == 2) {
+            std::vector<T> y(M_out * p.d.c_out);
+            maxpool2_fwd(B.y0.data(), y.data(), b, p.h_in, p.w_in, p.d.c_out);
+            x.swap(y);
+          } else {
+            x = B.y0;
+          }
+        } else if (p.d.kind == K_DENSE) {
+          std::vector<T> cc((size_t)b * p.d.c_out);
+          conv_fwd(x.data(), P + p.cv[0].w, cc.data(), b, 1, 1, p.cv[0].cin, p.cv[0].cout, 1, 1, (const T*)nullptr, bf);
+          B.y0.resize(cc.size());
+          bias_act_fwd(cc.data(), P + p.bias, B.y0.data(), (size_t)b, p.d.c_out, p.d.c_mid != 0, bf);
+          x = B.y0;
+        } else if (p.d.kind == K_BN_RELU) {
+          bnrelu(0, x);
+          x = B.a[0];
+        } else {
+          B.y0.resize(x.size());
+          bias_act_fwd(x.data(), P + p.bias, B.y0.data(), M_in, p.d.c_in, 1, bf);
+          x = B.y0;
+        }
+        continue;
+      }
       std::vector<T> sc;                                   // shortcut: x, or the 1x1 projection of a
       std::vector<T> r;
       if (p.j0 == 0) {
@@ -487,12 +695,16 @@ struct Partition {
     }
     if (d.has_head) {
       const int C = out_c, hw = out_h * out_w;
-      S.head_bn.x = x; S.head_bn.mean.resize(C); S.head_bn.invstd.resize(C);
-      S.head_a.resize(x.size());
-      const double* rm = inference ? running.data() + head_bn.run : nullptr;
-      bn_relu_fwd(x.data(), P + head_bn.g, P + head_bn.b, S.head_a.data(), S.head_bn.mean.data(),
-                  S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode, bf, rm, rm ? rm + C : nullptr);
-      if (!inference) update_running(head_bn, S.head_bn.mean.data(), S.head_bn.invstd.data());
+      if (d.head_bn) {
+        S.head_bn.x = x; S.head_bn.mean.resize(C); S.head_bn.invstd.resize(C);
+        S.head_a.resize(x.size());
+        const double* rm = inference ? running.data() + head_bn.run : nullptr;
+        bn_relu_fwd(x.data(), P + head_bn.g, P + head_bn.b, S.head_a.data(), S.head_bn.mean.data(),
+                    S.head_bn.invstd.data(), (size_t)b * hw, C, d.bn_eps, d.bn_mode, bf, rm, rm ? rm + C : nullptr);
+        if (!inference) update_running(head_bn, S.head_bn.mean.data(), S.head_bn.invstd.data());
+      } else {
+        S.head_a = x;   // pool - FC directly on the last unit's output
+      }
       S.g.resize((size_t)b * C); S.dlogits.resize((size_t)b * d.num_classes);
       if (inference) {   // logits = mean_{h,w}(a) * Wfc + bfc
         if (!act_out) return E_INVAL;
@@ -533,9 +745,13 @@ struct Partition {
       const int C = out_c, hw = out_h * out_w;
       std::vector<T> da((size_t)b * hw * C);
       head_bwd(S.g.data(), S.dlogits.data(), P + wfc, G + wfc, G + bfc, da.data(), b, hw, C, d.num_classes, bf);
-      dy.resize(da.size());
-      bn_relu_bwd(S.head_bn.x.data(), da.data(), P + head_bn.g, P + head_bn.b, S.head_bn.mean.data(),
-                  S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode, none, bf);
+      if (d.head_bn) {
+        dy.resize(da.size());
+        bn_relu_bwd(S.head_bn.x.data(), da.data(), P + head_bn.g, P + head_bn.b, S.head_bn.mean.data(),
+                    S.head_bn.invstd.data(), dy.data(), G + head_bn.g, G + head_bn.b, (size_t)b * hw, C, d.bn_mode, none, bf);
+      } else {
+        dy.swap(da);
+      }
     } else {
       if (!err_in) return E_INVAL;
       dy.assign(err_in, err_in + (size_t)b * out_h * out_w * out_c);
@@ -543,6 +759,48 @@ struct Partition {
     for (size_t ii = bp.size(); ii-- > 0;) {
       const BlockP& p = bp[ii]; BlockStash<T>& B = S.blk[ii];
       const size_t M_in = (size_t)b * p.h_in * p.w_in, M_out = (size_t)b * p.h_out * p.w_out;
+      if (p.d.kind >= K_POSTACT) {
+        std::vector<T> dx(B.x.size());
+        if (p.d.kind == K_POSTACT) {
+          // through the join: dz = dy*[y>0] goes to the shortcut as it is and through bn2 to c2
+          std::vector<T> dc2(dy.size()), dz(dy.size());
+          bn_add_relu_bwd(B.bn[1].x.data(), B.y.data(), dy.data(), P + p.bn[1].g, B.bn[1].mean.data(), B.bn[1].invstd.data(),
+                          dc2.data(), dz.data(), G + p.bn[1].g, G + p.bn[1].b, M_out, p.bn[1].c, d.bn_mode, bf);
+          conv_wgrad(B.a[0].data(), dc2.data(), G + p.cv[1].w, b, p.h_out, p.w_out, p.cv[1].cin, p.cv[1].cout, 3, 1);
+          std::vector<T> da1(M_out * p.d.c_mid), dc1(M_out * p.d.c_mid);
+          conv_dgrad(dc2.data(), P + p.cv[1].w, da1.data(), b, p.h_out, p.w_out, p.cv[1].cin, p.cv[1].cout, 3, 1, none, bf);
+          bn_relu_bwd(B.bn[0].x.data(), da1.data(), P + p.bn[0].g, P + p.bn[0].b, B.bn[0].mean.data(), B.bn[0].invstd.data(),
+                      dc1.data(), G + p.bn[0].g, G + p.bn[0].b, M_out, p.bn[0].c, d.bn_mode, none, bf);
+          conv_wgrad(B.x.data(), dc1.data(), G + p.cv[0].w, b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, p.cv[0].st);
+          if (p.proj) {
+            conv_wgrad(B.x.data(), dz.data(), G + p.pj.w, b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st);
+            std::vector<T> dsx(dx.size());
+            conv_dgrad(dz.data(), P + p.pj.w, dsx.data(), b, p.h_in, p.w_in, p.pj.cin, p.pj.cout, 1, p.pj.st, none, bf);
+            conv_dgrad(dc1.data(), P + p.cv[0].w, dx.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, p.cv[0].st, dsx.data(), bf);
+          } else {
+            conv_dgrad(dc1.data(), P + p.cv[0].w, dx.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, p.cv[0].st, dz.data(), bf);
+          }
+        } else if (p.d.kind == K_CONV_RELU) {
+          std::vector<T> d0(B.y0.size()), dz(B.y0.size());
+          if (p.d.stride == 2) maxpool2_bwd(B.y0.data(), dy.data(), d0.data(), b, p.h_in, p.w_in, p.d.c_out);
+          else d0 = dy;
+          bias_act_bwd(B.y0.data(), d0.data(), dz.data(), G + p.bias, M_in, p.d.c_out, 1, bf);
+          conv_wgrad(B.x.data(), dz.data(), G + p.cv[0].w, b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, 1);
+          conv_dgrad(dz.data(), P + p.cv[0].w, dx.data(), b, p.h_in, p.w_in, p.cv[0].cin, p.cv[0].cout, 3, 1, none, bf);
+        } else if (p.d.kind == K_DENSE) {
+          std::vector<T> dz(B.y0.size());
+          bias_act_bwd(B.y0.data(), dy.data(), dz.data(), G + p.bias, (size_t)b, p.d.c_out, p.d.c_mid != 0, bf);
+          conv_wgrad(B.x.data(), dz.data(), G + p.cv[0].w, b, 1, 1, p.cv[0].cin, p.cv[0].cout, 1, 1);
+          conv_dgrad(dz.data(), P + p.cv[0].w, dx.data(), b, 1, 1, p.cv[0].cin, p.cv[0].cout, 1, 1, none, bf);
+        } else if (p.d.kind == K_BN_RELU) {
+          bn_relu_bwd(B.bn[0].x.data(), dy.data(), P + p.bn[0].g, P + p.bn[0].b, B.bn[0].mean.data(), B.bn[0].invstd.data(),
+                      dx.data(), G + p.bn[0].g, G + p.bn[0].b, M_in, p.bn[0].c, d.bn_mode, none, bf);
+        } else {
+          bias_act_bwd(B.y0.data(), dy.data(), dx.data(), G + p.bias, M_in, p.d.c_in, 1, bf);
+        }
+        dy.swap(dx);
+        continue;
+      }
       // residual branch, last conv held here to first; dsc: gradient w.r.t. the shortcut value
       std::vector<T> dr = dy;
       std::vector<T> dsc;
@@ -637,6 +895,18 @@ bool valid(const Desc& d) {
   if (d.last_to > 0 && (nb == 0 || d.has_head)) return false;
   for (int i = 0; i < nb; ++i) {
     const BlockDesc& b = d.blocks[i];
+    if (b.kind >= K_POSTACT && b.kind <= K_BIAS_RELU) {
+      if ((i == 0 && d.first_from > 0) || (i == nb - 1 && d.last_to > 0)) return false;   // no cuts inside these units
+      if (b.c_in != c || b.c_out <= 0) return false;
+      if (b.kind == K_POSTACT && (b.c_mid != b.c_out || (b.stride != 1 && b.stride != 2))) return false;
+      if (b.kind == K_CONV_RELU && (b.stride != 1 && b.stride != 2)) return false;
+      if ((b.kind == K_DENSE || b.kind == K_BN_RELU || b.kind == K_BIAS_RELU) && b.stride != 1) return false;
+      if ((b.kind == K_BN_RELU || b.kind == K_BIAS_RELU) && b.c_in != b.c_out) return false;
+      if (b.kind == K_DENSE) { h = 1; w = 1; }
+      else { if (h % b.stride || w % b.stride) return false; h /= b.stride; w /= b.stride; }
+      c = b.c_out;
+      continue;
+    }
     if (b.kind != 0 && b.kind != 1) return false;
     const int nconv = b.kind == 0 ? 2 : 3;
     const int j0 = i == 0 ? d.first_from : 0, j1 = (i == nb - 1 && d.last_to > 0) ? d.last_to : nconv;
@@ -662,14 +932,14 @@ bool valid(const Desc& d) {
 extern "C" {
 
 // desc_i: in_h,in_w,in_c,has_stem,stem_c_out,n_blocks,has_head,num_classes,microbatch,
-//         num_microbatches,loss_divisor,bn_mode,storage,first_from,last_to ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
+//         num_microbatches,loss_divisor,bn_mode,storage,first_from,last_to,head_bn ; blocks: n_blocks x (kind,c_in,c_mid,c_out,stride)
 void* oracle_partition_create(const int32_t* desc_i, double bn_eps, const int32_t* blocks,
                               const void* host_params, int is_f64) {
   Desc d;
   d.in_h = desc_i[0]; d.in_w = desc_i[1]; d.in_c = desc_i[2]; d.has_stem = desc_i[3];
   d.stem_c_out = desc_i[4]; d.n_blocks = desc_i[5]; d.has_head = desc_i[6]; d.num_classes = desc_i[7];
   d.microbatch = desc_i[8]; d.num_microbatches = desc_i[9]; d.loss_divisor = desc_i[10]; d.bn_mode = desc_i[11];
-  d.storage = desc_i[12]; d.first_from = desc_i[13]; d.last_to = desc_i[14];
+  d.storage = desc_i[12]; d.first_from = desc_i[13]; d.last_to = desc_i[14]; d.head_bn = desc_i[15];
   d.bn_eps = bn_eps;
   for (int i = 0; i < d.n_blocks; ++i)
     d.blocks.push_back(BlockDesc{blocks[5 * i], blocks[5 * i + 1], blocks[5 * i + 2], blocks[5 * i + 3], blocks[5 * i + 4]});
@@ -801,7 +1071,22 @@ int oracle_params_write(void* hp, const void* src, size_t n) {
     return head_fwd<T>(a, wfc, bfc, labels, g, dlogits, n, hw, C, classes, divisor); }                  \
   void oracle_head_bwd_##SUF(const T* g, const T* dl, const T* wfc, double* dwfc, double* dbfc, T* da,  \
                              int n, int hw, int C, int classes) {                                       \
-    head_bwd<T>(g, dl, wfc, dwfc, dbfc, da, n, hw, C, classes); }
+    head_bwd<T>(g, dl, wfc, dwfc, dbfc, da, n, hw, C, classes); }                                       \
+  void oracle_bias_act_fwd_##SUF(const T* x, const T* bias, T* y, size_t M, int C, int relu) {          \
+    bias_act_fwd<T>(x, bias, y, M, C, relu); }                                                          \
+  void oracle_bias_act_bwd_##SUF(const T* y, const T* dy, T* dx, double* db, size_t M, int C, int relu) { \
+    bias_act_bwd<T>(y, dy, dx, db, M, C, relu); }                                                       \
+  void oracle_maxpool2_fwd_##SUF(const T* x, T* y, int n, int h, int w, int C) {                        \
+    maxpool2_fwd<T>(x, y, n, h, w, C); }                                                                \
+  void oracle_maxpool2_bwd_##SUF(const T* x, const T* dy, T* dx, int n, int h, int w, int C) {          \
+    maxpool2_bwd<T>(x, dy, dx, n, h, w, C); }                                                           \
+  void oracle_bn_add_relu_fwd_##SUF(const T* x, const T* g, const T* b, const T* add, T* y, double* mean, \
+                                    double* invstd, size_t M, int C, double eps, int mode) {            \
+    bn_add_relu_fwd<T>(x, g, b, add, y, mean, invstd, M, C, eps, mode); }                               \
+  void oracle_bn_add_relu_bwd_##SUF(const T* x, const T* y, const T* dy, const T* g, const double* mean, \
+                                    const double* invstd, T* dx, T* dadd, double* dg, double* db,       \
+                                    size_t M, int C, int mode) {                                        \
+    bn_add_relu_bwd<T>(x, y, dy, g, mean, invstd, dx, dadd, dg, db, M, C, mode); }
 
 float oracle_round_bf16(float v) { return rnd<float>(v, 1); }
 

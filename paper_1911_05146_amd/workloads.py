@@ -26,6 +26,11 @@ import numpy as np
 
 BASIC = 0
 BOTTLENECK = 1
+POSTACT = 2      # ResNet-v1 basic block: conv3x3(stride) - bn - relu - conv3x3 - bn, + shortcut, relu
+CONV_RELU = 3    # plain (VGG) unit: conv3x3 + bias + relu, followed by a 2x2 max-pool iff stride == 2
+DENSE = 4        # flatten - fully connected + bias, relu iff c_mid != 0
+BN_RELU = 5      # BatchNorm + relu on its own (the stem of ResNet-v1 is conv - bn - relu)
+BIAS_RELU = 6    # bias + relu on its own (VGG's first convolution is the stem, its bias and relu this unit)
 
 SEED_BASE = 191105146
 
@@ -37,6 +42,15 @@ class Block:
     kind BASIC:      bn-relu-conv3x3(stride) - bn-relu-conv3x3, c_mid == c_out
     kind BOTTLENECK: bn-relu-conv1x1(stride) - bn-relu-conv3x3 - bn-relu-conv1x1
     A 1x1 projection shortcut (same stride) exists iff stride != 1 or c_in != c_out.
+
+    The units of the paper's other two models (Section "Model-Parallelism on a Single Node": ResNet-110-v1,
+    VGG-16), which are not pre-activation residual blocks:
+    kind POSTACT:    y = relu(bn2(conv3x3(relu(bn1(conv3x3_stride(x))))) + shortcut), c_mid == c_out; shortcut = x, or
+                     a 1x1 convolution (same stride, no BatchNorm) of x iff stride != 1 or c_in != c_out
+    kind CONV_RELU:  relu(conv3x3(x) + bias) with padding 1, then a 2x2 max-pool of stride 2 iff stride == 2
+    kind DENSE:      flatten(x) * W + bias, relu iff c_mid != 0; the output is 1 x 1 x c_out
+    kind BN_RELU:    relu(bn(x)), c_in == c_out
+    kind BIAS_RELU:  relu(x + bias), c_in == c_out
     """
     kind: int
     c_in: int
@@ -46,7 +60,12 @@ class Block:
 
     @property
     def has_proj(self) -> bool:
-        return self.stride != 1 or self.c_in != self.c_out
+        return self.kind in (BASIC, BOTTLENECK, POSTACT) and (self.stride != 1 or self.c_in != self.c_out)
+
+    @property
+    def residual(self) -> bool:
+        """A pre-activation residual block (the only kinds that can be cut at layer granularity)."""
+        return self.kind in (BASIC, BOTTLENECK)
 
 
 @dataclass(frozen=True)
@@ -60,6 +79,7 @@ class PartitionSpec:
     stem_c_out: int = 0
     has_head: bool = False
     num_classes: int = 0
+    head_bn: bool = True           # the head starts with BatchNorm + relu (pre-activation models); False: pool - FC only
     microbatch: int = 1
     num_microbatches: int = 1
     loss_divisor: int = 0          # full batch B; 0 -> microbatch * num_microbatches
@@ -83,6 +103,8 @@ class PartitionSpec:
 
     def conv_range(self, i: int) -> Tuple[int, int]:
         """[j0, j1): the convolutions of block i that this partition holds."""
+        if not self.blocks[i].residual:
+            return 0, {POSTACT: 2, CONV_RELU: 1, DENSE: 1, BN_RELU: 0, BIAS_RELU: 0}[self.blocks[i].kind]
         n = 2 if self.blocks[i].kind == BASIC else 3
         j0 = self.first_from if i == 0 else 0
         j1 = self.last_to if (i == len(self.blocks) - 1 and self.last_to > 0) else n
@@ -93,6 +115,14 @@ class PartitionSpec:
         h, w = self.in_h, self.in_w
         c = self.stem_c_out if self.has_stem else self.in_c
         for i, b in enumerate(self.blocks):
+            if not b.residual:
+                assert b.c_in == c, (self.name, b, c)
+                if b.kind == DENSE:
+                    h, w = 1, 1
+                else:
+                    h, w = h // b.stride, w // b.stride
+                c = b.c_out
+                continue
             j0, j1 = self.conv_range(i)
             n = 2 if b.kind == BASIC else 3
             if j0 == 0:
@@ -225,6 +255,59 @@ def resnet1001_wide_partition(p=7, n_parts=16, microbatch=32, num_microbatches=8
                         32, 16, 16, 10, microbatch, num_microbatches, seed)
 
 
+def resnet_v1_blocks(n_per_stage: int, widths=(16, 32, 64)) -> List[Block]:
+    """ResNet-v1 for 32x32 images (6n+2 layers: n = 18 gives the ResNet-110 the paper trains): after the stem
+    (conv3x3 - BatchNorm - relu) three stages of n post-activation basic blocks; the first block of stages 2 and 3
+    halves the resolution and doubles the width, its shortcut is a 1x1 convolution of stride 2."""
+    blocks, c = [Block(BN_RELU, widths[0], widths[0], widths[0], 1)], widths[0]
+    for s, wdt in enumerate(widths):
+        for i in range(n_per_stage):
+            blocks.append(Block(POSTACT, c, wdt, wdt, 2 if (s > 0 and i == 0) else 1))
+            c = wdt
+    return blocks
+
+
+def resnet110_v1(n_parts=1, p=0, microbatch=16, num_microbatches=8, seed=SEED_BASE + 7, n_per_stage=18) -> PartitionSpec:
+    """Partition p of n_parts of ResNet-110-v1 (paper Section "Model-Parallelism on a Single Node"): units = the stem's
+    BatchNorm-relu and 54 post-activation blocks; the head is global average pool - FC (no BatchNorm)."""
+    spec = partition_of(f"resnet{6 * n_per_stage + 2}v1-part{p}of{n_parts}", resnet_v1_blocks(n_per_stage), n_parts, p,
+                        32, 16, 16, 10, microbatch, num_microbatches, seed)
+    return replace(spec, head_bn=False)
+
+
+def vgg16_blocks(in_hw=32, widths=(64, 128, 256, 512, 512), convs=(2, 2, 3, 3, 3), dense=(4096, 4096), in_c=3) -> List[Block]:
+    """VGG-16 (configuration D of the VGG paper: 13 convolutions 3x3 in five groups, each group followed by a 2x2
+    max-pool, then fully connected layers), the paper's third model; on 32x32 images the last pool leaves 1 x 1 x 512.
+    The last fully connected layer (-> classes) with the softmax is the partition's head."""
+    blocks, c = [Block(BIAS_RELU, widths[0], widths[0], widths[0], 1)], widths[0]   # after the stem convolution
+    for g, (wdt, n) in enumerate(zip(widths, convs)):
+        for i in range(1 if g == 0 else 0, n):
+            blocks.append(Block(CONV_RELU, c, wdt, wdt, 2 if i == n - 1 else 1))
+            c = wdt
+    for d in dense:
+        blocks.append(Block(DENSE, c, 1, d, 1))
+        c = d
+    return blocks
+
+
+def vgg16(n_parts=1, p=0, microbatch=16, num_microbatches=8, seed=SEED_BASE + 8, **kw) -> PartitionSpec:
+    """Partition p of n_parts of VGG-16 on 32x32x3 images, cut at unit boundaries (the paper runs it in up to 8
+    partitions).  The first convolution (3 -> 64 channels, on the fp32 image) is the partition's stem; its bias and
+    relu are the first unit."""
+    blocks = vgg16_blocks(**kw)
+    lo, hi = split_range(len(blocks), n_parts, p)
+    h = w = kw.get("in_hw", 32)
+    c = blocks[0].c_in
+    for b in blocks[:lo]:
+        h, w = (1, 1) if b.kind == DENSE else (h // b.stride, w // b.stride)
+        c = b.c_out
+    first, last = p == 0, p == n_parts - 1
+    return PartitionSpec(name=f"vgg16-part{p}of{n_parts}", in_h=h, in_w=w, in_c=kw.get("in_c", 3) if first else c,
+                         blocks=tuple(blocks[lo:hi]), has_stem=first, stem_c_out=blocks[0].c_in if first else 0,
+                         has_head=last, num_classes=10 if last else 0, head_bn=False, microbatch=microbatch,
+                         num_microbatches=num_microbatches, seed=seed)
+
+
 def config(index: int) -> PartitionSpec:
     """The five benchmark configurations, numbered 1..5, and 6: the same cut of the wider ResNet-1001."""
     return {1: resnet20, 2: resnet110_partition, 3: resnet1001_partition,
@@ -267,8 +350,35 @@ def param_layout(spec: PartitionSpec) -> List[ParamEntry]:
 
     if spec.has_stem:
         add("stem.W", (3, 3, spec.in_c, spec.stem_c_out), "conv")
+    h, w = spec.in_h, spec.in_w
     for i, b in enumerate(spec.blocks):
         p = f"block{i}."
+        if not b.residual:
+            if b.kind == POSTACT:
+                add(p + "W1", (3, 3, b.c_in, b.c_mid), "conv")
+                add(p + "bn1.gamma", (b.c_mid,), "gamma")
+                add(p + "bn1.beta", (b.c_mid,), "beta")
+                add(p + "W2", (3, 3, b.c_mid, b.c_out), "conv")
+                add(p + "bn2.gamma", (b.c_out,), "gamma")
+                add(p + "bn2.beta", (b.c_out,), "beta")
+                if b.has_proj:
+                    add(p + "Wproj", (1, 1, b.c_in, b.c_out), "conv")
+                h, w = h // b.stride, w // b.stride
+            elif b.kind == CONV_RELU:
+                add(p + "W", (3, 3, b.c_in, b.c_out), "conv")
+                add(p + "bias", (b.c_out,), "bias")
+                h, w = h // b.stride, w // b.stride
+            elif b.kind == DENSE:
+                add(p + "W", (h * w * b.c_in, b.c_out), "fc")
+                add(p + "bias", (b.c_out,), "bias")
+                h, w = 1, 1
+            elif b.kind == BN_RELU:
+                add(p + "bn.gamma", (b.c_in,), "gamma")
+                add(p + "bn.beta", (b.c_in,), "beta")
+            else:
+                add(p + "bias", (b.c_in,), "bias")
+            continue
+        h, w = h // b.stride, w // b.stride
         j0, j1 = spec.conv_range(i)
         cin = (b.c_in, b.c_mid, b.c_mid)
         cout = (b.c_mid, b.c_out, None) if b.kind == BASIC else (b.c_mid, b.c_mid, b.c_out)
@@ -281,8 +391,9 @@ def param_layout(spec: PartitionSpec) -> List[ParamEntry]:
             add(p + "Wproj", (1, 1, b.c_in, b.c_out), "conv")
     if spec.has_head:
         c = spec.out_shape()[2]
-        add("head.bn.gamma", (c,), "gamma")
-        add("head.bn.beta", (c,), "beta")
+        if spec.head_bn:
+            add("head.bn.gamma", (c,), "gamma")
+            add("head.bn.beta", (c,), "beta")
         add("head.Wfc", (c, spec.num_classes), "fc")
         add("head.bfc", (spec.num_classes,), "bias")
     return out
