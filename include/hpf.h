@@ -64,11 +64,25 @@ typedef enum {
   HPF_BF16 = 1 /* bf16 tensors and MFMA operands, fp32 accumulation, fp32 statistics/gradients */
 } hpf_dtype;
 
-/* One pre-activation residual block.
- * kind 0 (basic):      bn-relu-conv3x3(stride) -> bn-relu-conv3x3;            c_mid must equal c_out
- * kind 1 (bottleneck): bn-relu-conv1x1(stride) -> bn-relu-conv3x3 -> bn-relu-conv1x1
- * Shortcut: identity if stride == 1 and c_in == c_out, else a 1x1 convolution (same stride) of the
- * block's first bn-relu output.  3x3 convolutions use symmetric zero padding 1; no conv bias. */
+/* One unit of the partition.
+ * Pre-activation residual blocks (the ResNets of the benchmark configurations):
+ *   kind 0 (basic):      bn-relu-conv3x3(stride) -> bn-relu-conv3x3;            c_mid must equal c_out
+ *   kind 1 (bottleneck): bn-relu-conv1x1(stride) -> bn-relu-conv3x3 -> bn-relu-conv1x1
+ *   Shortcut: identity if stride == 1 and c_in == c_out, else a 1x1 convolution (same stride) of the
+ *   block's first bn-relu output.  3x3 convolutions use symmetric zero padding 1; no conv bias.
+ * Units of the paper's two other models (Section "Model-Parallelism on a Single Node": ResNet-110-v1, VGG-16);
+ * they run as plain per-layer launches at every fusion level, cannot be cut inside, and keep every intermediate:
+ *   kind 2 (post-activation basic block): y = relu(bn2(conv3x3(relu(bn1(conv3x3_stride(x))))) + shortcut), c_mid == c_out;
+ *           shortcut = x, or a 1x1 convolution (same stride, no BatchNorm) of x iff stride != 1 or c_in != c_out.
+ *           Parameters: W1, bn1.gamma, bn1.beta, W2, bn2.gamma, bn2.beta, [Wproj].
+ *   kind 3 (conv unit):  relu(conv3x3(x) + bias), padding 1, stride 1; a 2x2 max-pool of stride 2 follows iff
+ *           `stride` == 2 (its gradient goes to the first maximum of a window in row-major order).  Parameters: W, bias.
+ *   kind 4 (dense unit): flatten(x) [h*w*c_in, in h, w, c order] * W + bias, relu iff c_mid != 0; the output is
+ *           1 x 1 x c_out.  Parameters: W [h*w*c_in][c_out], bias.  stride must be 1.
+ *   kind 5 (bn-relu):    relu(bn(x)), c_in == c_out (the stem of ResNet-v1 is has_stem followed by this unit).
+ *           Parameters: gamma, beta.
+ *   kind 6 (bias-relu):  relu(x + bias), c_in == c_out (VGG's first convolution is has_stem followed by this unit).
+ *           Parameters: bias. */
 typedef struct {
   int32_t kind;
   int32_t c_in, c_mid, c_out;
@@ -81,7 +95,8 @@ typedef struct {
   int32_t has_stem, stem_c_out;   /* first partition: 3x3 stride-1 conv in_c -> stem_c_out */
   int32_t n_blocks;
   const hpf_block_desc* blocks;   /* (host) n_blocks entries, copied */
-  int32_t has_head, num_classes;  /* last partition: bn-relu, global average pool, FC+bias, softmax-CE */
+  int32_t has_head, num_classes;  /* last partition: 1 = bn-relu, global average pool, FC+bias, softmax-CE;
+                                     2 = the same without the bn-relu (ResNet-v1, VGG: parameters Wfc, bfc only) */
   int32_t microbatch;             /* images per micro-batch */
   int32_t num_microbatches;       /* micro-batches per batch */
   int32_t loss_divisor;           /* full batch size B: loss = sum over samples of CE / B */
@@ -205,9 +220,17 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per
  *      image, all of them on the chip together.  Needs microbatch <= number of CUs; a group call
  *      then processes floor(CUs / microbatch) micro-batches (at most 8) per launch, and launches
- *      of this kind from all streams and partitions of the process are serialised.  If a launch
- *      ever waits in vain for its partner work-groups it gives up after about a second and the
- *      next hpf_grad_accum_read to host memory or hpf_params_read returns HPF_EDEVICE.
+ *      of this kind from all streams and partitions of the process are serialised through events
+ *      recorded at call time.  A stream that the CALLER is capturing into a graph cannot take part
+ *      in that: forward / backward calls on such a stream return HPF_EUNSUPPORTED at level 2 when the
+ *      partition has such runs -- set level 1 for partitions whose calls are captured.  If a launch
+ *      ever waits in vain for its partner work-groups it gives up after about a second and sets a
+ *      flag in the arena that marks the handle's results invalid.  The flag is sticky (it stays set
+ *      until the handle is destroyed) and is reported as HPF_EDEVICE by every call that already
+ *      blocks -- hpf_grad_accum_read to host memory, hpf_params_read, hpf_bn_running_read,
+ *      hpf_partition_profile_read, hpf_stash_read -- and by hpf_partition_check; hpf_sgd_step tests it
+ *      on the device and then leaves parameters, momentum and gradients untouched; the calls that
+ *      only enqueue work (hpf_grad_accum_read to device memory among them) cannot report it.
  * Not allowed while a micro-batch is between forward and backward (HPF_ESTATE). */
 hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
 
@@ -268,6 +291,16 @@ hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entri
 
 /* fp32 master parameters to host_dst (host), canonical order.  Blocks. */
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats);
+
+/* Waits for all work of the device and reports what only a blocking call can: HPF_EDEVICE if a HIP error is
+ * pending or if an image-resident launch of this handle ever gave up waiting (see hpf_partition_set_fusion).  For
+ * callers that read the gradients into device memory and never through a blocking call. */
+hpf_status hpf_partition_check(hpf_partition* p);
+
+/* Test aid: writes the handle's "results invalid" flag from the host (a plain copy into the arena after a device
+ * synchronisation; no kernel runs), so that the error path of the calls above can be tested without making a
+ * launch time out.  HPF_EUNSUPPORTED for a partition without image-resident runs (it has no such flag). */
+hpf_status hpf_debug_set_invalid(hpf_partition* p, int32_t value);
 
 /* Test and debugging aid: reads one of the tensors that back-propagation keeps per micro-batch (paper Section
  * "Implementing Distributed Back-Propagation": the layer inputs of the forward pass and the partial errors of

@@ -199,6 +199,25 @@ hipError_t launch_bn_bwd_apply(int dt, int g, const PtrTab& x, const PtrTab& da,
                                const PtrTab& stats, const PtrTab& sums, const PtrTab& skip, const PtrTab& dx, int M,
                                int C, int frozen, hipStream_t stream);
 hipError_t launch_bn_frozen_stats(int dt, int g, const PtrTab& stats, int C, float eps, hipStream_t stream);
+
+// Layers of VGG-16 and of the post-activation ResNet-v1 block; tensors [M, C] (or b x h x w x C) of dtype dt, C % 8 == 0.
+// y = x + bias[c], then max(., 0) when relu.
+hipError_t launch_bias_act_fwd(int dt, int g, const PtrTab& x, const PtrTab& y, const float* bias, int M, int C, int relu,
+                               hipStream_t stream);
+// dx = dy * [y > 0] (relu) or dy; g_bias[c] += sum of dx over the rows.  sums / partials: scratch as for the BatchNorm backward.
+hipError_t launch_bias_act_bwd(int dt, int g, const PtrTab& y, const PtrTab& dy, const PtrTab& dx, float* g_bias, int M, int C,
+                               int relu, const PtrTab& sums, const PtrTab& partials, hipStream_t stream);
+// 2x2 max-pool of stride 2 (h, w even) and its backward pass (gradient to the first maximum in row-major order).
+hipError_t launch_maxpool2_fwd(int dt, int g, const PtrTab& x, const PtrTab& y, int b, int h, int w, int C, hipStream_t stream);
+hipError_t launch_maxpool2_bwd(int dt, int g, const PtrTab& x, const PtrTab& dy, const PtrTab& dx, int b, int h, int w, int C,
+                               hipStream_t stream);
+// Residual join of a post-activation block, y = max(bn(x) + add, 0) (statistics given), and its backward pass:
+// dz = dy * [y > 0]; dadd = dz; dx through the BatchNorm; dgamma / dbeta added into g_gamma / g_beta.
+hipError_t launch_bn_add_relu_apply(int dt, int g, const PtrTab& x, const PtrTab& add, const PtrTab& y, const float* gamma,
+                                    const float* beta, const PtrTab& stats, int M, int C, hipStream_t stream);
+hipError_t launch_join_bwd(int dt, int g, const PtrTab& x, const PtrTab& y, const PtrTab& dy, const float* gamma, const PtrTab& stats,
+                           int M, int C, const PtrTab& sums, float* g_gamma, float* g_beta, const PtrTab& partials, const PtrTab& dx,
+                           const PtrTab& dadd, int frozen, hipStream_t stream);
 // Running statistics (fp32): per BatchNorm mean[C] then variance[C] at run_off floats into `running`.
 struct BnRunDesc { unsigned long long stats_off; int C; int run_off; };   // stats_off: bytes into a member's region
 // After a training forward: for the group's members in order, r <- momentum*r + (1-momentum)*{mean, 1/invstd^2 - eps}.
@@ -222,7 +241,8 @@ hipError_t launch_head_fwd(int dt, int g, const PtrTab& a, const float* wfc, con
 hipError_t launch_head_bwd(int dt, int g, const PtrTab& gp, const PtrTab& dlogits, const float* wfc, float* g_wfc,
                            float* g_bfc, const PtrTab& da, int b, int hw, int C, int classes, hipStream_t stream);
 
-hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, hipStream_t stream);
+// invalid (device, may be null): when it reads non-zero the step changes nothing
+hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, const int* invalid, hipStream_t stream);
 hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream);
 hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
                                hipStream_t stream);

@@ -60,7 +60,15 @@ struct BlockPlan {
   bool mat[3] = {false, false, false};   // bf16 mode: a[j] = relu(bn_j(.)) is written to memory (else applied while staging)
   Loc gy;      // gradient w.r.t. the block output (kept until the deferred weight-gradient pass)
   Loc dc[2];   // gradient w.r.t. c[j], the output of conv j (j < nconv-1)
+  // units of the other models (kinds HPF_POSTACT ... HPF_BIAS_RELU)
+  size_t bias_off = 0;   // floats: the unit's bias vector
+  Loc y0;                // conv + bias + relu output before the max-pool (== y without a pool)
+  Loc sc;                // post-activation block: the projected shortcut (== x_in for an identity shortcut)
+  bool copy_out = false; // the unit is the partition's last and its backward pass reads y: y stays in the arena and a
+                         // copy goes to the caller's act_out (a backward call is not handed the forward's act_out)
+  bool residual() const { return d.kind == 0 || d.kind == 1; }
 };
+enum : int { K_POSTACT = 2, K_CONV_RELU = 3, K_DENSE = 4, K_BN_RELU = 5, K_BIAS_RELU = 6 };
 
 struct Plan {
   hpf_partition_desc d{};
@@ -118,6 +126,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (!(d.bn_eps > 0.f)) return fail(HPF_EINVAL, "bn_eps must be positive");
   if (d.has_stem && d.stem_c_out <= 0) return fail(HPF_EINVAL, "stem_c_out must be positive");
   if (d.has_head && d.num_classes <= 0) return fail(HPF_EINVAL, "num_classes must be positive");
+  if (d.has_head < 0 || d.has_head > 2) return fail(HPF_EINVAL, "has_head must be 0, 1 or 2");
   P.blocks.assign(d.blocks, d.blocks + d.n_blocks);
   P.d.blocks = nullptr;
   P.dt = d.compute_dtype == HPF_BF16 ? DT_BF16 : DT_F32;
@@ -128,12 +137,27 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   int h = d.in_h, w = d.in_w, c = d.has_stem ? d.stem_c_out : d.in_c;
   if (c % cmul) return fail(HPF_EUNSUPPORTED, "channel count %d is not a multiple of %d", c, cmul);
   const int cmax = 1024;   // bf16 mode keeps a per-channel table of the source tensor in LDS
-  if (P.dt == DT_BF16 && c > cmax) return fail(HPF_EUNSUPPORTED, "more than %d channels", cmax);
   if (d.first_block_from_conv < 0 || d.last_block_to_conv < 0) return fail(HPF_EINVAL, "negative layer cut");
   if (d.first_block_from_conv > 0 && (d.n_blocks == 0 || d.has_stem)) return fail(HPF_EINVAL, "first_block_from_conv needs a first block and no stem");
   if (d.last_block_to_conv > 0 && (d.n_blocks == 0 || d.has_head)) return fail(HPF_EINVAL, "last_block_to_conv needs a last block and no head");
   for (int i = 0; i < d.n_blocks; ++i) {
     const hpf_block_desc& b = P.blocks[i];
+    if (b.kind >= K_POSTACT && b.kind <= K_BIAS_RELU) {   // units of VGG-16 / ResNet-v1: no cuts inside them
+      if ((i == 0 && d.first_block_from_conv > 0) || (i == d.n_blocks - 1 && d.last_block_to_conv > 0))
+        return fail(HPF_EINVAL, "block %d: layer cuts exist only inside pre-activation residual blocks", i);
+      if (b.c_out <= 0 || b.c_in != c) return fail(HPF_EINVAL, "block %d: c_in %d does not continue the chain (%d)", i, b.c_in, c);
+      if (b.kind == K_POSTACT && b.c_mid != b.c_out) return fail(HPF_EINVAL, "block %d: a post-activation block needs c_mid == c_out", i);
+      if ((b.kind == K_BN_RELU || b.kind == K_BIAS_RELU) && b.c_in != b.c_out) return fail(HPF_EINVAL, "block %d: c_in must equal c_out", i);
+      const bool strided = b.kind == K_POSTACT || b.kind == K_CONV_RELU;
+      if (b.stride != 1 && !(strided && b.stride == 2)) return fail(HPF_EINVAL, "block %d: stride %d", i, b.stride);
+      if (h % b.stride || w % b.stride) return fail(HPF_EINVAL, "block %d: %dx%d not divisible by stride", i, h, w);
+      const long flat = (long)h * w * b.c_in;
+      if (b.kind == K_DENSE && flat > (1 << 20)) return fail(HPF_EUNSUPPORTED, "block %d: dense input of %ld values", i, flat);
+      if (b.c_in % cmul || b.c_out % cmul) return fail(HPF_EUNSUPPORTED, "block %d: channel counts must be multiples of %d", i, cmul);
+      if (b.kind == K_DENSE) { h = 1; w = 1; } else { h /= b.stride; w /= b.stride; }
+      c = b.c_out;
+      continue;
+    }
     if (b.kind != 0 && b.kind != 1) return fail(HPF_EINVAL, "block %d: kind %d", i, b.kind);
     const int nconv = b.kind == 0 ? 2 : 3;
     const int j0 = i == 0 ? d.first_block_from_conv : 0;
@@ -198,6 +222,35 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const hpf_block_desc& b = P.blocks[i];
     p.d = b;
+    if (!p.residual()) {
+      p.h_in = h; p.w_in = w;
+      p.h_out = b.kind == K_DENSE ? 1 : h / b.stride; p.w_out = b.kind == K_DENSE ? 1 : w / b.stride;
+      p.j0 = 0;
+      if (b.kind == K_POSTACT) {
+        p.nconv = 2;
+        p.proj = (b.stride != 1 || b.c_in != b.c_out);
+        p.cv[0] = mk_conv(b.c_in, b.c_mid, 3, b.stride, h, w); p.bn[0] = mk_bn(b.c_mid);
+        p.cv[1] = mk_conv(b.c_mid, b.c_out, 3, 1, p.h_out, p.w_out); p.bn[1] = mk_bn(b.c_out);
+        if (p.proj) p.pj = mk_conv(b.c_in, b.c_out, 1, b.stride, h, w);
+        add_pack(p.cv[0], p.cv[0].cin, true); add_pack(p.cv[1], p.cv[1].cin, true);
+        if (p.proj) add_pack(p.pj, p.pj.cin, true);
+      } else if (b.kind == K_CONV_RELU) {
+        p.nconv = 1;
+        p.cv[0] = mk_conv(b.c_in, b.c_out, 3, 1, h, w); p.bias_off = off; off += b.c_out;
+        add_pack(p.cv[0], p.cv[0].cin, true);
+      } else if (b.kind == K_DENSE) {
+        p.nconv = 1;
+        p.cv[0] = mk_conv(h * w * b.c_in, b.c_out, 1, 1, 1, 1); p.bias_off = off; off += b.c_out;
+        add_pack(p.cv[0], p.cv[0].cin, true);
+      } else if (b.kind == K_BN_RELU) {
+        p.nconv = 0; p.bn[0] = mk_bn(b.c_in);
+      } else {
+        p.nconv = 0; p.bias_off = off; off += b.c_in;
+      }
+      p.j1 = p.nconv;
+      h = p.h_out; w = p.w_out;
+      continue;
+    }
     p.nconv = b.kind == 0 ? 2 : 3;
     p.j0 = i == 0 ? d.first_block_from_conv : 0;
     p.j1 = (i == d.n_blocks - 1 && d.last_block_to_conv > 0) ? d.last_block_to_conv : p.nconv;
@@ -218,7 +271,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     h = p.h_out; w = p.w_out;
   }
   if (d.has_head) {
-    P.head_bn = mk_bn(P.out_c);
+    if (d.has_head == 1) P.head_bn = mk_bn(P.out_c);
     P.wfc_off = off; off += (size_t)P.out_c * d.num_classes;
     P.bfc_off = off; off += d.num_classes;
   }
@@ -257,6 +310,37 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   for (int i = 0; i < d.n_blocks; ++i) {
     BlockPlan& p = P.bp[i];
     const size_t M_in = b_ * p.h_in * p.w_in, M_out = b_ * p.h_out * p.w_out;
+    if (!p.residual()) {   // every intermediate tensor of these units is kept; nothing is recomputed
+      const bool to_caller = (i == d.n_blocks - 1) && !d.has_head;
+      // needs_y: the unit's backward pass reads its output (the ReLU decision is taken on y)
+      auto out_tensor = [&](size_t elems, bool needs_y) {
+        if (to_caller && !needs_y) { Loc l; l.kind = CALLER_ACT_OUT; if (elems > max_elems) max_elems = elems; return l; }
+        if (to_caller) p.copy_out = true;
+        return tensor(elems);
+      };
+      p.x_in = cur;
+      if (p.d.kind == K_POSTACT) {
+        stats(p.bn[0], M_out); stats(p.bn[1], M_out);
+        p.c[0] = tensor(M_out * p.d.c_mid); p.a[0] = tensor(M_out * p.d.c_mid); p.c[1] = tensor(M_out * p.d.c_out);
+        p.sc = p.proj ? tensor(M_out * p.d.c_out) : p.x_in;
+        p.y = out_tensor(M_out * p.d.c_out, true);
+      } else if (p.d.kind == K_CONV_RELU) {
+        if (p.d.stride == 2) { p.y0 = tensor(M_in * p.d.c_out); p.y = out_tensor(M_out * p.d.c_out, false); }
+        else { p.y = out_tensor(M_out * p.d.c_out, true); p.y0 = p.y; }
+      } else if (p.d.kind == K_DENSE) {
+        p.y = out_tensor(b_ * p.d.c_out, true); p.y0 = p.y;
+      } else if (p.d.kind == K_BN_RELU) {
+        stats(p.bn[0], M_in);
+        p.y = out_tensor(M_in * p.d.c_in, false); p.a[0] = p.y;   // the mask is recomputed from x
+      } else {
+        p.y = out_tensor(M_in * p.d.c_in, true); p.y0 = p.y;
+      }
+      if (M_in * p.d.c_in > max_elems) max_elems = M_in * p.d.c_in;
+      if (M_in * p.d.c_out > max_elems) max_elems = M_in * p.d.c_out;
+      if (p.d.c_out > max_c) max_c = p.d.c_out;   // the bias-gradient sums use the BatchNorm scratch
+      cur = p.y;
+      continue;
+    }
     if (p.j0 == 0) p.x_in = cur; else p.c[p.j0 - 1] = cur;   // a block cut after its start takes convolution j0-1's output
     // bf16 mode: the convolutions apply a = relu(bn(x)) while staging x, so a is not written to memory -- except
     // where the staged operand is re-read so often (filter taps x channel tiles) that one pass writing a is cheaper
@@ -286,8 +370,12 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   }
   if (d.has_head) {
     P.head_x = cur;
-    stats(P.head_bn, b_ * P.out_h * P.out_w);
-    P.head_a = tensor(b_ * P.out_h * P.out_w * P.out_c);
+    if (d.has_head == 1) {
+      stats(P.head_bn, b_ * P.out_h * P.out_w);
+      P.head_a = tensor(b_ * P.out_h * P.out_w * P.out_c);
+    } else {
+      P.head_a = cur;   // global average pool - FC on the last unit's output as it is
+    }
     P.head_g = alloc(b_ * P.out_c * sizeof(float));
     P.head_dl = alloc(b_ * d.num_classes * sizeof(float));
   }
@@ -301,6 +389,10 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     BlockPlan& p = P.bp[i];
     const size_t M_out = b_ * p.h_out * p.w_out;
     const bool last = (i == d.n_blocks - 1);
+    if (!p.residual()) {
+      if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
+      continue;
+    }
     if (p.j1 == p.nconv) {
       if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
     } else {
@@ -328,7 +420,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (P.dt == DT_BF16 && d.bn_mode == 0) {
     auto eligible = [&](int i) {
       const BlockPlan& p = P.bp[i];
-      return p.whole() && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
+      return p.residual() && p.whole() && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
     };
     int cmax_run = 0;
     for (int i = 0; i < d.n_blocks;) {
@@ -389,6 +481,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr, false});
     for (int i = 0; i < d.n_blocks; ++i) {
       const BlockPlan& p = P.bp[i];
+      if (!p.residual()) continue;   // these units form their weight gradients right where the operands are at hand
       bool in_run = false;
       for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
       for (int j = p.j0; j < p.j1; ++j)
@@ -744,6 +837,9 @@ struct Ctx {
   }
 };
 
+// The unit starts with a BatchNorm on its input, so the convolution in front of it may take the statistics in its epilogue.
+bool takes_stats(const BlockPlan& p) { return p.residual() || p.d.kind == K_BN_RELU; }
+
 void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   const Plan& P = c.h->P;
   const size_t b = (size_t)P.d.microbatch;
@@ -752,7 +848,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   c.seg_same(PROF_OTHER_FWD);
   if (P.d.has_stem) {
     Loc in; in.kind = CALLER_ACT_IN;
-    const bool feeds_bn = (!P.bp.empty() && !(resident && P.run_at[0] >= 0)) || (P.bp.empty() && P.d.has_head);
+    const bool feeds_bn = (!P.bp.empty() && !(resident && P.run_at[0] >= 0) && takes_stats(P.bp[0])) || (P.bp.empty() && P.d.has_head == 1);
     if (P.dt == DT_BF16) {
       const PtrTab col = c.tab(P.stem_col);
       c.chk(launch_im2col3x3(c.g, c.tab(in), col, (int)b, P.d.in_h, P.d.in_w, P.d.in_c, P.stem_kc, c.s), "im2col");
@@ -775,6 +871,39 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     const BlockPlan& p = P.bp[bi];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
     const bool bf = (P.dt == DT_BF16);
+    if (!p.residual()) {   // a unit of VGG-16 / ResNet-v1: plain launches, every intermediate tensor kept
+      const PtrTab x = c.tab(p.x_in), y = c.tab(p.y);
+      const float* bias = c.h->params() + p.bias_off;
+      if (p.d.kind == K_POSTACT) {
+        // c1 = conv1(x); a1 = relu(bn1(c1)); c2 = conv2(a1); y = relu(bn2(c2) + shortcut)
+        const PtrTab c1 = c.tab(p.c[0]), a1 = c.tab(p.a[0]), c2 = c.tab(p.c[1]);
+        c.conv_fwd(p.cv[0], x, c1, Ctx::none());
+        c.bn_fwd(p.bn[0], c1, a1, M_out);
+        c.conv_fwd(p.cv[1], a1, c2, Ctx::none());
+        if (p.proj) c.conv_fwd(p.pj, x, c.tab(p.sc), Ctx::none());
+        c.bn_fwd(p.bn[1], c2, Ctx::none(), M_out, 0, false);   // statistics only
+        c.chk(launch_bn_add_relu_apply(P.dt, c.g, c2, c.tab(p.sc), y, c.h->params() + p.bn[1].g_off, c.h->params() + p.bn[1].b_off,
+                                       c.mbp(p.bn[1].stats_off), (int)M_out, p.bn[1].C, c.s),
+              "bn_add_relu");
+      } else if (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) {
+        const PtrTab y0 = c.tab(p.y0);
+        c.conv_fwd(p.cv[0], x, y0, Ctx::none());
+        const int rows = p.d.kind == K_DENSE ? (int)b : (int)M_in;
+        c.chk(launch_bias_act_fwd(P.dt, c.g, y0, y0, bias, rows, p.d.c_out, p.d.kind == K_DENSE ? (p.d.c_mid != 0) : 1, c.s), "bias_act");
+        if (p.d.kind == K_CONV_RELU && p.d.stride == 2)
+          c.chk(launch_maxpool2_fwd(P.dt, c.g, y0, y, (int)b, p.h_in, p.w_in, p.d.c_out, c.s), "maxpool");
+      } else if (p.d.kind == K_BN_RELU) {
+        c.bn_fwd(p.bn[0], x, y, M_in, part_rows);
+      } else {
+        c.chk(launch_bias_act_fwd(P.dt, c.g, x, y, bias, (int)M_in, p.d.c_in, 1, c.s), "bias_act");
+      }
+      if (p.copy_out) {
+        Loc lo; lo.kind = CALLER_ACT_OUT;
+        c.copy(c.tab(lo), y, b * p.h_out * p.w_out * p.d.c_out * P.esz);
+      }
+      part_rows = 0;
+      continue;
+    }
     // bf16: BN + ReLU applied inside the consuming convolutions unless the plan writes the activation out
     PtrTab shortcut{}, src{};
     bool pro = false;
@@ -801,7 +930,8 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
       const bool last = (j == p.nconv - 1);
       const PtrTab out = last ? c.tab(p.y) : c.tab(p.c[j]);
       const bool next_resident = resident && bi + 1 < P.bp.size() && P.run_at[bi + 1] >= 0;
-      const bool feeds_bn = (!last && j + 1 < p.j1) || (last && ((bi + 1 < P.bp.size() && !next_resident) || (bi + 1 == P.bp.size() && P.d.has_head)));
+      const bool feeds_bn = (!last && j + 1 < p.j1) ||
+                            (last && ((bi + 1 < P.bp.size() && !next_resident && takes_stats(P.bp[bi + 1])) || (bi + 1 == P.bp.size() && P.d.has_head == 1)));
       part_rows = c.conv_fwd(p.cv[j], src, out, last ? shortcut : Ctx::none(), feeds_bn, pro ? &p.bn[j] : nullptr);
       if (j + 1 < p.j1) {
         pro = bf && !p.mat[j + 1];
@@ -813,7 +943,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
     c.seg_same(PROF_OTHER_FWD);
-    c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M, part_rows);
+    if (P.d.has_head == 1) c.bn_fwd(P.head_bn, c.tab(P.head_x), c.tab(P.head_a), M, part_rows);
     if (c.inference) {
       Loc lo; lo.kind = CALLER_ACT_OUT;   // logits
       c.chk(launch_head_logits(P.dt, c.g, c.tab(P.head_a), c.h->params() + P.wfc_off, c.h->params() + P.bfc_off, c.tab(lo), (int)b,
@@ -850,10 +980,11 @@ void run_backward(Ctx& c) {
   c.seg_same(PROF_OTHER_BWD);
   if (P.d.has_head) {
     const size_t M = b * P.out_h * P.out_w;
+    const PtrTab dst = P.d.has_head == 1 ? tA : c.tab(grad_in_loc(P.bp.size()));   // without a BatchNorm: straight to the last unit
     c.chk(launch_head_bwd(P.dt, c.g, c.tab(P.head_g), c.tab(P.head_dl), c.h->params() + P.wfc_off, c.h->grads() + P.wfc_off,
-                          c.h->grads() + P.bfc_off, tA, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes, c.s),
+                          c.h->grads() + P.bfc_off, dst, (int)b, P.out_h * P.out_w, P.out_c, P.d.num_classes, c.s),
           "head_bwd");
-    c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
+    if (P.d.has_head == 1) c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
     if (c.h->resident() && P.run_end_at[ii] >= 0) {
@@ -865,6 +996,48 @@ void run_backward(Ctx& c) {
     c.seg_same(PROF_OTHER_BWD);
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
+    if (!p.residual()) {   // a unit of VGG-16 / ResNet-v1; weight gradients formed at once (both operands are at hand)
+      const PtrTab x = c.tab(p.x_in), dy = c.tab(p.gy), gx = c.tab(grad_in_loc(ii));
+      const PtrTab t0 = c.scratch(0), t1 = c.scratch(1), t2 = c.scratch(2), t3 = c.scratch(3);
+      const PtrTab sums = c.mbp(P.sums_off), parts = c.mbp(P.partials_off);
+      float* g_bias = c.h->grads() + p.bias_off;
+      if (p.d.kind == K_POSTACT) {
+        const PtrTab c1 = c.tab(p.c[0]), a1 = c.tab(p.a[0]), c2 = c.tab(p.c[1]);
+        // through the join: dz = dy*[y>0] (t1) feeds the shortcut, dc2 (t0) the branch
+        c.chk(launch_join_bwd(P.dt, c.g, c2, c.tab(p.y), dy, c.h->params() + p.bn[1].g_off, c.mbp(p.bn[1].stats_off), (int)M_out,
+                              p.bn[1].C, sums, c.h->grads() + p.bn[1].g_off, c.h->grads() + p.bn[1].b_off, parts, t0, t1,
+                              P.d.bn_mode, c.s),
+              "join_bwd");
+        c.conv_wgrad(p.cv[1], a1, t0);
+        c.conv_dgrad(p.cv[1], t0, t2, Ctx::none());
+        c.bn_bwd(p.bn[0], c1, t2, Ctx::none(), t3, M_out);              // dc1
+        c.conv_wgrad(p.cv[0], x, t3);
+        if (p.proj) {
+          c.conv_wgrad(p.pj, x, t1);
+          c.conv_dgrad(p.pj, t1, t0, Ctx::none());
+          c.conv_dgrad(p.cv[0], t3, gx, t0);
+        } else {
+          c.conv_dgrad(p.cv[0], t3, gx, t1);
+        }
+      } else if (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) {
+        const PtrTab y0 = c.tab(p.y0);
+        PtrTab d0 = dy;
+        if (p.d.kind == K_CONV_RELU && p.d.stride == 2) {
+          c.chk(launch_maxpool2_bwd(P.dt, c.g, y0, dy, t0, (int)b, p.h_in, p.w_in, p.d.c_out, c.s), "maxpool_bwd");
+          d0 = t0;
+        }
+        const int rows = p.d.kind == K_DENSE ? (int)b : (int)M_in;
+        c.chk(launch_bias_act_bwd(P.dt, c.g, y0, d0, t1, g_bias, rows, p.d.c_out, p.d.kind == K_DENSE ? (p.d.c_mid != 0) : 1, sums, parts, c.s),
+              "bias_act_bwd");
+        c.conv_wgrad(p.cv[0], x, t1);
+        c.conv_dgrad(p.cv[0], t1, gx, Ctx::none());
+      } else if (p.d.kind == K_BN_RELU) {
+        c.bn_bwd(p.bn[0], x, dy, Ctx::none(), gx, M_in);
+      } else {
+        c.chk(launch_bias_act_bwd(P.dt, c.g, c.tab(p.y0), dy, gx, g_bias, (int)M_in, p.d.c_in, 1, sums, parts, c.s), "bias_act_bwd");
+      }
+      continue;
+    }
     Loc lskip_err_in; lskip_err_in.kind = CALLER_SKIP_ERR_IN;
     Loc lskip_err_out; lskip_err_out.kind = CALLER_SKIP_ERR_OUT;
     // dy: gradient w.r.t. the block output, which is also the gradient w.r.t. the shortcut value.  A block that
@@ -994,14 +1167,21 @@ hpf_status run_graphed(hpf_partition* p, GraphSlot& slot, const std::vector<cons
 std::mutex g_res_mu;
 struct ResidentLink { hipEvent_t ev = nullptr; hipStream_t stream = nullptr; const hpf_partition* owner = nullptr; } g_res;
 
+// Launches of this kind are ordered against each other through events recorded at call time, which a stream under
+// capture by the caller cannot take part in: two captured partitions replayed side by side would each wait for CUs
+// the other holds.  Such calls are refused instead.
+const char* const kNoCaptureMsg =
+    "image-resident launches (fusion level 2) cannot be recorded into a caller's graph capture: call "
+    "hpf_partition_set_fusion(p, 1) for partitions whose calls are captured";
+
 hpf_status resident_enter(hpf_partition* p, hipStream_t s) {
-  if (!p->resident() || stream_is_capturing(s)) return HPF_OK;
+  if (!p->resident()) return HPF_OK;
   std::lock_guard<std::mutex> lk(g_res_mu);
   return g_res.owner ? wait_for(s, g_res.ev, g_res.stream) : HPF_OK;
 }
 // done: the event recorded on s after the call's last launch
 void resident_leave(hpf_partition* p, hipStream_t s, hipEvent_t done) {
-  if (!p->resident() || stream_is_capturing(s)) return;
+  if (!p->resident()) return;
   std::lock_guard<std::mutex> lk(g_res_mu);
   g_res.ev = done; g_res.stream = s; g_res.owner = p;
 }
@@ -1167,6 +1347,7 @@ hpf_status forward_group(hpf_partition* p, int32_t mb_first, int32_t count, cons
     if (p->fwd_done[mb_first + i]) return fail(HPF_ESTATE, "forward(%d) already ran in this batch", mb_first + i);
   }
   hipStream_t s = (hipStream_t)hip_stream;
+  if (p->resident() && stream_is_capturing(s)) return fail(HPF_EUNSUPPORTED, kNoCaptureMsg);
   if (p->step_recorded) {
     const hpf_status st = wait_for(s, p->ev_step, p->step_stream);
     if (st != HPF_OK) return st;
@@ -1243,6 +1424,7 @@ hpf_status backward_group(hpf_partition* p, int32_t mb_first, int32_t count, con
     if (p->bwd_done[mb]) return fail(HPF_ESTATE, "backward(%d) already ran in this batch", mb);
   }
   hipStream_t s = (hipStream_t)hip_stream;
+  if (p->resident() && stream_is_capturing(s)) return fail(HPF_EUNSUPPORTED, kNoCaptureMsg);
   for (int i = 0; i < count; ++i)
     if (i == 0 || p->fwd_ev[mb_first + i] != p->fwd_ev[mb_first + i - 1]) {
       const int lead = p->fwd_ev[mb_first + i];
@@ -1369,7 +1551,9 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
   const hpf_status st = wait_all_backward(p, s);
   if (st != HPF_OK) return st;
   const Plan& P = p->P;
-  if (launch_sgd(p->params(), p->mom(), p->grads(), P.n_params, lr, momentum, s) != hipSuccess) return fail(HPF_EDEVICE, "sgd failed");
+  // a batch whose image-resident launches timed out has no valid gradients: the kernel then leaves everything alone
+  if (launch_sgd(p->params(), p->mom(), p->grads(), P.n_params, lr, momentum, P.runs.empty() ? nullptr : p->abort_flag(), s) != hipSuccess)
+    return fail(HPF_EDEVICE, "sgd failed");
   if (launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, s) != hipSuccess)
     return fail(HPF_EDEVICE, "pack failed");
   begin_next_batch(p, s);
@@ -1512,6 +1696,21 @@ hpf_status hpf_partition_profile_read(hpf_partition* p, hpf_profile_entry* entri
   return check_abort_flag(p);
 }
 
+hpf_status hpf_partition_check(hpf_partition* p) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (hipDeviceSynchronize() != hipSuccess) return fail(HPF_EDEVICE, "synchronize failed: %s", hipGetErrorString(hipGetLastError()));
+  return check_abort_flag(p);
+}
+
+hpf_status hpf_debug_set_invalid(hpf_partition* p, int32_t value) {
+  if (!p) return fail(HPF_EINVAL, "null handle");
+  if (p->P.runs.empty()) return fail(HPF_EUNSUPPORTED, "the partition has no image-resident runs and therefore no such flag");
+  const int v = value != 0;
+  if (hipDeviceSynchronize() != hipSuccess || hipMemcpy(p->abort_flag(), &v, sizeof(int), hipMemcpyHostToDevice) != hipSuccess)
+    return fail(HPF_EDEVICE, "host-to-device copy failed");
+  return HPF_OK;
+}
+
 hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t tensor, void* host_dst, size_t bytes,
                           size_t* bytes_needed, int32_t* where) {
   if (!p || !where) return fail(HPF_EINVAL, "null argument");
@@ -1571,7 +1770,7 @@ hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t te
   if (hipDeviceSynchronize() != hipSuccess ||
       hipMemcpy(host_dst, p->mb_base(mb) + loc.off, need, hipMemcpyDeviceToHost) != hipSuccess)
     return fail(HPF_EDEVICE, "device-to-host copy failed");
-  return HPF_OK;
+  return check_abort_flag(p);
 }
 
 hpf_status hpf_params_read(hpf_partition* p, float* host_dst, size_t n_floats) {

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize(int C, unsigned 
     sums[c] = a1;
     sums[C + c] = a2;
     atomicAdd(&g_beta[c], (float)a1);
-    atomicAdd(&g_gamma[c], (float)a2);
+    if (g_gamma) atomicAdd(&g_gamma[c], (float)a2);
   }
 }
 
@@ -360,6 +360,225 @@ __global__ void k_bn_running_stats(PtrTab statss, const float* __restrict__ runn
   A* stats = (A*)pick(statss, blockIdx.z);
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c < C) { stats[c] = (A)running[c]; stats[C + c] = rsqrt_exact((A)running[C + c] + (A)eps); }
+}
+
+
+// ------------------------------------------------------------------------------------------------------------
+// Layers of the paper's two other models (Section "Model-Parallelism on a Single Node": VGG-16, ResNet-110-v1),
+// built on the same row / channel mapping and the same two-step reductions.
+// ------------------------------------------------------------------------------------------------------------
+// y = x + bias[c], then max(., 0) when relu.
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bias_act_fwd(PtrTab xs, PtrTab ys, const float* __restrict__ bias, int M, int C,
+                                                             int relu) {
+  const T* x = (const T*)pick(xs, blockIdx.z);   // may be y (in place)
+  T* y = (T*)pick(ys, blockIdx.z);
+  const BnMap m = bn_map(C);
+  if (!m.active) return;
+  A bs[8], v[8];
+  load8t(bias + m.c0, bs);
+  for (int r = blockIdx.x * m.rpp + m.rl; r < M; r += gridDim.x * m.rpp) {
+    load8t(x + (size_t)r * C + m.c0, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const A z = v[j] + bs[j];
+      v[j] = (relu && !(z > 0)) ? (A)0 : z;
+    }
+    store8t(y + (size_t)r * C + m.c0, v);
+  }
+}
+// dx = dz = dy * [y > 0] (relu) or dy; partial sums of dz per block of rows (record layout of the BatchNorm backward).
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bias_act_bwd(PtrTab ys, PtrTab dys, PtrTab dxs, int M, int C, int relu,
+                                                             int rows_per_block, PtrTab parts) {
+  const T* __restrict__ y = (const T*)pick(ys, blockIdx.z);
+  const T* __restrict__ dy = (const T*)pick(dys, blockIdx.z);
+  T* __restrict__ dx = (T*)pick(dxs, blockIdx.z);
+  A* __restrict__ partials = (A*)pick(parts, blockIdx.z);
+  __shared__ A sh[16][BN_THREADS];
+  const BnMap m = bn_map(C);
+  A s[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) s[j] = 0;
+  if (m.active) {
+    A v[8], d[8];
+    const int r0 = blockIdx.x * rows_per_block;
+    const int r1 = min(M, r0 + rows_per_block);
+    for (int r = r0 + m.rl; r < r1; r += m.rpp) {
+      const size_t o = (size_t)r * C + m.c0;
+      load8t(y + o, v);
+      load8t(dy + o, d);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const A dz = (!relu || v[j] > 0) ? d[j] : (A)0;
+        s[j] += dz;
+        d[j] = dz;
+      }
+      store8t(dx + o, d);
+    }
+  }
+  block_reduce16(s, m, C, sh);
+  if (m.active && m.rl == 0) {
+    A* p = partials + ((size_t)blockIdx.x * C + m.c0) * 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { p[2 * j] = s[j]; p[2 * j + 1] = 0; }
+  }
+}
+
+// 2x2 max-pool of stride 2.  One thread per output pixel and 8 channels.
+template <class T>
+__global__ __launch_bounds__(256) void k_maxpool2_fwd(PtrTab xs, PtrTab ys, int b, int h, int w, int C) {
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  T* __restrict__ y = (T*)pick(ys, blockIdx.z);
+  const int ho = h / 2, wo = w / 2, CG = C / 8;
+  const size_t total = (size_t)b * ho * wo * CG;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int cg = (int)(i % CG);
+    const size_t px = i / CG;
+    const int q = (int)(px % wo), p = (int)((px / wo) % ho), n = (int)(px / ((size_t)wo * ho));
+    float best[8], v[8];
+    load8(x + (((size_t)n * h + 2 * p) * w + 2 * q) * C + cg * 8, best);
+#pragma unroll
+    for (int t = 1; t < 4; ++t) {
+      load8(x + (((size_t)n * h + 2 * p + (t >> 1)) * w + 2 * q + (t & 1)) * C + cg * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) best[j] = v[j] > best[j] ? v[j] : best[j];
+    }
+    store8(y + px * C + cg * 8, best);
+  }
+}
+// The gradient of a window goes to its maximum; among equal maxima to the first in row-major order.
+template <class T>
+__global__ __launch_bounds__(256) void k_maxpool2_bwd(PtrTab xs, PtrTab dys, PtrTab dxs, int b, int h, int w, int C) {
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ dy = (const T*)pick(dys, blockIdx.z);
+  T* __restrict__ dx = (T*)pick(dxs, blockIdx.z);
+  const int ho = h / 2, wo = w / 2, CG = C / 8;
+  const size_t total = (size_t)b * ho * wo * CG;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int cg = (int)(i % CG);
+    const size_t px = i / CG;
+    const int q = (int)(px % wo), p = (int)((px / wo) % ho), n = (int)(px / ((size_t)wo * ho));
+    float v[4][8], d[8], o[8];
+    int arg[8];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) load8(x + (((size_t)n * h + 2 * p + (t >> 1)) * w + 2 * q + (t & 1)) * C + cg * 8, v[t]);
+    load8(dy + px * C + cg * 8, d);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float best = v[0][j];
+      arg[j] = 0;
+#pragma unroll
+      for (int t = 1; t < 4; ++t)
+        if (v[t][j] > best) { best = v[t][j]; arg[j] = t; }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = arg[j] == t ? d[j] : 0.f;
+      store8(dx + (((size_t)n * h + 2 * p + (t >> 1)) * w + 2 * q + (t & 1)) * C + cg * 8, o);
+    }
+  }
+}
+
+// Residual join of a post-activation block: y = max(gamma*xhat + beta + add, 0).
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_bn_add_relu_apply(PtrTab xs, PtrTab adds, PtrTab ys, const float* __restrict__ gamma,
+                                                                  const float* __restrict__ beta, PtrTab statss, int M, int C) {
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ add = (const T*)pick(adds, blockIdx.z);
+  T* __restrict__ y = (T*)pick(ys, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
+  const BnMap m = bn_map(C);
+  if (!m.active) return;
+  A mu[8], is[8], g[8], bt[8], v[8], k[8];
+  load8a(stats + m.c0, mu); load8a(stats + C + m.c0, is); load8t(gamma + m.c0, g); load8t(beta + m.c0, bt);
+  for (int r = blockIdx.x * m.rpp + m.rl; r < M; r += gridDim.x * m.rpp) {
+    const size_t o = (size_t)r * C + m.c0;
+    load8t(x + o, v);
+    load8t(add + o, k);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const A z = g[j] * ((v[j] - mu[j]) * is[j]) + bt[j] + k[j];
+      v[j] = z > 0 ? z : (A)0;
+    }
+    store8t(y + o, v);
+  }
+}
+// Its backward pass: dz = dy * [y > 0]; partial sums {sum dz, sum dz*xhat}.
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_join_bwd_reduce(PtrTab xs, PtrTab ys, PtrTab dys, PtrTab statss, int M, int C,
+                                                                int rows_per_block, PtrTab parts) {
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ y = (const T*)pick(ys, blockIdx.z);
+  const T* __restrict__ dy = (const T*)pick(dys, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
+  A* __restrict__ partials = (A*)pick(parts, blockIdx.z);
+  __shared__ A sh[16][BN_THREADS];
+  const BnMap m = bn_map(C);
+  A s[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) s[j] = 0;
+  if (m.active) {
+    A mu[8], is[8], v[8], d[8], yy[8];
+    load8a(stats + m.c0, mu); load8a(stats + C + m.c0, is);
+    const int r0 = blockIdx.x * rows_per_block;
+    const int r1 = min(M, r0 + rows_per_block);
+    for (int r = r0 + m.rl; r < r1; r += m.rpp) {
+      const size_t o = (size_t)r * C + m.c0;
+      load8t(x + o, v);
+      load8t(dy + o, d);
+      load8t(y + o, yy);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const A dz = yy[j] > 0 ? d[j] : (A)0;
+        s[j] += dz;
+        s[8 + j] += dz * ((v[j] - mu[j]) * is[j]);
+      }
+    }
+  }
+  block_reduce16(s, m, C, sh);
+  if (m.active && m.rl == 0) {
+    A* p = partials + ((size_t)blockIdx.x * C + m.c0) * 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { p[2 * j] = s[j]; p[2 * j + 1] = s[8 + j]; }
+  }
+}
+// dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M) (frozen: gamma*invstd*dz) and dadd = dz for the shortcut.
+template <class T, class A>
+__global__ __launch_bounds__(BN_THREADS) void k_join_bwd_apply(PtrTab xs, PtrTab ys, PtrTab dys, const float* __restrict__ gamma,
+                                                               PtrTab statss, PtrTab sumss, PtrTab dxs, PtrTab dadds, int M, int C,
+                                                               int frozen) {
+  const T* __restrict__ x = (const T*)pick(xs, blockIdx.z);
+  const T* __restrict__ y = (const T*)pick(ys, blockIdx.z);
+  const T* __restrict__ dy = (const T*)pick(dys, blockIdx.z);
+  const A* __restrict__ stats = (const A*)pick(statss, blockIdx.z);
+  const A* __restrict__ sums = (const A*)pick(sumss, blockIdx.z);
+  T* __restrict__ dx = (T*)pick(dxs, blockIdx.z);
+  T* __restrict__ dadd = (T*)pick(dadds, blockIdx.z);
+  const BnMap m = bn_map(C);
+  if (!m.active) return;
+  A mu[8], is[8], g[8], sb[8], sg[8], v[8], d[8], yy[8];
+  load8a(stats + m.c0, mu); load8a(stats + C + m.c0, is); load8t(gamma + m.c0, g);
+  load8a(sums + m.c0, sb); load8a(sums + C + m.c0, sg);
+  const A inv_m = frozen ? (A)0 : (A)1 / (A)M;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { sb[j] *= inv_m; sg[j] *= inv_m; }
+  for (int r = blockIdx.x * m.rpp + m.rl; r < M; r += gridDim.x * m.rpp) {
+    const size_t o = (size_t)r * C + m.c0;
+    load8t(x + o, v);
+    load8t(dy + o, d);
+    load8t(y + o, yy);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const A xh = (v[j] - mu[j]) * is[j];
+      const A dz = yy[j] > 0 ? d[j] : (A)0;
+      v[j] = g[j] * is[j] * (dz - sb[j] - xh * sg[j]);
+      d[j] = dz;
+    }
+    store8t(dx + o, v);
+    store8t(dadd + o, d);
+  }
 }
 
 struct BnGrid { dim3 grid; int rows_per_block; };
@@ -473,6 +692,74 @@ hipError_t launch_bn_running_stats(int dt, int ng, const PtrTab& stats, const fl
   const dim3 grid((unsigned)((C + 255) / 256), 1, (unsigned)ng);
   if (dt == DT_BF16) k_bn_running_stats<float><<<grid, 256, 0, stream>>>(stats, running_mean_var, C, eps);
   else k_bn_running_stats<double><<<grid, 256, 0, stream>>>(stats, running_mean_var, C, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_act_fwd(int dt, int ng, const PtrTab& x, const PtrTab& y, const float* bias, int M, int C, int relu,
+                               hipStream_t stream) {
+  dim3 grid = apply_grid(M, C);
+  grid.z = (unsigned)ng;
+  if (dt == DT_BF16) k_bias_act_fwd<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, y, bias, M, C, relu);
+  else k_bias_act_fwd<float, double><<<grid, BN_THREADS, 0, stream>>>(x, y, bias, M, C, relu);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_act_bwd(int dt, int ng, const PtrTab& y, const PtrTab& dy, const PtrTab& dx, float* g_bias, int M, int C,
+                               int relu, const PtrTab& sums, const PtrTab& partials, hipStream_t stream) {
+  const BnGrid g = reduce_grid(M, C);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
+  if (dt == DT_BF16) {
+    k_bias_act_bwd<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(y, dy, dx, M, C, relu, g.rows_per_block, partials);
+    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, nullptr, g_bias);
+  } else {
+    k_bias_act_bwd<float, double><<<grid, BN_THREADS, 0, stream>>>(y, dy, dx, M, C, relu, g.rows_per_block, partials);
+    k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, nullptr, g_bias);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool2_fwd(int dt, int ng, const PtrTab& x, const PtrTab& y, int b, int h, int w, int C, hipStream_t stream) {
+  const size_t total = (size_t)b * (h / 2) * (w / 2) * (C / 8);
+  const dim3 grid((unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096), 1, (unsigned)ng);
+  if (dt == DT_BF16) k_maxpool2_fwd<bf16_t><<<grid, 256, 0, stream>>>(x, y, b, h, w, C);
+  else k_maxpool2_fwd<float><<<grid, 256, 0, stream>>>(x, y, b, h, w, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool2_bwd(int dt, int ng, const PtrTab& x, const PtrTab& dy, const PtrTab& dx, int b, int h, int w, int C,
+                               hipStream_t stream) {
+  const size_t total = (size_t)b * (h / 2) * (w / 2) * (C / 8);
+  const dim3 grid((unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096), 1, (unsigned)ng);
+  if (dt == DT_BF16) k_maxpool2_bwd<bf16_t><<<grid, 256, 0, stream>>>(x, dy, dx, b, h, w, C);
+  else k_maxpool2_bwd<float><<<grid, 256, 0, stream>>>(x, dy, dx, b, h, w, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_add_relu_apply(int dt, int ng, const PtrTab& x, const PtrTab& add, const PtrTab& y, const float* gamma,
+                                    const float* beta, const PtrTab& stats, int M, int C, hipStream_t stream) {
+  dim3 grid = apply_grid(M, C);
+  grid.z = (unsigned)ng;
+  if (dt == DT_BF16) k_bn_add_relu_apply<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, add, y, gamma, beta, stats, M, C);
+  else k_bn_add_relu_apply<float, double><<<grid, BN_THREADS, 0, stream>>>(x, add, y, gamma, beta, stats, M, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_join_bwd(int dt, int ng, const PtrTab& x, const PtrTab& y, const PtrTab& dy, const float* gamma, const PtrTab& stats,
+                           int M, int C, const PtrTab& sums, float* g_gamma, float* g_beta, const PtrTab& partials, const PtrTab& dx,
+                           const PtrTab& dadd, int frozen, hipStream_t stream) {
+  const BnGrid g = reduce_grid(M, C);
+  const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
+  dim3 ag = apply_grid(M, C);
+  ag.z = (unsigned)ng;
+  if (dt == DT_BF16) {
+    k_join_bwd_reduce<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, y, dy, stats, M, C, g.rows_per_block, partials);
+    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
+    k_join_bwd_apply<bf16_t, float><<<ag, BN_THREADS, 0, stream>>>(x, y, dy, gamma, stats, sums, dx, dadd, M, C, frozen);
+  } else {
+    k_join_bwd_reduce<float, double><<<grid, BN_THREADS, 0, stream>>>(x, y, dy, stats, M, C, g.rows_per_block, partials);
+    k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
+    k_join_bwd_apply<float, double><<<ag, BN_THREADS, 0, stream>>>(x, y, dy, gamma, stats, sums, dx, dadd, M, C, frozen);
+  }
   return hipGetLastError();
 }
 

@@ -144,8 +144,11 @@ __global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const 
   for (int i = threadIdx.x; i < hw * C; i += blockDim.x) from_f32(&dan[i], dg[i % C]);
 }
 
+// invalid (may be null): set when the batch's gradients are not to be trusted (an image-resident launch gave up
+// waiting for its partners); the step then leaves parameters, momentum and gradients alone.
 __global__ __launch_bounds__(256) void k_sgd(float* __restrict__ w, float* __restrict__ v, float* __restrict__ g,
-                                             size_t n, float lr, float mu) {
+                                             size_t n, float lr, float mu, const int* __restrict__ invalid) {
+  if (invalid && *invalid) return;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
     const float vel = fmaf(mu, v[i], g[i]);
     v[i] = vel;
@@ -254,8 +257,8 @@ hipError_t launch_head_bwd(int dt, int ng, const PtrTab& gp, const PtrTab& dlogi
   return hipGetLastError();
 }
 
-hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, hipStream_t stream) {
-  k_sgd<<<grid_for(n, 4096), 256, 0, stream>>>(w, v, g, n, lr, mu);
+hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, const int* invalid, hipStream_t stream) {
+  k_sgd<<<grid_for(n, 4096), 256, 0, stream>>>(w, v, g, n, lr, mu, invalid);
   return hipGetLastError();
 }
 

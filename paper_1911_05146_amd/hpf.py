@@ -92,6 +92,8 @@ def _load():
     L.hpf_op_bn_relu_forward.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp, sz, vp]
     L.hpf_op_bn_relu_backward.argtypes = [C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp]
     L.hpf_op_bn_relu_forward_noalloc.argtypes = [C.c_int, vp, vp, vp, C.c_float, vp, vp, i32, i32, vp]
+    L.hpf_partition_check.argtypes = [vp]
+    L.hpf_debug_set_invalid.argtypes = [vp, i32]
     L.hpf_stash_read.argtypes = [vp, i32, i32, i32, vp, sz, C.POINTER(sz), C.POINTER(i32)]
     L.hpf_probe_copy.argtypes = [vp, vp, sz, vp]
     L.hpf_probe_mfma_bf16.argtypes = [vp, i32, i32, i32, vp]
@@ -109,7 +111,7 @@ EXPORTS = ["hpf_partition_sizes", "hpf_partition_create", "hpf_forward_microbatc
            "hpf_bn_running_read", "hpf_bn_running_write", "hpf_forward_inference", "hpf_forward_inference_group",
            "hpf_last_error", "hpf_op_workspace_bytes", "hpf_op_conv_forward",
            "hpf_op_conv_dgrad", "hpf_op_conv_wgrad", "hpf_op_bn_relu_forward", "hpf_op_bn_relu_backward",
-           "hpf_stash_read", "hpf_op_bn_relu_forward_noalloc", "hpf_probe_copy", "hpf_probe_mfma_bf16"]
+           "hpf_stash_read", "hpf_partition_check", "hpf_debug_set_invalid", "hpf_op_bn_relu_forward_noalloc", "hpf_probe_copy", "hpf_probe_mfma_bf16"]
 
 
 def hpf_last_error() -> str:
@@ -129,7 +131,8 @@ def make_desc(spec, compute_dtype=HPF_BF16):
     for i, b in enumerate(spec.blocks):
         arr[i] = hpf_block_desc(b.kind, b.c_in, b.c_mid, b.c_out, b.stride)
     d = hpf_partition_desc(HPF_ABI_VERSION, spec.in_h, spec.in_w, spec.in_c, int(spec.has_stem), spec.stem_c_out,
-                           n, C.cast(arr, C.POINTER(hpf_block_desc)), int(spec.has_head), spec.num_classes,
+                           n, C.cast(arr, C.POINTER(hpf_block_desc)),
+                           (1 if getattr(spec, "head_bn", True) else 2) if spec.has_head else 0, spec.num_classes,
                            spec.microbatch, spec.num_microbatches, spec.divisor, compute_dtype,
                            float(spec.bn_eps), spec.bn_mode, getattr(spec, "first_from", 0), getattr(spec, "last_to", 0))
     return d, arr
@@ -262,6 +265,14 @@ def hpf_stash_read(handle, mb, unit, tensor, host_dst, nbytes):
     need, where = C.c_size_t(0), C.c_int32(-1)
     _check(lib.hpf_stash_read(handle, mb, unit, tensor, host_dst, nbytes, C.byref(need), C.byref(where)))
     return where.value, need.value
+
+
+def hpf_partition_check(handle):
+    _check(lib.hpf_partition_check(handle))
+
+
+def hpf_debug_set_invalid(handle, value):
+    _check(lib.hpf_debug_set_invalid(handle, int(value)))
 
 
 def hpf_partition_destroy(handle):
@@ -629,6 +640,10 @@ class Partition:
         if self.compute_dtype == HPF_BF16:
             return torch.from_numpy(raw.view(np.int16)).view(torch.bfloat16).float().numpy()
         return raw.view(np.float32).copy()
+
+    def check(self):
+        """Waits for the device; raises HpfError(HPF_EDEVICE) if the handle's results are marked invalid."""
+        hpf_partition_check(self.handle)
 
     def params_read(self):
         import numpy as np

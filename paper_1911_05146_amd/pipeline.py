@@ -74,8 +74,8 @@ class Pipeline:
             return self._run_batch_cut(act_in, labels)
         torch, P, g = self.torch, len(self.parts), self.group
         units = [list(range(u, u + g)) for u in range(0, self.m, g)]
-        self.parts[-1].loss.zero_()
-        torch.cuda.synchronize(self.device)
+        with torch.cuda.stream(self.streams[-1]):     # in the order of the head's own work; no drain of the device
+            self.parts[-1].loss.zero_()
         fwd_done = [[torch.cuda.Event() for _ in units] for _ in range(P)]
         bwd_done = [[torch.cuda.Event() for _ in units] for _ in range(P)]
         acts = [[None] * self.m for _ in range(P)]   # acts[p][i]: output of partition p (input of p+1)
@@ -109,7 +109,9 @@ class Pipeline:
                 for i, o in zip(unit, out):
                     errs[p][i] = o
                 bwd_done[p][ui].record(s)
-        self._keep = [acts, errs, act_in, labels]   # the boundary tensors must outlive the queued work
+        # the boundary tensors must outlive the queued work: those of the batch before are let go only now that this
+        # batch is queued behind it on the same streams
+        self._keep = [self._keep[-4:] if self._keep else None, acts, errs, act_in, labels]
 
     def _run_batch_cut(self, act_in, labels):
         """The same schedule for partitions cut at layer granularity.  Every rank walks its Forward list (receives
@@ -117,8 +119,8 @@ class Pipeline:
         list; a receive is a wait on the sender's event plus the use of its buffer, a send is the record of the
         rank's own event (all tensors of one call are complete together)."""
         torch, P = self.torch, len(self.parts)
-        self.parts[-1].loss.zero_()
-        torch.cuda.synchronize(self.device)
+        with torch.cuda.stream(self.streams[-1]):
+            self.parts[-1].loss.zero_()
         fwd_done = [[torch.cuda.Event() for _ in range(self.m)] for _ in range(P)]
         bwd_done = [[torch.cuda.Event() for _ in range(self.m)] for _ in range(P)]
         sent = [[{} for _ in range(self.m)] for _ in range(P)]       # sent[p][i][tensor]: forward outputs of rank p
@@ -144,7 +146,7 @@ class Pipeline:
                 err_out, skip_err_out = part.backward_microbatch_cut(i, got["act"], got["skip"], stream=s)
                 grads[p][i] = {"act": err_out, "skip": skip_err_out}
                 bwd_done[p][i].record(s)
-        self._keep = [sent, grads, act_in, labels]
+        self._keep = [self._keep[-4:] if self._keep else None, sent, grads, act_in, labels]
 
     def synchronize(self):
         self.torch.cuda.synchronize(self.device)

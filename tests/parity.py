@@ -109,28 +109,45 @@ def _tensors(res, spec):
     return out
 
 
-KAPPA = 1.1
+KAPPA = 1.1          # whole tensors (act_out, err_out, the whole G)
 FLOOR = {"bf16": 5e-3, "f32": 5e-3}
+KAPPA_SLICE = 1.5    # one parameter tensor of G: the two chaotic evaluations scatter per tensor (see compare)
+FLOOR_SLICE = 5e-2
 NOT_A_TEST = 0.5
+SLICE_TOL_FACTOR = 2.0   # criterion A on one parameter tensor: its own max|ref| is below the whole tensor's, so the same
+                         # absolute error weighs more; the tolerance proper applies to the whole G
+SLICE_FLOOR = 5e-2   # a parameter tensor is measured against at least this fraction of the whole gradient's scale
 
 
-def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None, plain=None):
+def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None, plain=None, insensitive="fail"):
     """Parity of one batch, tensor by tensor (the gradient and the parameters also per parameter tensor).
 
     yard : the oracle run in the device's precision reading on the same inputs (float storage; in bf16 mode with
            the tensors the device keeps as bfloat16 rounded at the same points).
     plain: optionally the plain fp32 oracle (nothing rounded); the error against it is reported next to the other.
     Criterion A: max|gpu - yard| / max|yard| <= tol for the tensor (2e-2 bf16, 1e-4 fp32).  strict: A is required.
+           For one parameter tensor of the gradient the bound is 2 tol and the denominator max(max|yard slice|, 5e-2 max|yard G|):
+           some slices are zero up to rounding by construction (with every ReLU active the gradient of a
+           BatchNorm's beta is a sum that the following BatchNorm's backward pass has centred; what is left is the
+           rounding of the stored gradient tensor, measured at up to 5e-4 of max|G|), and noise has no relative
+           error; a layer whose gradient is within a factor 20 of the largest is judged on its own scale.
     Criterion B (sensitivity-limited), only for tensors that fail A and only if strict is False: a deep ReLU
            network's backward pass is discontinuous where a pre-activation is within rounding of 0, so two correct
            implementations of one precision reading scatter around the exact result by an amount the oracle
            itself can measure.  With ref64 the oracle in double and nothing rounded,
-               relL2(gpu, ref64) <= (KAPPA + 3 / sqrt(2 n)) * relL2(yard, ref64) + FLOOR
-           per tensor of n elements (KAPPA = 1.1: the two distances were measured equal to within 2 %; the second
-           term is three standard deviations of a norm estimated from n samples, which matters for the
-           per-channel tensors of 16 ... 128 elements).  A tensor for which the yardstick itself is at
-           relL2 >= 0.5 of the exact result says nothing either way and fails the case as "not a test":
-           such configurations are covered layer by layer instead (tests/teacher.py).
+               relL2(gpu, ref64) <= KAPPA * relL2(yard, ref64) + FLOOR            (KAPPA 1.1, FLOOR 5e-3)
+           for whole tensors -- act_out, err_out, the whole G: the two distances were measured equal to within
+           2 % -- and, for each parameter tensor of n elements on its own,
+               relL2(gpu, ref64) <= (KAPPA_SLICE + 3 / sqrt(2 n)) * relL2(yard, ref64) + FLOOR_SLICE   (1.5, 5e-2):
+           per tensor the two evaluations scatter (measured ratios up to 1.66 among the 190 parameter tensors of
+           the 21-block partition, a single differing ReLU decision weighs on a tensor of 32 elements), while a
+           wrong layer is uncorrelated with the exact result and sits at relL2 >= 1; the second term is three
+           standard deviations of a norm estimated from n samples.  Norms of a parameter tensor are taken relative
+           to at least 5e-2 of the whole gradient's norm per element, as above.  Whenever a case needs criterion
+           B the caller also checks every layer on its own, element by element (tests/teacher.py).  A tensor for which the yardstick itself is at
+           relL2 >= 0.5 of the exact result says nothing either way: insensitive = "fail" fails the case as "not a
+           test"; "skip" records it as ("skipped", ...) so that the caller covers the case layer by layer instead
+           (tests/teacher.py), which test_gpu_parity.check does.
     A tensor the oracle returns and the device does not is a failure.  Returns {tensor: (criterion, error, ...)}.
     """
     tol = TOL[mode] if tol is None else tol
@@ -138,37 +155,57 @@ def compare(spec, res, yard, mode, ref64=None, strict=False, tol=None, plain=Non
     pl = _tensors(plain, spec) if plain is not None else None
     report, bad = {}, {}
     r64 = None
+
+    def scale(t, k, norm):
+        """Floor of the denominator for a slice k = 'grad:<name>' / 'params:<name>' of the flat tensor."""
+        if ":" not in k:
+            return 0.0
+        whole = t[k.split(":", 1)[0]]
+        if norm == "max":
+            return SLICE_FLOOR * float(np.abs(whole).max())
+        return SLICE_FLOOR * float(np.linalg.norm(whole)) * np.sqrt(t[k].size / whole.size)
+
     for k in y:
         if k not in g:
             bad[k] = ("missing",)
             continue
-        e = rel_err(g[k], y[k])
-        if e <= tol:
+        den = max(float(np.abs(y[k]).max()), scale(y, k, "max")) or 1.0
+        e = float(np.abs(g[k] - y[k]).max() / den)
+        if e <= (SLICE_TOL_FACTOR * tol if ":" in k else tol):
             if ":" not in k:      # the per-parameter-tensor entries are only listed when they need criterion B
                 report[k] = ("A", e) + ((rel_err(g[k], pl[k]),) if pl is not None else ())
             continue
-        if k in ("grad", "params"):
-            continue              # judged per parameter tensor below
+        if strict and k in ("grad", "params"):
+            continue              # strict: judged per parameter tensor
         if strict or ref64 is None:
             bad[k] = ("A", e)
             continue
         if r64 is None:
             r64 = _tensors(ref64() if callable(ref64) else ref64, spec)
-        eg, ey = rel_l2(g[k], r64[k]), rel_l2(y[k], r64[k])
-        report[k] = ("B", e, eg, ey)
+        den2 = max(float(np.linalg.norm(r64[k])), scale(r64, k, "l2")) or 1.0
+        eg, ey = float(np.linalg.norm(g[k] - r64[k]) / den2), float(np.linalg.norm(y[k] - r64[k]) / den2)
         if ey >= NOT_A_TEST:
-            bad[k] = ("not a test: the yardstick is itself at relL2", ey)
-        elif not eg <= (KAPPA + 3.0 / np.sqrt(2.0 * g[k].size)) * ey + FLOOR[mode]:
+            report[k] = ("skipped", e, eg, ey)
+            if insensitive == "fail":
+                bad[k] = ("not a test: the yardstick is itself at relL2", ey)
+            continue
+        report[k] = ("B", e, eg, ey)
+        lim = (KAPPA_SLICE + 3.0 / np.sqrt(2.0 * g[k].size)) * ey + FLOOR_SLICE if ":" in k else KAPPA * ey + FLOOR[mode]
+        if not eg <= lim:
             bad[k] = ("B", e, eg, ey)
+    if bad:
+        print(f"[parity FAILED] {spec.name} [{mode}]: {dict(list(bad.items())[:12])} ({len(bad)} tensors)", flush=True)
     assert not bad, f"{spec.name} [{mode}] parity failed: {bad} (passed: {report})"
     return report
 
 
 def fmt(report):
-    out, nb, worst = [], 0, None
+    out, nb, ns, worst = [], 0, 0, None
     for k, v in report.items():
         if v[0] == "A":
             out.append(f"{k}: max-norm {v[1]:.2e}" + (f" (vs the plain fp32 oracle {v[2]:.2e})" if len(v) > 2 else ""))
+        elif v[0] == "skipped":
+            ns += 1
         elif ":" in k:
             nb += 1
             if worst is None or v[2] / max(v[3], 1e-30) > worst[1][2] / max(worst[1][3], 1e-30):
@@ -178,4 +215,11 @@ def fmt(report):
     if nb:
         k, v = worst
         out.append(f"{nb} parameter tensors sensitivity-limited, largest gpu/yardstick ratio at {k}: relL2 {v[2]:.2e} vs {v[3]:.2e}")
+    if ns:
+        out.append(f"{ns} tensors say nothing end to end (the yardstick itself is at relL2 >= {NOT_A_TEST} of the exact result): covered layer by layer")
     return "; ".join(out)
+
+
+def needs_layerwise(report):
+    """True when some tensor of the case passed only statistically or said nothing end to end."""
+    return any(v[0] in ("B", "skipped") for v in report.values())

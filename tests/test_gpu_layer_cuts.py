@@ -75,7 +75,7 @@ def test_cut_partition_against_oracle(gpu, oracle, case, mode):
     seen, res = run_gpu_cut_step(spec, inp, mode)
     yard = oracle.run_step(spec, seen, np.float32, storage="bf16" if mode == "bf16" else "none")
     ref64 = lambda: oracle.run_step(spec, seen, np.float64)
-    rep = parity.compare(spec, res, yard, mode, ref64=ref64)
+    rep = parity.compare(spec, res, yard, mode, ref64=ref64, insensitive="skip")
     assert set(rep) >= {"act_out", "err_out", "grad"} | ({"skip_out"} if spec.has_skip_out else set()) | \
         ({"skip_err_out"} if spec.has_skip_in else set())
     print("[parity]", parity.fmt(rep), flush=True)
@@ -139,5 +139,5 @@ def test_layer_cut_pipeline_bf16(gpu, oracle):
     pipe.run_batch(act, lab)
     res = {"grad": pipe.grad_accum_read(), "loss": float(pipe.loss.item())}
     pipe.close()
-    rep = parity.compare(cm.whole, res, yard, "bf16", ref64=lambda: oracle.run_step(cm.whole, inp, np.float64))
+    rep = parity.compare(cm.whole, res, yard, "bf16", ref64=lambda: oracle.run_step(cm.whole, inp, np.float64), insensitive="skip")
     print("[parity]", parity.fmt(rep), flush=True)

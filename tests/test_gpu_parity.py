@@ -42,7 +42,7 @@ def check_block(oracle, spec, mode, grouped=False, fusion=2):
 
 
 def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, beta_shift, grouped=False, fusion=2):
-    from parity import compare, fmt, run_gpu_step
+    from parity import compare, fmt, needs_layerwise, run_gpu_step
     print(f"\n[case] {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} streams={multi_stream} "
           f"grouped={grouped} fusion={int(fusion)} seed={spec.seed}", flush=True)
     inp = W.make_inputs(spec, randomize_affine=randomize_affine)
@@ -50,10 +50,20 @@ def check_once(oracle, spec, mode, multi_stream, sgd, randomize_affine, strict, 
         for e in W.param_layout(spec):
             if e.kind == "beta":
                 inp.params[e.offset:e.offset + e.size] += beta_shift
-    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd, grouped=grouped, fusion=fusion)
-    yard = oracle.run_step(spec, seen, np.float32, sgd=sgd, storage="bf16" if mode == "bf16" else "none")
-    rep = compare(spec, res, yard, mode, ref64=lambda: oracle.run_step(spec, to64(seen), np.float64, sgd=sgd), strict=strict)
-    print(f"[parity] {spec.name} {mode}: " + fmt(rep), flush=True)
+    seen, res = run_gpu_step(spec, inp, mode, multi_stream=multi_stream, sgd=sgd, grouped=grouped, fusion=fusion, keep=True)
+    part = res.pop("part")
+    try:
+        yard = oracle.run_step(spec, seen, np.float32, sgd=sgd, storage="bf16" if mode == "bf16" else "none")
+        rep = compare(spec, res, yard, mode, ref64=lambda: oracle.run_step(spec, to64(seen), np.float64, sgd=sgd), strict=strict,
+                      insensitive="skip")
+        print(f"[parity] {spec.name} {mode}: " + fmt(rep), flush=True)
+        if needs_layerwise(rep) and spec.first_from == 0 and spec.last_to == 0:
+            # end to end some tensors passed only statistically, or could not be judged at all: every layer on its own
+            from teacher import layerwise_check
+            lw = layerwise_check(oracle, part, spec, seen, res, mode)
+            print(f"[layer-wise] {spec.name} {mode}: {lw.summary()}", flush=True)
+    finally:
+        part.close()
     return rep
 
 
@@ -282,7 +292,13 @@ def test_grouped_calls_equal_single_calls(gpu, oracle, mode):
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
 def test_resnet1001_whole_model_small_batch(gpu, oracle, mode):
-    check(oracle, W.resnet1001_whole(microbatch=2, num_microbatches=2), mode, sgd=(0.1, 0.9), randomize_affine=False)
+    """333 blocks at 2 micro-batches of 2 images: end to end the backward pass of this network says nothing (two
+    evaluations of the oracle itself, float and double, differ by a third in G), so every layer is checked on its
+    own; the full-size configuration is in test_gpu_teacher.py."""
+    from teacher import run_and_check
+    spec = W.resnet1001_whole(microbatch=2, num_microbatches=2)
+    print(f"\n[case] {spec.name} b=2 m=2 mode={mode} (layer-wise)", flush=True)
+    run_and_check(oracle, spec, mode, randomize_affine=False, blockwise=False)
 
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])

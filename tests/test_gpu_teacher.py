@@ -94,9 +94,9 @@ def test_config6_wide_resnet1001_partition_full_size_layerwise(gpu, oracle):
 
 def test_config4_resnet1001_whole_full_size_layerwise(gpu, oracle):
     """333 blocks + stem + head, 8 micro-batches of 8 images."""
-    layerwise(oracle, W.config(4), "bf16")
+    layerwise(oracle, W.config(4), "bf16", blockwise=False)
 
 
 def test_config5_resnet152_stage3_full_size_layerwise(gpu, oracle):
     """36 blocks at 14x14x1024, 4 micro-batches of 16 images (3 TFLOP per oracle pass)."""
-    layerwise(oracle, W.config(5), "bf16")
+    layerwise(oracle, W.config(5), "bf16", blockwise=False)
