@@ -329,7 +329,11 @@ typedef enum {
   HPF_T_DC2 = 6,  /* gradient w.r.t. c2 */
   HPF_T_GX = 7,   /* gradient w.r.t. the block input */
   HPF_T_STATS0 = 8, HPF_T_STATS1 = 9, HPF_T_STATS2 = 10,
-  HPF_T_A0 = 11, HPF_T_A1 = 12, HPF_T_A2 = 13   /* relu(bn_j(.)) where the partition stores it */
+  HPF_T_A0 = 11, HPF_T_A1 = 12, HPF_T_A2 = 13,  /* relu(bn_j(.)) where the partition stores it */
+  /* units of kinds 2 ... 6: HPF_T_X, HPF_T_Y, HPF_T_GY, HPF_T_GX for all of them; kind 2 also HPF_T_C1 (first
+   * convolution's output), HPF_T_A0 (relu(bn1(c1))), HPF_T_C2, HPF_T_SC (the shortcut value added before the last
+   * relu), HPF_T_STATS0 / 1; kind 5 HPF_T_STATS0; kind 3 with a max-pool HPF_T_Y0 (the output before the pool) */
+  HPF_T_Y0 = 14, HPF_T_SC = 15
 } hpf_tensor_id;
 hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t tensor, void* host_dst, size_t bytes,
                           size_t* bytes_needed, int32_t* where);

@@ -1741,6 +1741,23 @@ hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t te
     const BlockPlan& q = P.bp[unit];
     const size_t M_in = b * q.h_in * q.w_in, M_out = b * q.h_out * q.w_out;
     auto held = [&](int j) { return j >= q.j0 && j < q.j1; };
+    if (!q.residual()) {   // units of VGG-16 / ResNet-v1: input, output, the tensors in between, the boundary gradients
+      const size_t n_in = M_in * q.d.c_in, n_out = (q.d.kind == K_DENSE ? b : M_out) * q.d.c_out;
+      switch (tensor) {
+        case HPF_T_X: loc = q.x_in; need = n_in * P.esz; break;
+        case HPF_T_Y: loc = q.y; need = n_out * P.esz; break;
+        case HPF_T_Y0: if (q.d.kind == K_CONV_RELU) { loc = q.y0; need = M_in * q.d.c_out * P.esz; } break;
+        case HPF_T_GY: loc = q.gy; need = n_out * P.esz; break;
+        case HPF_T_GX: loc = grad_in(unit); need = n_in * P.esz; break;
+        case HPF_T_C1: if (q.d.kind == K_POSTACT) { loc = q.c[0]; need = M_out * q.d.c_mid * P.esz; } break;
+        case HPF_T_A0: if (q.d.kind == K_POSTACT) { loc = q.a[0]; need = M_out * q.d.c_mid * P.esz; } break;
+        case HPF_T_C2: if (q.d.kind == K_POSTACT) { loc = q.c[1]; need = M_out * q.d.c_out * P.esz; } break;
+        case HPF_T_SC: if (q.d.kind == K_POSTACT) { loc = q.sc; need = M_out * q.d.c_out * P.esz; } break;
+        case HPF_T_STATS0: if (q.d.kind == K_POSTACT || q.d.kind == K_BN_RELU) stats_of(q.bn[0]); break;
+        case HPF_T_STATS1: if (q.d.kind == K_POSTACT) stats_of(q.bn[1]); break;
+        default: break;
+      }
+    } else
     switch (tensor) {
       case HPF_T_X: if (q.j0 == 0) { loc = q.x_in; need = M_in * q.d.c_in * P.esz; } break;
       case HPF_T_C1: if (held(0) || q.j0 == 1) { loc = q.c[0]; need = M_out * q.d.c_mid * P.esz; } break;

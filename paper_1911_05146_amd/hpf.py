@@ -255,7 +255,7 @@ def hpf_partition_profile_read(handle, capacity=16):
 
 # hpf_tensor_id
 (HPF_T_X, HPF_T_C1, HPF_T_C2, HPF_T_Y, HPF_T_GY, HPF_T_DC1, HPF_T_DC2, HPF_T_GX, HPF_T_STATS0, HPF_T_STATS1,
- HPF_T_STATS2, HPF_T_A0, HPF_T_A1, HPF_T_A2) = range(14)
+ HPF_T_STATS2, HPF_T_A0, HPF_T_A1, HPF_T_A2, HPF_T_Y0, HPF_T_SC) = range(16)
 STASH_WHERE = {1: "act_in", 2: "act_out", 3: "err_in", 4: "err_out", 5: "skip_in", 6: "skip_out", 7: "skip_err_in",
                8: "skip_err_out"}
 

@@ -130,6 +130,95 @@ def layerwise_check(oracle, part, spec, seen, res, mode, eps=None, check_grad=Tr
         Gabs[gname + ".tie"] = Gabs.get(gname + ".tie", 0.0) + (np.abs(da * xh) * tie).sum(axis=ax)
         return dx, tie
 
+    def stats_cmp(mb, unit, j, mean, invstd, where):
+        st = part.stash_read(mb, unit, hpf.HPF_T_STATS0 + j)
+        C = mean.size
+        rep.cmp("bn.mean", where, st[:C] * invstd, mean * invstd,
+                tol=STATS_TOL[mode] * max(1.0, 1.0 / (float(np.abs(mean * invstd).max()) or 1.0)))
+        rep.cmp("bn.invstd", where, st[C:], invstd, tol=STATS_TOL[mode])
+
+    def other_unit(mb, i, blk, h, w, pre, tag):
+        """One unit of VGG-16 / ResNet-v1: every stored tensor of the forward pass from the device's stored input of
+        its layer, and the gradient the unit hands on from the gradient it received (the gradients between its
+        layers live in scratch memory on the device and are not kept; every ReLU decision inside the unit is taken
+        on a stored tensor, the same on both sides).  Returns the unit's output height and width."""
+        x = rd(mb, i, hpf.HPF_T_X, (b, h, w, blk.c_in))
+        if blk.kind == W.DENSE:
+            ho, wo = 1, 1
+        else:
+            ho, wo = h // blk.stride, w // blk.stride
+        y_dev = rd(mb, i, hpf.HPF_T_Y, (b, ho, wo, blk.c_out))
+        gy = rd(mb, i, hpf.HPF_T_GY, y_dev.shape)
+        gx_dev = rd(mb, i, hpf.HPF_T_GX, x.shape)
+        taint = None
+        if blk.kind == W.POSTACT:
+            c1 = rd(mb, i, hpf.HPF_T_C1, (b, ho, wo, blk.c_mid))
+            a1 = rd(mb, i, hpf.HPF_T_A0, c1.shape)
+            c2 = rd(mb, i, hpf.HPF_T_C2, y_dev.shape)
+            W1, W2 = P(pre + "W1"), P(pre + "W2")
+            g1, b1, g2, b2 = (P(pre + n) for n in ("bn1.gamma", "bn1.beta", "bn2.gamma", "bn2.beta"))
+            rep.cmp("fwd.c1", tag, c1, oracle.conv_fwd(x, W1, blk.stride))
+            a1_ref, mean1, inv1 = oracle.bn_relu_fwd(c1, g1, b1, eps, mode=bn_mode)
+            stats_cmp(mb, i, 0, mean1, inv1, tag + " bn1")
+            rep.cmp("fwd.a1", tag, a1, a1_ref)
+            rep.cmp("fwd.c2", tag, c2, oracle.conv_fwd(a1, W2, 1))
+            if blk.has_proj:
+                sc = rd(mb, i, hpf.HPF_T_SC, y_dev.shape)
+                rep.cmp("fwd.shortcut", tag, sc, oracle.conv_fwd(x, P(pre + "Wproj"), blk.stride))
+            else:
+                sc = x
+            y_ref, mean2, inv2 = oracle.bn_add_relu_fwd(c2, g2, b2, sc, eps, mode=bn_mode)
+            stats_cmp(mb, i, 1, mean2, inv2, tag + " bn2")
+            rep.cmp("fwd.y", tag, y_dev, y_ref)
+            dc2, dz, dg2, db2 = oracle.bn_add_relu_bwd(c2, y_dev, gy, g2, mean2, inv2, mode=bn_mode)
+            G[pre + "bn2.gamma"] += dg2
+            G[pre + "bn2.beta"] += db2
+            G[pre + "W2"] += oracle.conv_wgrad(a1, dc2, 3, 1)
+            da1 = oracle.conv_dgrad(dc2, W2, (ho, wo), 1)
+            dc1, tie = bn_bwd(c1, da1, g1, b1, mean1, inv1, None, pre + "bn1.gamma", pre + "bn1.beta")
+            G[pre + "W1"] += oracle.conv_wgrad(x, dc1, 3, blk.stride)
+            gx = oracle.conv_dgrad(dc1, W1, (h, w), blk.stride)
+            if blk.has_proj:
+                G[pre + "Wproj"] += oracle.conv_wgrad(x, dz, 1, blk.stride)
+                gx = gx + oracle.conv_dgrad(dz, P(pre + "Wproj"), (h, w), blk.stride)
+            else:
+                gx = gx + dz
+            taint = np.broadcast_to(_spread(oracle, tie.any(axis=-1), 3, blk.stride, (h, w))[..., None], gx.shape)
+        elif blk.kind == W.CONV_RELU:
+            Wc, bias = P(pre + "W"), P(pre + "bias")
+            y0 = rd(mb, i, hpf.HPF_T_Y0, (b, h, w, blk.c_out)) if blk.stride == 2 else y_dev
+            rep.cmp("fwd.conv_relu", tag, y0, oracle.bias_act_fwd(oracle.conv_fwd(x, Wc, 1), bias, True))
+            d0 = gy
+            if blk.stride == 2:
+                rep.cmp("fwd.pool", tag, y_dev, oracle.maxpool2_fwd(y0), tol=0.0)       # a selection: exact
+                d0 = oracle.maxpool2_bwd(y0, gy)
+            dz, db = oracle.bias_act_bwd(y0, d0, True)
+            G[pre + "bias"] += db
+            G[pre + "W"] += oracle.conv_wgrad(x, dz, 3, 1)
+            gx = oracle.conv_dgrad(dz, Wc, (h, w), 1)
+        elif blk.kind == W.DENSE:
+            K = h * w * blk.c_in
+            W4, bias = P(pre + "W").reshape(1, 1, K, blk.c_out), P(pre + "bias")
+            xr = x.reshape(b, 1, 1, K)
+            rep.cmp("fwd.dense", tag, y_dev, oracle.bias_act_fwd(oracle.conv_fwd(xr, W4, 1), bias, blk.c_mid != 0))
+            dz, db = oracle.bias_act_bwd(y_dev, gy, blk.c_mid != 0)
+            G[pre + "bias"] += db
+            G[pre + "W"] += oracle.conv_wgrad(xr, dz, 1, 1).reshape(K, blk.c_out)
+            gx = oracle.conv_dgrad(dz, W4, (1, 1), 1).reshape(x.shape)
+        elif blk.kind == W.BN_RELU:
+            g, bt = P(pre + "bn.gamma"), P(pre + "bn.beta")
+            a_ref, mean, invstd = oracle.bn_relu_fwd(x, g, bt, eps, mode=bn_mode)
+            stats_cmp(mb, i, 0, mean, invstd, tag + " bn")
+            rep.cmp("fwd.bn_relu", tag, y_dev, a_ref)
+            gx, taint = bn_bwd(x, gy, g, bt, mean, invstd, None, pre + "bn.gamma", pre + "bn.beta")
+        else:
+            bias = P(pre + "bias")
+            rep.cmp("fwd.bias_relu", tag, y_dev, oracle.bias_act_fwd(x, bias, True))
+            gx, db = oracle.bias_act_bwd(y_dev, gy, True)
+            G[pre + "bias"] += db
+        rep.cmp("bwd.gx", tag, gx_dev, gx, mask=taint)
+        return ho, wo
+
     loss = 0.0
     t_last = time.time()
     for mb in range(m):
@@ -146,6 +235,9 @@ def layerwise_check(oracle, part, spec, seen, res, mode, eps=None, check_grad=Tr
                 print(f"  ... layer-wise {spec.name}: micro-batch {mb}, block {i}", flush=True)
                 t_last = time.time()
             pre, tag = f"block{i}.", f"mb{mb} block{i}"
+            if not blk.residual:
+                h, w = other_unit(mb, i, blk, h, w, pre, tag)
+                continue
             ho, wo = h // blk.stride, w // blk.stride
             nconv = 2 if blk.kind == W.BASIC else 3
             R = (3, 3) if blk.kind == W.BASIC else (1, 3, 1)
@@ -191,13 +283,17 @@ def layerwise_check(oracle, part, spec, seen, res, mode, eps=None, check_grad=Tr
         if spec.has_head:
             c = spec.out_shape()[2]
             x = rd(mb, nb, hpf.HPF_T_X, (b, h, w, c))
-            a, mean, invstd, g, bt = bn(mb, nb, 0, x, "head.bn.gamma", "head.bn.beta", f"mb{mb} head bn")
+            head_bn = getattr(spec, "head_bn", True)
+            if head_bn:
+                a, mean, invstd, g, bt = bn(mb, nb, 0, x, "head.bn.gamma", "head.bn.beta", f"mb{mb} head bn")
+            else:
+                a = x
             l, gp, dl = oracle.head_fwd(a, P("head.Wfc"), P("head.bfc"), seen.labels[mb], spec.divisor)
             loss += l
             dwfc, dbfc, da = oracle.head_bwd(gp, dl, P("head.Wfc"), (h, w))
             G["head.Wfc"] += dwfc
             G["head.bfc"] += dbfc
-            dx, tie = bn_bwd(x, da, g, bt, mean, invstd, None, "head.bn.gamma", "head.bn.beta")
+            dx, tie = bn_bwd(x, da, g, bt, mean, invstd, None, "head.bn.gamma", "head.bn.beta") if head_bn else (da, None)
             rep.cmp("bwd.head.gx", f"mb{mb}", rd(mb, nb, hpf.HPF_T_GX, x.shape), dx, mask=tie)
     if spec.has_head:
         rep.cmp("loss", "batch", [res["loss"]], [loss], tol=1e-3 if mode == "bf16" else 1e-5)
@@ -254,6 +350,7 @@ def blockwise_check(oracle, part, spec, seen, res, mode, frac_ok=0.9, l2_ok=0.15
     decision, so for wide blocks the strict statement is the layer-wise one."""
     from paper_1911_05146_amd import hpf
     assert spec.first_from == 0 and spec.last_to == 0 and spec.bn_mode == 0
+    assert all(blk.residual for blk in spec.blocks), "block-wise: pre-activation residual blocks only"
     rep = Report(mode)
     tol = rep.tol
     lay = {e.name: e for e in W.param_layout(spec)}

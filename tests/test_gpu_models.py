@@ -58,6 +58,7 @@ def test_units_of_both_models(gpu, oracle, mode):
     for spec in cases:
         check(oracle, spec, mode, strict=(mode == "f32"))
         check(oracle, spec, mode, strict=(mode == "f32"), grouped=True)
+        layerwise(oracle, spec, mode)
 
 
 @pytest.mark.parametrize("mode", ["f32", "bf16"])
@@ -67,16 +68,28 @@ def test_small_models_with_sgd(gpu, oracle, mode):
           strict=(mode == "f32"), sgd=(0.1, 0.9))
 
 
+def layerwise(oracle, spec, mode, grouped=True):
+    """Every layer on its own from the device's stored input of that layer (tests/teacher.py): element-wise."""
+    from teacher import run_and_check
+    print(f"\n[case] layer-wise {spec.name} b={spec.microbatch} m={spec.num_microbatches} mode={mode} grouped={grouped}", flush=True)
+    return run_and_check(oracle, spec, mode, grouped=grouped, blockwise=False)
+
+
 def test_resnet110_v1_full_size(gpu, oracle):
-    """54 post-activation blocks, 8 micro-batches of 16 images of 32x32x3."""
+    """54 post-activation blocks, 8 micro-batches of 16 images of 32x32x3: end to end (the deep backward pass is
+    sensitivity-limited in bf16) and layer by layer (element-wise)."""
     check(oracle, W.resnet110_v1(), "bf16", grouped=True)
+    layerwise(oracle, W.resnet110_v1(), "bf16")
     check(oracle, W.resnet110_v1(microbatch=4, num_microbatches=2), "f32", strict=True)
+    layerwise(oracle, W.resnet110_v1(microbatch=4, num_microbatches=2), "f32", grouped=False)
 
 
 def test_vgg16_full_size(gpu, oracle):
     """13 convolutions, 5 max-pools, two dense layers of 4096 and the classifier; 8 micro-batches of 16 images."""
     check(oracle, W.vgg16(), "bf16", grouped=True)
+    layerwise(oracle, W.vgg16(), "bf16")
     check(oracle, W.vgg16(microbatch=4, num_microbatches=2), "f32", strict=True)
+    layerwise(oracle, W.vgg16(microbatch=4, num_microbatches=2), "f32", grouped=False)
 
 
 @pytest.mark.parametrize("model,n_parts", [("vgg16", 8), ("resnet110v1", 4)])
