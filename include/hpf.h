@@ -273,6 +273,7 @@ hpf_status hpf_forward_inference_group(hpf_partition* p, int32_t count, const vo
  *   "resident_forward" / "resident_backward" / "resident_wgrad"
  *                                             one launch each per run of bottleneck blocks and group,
  *   "wgrad_grouped"                           the other deferred weight-gradient launches (one per tile class),
+ *   "conv_forward" / "conv_dgrad"             the bf16 MFMA convolution launches outside image-resident runs,
  *   "other_forward" / "other_backward"        every other kernel of the pass.
  * hpf_partition_profile_read waits for the device, adds the finished segments to the totals kept
  * since profiling was enabled, and writes up to `capacity` entries (classes with no launch are

@@ -558,8 +558,10 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
 
 }  // namespace
 
-enum ProfCat { PROF_NONE = -1, PROF_RES_FWD = 0, PROF_RES_BWD, PROF_RES_WGRAD, PROF_WGRAD, PROF_OTHER_FWD, PROF_OTHER_BWD, PROF_N };
-const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward", "resident_wgrad", "wgrad_grouped", "other_forward", "other_backward"};
+enum ProfCat { PROF_NONE = -1, PROF_RES_FWD = 0, PROF_RES_BWD, PROF_RES_WGRAD, PROF_WGRAD, PROF_CONV_FWD, PROF_CONV_DGRAD, PROF_OTHER_FWD,
+               PROF_OTHER_BWD, PROF_N };
+const char* const kProfNames[PROF_N] = {"resident_forward", "resident_backward", "resident_wgrad", "wgrad_grouped", "conv_forward",
+                                        "conv_dgrad",       "other_forward",     "other_backward"};
 
 // One captured HIP graph of a micro-batch's forward or backward kernel sequence, valid for the caller
 // pointers it was captured with.
@@ -715,6 +717,16 @@ struct Ctx {
                             bn.C, P.d.bn_mode, s),
         "bn_bwd_apply");
   }
+  // Profiling: a bf16 convolution launch is a segment of its own with its algorithmic figures (2*M*K*N flop; source,
+  // weights, output [, residual operand] once).  Returns the class to go back to afterwards (PROF_NONE: not profiling).
+  int conv_seg(int cat, const ConvGeom& q, bool has_add) {
+    if (!h->profiling) return PROF_NONE;
+    const int back = cur.cat == PROF_NONE ? (cat == PROF_CONV_FWD ? PROF_OTHER_FWD : PROF_OTHER_BWD) : cur.cat;
+    const double m_src = (double)q.b * q.Hs * q.Ws;
+    seg(cat, (double)g * 2.0 * (m_src * q.Cs + (double)q.Ktot * q.N + (double)q.M * q.N * (has_add ? 2.0 : 1.0)),
+        (double)g * 2.0 * q.M * (double)q.Ktot * q.N);
+    return back;
+  }
   ConvGeom geom_fwd(const ConvPlan& cv) const {
     ConvGeom q{};
     q.b = h->P.d.microbatch; q.Ho = cv.h_out; q.Wo = cv.w_out; q.Hs = cv.h_in; q.Ws = cv.w_in; q.Cs = cv.cin; q.N = cv.cout;
@@ -745,7 +757,9 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
+      const int back = conv_seg(PROF_CONV_FWD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi, pro), "conv_fwd");
+      if (back != PROF_NONE) seg(back);
       return rows;
     }
     chk(launch_conv_f32(CONV_FWD, g, x, h->params() + cv.w_off, y, add, q, s), "conv_fwd_f32");
@@ -764,7 +778,9 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
+      const int back = conv_seg(PROF_CONV_DGRAD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s, epi), "conv_dgrad");
+      if (back != PROF_NONE) seg(back);
       return rows;
     }
     chk(launch_conv_f32(CONV_DGRAD, g, dy, h->params() + cv.w_off, dx, add, q, s), "conv_dgrad_f32");
