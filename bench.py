@@ -202,7 +202,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..6 (default 3: ResNet-1001 partition; 6: the same cut of the 30 M-parameter variant)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 1..8 (default 3: ResNet-1001 partition; 6: the same cut of the 30 M-parameter variant; 7: ResNet-110-v1 whole; 8: VGG-16 whole)")
     ap.add_argument("--schedule", choices=["grouped", "streams", "single-stream"], default="grouped",
                     help="grouped: all micro-batches of the batch in one group call per direction (default); "
                          "streams: one call and one stream per micro-batch; single-stream: one call per micro-batch, one stream")
@@ -257,7 +257,7 @@ def main():
     if args.others:
         # the other configurations, after the timed region of the headline one: shorter runs, same launch configuration
         result["other_configs"] = []
-        for cfg in (1, 2, 4, 5, 6):
+        for cfg in (1, 2, 4, 5, 6, 7, 8):
             if cfg == args.config:
                 continue
             r = run_config(args, torch, dev, cfg, max(5, args.steps // 3), 3, probe=not args.no_probe, cpu=False, ceilings=False)
@@ -280,7 +280,7 @@ def run_config(args, torch, dev, config, steps, warmup, probe=True, cpu=True, ce
     spec = W.config(config)
     inputs = W.make_inputs(spec)
     m = spec.num_microbatches
-    sgd = (0.1, 0.9) if config == 4 else None
+    sgd = (0.1, 0.9) if config in (4, 7, 8) else None   # the whole models take the SGD step too
 
     part = hpf.Partition(spec, inputs.params, hpf.HPF_BF16)
     if args.no_graphs:

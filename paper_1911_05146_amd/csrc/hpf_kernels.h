@@ -244,7 +244,8 @@ hipError_t launch_head_bwd(int dt, int g, const PtrTab& gp, const PtrTab& dlogit
 // invalid (device, may be null): when it reads non-zero the step changes nothing
 hipError_t launch_sgd(float* w, float* v, float* g, size_t n, float lr, float mu, const int* invalid, hipStream_t stream);
 hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream);
-hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
+// max_elems: elements of the largest convolution's forward copy (sizes the grid)
+hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs, size_t max_elems,
                                hipStream_t stream);
 hipError_t launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
 // iters rounds of 131 072 flop of bf16 MFMA per wave (8 x 16x16x32, or 4 x 32x32x16 when wide), 4 waves per

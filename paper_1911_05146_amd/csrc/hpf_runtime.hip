@@ -59,7 +59,8 @@ struct BlockPlan {
   Loc x_in, a[3], c[2], y;
   bool mat[3] = {false, false, false};   // bf16 mode: a[j] = relu(bn_j(.)) is written to memory (else applied while staging)
   Loc gy;      // gradient w.r.t. the block output (kept until the deferred weight-gradient pass)
-  Loc dc[2];   // gradient w.r.t. c[j], the output of conv j (j < nconv-1)
+  Loc dc[3];   // gradient w.r.t. c[j], the output of conv j (j < nconv-1); units of the other models (bf16 mode): the
+               // gradient operand of the unit's convolution j (2: the projection), kept for the deferred weight gradients
   // units of the other models (kinds HPF_POSTACT ... HPF_BIAS_RELU)
   size_t bias_off = 0;   // floats: the unit's bias vector
   Loc y0;                // conv + bias + relu output before the max-pool (== y without a pool)
@@ -102,6 +103,11 @@ struct Plan {
   size_t n_running = 0, running_off = 0, bn_table_off = 0;   // BatchNorm running statistics (fp32) and their table
   std::vector<BnRunDesc> bn_table;
   std::vector<PackDesc> table;
+  size_t pack_max_elems() const {
+    size_t m = 0;
+    for (const PackDesc& d : table) m = std::max(m, (size_t)d.Cout * d.Kf);
+    return m;
+  }
   // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
   struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
   std::vector<ResRun> runs;
@@ -391,6 +397,17 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     const bool last = (i == d.n_blocks - 1);
     if (!p.residual()) {
       if (last && !d.has_head) p.gy.kind = CALLER_ERR_IN; else p.gy = tensor(M_out * p.d.c_out);
+      if (P.dt == DT_BF16) {   // what the deferred weight gradients read
+        const size_t M_in = b_ * p.h_in * p.w_in;
+        if (p.d.kind == K_POSTACT) {
+          p.dc[0] = tensor(M_out * p.d.c_mid); p.dc[1] = tensor(M_out * p.d.c_out);
+          if (p.proj) p.dc[2] = tensor(M_out * p.d.c_out);
+        } else if (p.d.kind == K_CONV_RELU) {
+          p.dc[0] = tensor(M_in * p.d.c_out);
+        } else if (p.d.kind == K_DENSE) {
+          p.dc[0] = tensor(b_ * p.d.c_out);
+        }
+      }
       continue;
     }
     if (p.j1 == p.nconv) {
@@ -481,7 +498,16 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr, false});
     for (int i = 0; i < d.n_blocks; ++i) {
       const BlockPlan& p = P.bp[i];
-      if (!p.residual()) continue;   // these units form their weight gradients right where the operands are at hand
+      if (!p.residual()) {   // the operands are stored activations (no BatchNorm to recompute)
+        if (p.d.kind == K_POSTACT) {
+          wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
+          wc.push_back(WConv{&p.cv[1], p.cv[1].cin, p.cv[1].cin, p.cv[1].R, p.a[0], p.dc[1], nullptr, false});
+          if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.dc[2], nullptr, false});
+        } else if (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) {
+          wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
+        }
+        continue;
+      }
       bool in_run = false;
       for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
       for (int j = p.j0; j < p.j1; ++j)
@@ -1012,9 +1038,14 @@ void run_backward(Ctx& c) {
     c.seg_same(PROF_OTHER_BWD);
     const BlockPlan& p = P.bp[ii];
     const size_t M_in = b * p.h_in * p.w_in, M_out = b * p.h_out * p.w_out;
-    if (!p.residual()) {   // a unit of VGG-16 / ResNet-v1; weight gradients formed at once (both operands are at hand)
+    if (!p.residual()) {   // a unit of VGG-16 / ResNet-v1; the gradient operands of its convolutions keep buffers of their
+                           // own when the weight gradients are deferred (fp32 mode forms them at once, from scratch tensors)
       const PtrTab x = c.tab(p.x_in), dy = c.tab(p.gy), gx = c.tab(grad_in_loc(ii));
-      const PtrTab t0 = c.scratch(0), t1 = c.scratch(1), t2 = c.scratch(2), t3 = c.scratch(3);
+      const PtrTab t2 = c.scratch(2);
+      const PtrTab t0 = deferred && p.d.kind == K_POSTACT ? c.tab(p.dc[1]) : c.scratch(0);
+      const PtrTab t1 = deferred && (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) ? c.tab(p.dc[0])
+                        : deferred && p.d.kind == K_POSTACT && p.proj ? c.tab(p.dc[2]) : c.scratch(1);
+      const PtrTab t3 = deferred && p.d.kind == K_POSTACT ? c.tab(p.dc[0]) : c.scratch(3);
       const PtrTab sums = c.mbp(P.sums_off), parts = c.mbp(P.partials_off);
       float* g_bias = c.h->grads() + p.bias_off;
       if (p.d.kind == K_POSTACT) {
@@ -1024,14 +1055,14 @@ void run_backward(Ctx& c) {
                               p.bn[1].C, sums, c.h->grads() + p.bn[1].g_off, c.h->grads() + p.bn[1].b_off, parts, t0, t1,
                               P.d.bn_mode, c.s),
               "join_bwd");
-        c.conv_wgrad(p.cv[1], a1, t0);
+        if (!deferred) c.conv_wgrad(p.cv[1], a1, t0);
         c.conv_dgrad(p.cv[1], t0, t2, Ctx::none());
         c.bn_bwd(p.bn[0], c1, t2, Ctx::none(), t3, M_out);              // dc1
-        c.conv_wgrad(p.cv[0], x, t3);
+        if (!deferred) c.conv_wgrad(p.cv[0], x, t3);
         if (p.proj) {
-          c.conv_wgrad(p.pj, x, t1);
-          c.conv_dgrad(p.pj, t1, t0, Ctx::none());
-          c.conv_dgrad(p.cv[0], t3, gx, t0);
+          if (!deferred) c.conv_wgrad(p.pj, x, t1);
+          c.conv_dgrad(p.pj, t1, t2, Ctx::none());                      // t2 is free again
+          c.conv_dgrad(p.cv[0], t3, gx, t2);
         } else {
           c.conv_dgrad(p.cv[0], t3, gx, t1);
         }
@@ -1045,7 +1076,7 @@ void run_backward(Ctx& c) {
         const int rows = p.d.kind == K_DENSE ? (int)b : (int)M_in;
         c.chk(launch_bias_act_bwd(P.dt, c.g, y0, d0, t1, g_bias, rows, p.d.c_out, p.d.kind == K_DENSE ? (p.d.c_mid != 0) : 1, sums, parts, c.s),
               "bias_act_bwd");
-        c.conv_wgrad(p.cv[0], x, t1);
+        if (!deferred) c.conv_wgrad(p.cv[0], x, t1);
         c.conv_dgrad(p.cv[0], t1, gx, Ctx::none());
       } else if (p.d.kind == K_BN_RELU) {
         c.bn_bwd(p.bn[0], x, dy, Ctx::none(), gx, M_in);
@@ -1273,7 +1304,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
   for (int i = 0; i < m; ++i) ok(hipMemset(p->mb_base(i) + P.tickets_off, 0, 64 * sizeof(unsigned)));
   if (!P.table.empty()) {
     ok(hipMemcpy(p->arena + P.table_off, P.table.data(), P.table.size() * sizeof(PackDesc), hipMemcpyHostToDevice));
-    ok(launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, nullptr));
+    ok(launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, P.pack_max_elems(), nullptr));
   }
   for (int k = 0; k < WGRAD_CLASSES; ++k)
     if (!P.items[k].empty())
@@ -1570,7 +1601,7 @@ hpf_status hpf_sgd_step(hpf_partition* p, float lr, float momentum, void* hip_st
   // a batch whose image-resident launches timed out has no valid gradients: the kernel then leaves everything alone
   if (launch_sgd(p->params(), p->mom(), p->grads(), P.n_params, lr, momentum, P.runs.empty() ? nullptr : p->abort_flag(), s) != hipSuccess)
     return fail(HPF_EDEVICE, "sgd failed");
-  if (launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, s) != hipSuccess)
+  if (launch_pack_weights(p->params(), p->packed(), (const PackDesc*)(p->arena + P.table_off), P.n_convs, P.pack_max_elems(), s) != hipSuccess)
     return fail(HPF_EDEVICE, "pack failed");
   begin_next_batch(p, s);
   return HPF_OK;
@@ -1863,7 +1894,7 @@ static hpf_status op_conv(int mode, hpf_dtype dtype, const void* src, const floa
   if (repack) {
     if (hipMemcpyAsync(base + table_off, &pd, sizeof(pd), hipMemcpyHostToDevice, s) != hipSuccess) return fail(HPF_EDEVICE, "table copy failed");
     if (hipStreamSynchronize(s) != hipSuccess) return fail(HPF_EDEVICE, "sync failed");   // pd is a stack object
-    if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
+    if (launch_pack_weights(w, (bf16_t*)base, (const PackDesc*)(base + table_off), 1, (size_t)cout * pd.Kf, s) != hipSuccess) return fail(HPF_EDEVICE, "pack failed");
   }
   const bf16_t* wp = (const bf16_t*)base + (mode == CONV_FWD ? pd.wf_off : pd.wd_off);
   if (conv_prepare() != hipSuccess) return fail(HPF_EDEVICE, "kernel set-up failed");

@@ -183,17 +183,33 @@ __global__ __launch_bounds__(256) void k_copy16(u32x4* __restrict__ dst, const u
   if (blockIdx.x == 0 && (int)threadIdx.x < ntail) dtail[threadIdx.x] = stail[threadIdx.x];
 }
 
-// grid (n_convs, 8): block (i, j) fills every 8th 256-element chunk of conv i's two packed copies.
+// grid (n_convs, Y): the Y blocks of conv i share its work round-robin.  The forward copy is a transpose of the
+// fp32 master ([k][n] -> [n][k]), done in 64 x 64 tiles through LDS so that both the reads and the writes are
+// contiguous; the data-gradient copy keeps n contiguous and is a flat loop.
 __global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ params, bf16_t* __restrict__ packed,
                                                       const PackDesc* __restrict__ table) {
+  __shared__ float tile[64][65];
   const PackDesc d = table[blockIdx.x];
   const float* w = params + d.w_off;
   {
     bf16_t* wf = packed + d.wf_off;  // [Cout][Kf], k = tap*Cin + c
-    const int total = d.Cout * d.Kf, ktot = d.T * d.Cin;
-    for (int i = blockIdx.y * 256 + threadIdx.x; i < total; i += gridDim.y * 256) {
-      const int n = i / d.Kf, k = i - n * d.Kf;
-      wf[i] = f32_to_bf16(k < ktot ? w[(size_t)k * d.Cout + n] : 0.f);
+    const int ktot = d.T * d.Cin;
+    const int tk = (d.Kf + 63) / 64, tn = (d.Cout + 63) / 64;
+    const int lx = threadIdx.x & 63, ly = threadIdx.x >> 6;
+    for (int t = blockIdx.y; t < tk * tn; t += gridDim.y) {
+      const int k0 = (t / tn) * 64, n0 = (t % tn) * 64;
+      __syncthreads();
+#pragma unroll 4
+      for (int r = ly; r < 64; r += 4) {
+        const int k = k0 + r, n = n0 + lx;
+        tile[r][lx] = (k < ktot && n < d.Cout) ? w[(size_t)k * d.Cout + n] : 0.f;
+      }
+      __syncthreads();
+#pragma unroll 4
+      for (int r = ly; r < 64; r += 4) {
+        const int n = n0 + r, k = k0 + lx;
+        if (n < d.Cout && k < d.Kf) wf[(size_t)n * d.Kf + k] = f32_to_bf16(tile[lx][r]);
+      }
     }
   }
   if (d.wd_off != ~0ull) {
@@ -267,10 +283,13 @@ hipError_t launch_zero_f32(float* p, size_t n, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs,
+hipError_t launch_pack_weights(const float* params, bf16_t* packed, const PackDesc* table_dev, int n_convs, size_t max_elems,
                                hipStream_t stream) {
   if (n_convs <= 0) return hipSuccess;
-  k_pack_weights<<<dim3((unsigned)n_convs, 8), 256, 0, stream>>>(params, packed, table_dev);
+  // blocks per convolution: one per 8192 elements of the largest one (blocks with nothing to do leave at once)
+  size_t y = (max_elems + 8191) / 8192;
+  y = y < 8 ? 8 : (y > 1024 ? 1024 : y);
+  k_pack_weights<<<dim3((unsigned)n_convs, (unsigned)y), 256, 0, stream>>>(params, packed, table_dev);
   return hipGetLastError();
 }
 

@@ -309,9 +309,11 @@ def vgg16(n_parts=1, p=0, microbatch=16, num_microbatches=8, seed=SEED_BASE + 8,
 
 
 def config(index: int) -> PartitionSpec:
-    """The five benchmark configurations, numbered 1..5, and 6: the same cut of the wider ResNet-1001."""
+    """The five benchmark configurations, numbered 1..5; 6: the same cut of the wider ResNet-1001; 7 and 8: the
+    paper's two other models whole, ResNet-110-v1 and VGG-16 on 32x32 images (8 micro-batches of 16 images)."""
     return {1: resnet20, 2: resnet110_partition, 3: resnet1001_partition,
-            4: resnet1001_whole, 5: resnet152_stage3, 6: resnet1001_wide_partition}[index]()
+            4: resnet1001_whole, 5: resnet152_stage3, 6: resnet1001_wide_partition,
+            7: resnet110_v1, 8: vgg16}[index]()
 
 
 def with_microbatching(spec: PartitionSpec, microbatch: int, num_microbatches: int,
