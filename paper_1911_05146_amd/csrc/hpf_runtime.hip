@@ -919,11 +919,12 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
       if (p.d.kind == K_POSTACT) {
         // c1 = conv1(x); a1 = relu(bn1(c1)); c2 = conv2(a1); y = relu(bn2(c2) + shortcut)
         const PtrTab c1 = c.tab(p.c[0]), a1 = c.tab(p.a[0]), c2 = c.tab(p.c[1]);
-        c.conv_fwd(p.cv[0], x, c1, Ctx::none());
-        c.bn_fwd(p.bn[0], c1, a1, M_out);
-        c.conv_fwd(p.cv[1], a1, c2, Ctx::none());
+        // the BatchNorm sums come out of the producing convolution's epilogue (fusion levels 1 and 2)
+        const int rows1 = c.conv_fwd(p.cv[0], x, c1, Ctx::none(), true);
+        c.bn_fwd(p.bn[0], c1, a1, M_out, rows1);
         if (p.proj) c.conv_fwd(p.pj, x, c.tab(p.sc), Ctx::none());
-        c.bn_fwd(p.bn[1], c2, Ctx::none(), M_out, 0, false);   // statistics only
+        const int rows2 = c.conv_fwd(p.cv[1], a1, c2, Ctx::none(), true);
+        c.bn_fwd(p.bn[1], c2, Ctx::none(), M_out, rows2, false);   // statistics only
         c.chk(launch_bn_add_relu_apply(P.dt, c.g, c2, c.tab(p.sc), y, c.h->params() + p.bn[1].g_off, c.h->params() + p.bn[1].b_off,
                                        c.mbp(p.bn[1].stats_off), (int)M_out, p.bn[1].C, c.s),
               "bn_add_relu");
@@ -1056,8 +1057,8 @@ void run_backward(Ctx& c) {
                               P.d.bn_mode, c.s),
               "join_bwd");
         if (!deferred) c.conv_wgrad(p.cv[1], a1, t0);
-        c.conv_dgrad(p.cv[1], t0, t2, Ctx::none());
-        c.bn_bwd(p.bn[0], c1, t2, Ctx::none(), t3, M_out);              // dc1
+        const int rows = c.conv_dgrad(p.cv[1], t0, t2, Ctx::none(), &p.bn[0], &c1);
+        c.bn_bwd(p.bn[0], c1, t2, Ctx::none(), t3, M_out, rows);        // dc1
         if (!deferred) c.conv_wgrad(p.cv[0], x, t3);
         if (p.proj) {
           if (!deferred) c.conv_wgrad(p.pj, x, t1);

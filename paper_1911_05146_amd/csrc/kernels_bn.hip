@@ -201,6 +201,98 @@ __global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize(int M, int C, 
   }
 }
 
+// The float (bf16 mode) finalize kernels: the same two-pass arithmetic with 16 channels x 16 row-groups per block and
+// the first FIN_CACHE records of every thread held in registers -- all their loads are in flight at once and the
+// second pass does not go back to memory (up to 128 tile rows: one memory round trip instead of a chain of them;
+// these launches sit between every convolution and its consumer, so their latency is on the critical path).
+constexpr int FINW_CH = 16, FINW_RG = BN_THREADS / FINW_CH, FIN_CACHE = 8;
+
+__device__ __forceinline__ float finw_sum(float v, float (*sh)[FINW_CH + 1], int cl, int j) {
+  __syncthreads();
+  sh[j][cl] = v;
+  __syncthreads();
+  float t = sh[0][cl];
+#pragma unroll
+  for (int r = 1; r < FINW_RG; ++r) t += sh[r][cl];
+  return t;
+}
+
+__global__ __launch_bounds__(BN_THREADS) void k_bn_stats_finalize_wide(int M, int C, unsigned nblocks, float eps, PtrTab parts,
+                                                                       PtrTab statss) {
+  const float4* __restrict__ partials = (const float4*)pick(parts, blockIdx.z);
+  float* __restrict__ stats = (float*)pick(statss, blockIdx.z);
+  __shared__ float sh[FINW_RG][FINW_CH + 1];
+  const int cl = threadIdx.x % FINW_CH, j = threadIdx.x / FINW_CH;
+  const int c = blockIdx.x * FINW_CH + cl;
+  const bool cv = c < C;
+  const float4* p = partials + (cv ? c : 0);
+  float4 rec[FIN_CACHE];   // {K, S1, S2, n}
+#pragma unroll
+  for (int i = 0; i < FIN_CACHE; ++i) {
+    const unsigned bx = (unsigned)j + (unsigned)i * FINW_RG;
+    rec[i] = (cv && bx < nblocks) ? p[(size_t)bx * C] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < FIN_CACHE; ++i) tot += rec[i].w * rec[i].x + rec[i].y;   // n*K + S1 = sum of the tile's values
+  if (cv)
+    for (unsigned bx = (unsigned)j + FIN_CACHE * FINW_RG; bx < nblocks; bx += FINW_RG) {
+      const float4 q = p[(size_t)bx * C];
+      tot += q.w * q.x + q.y;
+    }
+  const float mean = finw_sum(tot, sh, cl, j) / (float)M;
+  auto dev2 = [&](const float4& q) {   // sum of squared deviations of the tile about the overall mean
+    if (!(q.w > 0.f)) return 0.f;
+    const float s1n = q.y / q.w, d = q.x + s1n - mean;
+    return q.z - q.y * s1n + q.w * d * d;
+  };
+  float m2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < FIN_CACHE; ++i) m2 += dev2(rec[i]);
+  if (cv)
+    for (unsigned bx = (unsigned)j + FIN_CACHE * FINW_RG; bx < nblocks; bx += FINW_RG) m2 += dev2(p[(size_t)bx * C]);
+  m2 = finw_sum(m2, sh, cl, j);
+  if (cv && j == 0) {
+    float var = m2 / (float)M;
+    var = var > 0.f ? var : 0.f;
+    stats[c] = mean;
+    stats[C + c] = rsqrt_exact(var + eps);
+  }
+}
+
+__global__ __launch_bounds__(BN_THREADS) void k_bn_bwd_finalize_wide(int C, unsigned nblocks, PtrTab parts, PtrTab sumss, float* g_gamma,
+                                                                     float* g_beta) {
+  const float2* __restrict__ partials = (const float2*)pick(parts, blockIdx.z);
+  float* __restrict__ sums = (float*)pick(sumss, blockIdx.z);
+  __shared__ float sh[FINW_RG][FINW_CH + 1];
+  const int cl = threadIdx.x % FINW_CH, j = threadIdx.x / FINW_CH;
+  const int c = blockIdx.x * FINW_CH + cl;
+  const bool cv = c < C;
+  const float2* p = partials + (cv ? c : 0);
+  float2 rec[FIN_CACHE];
+#pragma unroll
+  for (int i = 0; i < FIN_CACHE; ++i) {
+    const unsigned bx = (unsigned)j + (unsigned)i * FINW_RG;
+    rec[i] = (cv && bx < nblocks) ? p[(size_t)bx * C] : make_float2(0.f, 0.f);
+  }
+  float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < FIN_CACHE; ++i) { a1 += rec[i].x; a2 += rec[i].y; }
+  if (cv)
+    for (unsigned bx = (unsigned)j + FIN_CACHE * FINW_RG; bx < nblocks; bx += FINW_RG) {
+      const float2 q = p[(size_t)bx * C];
+      a1 += q.x; a2 += q.y;
+    }
+  a1 = finw_sum(a1, sh, cl, j);
+  a2 = finw_sum(a2, sh, cl, j);
+  if (cv && j == 0) {
+    sums[c] = a1;
+    sums[C + c] = a2;
+    atomicAdd(&g_beta[c], a1);
+    if (g_gamma) atomicAdd(&g_gamma[c], a2);
+  }
+}
+
 template <class T, class A>
 __global__ __launch_bounds__(BN_THREADS) void k_bn_apply_relu(PtrTab xs, PtrTab as, const float* __restrict__ gamma,
                                                               const float* __restrict__ beta, PtrTab statss, int M,
@@ -604,13 +696,15 @@ dim3 apply_grid(int M, int C) {
 
 size_t bn_partials_floats(int C) { return (size_t)BN_MAX_ROW_BLOCKS * C * 4 * 2; }  // 4 values, sized for double
 
+static dim3 finw(int C, int ng) { return dim3((unsigned)((C + FINW_CH - 1) / FINW_CH), 1u, (unsigned)ng); }
+
 hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float eps, const PtrTab& stats,
                            const PtrTab& partials, hipStream_t stream) {
   const BnGrid g = reduce_grid(M, C);
   const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bn_stats<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
-    k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
+    k_bn_stats_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
   } else {
     k_bn_stats<float, double><<<grid, BN_THREADS, 0, stream>>>(x, M, C, g.rows_per_block, partials);
     k_bn_stats_finalize<double><<<fin, BN_THREADS, 0, stream>>>(M, C, g.grid.x, eps, partials, stats);
@@ -622,15 +716,13 @@ hipError_t launch_bn_stats(int dt, int ng, const PtrTab& x, int M, int C, float 
 // pixel-row tile).  float arithmetic (bf16 mode).
 hipError_t launch_bn_stats_finalize(int ng, int M, int C, int nrows, float eps, const PtrTab& partials, const PtrTab& stats,
                                     hipStream_t stream) {
-  const dim3 fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
-  k_bn_stats_finalize<float><<<fin, BN_THREADS, 0, stream>>>(M, C, (unsigned)nrows, eps, partials, stats);
+  k_bn_stats_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(M, C, (unsigned)nrows, eps, partials, stats);
   return hipGetLastError();
 }
 
 hipError_t launch_bn_bwd_finalize(int ng, int C, int nrows, const PtrTab& partials, const PtrTab& sums, float* g_gamma,
                                   float* g_beta, hipStream_t stream) {
-  const dim3 fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
-  k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, (unsigned)nrows, partials, sums, g_gamma, g_beta);
+  k_bn_bwd_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(C, (unsigned)nrows, partials, sums, g_gamma, g_beta);
   return hipGetLastError();
 }
 
@@ -652,7 +744,7 @@ hipError_t launch_bn_bwd_reduce(int dt, int ng, const PtrTab& x, const PtrTab& d
   const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bn_bwd_reduce<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, M, C, g.rows_per_block, partials);
-    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
+    k_bn_bwd_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
   } else {
     k_bn_bwd_reduce<float, double><<<grid, BN_THREADS, 0, stream>>>(x, da, gamma, beta, stats, M, C, g.rows_per_block, partials);
     k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
@@ -710,7 +802,7 @@ hipError_t launch_bias_act_bwd(int dt, int ng, const PtrTab& y, const PtrTab& dy
   const dim3 grid(g.grid.x, g.grid.y, (unsigned)ng), fin((unsigned)((C + FIN_CH - 1) / FIN_CH), 1, (unsigned)ng);
   if (dt == DT_BF16) {
     k_bias_act_bwd<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(y, dy, dx, M, C, relu, g.rows_per_block, partials);
-    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, nullptr, g_bias);
+    k_bn_bwd_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, nullptr, g_bias);
   } else {
     k_bias_act_bwd<float, double><<<grid, BN_THREADS, 0, stream>>>(y, dy, dx, M, C, relu, g.rows_per_block, partials);
     k_bn_bwd_finalize<double><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, nullptr, g_bias);
@@ -753,7 +845,7 @@ hipError_t launch_join_bwd(int dt, int ng, const PtrTab& x, const PtrTab& y, con
   ag.z = (unsigned)ng;
   if (dt == DT_BF16) {
     k_join_bwd_reduce<bf16_t, float><<<grid, BN_THREADS, 0, stream>>>(x, y, dy, stats, M, C, g.rows_per_block, partials);
-    k_bn_bwd_finalize<float><<<fin, BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
+    k_bn_bwd_finalize_wide<<<finw(C, ng), BN_THREADS, 0, stream>>>(C, g.grid.x, partials, sums, g_gamma, g_beta);
     k_join_bwd_apply<bf16_t, float><<<ag, BN_THREADS, 0, stream>>>(x, y, dy, gamma, stats, sums, dx, dadd, M, C, frozen);
   } else {
     k_join_bwd_reduce<float, double><<<grid, BN_THREADS, 0, stream>>>(x, y, dy, stats, M, C, g.rows_per_block, partials);
