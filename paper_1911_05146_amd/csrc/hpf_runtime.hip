@@ -109,7 +109,7 @@ struct Plan {
     return m;
   }
   // image-resident runs of identity bottleneck blocks (bf16 mode, micro-batch statistics)
-  struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0; size_t table_off = 0; /* bytes from the arena base */ };
+  struct ResRun { int first = 0, count = 0, kind = 1, C = 0, MID = 0, bands = 1; size_t table_off = 0; /* bytes from the arena base */ };
   std::vector<ResRun> runs;
   std::vector<int> run_at;             // per block: index of the run that starts (forward) at this block, else -1
   std::vector<int> run_end_at;         // per block: index of the run that ends at this block, else -1
@@ -440,6 +440,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       return p.residual() && p.whole() && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
     };
     int cmax_run = 0;
+    size_t xchg_bytes = 0;
     for (int i = 0; i < d.n_blocks;) {
       if (!eligible(i)) { ++i; continue; }
       int j = i + 1;
@@ -448,6 +449,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         ++j;
       Plan::ResRun r;
       r.first = i; r.count = j - i; r.kind = P.bp[i].d.kind; r.C = P.bp[i].d.c_in; r.MID = P.bp[i].d.c_mid;
+      r.bands = resident_bands(r.kind, r.C, r.MID, P.bp[i].h_in, P.bp[i].w_in);
       r.table_off = P.res_blocks.size() * sizeof(ResBlock);   // made absolute below
       auto res_loc = [](const Loc& l) -> unsigned long long {
         switch (l.kind) {
@@ -480,10 +482,11 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       P.run_end_at[j - 1] = (int)P.runs.size();
       P.runs.push_back(r);
       if (r.C > cmax_run) cmax_run = r.C;
+      xchg_bytes = std::max(xchg_bytes, resident_xchg_bytes(r.C, d.microbatch, r.bands));
       i = j;
     }
     if (!P.runs.empty()) {
-      P.xchg_off = alloc(resident_xchg_bytes(cmax_run, d.microbatch)).off;
+      P.xchg_off = alloc(std::max(xchg_bytes, resident_xchg_bytes(cmax_run, d.microbatch, 1))).off;
       P.tag_off = alloc(sizeof(unsigned)).off;
     }
   }
@@ -509,7 +512,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         continue;
       }
       bool in_run = false;
-      for (const Plan::ResRun& r : P.runs) in_run = in_run || (i >= r.first && i < r.first + r.count);
+      for (const Plan::ResRun& r : P.runs) in_run = in_run || (r.bands == 1 && i >= r.first && i < r.first + r.count);   // band runs: forward launch only
       for (int j = p.j0; j < p.j1; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
                            j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
@@ -901,7 +904,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     }
   }
   for (size_t bi = 0; bi < P.bp.size(); ++bi) {
-    if (resident && P.run_at[bi] >= 0) {   // the whole run in one launch; it takes its own statistics
+    if (resident && P.run_at[bi] >= 0 && !(c.inference && P.runs[P.run_at[bi]].bands > 1)) {   // the whole run in one launch; it takes its own statistics
       const Plan::ResRun& r = P.runs[P.run_at[bi]];
       if (c.inference) c.res_inference(r);
       else c.res_forward(r);
@@ -1030,7 +1033,7 @@ void run_backward(Ctx& c) {
     if (P.d.has_head == 1) c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
-    if (c.h->resident() && P.run_end_at[ii] >= 0) {
+    if (c.h->resident() && P.run_end_at[ii] >= 0 && P.runs[P.run_end_at[ii]].bands == 1) {
       const Plan::ResRun& r = P.runs[P.run_end_at[ii]];
       c.res_backward(r);
       ii = (size_t)r.first;
@@ -1129,7 +1132,8 @@ void run_backward(Ctx& c) {
     }
     const bool res = c.h->resident();
     if (res)
-      for (const Plan::ResRun& r : P.runs) c.res_wgrad(r);
+      for (const Plan::ResRun& r : P.runs)
+        if (r.bands == 1) c.res_wgrad(r);
     for (int k = 0; k < WGRAD_CLASSES; ++k) {
       const std::vector<WgradItem>& items = res ? P.items_nr[k] : P.items[k];
       if (items.empty()) continue;
@@ -1328,7 +1332,9 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
       ok(hipMemset(p->mb_base(i) + P.xchg_off, 0, P.tag_off - P.xchg_off));
       ok(hipMemset(p->mb_base(i) + P.tag_off, 0, sizeof(unsigned)));
     }
-    p->res_group = resident_max_group(P.d.microbatch);
+    int max_bands = 1;
+    for (const Plan::ResRun& r : P.runs) max_bands = std::max(max_bands, r.bands);
+    p->res_group = resident_max_group(P.d.microbatch * max_bands);
     if (p->res_group >= 1) ok(resident_prepare());
   }
   p->ev_fwd.resize(m); p->ev_bwd.resize(m);

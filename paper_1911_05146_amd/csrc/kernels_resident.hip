@@ -1406,6 +1406,354 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
                      a.grads + B.w_off[1], smem);
 }
 
+// ------------------------------------------------------------------------------------------ row bands
+// Runs of identity bottleneck blocks whose image does not fit one CU's LDS (ResNet-1001's first stage: 64-16-16-64
+// channels at 32x32, 128 KiB of residual stream per image): the image is cut into bands of BAND_ROWS image rows and
+// one work-group owns one band.  In NHWC a band is a contiguous range of 256 pixels, so every tensor of the band
+// sits at member_index * 256 * channels, exactly like an image of the kernels above; what is new is the 3x3
+// convolution, which needs the image rows just above and below the band.  Those two rows of c1 (bf16, as stored)
+// travel with the BatchNorm records of the exchange that separates conv1 from conv2 anyway -- each work-group
+// publishes its first and last row next to its {mean, M2} record and collects the facing rows of its two
+// neighbours -- so a block still has three exchanges.  The members of an exchange are the bands of all images of the
+// micro-batch (statistics are over the micro-batch); neighbours are the members me - 1 / me + 1 of the same image.
+// A reduction of 16 channels per filter tap fills half an MFMA step, so a step of the 3x3 convolution covers two
+// taps (lane groups 0-1 the first, 2-3 the second; the packed weights have k = tap*16 + c contiguous, which is the
+// same thing), and the 1x1 convolution out of 16 channels runs a half-empty step against zero-padded weights.
+constexpr int BAND_ROWS = 8, BAND_W = 32, BAND_P = BAND_ROWS * BAND_W;   // 256 pixels = 16 pixel tiles, two per wave
+constexpr int BAND_PTW = BAND_P / 16 / RES_NWV;
+constexpr int BAND_HALO_F = BAND_W * 16 / 2;     // words of one row of 16 bf16 channels (two values per word)
+constexpr int BAND_HALO_B = BAND_W * 16;         // words of one row of 16 fp32 channels (backward)
+constexpr int BAND_RW = 2 * 16 + 2 * BAND_HALO_B;   // record width in words: the widest record (backward conv2 exchange), >= 2*64
+static_assert(BAND_RW >= 2 * 64 && BAND_PTW == 2, "record width / tiles per wave");
+
+// Collects, from the records of all nwg members, the first ns words each into gath[m*ns + w], and nh words from
+// offset off_up of member `up` / off_dn of member `dn` (a negative member: none, nothing is read) into halo[0..nh) /
+// halo[nh..2nh) as raw 32-bit payloads.  Returns false, uniformly, when a word did not arrive.  Ends with a barrier.
+__device__ __forceinline__ bool band_collect(const u64* slot, int nwg, int ns, unsigned tag, float* gath, int up, int dn, int off_up,
+                                             int off_dn, int nh, uint32_t* halo, int* abort_flag) {
+  constexpr int INFL = 8;   // words in flight per thread and polling round
+  const int n_stats = nwg * ns, total = n_stats + 2 * nh;
+  int timed_out = 0;
+  for (int i0 = threadIdx.x; i0 < total; i0 += RES_NT * INFL) {
+    const u64* src[INFL];
+    bool want[INFL];
+    u64 v[INFL];
+#pragma unroll
+    for (int k = 0; k < INFL; ++k) {
+      const int i = i0 + k * RES_NT;
+      want[k] = i < total;
+      src[k] = slot;
+      v[k] = 0;
+      if (i < n_stats) {
+        const int m = i / ns;
+        src[k] = slot + (size_t)m * BAND_RW + (i - m * ns);
+      } else if (i < total) {
+        const int j = i - n_stats, second = j >= nh ? 1 : 0, w = j - second * nh;
+        const int mem = second ? dn : up;
+        want[k] = mem >= 0;
+        src[k] = slot + (size_t)(mem >= 0 ? mem : 0) * BAND_RW + (second ? off_dn : off_up) + w;
+      }
+    }
+    unsigned spins = 0;
+    for (;;) {
+#pragma unroll
+      for (int k = 0; k < INFL; ++k)
+        if (want[k]) v[k] = __hip_atomic_load(src[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      bool all = true;
+#pragma unroll
+      for (int k = 0; k < INFL; ++k) all = all && (!want[k] || (unsigned)(v[k] >> 32) == tag);
+      if (all) break;
+      if (++spins > RES_SPIN_LIMIT) { timed_out = 1; break; }
+    }
+#pragma unroll
+    for (int k = 0; k < INFL; ++k) {
+      const int i = i0 + k * RES_NT;
+      if (i < n_stats) gath[i] = __uint_as_float((unsigned)v[k]);
+      else if (i < total) halo[i - n_stats] = want[k] ? (uint32_t)v[k] : 0u;
+    }
+  }
+  const int any = __syncthreads_or(timed_out);
+  if (any && threadIdx.x == 0) atomicExch(abort_flag, 1);
+  return any == 0;
+}
+
+// stats_publish for a record of width BAND_RW: words c and Cc + c of `rec`.
+template <int Cc>
+__device__ __forceinline__ void band_stats_publish(const bf16_t* s, float* red, u64* rec, unsigned tag) {
+  constexpr int U = Cc / 8, NG = 32 / U, P = BAND_P;
+  static_assert(U <= 32 && 32 % U == 0, "unit count");
+  const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+  const int unit = row % U, grp = row / U;
+  float K[8], s1[8], s2[8];
+  load8(s + unit * 8, K);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { s1[i] = 0.f; s2[i] = 0.f; }
+  for (int p = grp * 16 + l16; p < P; p += NG * 16) {
+    float v[8];
+    load8(s + p * (Cc + 8) + unit * 8, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float d = v[i] - K[i];
+      s1[i] += d;
+      s2[i] = fmaf(d, d, s2[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { s1[i] = row_sum<1>(s1[i]); s2[i] = row_sum<1>(s2[i]); }
+  if (l16 == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      red[grp * 2 * Cc + unit * 8 + i] = s1[i];
+      red[grp * 2 * Cc + Cc + unit * 8 + i] = s2[i];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < Cc) {
+    const int c = threadIdx.x;
+    float S1 = 0.f, S2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) { S1 += red[i * 2 * Cc + c]; S2 += red[i * 2 * Cc + Cc + c]; }
+    const float inv = 1.f / (float)P;
+    __hip_atomic_store(rec + c, ((u64)tag << 32) | (u64)__float_as_uint(bf16_to_f32(s[c]) + S1 * inv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(rec + Cc + c, ((u64)tag << 32) | (u64)__float_as_uint(fmaxf(S2 - S1 * S1 * inv, 0.f)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// merge_coef for 16 <= Cc: channels are dealt to the rows of 16 lanes CR at a time (CR = 1 below 32 channels, where
+// only the first Cc rows work), the lanes of a row split the members.  Ends with a barrier.
+template <int Cc>
+__device__ __forceinline__ void band_merge_coef(const float* gath, int nwg, float eps, const float* gamma, const float* beta, float2* coef,
+                                                float* stats_out) {
+  constexpr int CR = Cc >= 32 ? Cc / 32 : 1, MP = 16 / CR, ROWS = Cc / CR;
+  const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+  const bool act = row < ROWS;
+  const int c = act ? row * CR + l16 % CR : 0, part = l16 / CR;
+  const float g = gamma[c], b = beta[c];
+  float s = 0.f;
+  for (int m = part; m < nwg; m += MP) s += gath[m * 2 * Cc + c];
+  s = row_sum<CR>(s);
+  const float inv_n = 1.f / (float)nwg;
+  const float mean = s * inv_n;
+  float s2 = 0.f;
+  for (int m = part; m < nwg; m += MP) {
+    const float d = gath[m * 2 * Cc + c] - mean;
+    s2 += gath[m * 2 * Cc + Cc + c] + (float)BAND_P * d * d;
+  }
+  s2 = row_sum<CR>(s2);
+  if (act && part == 0) {
+    const float var = s2 * inv_n / (float)BAND_P;
+    const float is = 1.0f / sqrtf(var + eps);
+    coef[c] = bn_scale_shift(mean, is, g, b);
+    if (stats_out) { stats_out[c] = mean; stats_out[Cc + c] = is; }
+  }
+  __syncthreads();
+}
+
+// 3x3 convolution of 16 -> 16 channels over a band tile with one halo row above and below: src is [10 rows][32][MS],
+// output pixel (r, q) of the band reads tile rows r .. r+2; two filter taps per MFMA step (see above).  Weights
+// [16][160] bf16, k = tap*16 + c (forward) or tap*16 + n (backward), zero beyond k = 144.
+template <bool BACKWARD, class WF>
+__device__ __forceinline__ void band_conv3x3(const bf16_t* src, const WF& wfr, int wave, int fr, int fq, floatx4 (&acc)[BAND_PTW][1]) {
+  constexpr int MS = 16 + 8;
+  int py[BAND_PTW], px[BAND_PTW];
+#pragma unroll
+  for (int j = 0; j < BAND_PTW; ++j) {
+    const int p = (wave + j * RES_NWV) * 16 + fr;
+    py[j] = p / BAND_W;
+    px[j] = p - py[j] * BAND_W;
+  }
+  const int c8 = (fq & 1) * 8;
+#pragma unroll
+  for (int st = 0; st < 5; ++st) {
+    const int tap = 2 * st + (fq >> 1);
+    const int r = tap / 3, s = tap - r * 3;
+    const int dh = BACKWARD ? 1 - r : r - 1, dw = BACKWARD ? 1 - s : s - 1;
+    const bf16x8 wf = wfr.get(st, 0);
+#pragma unroll
+    for (int j = 0; j < BAND_PTW; ++j) {
+      const int ws = px[j] + dw;
+      const bool ok = tap < 9 && (unsigned)ws < (unsigned)BAND_W;
+      const int row = ok ? (py[j] + 1 + dh) * BAND_W + ws : 0;
+      bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(src + row * MS + c8);
+      if (!ok) bfrag = frag_zero();
+      acc[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, bfrag, acc[j][0], 0, 0, 0);
+    }
+  }
+}
+
+template <int C, int MID>
+__global__ void __launch_bounds__(RES_NT) k_band_forward(const ResArgs a) {
+  static_assert(C == 64 && MID == 16, "the shape of ResNet-1001's first stage");
+  constexpr int XS = C + 8, MS = MID + 8, P = BAND_P, PTW = BAND_PTW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int nb = a.H / BAND_ROWS, nwg = a.nmem * nb;      // bands per image, members of an exchange
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  const int band = me % nb;
+  const int up = band > 0 ? me - 1 : -1, dn = band + 1 < nb ? me + 1 : -1;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sx = reinterpret_cast<bf16_t*>(smem);               // residual stream of the band, [P][XS]
+  bf16_t* smA = sx + (size_t)P * XS;                          // c1 with its halo rows, then relu(bn2(.)): [10*32][MS]
+  bf16_t* smB = smA + (size_t)(P + 2 * BAND_W) * MS;          // c2, [P][MS]
+  float2* coefC = reinterpret_cast<float2*>(smB + (size_t)P * MS);
+  float2* coefM = coefC + C;
+  float* red = reinterpret_cast<float*>(coefM + MID);         // RES_NWV * 2*C floats
+  float* gath = red + RES_NWV * 2 * C;                        // nwg * 2*C floats
+  uint32_t* halo = reinterpret_cast<uint32_t*>(gath + (size_t)nwg * 2 * C);   // 2 * BAND_HALO_F words
+  bf16_t* bandA = smA + BAND_W * MS;                          // the band's own rows of the c1 tile
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * nwg * BAND_RW; };
+
+  WFrags<C / 32, 1, true> w1;     // conv1 [MID][C]
+  WFrags<5, 1, true> w2;          // conv2 [MID][160]
+  WFrags<1, C / 16, true> w3;     // conv3 [C][32], k >= MID zero
+
+  {
+    const ResBlock B0 = a.blocks[0];
+    tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
+    w1.load(a.packed + B0.wf_off[0], C, fr, fk);
+    __syncthreads();
+    band_stats_publish<C>(sx, red, slot() + (size_t)me * BAND_RW, tag0 + 1u + phase);
+    if (!band_collect(slot(), nwg, 2 * C, tag0 + 1u + phase, gath, -1, -1, 0, 0, 0, halo, a.abort_flag)) return;
+    ++phase;
+    band_merge_coef<C>(gath, nwg, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
+                       me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+  }
+
+  for (int bi = 0; bi < a.nblk; ++bi) {
+    const ResBlock B = a.blocks[bi];
+    // ---- conv1 (1x1, C -> MID) on relu(bn1(x))
+    {
+      floatx4 acc[PTW];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < C / 32; ++ks) {
+        float2 cf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cf[i] = coefC[ks * 32 + fk + i];
+        const bf16x8 wf = w1.get(ks, 0);
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const int pt = wave + j * RES_NWV;
+          const uint4 xv = *reinterpret_cast<const uint4*>(sx + (pt * 16 + fr) * XS + ks * 32 + fk);
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, frag_bn_relu(xv, cf), acc[j], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+        *reinterpret_cast<uint2*>(bandA + ((wave + j * RES_NWV) * 16 + fr) * MS + fq * 4) = pack4(acc[j]);
+    }
+    w2.load(a.packed + B.wf_off[1], 160, fr, fk);
+    __syncthreads();
+    {
+      u64* rec = slot() + (size_t)me * BAND_RW;
+      const unsigned tag = tag0 + 1u + phase;
+      band_stats_publish<MID>(bandA, red, rec, tag);
+      // the band's first and last row of c1 (as stored) for the neighbours: word w = pixel w/8, channels 2*(w%8), +1
+      {
+        const int w = tid & (BAND_HALO_F - 1), last = tid >> 8;     // RES_NT == 2 * BAND_HALO_F
+        const int px = w >> 3, ch = (w & 7) * 2;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(bandA + ((last ? BAND_ROWS - 1 : 0) * BAND_W + px) * MS + ch);
+        __hip_atomic_store(rec + 2 * MID + last * BAND_HALO_F + w, ((u64)tag << 32) | (u64)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      // the row above the band is the last row of the member before, the row below the first row of the member after
+      if (!band_collect(slot(), nwg, 2 * MID, tag, gath, up, dn, 2 * MID + BAND_HALO_F, 2 * MID, BAND_HALO_F, halo, a.abort_flag)) return;
+      tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, bandA, P);
+      ++phase;
+      band_merge_coef<MID>(gath, nwg, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
+                           me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    }
+    // relu(bn2(.)) in place over the band and the two halo rows; a row outside the image is zero AFTER the activation
+    {
+      const int w = tid & (BAND_HALO_F - 1), below = tid >> 8;
+      const int px = w >> 3, ch = (w & 7) * 2;
+      *reinterpret_cast<uint32_t*>(smA + ((below ? BAND_ROWS + 1 : 0) * BAND_W + px) * MS + ch) = halo[below * BAND_HALO_F + w];
+    }
+    __syncthreads();
+    for (int u = tid; u < (P + 2 * BAND_W) * 2; u += RES_NT) {
+      const int row = u >> 1, col = u & 1;
+      const int trow = row / BAND_W;
+      uint4* q = reinterpret_cast<uint4*>(smA + row * MS + col * 8);
+      const bool outside = (trow == 0 && up < 0) || (trow == BAND_ROWS + 1 && dn < 0);
+      const uint4 v = *q;
+      const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+      const float4* cf = reinterpret_cast<const float4*>(coefM + col * 8);
+      uint32_t r[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 k = cf[i];
+        r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(wv[i]), k.x, k.y), 0.f), fmaxf(fmaf(bf_hi(wv[i]), k.z, k.w), 0.f));
+      }
+      *q = outside ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(r[0], r[1], r[2], r[3]);
+    }
+    __syncthreads();
+    // ---- conv2 (3x3, MID -> MID)
+    {
+      floatx4 acc[PTW][1];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) acc[j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+      band_conv3x3<false>(smA, w2, wave, fr, fq, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+        *reinterpret_cast<uint2*>(smB + ((wave + j * RES_NWV) * 16 + fr) * MS + fq * 4) = pack4(acc[j][0]);
+    }
+    w3.load(a.packed + B.wf_off[2], 32, fr, fk);
+    __syncthreads();
+    {
+      const unsigned tag = tag0 + 1u + phase;
+      band_stats_publish<MID>(smB, red, slot() + (size_t)me * BAND_RW, tag);
+      if (!band_collect(slot(), nwg, 2 * MID, tag, gath, -1, -1, 0, 0, 0, halo, a.abort_flag)) return;
+      tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
+      ++phase;
+      band_merge_coef<MID>(gath, nwg, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
+                           me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
+    }
+    // ---- conv3 (1x1, MID -> C) on relu(bn3(c2)) + residual, written over x; lane groups 2-3 hold the empty half of the step
+    {
+      bf16x8 bfrag[PTW];
+      float2 cf[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cf[i] = coefM[(fk + i) & (MID - 1)];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const uint4 cv = *reinterpret_cast<const uint4*>(smB + ((wave + j * RES_NWV) * 16 + fr) * MS + (fk & (MID - 1)));
+        bfrag[j] = fq < 2 ? frag_bn_relu(cv, cf) : frag_zero();
+      }
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt) {
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(0, nt), bfrag[j], acc, 0, 0, 0);
+          uint2* q = reinterpret_cast<uint2*>(sx + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
+          const uint2 xr = *q;
+          acc[0] += bf_lo(xr.x); acc[1] += bf_hi(xr.x); acc[2] += bf_lo(xr.y); acc[3] += bf_hi(xr.y);
+          *q = pack4(acc);
+        }
+      }
+    }
+    const bool more = bi + 1 < a.nblk;
+    const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
+    if (more) w1.load(a.packed + Bn.wf_off[0], C, fr, fk);
+    __syncthreads();
+    if (more) band_stats_publish<C>(sx, red, slot() + (size_t)me * BAND_RW, tag0 + 1u + phase);
+    tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+    if (more) {
+      if (!band_collect(slot(), nwg, 2 * C, tag0 + 1u + phase, gath, -1, -1, 0, 0, 0, halo, a.abort_flag)) return;
+      ++phase;
+      band_merge_coef<C>(gath, nwg, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
+                         me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
+    }
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
 size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
   const size_t tile = (size_t)P * (C + 8) * 2;
   const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16
@@ -1442,6 +1790,13 @@ size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
 
 constexpr size_t RES_LDS_BYTES = 160 * 1024 - 1024;   // LDS of a gfx950 CU, less room for the kernels' static allocations
 
+// row-band kernels (64-16 blocks at 32x32): tiles, coefficient tables, reduction and gather areas, halo words
+size_t band_fwd_lds(int nwg) {
+  const int C = 64, MID = 16;
+  return (size_t)BAND_P * (C + 8) * 2 + (size_t)(2 * BAND_P + 2 * BAND_W) * (MID + 8) * 2 + (size_t)(C + MID) * 8 +
+         (size_t)RES_NWV * 2 * C * 4 + (size_t)nwg * 2 * C * 4 + (size_t)2 * BAND_HALO_F * 4;
+}
+
 template <class K>
 hipError_t launch_res(K kernel, size_t lds, int own, int g, const ResArgs& a, hipStream_t stream) {
   ResArgs b = a;
@@ -1452,7 +1807,14 @@ hipError_t launch_res(K kernel, size_t lds, int own, int g, const ResArgs& a, hi
 
 }  // namespace
 
-size_t resident_xchg_bytes(int C, int nmem) { return 2 * (size_t)nmem * 2 * C * sizeof(u64); }
+int resident_bands(int kind, int C, int MID, int H, int W) {
+  return (kind == 1 && C == 64 && MID == 16 && H == 32 && W == BAND_W && H % BAND_ROWS == 0) ? H / BAND_ROWS : 1;
+}
+
+size_t resident_xchg_bytes(int C, int nmem, int bands) {
+  if (bands > 1) return 2 * (size_t)nmem * bands * BAND_RW * sizeof(u64);
+  return 2 * (size_t)nmem * 2 * C * sizeof(u64);
+}
 
 bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   const int P = H * W;
@@ -1461,6 +1823,7 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   if (H <= 0 || (W != 8 && W != 16 && W != 32) || P % 32) return false;
   if (nmem < 1 || nmem > 1024) return false;
   int own = 0;
+  if (const int nb = resident_bands(kind, C, MID, H, W); nb > 1) return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES;
   if (kind == 0) {   // basic blocks: C -> C -> C
     if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
     return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
@@ -1496,6 +1859,7 @@ hipError_t resident_prepare() {
                         reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* infer[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, true>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, true>),
                          reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, true>), reinterpret_cast<const void*>(k_bb_forward<32, 2, true, true>),
                          reinterpret_cast<const void*>(k_bb_forward<64, 1, false, true>)};
@@ -1505,6 +1869,14 @@ hipError_t resident_prepare() {
 }
 
 hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (const int nb = resident_bands(kind, C, MID, a.H, a.W); nb > 1) {   // one work-group per band of 8 image rows
+    const int nwg = a.nmem * nb;
+    if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(nwg)) return hipErrorInvalidValue;
+    ResArgs b = a;
+    b.ngroup = g;
+    k_band_forward<64, 16><<<dim3((unsigned)(nwg * g)), RES_NT, band_fwd_lds(nwg), stream>>>(b);
+    return hipGetLastError();
+  }
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {
@@ -1520,6 +1892,7 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
 
 // Inference forward of a run: the images are independent (no exchange), so any number of work-groups may queue.
 hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP || !a.running) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {
@@ -1534,6 +1907,7 @@ hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResA
 }
 
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
   ResWgArgs w{};
   w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
@@ -1559,6 +1933,7 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
 }
 
 hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
+  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {

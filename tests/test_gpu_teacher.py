@@ -63,6 +63,20 @@ def test_single_blocks_layerwise(gpu, oracle, mode):
         layerwise(oracle, spec, mode)
 
 
+def test_row_band_runs_layerwise(gpu, oracle):
+    """Runs of 64-16-16-64 bottlenecks at 32x32 (the first stage of ResNet-1001): each image is cut into four bands of
+    eight rows, one work-group each, and the rows next to a band travel with the BatchNorm records.  Three blocks, so
+    that every exchange of the loop runs; an odd number of images; one and several micro-batches per launch."""
+    blocks = tuple(W.Block(W.BOTTLENECK, 64, 16, 64, 1) for _ in range(3))
+    for b, m, grouped in ((8, 2, True), (3, 2, True), (5, 3, False)):
+        spec = W.PartitionSpec(name=f"bands-3x(64-16-64)@32x32-b{b}", in_h=32, in_w=32, in_c=64, blocks=blocks, microbatch=b,
+                               num_microbatches=m, seed=23)
+        layerwise(oracle, spec, "bf16", grouped=grouped)
+    spec = W.PartitionSpec(name="bands-3x(64-16-64)@32x32-level1", in_h=32, in_w=32, in_c=64, blocks=blocks, microbatch=4,
+                           num_microbatches=2, seed=23)
+    layerwise(oracle, spec, "bf16", fusion=1)
+
+
 def test_config1_resnet20_layerwise(gpu, oracle):
     for mode in ("bf16", "f32"):
         layerwise(oracle, W.config(1), mode, grouped=False)
