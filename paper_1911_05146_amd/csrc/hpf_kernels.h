@@ -162,8 +162,8 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem);   // k
 // every work-group takes a CU of its own and all of them must be resident together.
 int resident_max_group(int nmem);   // nmem: work-groups per micro-batch (images x bands)
 // Runs whose image does not fit one CU's LDS are cut into row bands, one work-group each (64-16-16-64 bottlenecks at
-// 32x32: 4 bands of 8 rows): bands per image of the shape, 1 = whole images.  Such runs have a forward launch only;
-// their backward pass and weight gradients go through the per-layer kernels.
+// 32x32: 4 bands of 8 rows): bands per image of the shape, 1 = whole images.  Such runs have a forward and a backward launch;
+// their weight gradients go through the grouped per-layer launch and inference through the per-layer kernels.
 int resident_bands(int kind, int C, int MID, int H, int W);
 size_t resident_xchg_bytes(int C, int nmem, int bands);
 hipError_t resident_prepare();   // once per process, outside stream capture: raises the kernels' LDS limits

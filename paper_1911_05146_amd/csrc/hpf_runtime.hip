@@ -512,7 +512,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         continue;
       }
       bool in_run = false;
-      for (const Plan::ResRun& r : P.runs) in_run = in_run || (r.bands == 1 && i >= r.first && i < r.first + r.count);   // band runs: forward launch only
+      for (const Plan::ResRun& r : P.runs) in_run = in_run || (r.bands == 1 && i >= r.first && i < r.first + r.count);   // band runs have no weight-gradient launch of their own
       for (int j = p.j0; j < p.j1; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
                            j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
@@ -1033,7 +1033,7 @@ void run_backward(Ctx& c) {
     if (P.d.has_head == 1) c.bn_bwd(P.head_bn, c.tab(P.head_x), tA, Ctx::none(), c.tab(grad_in_loc(P.bp.size())), M);
   }
   for (size_t ii = P.bp.size(); ii-- > 0;) {
-    if (c.h->resident() && P.run_end_at[ii] >= 0 && P.runs[P.run_end_at[ii]].bands == 1) {
+    if (c.h->resident() && P.run_end_at[ii] >= 0) {
       const Plan::ResRun& r = P.runs[P.run_end_at[ii]];
       c.res_backward(r);
       ii = (size_t)r.first;

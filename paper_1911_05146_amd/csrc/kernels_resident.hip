@@ -1423,7 +1423,7 @@ constexpr int BAND_ROWS = 8, BAND_W = 32, BAND_P = BAND_ROWS * BAND_W;   // 256 
 constexpr int BAND_PTW = BAND_P / 16 / RES_NWV;
 constexpr int BAND_HALO_F = BAND_W * 16 / 2;     // words of one row of 16 bf16 channels (two values per word)
 constexpr int BAND_HALO_B = BAND_W * 16;         // words of one row of 16 fp32 channels (backward)
-constexpr int BAND_RW = 2 * 16 + 2 * BAND_HALO_B;   // record width in words: the widest record (backward conv2 exchange), >= 2*64
+constexpr int BAND_RW = 2 * 16 + 2 * BAND_HALO_B;   // record width in words: the widest record (sums + two rows of dz, backward), >= 2*64
 static_assert(BAND_RW >= 2 * 64 && BAND_PTW == 2, "record width / tiles per wave");
 
 // Collects, from the records of all nwg members, the first ns words each into gath[m*ns + w], and nh words from
@@ -1754,6 +1754,251 @@ __global__ void __launch_bounds__(RES_NT) k_band_forward(const ResArgs a) {
   if (me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
+// BatchNorm + ReLU backward on a gradient tile in accumulator layout, for a band (cf. bn_relu_bwd_acc): records of
+// width BAND_RW, nwg members of BAND_P pixels each, any channel count from 16.  HALO: the band's first and last row
+// of dz (fp32, one word per value) travel with the sums, and halo[0 .. BAND_HALO_B) / halo[BAND_HALO_B ..) return
+// the last row of the member above / the first row of the member below (zeros where there is none).
+// g_beta / g_gamma (member 0 only, else null): the micro-batch sums are added to the parameter gradients.
+template <int Cc, bool HALO, class Fin>
+__device__ __forceinline__ bool band_bn_relu_bwd_acc(floatx4 (&dz)[BAND_PTW][Cc / 16], const uint2 (&xin)[BAND_PTW][Cc / 16], const float4* cf_,
+                                                     int wave, int fr, int fq, float* red, float4* tab_, float* gath, u64* slot, int me,
+                                                     int nwg, int up, int dn, uint32_t* halo, unsigned tag, float* g_beta, float* g_gamma,
+                                                     int* abort_flag, Fin&& fin) {
+  constexpr int NTL = Cc / 16, PTW = BAND_PTW;
+  static_assert(!HALO || Cc == 16, "halo rows are 16 channels wide");
+  const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(cf_, 16));
+  float4* tab = reinterpret_cast<float4*>(__builtin_assume_aligned(tab_, 16));
+  u64* rec = slot + (size_t)me * BAND_RW;
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) {
+    float4 k[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) k[e] = cf[nt * 16 + fq * 4 + e];
+    float sb[4] = {0.f, 0.f, 0.f, 0.f}, sg[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float v = elem4(xin[j][nt], e);
+        const float d = fmaf(v, k[e].x, k[e].y) > 0.f ? dz[j][nt][e] : 0.f;
+        dz[j][nt][e] = d;
+        sb[e] += d;
+        sg[e] = fmaf(d, fmaf(v, k[e].z, k[e].w), sg[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { sb[e] = sum16(sb[e]); sg[e] = sum16(sg[e]); }
+    if (fr == 0) {
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + nt * 16 + fq * 4) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + Cc + nt * 16 + fq * 4) = make_float4(sg[0], sg[1], sg[2], sg[3]);
+    }
+  }
+  if (HALO) {   // pixel tiles 0, 1 are the band's first row, tiles 14, 15 its last: word = pixel*16 + channel
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+      const bool first = pt < 2, last = pt >= BAND_P / 16 - 2;
+      if (first || last) {
+        const int px = (first ? pt : pt - (BAND_P / 16 - 2)) * 16 + fr;
+        u64* dst = rec + 2 * Cc + (last ? BAND_HALO_B : 0) + px * 16 + fq * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          __hip_atomic_store(dst + e, ((u64)tag << 32) | (u64)__float_as_uint(dz[j][0][e]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  __syncthreads();
+  for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RES_NWV; ++i) s += red[i * 2 * Cc + w];
+    __hip_atomic_store(rec + w, ((u64)tag << 32) | (u64)__float_as_uint(s), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (!band_collect(slot, nwg, 2 * Cc, tag, gath, HALO ? up : -1, HALO ? dn : -1, 2 * Cc + BAND_HALO_B, 2 * Cc, HALO ? BAND_HALO_B : 0, halo,
+                    abort_flag))
+    return false;
+  const float invM = 1.f / ((float)nwg * (float)BAND_P);
+  {
+    constexpr int CR = Cc >= 32 ? Cc / 32 : 1, MP = 16 / CR, ROWS = Cc / CR;
+    const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const bool act = row < ROWS;
+    const int c = act ? row * CR + l16 % CR : 0, part = l16 / CR;
+    float sb = 0.f, sg = 0.f;
+    for (int m = part; m < nwg; m += MP) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
+    sb = row_sum<CR>(sb);
+    sg = row_sum<CR>(sg);
+    if (act && part == 0) {
+      if (g_beta) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
+      const float4 k = cf[c];
+      tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) {
+    float4 t[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[e] = tab[nt * 16 + fq * 4 + e];
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      floatx4 out;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[e] = fmaf(t[e].x, dz[j][nt][e], fmaf(t[e].y, elem4(xin[j][nt], e), t[e].z));
+      fin(j, nt, out);
+    }
+  }
+  return true;
+}
+
+template <int C, int MID>
+__global__ void __launch_bounds__(RES_NT) k_band_backward(const ResArgs a) {
+  static_assert(C == 64 && MID == 16, "the shape of ResNet-1001's first stage");
+  constexpr int XS = C + 8, MS = MID + 8, P = BAND_P, PTW = BAND_PTW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int nb = a.H / BAND_ROWS, nwg = a.nmem * nb;
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  const int band = me % nb;
+  const int up = band > 0 ? me - 1 : -1, dn = band + 1 < nb ? me + 1 : -1;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);              // gradient of the residual stream of the band, [P][XS]
+  bf16_t* sm2 = sdy + (size_t)P * XS;                         // dc1, [P][MS]
+  bf16_t* sdc = sm2 + (size_t)P * MS;                         // dc2 with one halo row above and below, [10*32][MS]
+  float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)(P + 2 * BAND_W) * MS);
+  float4* cf2 = cf1 + C;
+  float4* cf3 = cf2 + MID;
+  float* red = reinterpret_cast<float*>(cf3 + MID);           // RES_NWV * 2*C floats
+  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);   // C float4
+  float* gath = reinterpret_cast<float*>(tab + C);            // nwg * 2*C floats
+  uint32_t* halo = reinterpret_cast<uint32_t*>(gath + (size_t)nwg * 2 * C);   // 2 * BAND_HALO_B words
+  bf16_t* bandD = sdc + BAND_W * MS;                          // the band's own rows of the dc2 tile
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * nwg * BAND_RW; };
+
+  WFrags<C / 32, 1, true> w3;     // conv3 data gradient [MID][C]
+  WFrags<5, 1, true> w2;          // conv2 data gradient [MID][160]
+  WFrags<1, C / 16, true> w1;     // conv1 data gradient [C][32], k >= MID zero
+  {
+    const ResBlock BL = a.blocks[a.nblk - 1];
+    tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+  }
+  __syncthreads();
+  for (int bi = a.nblk - 1; bi >= 0; --bi) {
+    const ResBlock B = a.blocks[bi];
+    float* const g_b[3] = {me == 0 ? a.grads + B.beta_off[0] : nullptr, me == 0 ? a.grads + B.beta_off[1] : nullptr,
+                           me == 0 ? a.grads + B.beta_off[2] : nullptr};
+    float* const g_g[3] = {a.grads + B.gamma_off[0], a.grads + B.gamma_off[1], a.grads + B.gamma_off[2]};
+    uint2 xc1[PTW][1], xc2[PTW][1];   // c1 / c2 at this lane's accumulator positions
+    // ---- conv3 data gradient, then BN3 + ReLU backward -> dc2 (with the neighbours' rows next to the band)
+    floatx4 acc3[PTW][1];
+    // c2 at the halo positions (two values per thread: word w = row*512 + pixel*16 + channel), asked for up front
+    bf16_t hx[2];
+    {
+      BwdLoads<C, MID, PTW> ld;
+      w3.load(a.packed + B.wd_off[2], C, fr, fk);
+      ld.issue(B, cx, a.params, me, P, P >> 4, wave, fr, fq);
+      const bf16_t* g2 = cx.tensor(B.c2_off) + (size_t)me * P * MID;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int w = tid + q * RES_NT, below = w >> 9, px = (w >> 4) & (BAND_W - 1), ch = w & 15;
+        const bool have = below ? dn >= 0 : up >= 0;
+        const long off = have ? ((long)(below ? P : -BAND_W) + px) * MID + ch : 0;   // the neighbour's row sits right next to the band
+        hx[q] = g2[off];
+      }
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) acc3[j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < C / 32; ++ks) {
+#pragma unroll
+        for (int j = 0; j < PTW; ++j) {
+          const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + ks * 32 + fk);
+          acc3[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.get(ks, 0), bfrag, acc3[j][0], 0, 0, 0);
+        }
+      }
+      ld.commit_tables(cf1, cf2, cf3);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) { xc1[j][0] = ld.x1[j][0]; xc2[j][0] = ld.x2[j][0]; }
+    }
+    __syncthreads();
+    w2.load(a.packed + B.wd_off[1], 160, fr, fk);
+    if (!band_bn_relu_bwd_acc<MID, true>(acc3, xc2, cf3, wave, fr, fq, red, tab, gath, slot(), me, nwg, up, dn, halo, tag0 + 1u + phase,
+                                         g_b[2], g_g[2], a.abort_flag, [&](int j, int, const floatx4& out) {
+                                           *reinterpret_cast<uint2*>(bandD + ((wave + j * RES_NWV) * 16 + fr) * MS + fq * 4) = pack4(out);
+                                         }))
+      return;
+    ++phase;
+    // the neighbours' rows of dc2: the same map applied to their dz and their c2 (tab is complete: barrier inside)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int w = tid + q * RES_NT, below = w >> 9, px = (w >> 4) & (BAND_W - 1), ch = w & 15;
+      const bool have = below ? dn >= 0 : up >= 0;
+      const float4 t = tab[ch];
+      const float v = fmaf(t.x, __uint_as_float(halo[w]), fmaf(t.y, bf16_to_f32(hx[q]), t.z));
+      sdc[((below ? BAND_ROWS + 1 : 0) * BAND_W + px) * MS + ch] = have ? f32_to_bf16(v) : (bf16_t)0;
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, bandD, P);
+    // ---- conv2 data gradient, BN2 + ReLU backward -> dc1
+    uint2 x1[PTW][C / 16];   // the block input at this lane's accumulator positions, for the BN1 backward below
+    {
+      floatx4 acc[PTW][1];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) acc[j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+      {
+        const bf16_t* xg = cx.tensor(B.x_off) + (size_t)me * P * C;
+#pragma unroll
+        for (int j = 0; j < PTW; ++j)
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt)
+            x1[j][nt] = *reinterpret_cast<const uint2*>(xg + (size_t)((wave + j * RES_NWV) * 16 + fr) * C + nt * 16 + fq * 4);
+      }
+      band_conv3x3<true>(sdc, w2, wave, fr, fq, acc);
+      w1.load(a.packed + B.wd_off[0], 32, fr, fk);
+      if (!band_bn_relu_bwd_acc<MID, false>(acc, xc1, cf2, wave, fr, fq, red, tab, gath, slot(), me, nwg, -1, -1, halo, tag0 + 1u + phase,
+                                            g_b[1], g_g[1], a.abort_flag, [&](int j, int, const floatx4& out) {
+                                              *reinterpret_cast<uint2*>(sm2 + ((wave + j * RES_NWV) * 16 + fr) * MS + fq * 4) = pack4(out);
+                                            }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<MID>(cx.tensor(B.dc1_off) + (size_t)me * P * MID, sm2, P);
+    // ---- conv1 data gradient (half-empty step), BN1 + ReLU backward, plus the shortcut: dx = bn1_bwd(...) + dy over dy
+    {
+      floatx4 acc[PTW][C / 16];
+      bf16x8 bfrag[PTW];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(sm2 + ((wave + j * RES_NWV) * 16 + fr) * MS + (fk & (MID - 1)));
+        bfrag[j] = fq < 2 ? v : frag_zero();
+      }
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt)
+#pragma unroll
+        for (int j = 0; j < PTW; ++j)
+          acc[j][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1.get(0, nt), bfrag[j], floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+      if (!band_bn_relu_bwd_acc<C, false>(acc, x1, cf1, wave, fr, fq, red, tab, gath, slot(), me, nwg, -1, -1, halo, tag0 + 1u + phase, g_b[0],
+                                          g_g[0], a.abort_flag, [&](int j, int nt, const floatx4& out) {
+                                            uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
+                                            const uint2 d = *q;
+                                            floatx4 v = out;
+                                            v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
+                                            *q = pack4(v);
+                                          }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
 size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
   const size_t tile = (size_t)P * (C + 8) * 2;
   const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16
@@ -1791,6 +2036,11 @@ size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
 constexpr size_t RES_LDS_BYTES = 160 * 1024 - 1024;   // LDS of a gfx950 CU, less room for the kernels' static allocations
 
 // row-band kernels (64-16 blocks at 32x32): tiles, coefficient tables, reduction and gather areas, halo words
+size_t band_bwd_lds(int nwg) {
+  const int C = 64, MID = 16;
+  return (size_t)BAND_P * (C + 8) * 2 + (size_t)(2 * BAND_P + 2 * BAND_W) * (MID + 8) * 2 + (size_t)(C + 2 * MID) * 16 +
+         (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16 + (size_t)nwg * 2 * C * 4 + (size_t)2 * BAND_HALO_B * 4;
+}
 size_t band_fwd_lds(int nwg) {
   const int C = 64, MID = 16;
   return (size_t)BAND_P * (C + 8) * 2 + (size_t)(2 * BAND_P + 2 * BAND_W) * (MID + 8) * 2 + (size_t)(C + MID) * 8 +
@@ -1823,7 +2073,8 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   if (H <= 0 || (W != 8 && W != 16 && W != 32) || P % 32) return false;
   if (nmem < 1 || nmem > 1024) return false;
   int own = 0;
-  if (const int nb = resident_bands(kind, C, MID, H, W); nb > 1) return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES;
+  if (const int nb = resident_bands(kind, C, MID, H, W); nb > 1)
+    return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES && band_bwd_lds(nmem * nb) <= RES_LDS_BYTES;
   if (kind == 0) {   // basic blocks: C -> C -> C
     if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
     return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
@@ -1860,6 +2111,7 @@ hipError_t resident_prepare() {
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_backward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* infer[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, true>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, true>),
                          reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, true>), reinterpret_cast<const void*>(k_bb_forward<32, 2, true, true>),
                          reinterpret_cast<const void*>(k_bb_forward<64, 1, false, true>)};
@@ -1892,7 +2144,7 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
 
 // Inference forward of a run: the images are independent (no exchange), so any number of work-groups may queue.
 hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
+  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward and backward launches only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP || !a.running) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {
@@ -1907,7 +2159,7 @@ hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResA
 }
 
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
+  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward and backward launches only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
   ResWgArgs w{};
   w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
@@ -1933,7 +2185,14 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
 }
 
 hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
-  if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward launch only
+  if (const int nb = resident_bands(kind, C, MID, a.H, a.W); nb > 1) {
+    const int nwg = a.nmem * nb;
+    if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(nwg)) return hipErrorInvalidValue;
+    ResArgs b = a;
+    b.ngroup = g;
+    k_band_backward<64, 16><<<dim3((unsigned)(nwg * g)), RES_NT, band_bwd_lds(nwg), stream>>>(b);
+    return hipGetLastError();
+  }
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {
