@@ -437,6 +437,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   if (P.dt == DT_BF16 && d.bn_mode == 0) {
     auto eligible = [&](int i) {
       const BlockPlan& p = P.bp[i];
+      if (p.d.kind == K_POSTACT)   // post-activation basic block with identity shortcut
+        return p.d.stride == 1 && !p.proj && p.d.c_in == p.d.c_mid && resident_shape_ok(2, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
       return p.residual() && p.whole() && p.d.stride == 1 && !p.proj && resident_shape_ok(p.d.kind, p.d.c_in, p.d.c_mid, p.h_in, p.w_in, d.microbatch);
     };
     int cmax_run = 0;
@@ -465,7 +467,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         ResBlock rb{};
         rb.x_off = res_loc(p.x_in); rb.c1_off = res_loc(p.c[0]); rb.y_off = res_loc(p.y);
         rb.gy_off = res_loc(p.gy); rb.dc1_off = res_loc(p.dc[0]);
-        if (p.nconv == 3) { rb.c2_off = res_loc(p.c[1]); rb.dc2_off = res_loc(p.dc[1]); }
+        if (p.nconv == 3 || p.d.kind == K_POSTACT) { rb.c2_off = res_loc(p.c[1]); rb.dc2_off = res_loc(p.dc[1]); }
         Loc gx; gx.kind = CALLER_ERR_OUT;
         if (k > 0) gx = P.bp[k - 1].gy; else if (d.has_stem) gx = P.g_stem;
         rb.gx_off = res_loc(gx);
@@ -504,7 +506,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       if (!p.residual()) {   // the operands are stored activations (no BatchNorm to recompute)
         if (p.d.kind == K_POSTACT) {
           wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
-          wc.push_back(WConv{&p.cv[1], p.cv[1].cin, p.cv[1].cin, p.cv[1].R, p.a[0], p.dc[1], nullptr, false});
+          wc.push_back(WConv{&p.cv[1], p.cv[1].cin, p.cv[1].cin, p.cv[1].R, p.c[0], p.dc[1], &p.bn[0], false});   // relu(bn1(c1)) recomputed: a resident run does not write it
           if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.dc[2], nullptr, false});
         } else if (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) {
           wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
@@ -512,7 +514,8 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         continue;
       }
       bool in_run = false;
-      for (const Plan::ResRun& r : P.runs) in_run = in_run || (r.bands == 1 && i >= r.first && i < r.first + r.count);   // band runs have no weight-gradient launch of their own
+      for (const Plan::ResRun& r : P.runs)   // runs without a weight-gradient launch of their own stay in the grouped launch
+        in_run = in_run || (resident_has_wgrad_launch(r.kind, r.bands) && i >= r.first && i < r.first + r.count);
       for (int j = p.j0; j < p.j1; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
                            j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
@@ -832,7 +835,8 @@ struct Ctx {
   }
   // algorithmic figures of a run per image: every stashed tensor once (elements), contraction flop of one direction
   static void res_figures(const Plan::ResRun& r, double px, double* stash_elems, double* flops) {
-    if (r.kind == 0) { *stash_elems = px * 2.0 * r.C; *flops = 2.0 * px * 2.0 * 9.0 * r.C * r.C; }
+    if (r.kind == 2) { *stash_elems = px * 3.0 * r.C; *flops = 2.0 * px * 2.0 * 9.0 * r.C * r.C; }
+    else if (r.kind == 0) { *stash_elems = px * 2.0 * r.C; *flops = 2.0 * px * 2.0 * 9.0 * r.C * r.C; }
     else { *stash_elems = px * (2.0 * r.MID + r.C); *flops = 2.0 * px * (2.0 * r.C * r.MID + 9.0 * r.MID * r.MID); }
   }
   void res_forward(const Plan::ResRun& r) {
@@ -904,11 +908,16 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
     }
   }
   for (size_t bi = 0; bi < P.bp.size(); ++bi) {
-    if (resident && P.run_at[bi] >= 0 && !(c.inference && P.runs[P.run_at[bi]].bands > 1)) {   // the whole run in one launch; it takes its own statistics
+    if (resident && P.run_at[bi] >= 0 &&
+        !(c.inference && !resident_has_wgrad_launch(P.runs[P.run_at[bi]].kind, P.runs[P.run_at[bi]].bands))) {   // the whole run in one launch; it takes its own statistics
       const Plan::ResRun& r = P.runs[P.run_at[bi]];
       if (c.inference) c.res_inference(r);
       else c.res_forward(r);
       bi += r.count - 1;
+      if (const BlockPlan& pl = P.bp[bi]; pl.copy_out) {   // the partition's last unit keeps its output for the backward pass
+        Loc lo; lo.kind = CALLER_ACT_OUT;
+        c.copy(c.tab(lo), c.tab(pl.y), b * pl.h_out * pl.w_out * pl.d.c_out * P.esz);
+      }
       part_rows = 0;
       continue;
     }
@@ -1133,7 +1142,7 @@ void run_backward(Ctx& c) {
     const bool res = c.h->resident();
     if (res)
       for (const Plan::ResRun& r : P.runs)
-        if (r.bands == 1) c.res_wgrad(r);
+        if (resident_has_wgrad_launch(r.kind, r.bands)) c.res_wgrad(r);
     for (int k = 0; k < WGRAD_CLASSES; ++k) {
       const std::vector<WgradItem>& items = res ? P.items_nr[k] : P.items[k];
       if (items.empty()) continue;
@@ -1795,6 +1804,11 @@ hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t te
     const BlockPlan& q = P.bp[unit];
     const size_t M_in = b * q.h_in * q.w_in, M_out = b * q.h_out * q.w_out;
     auto held = [&](int j) { return j >= q.j0 && j < q.j1; };
+    auto in_run = [&](int i) {
+      for (const Plan::ResRun& r : P.runs)
+        if (i >= r.first && i < r.first + r.count) return true;
+      return false;
+    };
     if (!q.residual()) {   // units of VGG-16 / ResNet-v1: input, output, the tensors in between, the boundary gradients
       const size_t n_in = M_in * q.d.c_in, n_out = (q.d.kind == K_DENSE ? b : M_out) * q.d.c_out;
       switch (tensor) {
@@ -1804,7 +1818,9 @@ hpf_status hpf_stash_read(hpf_partition* p, int32_t mb, int32_t unit, int32_t te
         case HPF_T_GY: loc = q.gy; need = n_out * P.esz; break;
         case HPF_T_GX: loc = grad_in(unit); need = n_in * P.esz; break;
         case HPF_T_C1: if (q.d.kind == K_POSTACT) { loc = q.c[0]; need = M_out * q.d.c_mid * P.esz; } break;
-        case HPF_T_A0: if (q.d.kind == K_POSTACT) { loc = q.a[0]; need = M_out * q.d.c_mid * P.esz; } break;
+        case HPF_T_A0:   // inside an image-resident run relu(bn1(c1)) never reaches memory
+          if (q.d.kind == K_POSTACT && !(p->resident() && (P.run_at[unit] >= 0 || in_run(unit)))) { loc = q.a[0]; need = M_out * q.d.c_mid * P.esz; }
+          break;
         case HPF_T_C2: if (q.d.kind == K_POSTACT) { loc = q.c[1]; need = M_out * q.d.c_out * P.esz; } break;
         case HPF_T_SC: if (q.d.kind == K_POSTACT) { loc = q.sc; need = M_out * q.d.c_out * P.esz; } break;
         case HPF_T_STATS0: if (q.d.kind == K_POSTACT || q.d.kind == K_BN_RELU) stats_of(q.bn[0]); break;

@@ -1406,6 +1406,330 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
                      a.grads + B.w_off[1], smem);
 }
 
+// ------------------------------------------------------------------------------------------ post-activation blocks
+// The same ownership for runs of post-activation basic blocks with identity shortcut (ResNet-v1, paper Section
+// "Model-Parallelism on a Single Node": ResNet-110-v1):
+//   c1 = conv1(x); a1 = relu(bn1(c1)); c2 = conv2(a1); y = relu(bn2(c2) + x).
+// x is the stored output of the block before, so conv1 reads it as it is and nothing is exchanged ahead of the first
+// block; two exchanges per block and direction (statistics of c1 and c2; sums of the two BatchNorm backward passes).
+// Backward: dz = dy*[y > 0] is the gradient of the shortcut and, through BN2's backward (no ReLU of its own), of c2.
+// ResBlock fields used: x, c1, c2, y, gy, dc1, dc2, gx and entries 0 / 1 of the per-BatchNorm / per-convolution arrays.
+// The weight gradients of such runs go through the grouped per-layer launch, inference through the per-layer kernels.
+
+// y = relu(c2*scale + shift + x), tile to tile (written over x)
+template <int Cc>
+__device__ __forceinline__ void tile_join_relu(bf16_t* sx, const bf16_t* sc2, const float2* coef, int P) {
+  constexpr int U = Cc / 8;
+  for (int u = threadIdx.x; u < P * U; u += RES_NT) {
+    const int row = u / U, col = u - row * U;
+    uint4* q = reinterpret_cast<uint4*>(sx + row * (Cc + 8) + col * 8);
+    const uint4 xv = *q, cv = *reinterpret_cast<const uint4*>(sc2 + row * (Cc + 8) + col * 8);
+    const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, cw[4] = {cv.x, cv.y, cv.z, cv.w};
+    const float4* cf = reinterpret_cast<const float4*>(coef + col * 8);
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 k = cf[i];
+      r[i] = pack_bf16x2(fmaxf(fmaf(bf_lo(cw[i]), k.x, k.y) + bf_lo(xw[i]), 0.f), fmaxf(fmaf(bf_hi(cw[i]), k.z, k.w) + bf_hi(xw[i]), 0.f));
+    }
+    *q = make_uint4(r[0], r[1], r[2], r[3]);
+  }
+}
+
+template <int C, int PTW, bool PRE>
+__global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sx = reinterpret_cast<bf16_t*>(smem);           // block input, then block output, [P][XS]
+  bf16_t* sB = sx + (size_t)P * XS;                       // c1, then relu(bn1(c1))
+  bf16_t* sC = sB + (size_t)P * XS;                       // c2
+  float2* coef = reinterpret_cast<float2*>(sC + (size_t)P * XS);
+  float* red = reinterpret_cast<float*>(coef + C);        // RES_NWV * 2*C floats
+  float* own = red + RES_NWV * 2 * C;
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+  WFrags<9 * C / 32, C / 16, PRE> w1, w2;
+
+  auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+      if (pt < npt)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt)
+          *reinterpret_cast<uint2*>(dst + (pt * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+    }
+  };
+  {
+    const ResBlock B0 = a.blocks[0];
+    tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
+    w1.load(a.packed + B0.wf_off[0], 9 * C, fr, fk);
+    __syncthreads();
+  }
+  for (int bi = 0; bi < a.nblk; ++bi) {
+    const ResBlock B = a.blocks[bi];
+    {   // ---- conv1 (3x3) on x
+      floatx4 acc[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, false>(sx, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      store_acc(sB, acc);
+    }
+    w2.load(a.packed + B.wf_off[1], 9 * C, fr, fk);
+    __syncthreads();
+    {
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sC);   // c2 of the block before has been consumed
+      stats_publish<C>(sB, P, red, slot(), me, tag0 + 1u + phase);
+      tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
+      if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
+      ++phase;
+      merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[0], a.params + B.beta_off[0], coef,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[0]) : nullptr);
+    }
+    tile_bn_relu<C>(sB, coef, P);
+    __syncthreads();
+    {   // ---- conv2 (3x3) on relu(bn1(c1))
+      floatx4 acc[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, false>(sB, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      store_acc(sC, acc);
+    }
+    if (bi + 1 < a.nblk) w1.load(a.packed + a.blocks[bi + 1].wf_off[0], 9 * C, fr, fk);
+    __syncthreads();
+    {
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sB);   // conv2 has read relu(bn1(c1)): barrier above
+      stats_publish<C>(sC, P, red, slot(), me, tag0 + 1u + phase);
+      tile_store<C>(cx.tensor(B.c2_off) + (size_t)me * P * C, sC, P);
+      if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
+      ++phase;
+      merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
+                    me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+    }
+    tile_join_relu<C>(sx, sC, coef, P);
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.y_off) + (size_t)me * P * C, sx, P);
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
+// BatchNorm backward on a gradient tile in accumulator layout (cf. bn_relu_bwd_acc), for the two BatchNorms of a
+// post-activation block.  JOIN = false: BN + ReLU backward, the mask recomputed from the BatchNorm input xin.
+// JOIN = true: the ReLU sits behind the shortcut add, so the mask is [y > 0] with y = ysrc the stored block output;
+// dz is left masked in place (it is also the gradient of the shortcut) and the BatchNorm itself has no ReLU.
+// g_beta / g_gamma (member 0 only, else null): the micro-batch sums are added to the parameter gradients.
+template <int Cc, int PTW, bool JOIN, class Fin>
+__device__ __forceinline__ bool v1_bn_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const uint2 (&ysrc)[PTW][Cc / 16],
+                                              const float4* cf_, int npt, int wave, int fr, int fq, float* red, float4* tab_, float* gath,
+                                              u64* slot, int me, int nmem, int P, unsigned tag, float* g_beta, float* g_gamma,
+                                              int* abort_flag, Fin&& fin) {
+  constexpr int NTL = Cc / 16;
+  const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(cf_, 16));
+  float4* tab = reinterpret_cast<float4*>(__builtin_assume_aligned(tab_, 16));
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) {
+    float4 k[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) k[e] = cf[nt * 16 + fq * 4 + e];
+    float sb[4] = {0.f, 0.f, 0.f, 0.f}, sg[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      if (wave + j * RES_NWV < npt) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v = elem4(xin[j][nt], e);
+          const bool on = JOIN ? elem4(ysrc[j][nt], e) > 0.f : fmaf(v, k[e].x, k[e].y) > 0.f;
+          const float d = on ? dz[j][nt][e] : 0.f;
+          dz[j][nt][e] = d;
+          sb[e] += d;
+          sg[e] = fmaf(d, fmaf(v, k[e].z, k[e].w), sg[e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { sb[e] = sum16(sb[e]); sg[e] = sum16(sg[e]); }
+    if (fr == 0) {
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + nt * 16 + fq * 4) = make_float4(sb[0], sb[1], sb[2], sb[3]);
+      *reinterpret_cast<float4*>(red + wave * 2 * Cc + Cc + nt * 16 + fq * 4) = make_float4(sg[0], sg[1], sg[2], sg[3]);
+    }
+  }
+  __syncthreads();
+  for (int w = threadIdx.x; w < 2 * Cc; w += RES_NT) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RES_NWV; ++i) s += red[i * 2 * Cc + w];
+    publish_word(slot, me, 2 * Cc, w, s, tag);
+  }
+  if (!collect<4, true>(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
+  const float invM = 1.f / ((float)nmem * (float)P);
+  {
+    constexpr int CR = Cc / 32, MP = 16 / CR;
+    const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const int c = row * CR + l16 % CR, part = l16 / CR;
+    float sb = 0.f, sg = 0.f;
+    for (int m = part; m < nmem; m += MP) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
+    sb = row_sum<CR>(sb);
+    sg = row_sum<CR>(sg);
+    if (part == 0) {
+      if (g_beta) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
+      const float4 k = cf[c];
+      tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) {
+    float4 t[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[e] = tab[nt * 16 + fq * 4 + e];
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      if (wave + j * RES_NWV < npt) {
+        floatx4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = fmaf(t[e].x, dz[j][nt][e], fmaf(t[e].y, elem4(xin[j][nt], e), t[e].z));
+        fin(j, nt, out);
+      }
+    }
+  }
+  return true;
+}
+
+template <int C, int PTW, bool PRE>
+__global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const int gath_own) {
+  constexpr int XS = C + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+  const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
+  const int P = a.H * a.W, npt = P >> 4;
+  const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
+  ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
+  u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
+  unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
+  const unsigned tag0 = *tagp;
+  unsigned phase = 0;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient w.r.t. the block output, then w.r.t. its input
+  bf16_t* sdc = sdy + (size_t)P * XS;                     // dc2, then dc1
+  float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * XS);
+  float4* cf2 = cf1 + C;
+  float* red = reinterpret_cast<float*>(cf2 + C);         // RES_NWV * 2*C floats
+  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);
+  float* own = reinterpret_cast<float*>(tab + C);
+  auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
+  WFrags<9 * C / 32, C / 16, PRE> w2, w1;   // data-gradient operands [C][9*C]
+
+  auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
+#pragma unroll
+    for (int j = 0; j < PTW; ++j) {
+      const int pt = wave + j * RES_NWV;
+      const size_t row = (size_t)((pt < npt ? pt : 0) * 16 + fr) * C + fq * 4;   // always a valid address
+#pragma unroll
+      for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = *reinterpret_cast<const uint2*>(g + row + nt * 16);
+    }
+  };
+  {
+    const ResBlock BL = a.blocks[a.nblk - 1];
+    tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+  }
+  for (int bi = a.nblk - 1; bi >= 0; --bi) {
+    const ResBlock B = a.blocks[bi];
+    float* const gb1 = me == 0 ? a.grads + B.beta_off[0] : nullptr;
+    float* const gb2 = me == 0 ? a.grads + B.beta_off[1] : nullptr;
+    uint2 xc1[PTW][C / 16], xc2[PTW][C / 16], yv[PTW][C / 16];
+    floatx4 dzs[PTW][C / 16];   // dy*[y > 0]: the gradient of the shortcut, added to the input gradient at the end
+    {   // one round trip to memory for everything the block reads up front
+      at_acc(cx.tensor(B.y_off) + (size_t)me * P * C, yv);
+      at_acc(cx.tensor(B.c2_off) + (size_t)me * P * C, xc2);
+      at_acc(cx.tensor(B.c1_off) + (size_t)me * P * C, xc1);
+      const int c = tid < C ? tid : 0;
+      const float4 t1 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[0]), a.params + B.gamma_off[0],
+                                              a.params + B.beta_off[0], c, C);
+      const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
+                                              a.params + B.beta_off[1], c, C);
+      w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
+      if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
+    }
+    __syncthreads();   // the tables; and (first block) the gradient tile
+    {   // ---- through the join and BN2: dz = dy*[y > 0] -> dc2
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) {
+          const uint2 d = pt < npt ? *reinterpret_cast<const uint2*>(sdy + (pt * 16 + fr) * XS + nt * 16 + fq * 4) : make_uint2(0u, 0u);
+          dzs[j][nt] = floatx4{bf_lo(d.x), bf_hi(d.x), bf_lo(d.y), bf_hi(d.y)};
+        }
+      }
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
+      if (!v1_bn_bwd_acc<C, PTW, true>(dzs, xc2, yv, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase, gb2,
+                                       a.grads + B.gamma_off[1], a.abort_flag, [&](int j, int nt, const floatx4& out) {
+                                         *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(out);
+                                       }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.dc2_off) + (size_t)me * P * C, sdc, P);
+    {   // ---- conv2 data gradient, BN1 + ReLU backward -> dc1 (over dc2)
+      floatx4 acc[PTW][C / 16];
+      uint2 xin[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+      conv3x3_tile<C, PTW, true>(sdc, w2, a.H, a.W, npt, wave, fr, fk, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
+      w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
+      // every wave is past its reads of dc2 at the first barrier inside; the results are written behind the last one
+      float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
+      if (!v1_bn_bwd_acc<C, PTW, false>(acc, xin, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase, gb1,
+                                        a.grads + B.gamma_off[0], a.abort_flag, [&](int j, int nt, const floatx4& out) {
+                                          *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(out);
+                                        }))
+        return;
+      ++phase;
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.dc1_off) + (size_t)me * P * C, sdc, P);
+    {   // ---- conv1 data gradient plus the shortcut: dx = conv1^T(dc1) + dz, written over dy
+      floatx4 acc[PTW][C / 16];
+#pragma unroll
+      for (int j = 0; j < PTW; ++j)
+#pragma unroll
+        for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = dzs[j][nt];
+      conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        const int pt = wave + j * RES_NWV;
+        if (pt < npt)
+#pragma unroll
+          for (int nt = 0; nt < C / 16; ++nt)
+            *reinterpret_cast<uint2*>(sdy + (pt * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
+      }
+    }
+    __syncthreads();
+    tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
+  }
+  if (me == 0 && tid == 0) *tagp = tag0 + phase;
+}
+
 // ------------------------------------------------------------------------------------------ row bands
 // Runs of identity bottleneck blocks whose image does not fit one CU's LDS (ResNet-1001's first stage: 64-16-16-64
 // channels at 32x32, 128 KiB of residual stream per image): the image is cut into bands of BAND_ROWS image rows and
@@ -2075,6 +2399,10 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   int own = 0;
   if (const int nb = resident_bands(kind, C, MID, H, W); nb > 1)
     return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES && band_bwd_lds(nmem * nb) <= RES_LDS_BYTES;
+  if (kind == 2) {   // post-activation basic blocks: the same tiles as the pre-activation ones, no weight-gradient launch
+    if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
+    return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES;
+  }
   if (kind == 0) {   // basic blocks: C -> C -> C
     if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
     return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
@@ -2110,6 +2438,10 @@ hipError_t resident_prepare() {
                         reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
+                      reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>)};
+  for (const void* f : v1)
+    if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_backward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* infer[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, true>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, true>),
@@ -2131,6 +2463,11 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   }
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
+  if (kind == 2) {
+    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 32) return launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
+    return launch_res(k_v1_forward<64, 1, false>, lds, own, g, a, stream);
+  }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
     if (C == 32) return launch_res(k_bb_forward<32, 2, true>, lds, own, g, a, stream);
@@ -2145,6 +2482,7 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
 // Inference forward of a run: the images are independent (no exchange), so any number of work-groups may queue.
 hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
   if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward and backward launches only
+  if (kind == 2) return hipErrorInvalidValue;   // post-activation runs: forward and backward launches only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP || !a.running) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 0) {
@@ -2160,6 +2498,7 @@ hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResA
 
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
   if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward and backward launches only
+  if (kind == 2) return hipErrorInvalidValue;   // post-activation runs: forward and backward launches only
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
   ResWgArgs w{};
   w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
@@ -2195,6 +2534,11 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   }
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
+  if (kind == 2) {
+    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
+    if (C == 32) return launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
+    return launch_res(k_v1_backward<64, 1, false>, lds, own, g, a, stream);
+  }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
     if (C == 32) return launch_res(k_bb_backward<32, 2, true>, lds, own, g, a, stream);
