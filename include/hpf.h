@@ -71,7 +71,8 @@ typedef enum {
  *   Shortcut: identity if stride == 1 and c_in == c_out, else a 1x1 convolution (same stride) of the
  *   block's first bn-relu output.  3x3 convolutions use symmetric zero padding 1; no conv bias.
  * Units of the paper's two other models (Section "Model-Parallelism on a Single Node": ResNet-110-v1, VGG-16);
- * they run as plain per-layer launches at every fusion level, cannot be cut inside, and keep every intermediate:
+ * they cannot be cut inside and, except inside the runs of hpf_partition_set_fusion level 2, run as per-layer
+ * launches that keep every intermediate:
  *   kind 2 (post-activation basic block): y = relu(bn2(conv3x3(relu(bn1(conv3x3_stride(x))))) + shortcut), c_mid == c_out;
  *           shortcut = x, or a 1x1 convolution (same stride, no BatchNorm) of x iff stride != 1 or c_in != c_out.
  *           Parameters: W1, bn1.gamma, bn1.beta, W2, bn2.gamma, bn2.beta, [Wproj].
@@ -216,10 +217,14 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *   2  (default) additionally, runs of consecutive blocks of one shape with stride 1 and identity
  *      shortcut -- bottleneck 128->32->32->128 or 128->64->64->128 channels at up to 256 pixels or 256->64->64->256 at
  *      up to 128; basic (two 3x3 convolutions) with 32 channels at up to 256 pixels or 64 at up to
- *      128; image width 8, 16 or 32, pixel count a multiple of 32 -- run
+ *      128; post-activation basic (kind 2) of the same two shapes; image width 8, 16 or 32, pixel count a
+ *      multiple of 32 -- run
  *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per
- *      image, all of them on the chip together.  Needs microbatch <= number of CUs; a group call
- *      then processes floor(CUs / microbatch) micro-batches (at most 8) per launch, and launches
+ *      image, all of them on the chip together.  Bottleneck 64->16->16->64 at 32 x 32 pixels, whose image
+ *      does not fit, runs the same way with each image cut into four bands of eight rows, one work-group
+ *      per band (the image rows next to a band travel with the BatchNorm records).  Needs
+ *      microbatch (x 4 for banded runs) <= number of CUs; a group call
+ *      then processes floor(CUs / that) micro-batches (at most 8) per launch, and launches
  *      of this kind from all streams and partitions of the process are serialised through events
  *      recorded at call time.  A stream that the CALLER is capturing into a graph cannot take part
  *      in that: forward / backward calls on such a stream return HPF_EUNSUPPORTED at level 2 when the
@@ -256,8 +261,9 @@ hpf_status hpf_partition_set_fusion(hpf_partition* p, int32_t level);
  * hpf_forward_inference_group: the same for `count` micro-batches (1 .. min(num_microbatches, 8)) in one call,
  *   every layer launched once for all of them; arguments are (host) arrays of `count` (dev) pointers, the skip
  *   arrays NULL exactly when the single-call arguments would be.
- *   At fusion level 2 the runs of blocks described there go through inference variants of the same kernels
- *   (one work-group per image; nothing is exchanged, so these launches are not serialised). */
+ *   At fusion level 2 the runs of pre-activation blocks with whole images per work-group go through inference
+ *   variants of the same kernels (nothing is exchanged, so these launches are not serialised); banded runs and
+ *   runs of kind-2 blocks use the per-layer kernels. */
 hpf_status hpf_partition_set_bn_momentum(hpf_partition* p, float momentum);
 hpf_status hpf_bn_running_read(hpf_partition* p, float* host_dst, size_t n_floats);
 hpf_status hpf_bn_running_write(hpf_partition* p, const float* host_src, size_t n_floats);
