@@ -47,6 +47,31 @@ __device__ __forceinline__ float block_reduce_sum(float v, float* sh) {
   return r;
 }
 
+// logits[j] = bias[j] + sum_c gs[c] * W[c][j] for one sample, all 256 threads at work whatever the class count: the
+// threads form CS slices over the channels x JT class lanes (JT = the power of two that covers min(classes, 256)),
+// every thread sums its channel slice for its classes and the slices are added in a fixed order through LDS.
+// part: 256 floats of LDS.  Ends with a barrier; lg[0 .. classes) is then complete.
+__device__ __forceinline__ void fc_logits(const float* gs, const float* __restrict__ wfc, const float* __restrict__ bfc, float* lg, float* part,
+                                          int C, int classes) {
+  int jt = 1;
+  while (jt < classes && jt < 256) jt <<= 1;
+  const int cs_n = 256 / jt, jl = threadIdx.x % jt, cs = threadIdx.x / jt;
+  for (int j0 = 0; j0 < classes; j0 += jt) {
+    const int j = j0 + jl;
+    float s = 0.f;
+    if (j < classes)
+      for (int c = cs; c < C; c += cs_n) s = fmaf(gs[c], wfc[(size_t)c * classes + j], s);
+    part[cs * jt + jl] = s;
+    __syncthreads();
+    if (cs == 0 && j < classes) {
+      float t = bfc[j];
+      for (int k = 0; k < cs_n; ++k) t += part[k * jt + jl];
+      lg[j] = t;
+    }
+    __syncthreads();
+  }
+}
+
 // One block per sample.  Dynamic LDS: C + classes floats.
 template <class T>
 __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __restrict__ wfc, const float* __restrict__ bfc,
@@ -58,6 +83,7 @@ __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __rest
   float* __restrict__ dlogits = (float*)pick(dls, blockIdx.z);
   extern __shared__ float dyn[];
   __shared__ float red[8];
+  __shared__ float part[256];
   float* gs = dyn;
   float* lg = dyn + C;
   const int n = blockIdx.x;
@@ -71,13 +97,9 @@ __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __rest
     g[(size_t)n * C + c] = s;
   }
   __syncthreads();
+  fc_logits(gs, wfc, bfc, lg, part, C, classes);
   float mx = -3.0e38f;
-  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
-    float s = bfc[j];
-    for (int c = 0; c < C; ++c) s = fmaf(gs[c], wfc[(size_t)c * classes + j], s);
-    lg[j] = s;
-    mx = fmaxf(mx, s);
-  }
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) mx = fmaxf(mx, lg[j]);
   mx = block_reduce_max(mx, red);
   float den = 0.f;
   for (int j = threadIdx.x; j < classes; j += blockDim.x) den += expf(lg[j] - mx);
@@ -88,14 +110,16 @@ __global__ __launch_bounds__(256) void k_head_fwd(PtrTab as, const float* __rest
   if (threadIdx.x == 0) atomicAdd(loss_accum, -(lg[y] - mx - logf(den)) * inv_div);
 }
 
-// Inference head, one block per sample: logits = mean_{h,w}(a) * Wfc + bfc.
+// Inference head, one block per sample: logits = mean_{h,w}(a) * Wfc + bfc.  Dynamic LDS: C + classes floats.
 template <class T>
 __global__ __launch_bounds__(256) void k_head_logits(PtrTab as, const float* __restrict__ wfc, const float* __restrict__ bfc,
                                                      PtrTab outs, int hw, int C, int classes) {
   const T* __restrict__ a = (const T*)pick(as, blockIdx.z);
   float* __restrict__ out = (float*)pick(outs, blockIdx.z);
   extern __shared__ float dyn[];
+  __shared__ float part[256];
   float* gs = dyn;
+  float* lg = dyn + C;
   const int n = blockIdx.x;
   const T* an = a + (size_t)n * hw * C;
   const float inv_hw = 1.0f / (float)hw;
@@ -105,11 +129,8 @@ __global__ __launch_bounds__(256) void k_head_logits(PtrTab as, const float* __r
     gs[c] = s * inv_hw;
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
-    float s = bfc[j];
-    for (int c = 0; c < C; ++c) s = fmaf(gs[c], wfc[(size_t)c * classes + j], s);
-    out[(size_t)n * classes + j] = s;
-  }
+  fc_logits(gs, wfc, bfc, lg, part, C, classes);
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) out[(size_t)n * classes + j] = lg[j];
 }
 
 // One block per sample: dWfc += g^T dlogits, dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw.
@@ -255,7 +276,7 @@ hipError_t launch_head_fwd(int dt, int ng, const PtrTab& a, const float* wfc, co
 
 hipError_t launch_head_logits(int dt, int ng, const PtrTab& a, const float* wfc, const float* bfc, const PtrTab& logits, int b,
                               int hw, int C, int classes, hipStream_t stream) {
-  const size_t lds = (size_t)C * sizeof(float);
+  const size_t lds = (size_t)(C + classes) * sizeof(float);
   const dim3 grid((unsigned)b, 1, (unsigned)ng);
   if (dt == DT_BF16) k_head_logits<bf16_t><<<grid, 256, lds, stream>>>(a, wfc, bfc, logits, hw, C, classes);
   else k_head_logits<float><<<grid, 256, lds, stream>>>(a, wfc, bfc, logits, hw, C, classes);
