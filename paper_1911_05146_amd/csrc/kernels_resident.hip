@@ -142,10 +142,11 @@ __device__ __forceinline__ bool collect(const u64* slot, int nmem, int nw, unsig
 template <int Cc>
 __device__ __forceinline__ void merge_coef(const float* gath, int nmem, int P, float eps, const float* gamma, const float* beta,
                                            float2* coef, float* stats_out) {
-  constexpr int CR = Cc / 32;        // channels per row
+  constexpr int CR = Cc >= 32 ? Cc / 32 : 1;   // channels per row (below 32 channels only the first Cc rows work)
   constexpr int MP = 16 / CR;        // member subsets per row
   const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
-  const int c = row * CR + l16 % CR, part = l16 / CR;
+  const bool act = row * CR < Cc;
+  const int c = act ? row * CR + l16 % CR : 0, part = l16 / CR;
   const float g = gamma[c], b = beta[c];
   float s = 0.f;
   for (int m = part; m < nmem; m += MP) s += gath[m * 2 * Cc + c];
@@ -158,7 +159,7 @@ __device__ __forceinline__ void merge_coef(const float* gath, int nmem, int P, f
     s2 += gath[m * 2 * Cc + Cc + c] + (float)P * d * d;
   }
   s2 = row_sum<CR>(s2);
-  if (part == 0) {
+  if (act && part == 0) {
     const float var = s2 * inv_n / (float)P;
     const float is = 1.0f / sqrtf(var + eps);
     coef[c] = bn_scale_shift(mean, is, g, b);
@@ -201,6 +202,7 @@ template <int KT, int NT, bool PRE>
 struct WFrags;
 template <int KT, int NT>
 struct WFrags<KT, NT, true> {
+  static constexpr bool pre = true;
   bf16x8 r[KT][NT];
   __device__ __forceinline__ void load(const bf16_t* w, int ld, int fr, int fk) {
 #pragma unroll
@@ -212,6 +214,7 @@ struct WFrags<KT, NT, true> {
 };
 template <int KT, int NT>
 struct WFrags<KT, NT, false> {
+  static constexpr bool pre = false;
   const bf16_t* w; int ld, fr, fk;
   __device__ __forceinline__ void load(const bf16_t* w_, int ld_, int fr_, int fk_) { w = w_; ld = ld_; fr = fr_; fk = fk_; }
   __device__ __forceinline__ bf16x8 get(int kt, int nt) const {
@@ -232,6 +235,36 @@ __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const WF& wfr, i
     const int p = (wave + j * RES_NWV) * 16 + fr;
     py[j] = p / W;
     px[j] = p - py[j] * W;
+  }
+  if constexpr (MID == 16) {
+    // 16 channels per tap fill half an MFMA step: a step covers two taps, lane groups 0-1 the first and 2-3 the second
+    // (the packed weights [16][160] have k = tap*16 + channel contiguous and are zero beyond k = 144)
+    const int fq = fk >> 3, c8 = (fq & 1) * 8;
+    auto step = [&](int st) {
+      const int tap = 2 * st + (fq >> 1);
+      const int r = tap / 3, s = tap - r * 3;
+      const int dh = BACKWARD ? 1 - r : r - 1, dw = BACKWARD ? 1 - s : s - 1;
+      const bf16x8 wf = wfr.get(st, 0);
+#pragma unroll
+      for (int j = 0; j < PTW; ++j) {
+        if (wave + j * RES_NWV < npt) {
+          const int hs = py[j] + dh, ws = px[j] + dw;
+          const bool ok = tap < 9 && (unsigned)hs < (unsigned)H && (unsigned)ws < (unsigned)W;
+          const int row = ok ? hs * W + ws : 0;
+          bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(src + row * MS + c8);
+          if (!ok) bfrag = frag_zero();
+          acc[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, bfrag, acc[j][0], 0, 0, 0);
+        }
+      }
+    };
+    if constexpr (WF::pre) {   // fragments in registers: the step index must be a constant
+#pragma unroll
+      for (int st = 0; st < 5; ++st) step(st);
+    } else {                   // fetched where used: a rolled loop keeps the addresses of 40 operand reads out of the registers
+#pragma unroll 1
+      for (int st = 0; st < 5; ++st) step(st);
+    }
+    return;
   }
 #pragma unroll
   for (int tap = 0; tap < 9; ++tap) {
@@ -1416,6 +1449,9 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
 // ResBlock fields used: x, c1, c2, y, gy, dc1, dc2, gx and entries 0 / 1 of the per-BatchNorm / per-convolution arrays.
 // The weight gradients of such runs go through the grouped per-layer launch, inference through the per-layer kernels.
 
+// floats of the reduction area: 8 waves x 2*C sums (backward), and 32/(C/8) pixel groups x 2*C (statistics) = 512
+constexpr int V1_RED(int C) { return RES_NWV * 2 * C > 512 ? RES_NWV * 2 * C : 512; }
+
 // y = relu(c2*scale + shift + x), tile to tile (written over x)
 template <int Cc>
 __device__ __forceinline__ void tile_join_relu(bf16_t* sx, const bf16_t* sc2, const float2* coef, int P) {
@@ -1441,7 +1477,9 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  // the 16-channel shape is 32 x 32 pixels only: constants instead of kernel arguments (fewer address temporaries)
+  const int H = C == 16 ? 32 : a.H, W = C == 16 ? 32 : a.W;
+  const int P = H * W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
@@ -1454,10 +1492,11 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
   bf16_t* sB = sx + (size_t)P * XS;                       // c1, then relu(bn1(c1))
   bf16_t* sC = sB + (size_t)P * XS;                       // c2
   float2* coef = reinterpret_cast<float2*>(sC + (size_t)P * XS);
-  float* red = reinterpret_cast<float*>(coef + C);        // RES_NWV * 2*C floats
-  float* own = red + RES_NWV * 2 * C;
+  float* red = reinterpret_cast<float*>(coef + C);        // V1_RED(C) floats
+  float* own = red + V1_RED(C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  WFrags<9 * C / 32, C / 16, PRE> w1, w2;
+  constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;     // reduction steps and row length of the packed weights
+  WFrags<KT, C / 16, PRE> w1, w2;
 
   auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
 #pragma unroll
@@ -1472,7 +1511,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
-    w1.load(a.packed + B0.wf_off[0], 9 * C, fr, fk);
+    w1.load(a.packed + B0.wf_off[0], LD, fr, fk);
     __syncthreads();
   }
   for (int bi = 0; bi < a.nblk; ++bi) {
@@ -1483,10 +1522,10 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, false>(sx, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, false>(sx, w1, H, W, npt, wave, fr, fk, acc);
       store_acc(sB, acc);
     }
-    w2.load(a.packed + B.wf_off[1], 9 * C, fr, fk);
+    w2.load(a.packed + B.wf_off[1], LD, fr, fk);
     __syncthreads();
     {
       float* gath = gath_own ? own : reinterpret_cast<float*>(sC);   // c2 of the block before has been consumed
@@ -1505,10 +1544,10 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, false>(sB, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, false>(sB, w2, H, W, npt, wave, fr, fk, acc);
       store_acc(sC, acc);
     }
-    if (bi + 1 < a.nblk) w1.load(a.packed + a.blocks[bi + 1].wf_off[0], 9 * C, fr, fk);
+    if (bi + 1 < a.nblk) w1.load(a.packed + a.blocks[bi + 1].wf_off[0], LD, fr, fk);
     __syncthreads();
     {
       float* gath = gath_own ? own : reinterpret_cast<float*>(sB);   // conv2 has read relu(bn1(c1)): barrier above
@@ -1576,14 +1615,15 @@ __device__ __forceinline__ bool v1_bn_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const
   if (!collect<4, true>(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
   const float invM = 1.f / ((float)nmem * (float)P);
   {
-    constexpr int CR = Cc / 32, MP = 16 / CR;
+    constexpr int CR = Cc >= 32 ? Cc / 32 : 1, MP = 16 / CR;
     const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
-    const int c = row * CR + l16 % CR, part = l16 / CR;
+    const bool act = row * CR < Cc;
+    const int c = act ? row * CR + l16 % CR : 0, part = l16 / CR;
     float sb = 0.f, sg = 0.f;
     for (int m = part; m < nmem; m += MP) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
     sb = row_sum<CR>(sb);
     sg = row_sum<CR>(sg);
-    if (part == 0) {
+    if (act && part == 0) {
       if (g_beta) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
       const float4 k = cf[c];
       tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
@@ -1613,7 +1653,9 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  // the 16-channel shape is 32 x 32 pixels only: constants instead of kernel arguments (fewer address temporaries)
+  const int H = C == 16 ? 32 : a.H, W = C == 16 ? 32 : a.W;
+  const int P = H * W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
@@ -1626,11 +1668,12 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
   bf16_t* sdc = sdy + (size_t)P * XS;                     // dc2, then dc1
   float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * XS);
   float4* cf2 = cf1 + C;
-  float* red = reinterpret_cast<float*>(cf2 + C);         // RES_NWV * 2*C floats
-  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);
+  float* red = reinterpret_cast<float*>(cf2 + C);         // V1_RED(C) floats
+  float4* tab = reinterpret_cast<float4*>(red + V1_RED(C));
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  WFrags<9 * C / 32, C / 16, PRE> w2, w1;   // data-gradient operands [C][9*C]
+  constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;
+  WFrags<KT, C / 16, PRE> w2, w1;   // data-gradient operands [C][LD]
 
   auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
 #pragma unroll
@@ -1660,7 +1703,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
                                               a.params + B.beta_off[0], c, C);
       const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
-      w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
+      w2.load(a.packed + B.wd_off[1], LD, fr, fk);
       if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
     }
     __syncthreads();   // the tables; and (first block) the gradient tile
@@ -1691,12 +1734,12 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, true>(sdc, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, true>(sdc, w2, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
-      w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
+      w1.load(a.packed + B.wd_off[0], LD, fr, fk);
       // every wave is past its reads of dc2 at the first barrier inside; the results are written behind the last one
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!v1_bn_bwd_acc<C, PTW, false>(acc, xin, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase, gb1,
@@ -1714,7 +1757,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = dzs[j][nt];
-      conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, true>(sdc, w1, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -2330,6 +2373,12 @@ size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
   *own = (size_t)nmem * 2 * C * 4 > tile ? 1 : 0;
   return (backward ? 2 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
+size_t v1_lds(int C, int P, int nmem, bool backward, int* own) {
+  const size_t tile = (size_t)P * (C + 8) * 2;
+  const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)V1_RED(C) * 4 + (size_t)C * 16 : (size_t)C * 8 + (size_t)V1_RED(C) * 4;
+  *own = (size_t)nmem * 2 * C * 4 > tile ? 1 : 0;
+  return (backward ? 2 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
+}
 size_t bb_wgrad_lds(int C, int P, int W) {
   return (size_t)3 * C * (P + 2 * W + 8) * 2 + (size_t)C * (P + 8) * 2 + (size_t)C * 8;
 }
@@ -2399,9 +2448,9 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
   int own = 0;
   if (const int nb = resident_bands(kind, C, MID, H, W); nb > 1)
     return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES && band_bwd_lds(nmem * nb) <= RES_LDS_BYTES;
-  if (kind == 2) {   // post-activation basic blocks: the same tiles as the pre-activation ones, no weight-gradient launch
-    if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
-    return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES;
+  if (kind == 2) {   // post-activation basic blocks: three / two tiles, no weight-gradient launch
+    if (!((C == 16 && P == 1024 && W == 32) || (C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
+    return v1_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && v1_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES;
   }
   if (kind == 0) {   // basic blocks: C -> C -> C
     if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
@@ -2439,7 +2488,8 @@ hipError_t resident_prepare() {
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
-                      reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>)};
+                      reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
+                      reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>)};
   for (const void* f : v1)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2464,7 +2514,8 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 2) {
-    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    const size_t lds = v1_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 16) return launch_res(k_v1_forward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
     return launch_res(k_v1_forward<64, 1, false>, lds, own, g, a, stream);
   }
@@ -2535,7 +2586,8 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > resident_max_group(a.nmem)) return hipErrorInvalidValue;
   int own = 0;
   if (kind == 2) {
-    const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
+    const size_t lds = v1_lds(C, a.H * a.W, a.nmem, true, &own);
+    if (C == 16) return launch_res(k_v1_backward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
     return launch_res(k_v1_backward<64, 1, false>, lds, own, g, a, stream);
   }
