@@ -370,12 +370,15 @@ __device__ __forceinline__ void running_coef(float2* coef, const float* run, con
 // PRE: weight fragments are preloaded into registers ahead of the exchanges (needs the register room).
 // INFER: inference forward (BatchNorm by running statistics): the images are independent, nothing is stashed and
 // only the output of the last block is written.
-template <int C, int MID, int PTW, bool PRE, bool INFER = false>
+// HW: 0 = image height and width from the arguments; 16 = 16 x 16 pixels as compile-time constants in the 3x3 convolution
+// (the shape of the benchmark partition: pixel-row decodes and tap addresses become shifts).
+template <int C, int MID, int PTW, bool PRE, bool INFER = false, int HW = 0>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  const int H = HW ? HW : a.H, W = HW ? HW : a.W;   // constants in the pixel-row arithmetic of the 3x3 convolution only:
+  const int P = a.H * a.W, npt = P >> 4;           // with constant trip counts the tile loops unroll into register spills
   // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
@@ -474,7 +477,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<MID, PTW, false>(smA, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<MID, PTW, false>(smA, w2, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -675,12 +678,13 @@ struct BwdLoads {
   }
 };
 
-template <int C, int MID, int PTW, bool PRE>
+template <int C, int MID, int PTW, bool PRE, int HW = 0>
 __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  const int H = HW ? HW : a.H, W = HW ? HW : a.W;   // constants in the pixel-row arithmetic of the 3x3 convolution only:
+  const int P = a.H * a.W, npt = P >> 4;           // with constant trip counts the tile loops unroll into register spills
   // work-groups are dealt to the XCDs round-robin by linear id: with g == 8 micro-batch z lives on XCD z
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
@@ -785,7 +789,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
             x1[j][nt] = *reinterpret_cast<const uint2*>(xg + (size_t)((pt < npt ? pt : 0) * 16 + fr) * C + nt * 16 + fq * 4);
         }
       }
-      conv3x3_tile<MID, PTW, true>(sdc, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<MID, PTW, true>(sdc, w2, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -2487,6 +2491,10 @@ hipError_t resident_prepare() {
                         reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* sq[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, false, 16>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, false, 16>),
+                      reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true, 16>),       reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false, 16>)};
+  for (const void* f : sq)
+    if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>)};
@@ -2525,8 +2533,13 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
     return launch_res(k_bb_forward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
-  if (C == 128 && MID == 64) return launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
-  if (C == 128) return launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
+  const bool sq16 = a.H == 16 && a.W == 16;
+  if (C == 128 && MID == 64)
+    return sq16 ? launch_res(k_res_forward<128, 64, 2, false, false, 16>, lds, own, g, a, stream)
+                : launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
+  if (C == 128)
+    return sq16 ? launch_res(k_res_forward<128, 32, 2, true, false, 16>, lds, own, g, a, stream)
+                : launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
@@ -2597,8 +2610,13 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
     return launch_res(k_bb_backward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
-  if (C == 128 && MID == 64) return launch_res(k_res_backward<128, 64, 2, false>, lds, own, g, a, stream);
-  if (C == 128) return launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
+  const bool sq16 = a.H == 16 && a.W == 16;
+  if (C == 128 && MID == 64)
+    return sq16 ? launch_res(k_res_backward<128, 64, 2, false, 16>, lds, own, g, a, stream)
+                : launch_res(k_res_backward<128, 64, 2, false>, lds, own, g, a, stream);
+  if (C == 128)
+    return sq16 ? launch_res(k_res_backward<128, 32, 2, true, 16>, lds, own, g, a, stream)
+                : launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
   return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
