@@ -31,8 +31,8 @@ PEAK_HBM = 8.0e12         # bytes/s
 # HBM bytes per launch from rocprofv3 counter runs of this same command (FETCH_SIZE + WRITE_SIZE, each
 # scaled by what the counter reads for a plain device copy of known size); the summaries with the
 # commands are under profiles/.  Keyed by (kernel class, configuration).
-MEASURED_TRAFFIC = {("resident_backward", 3): 1.125e9}
-TRAFFIC_SOURCE = ("constant taken from profiles/mfma_and_bn_counters_resnet1001_partition.md (two rocprofv3 --pmc runs of this "
+MEASURED_TRAFFIC = {("resident_backward", 3): 1.135e9}
+TRAFFIC_SOURCE = ("constant taken from profiles/hbm_traffic_resnet1001_partition.md (two rocprofv3 --pmc runs of this "
                   "command), not measured in this run")
 
 
