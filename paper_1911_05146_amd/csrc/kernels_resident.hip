@@ -18,6 +18,8 @@
 // the number of CUs, and a bounded spin turns a missing partner into an error flag instead of a hang.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "hpf_device.h"
 
 namespace hpf {
@@ -202,7 +204,7 @@ template <int KT, int NT, bool PRE>
 struct WFrags;
 template <int KT, int NT>
 struct WFrags<KT, NT, true> {
-  static constexpr bool pre = true;
+  static constexpr bool pre = true, staged = false;
   bf16x8 r[KT][NT];
   __device__ __forceinline__ void load(const bf16_t* w, int ld, int fr, int fk) {
 #pragma unroll
@@ -214,13 +216,65 @@ struct WFrags<KT, NT, true> {
 };
 template <int KT, int NT>
 struct WFrags<KT, NT, false> {
-  static constexpr bool pre = false;
+  static constexpr bool pre = false, staged = false;
   const bf16_t* w; int ld, fr, fk;
   __device__ __forceinline__ void load(const bf16_t* w_, int ld_, int fr_, int fk_) { w = w_; ld = ld_; fr = fr_; fk = fk_; }
   __device__ __forceinline__ bf16x8 get(int kt, int nt) const {
     return *reinterpret_cast<const bf16x8*>(w + (size_t)(nt * 16 + fr) * ld + kt * 32 + fk);
   }
 };
+
+// Third form: the fragments come from an LDS copy of the matrix that the whole work-group stages once.  load()
+// only asks for this thread's 16-byte units (into registers, ahead of an exchange); commit() stores them to the
+// LDS area behind the wait, when every wave has finished with the matrix staged before (the caller puts a barrier
+// between the last get() of the old matrix and commit(), and one between commit() and the first get()).  With
+// weights fetched where they are used every reduction step is an L2 round trip that nothing hides when a wave has
+// one pixel tile to work on; from LDS a step costs an LDS read.  Rows are KT*32 long (the packed matrix is exactly
+// that wide) and padded by 8 elements in LDS: 16 consecutive rows start in 16 different bank groups.
+template <int KT, int NT>
+struct WFragsL {
+  static constexpr bool pre = true;    // get() takes constants only (the same loop shapes as the register form)
+  static constexpr bool staged = true;
+  static constexpr int ROWS = NT * 16, LEN = KT * 32, STRIDE = LEN + 8, UNITS = ROWS * LEN / 8, NU = (UNITS + RES_NT - 1) / RES_NT;
+  const bf16_t* s;
+  int fr, fk;
+  // st: the thread's staging registers, shared by the matrices of a block (one is in flight at a time)
+  template <int N>
+  __device__ __forceinline__ void issue(u32x4 (&st)[N], const bf16_t* w, int fr_, int fk_) {
+    static_assert(NU <= N, "staging registers");
+    fr = fr_; fk = fk_;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      st[i] = *reinterpret_cast<const u32x4*>(w + (size_t)(u < UNITS ? u : 0) * 8);   // the packed matrix is contiguous
+    }
+  }
+  template <int N>
+  __device__ __forceinline__ void commit(const u32x4 (&st)[N], bf16_t* sw) {
+    s = sw;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      if (u < UNITS) {
+        const int row = u / (LEN / 8), col = u - row * (LEN / 8);
+        *reinterpret_cast<u32x4*>(sw + row * STRIDE + col * 8) = st[i];
+      }
+    }
+  }
+  __device__ __forceinline__ bf16x8 get(int kt, int nt) const {
+    return *reinterpret_cast<const bf16x8*>(s + (nt * 16 + fr) * STRIDE + kt * 32 + fk);
+  }
+};
+// issue / commit for any form: the register and fetch-where-used forms load at once and have nothing to commit
+template <class WF, int N>
+__device__ __forceinline__ void w_issue(WF& w, u32x4 (&st)[N], const bf16_t* p, int ld, int fr, int fk) {
+  if constexpr (WF::staged) w.issue(st, p, fr, fk);
+  else w.load(p, ld, fr, fk);
+}
+template <class WF, int N>
+__device__ __forceinline__ void w_commit(WF& w, const u32x4 (&st)[N], bf16_t* sw) {
+  if constexpr (WF::staged) w.commit(st, sw);
+}
 
 // 3x3 convolution (stride 1, zero padding) of a [P][MID] tile in LDS, both directions:
 //   forward : out(p,q) += src(p+r-1, q+s-1) * W[r][s]       weights [MID][9*MID], k = tap*MID + c
@@ -372,8 +426,10 @@ __device__ __forceinline__ void running_coef(float2* coef, const float* run, con
 // only the output of the last block is written.
 // HW: 0 = image height and width from the arguments; 16 = 16 x 16 pixels as compile-time constants in the 3x3 convolution
 // (the shape of the benchmark partition: pixel-row decodes and tap addresses become shifts).
-template <int C, int MID, int PTW, bool PRE, bool INFER = false, int HW = 0>
+// WL: the weights go through LDS (WFragsL): for shapes with one pixel tile per wave and LDS to spare (256-64 at 8x8).
+template <int C, int MID, int PTW, bool PRE, bool INFER = false, int HW = 0, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && (PRE || INFER)), "the LDS form replaces the fetch-where-used form of the training kernels");
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -399,14 +455,16 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   float* gathB = gath_own ? own : reinterpret_cast<float*>(smB);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
-  WFrags<C / 32, MID / 16, PRE> w1;        // conv1 [MID][C]
-  WFrags<9 * MID / 32, MID / 16, PRE> w2;  // conv2 [MID][9*MID]
-  WFrags<MID / 32, C / 16, PRE> w3;        // conv3 [C][MID]
+  std::conditional_t<WL, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w1;            // conv1 [MID][C]
+  std::conditional_t<WL, WFragsL<9 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>> w2;  // conv2 [MID][9*MID]
+  std::conditional_t<WL, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w3;            // conv3 [C][MID]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (9 * MID / 32 * (MID / 16) + 7) / 8 : 1];                                  // WL: its units on their way
 
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
-    w1.load(a.packed + B0.wf_off[0], C, fr, fk);
+    w_issue(w1, wst, a.packed + B0.wf_off[0], C, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<C>(coefC, a.running + B0.run_off[0], a.params + B0.gamma_off[0], a.params + B0.beta_off[0], a.eps);
@@ -414,6 +472,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
+      w_commit(w1, wst, sW);   // the barrier at the end of the merge lies between this and conv1
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
     }
@@ -456,7 +515,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
             *reinterpret_cast<uint2*>(smA + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
       }
     }
-    w2.load(a.packed + B.wf_off[1], 9 * MID, fr, fk);
+    w_issue(w2, wst, a.packed + B.wf_off[1], 9 * MID, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<MID>(coefM, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
@@ -465,6 +524,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
       tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // after the polls (measured: 2 % faster than before them)
       ++phase;
+      w_commit(w2, wst, sW);   // conv1 is behind the barrier above the statistics; conv2 behind the ones below
       merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
                       me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
     }
@@ -487,7 +547,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
             *reinterpret_cast<uint2*>(smB + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
       }
     }
-    w3.load(a.packed + B.wf_off[2], MID, fr, fk);
+    w_issue(w3, wst, a.packed + B.wf_off[2], MID, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<MID>(coefM, a.running + B.run_off[2], a.params + B.gamma_off[2], a.params + B.beta_off[2], a.eps);
@@ -496,6 +556,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
       ++phase;
+      w_commit(w3, wst, sW);
       merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
                       me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
     }
@@ -532,7 +593,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     }
     const bool more = bi + 1 < a.nblk;
     const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
-    if (more) w1.load(a.packed + Bn.wf_off[0], C, fr, fk);
+    if (more) w_issue(w1, wst, a.packed + Bn.wf_off[0], C, fr, fk);
     __syncthreads();
     if (INFER) {
       if (more) running_coef<C>(coefC, a.running + Bn.run_off[0], a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], a.eps);
@@ -544,6 +605,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     if (more) {
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
+      w_commit(w1, wst, sW);
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
     }
@@ -678,8 +740,9 @@ struct BwdLoads {
   }
 };
 
-template <int C, int MID, int PTW, bool PRE, int HW = 0>
+template <int C, int MID, int PTW, bool PRE, int HW = 0, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && PRE), "the LDS form replaces the fetch-where-used form");
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -705,12 +768,18 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
-  WFrags<C / 32, MID / 16, PRE> w3;        // conv3 data gradient [MID][C]
-  WFrags<9 * MID / 32, MID / 16, PRE> w2;  // conv2 data gradient [MID][9*MID]
-  WFrags<MID / 32, C / 16, PRE> w1;        // conv1 data gradient [C][MID]
+  std::conditional_t<WL, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w3;            // conv3 data gradient [MID][C]
+  std::conditional_t<WL, WFragsL<9 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>> w2;  // conv2 data gradient [MID][9*MID]
+  std::conditional_t<WL, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w1;            // conv1 data gradient [C][MID]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (9 * MID / 32 * (MID / 16) + 7) / 8 : 1];                                  // WL: its units on their way
   {
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+    if constexpr (WL) {   // the first block's conv3 matrix; later ones are staged behind the exchange before
+      w_issue(w3, wst, a.packed + BL.wd_off[2], C, fr, fk);
+      w_commit(w3, wst, sW);
+    }
   }
   __syncthreads();   // the first contraction reads the tile right away
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
@@ -722,7 +791,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
     floatx4 acc3[PTW][MID / 16];
     {
       BwdLoads<C, MID, PTW> ld;
-      w3.load(a.packed + B.wd_off[2], C, fr, fk);
+      if constexpr (!WL) w3.load(a.packed + B.wd_off[2], C, fr, fk);
       ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
@@ -758,7 +827,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
           xin[j][nt] = pt < npt ? xc2[j][nt] : make_uint2(0u, 0u);
         }
       }
-      w2.load(a.packed + B.wd_off[1], 9 * MID, fr, fk);
+      w_issue(w2, wst, a.packed + B.wd_off[1], 9 * MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                      me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[2]) : nullptr, a.abort_flag,
@@ -767,6 +836,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                      }))
         return;
       ++phase;
+      w_commit(w2, wst, sW);   // conv3's matrix was last read above the barrier that follows the tables
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, sdc, P);
@@ -798,7 +868,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
           xin[j][nt] = pt < npt ? xc1[j][nt] : make_uint2(0u, 0u);
         }
       }
-      w1.load(a.packed + B.wd_off[0], MID, fr, fk);
+      w_issue(w1, wst, a.packed + B.wd_off[0], MID, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                      me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
@@ -807,6 +877,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                      }))
         return;
       ++phase;
+      w_commit(w1, wst, sW);
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc1_off) + (size_t)me * P * MID, sm2, P);
@@ -831,6 +902,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         }
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
+      if constexpr (WL)
+        if (bi > 0) w_issue(w3, wst, a.packed + a.blocks[bi - 1].wd_off[2], C, fr, fk);   // the next block's conv3 matrix
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);   // dc1 left the tile above
       if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                    me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[0]) : nullptr, a.abort_flag,
@@ -843,6 +916,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                    }))
         return;
       ++phase;
+      if constexpr (WL)
+        if (bi > 0) w_commit(w3, wst, sW);
     }
     __syncthreads();   // dx is complete; the BN tables and the small tiles of this block are no longer read
     tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
@@ -2402,6 +2477,11 @@ size_t fwd_lds(int C, int MID, int P, int nmem, int* own) {
   *own = ((size_t)nmem * 2 * C * 4 > 2 * one_tile || (size_t)nmem * 2 * MID * 4 > one_tile) ? 1 : 0;
   return tiles + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
+// LDS copy of the largest weight matrix of a block (rows padded by 8 elements), for the kernels that stage their weights
+size_t wl_bytes(int C, int MID) {
+  const size_t m1 = (size_t)MID * (C + 8) * 2, m2 = (size_t)MID * (9 * MID + 8) * 2, m3 = (size_t)C * (MID + 8) * 2;
+  return m1 > m2 ? (m1 > m3 ? m1 : m3) : (m2 > m3 ? m2 : m3);
+}
 size_t bwd_lds(int C, int MID, int P, int nmem, int* own) {
   const size_t tiles = (size_t)P * (C + 8) * 2 + 2 * (size_t)P * (MID + 8) * 2;
   const size_t fixed = (size_t)(C + 2 * MID) * 16 + (size_t)RES_NWV * 2 * C * 4 + 4 * (size_t)C * 4;
@@ -2495,6 +2575,8 @@ hipError_t resident_prepare() {
                       reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true, 16>),       reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false, 16>)};
   for (const void* f : sq)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>)};
@@ -2540,6 +2622,9 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   if (C == 128)
     return sq16 ? launch_res(k_res_forward<128, 32, 2, true, false, 16>, lds, own, g, a, stream)
                 : launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
+  // one pixel tile per wave: the weights through LDS where the tiles leave room for them (8x8 images)
+  if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
+    return launch_res(k_res_forward<256, 64, 1, false, false, 0, true>, lds + wl_bytes(C, MID), own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
@@ -2617,6 +2702,8 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   if (C == 128)
     return sq16 ? launch_res(k_res_backward<128, 32, 2, true, 16>, lds, own, g, a, stream)
                 : launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
+  if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
+    return launch_res(k_res_backward<256, 64, 1, false, 0, true>, lds + wl_bytes(C, MID), own, g, a, stream);
   return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
