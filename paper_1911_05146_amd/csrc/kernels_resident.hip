@@ -1551,8 +1551,9 @@ __device__ __forceinline__ void tile_join_relu(bf16_t* sx, const bf16_t* sc2, co
   }
 }
 
-template <int C, int PTW, bool PRE>
+template <int C, int PTW, bool PRE, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && PRE), "the LDS form replaces the fetch-where-used form");
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -1575,7 +1576,9 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
   float* own = red + V1_RED(C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
   constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;     // reduction steps and row length of the packed weights
-  WFrags<KT, C / 16, PRE> w1, w2;
+  std::conditional_t<WL, WFragsL<KT, C / 16>, WFrags<KT, C / 16, PRE>> w1, w2;
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (KT * (C / 16) + 7) / 8 : 1];                                              // WL: its units on their way
 
   auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
 #pragma unroll
@@ -1590,7 +1593,8 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
-    w1.load(a.packed + B0.wf_off[0], LD, fr, fk);
+    w_issue(w1, wst, a.packed + B0.wf_off[0], LD, fr, fk);
+    w_commit(w1, wst, sW);
     __syncthreads();
   }
   for (int bi = 0; bi < a.nblk; ++bi) {
@@ -1604,7 +1608,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       conv3x3_tile<C, PTW, false>(sx, w1, H, W, npt, wave, fr, fk, acc);
       store_acc(sB, acc);
     }
-    w2.load(a.packed + B.wf_off[1], LD, fr, fk);
+    w_issue(w2, wst, a.packed + B.wf_off[1], LD, fr, fk);
     __syncthreads();
     {
       float* gath = gath_own ? own : reinterpret_cast<float*>(sC);   // c2 of the block before has been consumed
@@ -1612,6 +1616,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
       if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
       ++phase;
+      w_commit(w2, wst, sW);   // conv1 read its matrix above the barrier before the statistics
       merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[0], a.params + B.beta_off[0], coef,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[0]) : nullptr);
     }
@@ -1626,7 +1631,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       conv3x3_tile<C, PTW, false>(sB, w2, H, W, npt, wave, fr, fk, acc);
       store_acc(sC, acc);
     }
-    if (bi + 1 < a.nblk) w1.load(a.packed + a.blocks[bi + 1].wf_off[0], LD, fr, fk);
+    if (bi + 1 < a.nblk) w_issue(w1, wst, a.packed + a.blocks[bi + 1].wf_off[0], LD, fr, fk);
     __syncthreads();
     {
       float* gath = gath_own ? own : reinterpret_cast<float*>(sB);   // conv2 has read relu(bn1(c1)): barrier above
@@ -1634,6 +1639,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_forward(const ResArgs a, const in
       tile_store<C>(cx.tensor(B.c2_off) + (size_t)me * P * C, sC, P);
       if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
       ++phase;
+      if (bi + 1 < a.nblk) w_commit(w1, wst, sW);
       merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
     }
@@ -1727,8 +1733,9 @@ __device__ __forceinline__ bool v1_bn_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const
   return true;
 }
 
-template <int C, int PTW, bool PRE>
+template <int C, int PTW, bool PRE, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && PRE), "the LDS form replaces the fetch-where-used form");
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -1752,7 +1759,9 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
   constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;
-  WFrags<KT, C / 16, PRE> w2, w1;   // data-gradient operands [C][LD]
+  std::conditional_t<WL, WFragsL<KT, C / 16>, WFrags<KT, C / 16, PRE>> w2, w1;   // data-gradient operands [C][LD]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (KT * (C / 16) + 7) / 8 : 1];
 
   auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
 #pragma unroll
@@ -1782,7 +1791,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
                                               a.params + B.beta_off[0], c, C);
       const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
-      w2.load(a.packed + B.wd_off[1], LD, fr, fk);
+      w_issue(w2, wst, a.packed + B.wd_off[1], LD, fr, fk);
       if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
     }
     __syncthreads();   // the tables; and (first block) the gradient tile
@@ -1803,6 +1812,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
                                        }))
         return;
       ++phase;
+      w_commit(w2, wst, sW);   // the matrix staged before was last read above the barrier that ends the block before
     }
     __syncthreads();
     tile_store<C>(cx.tensor(B.dc2_off) + (size_t)me * P * C, sdc, P);
@@ -1818,7 +1828,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
-      w1.load(a.packed + B.wd_off[0], LD, fr, fk);
+      w_issue(w1, wst, a.packed + B.wd_off[0], LD, fr, fk);
       // every wave is past its reads of dc2 at the first barrier inside; the results are written behind the last one
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!v1_bn_bwd_acc<C, PTW, false>(acc, xin, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase, gb1,
@@ -1827,6 +1837,7 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
                                         }))
         return;
       ++phase;
+      w_commit(w1, wst, sW);
     }
     __syncthreads();
     tile_store<C>(cx.tensor(B.dc1_off) + (size_t)me * P * C, sdc, P);
@@ -2579,7 +2590,8 @@ hipError_t resident_prepare() {
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
-                      reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>)};
+                      reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>),
+                      reinterpret_cast<const void*>(k_v1_forward<64, 1, false, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false, true>)};
   for (const void* f : v1)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2607,6 +2619,8 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
     const size_t lds = v1_lds(C, a.H * a.W, a.nmem, false, &own);
     if (C == 16) return launch_res(k_v1_forward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
+    const size_t wl = (size_t)C * (9 * C + 8) * 2;   // one pixel tile per wave: the 3x3 matrices through LDS where they fit
+    if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_forward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_v1_forward<64, 1, false>, lds, own, g, a, stream);
   }
   if (kind == 0) {
@@ -2687,6 +2701,8 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
     const size_t lds = v1_lds(C, a.H * a.W, a.nmem, true, &own);
     if (C == 16) return launch_res(k_v1_backward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
+    const size_t wl = (size_t)C * (9 * C + 8) * 2;
+    if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_backward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_v1_backward<64, 1, false>, lds, own, g, a, stream);
   }
   if (kind == 0) {
