@@ -1271,8 +1271,9 @@ __device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, 
   }
 }
 
-template <int C, int PTW, bool PRE, bool INFER = false>
+template <int C, int PTW, bool PRE, bool INFER = false, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && (PRE || INFER)), "the LDS form replaces the fetch-where-used form of the training kernels");
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -1293,7 +1294,9 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
   float* own = red + RES_NWV * 2 * C;
   float* gath = gath_own ? own : reinterpret_cast<float*>(sA);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  WFrags<9 * C / 32, C / 16, PRE> w1, w2;
+  std::conditional_t<WL, WFragsL<9 * C / 32, C / 16>, WFrags<9 * C / 32, C / 16, PRE>> w1, w2;
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (9 * C / 32 * (C / 16) + 7) / 8 : 1];                                      // WL: its units on their way
 
   auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
 #pragma unroll
@@ -1308,7 +1311,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
-    w1.load(a.packed + B0.wf_off[0], 9 * C, fr, fk);
+    w_issue(w1, wst, a.packed + B0.wf_off[0], 9 * C, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<C>(coef, a.running + B0.run_off[0], a.params + B0.gamma_off[0], a.params + B0.beta_off[0], a.eps);
@@ -1316,6 +1319,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
       stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
       if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
       ++phase;
+      w_commit(w1, wst, sW);
       merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coef,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
     }
@@ -1333,7 +1337,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
       conv3x3_tile<C, PTW, false>(sA, w1, a.H, a.W, npt, wave, fr, fk, acc);
       store_acc(sB, acc);
     }
-    w2.load(a.packed + B.wf_off[1], 9 * C, fr, fk);
+    w_issue(w2, wst, a.packed + B.wf_off[1], 9 * C, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<C>(coef, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
@@ -1342,6 +1346,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
       tile_store<C>(cx.tensor(B.c1_off) + (size_t)me * P * C, sB, P);
       if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;   // sA is free: conv1 is done
       ++phase;
+      w_commit(w2, wst, sW);   // conv1 read its matrix above the barrier before the statistics
       merge_coef<C>(gath, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coef,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
     }
@@ -1370,7 +1375,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     }
     const bool more = bi + 1 < a.nblk;
     const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
-    if (more) w1.load(a.packed + Bn.wf_off[0], 9 * C, fr, fk);
+    if (more) w_issue(w1, wst, a.packed + Bn.wf_off[0], 9 * C, fr, fk);
     __syncthreads();
     if (INFER) {
       if (more) running_coef<C>(coef, a.running + Bn.run_off[0], a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], a.eps);
@@ -1382,6 +1387,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     if (more) {
       if (!collect<4>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gath, a.abort_flag)) return;
       ++phase;
+      w_commit(w1, wst, sW);
       merge_coef<C>(gath, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coef,
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
     }
@@ -1389,8 +1395,9 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
   if (!INFER && me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
-template <int C, int PTW, bool PRE>
+template <int C, int PTW, bool PRE, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const int gath_own) {
+  static_assert(!(WL && PRE), "the LDS form replaces the fetch-where-used form");
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -1411,7 +1418,9 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
   float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  WFrags<9 * C / 32, C / 16, PRE> w2, w1;   // data-gradient operands [C][9*C]
+  std::conditional_t<WL, WFragsL<9 * C / 32, C / 16>, WFrags<9 * C / 32, C / 16, PRE>> w2, w1;   // data-gradient operands [C][9*C]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
+  u32x4 wst[WL ? (9 * C / 32 * (C / 16) + 7) / 8 : 1];
 
   // x / c1 (the BatchNorm inputs) are needed only at this lane's accumulator positions: read there from memory
   auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
@@ -1426,6 +1435,10 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
   {
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
+    if constexpr (WL) {   // the first block's conv2 matrix (the barrier below the tables precedes its use); later ones are
+      w_issue(w2, wst, a.packed + BL.wd_off[1], 9 * C, fr, fk);   // staged behind the last exchange of the block before
+      w_commit(w2, wst, sW);
+    }
   }
   for (int bi = a.nblk - 1; bi >= 0; --bi) {
     const ResBlock B = a.blocks[bi];
@@ -1438,7 +1451,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
                                               a.params + B.beta_off[0], c, C);
       const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
-      w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
+      if constexpr (!WL) w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
       if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
     }
     __syncthreads();
@@ -1454,7 +1467,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
-      w1.load(a.packed + B.wd_off[0], 9 * C, fr, fk);
+      w_issue(w1, wst, a.packed + B.wd_off[0], 9 * C, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                    me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
@@ -1463,6 +1476,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
                                    }))
         return;
       ++phase;
+      w_commit(w1, wst, sW);
     }
     __syncthreads();
     tile_store<C>(cx.tensor(B.dc1_off) + (size_t)me * P * C, sdc, P);
@@ -1474,6 +1488,8 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
       conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      if constexpr (WL)
+        if (bi > 0) w_issue(w2, wst, a.packed + a.blocks[bi - 1].wd_off[1], 9 * C, fr, fk);   // the next block's conv2 matrix
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
@@ -1492,6 +1508,8 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
                                    }))
         return;
       ++phase;
+      if constexpr (WL)
+        if (bi > 0) w_commit(w2, wst, sW);   // every wave is past conv1's data gradient: the barriers of the BatchNorm backward
     }
     __syncthreads();
     tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
@@ -2591,7 +2609,8 @@ hipError_t resident_prepare() {
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>),
-                      reinterpret_cast<const void*>(k_v1_forward<64, 1, false, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false, true>)};
+                      reinterpret_cast<const void*>(k_v1_forward<64, 1, false, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false, true>),
+                      reinterpret_cast<const void*>(k_bb_forward<64, 1, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false, true>)};
   for (const void* f : v1)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_forward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2626,6 +2645,8 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
     if (C == 32) return launch_res(k_bb_forward<32, 2, true>, lds, own, g, a, stream);
+    const size_t wl = (size_t)C * (9 * C + 8) * 2;
+    if (lds + wl <= RES_LDS_BYTES) return launch_res(k_bb_forward<64, 1, false, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_bb_forward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
@@ -2708,6 +2729,8 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
     if (C == 32) return launch_res(k_bb_backward<32, 2, true>, lds, own, g, a, stream);
+    const size_t wl = (size_t)C * (9 * C + 8) * 2;
+    if (lds + wl <= RES_LDS_BYTES) return launch_res(k_bb_backward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_bb_backward<64, 1, false>, lds, own, g, a, stream);
   }
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
