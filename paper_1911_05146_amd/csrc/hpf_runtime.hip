@@ -503,19 +503,19 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     if (d.has_stem) wc.push_back(WConv{&stem1x1, P.stem_kc, 9 * d.in_c, 1, P.stem_col, P.g_stem, nullptr, false});
     for (int i = 0; i < d.n_blocks; ++i) {
       const BlockPlan& p = P.bp[i];
+      bool in_run = false;
+      for (const Plan::ResRun& r : P.runs)   // runs without a weight-gradient launch of their own stay in the grouped launch
+        in_run = in_run || (resident_has_wgrad_launch(r.kind, r.C, r.bands) && i >= r.first && i < r.first + r.count);
       if (!p.residual()) {   // the operands are stored activations (no BatchNorm to recompute)
         if (p.d.kind == K_POSTACT) {
-          wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
-          wc.push_back(WConv{&p.cv[1], p.cv[1].cin, p.cv[1].cin, p.cv[1].R, p.c[0], p.dc[1], &p.bn[0], false});   // relu(bn1(c1)) recomputed: a resident run does not write it
+          wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, in_run});
+          wc.push_back(WConv{&p.cv[1], p.cv[1].cin, p.cv[1].cin, p.cv[1].R, p.c[0], p.dc[1], &p.bn[0], in_run});   // relu(bn1(c1)) recomputed: a resident run does not write it
           if (p.proj) wc.push_back(WConv{&p.pj, p.pj.cin, p.pj.cin, 1, p.x_in, p.dc[2], nullptr, false});
         } else if (p.d.kind == K_CONV_RELU || p.d.kind == K_DENSE) {
           wc.push_back(WConv{&p.cv[0], p.cv[0].cin, p.cv[0].cin, p.cv[0].R, p.x_in, p.dc[0], nullptr, false});
         }
         continue;
       }
-      bool in_run = false;
-      for (const Plan::ResRun& r : P.runs)   // runs without a weight-gradient launch of their own stay in the grouped launch
-        in_run = in_run || (resident_has_wgrad_launch(r.kind, r.bands) && i >= r.first && i < r.first + r.count);
       for (int j = p.j0; j < p.j1; ++j)
         wc.push_back(WConv{&p.cv[j], p.cv[j].cin, p.cv[j].cin, p.cv[j].R, p.mat[j] ? p.a[j] : (j == 0 ? p.x_in : p.c[j - 1]),
                            j == p.nconv - 1 ? p.gy : p.dc[j], p.mat[j] ? nullptr : &p.bn[j], in_run});
@@ -909,7 +909,7 @@ void run_forward(Ctx& c, const PtrTab& labels, float* loss_accum) {
   }
   for (size_t bi = 0; bi < P.bp.size(); ++bi) {
     if (resident && P.run_at[bi] >= 0 &&
-        !(c.inference && !resident_has_wgrad_launch(P.runs[P.run_at[bi]].kind, P.runs[P.run_at[bi]].bands))) {   // the whole run in one launch; it takes its own statistics
+        !(c.inference && !resident_has_inference_launch(P.runs[P.run_at[bi]].kind, P.runs[P.run_at[bi]].bands))) {   // the whole run in one launch; it takes its own statistics
       const Plan::ResRun& r = P.runs[P.run_at[bi]];
       if (c.inference) c.res_inference(r);
       else c.res_forward(r);
@@ -1142,7 +1142,7 @@ void run_backward(Ctx& c) {
     const bool res = c.h->resident();
     if (res)
       for (const Plan::ResRun& r : P.runs)
-        if (resident_has_wgrad_launch(r.kind, r.bands)) c.res_wgrad(r);
+        if (resident_has_wgrad_launch(r.kind, r.C, r.bands)) c.res_wgrad(r);
     for (int k = 0; k < WGRAD_CLASSES; ++k) {
       const std::vector<WgradItem>& items = res ? P.items_nr[k] : P.items[k];
       if (items.empty()) continue;

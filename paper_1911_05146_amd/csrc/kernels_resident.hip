@@ -1110,6 +1110,7 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
                                               const float* gamma, const float* beta, unsigned long long dy_off, float* dw,
                                               unsigned char* smem) {
   const int P = a.H * a.W, W = a.W, PS = P + 8, PSH = P + 2 * W + 8;
+  const bool plain = gamma == nullptr;   // the operand is the stored tensor as it is (no BatchNorm + ReLU in front of the convolution)
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index(), fr = lane & 15, fq = lane >> 4, fk = fq * 8;
   bf16_t* Tsh = reinterpret_cast<bf16_t*>(smem);          // [3][MID][PSH]: a shifted by s-1 pixels along the row
   bf16_t* Td = Tsh + (size_t)3 * MID * PSH;               // [MID][PS]
@@ -1141,7 +1142,7 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
       PairRegs<MID, NTH>::unit(u, pr, cg);
       const bool ok = 2 * pr < P;
       const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-      const uint4 e0 = bn_relu8(A.v[u][0], coef + cg * 8), e1 = bn_relu8(A.v[u][1], coef + cg * 8);
+      const uint4 e0 = plain ? A.v[u][0] : bn_relu8(A.v[u][0], coef + cg * 8), e1 = plain ? A.v[u][1] : bn_relu8(A.v[u][1], coef + cg * 8);
       // the neighbouring pairs of the image row sit four lanes away (the 16 pairs of a wave hold whole rows)
       uint4 left = lanes_up4(e1), right = lanes_down4(e0);
       const int pc = pr % half_w;
@@ -1176,7 +1177,7 @@ __device__ __forceinline__ void res_wgrad_3x3(const ResWgArgs& a, int img0, unsi
   {
     int me;
     const ResCtx cx = wi.ctx(0, me);
-    wg_coef<MID, NTH>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
+    if (!plain) wg_coef<MID, NTH>(coef, reinterpret_cast<const float*>(cx.base + st_off), gamma, beta, 0, MID);
   }
 #pragma unroll
   for (int k = 0; k < NS; ++k)
@@ -1881,6 +1882,22 @@ __global__ void __launch_bounds__(RES_NT) k_v1_backward(const ResArgs a, const i
   if (me == 0 && tid == 0) *tagp = tag0 + phase;
 }
 
+// weight gradients of a run of post-activation blocks: grid (image groups, 2 convolutions, blocks).  conv1 takes the
+// stored block input as it is, conv2 relu(bn1(c1)) recomputed while staging; the BatchNorm parameter gradients were
+// added by the backward launch.
+template <int C>
+__global__ void __launch_bounds__(rw_threads(C)) k_v1_wgrad(const ResWgArgs a) {
+  constexpr int NTH = rw_threads(C);
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ResBlock B = a.blocks[blockIdx.z];
+  const int img0 = blockIdx.x * a.ipw;
+  if (blockIdx.y == 0)
+    res_wgrad_3x3<C, NTH>(a, img0, B.x_off, 0, nullptr, nullptr, B.dc1_off, a.grads + B.w_off[0], smem);
+  else
+    res_wgrad_3x3<C, NTH>(a, img0, B.c1_off, B.stats_off[0], a.params + B.gamma_off[0], a.params + B.beta_off[0], B.dc2_off,
+                     a.grads + B.w_off[1], smem);
+}
+
 // ------------------------------------------------------------------------------------------ row bands
 // Runs of identity bottleneck blocks whose image does not fit one CU's LDS (ResNet-1001's first stage: 64-16-16-64
 // channels at 32x32, 128 KiB of residual stream per image): the image is cut into bands of BAND_ROWS image rows and
@@ -2563,7 +2580,8 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
     return band_fwd_lds(nmem * nb) <= RES_LDS_BYTES && band_bwd_lds(nmem * nb) <= RES_LDS_BYTES;
   if (kind == 2) {   // post-activation basic blocks: three / two tiles, no weight-gradient launch
     if (!((C == 16 && P == 1024 && W == 32) || (C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
-    return v1_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && v1_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES;
+    return v1_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && v1_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
+           (C == 16 || bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES);
   }
   if (kind == 0) {   // basic blocks: C -> C -> C
     if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
@@ -2606,6 +2624,8 @@ hipError_t resident_prepare() {
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_v1_wgrad<32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_v1_wgrad<64>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>),
@@ -2682,7 +2702,7 @@ hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResA
 
 hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs& a, hipStream_t stream) {
   if (resident_bands(kind, C, MID, a.H, a.W) > 1) return hipErrorInvalidValue;   // bands: forward and backward launches only
-  if (kind == 2) return hipErrorInvalidValue;   // post-activation runs: forward and backward launches only
+  if (!resident_has_wgrad_launch(kind, C, 1)) return hipErrorInvalidValue;
   if (!resident_shape_ok(kind, C, MID, a.H, a.W, a.nmem) || a.nblk < 1 || g < 1 || g > MAX_GROUP) return hipErrorInvalidValue;
   ResWgArgs w{};
   w.blocks = a.blocks; w.nmem = a.nmem; w.H = a.H; w.W = a.W;
@@ -2692,10 +2712,13 @@ hipError_t launch_resident_wgrad(int kind, int g, int C, int MID, const ResArgs&
   w.base = a.base; w.act_in = a.act_in; w.err_in = a.err_in; w.params = a.params; w.grads = a.grads;
   w.ngroup = g;
   const unsigned groups = (unsigned)(g * a.nmem / w.ipw);
-  if (kind == 0) {
+  if (kind == 0 || kind == 2) {
     const size_t lds = bb_wgrad_lds(C, a.H * a.W, a.W);
     const dim3 grid(groups, 2u, (unsigned)a.nblk);
-    if (C == 32) k_bb_wgrad<32><<<grid, rw_threads(32), lds, stream>>>(w);
+    if (kind == 2) {
+      if (C == 32) k_v1_wgrad<32><<<grid, rw_threads(32), lds, stream>>>(w);
+      else k_v1_wgrad<64><<<grid, rw_threads(64), lds, stream>>>(w);
+    } else if (C == 32) k_bb_wgrad<32><<<grid, rw_threads(32), lds, stream>>>(w);
     else k_bb_wgrad<64><<<grid, rw_threads(64), lds, stream>>>(w);
     return hipGetLastError();
   }
