@@ -697,9 +697,13 @@ hipError_t launch_tile(int mode, int ng, const PtrTab& src, const bf16_t* wpk, c
 }
 
 // 0: 128x128, 1: 64x64, 2: 64x32, 3: 64x16, 4: 128x128 with 64-element steps on 8 waves
-constexpr int BIG_MIN_K = 256;   // shorter reductions stay on the narrow tiles
+constexpr int BIG_MIN_K = 256;        // reductions from here on count as wide for the choice of what is written to memory
+// The 8-wave tile pays a fixed 8 us per work-group (pipeline fill, epilogue through LDS) and runs one work-group
+// per CU: with four reduction steps (K = 256) the 64x64 tiles, five work-groups per CU, are faster (1x1 256 -> 1024
+// on 12 544 rows: 22.8 us against 27.8 us); from eight steps on the wide tile wins (K = 512: 11.6 against 14.7 us).
+constexpr int BIG_MIN_K_TILE = 512;
 int pick_tile(int ng, const ConvGeom& g) {
-  if (big_tile_fits(g) && g.Kpad >= BIG_MIN_K) return 4;
+  if (big_tile_fits(g) && g.Kpad >= BIG_MIN_K_TILE) return 4;
   // the 128x128 tile pays off through operand reuse over a long reduction; short reductions are
   // latency bound and want many small work-groups
   if (g.N % 128 == 0 && g.Kpad >= 512) {
