@@ -106,13 +106,18 @@ struct WgradItem {
 };
 // tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}; 9 = 128 x 128 (both channel counts
 // multiples of 128: each wave owns a 64 x 64 quadrant of the tile over the whole reduction)
-constexpr int WGRAD_CLASSES = 10;
+// 10 = whole 3x3 convolutions between 16 and 16 channels on 1024-pixel images: an item is a range of whole images
+// (m_begin, m_end multiples of 1024; tap, c0, n0 unused) and its work-group forms all nine taps from one staging
+constexpr int WGRAD_CLASSES = 11;
+constexpr int WGRAD_CLASS_T9 = 10;
 int wgrad_tile_class(int cin, int cout);
+int wgrad_item_class(const WgradGeom& g);      // WGRAD_CLASS_T9 where it applies, else wgrad_tile_class
+int wgrad_t9_lds_bytes(int H, int W);          // dynamic LDS of a class-10 launch for that image shape
 void wgrad_tile_dims(int tile_class, int* bc, int* bn);
 hipError_t wgrad_prepare();   // once per device before the first grouped launch
 hipError_t launch_wgrad_grouped(int tile_class, int g, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
                                 const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
-                                hipStream_t stream);
+                                hipStream_t stream, int lds_bytes = 0);
 
 // ---- image-resident runs of identity blocks (bf16 mode, BatchNorm on micro-batch statistics)
 // A run is a sequence of consecutive blocks of one kind and shape (bottleneck or basic) with stride 1 and identity

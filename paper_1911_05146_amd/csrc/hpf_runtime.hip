@@ -91,6 +91,7 @@ struct Plan {
   size_t params_off = 0, grads_off = 0, mom_off = 0, packed_off = 0, table_off = 0, mb_off = 0;
   size_t packed_elems = 0; int n_convs = 0;
   Loc g_stem;                          // gradient w.r.t. the stem output
+  int t9_h = 0, t9_w = 0;                          // image shape of the whole-convolution weight-gradient items (class 10)
   std::vector<WgradItem> items[WGRAD_CLASSES];     // deferred weight-gradient work, per tile class (bf16 mode)
   std::vector<WgradItem> items_nr[WGRAD_CLASSES];  // the same without the blocks of image-resident runs (those have a launch of their own)
   size_t items_nr_off[WGRAD_CLASSES] = {};
@@ -523,27 +524,60 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     }
     // output tiles per class: the pixel rows are split so that every class launches roughly 1500 work-groups
     // (5-6 per CU: enough to hide the staging latency) while atomics per output element stay few
+    auto geom_of = [&](const WConv& w) {
+      const ConvPlan& cv = *w.cv;
+      WgradGeom q{};
+      q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = w.cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
+      q.R = w.R; q.stride = cv.stride; q.pad = (w.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = w.c_valid;
+      return q;
+    };
+    // whole-convolution items (3x3 between 16 and 16 channels) share one launch, so one image shape: the first one's
+    auto class_of = [&](const WgradGeom& q) {
+      int cls = wgrad_item_class(q);
+      if (cls == WGRAD_CLASS_T9) {
+        if (P.t9_h == 0) { P.t9_h = q.H; P.t9_w = q.W; }
+        if (q.H != P.t9_h || q.W != P.t9_w) cls = wgrad_tile_class(q.Cin, q.N);
+      }
+      return cls;
+    };
     for (int pass = 0; pass < 2; ++pass) {   // pass 1: without the convolutions of image-resident runs
     if (pass == 1 && P.runs.empty()) break;
     long tiles_in_class[WGRAD_CLASSES] = {};
     for (const WConv& w : wc) {
       if (pass == 1 && w.in_run) continue;
-      const int cls = wgrad_tile_class(w.cin_run, w.cv->cout);
+      const int cls = class_of(geom_of(w));
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
-      tiles_in_class[cls] += (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
+      tiles_in_class[cls] += cls == WGRAD_CLASS_T9 ? 1 : (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
     }
     for (const WConv& w : wc) {
       if (pass == 1 && w.in_run) continue;
       const ConvPlan& cv = *w.cv;
-      WgradGeom q{};
-      q.b = d.microbatch; q.H = cv.h_in; q.W = cv.w_in; q.Cin = w.cin_run; q.Ho = cv.h_out; q.Wo = cv.w_out; q.N = cv.cout;
-      q.R = w.R; q.stride = cv.stride; q.pad = (w.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.c_valid = w.c_valid;
-      const int cls = wgrad_tile_class(w.cin_run, cv.cout);
+      const WgradGeom q = geom_of(w);
+      const int cls = class_of(q);
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
       (pass ? P.wg_nr_bytes : P.wg_bytes)[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
       (pass ? P.wg_nr_flops : P.wg_flops)[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
+      auto item = [&](int tap, int c0, int n0, int m_begin, int m_end) {
+        WgradItem it{};
+        it.a_off = w.a.kind == IN_MB ? w.a.off : WGRAD_DY_CALLER;
+        it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
+        it.dw_off = cv.w_off;
+        it.stats_off = w.bn ? w.bn->stats_off : WGRAD_NO_BN;
+        it.gamma_off = w.bn ? w.bn->g_off : 0;
+        it.beta_off = w.bn ? w.bn->b_off : 0;
+        it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
+        it.m_begin = m_begin; it.m_end = m_end;
+        (pass ? P.items_nr : P.items)[cls].push_back(it);
+      };
+      if (cls == WGRAD_CLASS_T9) {   // whole images per item; about 1000 work-groups (two per CU at 67 KiB of LDS, twice over)
+        int parts = (int)((1024 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
+        if (parts > q.b) parts = q.b;
+        const int imgs = (q.b + parts - 1) / parts, px = q.H * q.W;
+        for (int i0 = 0; i0 < q.b; i0 += imgs) item(0, 0, 0, i0 * px, (i0 + imgs < q.b ? i0 + imgs : q.b) * px);
+        continue;
+      }
       int splits = (int)((1536 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
       const int max_splits = (q.M + 127) / 128;
       if (splits > max_splits) splits = max_splits;
@@ -553,18 +587,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       for (int tap = 0; tap < w.R * w.R; ++tap)
         for (int c0 = 0; c0 < w.cin_run; c0 += bc)
           for (int n0 = 0; n0 < cv.cout; n0 += bn)
-            for (int sp = 0; sp < splits; ++sp) {
-              WgradItem it{};
-              it.a_off = w.a.kind == IN_MB ? w.a.off : WGRAD_DY_CALLER;
-              it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
-              it.dw_off = cv.w_off;
-              it.stats_off = w.bn ? w.bn->stats_off : WGRAD_NO_BN;
-              it.gamma_off = w.bn ? w.bn->g_off : 0;
-              it.beta_off = w.bn ? w.bn->b_off : 0;
-              it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
-              it.m_begin = sp * rows; it.m_end = (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M;
-              (pass ? P.items_nr : P.items)[cls].push_back(it);
-            }
+            for (int sp = 0; sp < splits; ++sp) item(tap, c0, n0, sp * rows, (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M);
     }
     }
   }
@@ -1148,7 +1171,8 @@ void run_backward(Ctx& c) {
       if (items.empty()) continue;
       c.seg(PROF_WGRAD, c.g * (res ? P.wg_nr_bytes : P.wg_bytes)[k], c.g * (res ? P.wg_nr_flops : P.wg_flops)[k]);
       c.chk(launch_wgrad_grouped(k, c.g, (const WgradItem*)(c.h->arena + (res ? P.items_nr_off : P.items_off)[k]), (int)items.size(),
-                                 bases, caller_dy, caller_a, c.h->params(), c.h->grads(), c.s),
+                                 bases, caller_dy, caller_a, c.h->params(), c.h->grads(), c.s,
+                                 k == WGRAD_CLASS_T9 ? wgrad_t9_lds_bytes(P.t9_h, P.t9_w) : 0),
             "wgrad_grouped");
     }
   }
@@ -1333,7 +1357,7 @@ hpf_status hpf_partition_create(const hpf_partition_desc* desc, void* device_are
     ok(hipMemcpy(p->running(), r0.data(), P.n_running * sizeof(float), hipMemcpyHostToDevice));
     ok(hipMemcpy(p->arena + P.bn_table_off, P.bn_table.data(), P.bn_table.size() * sizeof(BnRunDesc), hipMemcpyHostToDevice));
   }
-  if (!P.items[WGRAD_CLASSES - 1].empty()) ok(wgrad_prepare());
+  if (!P.items[9].empty() || !P.items[WGRAD_CLASS_T9].empty()) ok(wgrad_prepare());
   if (!P.runs.empty()) {
     ok(hipMemcpy(p->arena + P.res_off, P.res_blocks.data(), P.res_blocks.size() * sizeof(ResBlock), hipMemcpyHostToDevice));
     ok(hipMemset(p->abort_flag(), 0, sizeof(int)));

@@ -371,6 +371,145 @@ __global__ __launch_bounds__(256, 2) void k_wgrad_grouped_quad(const WgradItem* 
       }
 }
 
+// ---- whole 3x3 convolutions between 16 and 16 channels --------------------------------------------------------
+// With 16 channels on both sides a per-tap item moves 64 bytes per pixel for one MFMA per 32 pixels, nine times
+// per convolution.  Here one work-group takes whole images: both operands of an image go to LDS once, channel-major
+// (the input with a zero row above and below), and every 32-pixel step feeds nine MFMAs: the three filter rows are
+// three fragment reads of the input at row offsets, the three filter columns three variants of the one gradient
+// fragment, shifted by a pixel in registers (the pixel that crosses into the next 8-pixel chunk comes from the lane
+// that holds that chunk; at the image border it is zero).  Needs stride 1, H*W = 1024 and W in {8, 16, 32}.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int T9_P = 1024, T9_NU = T9_P / 256;   // pixels per image; staging units (pixel pair x 8 channels) per thread and operand
+__host__ __device__ constexpr int t9_sa(int H, int W) { return (H + 2) * W + 8; }   // channel stride of the padded input tile (bf16):
+__host__ __device__ constexpr int t9_sd(int H, int W) { return H * W + 8; }         // = 8 mod 16, so 16 channels hit 16 bank groups
+__host__ __device__ constexpr int t9_lds_bytes(int H, int W) { return 16 * (t9_sa(H, W) + t9_sd(H, W)) * 2; }
+constexpr int T9_MAX_LDS = t9_lds_bytes(32, 32);   // the widest rows pad the most
+
+__global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __restrict__ items, int ng, PtrTab bases, PtrTab caller_dy,
+                                                          PtrTab caller_a, const float* __restrict__ params, float* grads) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_t9[];
+  const WgradItem it = items[blockIdx.x];
+  const int H = it.g.H, W = it.g.W;
+  const int SA = t9_sa(H, W), SD = t9_sd(H, W);
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_t9);
+  bf16_t* sD = sA + 16 * SA;
+  uint32_t* sA32 = reinterpret_cast<uint32_t*>(sA);
+  uint32_t* sD32 = reinterpret_cast<uint32_t*>(sD);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hf = tid & 1;                       // the thread's channels: 8*hf .. 8*hf+7 (256 is even: the same for all its units)
+  // the zero rows of the input tile (the staging below never writes them)
+  for (int i = tid; i < 16 * W; i += 256) {
+    const int c = i / W, j = i - c * W;
+    const int row = j >= (W >> 1) ? H + 1 : 0, col2 = j >= (W >> 1) ? j - (W >> 1) : j;
+    sA32[((c * SA + row * W) >> 1) + col2] = 0u;
+  }
+
+  const int nimg = (it.m_end - it.m_begin) / T9_P, img0 = it.m_begin / T9_P;
+  const int total = ng * nimg;
+  uint4 ra[T9_NU][2], rd[T9_NU][2];
+  auto load_image = [&](int i) {
+    const int z = i / nimg, img = img0 + (i - z * nimg);
+    const char* base = (const char*)pick(bases, z);
+    const bf16_t* a = it.a_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_a, z) : (const bf16_t*)(base + it.a_off);
+    const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_dy, z) : (const bf16_t*)(base + it.dy_off);
+    a += (size_t)img * T9_P * 16 + hf * 8;
+    dy += (size_t)img * T9_P * 16 + hf * 8;
+#pragma unroll
+    for (int k = 0; k < T9_NU; ++k) {
+      const int pp = (tid + 256 * k) >> 1;      // pixel pair
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        ra[k][e] = *reinterpret_cast<const uint4*>(a + (size_t)(2 * pp + e) * 16);
+        rd[k][e] = *reinterpret_cast<const uint4*>(dy + (size_t)(2 * pp + e) * 16);
+      }
+    }
+  };
+  float2 cf[8];
+  auto bn_relu8 = [&](const uint4& q) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    uint32_t r_[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float x0 = __uint_as_float(w[i] << 16), x1 = __uint_as_float(w[i] & 0xffff0000u);
+      r_[i] = pack_bf16x2(fmaxf(fmaf(x0, cf[2 * i].x, cf[2 * i].y), 0.f), fmaxf(fmaf(x1, cf[2 * i + 1].x, cf[2 * i + 1].y), 0.f));
+    }
+    return make_uint4(r_[0], r_[1], r_[2], r_[3]);
+  };
+  // transposing store: channel e of the two pixels of a pair becomes one dword of channel row 8*hf + e
+  auto store_pair = [&](uint32_t* dst, int cstride2, const uint4& q0, const uint4& q1) {
+    const uint32_t w0[4] = {q0.x, q0.y, q0.z, q0.w}, w1[4] = {q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      dst[(2 * i) * cstride2] = (w0[i] & 0xffffu) | (w1[i] << 16);
+      dst[(2 * i + 1) * cstride2] = (w0[i] >> 16) | (w1[i] & 0xffff0000u);
+    }
+  };
+
+  floatx4 acc[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const int r = lane & 15, g = lane >> 4;
+  const bool bn = it.stats_off != WGRAD_NO_BN;
+  if (total > 0) load_image(0);
+  for (int i = 0; i < total; ++i) {
+    if (bn && i % nimg == 0) {                  // a new member: its BatchNorm statistics
+      const float* stt = (const float*)((const char*)pick(bases, i / nimg) + it.stats_off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = hf * 8 + e;
+        const float sc = params[it.gamma_off + c] * stt[16 + c];
+        cf[e] = make_float2(sc, params[it.beta_off + c] - stt[c] * sc);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < T9_NU; ++k) {
+      const int pp = (tid + 256 * k) >> 1;
+      uint4 q0 = ra[k][0], q1 = ra[k][1];
+      if (bn) { q0 = bn_relu8(q0); q1 = bn_relu8(q1); }
+      store_pair(sA32 + ((hf * 8 * SA + W) >> 1) + pp, SA >> 1, q0, q1);
+      store_pair(sD32 + ((hf * 8 * SD) >> 1) + pp, SD >> 1, rd[k][0], rd[k][1]);
+    }
+    if (i + 1 < total) load_image(i + 1);
+    __syncthreads();
+#pragma unroll 2
+    for (int st = 0; st < T9_P / 128; ++st) {
+      const int px = (wave * (T9_P / 128) + st) * 32 + g * 8;   // first pixel of the lane's chunk
+      const int col = px & (W - 1);
+      const u32x4 d = *reinterpret_cast<const u32x4*>(&sD[r * SD + px]);
+      uint32_t left = (uint32_t)__builtin_amdgcn_ds_bpermute((lane - 16) * 4, (int)d.w);
+      uint32_t right = (uint32_t)__builtin_amdgcn_ds_bpermute((lane + 16) * 4, (int)d.x);
+      if (col == 0) left = 0u;
+      if (col + 8 >= W) right = 0u;
+      // filter column 0 multiplies input pixel w-1 with gradient pixel w: per input pixel w' the gradient of w'+1; column 2: of w'-1
+      u32x4 dm, dp;
+      dm.x = __builtin_amdgcn_alignbit(d.y, d.x, 16); dm.y = __builtin_amdgcn_alignbit(d.z, d.y, 16);
+      dm.z = __builtin_amdgcn_alignbit(d.w, d.z, 16); dm.w = __builtin_amdgcn_alignbit(right, d.w, 16);
+      dp.x = __builtin_amdgcn_alignbit(d.x, left, 16); dp.y = __builtin_amdgcn_alignbit(d.y, d.x, 16);
+      dp.z = __builtin_amdgcn_alignbit(d.z, d.y, 16); dp.w = __builtin_amdgcn_alignbit(d.w, d.z, 16);
+      const bf16x8 f0 = __builtin_bit_cast(bf16x8, dm), f1 = __builtin_bit_cast(bf16x8, d), f2 = __builtin_bit_cast(bf16x8, dp);
+#pragma unroll
+      for (int fr = 0; fr < 3; ++fr) {          // filter row fr reads the input one row up, in place, one row down
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(&sA[r * SA + fr * W + px]);
+        acc[fr * 3 + 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, f0, acc[fr * 3 + 0], 0, 0, 0);
+        acc[fr * 3 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, f1, acc[fr * 3 + 1], 0, 0, 0);
+        acc[fr * 3 + 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, f2, acc[fr * 3 + 2], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  // the four waves' sums through LDS, then one atomic per output element and work-group
+  float* red = reinterpret_cast<float*>(smem_t9);
+  for (int i = tid; i < 9 * 256; i += 256) red[i] = 0.f;
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) atomicAdd(&red[t * 256 + (g * 4 + v) * 16 + r], acc[t][v]);
+  __syncthreads();
+  float* dw = grads + it.dw_off;
+  for (int i = tid; i < 9 * 256; i += 256) atomicAdd(&dw[i], red[i]);
+}
+
 template <int BC, int BN>
 hipError_t launch_tile(int ng, const PtrTab& a, const PtrTab& dy, float* dw, const WgradGeom& g, hipStream_t stream) {
   const int tiles = g.R * g.R * (g.Cin / BC) * (g.N / BN);
@@ -405,13 +544,23 @@ namespace {
 int tile_index(int c) { return c % 64 == 0 ? 2 : (c % 32 == 0 ? 1 : 0); }
 }  // namespace
 
+int wgrad_t9_lds_bytes(int H, int W) { return t9_lds_bytes(H, W); }
+
 int wgrad_tile_class(int cin, int cout) {
   if (cin % 128 == 0 && cout % 128 == 0) return 9;
   return tile_index(cin) * 3 + tile_index(cout);
 }
 
+int wgrad_item_class(const WgradGeom& g) {
+  if (g.Cin == 16 && g.N == 16 && g.c_valid == 16 && g.R == 3 && g.stride == 1 && g.H * g.W == T9_P &&
+      (g.W == 8 || g.W == 16 || g.W == 32))
+    return WGRAD_CLASS_T9;
+  return wgrad_tile_class(g.Cin, g.N);
+}
+
 void wgrad_tile_dims(int tile_class, int* bc, int* bn) {
   static const int sz[3] = {16, 32, 64};
+  if (tile_class == WGRAD_CLASS_T9) { *bc = 16; *bn = 16; return; }
   if (tile_class == 9) { *bc = 128; *bn = 128; return; }
   *bc = sz[tile_class / 3];
   *bn = sz[tile_class % 3];
@@ -420,13 +569,16 @@ void wgrad_tile_dims(int tile_class, int* bc, int* bn) {
 // The 128 x 128 class takes its LDS (two operand tiles and the BatchNorm coefficients) as dynamic shared memory:
 // state the size once per device before the first launch (not a stream operation, so it stays out of captured graphs).
 hipError_t wgrad_prepare() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_grouped_quad), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             WgradTile<128, 128, 64>::QUAD_BYTES);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_grouped_quad), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     WgradTile<128, 128, 64>::QUAD_BYTES);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad_grouped_t9), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             T9_MAX_LDS);
 }
 
 hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_dev, int n_items, const PtrTab& region_base,
                                 const PtrTab& caller_dy, const PtrTab& caller_a, const float* params, float* grads,
-                                hipStream_t stream) {
+                                hipStream_t stream, int lds_bytes) {
   if (n_items <= 0) return hipSuccess;
   if (ng < 1 || ng > MAX_GROUP) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_items);
@@ -446,6 +598,12 @@ hipError_t launch_wgrad_grouped(int tile_class, int ng, const WgradItem* items_d
       k_wgrad_grouped_quad<<<grid, 256, WgradTile<128, 128, 64>::QUAD_BYTES, stream>>>(items_dev, ng, region_base, caller_dy, caller_a, params,
                                                                                  grads);
       break;
+    case WGRAD_CLASS_T9: {
+      // all items of the class have one image shape (checked by the planner): the LDS size comes with the call
+      if (lds_bytes < 9 * 256 * 4 || lds_bytes > T9_MAX_LDS) return hipErrorInvalidValue;
+      k_wgrad_grouped_t9<<<grid, 256, (size_t)lds_bytes, stream>>>(items_dev, ng, region_base, caller_dy, caller_a, params, grads);
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
 #undef HPF_WG
