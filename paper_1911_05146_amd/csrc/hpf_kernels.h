@@ -103,6 +103,7 @@ struct WgradItem {
   unsigned long long gamma_off, beta_off;     //   relu(bn(a)) recomputed while staging (floats into the parameters)
   WgradGeom g;
   int tap, c0, n0, m_begin, m_end;
+  int sole;   // 1: no other item of the launch adds into this output tile (one split): plain read-add-write instead of atomics
 };
 // tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}; 9 = 128 x 128 (both channel counts
 // multiples of 128: each wave owns a 64 x 64 quadrant of the tile over the whole reduction)

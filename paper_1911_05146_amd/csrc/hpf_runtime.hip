@@ -542,13 +542,15 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
     };
     for (int pass = 0; pass < 2; ++pass) {   // pass 1: without the convolutions of image-resident runs
     if (pass == 1 && P.runs.empty()) break;
-    long tiles_in_class[WGRAD_CLASSES] = {};
+    long tiles_in_class[WGRAD_CLASSES] = {}, steps_in_class[WGRAD_CLASSES] = {};   // steps: 128 pixel rows of one output tile
     for (const WConv& w : wc) {
       if (pass == 1 && w.in_run) continue;
       const int cls = class_of(geom_of(w));
       int bc, bn;
       wgrad_tile_dims(cls, &bc, &bn);
-      tiles_in_class[cls] += cls == WGRAD_CLASS_T9 ? 1 : (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
+      const long tiles = cls == WGRAD_CLASS_T9 ? 1 : (long)w.R * w.R * (w.cin_run / bc) * (w.cv->cout / bn);
+      tiles_in_class[cls] += tiles;
+      steps_in_class[cls] += tiles * ((d.microbatch * w.cv->h_out * w.cv->w_out + 127) / 128);
     }
     for (const WConv& w : wc) {
       if (pass == 1 && w.in_run) continue;
@@ -559,7 +561,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       wgrad_tile_dims(cls, &bc, &bn);
       (pass ? P.wg_nr_bytes : P.wg_bytes)[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
       (pass ? P.wg_nr_flops : P.wg_flops)[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
-      auto item = [&](int tap, int c0, int n0, int m_begin, int m_end) {
+      auto item = [&](int tap, int c0, int n0, int m_begin, int m_end, bool sole) {
         WgradItem it{};
         it.a_off = w.a.kind == IN_MB ? w.a.off : WGRAD_DY_CALLER;
         it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
@@ -568,18 +570,23 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         it.gamma_off = w.bn ? w.bn->g_off : 0;
         it.beta_off = w.bn ? w.bn->b_off : 0;
         it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
-        it.m_begin = m_begin; it.m_end = m_end;
+        it.m_begin = m_begin; it.m_end = m_end; it.sole = sole ? 1 : 0;
         (pass ? P.items_nr : P.items)[cls].push_back(it);
       };
       if (cls == WGRAD_CLASS_T9) {   // whole images per item; about 1000 work-groups (two per CU at 67 KiB of LDS, twice over)
         int parts = (int)((1024 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
         if (parts > q.b) parts = q.b;
         const int imgs = (q.b + parts - 1) / parts, px = q.H * q.W;
-        for (int i0 = 0; i0 < q.b; i0 += imgs) item(0, 0, 0, i0 * px, (i0 + imgs < q.b ? i0 + imgs : q.b) * px);
+        for (int i0 = 0; i0 < q.b; i0 += imgs) item(0, 0, 0, i0 * px, (i0 + imgs < q.b ? i0 + imgs : q.b) * px, imgs >= q.b);
         continue;
       }
-      int splits = (int)((1536 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
+      // Items of equal length: a class may mix convolutions with few tiles over many pixel rows and ones with many
+      // tiles over few rows (VGG-16: 128 -> 128 channels at 16x16 next to 4096 x 4096 over 16 rows); with one split
+      // count for all, the former made a handful of work-groups run 64 times longer than the rest of the launch.
+      const long want = 1536;
+      const long per_item = (steps_in_class[cls] + want - 1) / want;   // steps of 128 rows an item should take
       const int max_splits = (q.M + 127) / 128;
+      int splits = (int)((max_splits + per_item - 1) / per_item);
       if (splits > max_splits) splits = max_splits;
       if (splits < 1) splits = 1;
       const int rows = ((q.M + splits - 1) / splits + 127) / 128 * 128;
@@ -587,7 +594,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       for (int tap = 0; tap < w.R * w.R; ++tap)
         for (int c0 = 0; c0 < w.cin_run; c0 += bc)
           for (int n0 = 0; n0 < cv.cout; n0 += bn)
-            for (int sp = 0; sp < splits; ++sp) item(tap, c0, n0, sp * rows, (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M);
+            for (int sp = 0; sp < splits; ++sp) item(tap, c0, n0, sp * rows, (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M, splits == 1);
     }
     }
   }
