@@ -261,6 +261,30 @@ struct WFragsL {
       }
     }
   }
+  // a column block of a wider matrix (rows ld apart), into / from the staging registers st[OFF .. OFF+NU)
+  template <int OFF, int N>
+  __device__ __forceinline__ void issue_cols(u32x4 (&st)[N], const bf16_t* w, int ld, int fr_, int fk_) {
+    static_assert(OFF + NU <= N, "staging registers");
+    fr = fr_; fk = fk_;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT, uu = u < UNITS ? u : 0;
+      const int row = uu / (LEN / 8), col = uu - row * (LEN / 8);
+      st[OFF + i] = *reinterpret_cast<const u32x4*>(w + (size_t)row * ld + col * 8);
+    }
+  }
+  template <int OFF, int N>
+  __device__ __forceinline__ void commit_from(const u32x4 (&st)[N], bf16_t* sw) {
+    s = sw;
+#pragma unroll
+    for (int i = 0; i < NU; ++i) {
+      const int u = threadIdx.x + i * RES_NT;
+      if (u < UNITS) {
+        const int row = u / (LEN / 8), col = u - row * (LEN / 8);
+        *reinterpret_cast<u32x4*>(sw + row * STRIDE + col * 8) = st[OFF + i];
+      }
+    }
+  }
   __device__ __forceinline__ bf16x8 get(int kt, int nt) const {
     return *reinterpret_cast<const bf16x8*>(s + (nt * 16 + fr) * STRIDE + kt * 32 + fk);
   }
@@ -279,7 +303,8 @@ __device__ __forceinline__ void w_commit(WF& w, const u32x4 (&st)[N], bf16_t* sw
 // 3x3 convolution (stride 1, zero padding) of a [P][MID] tile in LDS, both directions:
 //   forward : out(p,q) += src(p+r-1, q+s-1) * W[r][s]       weights [MID][9*MID], k = tap*MID + c
 //   backward: out(p,q) += src(p+1-r, q+1-s) * W[r][s]^T     weights [MID][9*MID], k = tap*MID + n
-template <int MID, int PTW, bool BACKWARD, class WF>
+// TAP0, NTAPS: the filter taps this call adds (wfr then holds the columns of these taps only, from k = 0).
+template <int MID, int PTW, bool BACKWARD, int TAP0 = 0, int NTAPS = 9, class WF>
 __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const WF& wfr, int H, int W, int npt, int wave, int fr, int fk,
                                              floatx4 (&acc)[PTW][MID / 16]) {
   constexpr int MS = MID + 8;
@@ -321,14 +346,14 @@ __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const WF& wfr, i
     return;
   }
 #pragma unroll
-  for (int tap = 0; tap < 9; ++tap) {
+  for (int tap = TAP0; tap < TAP0 + NTAPS; ++tap) {
     const int r = tap / 3, s = tap % 3;
     const int dh = BACKWARD ? 1 - r : r - 1, dw = BACKWARD ? 1 - s : s - 1;
 #pragma unroll
     for (int ks = 0; ks < MID / 32; ++ks) {
       bf16x8 wf[MID / 16];
 #pragma unroll
-      for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = wfr.get(tap * (MID / 32) + ks, nt);
+      for (int nt = 0; nt < MID / 16; ++nt) wf[nt] = wfr.get((tap - TAP0) * (MID / 32) + ks, nt);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         if (wave + j * RES_NWV < npt) {
@@ -426,10 +451,15 @@ __device__ __forceinline__ void running_coef(float2* coef, const float* run, con
 // only the output of the last block is written.
 // HW: 0 = image height and width from the arguments; 16 = 16 x 16 pixels as compile-time constants in the 3x3 convolution
 // (the shape of the benchmark partition: pixel-row decodes and tap addresses become shifts).
-// WL: the weights go through LDS (WFragsL): for shapes with one pixel tile per wave and LDS to spare (256-64 at 8x8).
-template <int C, int MID, int PTW, bool PRE, bool INFER = false, int HW = 0, bool WL = false>
+// WL: the weights go through LDS (WFragsL).  1: into an area of their own, for shapes with LDS to spare (256-64 at 8x8).
+// 2: into the MID-wide tile that is idle at the time (128-64 at 16x16, whose tiles fill the LDS: eight waves fetching
+// the same 106 KB of weights per block from L2 were what bound that shape): conv1's matrix goes to the c2 tile (dead
+// since the conv3 before), conv3's to the c1 tile (dead since conv2), conv2's in three rounds of three filter taps to
+// the c2 tile, which the convolution only writes when all rounds are done.
+template <int C, int MID, int PTW, bool PRE, bool INFER = false, int HW = 0, int WL = 0>
 __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const int gath_own) {
   static_assert(!(WL && (PRE || INFER)), "the LDS form replaces the fetch-where-used form of the training kernels");
+  constexpr bool WT = WL == 2;   // staged in the tiles that are idle at the time
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -455,11 +485,17 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   float* gathB = gath_own ? own : reinterpret_cast<float*>(smB);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
-  std::conditional_t<WL, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w1;            // conv1 [MID][C]
-  std::conditional_t<WL, WFragsL<9 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>> w2;  // conv2 [MID][9*MID]
-  std::conditional_t<WL, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w3;            // conv3 [C][MID]
-  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
-  u32x4 wst[WL ? (9 * MID / 32 * (MID / 16) + 7) / 8 : 1];                                  // WL: its units on their way
+  std::conditional_t<WL != 0, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w1;            // conv1 [MID][C]
+  std::conditional_t<WL == 1, WFragsL<9 * MID / 32, MID / 16>,
+                     std::conditional_t<WT, WFragsL<3 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>>> w2;  // conv2 [MID][9*MID] (WT: three taps of it)
+  std::conditional_t<WL != 0, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w3;            // conv3 [C][MID]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL == 1: the staged matrix
+  bf16_t* const sW1 = WT ? smB : sW;
+  bf16_t* const sW3 = WT ? smA : sW;
+  constexpr int W2NU = (3 * MID * MID / 8 + RES_NT - 1) / RES_NT;                            // WT: units per thread and round
+  u32x4 wst[WL == 1 ? (9 * MID / 32 * (MID / 16) + 7) / 8 : WT ? 3 * W2NU : 1];             // the units on their way
+  static_assert(!WT || (MID * (C + 8) <= 256 * (MID + 8) && C * (MID + 8) <= 256 * (MID + 8) && MID * (3 * MID + 8) <= 256 * (MID + 8)),
+                "the matrices fit a MID-wide tile of 256 pixels");
 
   {
     const ResBlock B0 = a.blocks[0];
@@ -472,7 +508,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
-      w_commit(w1, wst, sW);   // the barrier at the end of the merge lies between this and conv1
+      w_commit(w1, wst, sW1);   // the barrier at the end of the merge lies between this and conv1
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
     }
@@ -515,7 +551,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
             *reinterpret_cast<uint2*>(smA + (pt * 16 + fr) * MS + nt * 16 + fq * 4) = pack4(acc[j][nt]);
       }
     }
-    w_issue(w2, wst, a.packed + B.wf_off[1], 9 * MID, fr, fk);
+    if constexpr (WT) {   // all three rounds are asked for now: the exchange below hides the latency
+      w2.template issue_cols<0>(wst, a.packed + B.wf_off[1], 9 * MID, fr, fk);
+      w2.template issue_cols<W2NU>(wst, a.packed + B.wf_off[1] + 3 * MID, 9 * MID, fr, fk);
+      w2.template issue_cols<2 * W2NU>(wst, a.packed + B.wf_off[1] + 6 * MID, 9 * MID, fr, fk);
+    } else {
+      w_issue(w2, wst, a.packed + B.wf_off[1], 9 * MID, fr, fk);
+    }
     __syncthreads();
     if (INFER) {
       running_coef<MID>(coefM, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
@@ -524,9 +566,10 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathB, a.abort_flag)) return;
       tile_store<MID>(cx.tensor(B.c1_off) + (size_t)me * P * MID, smA, P);   // after the polls (measured: 2 % faster than before them)
       ++phase;
-      w_commit(w2, wst, sW);   // conv1 is behind the barrier above the statistics; conv2 behind the ones below
+      if constexpr (!WT) w_commit(w2, wst, sW);   // conv1 is behind the barrier above the statistics; conv2 behind the ones below
       merge_coef<MID>(gathB, a.nmem, P, a.eps, a.params + B.gamma_off[1], a.params + B.beta_off[1], coefM,
                       me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[1]) : nullptr);
+      if constexpr (WT) w2.template commit_from<0>(wst, smB);   // the gathered records in that tile are behind the merge's barrier
     }
     tile_bn_relu<MID>(smA, coefM, P);   // once, not per filter tap
     __syncthreads();
@@ -537,7 +580,20 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < MID / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<MID, PTW, false>(smA, w2, H, W, npt, wave, fr, fk, acc);
+      if constexpr (WT) {   // a barrier on either side of every re-staging; the last one frees the tile for the output
+        conv3x3_tile<MID, PTW, false, 0, 3>(smA, w2, H, W, npt, wave, fr, fk, acc);
+        __syncthreads();
+        w2.template commit_from<W2NU>(wst, smB);
+        __syncthreads();
+        conv3x3_tile<MID, PTW, false, 3, 3>(smA, w2, H, W, npt, wave, fr, fk, acc);
+        __syncthreads();
+        w2.template commit_from<2 * W2NU>(wst, smB);
+        __syncthreads();
+        conv3x3_tile<MID, PTW, false, 6, 3>(smA, w2, H, W, npt, wave, fr, fk, acc);
+        __syncthreads();
+      } else {
+        conv3x3_tile<MID, PTW, false>(smA, w2, H, W, npt, wave, fr, fk, acc);
+      }
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -556,9 +612,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       if (!collect<4>(slot(), a.nmem, 2 * MID, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       tile_store<MID>(cx.tensor(B.c2_off) + (size_t)me * P * MID, smB, P);
       ++phase;
-      w_commit(w3, wst, sW);
+      if constexpr (!WT) w_commit(w3, wst, sW);
       merge_coef<MID>(gathA, a.nmem, P, a.eps, a.params + B.gamma_off[2], a.params + B.beta_off[2], coefM,
                       me == 0 ? reinterpret_cast<float*>(cx.base + B.stats_off[2]) : nullptr);
+      if constexpr (WT) {   // into the tile the records were gathered in: behind the merge's barrier, and one before conv3
+        w_commit(w3, wst, sW3);
+        __syncthreads();
+      }
     }
     // ---- conv3 (1x1, MID -> C) on relu(bn3(c2)) + residual: y = x + branch, written over x in LDS
     {
@@ -605,7 +665,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     if (more) {
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
-      w_commit(w1, wst, sW);
+      w_commit(w1, wst, sW1);
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
     }
@@ -740,9 +800,12 @@ struct BwdLoads {
   }
 };
 
-template <int C, int MID, int PTW, bool PRE, int HW = 0, bool WL = false>
+template <int C, int MID, int PTW, bool PRE, int HW = 0, int WL = 0>
 __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const int gath_own) {
   static_assert(!(WL && PRE), "the LDS form replaces the fetch-where-used form");
+  // WL == 2: the matrices go to the idle MID-wide tile: conv3's and conv1's to the dc2 tile (idle between the conv2
+  // contraction and the BN3 backward of the next block), conv2's in three rounds of three taps to the dc1 tile
+  constexpr bool WT = WL == 2;
   constexpr int XS = C + 8, MS = MID + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
@@ -768,17 +831,22 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
 
-  std::conditional_t<WL, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w3;            // conv3 data gradient [MID][C]
-  std::conditional_t<WL, WFragsL<9 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>> w2;  // conv2 data gradient [MID][9*MID]
-  std::conditional_t<WL, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w1;            // conv1 data gradient [C][MID]
-  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
-  u32x4 wst[WL ? (9 * MID / 32 * (MID / 16) + 7) / 8 : 1];                                  // WL: its units on their way
+  std::conditional_t<WL != 0, WFragsL<C / 32, MID / 16>, WFrags<C / 32, MID / 16, PRE>> w3;            // conv3 data gradient [MID][C]
+  std::conditional_t<WL == 1, WFragsL<9 * MID / 32, MID / 16>,
+                     std::conditional_t<WT, WFragsL<3 * MID / 32, MID / 16>, WFrags<9 * MID / 32, MID / 16, PRE>>> w2;  // conv2 data gradient [MID][9*MID] (WT: three taps of it)
+  std::conditional_t<WL != 0, WFragsL<MID / 32, C / 16>, WFrags<MID / 32, C / 16, PRE>> w1;            // conv1 data gradient [C][MID]
+  bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL == 1: the staged matrix
+  bf16_t* const sW13 = WT ? sdc : sW;
+  constexpr int W2NU = (3 * MID * MID / 8 + RES_NT - 1) / RES_NT;                            // WT: units per thread and round
+  u32x4 wst[WL == 1 ? (9 * MID / 32 * (MID / 16) + 7) / 8 : WT ? 3 * W2NU : 1];             // the units on their way
+  static_assert(!WT || (MID * (C + 8) <= 256 * (MID + 8) && C * (MID + 8) <= 256 * (MID + 8) && MID * (3 * MID + 8) <= 256 * (MID + 8)),
+                "the matrices fit a MID-wide tile of 256 pixels");
   {
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
-    if constexpr (WL) {   // the first block's conv3 matrix; later ones are staged behind the exchange before
+    if constexpr (WL != 0) {   // the first block's conv3 matrix; later ones are staged behind the exchange before
       w_issue(w3, wst, a.packed + BL.wd_off[2], C, fr, fk);
-      w_commit(w3, wst, sW);
+      w_commit(w3, wst, sW13);
     }
   }
   __syncthreads();   // the first contraction reads the tile right away
@@ -791,7 +859,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
     floatx4 acc3[PTW][MID / 16];
     {
       BwdLoads<C, MID, PTW> ld;
-      if constexpr (!WL) w3.load(a.packed + B.wd_off[2], C, fr, fk);
+      if constexpr (WL == 0) w3.load(a.packed + B.wd_off[2], C, fr, fk);
       ld.issue(B, cx, a.params, me, P, npt, wave, fr, fq);
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
@@ -827,7 +895,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
           xin[j][nt] = pt < npt ? xc2[j][nt] : make_uint2(0u, 0u);
         }
       }
-      w_issue(w2, wst, a.packed + B.wd_off[1], 9 * MID, fr, fk);
+      if constexpr (WT) {   // all three rounds are asked for now: the exchange below hides the latency
+        w2.template issue_cols<0>(wst, a.packed + B.wd_off[1], 9 * MID, fr, fk);
+        w2.template issue_cols<W2NU>(wst, a.packed + B.wd_off[1] + 3 * MID, 9 * MID, fr, fk);
+        w2.template issue_cols<2 * W2NU>(wst, a.packed + B.wd_off[1] + 6 * MID, 9 * MID, fr, fk);
+      } else {
+        w_issue(w2, wst, a.packed + B.wd_off[1], 9 * MID, fr, fk);
+      }
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<MID, PTW>(acc, xin, cf3, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
                                      me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[2]) : nullptr, a.abort_flag,
@@ -836,7 +910,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                      }))
         return;
       ++phase;
-      w_commit(w2, wst, sW);   // conv3's matrix was last read above the barrier that follows the tables
+      if constexpr (WT) w2.template commit_from<0>(wst, sm2);   // that tile was last read as the gather area of the block before
+      else w_commit(w2, wst, sW);   // conv3's matrix was last read above the barrier that follows the tables
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc2_off) + (size_t)me * P * MID, sdc, P);
@@ -859,7 +934,19 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
             x1[j][nt] = *reinterpret_cast<const uint2*>(xg + (size_t)((pt < npt ? pt : 0) * 16 + fr) * C + nt * 16 + fq * 4);
         }
       }
-      conv3x3_tile<MID, PTW, true>(sdc, w2, H, W, npt, wave, fr, fk, acc);
+      if constexpr (WT) {   // a barrier on either side of every re-staging (the BN backward below starts with one)
+        conv3x3_tile<MID, PTW, true, 0, 3>(sdc, w2, H, W, npt, wave, fr, fk, acc);
+        __syncthreads();
+        w2.template commit_from<W2NU>(wst, sm2);
+        __syncthreads();
+        conv3x3_tile<MID, PTW, true, 3, 3>(sdc, w2, H, W, npt, wave, fr, fk, acc);
+        __syncthreads();
+        w2.template commit_from<2 * W2NU>(wst, sm2);
+        __syncthreads();
+        conv3x3_tile<MID, PTW, true, 6, 3>(sdc, w2, H, W, npt, wave, fr, fk, acc);
+      } else {
+        conv3x3_tile<MID, PTW, true>(sdc, w2, H, W, npt, wave, fr, fk, acc);
+      }
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -877,7 +964,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                      }))
         return;
       ++phase;
-      w_commit(w1, wst, sW);
+      w_commit(w1, wst, sW13);   // WT: dc2 in that tile was last read by the contraction above the exchange
     }
     __syncthreads();
     tile_store<MID>(cx.tensor(B.dc1_off) + (size_t)me * P * MID, sm2, P);
@@ -902,7 +989,7 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
         }
       }
       __syncthreads();   // all waves are done with the small tiles: they become the gather area
-      if constexpr (WL)
+      if constexpr (WL != 0)
         if (bi > 0) w_issue(w3, wst, a.packed + a.blocks[bi - 1].wd_off[2], C, fr, fk);   // the next block's conv3 matrix
       float* gath = gath_own ? own : reinterpret_cast<float*>(sm2);   // dc1 left the tile above
       if (!bn_relu_bwd_acc<C, PTW>(acc, x1, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
@@ -916,8 +1003,8 @@ __global__ void __launch_bounds__(RES_NT) k_res_backward(const ResArgs a, const 
                                    }))
         return;
       ++phase;
-      if constexpr (WL)
-        if (bi > 0) w_commit(w3, wst, sW);
+      if constexpr (WL != 0)
+        if (bi > 0) w_commit(w3, wst, sW13);   // WT: conv1's matrix in that tile was last read above the barrier before the exchange
     }
     __syncthreads();   // dx is complete; the BN tables and the small tiles of this block are no longer read
     tile_store<C>(cx.tensor(B.gx_off) + (size_t)me * P * C, sdy, P);
@@ -2618,12 +2705,12 @@ hipError_t resident_prepare() {
                         reinterpret_cast<const void*>(k_res_wgrad<128, 64>)};
   for (const void* f : wide)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  const void* sq[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, false, 16>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, false, 16>),
-                      reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true, 16>),       reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false, 16>)};
+  const void* sq[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, false, 16>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, false, 16, 2>),
+                      reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true, 16>),       reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false, 16, 2>)};
   for (const void* f : sq)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, false, 0, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_v1_wgrad<32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_v1_wgrad<64>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
@@ -2672,14 +2759,14 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   const size_t lds = fwd_lds(C, MID, a.H * a.W, a.nmem, &own);
   const bool sq16 = a.H == 16 && a.W == 16;
   if (C == 128 && MID == 64)
-    return sq16 ? launch_res(k_res_forward<128, 64, 2, false, false, 16>, lds, own, g, a, stream)
+    return sq16 ? launch_res(k_res_forward<128, 64, 2, false, false, 16, 2>, lds, own, g, a, stream)   // weights through the idle tiles
                 : launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128)
     return sq16 ? launch_res(k_res_forward<128, 32, 2, true, false, 16>, lds, own, g, a, stream)
                 : launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   // one pixel tile per wave: the weights through LDS where the tiles leave room for them (8x8 images)
   if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
-    return launch_res(k_res_forward<256, 64, 1, false, false, 0, true>, lds + wl_bytes(C, MID), own, g, a, stream);
+    return launch_res(k_res_forward<256, 64, 1, false, false, 0, 1>, lds + wl_bytes(C, MID), own, g, a, stream);
   return launch_res(k_res_forward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
@@ -2759,13 +2846,13 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   const size_t lds = bwd_lds(C, MID, a.H * a.W, a.nmem, &own);
   const bool sq16 = a.H == 16 && a.W == 16;
   if (C == 128 && MID == 64)
-    return sq16 ? launch_res(k_res_backward<128, 64, 2, false, 16>, lds, own, g, a, stream)
+    return sq16 ? launch_res(k_res_backward<128, 64, 2, false, 16, 2>, lds, own, g, a, stream)
                 : launch_res(k_res_backward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128)
     return sq16 ? launch_res(k_res_backward<128, 32, 2, true, 16>, lds, own, g, a, stream)
                 : launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
   if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
-    return launch_res(k_res_backward<256, 64, 1, false, 0, true>, lds + wl_bytes(C, MID), own, g, a, stream);
+    return launch_res(k_res_backward<256, 64, 1, false, 0, 1>, lds + wl_bytes(C, MID), own, g, a, stream);
   return launch_res(k_res_backward<256, 64, 1, false>, lds, own, g, a, stream);
 }
 
