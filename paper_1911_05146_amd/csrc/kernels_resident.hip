@@ -336,10 +336,10 @@ __device__ __forceinline__ void conv3x3_tile(const bf16_t* src, const WF& wfr, i
         }
       }
     };
-    if constexpr (WF::pre) {   // fragments in registers: the step index must be a constant
+    if constexpr (WF::pre && !WF::staged) {   // fragments in registers: the step index must be a constant
 #pragma unroll
       for (int st = 0; st < 5; ++st) step(st);
-    } else {                   // fetched where used: a rolled loop keeps the addresses of 40 operand reads out of the registers
+    } else {                   // fetched where used or read from LDS: a rolled loop keeps the addresses of 40 operand reads out of the registers
 #pragma unroll 1
       for (int st = 0; st < 5; ++st) step(st);
     }
@@ -2709,6 +2709,8 @@ hipError_t resident_prepare() {
                       reinterpret_cast<const void*>(k_res_backward<128, 32, 2, true, 16>),       reinterpret_cast<const void*>(k_res_backward<128, 64, 2, false, 16, 2>)};
   for (const void* f : sq)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<128, 32, 2, false, false, 16, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<128, 32, 2, false, 16, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, false, 0, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false, 0, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_v1_wgrad<32>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2716,6 +2718,7 @@ hipError_t resident_prepare() {
   const void* v1[] = {reinterpret_cast<const void*>(k_v1_forward<32, 2, true>),  reinterpret_cast<const void*>(k_v1_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>),
+                      reinterpret_cast<const void*>(k_v1_forward<16, 8, false, true>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false, true>),
                       reinterpret_cast<const void*>(k_v1_forward<64, 1, false, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false, true>),
                       reinterpret_cast<const void*>(k_bb_forward<64, 1, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false, true>)};
   for (const void* f : v1)
@@ -2743,7 +2746,9 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   int own = 0;
   if (kind == 2) {
     const size_t lds = v1_lds(C, a.H * a.W, a.nmem, false, &own);
-    if (C == 16) return launch_res(k_v1_forward<16, 8, false>, lds, own, g, a, stream);
+    const size_t wl16 = (size_t)16 * (160 + 8) * 2;   // the [16][160] matrices through LDS: five L2 round trips per convolution less
+    if (C == 16) return lds + wl16 <= RES_LDS_BYTES ? launch_res(k_v1_forward<16, 8, false, true>, lds + wl16, own, g, a, stream)
+                                                    : launch_res(k_v1_forward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
     const size_t wl = (size_t)C * (9 * C + 8) * 2;   // one pixel tile per wave: the 3x3 matrices through LDS where they fit
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_forward<64, 1, false, true>, lds + wl, own, g, a, stream);
@@ -2762,7 +2767,9 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
     return sq16 ? launch_res(k_res_forward<128, 64, 2, false, false, 16, 2>, lds, own, g, a, stream)   // weights through the idle tiles
                 : launch_res(k_res_forward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128)
-    return sq16 ? launch_res(k_res_forward<128, 32, 2, true, false, 16>, lds, own, g, a, stream)
+    return sq16 ? (lds + wl_bytes(C, MID) <= RES_LDS_BYTES
+                       ? launch_res(k_res_forward<128, 32, 2, false, false, 16, 1>, lds + wl_bytes(C, MID), own, g, a, stream)
+                       : launch_res(k_res_forward<128, 32, 2, true, false, 16>, lds, own, g, a, stream))
                 : launch_res(k_res_forward<128, 32, 2, true>, lds, own, g, a, stream);
   // one pixel tile per wave: the weights through LDS where the tiles leave room for them (8x8 images)
   if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
@@ -2830,7 +2837,9 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   int own = 0;
   if (kind == 2) {
     const size_t lds = v1_lds(C, a.H * a.W, a.nmem, true, &own);
-    if (C == 16) return launch_res(k_v1_backward<16, 8, false>, lds, own, g, a, stream);
+    const size_t wl16 = (size_t)16 * (160 + 8) * 2;
+    if (C == 16) return lds + wl16 <= RES_LDS_BYTES ? launch_res(k_v1_backward<16, 8, false, true>, lds + wl16, own, g, a, stream)
+                                                    : launch_res(k_v1_backward<16, 8, false>, lds, own, g, a, stream);
     if (C == 32) return launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
     const size_t wl = (size_t)C * (9 * C + 8) * 2;
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_backward<64, 1, false, true>, lds + wl, own, g, a, stream);
@@ -2849,7 +2858,9 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
     return sq16 ? launch_res(k_res_backward<128, 64, 2, false, 16, 2>, lds, own, g, a, stream)
                 : launch_res(k_res_backward<128, 64, 2, false>, lds, own, g, a, stream);
   if (C == 128)
-    return sq16 ? launch_res(k_res_backward<128, 32, 2, true, 16>, lds, own, g, a, stream)
+    return sq16 ? (lds + wl_bytes(C, MID) <= RES_LDS_BYTES
+                       ? launch_res(k_res_backward<128, 32, 2, false, 16, 1>, lds + wl_bytes(C, MID), own, g, a, stream)
+                       : launch_res(k_res_backward<128, 32, 2, true, 16>, lds, own, g, a, stream))
                 : launch_res(k_res_backward<128, 32, 2, true>, lds, own, g, a, stream);
   if (lds + wl_bytes(C, MID) <= RES_LDS_BYTES)
     return launch_res(k_res_backward<256, 64, 1, false, 0, 1>, lds + wl_bytes(C, MID), own, g, a, stream);
