@@ -2696,6 +2696,7 @@ hipError_t resident_prepare() {
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_res_backward<256, 64, 1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* bb[] = {reinterpret_cast<const void*>(k_bb_forward<32, 2, true>),  reinterpret_cast<const void*>(k_bb_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_bb_backward<32, 2, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false>),
+                      reinterpret_cast<const void*>(k_bb_forward<32, 2, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<32, 2, false, true>),
                       reinterpret_cast<const void*>(k_bb_wgrad<32>),             reinterpret_cast<const void*>(k_bb_wgrad<64>)};
   for (const void* f : bb)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2719,6 +2720,7 @@ hipError_t resident_prepare() {
                       reinterpret_cast<const void*>(k_v1_backward<32, 2, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false>),
                       reinterpret_cast<const void*>(k_v1_forward<16, 8, false, true>),  reinterpret_cast<const void*>(k_v1_backward<16, 8, false, true>),
+                      reinterpret_cast<const void*>(k_v1_forward<32, 2, false, true>),  reinterpret_cast<const void*>(k_v1_backward<32, 2, false, true>),
                       reinterpret_cast<const void*>(k_v1_forward<64, 1, false, true>), reinterpret_cast<const void*>(k_v1_backward<64, 1, false, true>),
                       reinterpret_cast<const void*>(k_bb_forward<64, 1, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false, true>)};
   for (const void* f : v1)
@@ -2749,14 +2751,22 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
     const size_t wl16 = (size_t)16 * (160 + 8) * 2;   // the [16][160] matrices through LDS: five L2 round trips per convolution less
     if (C == 16) return lds + wl16 <= RES_LDS_BYTES ? launch_res(k_v1_forward<16, 8, false, true>, lds + wl16, own, g, a, stream)
                                                     : launch_res(k_v1_forward<16, 8, false>, lds, own, g, a, stream);
-    if (C == 32) return launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
+    if (C == 32) {
+      const size_t wl32 = (size_t)32 * (288 + 8) * 2;
+      return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_v1_forward<32, 2, false, true>, lds + wl32, own, g, a, stream)
+                                         : launch_res(k_v1_forward<32, 2, true>, lds, own, g, a, stream);
+    }
     const size_t wl = (size_t)C * (9 * C + 8) * 2;   // one pixel tile per wave: the 3x3 matrices through LDS where they fit
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_forward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_v1_forward<64, 1, false>, lds, own, g, a, stream);
   }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
-    if (C == 32) return launch_res(k_bb_forward<32, 2, true>, lds, own, g, a, stream);
+    if (C == 32) {
+      const size_t wl32 = (size_t)32 * (288 + 8) * 2;
+      return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_bb_forward<32, 2, false, false, true>, lds + wl32, own, g, a, stream)
+                                         : launch_res(k_bb_forward<32, 2, true>, lds, own, g, a, stream);
+    }
     const size_t wl = (size_t)C * (9 * C + 8) * 2;
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_bb_forward<64, 1, false, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_bb_forward<64, 1, false>, lds, own, g, a, stream);
@@ -2840,14 +2850,22 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
     const size_t wl16 = (size_t)16 * (160 + 8) * 2;
     if (C == 16) return lds + wl16 <= RES_LDS_BYTES ? launch_res(k_v1_backward<16, 8, false, true>, lds + wl16, own, g, a, stream)
                                                     : launch_res(k_v1_backward<16, 8, false>, lds, own, g, a, stream);
-    if (C == 32) return launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
+    if (C == 32) {
+      const size_t wl32 = (size_t)32 * (288 + 8) * 2;
+      return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_v1_backward<32, 2, false, true>, lds + wl32, own, g, a, stream)
+                                         : launch_res(k_v1_backward<32, 2, true>, lds, own, g, a, stream);
+    }
     const size_t wl = (size_t)C * (9 * C + 8) * 2;
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_v1_backward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_v1_backward<64, 1, false>, lds, own, g, a, stream);
   }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
-    if (C == 32) return launch_res(k_bb_backward<32, 2, true>, lds, own, g, a, stream);
+    if (C == 32) {
+      const size_t wl32 = (size_t)32 * (288 + 8) * 2;
+      return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_bb_backward<32, 2, false, true>, lds + wl32, own, g, a, stream)
+                                         : launch_res(k_bb_backward<32, 2, true>, lds, own, g, a, stream);
+    }
     const size_t wl = (size_t)C * (9 * C + 8) * 2;
     if (lds + wl <= RES_LDS_BYTES) return launch_res(k_bb_backward<64, 1, false, true>, lds + wl, own, g, a, stream);
     return launch_res(k_bb_backward<64, 1, false>, lds, own, g, a, stream);
