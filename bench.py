@@ -31,7 +31,7 @@ PEAK_HBM = 8.0e12         # bytes/s
 # HBM bytes per launch from rocprofv3 counter runs of this same command (FETCH_SIZE + WRITE_SIZE, each
 # scaled by what the counter reads for a plain device copy of known size); the summaries with the
 # commands are under profiles/.  Keyed by (kernel class, configuration).
-MEASURED_TRAFFIC = {("resident_backward", 3): 1.135e9}
+MEASURED_TRAFFIC = {("resident_backward", 3): 1.150e9}
 TRAFFIC_SOURCE = ("constant taken from profiles/hbm_traffic_resnet1001_partition.md (two rocprofv3 --pmc runs of this "
                   "command), not measured in this run")
 
