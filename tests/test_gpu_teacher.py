@@ -77,6 +77,43 @@ def test_row_band_runs_layerwise(gpu, oracle):
     layerwise(oracle, spec, "bf16", fusion=1)
 
 
+def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
+    """Resident runs whose weight matrices the work-group stages through LDS: 128-64 bottlenecks at 16x16 (through the
+    tile that is idle at the time, conv2 in three rounds), 128-32 at 16x16, 32-channel basic and post-activation blocks.
+    Three blocks, so that the staging of the first block, of a following block and of the last one all run; an odd
+    number of images; one call per micro-batch and one for all."""
+    runs = {
+        "wide-3x(128-64-128)@16x16": (tuple(W.Block(W.BOTTLENECK, 128, 64, 128, 1) for _ in range(3)), 16, 128, True),
+        "3x(128-32-128)@16x16": (tuple(W.Block(W.BOTTLENECK, 128, 32, 128, 1) for _ in range(3)), 16, 128, True),
+        "3x basic32@16x16": (tuple(W.Block(W.BASIC, 32, 32, 32, 1) for _ in range(3)), 16, 32, True),
+        "3x postact32@16x16": (tuple(W.Block(W.POSTACT, 32, 32, 32, 1) for _ in range(3)), 16, 32, False),
+        "3x postact16@32x32": (tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(3)), 32, 16, False),
+    }
+    for name, (blocks, hw, c, blockwise) in runs.items():
+        for b, m, grouped in ((3, 2, True), (4, 3, False)):
+            spec = W.PartitionSpec(name=f"{name}-b{b}", in_h=hw, in_w=hw, in_c=c, blocks=blocks, microbatch=b,
+                                   num_microbatches=m, seed=37)
+            layerwise(oracle, spec, "bf16", grouped=grouped, blockwise=blockwise)
+
+
+def test_whole_image_weight_gradient_of_16_channel_convolutions_layerwise(gpu, oracle):
+    """3x3 convolutions between 16 and 16 channels on 1024-pixel images take the weight-gradient kernel that forms all
+    nine taps from one staging of an image.  Square images (32 pixels per row: one image row per MFMA step) and the
+    two other row lengths it accepts (16 and 8 pixels: two and four image rows per step, other border lanes); image
+    counts that do not divide into equal work items; one image; pre- and post-activation operands (with and without
+    the BatchNorm recomputed while staging); one call per micro-batch and one for all."""
+    basic = tuple(W.Block(W.BASIC, 16, 16, 16, 1) for _ in range(2))
+    for (h, w), b, m, grouped in (((32, 32), 5, 3, True), ((32, 32), 1, 2, False), ((64, 16), 3, 2, True), ((128, 8), 2, 2, True)):
+        spec = W.PartitionSpec(name=f"t9-basic16@{h}x{w}-b{b}", in_h=h, in_w=w, in_c=16, blocks=basic, microbatch=b,
+                               num_microbatches=m, seed=29)
+        layerwise(oracle, spec, "bf16", grouped=grouped)
+    post = tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(2))
+    for fusion in (2, 1):
+        spec = W.PartitionSpec(name=f"t9-postact16@32x32-level{fusion}", in_h=32, in_w=32, in_c=16, blocks=post, microbatch=6,
+                               num_microbatches=2, seed=31)
+        layerwise(oracle, spec, "bf16", fusion=fusion, blockwise=False)   # the block-wise harness covers pre-activation blocks
+
+
 def test_config1_resnet20_layerwise(gpu, oracle):
     for mode in ("bf16", "f32"):
         layerwise(oracle, W.config(1), mode, grouped=False)
