@@ -68,7 +68,14 @@ struct ConvEpi {
   PtrTab stats{};           // EPI_BNBWD: {mean(N), invstd(N)} float
   const float* gamma = nullptr;
   const float* beta = nullptr;
+  // EPI_NONE without residual operand: room for a reduction split over several work-groups (long reductions
+  // into few output tiles); slab s of member z holds fp32 partial sums [M][N] at ((s*g + z)*M*N); 0 floats = none
+  float* splitk_ws = nullptr;
+  size_t splitk_floats = 0;
 };
+// Work-groups a bf16 convolution launch of g members splits every reduction over (1 = no split), and the fp32
+// workspace that takes (conv_splitk * g * M * N floats).
+int conv_splitk(int g, const ConvGeom& geom);
 // Optional BatchNorm + ReLU applied to the source tensor while it is staged (forward convolutions):
 // the source is the BatchNorm input x and the operand becomes bf16(max(gamma*((x-mean)*invstd)+beta, 0)),
 // so the normalised activation is never written to memory.  Padding stays zero.

@@ -48,6 +48,20 @@ struct ConvPlan {
   size_t wf_off = 0, wd_off = 0;    // packed bf16 offsets (elements)
   int Kf = 0, Kd = 0;
 };
+
+// implicit-GEMM geometry of a convolution of the plan, per micro-batch of b images
+ConvGeom conv_geom_fwd(const ConvPlan& cv, int b) {
+  ConvGeom q{};
+  q.b = b; q.Ho = cv.h_out; q.Wo = cv.w_out; q.Hs = cv.h_in; q.Ws = cv.w_in; q.Cs = cv.cin; q.N = cv.cout;
+  q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cin; q.Kpad = cv.Kf;
+  return q;
+}
+ConvGeom conv_geom_dgrad(const ConvPlan& cv, int b) {
+  ConvGeom q{};
+  q.b = b; q.Ho = cv.h_in; q.Wo = cv.w_in; q.Hs = cv.h_out; q.Ws = cv.w_out; q.Cs = cv.cout; q.N = cv.cin;
+  q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cout; q.Kpad = cv.Kd;
+  return q;
+}
 struct BnPlan { int C = 0; size_t g_off = 0, b_off = 0; size_t stats_off = 0; /* bytes in mb region */ size_t run_off = 0; /* floats: running mean, then variance */ };
 struct BlockPlan {
   hpf_block_desc d{};
@@ -116,6 +130,7 @@ struct Plan {
   std::vector<int> run_end_at;         // per block: index of the run that ends at this block, else -1
   std::vector<ResBlock> res_blocks;
   size_t res_off = 0, abort_off = 0;   // global regions
+  size_t splitk_off = 0, splitk_floats = 0;   // fp32 partial sums of convolutions whose reduction is split over work-groups (bf16 mode)
   size_t xchg_off = 0, tag_off = 0;    // per-micro-batch region
 };
 
@@ -611,6 +626,22 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
   for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
   P.abort_off = g;  g += align_up(sizeof(int));
+  if (P.dt == DT_BF16) {   // the largest split convolution of the plan, either direction, any group size (capped: beyond, no split)
+    const size_t cap = (size_t)32 << 20;
+    auto need = [&](const ConvGeom& q) {
+      for (int gm = 1; gm <= MAX_GROUP && gm <= d.num_microbatches; ++gm) {
+        const int sp = conv_splitk(gm, q);
+        const size_t n = (size_t)sp * gm * q.M * q.N;
+        if (sp > 1 && n <= cap && n > P.splitk_floats) P.splitk_floats = n;
+      }
+    };
+    for (int i = 0; i < d.n_blocks; ++i) {
+      const BlockPlan& p = P.bp[i];
+      for (int j = 0; j < p.nconv; ++j) { need(conv_geom_fwd(p.cv[j], d.microbatch)); need(conv_geom_dgrad(p.cv[j], d.microbatch)); }
+      if (p.proj) { need(conv_geom_fwd(p.pj, d.microbatch)); need(conv_geom_dgrad(p.pj, d.microbatch)); }
+    }
+    P.splitk_off = g; g += align_up(P.splitk_floats * sizeof(float));
+  }
   P.running_off = g; g += align_up(P.n_running * sizeof(float));
   P.bn_table_off = g; g += align_up(P.bn_table.size() * sizeof(BnRunDesc));
   P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
@@ -789,18 +820,8 @@ struct Ctx {
         (double)g * 2.0 * q.M * (double)q.Ktot * q.N);
     return back;
   }
-  ConvGeom geom_fwd(const ConvPlan& cv) const {
-    ConvGeom q{};
-    q.b = h->P.d.microbatch; q.Ho = cv.h_out; q.Wo = cv.w_out; q.Hs = cv.h_in; q.Ws = cv.w_in; q.Cs = cv.cin; q.N = cv.cout;
-    q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cin; q.Kpad = cv.Kf;
-    return q;
-  }
-  ConvGeom geom_dgrad(const ConvPlan& cv) const {
-    ConvGeom q{};
-    q.b = h->P.d.microbatch; q.Ho = cv.h_in; q.Wo = cv.w_in; q.Hs = cv.h_out; q.Ws = cv.w_out; q.Cs = cv.cout; q.N = cv.cin;
-    q.R = cv.R; q.stride = cv.stride; q.pad = (cv.R - 1) / 2; q.M = q.b * q.Ho * q.Wo; q.Ktot = cv.R * cv.R * cv.cout; q.Kpad = cv.Kd;
-    return q;
-  }
+  ConvGeom geom_fwd(const ConvPlan& cv) const { return conv_geom_fwd(cv, h->P.d.microbatch); }
+  ConvGeom geom_dgrad(const ConvPlan& cv) const { return conv_geom_dgrad(cv, h->P.d.microbatch); }
   // want_stats: the output feeds a BatchNorm; returns the number of partial rows written (0 = none).
   // pro_bn (bf16 mode): x is the input of that BatchNorm and the convolution normalises it while staging.
   int conv_fwd(const ConvPlan& cv, const PtrTab& x, const PtrTab& y, const PtrTab& add, bool want_stats = false,
@@ -819,6 +840,7 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
+      epi.splitk_ws = (float*)(h->arena + h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats;
       const int back = conv_seg(PROF_CONV_FWD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi, pro), "conv_fwd");
       if (back != PROF_NONE) seg(back);
@@ -840,6 +862,7 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
+      epi.splitk_ws = (float*)(h->arena + h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats;
       const int back = conv_seg(PROF_CONV_DGRAD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s, epi), "conv_dgrad");
       if (back != PROF_NONE) seg(back);

@@ -363,9 +363,13 @@ constexpr int BIG_T = 128, BIG_K = 64, BIG_LS = BIG_K + 8;   // LDS rows of 144 
 constexpr int BIG_STAGE = 2 * BIG_T * BIG_LS;                // bf16 elements per stage (pixel tile, then weight tile)
 constexpr int BIG_OPERAND_BYTES = 3 * BIG_STAGE * 2;         // three stages
 
-template <int MODE, int EPI, int PRO>
+// SPLIT: grid y = number of work-groups that share a reduction; each takes a contiguous range of the steps and
+// stores its fp32 partial tile into its slab of epi.splitk_ws (k_splitk_finish adds the slabs up): for long reductions
+// into few output tiles (VGG-16's 512 -> 512 convolutions on 4x4 and 2x2 pixels: 32-64 tiles, 72 steps).
+template <int MODE, int EPI, int PRO, bool SPLIT = false>
 __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds, ConvGeom g,
                                                   ConvEpi epi, ConvPro pro) {
+  static_assert(!SPLIT || (EPI == EPI_NONE && PRO == 0), "partial sums leave the kernel as they are");
   extern __shared__ __attribute__((aligned(16))) unsigned char big_smem[];
   bf16_t* stage = reinterpret_cast<bf16_t*>(big_smem);
   float2* coef = reinterpret_cast<float2*>(big_smem + BIG_OPERAND_BYTES);   // PRO: per source channel {scale, shift}
@@ -417,9 +421,15 @@ __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __r
   // at every wait and a wait for the oldest step never drains the younger ones.
   struct Slot { uint4 a[2]; uint4 w[2]; int c; bool av[2]; };
   Slot sl0, sl1, sl2;
-  const int nk = g.Kpad / BIG_K;
+  const int nk_all = g.Kpad / BIG_K;
+  const int k_begin = SPLIT ? (int)((long)blockIdx.y * nk_all / gridDim.y) : 0;
+  const int nk = SPLIT ? (int)((long)(blockIdx.y + 1) * nk_all / gridDim.y) - k_begin : nk_all;   // this work-group's steps
   int lk = 0, lc = 0, lr = 0, ls = 0;  // index, channel base and filter tap of the step that is loaded next (uniform)
-  const bf16_t* wrow = wpk + (size_t)(ch0 + (tid >> 3)) * g.Kpad + grp * 8;   // second unit: 64 rows further (uniform offset)
+  if (SPLIT) {
+    const int tap = (k_begin * BIG_K) / g.Cs;
+    lc = k_begin * BIG_K - tap * g.Cs; lr = tap / g.R; ls = tap - lr * g.R;
+  }
+  const bf16_t* wrow = wpk + (size_t)(ch0 + (tid >> 3)) * g.Kpad + grp * 8 + (size_t)k_begin * BIG_K;   // second unit: 64 rows further (uniform offset)
   auto load_chunk = [&](Slot& q) {
     const int cb = lc, c = cb + grp * 8, r = lr, s = ls, kc = lk;
     if (lk + 1 < nk) {                 // state only: no loads under this branch
@@ -580,6 +590,14 @@ __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __r
     const size_t o = (size_t)(mv ? m : 0) * g.N + ch;
     float (&vv)[8] = vals[u];
     load8(tile + rl * TS + cg * 8, vv);
+    if (SPLIT) {
+      if (mv) {
+        float* o4 = epi.splitk_ws + ((size_t)(blockIdx.y * gridDim.z + blockIdx.z) * g.M + m) * g.N + ch;
+        *reinterpret_cast<float4*>(o4) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        *reinterpret_cast<float4*>(o4 + 4) = make_float4(vv[4], vv[5], vv[6], vv[7]);
+      }
+      continue;
+    }
     if (add) {
       float rv[8];
       load8(add + o, rv);
@@ -652,14 +670,55 @@ __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __r
   }
 }
 
+// out[z][m][n] = bf16(sum over the slabs of the fp32 partial sums); 8 elements per thread
+__global__ __launch_bounds__(256) void k_splitk_finish(const float* __restrict__ ws, PtrTab outs, int splits, size_t mn, int ng) {
+  const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;   // unit of 8 elements within a member
+  const int z = blockIdx.y;
+  if (u * 8 >= mn) return;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const float4* q = reinterpret_cast<const float4*>(ws + ((size_t)s * ng + z) * mn + u * 8);
+    const float4 a = q[0], b = q[1];
+    acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+    acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
+  }
+  uint4 st;
+  st.x = pack_bf16x2(acc[0], acc[1]); st.y = pack_bf16x2(acc[2], acc[3]);
+  st.z = pack_bf16x2(acc[4], acc[5]); st.w = pack_bf16x2(acc[6], acc[7]);
+  *reinterpret_cast<uint4*>((bf16_t*)pick(outs, z) + u * 8) = st;
+}
+
 bool big_tile_fits(const ConvGeom& g) { return g.N % BIG_T == 0 && g.Cs % BIG_K == 0 && g.Kpad % BIG_K == 0 && g.Kpad == g.Ktot; }
+
+// Reductions of at least 16 steps into so few tiles that half of the CUs would idle are split over up to four
+// work-groups (each keeps at least 8 steps).
+int big_splits(int ng, const ConvGeom& g) {
+  const long wgs = (long)((g.M + BIG_T - 1) / BIG_T) * (g.N / BIG_T) * ng;
+  const int nk = g.Kpad / BIG_K;
+  if (nk < 16 || wgs > 128) return 1;
+  int s = (int)(256 / wgs);
+  if (s > 4) s = 4;
+  if (s > nk / 8) s = nk / 8;
+  return s < 2 ? 1 : s;
+}
 
 hipError_t launch_big(int mode, int ng, const PtrTab& src, const bf16_t* wpk, const PtrTab& out, const PtrTab& add, const ConvGeom& g,
                       hipStream_t stream, const ConvEpi& epi, const ConvPro& pro) {
   const int tiles = ((g.M + BIG_T - 1) / BIG_T) * (g.N / BIG_T);
-  const dim3 grid((unsigned)(8 * ((tiles + 7) / 8)), 1u, (unsigned)ng);
   const size_t dyn = BIG_OPERAND_BYTES + (pro.on ? (size_t)g.Cs * sizeof(float2) : 0);
   if (dyn > BIG_MAX_LDS) return hipErrorInvalidValue;
+  const int splits = (epi.kind == EPI_NONE && !pro.on && add.p[0] == nullptr && epi.splitk_ws) ? big_splits(ng, g) : 1;
+  if (splits > 1 && (size_t)splits * ng * g.M * g.N <= epi.splitk_floats) {
+    const dim3 sgrid((unsigned)(8 * ((tiles + 7) / 8)), (unsigned)splits, (unsigned)ng);
+    if (mode == CONV_FWD) k_conv_big<CONV_FWD, EPI_NONE, 0, true><<<sgrid, 512, dyn, stream>>>(src, wpk, out, add, g, epi, pro);
+    else k_conv_big<CONV_DGRAD, EPI_NONE, 0, true><<<sgrid, 512, dyn, stream>>>(src, wpk, out, add, g, epi, pro);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t mn = (size_t)g.M * g.N;   // a multiple of 128
+    k_splitk_finish<<<dim3((unsigned)((mn / 8 + 255) / 256), (unsigned)ng), 256, 0, stream>>>(epi.splitk_ws, out, splits, mn, ng);
+    return hipGetLastError();
+  }
+  const dim3 grid((unsigned)(8 * ((tiles + 7) / 8)), 1u, (unsigned)ng);
 #define HPF_CONV(MODE_, EPI_, PRO_) k_conv_big<MODE_, EPI_, PRO_><<<grid, 512, dyn, stream>>>(src, wpk, out, add, g, epi, pro)
   if (mode == CONV_FWD) {
     if (epi.kind == EPI_STATS) { if (pro.on) HPF_CONV(CONV_FWD, EPI_STATS, 1); else HPF_CONV(CONV_FWD, EPI_STATS, 0); }
@@ -722,6 +781,11 @@ int conv_mfma_tile_rows(int ng, const ConvGeom& g) {
   return t == 0 || t == 4 ? 128 : 64;
 }
 
+int conv_splitk(int ng, const ConvGeom& g) {
+  if (g.N % 16 != 0 || g.Cs % 8 != 0 || g.Kpad % KC != 0) return 1;
+  return pick_tile(ng, g) == 4 ? big_splits(ng, g) : 1;
+}
+
 int conv_operand_reuse(int cin, int cout, int R) {
   if (cout % BIG_T != 0 || cin % BIG_K != 0 || R * R * cin < BIG_MIN_K) return 0;
   return R * R * (cout / BIG_T);
@@ -746,6 +810,8 @@ hipError_t conv_prepare() {
   set(reinterpret_cast<const void*>(k_conv_big<CONV_FWD, EPI_NONE, 0>));
   set(reinterpret_cast<const void*>(k_conv_big<CONV_DGRAD, EPI_BNBWD, 0>));
   set(reinterpret_cast<const void*>(k_conv_big<CONV_DGRAD, EPI_NONE, 0>));
+  set(reinterpret_cast<const void*>(k_conv_big<CONV_FWD, EPI_NONE, 0, true>));
+  set(reinterpret_cast<const void*>(k_conv_big<CONV_DGRAD, EPI_NONE, 0, true>));
   if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
   return e;
 }

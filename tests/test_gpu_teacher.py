@@ -96,6 +96,20 @@ def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
             layerwise(oracle, spec, "bf16", grouped=grouped, blockwise=blockwise)
 
 
+def test_convolutions_with_split_reductions_layerwise(gpu, oracle):
+    """Plain 3x3 convolution units with long reductions into few output tiles (VGG-16's last two groups: 512 channels on
+    4x4 and 2x2 pixels) run with every reduction split over two to four work-groups whose fp32 partial sums a second
+    launch adds up, in both directions.  Group sizes 1 and several (the split count depends on it), a ragged last
+    tile (48 pixel rows), 9 x 256 and 9 x 512 reduction elements (36 and 72 steps: splits of unequal length)."""
+    cases = (("512@4x4", 512, 512, 4, 16, 2, True), ("512@4x4-single-calls", 512, 512, 4, 16, 2, False),
+             ("512@2x2-ragged", 512, 512, 2, 12, 3, True), ("256-512@4x4", 256, 512, 4, 8, 2, True))
+    for name, cin, cout, hw, b, m, grouped in cases:
+        blocks = (W.Block(W.CONV_RELU, cin, cout, cout, 1), W.Block(W.CONV_RELU, cout, cout, cout, 1))
+        spec = W.PartitionSpec(name=f"splitk-{name}-b{b}", in_h=hw, in_w=hw, in_c=cin, blocks=blocks, microbatch=b,
+                               num_microbatches=m, seed=41)
+        layerwise(oracle, spec, "bf16", grouped=grouped, blockwise=False)
+
+
 def test_whole_image_weight_gradient_of_16_channel_convolutions_layerwise(gpu, oracle):
     """3x3 convolutions between 16 and 16 channels on 1024-pixel images take the weight-gradient kernel that forms all
     nine taps from one staging of an image.  Square images (32 pixels per row: one image row per MFMA step) and the
