@@ -53,6 +53,31 @@ __device__ __forceinline__ float block_reduce_sum(float v, float* sh) {
 // part: 256 floats of LDS.  Ends with a barrier; lg[0 .. classes) is then complete.
 __device__ __forceinline__ void fc_logits(const float* gs, const float* __restrict__ wfc, const float* __restrict__ bfc, float* lg, float* part,
                                           int C, int classes) {
+  if (classes <= 16) {
+    // few classes (the benchmark heads have 10): every thread takes channels tid, tid + 256, ... for all classes -- its
+    // loads are independent of each other (consecutive threads read consecutive weight rows) and in flight together,
+    // where a thread per (class, channel slice) walked C/16 dependent steps; sums by wave shuffles, then over the 4 waves
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+    for (int c = threadIdx.x; c < C; c += 256) {
+      const float gv = gs[c];
+      const float* wr = wfc + (size_t)c * classes;
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (j < classes) acc[j] = fmaf(gv, wr[j], acc[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      float v = acc[j];
+      for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if ((threadIdx.x & 63) == 0) part[(threadIdx.x >> 6) * 16 + j] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < classes) lg[threadIdx.x] = bfc[threadIdx.x] + ((part[threadIdx.x] + part[16 + threadIdx.x]) + (part[32 + threadIdx.x] + part[48 + threadIdx.x]));
+    __syncthreads();
+    return;
+  }
   int jt = 1;
   while (jt < classes && jt < 256) jt <<= 1;
   const int cs_n = 256 / jt, jl = threadIdx.x % jt, cs = threadIdx.x / jt;
@@ -133,11 +158,32 @@ __global__ __launch_bounds__(256) void k_head_logits(PtrTab as, const float* __r
   for (int j = threadIdx.x; j < classes; j += blockDim.x) out[(size_t)n * classes + j] = lg[j];
 }
 
-// One block per sample: dWfc += g^T dlogits, dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw.
+// dWfc[c][j] += sum over the samples of all members of g[n][c] * dlogits[n][j]: a thread per output element walks the
+// samples (one atomic per element and launch; a block per sample adding its outer product cost b*g atomics per element).
+// Dynamic LDS: ng * b * classes floats (the dlogits of the launch).
+__global__ __launch_bounds__(256) void k_head_wgrad(PtrTab gs_, PtrTab dls, float* g_wfc, int ng, int b, int C, int classes) {
+  extern __shared__ float sdl[];
+  for (int z = 0; z < ng; ++z) {
+    const float* __restrict__ dl = (const float*)pick(dls, z);
+    for (int i = threadIdx.x; i < b * classes; i += 256) sdl[z * b * classes + i] = dl[i];
+  }
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= C * classes) return;
+  const int c = i / classes, j = i - c * classes;
+  float s = 0.f;
+  for (int z = 0; z < ng; ++z) {
+    const float* __restrict__ g = (const float*)pick(gs_, z);
+    for (int n = 0; n < b; ++n) s = fmaf(g[(size_t)n * C + c], sdl[(z * b + n) * classes + j], s);
+  }
+  atomicAdd(&g_wfc[i], s);
+}
+
+// One block per sample: dbfc += dlogits, da[n,i,c] = (dlogits[n] . Wfc[c]) / hw (dWfc: k_head_wgrad).
 template <class T>
 __global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const float* __restrict__ wfc, float* g_wfc,
                                                   float* g_bfc, PtrTab das, int hw, int C, int classes) {
-  const float* __restrict__ g = (const float*)pick(gs_, blockIdx.z);
+  (void)gs_; (void)g_wfc;
   const float* __restrict__ dlogits = (const float*)pick(dls, blockIdx.z);
   T* __restrict__ da = (T*)pick(das, blockIdx.z);
   extern __shared__ float dyn[];
@@ -155,10 +201,6 @@ __global__ __launch_bounds__(256) void k_head_bwd(PtrTab gs_, PtrTab dls, const 
     float s = 0.f;
     for (int j = 0; j < classes; ++j) s = fmaf(dl[j], wfc[(size_t)c * classes + j], s);
     dg[c] = s * inv_hw;
-  }
-  for (int i = threadIdx.x; i < C * classes; i += blockDim.x) {
-    const int c = i / classes, j = i - c * classes;
-    atomicAdd(&g_wfc[i], g[(size_t)n * C + c] * dl[j]);
   }
   __syncthreads();
   T* dan = da + (size_t)n * hw * C;
@@ -291,6 +333,11 @@ hipError_t launch_head_bwd(int dt, int ng, const PtrTab& gp, const PtrTab& dlogi
     k_head_bwd<bf16_t><<<grid, 256, lds, stream>>>(gp, dlogits, wfc, g_wfc, g_bfc, da, hw, C, classes);
   else
     k_head_bwd<float><<<grid, 256, lds, stream>>>(gp, dlogits, wfc, g_wfc, g_bfc, da, hw, C, classes);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t wl = (size_t)ng * b * classes * sizeof(float);
+  if (wl > 48 * 1024) return hipErrorInvalidValue;
+  k_head_wgrad<<<dim3((unsigned)(((size_t)C * classes + 255) / 256)), 256, wl, stream>>>(gp, dlogits, g_wfc, ng, b, C, classes);
   return hipGetLastError();
 }
 
