@@ -259,9 +259,35 @@ __global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ 
     const int ktot = d.T * d.Cin;
     const int tk = (d.Kf + 63) / 64, tn = (d.Cout + 63) / 64;
     const int lx = threadIdx.x & 63, ly = threadIdx.x >> 6;
+    const bool wide = d.Cout % 4 == 0 && d.Kf % 8 == 0 && d.w_off % 4 == 0 && d.wf_off % 8 == 0;   // 16-byte loads along n and 16-byte stores along k
     for (int t = blockIdx.y; t < tk * tn; t += gridDim.y) {
       const int k0 = (t / tn) * 64, n0 = (t % tn) * 64;
       __syncthreads();
+      if (wide) {
+        // load: a thread takes 4 consecutive n of one k row (16 lanes per row, 16 rows per pass)
+        const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+#pragma unroll
+        for (int r = r0; r < 64; r += 16) {
+          const int k = k0 + r, n = n0 + c4;
+          float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (k < ktot && n < d.Cout) v = *reinterpret_cast<const float4*>(w + (size_t)k * d.Cout + n);
+          tile[r][c4] = v.x; tile[r][c4 + 1] = v.y; tile[r][c4 + 2] = v.z; tile[r][c4 + 3] = v.w;
+        }
+        __syncthreads();
+        // store: a thread takes 8 consecutive k of one n row (8 lanes per row, 32 rows per pass)
+        const int k8 = (threadIdx.x & 7) * 8, nr0 = threadIdx.x >> 3;
+#pragma unroll
+        for (int r = nr0; r < 64; r += 32) {
+          const int n = n0 + r, k = k0 + k8;
+          if (n < d.Cout && k < d.Kf) {
+            uint4 st;
+            st.x = pack_bf16x2(tile[k8][r], tile[k8 + 1][r]); st.y = pack_bf16x2(tile[k8 + 2][r], tile[k8 + 3][r]);
+            st.z = pack_bf16x2(tile[k8 + 4][r], tile[k8 + 5][r]); st.w = pack_bf16x2(tile[k8 + 6][r], tile[k8 + 7][r]);
+            *reinterpret_cast<uint4*>(wf + (size_t)n * d.Kf + k) = st;
+          }
+        }
+        continue;
+      }
 #pragma unroll 4
       for (int r = ly; r < 64; r += 4) {
         const int k = k0 + r, n = n0 + lx;
@@ -277,15 +303,31 @@ __global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ 
   }
   if (d.wd_off != ~0ull) {
     bf16_t* wd = packed + d.wd_off;  // [Cin][Kd], k = tap*Cout + n
-    const int total = d.Cin * d.Kd, ktot = d.T * d.Cout;
-    for (int i = blockIdx.y * 256 + threadIdx.x; i < total; i += gridDim.y * 256) {
-      const int c = i / d.Kd, k = i - c * d.Kd;
-      float v = 0.f;
-      if (k < ktot) {
-        const int tap = k / d.Cout, n = k - tap * d.Cout;
-        v = w[((size_t)tap * d.Cin + c) * d.Cout + n];
+    const int ktot = d.T * d.Cout;
+    if (d.Cout % 2 == 0 && d.Kd % 2 == 0 && d.w_off % 2 == 0 && d.wd_off % 2 == 0) {   // pairs of n: 8-byte loads, 4-byte stores, no divisions
+      uint32_t* wd2 = reinterpret_cast<uint32_t*>(wd);
+      const int half = d.Cout >> 1, kd2 = d.Kd >> 1;
+      for (int c = blockIdx.y; c < d.Cin; c += gridDim.y) {
+        for (int tap = 0; tap < d.T; ++tap) {
+          const float* src = w + ((size_t)tap * d.Cin + c) * d.Cout;
+          for (int n2 = threadIdx.x; n2 < half; n2 += 256) {
+            const float2 v = *reinterpret_cast<const float2*>(src + 2 * n2);
+            wd2[(size_t)c * kd2 + tap * half + n2] = pack_bf16x2(v.x, v.y);
+          }
+        }
+        for (int k2 = (ktot >> 1) + threadIdx.x; k2 < kd2; k2 += 256) wd2[(size_t)c * kd2 + k2] = 0u;   // padding
       }
-      wd[i] = f32_to_bf16(v);
+    } else {
+      const int total = d.Cin * d.Kd;
+      for (int i = blockIdx.y * 256 + threadIdx.x; i < total; i += gridDim.y * 256) {
+        const int c = i / d.Kd, k = i - c * d.Kd;
+        float v = 0.f;
+        if (k < ktot) {
+          const int tap = k / d.Cout, n = k - tap * d.Cout;
+          v = w[((size_t)tap * d.Cin + c) * d.Cout + n];
+        }
+        wd[i] = f32_to_bf16(v);
+      }
     }
   }
 }
