@@ -687,7 +687,9 @@ template <int Cc, int PTW, class Fin>
 __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], const uint2 (&xin)[PTW][Cc / 16], const float4* cf_,
                                                 int npt, int wave, int fr, int fq, float* red, float4* tab_, float* gath,
                                                 u64* slot, int me, int nmem, int P, unsigned tag, float* dgb,
-                                                int* abort_flag, Fin&& fin) {
+                                                int* abort_flag, Fin&& fin, float* g_beta = nullptr, float* g_gamma = nullptr) {
+  // g_beta / g_gamma (member 0 of runs without a weight-gradient launch of their own, else null): the sums are added
+  // into the gradients of beta and gamma right here
   constexpr int NTL = Cc / 16;
   const float4* cf = reinterpret_cast<const float4*>(__builtin_assume_aligned(cf_, 16));
   float4* tab = reinterpret_cast<float4*>(__builtin_assume_aligned(tab_, 16));
@@ -726,16 +728,18 @@ __device__ __forceinline__ bool bn_relu_bwd_acc(floatx4 (&dz)[PTW][Cc / 16], con
   }
   if (!collect<(Cc >= 128 ? 16 : 4), true>(slot, nmem, 2 * Cc, tag, gath, abort_flag)) return false;
   const float invM = 1.f / ((float)nmem * (float)P);
-  {   // the 32 rows of 16 lanes take Cc/32 channels each; the lanes of a row split the members (fixed order)
-    constexpr int CR = Cc / 32, MP = 16 / CR;
+  {   // the 32 rows of 16 lanes take Cc/32 channels each (one each, on the first 16 rows, for 16 channels); the lanes of a row split the members (fixed order)
+    constexpr int CR = Cc >= 32 ? Cc / 32 : 1, MP = 16 / CR;
     const int l16 = threadIdx.x & 15, row = threadIdx.x >> 4;
-    const int c = row * CR + l16 % CR, part = l16 / CR;
+    const bool act = row * CR < Cc;
+    const int c = act ? row * CR + l16 % CR : 0, part = l16 / CR;
     float sb = 0.f, sg = 0.f;
     for (int m = part; m < nmem; m += MP) { sb += gath[m * 2 * Cc + c]; sg += gath[m * 2 * Cc + Cc + c]; }
     sb = row_sum<CR>(sb);
     sg = row_sum<CR>(sg);
-    if (part == 0) {
+    if (act && part == 0) {
       if (dgb) { dgb[c] = sb; dgb[Cc + c] = sg; }
+      if (g_beta) { atomicAdd(g_beta + c, sb); atomicAdd(g_gamma + c, sg); }
       const float4 k = cf[c];
       // scale*(dz - sb/M - (x*is + nm)*sg/M)
       tab[c] = make_float4(k.x, -k.x * sg * invM * k.z, -k.x * invM * (sb + k.w * sg), 0.f);
@@ -1359,13 +1363,18 @@ __device__ __forceinline__ void tile_bn_relu_to(bf16_t* dst, const bf16_t* src, 
   }
 }
 
+// floats of the reduction area: 8 waves x 2*C sums (backward), and 32/(C/8) pixel groups x 2*C (statistics) = 512
+constexpr int V1_RED(int C) { return RES_NWV * 2 * C > 512 ? RES_NWV * 2 * C : 512; }
+
 template <int C, int PTW, bool PRE, bool INFER = false, bool WL = false>
 __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const int gath_own) {
   static_assert(!(WL && (PRE || INFER)), "the LDS form replaces the fetch-where-used form of the training kernels");
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  // the 16-channel shape is 32 x 32 pixels only: constants instead of kernel arguments (fewer address temporaries)
+  const int H = C == 16 ? 32 : a.H, W = C == 16 ? 32 : a.W;
+  const int P = H * W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
@@ -1378,13 +1387,14 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
   bf16_t* sA = sx + (size_t)P * XS;                       // relu(bn1(x))
   bf16_t* sB = sA + (size_t)P * XS;                       // c1, then relu(bn2(c1))
   float2* coef = reinterpret_cast<float2*>(sB + (size_t)P * XS);
-  float* red = reinterpret_cast<float*>(coef + C);        // RES_NWV * 2*C floats
-  float* own = red + RES_NWV * 2 * C;
+  float* red = reinterpret_cast<float*>(coef + C);        // V1_RED(C) floats
+  float* own = red + V1_RED(C);
   float* gath = gath_own ? own : reinterpret_cast<float*>(sA);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  std::conditional_t<WL, WFragsL<9 * C / 32, C / 16>, WFrags<9 * C / 32, C / 16, PRE>> w1, w2;
+  constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;     // reduction steps and row length of the packed weights
+  std::conditional_t<WL, WFragsL<KT, C / 16>, WFrags<KT, C / 16, PRE>> w1, w2;
   bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
-  u32x4 wst[WL ? (9 * C / 32 * (C / 16) + 7) / 8 : 1];                                      // WL: its units on their way
+  u32x4 wst[WL ? (KT * (C / 16) + 7) / 8 : 1];                                      // WL: its units on their way
 
   auto store_acc = [&](bf16_t* dst, floatx4 (&acc)[PTW][C / 16]) {
 #pragma unroll
@@ -1399,7 +1409,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
   {
     const ResBlock B0 = a.blocks[0];
     tile_load<C>(sx, cx.tensor(B0.x_off) + (size_t)me * P * C, P);
-    w_issue(w1, wst, a.packed + B0.wf_off[0], 9 * C, fr, fk);
+    w_issue(w1, wst, a.packed + B0.wf_off[0], LD, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<C>(coef, a.running + B0.run_off[0], a.params + B0.gamma_off[0], a.params + B0.beta_off[0], a.eps);
@@ -1422,10 +1432,10 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, false>(sA, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, false>(sA, w1, H, W, npt, wave, fr, fk, acc);
       store_acc(sB, acc);
     }
-    w_issue(w2, wst, a.packed + B.wf_off[1], 9 * C, fr, fk);
+    w_issue(w2, wst, a.packed + B.wf_off[1], LD, fr, fk);
     __syncthreads();
     if (INFER) {
       running_coef<C>(coef, a.running + B.run_off[1], a.params + B.gamma_off[1], a.params + B.beta_off[1], a.eps);
@@ -1446,7 +1456,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, false>(sB, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, false>(sB, w2, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j) {
         const int pt = wave + j * RES_NWV;
@@ -1463,7 +1473,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_forward(const ResArgs a, const in
     }
     const bool more = bi + 1 < a.nblk;
     const ResBlock Bn = a.blocks[more ? bi + 1 : bi];
-    if (more) w_issue(w1, wst, a.packed + Bn.wf_off[0], 9 * C, fr, fk);
+    if (more) w_issue(w1, wst, a.packed + Bn.wf_off[0], LD, fr, fk);
     __syncthreads();
     if (INFER) {
       if (more) running_coef<C>(coef, a.running + Bn.run_off[0], a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], a.eps);
@@ -1489,26 +1499,31 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
   constexpr int XS = C + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int fr = lane & 15, fq = lane >> 4, fk = fq * 8;
-  const int P = a.H * a.W, npt = P >> 4;
+  const int H = C == 16 ? 32 : a.H, W = C == 16 ? 32 : a.W;   // as in the forward kernel
+  const int P = H * W, npt = P >> 4;
   const int z = blockIdx.x % a.ngroup, me = blockIdx.x / a.ngroup;
   ResCtx cx{(char*)pick(a.base, z), pick(a.act_in, z), pick(a.act_out, z), pick(a.err_in, z), pick(a.err_out, z)};
   u64* xchg = reinterpret_cast<u64*>(cx.base + a.xchg_off);
   unsigned* tagp = reinterpret_cast<unsigned*>(cx.base + a.tag_off);
   const unsigned tag0 = *tagp;
   unsigned phase = 0;
+  // 16 channels: the weight gradients go through the grouped launch, which knows nothing of the stored BatchNorm sums:
+  // member 0 adds them into the gradients of beta and gamma itself
+  constexpr bool DIRECT = C == 16;
 
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* sdy = reinterpret_cast<bf16_t*>(smem);          // gradient of the residual stream
   bf16_t* sdc = sdy + (size_t)P * XS;                     // dc1
   float4* cf1 = reinterpret_cast<float4*>(sdc + (size_t)P * XS);
   float4* cf2 = cf1 + C;
-  float* red = reinterpret_cast<float*>(cf2 + C);         // RES_NWV * 2*C floats
-  float4* tab = reinterpret_cast<float4*>(red + RES_NWV * 2 * C);
+  float* red = reinterpret_cast<float*>(cf2 + C);         // V1_RED(C) floats
+  float4* tab = reinterpret_cast<float4*>(red + V1_RED(C));
   float* own = reinterpret_cast<float*>(tab + C);
   auto slot = [&]() { return xchg + (size_t)(phase & 1u) * a.nmem * (2 * C); };
-  std::conditional_t<WL, WFragsL<9 * C / 32, C / 16>, WFrags<9 * C / 32, C / 16, PRE>> w2, w1;   // data-gradient operands [C][9*C]
+  constexpr int KT = (9 * C + 31) / 32, LD = KT * 32;
+  std::conditional_t<WL, WFragsL<KT, C / 16>, WFrags<KT, C / 16, PRE>> w2, w1;   // data-gradient operands [C][LD]
   bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL: the staged matrix
-  u32x4 wst[WL ? (9 * C / 32 * (C / 16) + 7) / 8 : 1];
+  u32x4 wst[WL ? (KT * (C / 16) + 7) / 8 : 1];
 
   // x / c1 (the BatchNorm inputs) are needed only at this lane's accumulator positions: read there from memory
   auto at_acc = [&](const bf16_t* g, uint2 (&xin)[PTW][C / 16]) {
@@ -1524,7 +1539,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
     const ResBlock BL = a.blocks[a.nblk - 1];
     tile_load<C>(sdy, cx.tensor(BL.gy_off) + (size_t)me * P * C, P);
     if constexpr (WL) {   // the first block's conv2 matrix (the barrier below the tables precedes its use); later ones are
-      w_issue(w2, wst, a.packed + BL.wd_off[1], 9 * C, fr, fk);   // staged behind the last exchange of the block before
+      w_issue(w2, wst, a.packed + BL.wd_off[1], LD, fr, fk);   // staged behind the last exchange of the block before
       w_commit(w2, wst, sW);
     }
   }
@@ -1539,7 +1554,7 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
                                               a.params + B.beta_off[0], c, C);
       const float4 t2 = BwdLoads<C, C, 1>::table(reinterpret_cast<const float*>(cx.base + B.stats_off[1]), a.params + B.gamma_off[1],
                                               a.params + B.beta_off[1], c, C);
-      if constexpr (!WL) w2.load(a.packed + B.wd_off[1], 9 * C, fr, fk);
+      if constexpr (!WL) w2.load(a.packed + B.wd_off[1], LD, fr, fk);
       if (tid < C) { cf1[tid] = t1; cf2[tid] = t2; }
     }
     __syncthreads();
@@ -1550,18 +1565,19 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, true>(sdy, w2, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, true>(sdy, w2, H, W, npt, wave, fr, fk, acc);
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) xin[j][nt] = wave + j * RES_NWV < npt ? xc1[j][nt] : make_uint2(0u, 0u);
-      w_issue(w1, wst, a.packed + B.wd_off[0], 9 * C, fr, fk);
+      w_issue(w1, wst, a.packed + B.wd_off[0], LD, fr, fk);
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf2, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
+                                   me == 0 && !DIRECT ? reinterpret_cast<float*>(cx.base + B.dgb_off[1]) : nullptr, a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      *reinterpret_cast<uint2*>(sdc + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4) = pack4(out);
-                                   }))
+                                   },
+                                   me == 0 && DIRECT ? a.grads + B.beta_off[1] : nullptr, me == 0 && DIRECT ? a.grads + B.gamma_off[1] : nullptr))
         return;
       ++phase;
       w_commit(w1, wst, sW);
@@ -1575,9 +1591,9 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
         for (int nt = 0; nt < C / 16; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-      conv3x3_tile<C, PTW, true>(sdc, w1, a.H, a.W, npt, wave, fr, fk, acc);
+      conv3x3_tile<C, PTW, true>(sdc, w1, H, W, npt, wave, fr, fk, acc);
       if constexpr (WL)
-        if (bi > 0) w_issue(w2, wst, a.packed + a.blocks[bi - 1].wd_off[1], 9 * C, fr, fk);   // the next block's conv2 matrix
+        if (bi > 0) w_issue(w2, wst, a.packed + a.blocks[bi - 1].wd_off[1], LD, fr, fk);   // the next block's conv2 matrix
 #pragma unroll
       for (int j = 0; j < PTW; ++j)
 #pragma unroll
@@ -1586,14 +1602,15 @@ __global__ void __launch_bounds__(RES_NT) k_bb_backward(const ResArgs a, const i
       // between that and the first write of the gathered words
       float* gath = gath_own ? own : reinterpret_cast<float*>(sdc);
       if (!bn_relu_bwd_acc<C, PTW>(acc, xin, cf1, npt, wave, fr, fq, red, tab, gath, slot(), me, a.nmem, P, tag0 + 1u + phase,
-                                   me == 0 ? reinterpret_cast<float*>(cx.base + B.dgb_off[0]) : nullptr, a.abort_flag,
+                                   me == 0 && !DIRECT ? reinterpret_cast<float*>(cx.base + B.dgb_off[0]) : nullptr, a.abort_flag,
                                    [&](int j, int nt, const floatx4& out) {
                                      uint2* q = reinterpret_cast<uint2*>(sdy + ((wave + j * RES_NWV) * 16 + fr) * XS + nt * 16 + fq * 4);
                                      const uint2 d = *q;
                                      floatx4 v = out;
                                      v[0] += bf_lo(d.x); v[1] += bf_hi(d.x); v[2] += bf_lo(d.y); v[3] += bf_hi(d.y);
                                      *q = pack4(v);
-                                   }))
+                                   },
+                                   me == 0 && DIRECT ? a.grads + B.beta_off[0] : nullptr, me == 0 && DIRECT ? a.grads + B.gamma_off[0] : nullptr))
         return;
       ++phase;
       if constexpr (WL)
@@ -1634,8 +1651,6 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
 // ResBlock fields used: x, c1, c2, y, gy, dc1, dc2, gx and entries 0 / 1 of the per-BatchNorm / per-convolution arrays.
 // The weight gradients of such runs go through the grouped per-layer launch, inference through the per-layer kernels.
 
-// floats of the reduction area: 8 waves x 2*C sums (backward), and 32/(C/8) pixel groups x 2*C (statistics) = 512
-constexpr int V1_RED(int C) { return RES_NWV * 2 * C > 512 ? RES_NWV * 2 * C : 512; }
 
 // y = relu(c2*scale + shift + x), tile to tile (written over x)
 template <int Cc>
@@ -2580,8 +2595,8 @@ __global__ void __launch_bounds__(RES_NT) k_band_backward(const ResArgs a) {
 
 size_t bb_lds(int C, int P, int nmem, bool backward, int* own) {
   const size_t tile = (size_t)P * (C + 8) * 2;
-  const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)RES_NWV * 2 * C * 4 + (size_t)C * 16
-                                : (size_t)C * 8 + (size_t)RES_NWV * 2 * C * 4;
+  const size_t fixed = backward ? (size_t)2 * C * 16 + (size_t)V1_RED(C) * 4 + (size_t)C * 16
+                                : (size_t)C * 8 + (size_t)V1_RED(C) * 4;
   *own = (size_t)nmem * 2 * C * 4 > tile ? 1 : 0;
   return (backward ? 2 : 3) * tile + fixed + (*own ? (size_t)nmem * 2 * C * 4 : 0);
 }
@@ -2671,9 +2686,9 @@ bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem) {
            (C == 16 || bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES);
   }
   if (kind == 0) {   // basic blocks: C -> C -> C
-    if (!((C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
+    if (!((C == 16 && P == 1024 && W == 32) || (C == 32 && P <= 256) || (C == 64 && P <= 128)) || MID != C) return false;
     return bb_lds(C, P, nmem, false, &own) <= RES_LDS_BYTES && bb_lds(C, P, nmem, true, &own) <= RES_LDS_BYTES &&
-           bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES;
+           (C == 16 || bb_wgrad_lds(C, P, W) <= RES_LDS_BYTES);
   }
   if (!((C == 128 && (MID == 32 || MID == 64) && P <= 256) || (C == 256 && MID == 64 && P <= 128))) return false;
   return fwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES && bwd_lds(C, MID, P, nmem, &own) <= RES_LDS_BYTES;
@@ -2697,6 +2712,7 @@ hipError_t resident_prepare() {
   const void* bb[] = {reinterpret_cast<const void*>(k_bb_forward<32, 2, true>),  reinterpret_cast<const void*>(k_bb_forward<64, 1, false>),
                       reinterpret_cast<const void*>(k_bb_backward<32, 2, true>), reinterpret_cast<const void*>(k_bb_backward<64, 1, false>),
                       reinterpret_cast<const void*>(k_bb_forward<32, 2, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<32, 2, false, true>),
+                      reinterpret_cast<const void*>(k_bb_forward<16, 8, false, false, true>), reinterpret_cast<const void*>(k_bb_backward<16, 8, false, true>),
                       reinterpret_cast<const void*>(k_bb_wgrad<32>),             reinterpret_cast<const void*>(k_bb_wgrad<64>)};
   for (const void* f : bb)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2729,6 +2745,7 @@ hipError_t resident_prepare() {
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_band_backward<64, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   const void* infer[] = {reinterpret_cast<const void*>(k_res_forward<128, 32, 2, true, true>), reinterpret_cast<const void*>(k_res_forward<128, 64, 2, false, true>),
                          reinterpret_cast<const void*>(k_res_forward<256, 64, 1, false, true>), reinterpret_cast<const void*>(k_bb_forward<32, 2, true, true>),
+                         reinterpret_cast<const void*>(k_bb_forward<16, 8, false, true>),
                          reinterpret_cast<const void*>(k_bb_forward<64, 1, false, true>)};
   for (const void* f : infer)
     if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -2762,6 +2779,11 @@ hipError_t launch_resident_forward(int kind, int g, int C, int MID, const ResArg
   }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 16) {   // 32x32 images; the [16][160] matrices through LDS
+      const size_t wl16 = (size_t)16 * (160 + 8) * 2;
+      if (lds + wl16 > RES_LDS_BYTES) return hipErrorInvalidValue;
+      return launch_res(k_bb_forward<16, 8, false, false, true>, lds + wl16, own, g, a, stream);
+    }
     if (C == 32) {
       const size_t wl32 = (size_t)32 * (288 + 8) * 2;
       return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_bb_forward<32, 2, false, false, true>, lds + wl32, own, g, a, stream)
@@ -2795,6 +2817,7 @@ hipError_t launch_resident_inference(int kind, int g, int C, int MID, const ResA
   int own = 0;
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, false, &own);
+    if (C == 16) return launch_res(k_bb_forward<16, 8, false, true>, lds, 0, g, a, stream);
     if (C == 32) return launch_res(k_bb_forward<32, 2, true, true>, lds, 0, g, a, stream);
     return launch_res(k_bb_forward<64, 1, false, true>, lds, 0, g, a, stream);
   }
@@ -2861,6 +2884,11 @@ hipError_t launch_resident_backward(int kind, int g, int C, int MID, const ResAr
   }
   if (kind == 0) {
     const size_t lds = bb_lds(C, a.H * a.W, a.nmem, true, &own);
+    if (C == 16) {
+      const size_t wl16 = (size_t)16 * (160 + 8) * 2;
+      if (lds + wl16 > RES_LDS_BYTES) return hipErrorInvalidValue;
+      return launch_res(k_bb_backward<16, 8, false, true>, lds + wl16, own, g, a, stream);
+    }
     if (C == 32) {
       const size_t wl32 = (size_t)32 * (288 + 8) * 2;
       return lds + wl32 <= RES_LDS_BYTES ? launch_res(k_bb_backward<32, 2, false, true>, lds + wl32, own, g, a, stream)

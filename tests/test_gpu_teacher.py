@@ -79,13 +79,15 @@ def test_row_band_runs_layerwise(gpu, oracle):
 
 def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
     """Resident runs whose weight matrices the work-group stages through LDS: 128-64 bottlenecks at 16x16 (through the
-    tile that is idle at the time, conv2 in three rounds), 128-32 at 16x16, 32-channel basic and post-activation blocks.
+    tile that is idle at the time, conv2 in three rounds), 128-32 at 16x16, 32-channel basic and post-activation blocks,
+    16-channel basic and post-activation blocks at 32x32.
     Three blocks, so that the staging of the first block, of a following block and of the last one all run; an odd
     number of images; one call per micro-batch and one for all."""
     runs = {
         "wide-3x(128-64-128)@16x16": (tuple(W.Block(W.BOTTLENECK, 128, 64, 128, 1) for _ in range(3)), 16, 128, True),
         "3x(128-32-128)@16x16": (tuple(W.Block(W.BOTTLENECK, 128, 32, 128, 1) for _ in range(3)), 16, 128, True),
         "3x basic32@16x16": (tuple(W.Block(W.BASIC, 32, 32, 32, 1) for _ in range(3)), 16, 32, True),
+        "3x basic16@32x32": (tuple(W.Block(W.BASIC, 16, 16, 16, 1) for _ in range(3)), 32, 16, True),
         "3x postact32@16x16": (tuple(W.Block(W.POSTACT, 32, 32, 32, 1) for _ in range(3)), 16, 32, False),
         "3x postact16@32x32": (tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(3)), 32, 16, False),
     }
