@@ -216,9 +216,9 @@ hpf_status hpf_partition_set_graphs(hpf_partition* p, int32_t enable);
  *      weight gradient stage their operand;
  *   2  (default) additionally, runs of consecutive blocks of one shape with stride 1 and identity
  *      shortcut -- bottleneck 128->32->32->128 or 128->64->64->128 channels at up to 256 pixels or 256->64->64->256 at
- *      up to 128; basic (two 3x3 convolutions) with 32 channels at up to 256 pixels or 64 at up to
- *      128; post-activation basic (kind 2) of the same two shapes; image width 8, 16 or 32, pixel count a
- *      multiple of 32 -- run
+ *      up to 128; basic (two 3x3 convolutions) with 32 channels at up to 256 pixels, 64 at up to
+ *      128 or 16 at 32 x 32; post-activation basic (kind 2) of the same three shapes; image width 8, 16 or 32,
+ *      pixel count a multiple of 32 -- run
  *      in one launch per direction that keeps each image in the LDS of one CU: one work-group per
  *      image, all of them on the chip together.  Bottleneck 64->16->16->64 at 32 x 32 pixels, whose image
  *      does not fit, runs the same way with each image cut into four bands of eight rows, one work-group
