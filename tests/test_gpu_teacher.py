@@ -123,6 +123,11 @@ def test_whole_image_weight_gradient_of_16_channel_convolutions_layerwise(gpu, o
         spec = W.PartitionSpec(name=f"t9-basic16@{h}x{w}-b{b}", in_h=h, in_w=w, in_c=16, blocks=basic, microbatch=b,
                                num_microbatches=m, seed=29)
         layerwise(oracle, spec, "bf16", grouped=grouped)
+    # many convolutions of the class in one partition: the work items then take several images each (here 3, 3, ..., 2)
+    many = tuple(W.Block(W.BASIC, 16, 16, 16, 1) for _ in range(40))
+    spec = W.PartitionSpec(name="t9-40xbasic16@32x32-b32", in_h=32, in_w=32, in_c=16, blocks=many, microbatch=32,
+                           num_microbatches=2, seed=29)
+    layerwise(oracle, spec, "bf16", blockwise=False)
     post = tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(2))
     for fusion in (2, 1):
         spec = W.PartitionSpec(name=f"t9-postact16@32x32-level{fusion}", in_h=32, in_w=32, in_c=16, blocks=post, microbatch=6,
