@@ -41,6 +41,11 @@ def test_sizes_of_the_benchmark_partitions(hpf):
         oh, ow, oc = spec.out_shape()
         assert z.act_out_elems == (0 if spec.has_head else b * oh * ow * oc)
         assert z.arena_bytes > z.stash_bytes > 0 and z.arena_bytes % 256 == 0
+    for i in (6, 7, 8):   # the wider ResNet-1001 partition, ResNet-110-v1 and VGG-16: the plan of their other unit kinds
+        spec = W.config(i)
+        z = hpf.hpf_partition_sizes(hpf.make_desc(spec)[0])
+        assert z.n_params == W.n_params(spec)
+        assert z.arena_bytes > z.stash_bytes > 0 and z.arena_bytes % 256 == 0
 
 
 def status_of(hpf, spec, dtype=None):
