@@ -492,6 +492,9 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
   bf16_t* sW = reinterpret_cast<bf16_t*>(own + (gath_own ? (size_t)a.nmem * 2 * C : 0));   // WL == 1: the staged matrix
   bf16_t* const sW1 = WT ? smB : sW;
   bf16_t* const sW3 = WT ? smA : sW;
+  // the C-wide records of a large micro-batch (more than 36 images at 128 channels) reach from the c1 tile into the c2
+  // tile: conv1's matrix then goes there only when they have been merged (one more barrier per block)
+  const bool w1_late = WT && !gath_own && (size_t)a.nmem * 2 * C * sizeof(float) > (size_t)P * MS * sizeof(bf16_t);
   constexpr int W2NU = (3 * MID * MID / 8 + RES_NT - 1) / RES_NT;                            // WT: units per thread and round
   u32x4 wst[WL == 1 ? (9 * MID / 32 * (MID / 16) + 7) / 8 : WT ? 3 * W2NU : 1];             // the units on their way
   static_assert(!WT || (MID * (C + 8) <= 256 * (MID + 8) && C * (MID + 8) <= 256 * (MID + 8) && MID * (3 * MID + 8) <= 256 * (MID + 8)),
@@ -508,9 +511,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
       stats_publish<C>(sx, P, red, slot(), me, tag0 + 1u + phase);
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
-      w_commit(w1, wst, sW1);   // the barrier at the end of the merge lies between this and conv1
+      if (!w1_late) w_commit(w1, wst, sW1);   // the barrier at the end of the merge lies between this and conv1
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + B0.gamma_off[0], a.params + B0.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + B0.stats_off[0]) : nullptr);
+      if (w1_late) {
+        w_commit(w1, wst, sW1);
+        __syncthreads();
+      }
     }
   }
 
@@ -665,9 +672,13 @@ __global__ void __launch_bounds__(RES_NT) k_res_forward(const ResArgs a, const i
     if (more) {
       if (!collect<16>(slot(), a.nmem, 2 * C, tag0 + 1u + phase, gathA, a.abort_flag)) return;
       ++phase;
-      w_commit(w1, wst, sW1);
+      if (!w1_late) w_commit(w1, wst, sW1);
       merge_coef<C>(gathA, a.nmem, P, a.eps, a.params + Bn.gamma_off[0], a.params + Bn.beta_off[0], coefC,
                     me == 0 ? reinterpret_cast<float*>(cx.base + Bn.stats_off[0]) : nullptr);
+      if (w1_late) {
+        w_commit(w1, wst, sW1);
+        __syncthreads();
+      }
     }
   }
   // every member has read the counter before it took part in the first exchange, which member 0 has left

@@ -91,6 +91,10 @@ def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
         "3x postact32@16x16": (tuple(W.Block(W.POSTACT, 32, 32, 32, 1) for _ in range(3)), 16, 32, False),
         "3x postact16@32x32": (tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(3)), 32, 16, False),
     }
+    # 40 images per micro-batch: the gathered 128-channel records then reach into the tile that also takes a weight matrix
+    spec = W.PartitionSpec(name="wide-3x(128-64-128)@16x16-b40", in_h=16, in_w=16, in_c=128, blocks=runs["wide-3x(128-64-128)@16x16"][0],
+                           microbatch=40, num_microbatches=2, seed=37)
+    layerwise(oracle, spec, "bf16", blockwise=False)
     for name, (blocks, hw, c, blockwise) in runs.items():
         for b, m, grouped in ((3, 2, True), (4, 3, False)):
             spec = W.PartitionSpec(name=f"{name}-b{b}", in_h=hw, in_w=hw, in_c=c, blocks=blocks, microbatch=b,
