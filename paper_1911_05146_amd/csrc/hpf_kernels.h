@@ -69,12 +69,13 @@ struct ConvEpi {
   const float* gamma = nullptr;
   const float* beta = nullptr;
   // EPI_NONE without residual operand: room for a reduction split over several work-groups (long reductions
-  // into few output tiles); slab s of member z holds fp32 partial sums [M][N] at ((s*g + z)*M*N); 0 floats = none
-  float* splitk_ws = nullptr;
+  // into few output tiles): per member a buffer of splitk_floats floats, slab s holds fp32 partial sums [M][N] at s*M*N;
+  // 0 floats = none.  Per member, because calls for different micro-batches may overlap on different streams.
+  PtrTab splitk_ws{};
   size_t splitk_floats = 0;
 };
 // Work-groups a bf16 convolution launch of g members splits every reduction over (1 = no split), and the fp32
-// workspace that takes (conv_splitk * g * M * N floats).
+// workspace that takes per member (conv_splitk * M * N floats).
 int conv_splitk(int g, const ConvGeom& geom);
 // Optional BatchNorm + ReLU applied to the source tensor while it is staged (forward convolutions):
 // the source is the BatchNorm input x and the operand becomes bf16(max(gamma*((x-mean)*invstd)+beta, 0)),
@@ -110,7 +111,6 @@ struct WgradItem {
   unsigned long long gamma_off, beta_off;     //   relu(bn(a)) recomputed while staging (floats into the parameters)
   WgradGeom g;
   int tap, c0, n0, m_begin, m_end;
-  int sole;   // 1: no other item of the launch adds into this output tile (one split): plain read-add-write instead of atomics
 };
 // tile_class: 0..8 = (BC index)*3 + (BN index) with sizes {16, 32, 64}; 9 = 128 x 128 (both channel counts
 // multiples of 128: each wave owns a 64 x 64 quadrant of the tile over the whole reduction)

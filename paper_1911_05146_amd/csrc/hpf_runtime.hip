@@ -130,7 +130,7 @@ struct Plan {
   std::vector<int> run_end_at;         // per block: index of the run that ends at this block, else -1
   std::vector<ResBlock> res_blocks;
   size_t res_off = 0, abort_off = 0;   // global regions
-  size_t splitk_off = 0, splitk_floats = 0;   // fp32 partial sums of convolutions whose reduction is split over work-groups (bf16 mode)
+  size_t splitk_off = 0, splitk_floats = 0;   // per micro-batch: fp32 partial sums of convolutions whose reduction is split over work-groups (bf16 mode)
   size_t xchg_off = 0, tag_off = 0;    // per-micro-batch region
 };
 
@@ -508,6 +508,22 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       P.tag_off = alloc(sizeof(unsigned)).off;
     }
   }
+  if (P.dt == DT_BF16) {   // fp32 partial sums of the largest split convolution of the plan, either direction, any group size (capped: beyond, no split)
+    const size_t cap = (size_t)8 << 20;   // floats per micro-batch
+    auto need = [&](const ConvGeom& q) {
+      for (int gm = 1; gm <= MAX_GROUP && gm <= d.num_microbatches; ++gm) {
+        const int sp = conv_splitk(gm, q);
+        const size_t n = (size_t)sp * q.M * q.N;
+        if (sp > 1 && n <= cap && n > P.splitk_floats) P.splitk_floats = n;
+      }
+    };
+    for (int i = 0; i < d.n_blocks; ++i) {
+      const BlockPlan& p = P.bp[i];
+      for (int j = 0; j < p.nconv; ++j) { need(conv_geom_fwd(p.cv[j], d.microbatch)); need(conv_geom_dgrad(p.cv[j], d.microbatch)); }
+      if (p.proj) { need(conv_geom_fwd(p.pj, d.microbatch)); need(conv_geom_dgrad(p.pj, d.microbatch)); }
+    }
+    if (P.splitk_floats) P.splitk_off = alloc(P.splitk_floats * sizeof(float)).off;
+  }
   P.mb_bytes = mo;
 
   // ---- deferred weight-gradient items (bf16 mode)
@@ -576,7 +592,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       wgrad_tile_dims(cls, &bc, &bn);
       (pass ? P.wg_nr_bytes : P.wg_bytes)[cls] += 2.0 * ((double)q.b * q.H * q.W * q.Cin + (double)q.M * q.N);
       (pass ? P.wg_nr_flops : P.wg_flops)[cls] += 2.0 * q.M * (double)(w.R * w.R * q.Cin) * q.N;
-      auto item = [&](int tap, int c0, int n0, int m_begin, int m_end, bool sole) {
+      auto item = [&](int tap, int c0, int n0, int m_begin, int m_end) {
         WgradItem it{};
         it.a_off = w.a.kind == IN_MB ? w.a.off : WGRAD_DY_CALLER;
         it.dy_off = w.dy.kind == IN_MB ? w.dy.off : WGRAD_DY_CALLER;
@@ -585,14 +601,14 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
         it.gamma_off = w.bn ? w.bn->g_off : 0;
         it.beta_off = w.bn ? w.bn->b_off : 0;
         it.g = q; it.tap = tap; it.c0 = c0; it.n0 = n0;
-        it.m_begin = m_begin; it.m_end = m_end; it.sole = sole ? 1 : 0;
+        it.m_begin = m_begin; it.m_end = m_end;
         (pass ? P.items_nr : P.items)[cls].push_back(it);
       };
       if (cls == WGRAD_CLASS_T9) {   // whole images per item; about 1000 work-groups (two per CU at 67 KiB of LDS, twice over)
         int parts = (int)((1024 + tiles_in_class[cls] - 1) / tiles_in_class[cls]);
         if (parts > q.b) parts = q.b;
         const int imgs = (q.b + parts - 1) / parts, px = q.H * q.W;
-        for (int i0 = 0; i0 < q.b; i0 += imgs) item(0, 0, 0, i0 * px, (i0 + imgs < q.b ? i0 + imgs : q.b) * px, imgs >= q.b);
+        for (int i0 = 0; i0 < q.b; i0 += imgs) item(0, 0, 0, i0 * px, (i0 + imgs < q.b ? i0 + imgs : q.b) * px);
         continue;
       }
       // Items of equal length: a class may mix convolutions with few tiles over many pixel rows and ones with many
@@ -609,7 +625,7 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
       for (int tap = 0; tap < w.R * w.R; ++tap)
         for (int c0 = 0; c0 < w.cin_run; c0 += bc)
           for (int n0 = 0; n0 < cv.cout; n0 += bn)
-            for (int sp = 0; sp < splits; ++sp) item(tap, c0, n0, sp * rows, (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M, splits == 1);
+            for (int sp = 0; sp < splits; ++sp) item(tap, c0, n0, sp * rows, (sp + 1) * rows < q.M ? (sp + 1) * rows : q.M);
     }
     }
   }
@@ -626,22 +642,6 @@ hpf_status build_plan(const hpf_partition_desc* desc, Plan& P) {
   P.res_off = g;    g += align_up(P.res_blocks.size() * sizeof(ResBlock));
   for (Plan::ResRun& r : P.runs) r.table_off += P.res_off;
   P.abort_off = g;  g += align_up(sizeof(int));
-  if (P.dt == DT_BF16) {   // the largest split convolution of the plan, either direction, any group size (capped: beyond, no split)
-    const size_t cap = (size_t)32 << 20;
-    auto need = [&](const ConvGeom& q) {
-      for (int gm = 1; gm <= MAX_GROUP && gm <= d.num_microbatches; ++gm) {
-        const int sp = conv_splitk(gm, q);
-        const size_t n = (size_t)sp * gm * q.M * q.N;
-        if (sp > 1 && n <= cap && n > P.splitk_floats) P.splitk_floats = n;
-      }
-    };
-    for (int i = 0; i < d.n_blocks; ++i) {
-      const BlockPlan& p = P.bp[i];
-      for (int j = 0; j < p.nconv; ++j) { need(conv_geom_fwd(p.cv[j], d.microbatch)); need(conv_geom_dgrad(p.cv[j], d.microbatch)); }
-      if (p.proj) { need(conv_geom_fwd(p.pj, d.microbatch)); need(conv_geom_dgrad(p.pj, d.microbatch)); }
-    }
-    P.splitk_off = g; g += align_up(P.splitk_floats * sizeof(float));
-  }
   P.running_off = g; g += align_up(P.n_running * sizeof(float));
   P.bn_table_off = g; g += align_up(P.bn_table.size() * sizeof(BnRunDesc));
   P.mb_off = g;     g += P.mb_bytes * (size_t)d.num_microbatches;
@@ -840,7 +840,7 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
-      epi.splitk_ws = (float*)(h->arena + h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats;
+      if (h->P.splitk_floats) { epi.splitk_ws = mbp(h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats; }
       const int back = conv_seg(PROF_CONV_FWD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_FWD, g, x, h->packed() + cv.wf_off, y, add, q, s, epi, pro), "conv_fwd");
       if (back != PROF_NONE) seg(back);
@@ -862,7 +862,7 @@ struct Ctx {
         const int bm = conv_mfma_tile_rows(g, q);
         rows = (q.M + bm - 1) / bm;
       }
-      epi.splitk_ws = (float*)(h->arena + h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats;
+      if (h->P.splitk_floats) { epi.splitk_ws = mbp(h->P.splitk_off); epi.splitk_floats = h->P.splitk_floats; }
       const int back = conv_seg(PROF_CONV_DGRAD, q, add.p[0] != nullptr);
       chk(launch_conv_mfma(CONV_DGRAD, g, dy, h->packed() + cv.wd_off, dx, add, q, s, epi), "conv_dgrad");
       if (back != PROF_NONE) seg(back);

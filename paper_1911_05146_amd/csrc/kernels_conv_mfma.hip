@@ -364,7 +364,7 @@ constexpr int BIG_STAGE = 2 * BIG_T * BIG_LS;                // bf16 elements pe
 constexpr int BIG_OPERAND_BYTES = 3 * BIG_STAGE * 2;         // three stages
 
 // SPLIT: grid y = number of work-groups that share a reduction; each takes a contiguous range of the steps and
-// stores its fp32 partial tile into its slab of epi.splitk_ws (k_splitk_finish adds the slabs up): for long reductions
+// stores its fp32 partial tile into its slab of the member's buffer epi.splitk_ws (k_splitk_finish adds the slabs up): for long reductions
 // into few output tiles (VGG-16's 512 -> 512 convolutions on 4x4 and 2x2 pixels: 32-64 tiles, 72 steps).
 template <int MODE, int EPI, int PRO, bool SPLIT = false>
 __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __restrict__ wpk, PtrTab outs, PtrTab adds, ConvGeom g,
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __r
     load8(tile + rl * TS + cg * 8, vv);
     if (SPLIT) {
       if (mv) {
-        float* o4 = epi.splitk_ws + ((size_t)(blockIdx.y * gridDim.z + blockIdx.z) * g.M + m) * g.N + ch;
+        float* o4 = (float*)pick(epi.splitk_ws, blockIdx.z) + ((size_t)blockIdx.y * g.M + m) * g.N + ch;
         *reinterpret_cast<float4*>(o4) = make_float4(vv[0], vv[1], vv[2], vv[3]);
         *reinterpret_cast<float4*>(o4 + 4) = make_float4(vv[4], vv[5], vv[6], vv[7]);
       }
@@ -671,13 +671,14 @@ __global__ __launch_bounds__(512) void k_conv_big(PtrTab srcs, const bf16_t* __r
 }
 
 // out[z][m][n] = bf16(sum over the slabs of the fp32 partial sums); 8 elements per thread
-__global__ __launch_bounds__(256) void k_splitk_finish(const float* __restrict__ ws, PtrTab outs, int splits, size_t mn, int ng) {
+__global__ __launch_bounds__(256) void k_splitk_finish(PtrTab wss, PtrTab outs, int splits, size_t mn) {
   const size_t u = (size_t)blockIdx.x * 256 + threadIdx.x;   // unit of 8 elements within a member
   const int z = blockIdx.y;
   if (u * 8 >= mn) return;
+  const float* __restrict__ ws = (const float*)pick(wss, z);
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < splits; ++s) {
-    const float4* q = reinterpret_cast<const float4*>(ws + ((size_t)s * ng + z) * mn + u * 8);
+    const float4* q = reinterpret_cast<const float4*>(ws + (size_t)s * mn + u * 8);
     const float4 a = q[0], b = q[1];
     acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
     acc[4] += b.x; acc[5] += b.y; acc[6] += b.z; acc[7] += b.w;
@@ -707,15 +708,15 @@ hipError_t launch_big(int mode, int ng, const PtrTab& src, const bf16_t* wpk, co
   const int tiles = ((g.M + BIG_T - 1) / BIG_T) * (g.N / BIG_T);
   const size_t dyn = BIG_OPERAND_BYTES + (pro.on ? (size_t)g.Cs * sizeof(float2) : 0);
   if (dyn > BIG_MAX_LDS) return hipErrorInvalidValue;
-  const int splits = (epi.kind == EPI_NONE && !pro.on && add.p[0] == nullptr && epi.splitk_ws) ? big_splits(ng, g) : 1;
-  if (splits > 1 && (size_t)splits * ng * g.M * g.N <= epi.splitk_floats) {
+  const int splits = (epi.kind == EPI_NONE && !pro.on && add.p[0] == nullptr && epi.splitk_floats) ? big_splits(ng, g) : 1;
+  if (splits > 1 && (size_t)splits * g.M * g.N <= epi.splitk_floats) {
     const dim3 sgrid((unsigned)(8 * ((tiles + 7) / 8)), (unsigned)splits, (unsigned)ng);
     if (mode == CONV_FWD) k_conv_big<CONV_FWD, EPI_NONE, 0, true><<<sgrid, 512, dyn, stream>>>(src, wpk, out, add, g, epi, pro);
     else k_conv_big<CONV_DGRAD, EPI_NONE, 0, true><<<sgrid, 512, dyn, stream>>>(src, wpk, out, add, g, epi, pro);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t mn = (size_t)g.M * g.N;   // a multiple of 128
-    k_splitk_finish<<<dim3((unsigned)((mn / 8 + 255) / 256), (unsigned)ng), 256, 0, stream>>>(epi.splitk_ws, out, splits, mn, ng);
+    k_splitk_finish<<<dim3((unsigned)((mn / 8 + 255) / 256), (unsigned)ng), 256, 0, stream>>>(epi.splitk_ws, out, splits, mn);
     return hipGetLastError();
   }
   const dim3 grid((unsigned)(8 * ((tiles + 7) / 8)), 1u, (unsigned)ng);

@@ -260,7 +260,7 @@ __device__ __forceinline__ void wgrad_accumulate(const bf16_t* __restrict__ a, c
 // Sums the four waves' accumulators through LDS and adds the tile into dw with one atomic per element.
 template <int BC, int BN>
 __device__ __forceinline__ void wgrad_flush(floatx4 (&acc)[BC / 16][BN / 16], float* red, float* dw, const WgradGeom& g, int tap,
-                                            int c0, int n0, bool sole = false) {
+                                            int c0, int n0) {
   constexpr int CTL = BC / 16, NTL = BN / 16;
   const int tid = threadIdx.x, lane = tid & 63;
   __syncthreads();
@@ -278,10 +278,7 @@ __device__ __forceinline__ void wgrad_flush(floatx4 (&acc)[BC / 16][BN / 16], fl
   __syncthreads();
   for (int i = tid; i < BC * BN; i += 256) {
     const int c = c0 + i / BN, n = n0 + i % BN;
-    if (c < g.c_valid) {
-      float* o = &dw[((size_t)tap * g.c_valid + c) * g.N + n];
-      if (sole) *o += red[i]; else atomicAdd(o, red[i]);
-    }
+    if (c < g.c_valid) atomicAdd(&dw[((size_t)tap * g.c_valid + c) * g.N + n], red[i]);
   }
 }
 
@@ -332,7 +329,7 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped(const WgradItem* __restri
     else
       wgrad_accumulate<BC, BN>(a, dy, it.g, it.tap, it.c0, it.n0, it.m_begin, it.m_end, sA, sD, acc);
   }
-  wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0, it.sole != 0);
+  wgrad_flush<BC, BN>(acc, reinterpret_cast<float*>(smem), grads + it.dw_off, it.g, it.tap, it.c0, it.n0);
 }
 
 // The 128 x 128 class: every wave owns a 64 x 64 quadrant over the whole reduction, so the sums go straight
@@ -370,10 +367,7 @@ __global__ __launch_bounds__(256, 2) void k_wgrad_grouped_quad(const WgradItem* 
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int c = qc + i * 16 + (lane >> 4) * 4 + v, n = qn + j * 16 + (lane & 15);
-        if (c < it.g.c_valid) {
-          float* o = &dw[((size_t)it.tap * it.g.c_valid + c) * it.g.N + n];
-          if (it.sole) *o += acc[i][j][v]; else atomicAdd(o, acc[i][j][v]);
-        }
+        if (c < it.g.c_valid) atomicAdd(&dw[((size_t)it.tap * it.g.c_valid + c) * it.g.N + n], acc[i][j][v]);
       }
 }
 
@@ -513,9 +507,7 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
     for (int v = 0; v < 4; ++v) atomicAdd(&red[t * 256 + (g * 4 + v) * 16 + r], acc[t][v]);
   __syncthreads();
   float* dw = grads + it.dw_off;
-  for (int i = tid; i < 9 * 256; i += 256) {
-    if (it.sole) dw[i] += red[i]; else atomicAdd(&dw[i], red[i]);
-  }
+  for (int i = tid; i < 9 * 256; i += 256) atomicAdd(&dw[i], red[i]);
 }
 
 template <int BC, int BN>

@@ -92,6 +92,23 @@ def test_vgg16_full_size(gpu, oracle):
     layerwise(oracle, W.vgg16(microbatch=4, num_microbatches=2), "f32", grouped=False)
 
 
+def test_micro_batches_on_their_own_streams_plain_units(gpu, oracle):
+    """Calls for different micro-batches may overlap on different streams: everything they write besides their own
+    regions must be either per micro-batch (the partial sums of the split reductions) or added atomically (the weight
+    gradients).  Eight micro-batches of plain 512-channel units on 4x4 pixels, several batches in a row."""
+    from parity import rel_err, run_gpu_step
+    blocks = tuple(W.Block(W.CONV_RELU, 512, 512, 512, 1) for _ in range(3))
+    spec = W.PartitionSpec(name="plain-512@4x4-streams", in_h=4, in_w=4, in_c=512, blocks=blocks, microbatch=8,
+                           num_microbatches=8, seed=67)
+    inp = W.make_inputs(spec)
+    _, a = run_gpu_step(spec, inp, "bf16", multi_stream=False)
+    for _ in range(3):
+        _, b = run_gpu_step(spec, inp, "bf16", multi_stream=True)
+        for x, y in zip(a["act_out"] + a["err_out"], b["act_out"] + b["err_out"]):
+            assert np.array_equal(x, y)                  # activations and errors: fixed summation order, no atomics
+        assert rel_err(b["grad"], a["grad"]) < 1e-5      # gradient sums: fp32 atomics, order may differ
+
+
 @pytest.mark.parametrize("model,n_parts", [("vgg16", 8), ("resnet110v1", 4)])
 def test_pipelines_of_partitions_equal_the_unsplit_model(gpu, oracle, model, n_parts):
     """The paper's premise on the GPU for both models: cut into partitions (VGG-16 in 8: the paper's best split),
