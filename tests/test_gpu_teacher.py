@@ -114,6 +114,7 @@ def test_convolutions_with_split_reductions_layerwise(gpu, oracle):
         spec = W.PartitionSpec(name=f"splitk-{name}-b{b}", in_h=hw, in_w=hw, in_c=cin, blocks=blocks, microbatch=b,
                                num_microbatches=m, seed=41)
         layerwise(oracle, spec, "bf16", grouped=grouped, blockwise=False)
+    layerwise(oracle, spec, "bf16", fusion=0, blockwise=False)   # every step a kernel of its own: the same convolution launches
 
 
 def test_whole_image_weight_gradient_of_16_channel_convolutions_layerwise(gpu, oracle):
@@ -133,7 +134,7 @@ def test_whole_image_weight_gradient_of_16_channel_convolutions_layerwise(gpu, o
                            num_microbatches=2, seed=29)
     layerwise(oracle, spec, "bf16", blockwise=False)
     post = tuple(W.Block(W.POSTACT, 16, 16, 16, 1) for _ in range(2))
-    for fusion in (2, 1):
+    for fusion in (2, 1, 0):
         spec = W.PartitionSpec(name=f"t9-postact16@32x32-level{fusion}", in_h=32, in_w=32, in_c=16, blocks=post, microbatch=6,
                                num_microbatches=2, seed=31)
         layerwise(oracle, spec, "bf16", fusion=fusion, blockwise=False)   # the block-wise harness covers pre-activation blocks
