@@ -171,8 +171,8 @@ struct ResArgs {
 };
 // Shapes this path covers (a property of the shapes alone).
 bool resident_shape_ok(int kind, int C, int MID, int H, int W, int nmem);   // kind: 0 basic (MID == C), 1 bottleneck, 2 post-activation basic
-// Runs cut into bands and 16-channel runs of kind 2 have forward and backward launches only (weight gradients: the
-// grouped per-layer launch); they and all runs of kind 2 go through the per-layer kernels at inference.
+// Runs cut into bands and 16-channel runs (kinds 0 and 2) have forward and backward launches only (weight gradients:
+// the grouped per-layer launch); banded runs and all runs of kind 2 go through the per-layer kernels at inference.
 inline bool resident_has_wgrad_launch(int kind, int C, int bands) { (void)kind; return bands == 1 && C != 16; }
 inline bool resident_has_inference_launch(int kind, int bands) { return bands == 1 && kind != 2; }
 // Largest number of micro-batches of nmem images one launch may hold on the current device (0: none):
