@@ -1660,8 +1660,8 @@ __global__ void __launch_bounds__(rw_threads(C)) k_bb_wgrad(const ResWgArgs a) {
 // block; two exchanges per block and direction (statistics of c1 and c2; sums of the two BatchNorm backward passes).
 // Backward: dz = dy*[y > 0] is the gradient of the shortcut and, through BN2's backward (no ReLU of its own), of c2.
 // ResBlock fields used: x, c1, c2, y, gy, dc1, dc2, gx and entries 0 / 1 of the per-BatchNorm / per-convolution arrays.
-// The weight gradients of such runs go through the grouped per-layer launch, inference through the per-layer kernels.
-
+// The weight gradients of the 32- and 64-channel runs have a launch of their own (k_v1_wgrad, further down), those of
+// the 16-channel runs go through the grouped per-layer launch; inference goes through the per-layer kernels.
 
 // y = relu(c2*scale + shift + x), tile to tile (written over x)
 template <int Cc>
