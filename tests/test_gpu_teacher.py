@@ -95,6 +95,9 @@ def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
     spec = W.PartitionSpec(name="wide-3x(128-64-128)@16x16-b40", in_h=16, in_w=16, in_c=128, blocks=runs["wide-3x(128-64-128)@16x16"][0],
                            microbatch=40, num_microbatches=2, seed=37)
     layerwise(oracle, spec, "bf16", blockwise=False)
+    spec = W.PartitionSpec(name="3x(128-32-128)@16x16-b40", in_h=16, in_w=16, in_c=128, blocks=runs["3x(128-32-128)@16x16"][0],
+                           microbatch=40, num_microbatches=2, seed=37)   # the records fill both narrow tiles
+    layerwise(oracle, spec, "bf16", blockwise=False)
     for name, (blocks, hw, c, blockwise) in runs.items():
         for b, m, grouped in ((3, 2, True), (4, 3, False)):
             spec = W.PartitionSpec(name=f"{name}-b{b}", in_h=hw, in_w=hw, in_c=c, blocks=blocks, microbatch=b,
