@@ -98,6 +98,13 @@ def test_runs_with_weights_through_lds_layerwise(gpu, oracle):
     spec = W.PartitionSpec(name="3x(128-32-128)@16x16-b40", in_h=16, in_w=16, in_c=128, blocks=runs["3x(128-32-128)@16x16"][0],
                            microbatch=40, num_microbatches=2, seed=37)   # the records fill both narrow tiles
     layerwise(oracle, spec, "bf16", blockwise=False)
+    # 100 images per micro-batch: the records no longer fit a tile and are gathered in an area of their own, behind
+    # which the staged matrix then lies
+    for name, blocks, hw, c in (("3x basic32@16x16-b100", runs["3x basic32@16x16"][0], 16, 32),
+                                ("3x basic64@8x8-b100", tuple(W.Block(W.BASIC, 64, 64, 64, 1) for _ in range(3)), 8, 64),
+                                ("3x postact32@16x16-b100", runs["3x postact32@16x16"][0], 16, 32)):
+        spec = W.PartitionSpec(name=name, in_h=hw, in_w=hw, in_c=c, blocks=blocks, microbatch=100, num_microbatches=2, seed=37)
+        layerwise(oracle, spec, "bf16", blockwise=False)
     for name, (blocks, hw, c, blockwise) in runs.items():
         for b, m, grouped in ((3, 2, True), (4, 3, False)):
             spec = W.PartitionSpec(name=f"{name}-b{b}", in_h=hw, in_w=hw, in_c=c, blocks=blocks, microbatch=b,
