@@ -406,22 +406,24 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
 
   const int nimg = (it.m_end - it.m_begin) / T9_P, img0 = it.m_begin / T9_P;
   const int total = ng * nimg;
-  uint4 ra[T9_NU][2], rd[T9_NU][2];
+  // Loads: 16-byte unit u of an image (pixel u/2, channel half u%2) goes to thread u % 256, so a wave reads 1 KB of
+  // contiguous memory per instruction.  Lanes t and t^2 then hold the two pixels of a pair (same channel half): they
+  // swap half of their channels (DPP within the quad), so that each ends up with 4 channels of both pixels and writes
+  // them as 4 dwords {pixel 2pp, pixel 2pp+1} into the channel-major tiles.
+  constexpr int T9_LD = 2 * T9_NU;               // loads per thread, operand and image
+  uint4 ra[T9_LD], rd[T9_LD];
+  const int odd = (tid >> 1) & 1;                // this thread's pixels are the odd ones of their pairs
   auto load_image = [&](int i) {
     const int z = i / nimg, img = img0 + (i - z * nimg);
     const char* base = (const char*)pick(bases, z);
     const bf16_t* a = it.a_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_a, z) : (const bf16_t*)(base + it.a_off);
     const bf16_t* dy = it.dy_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_dy, z) : (const bf16_t*)(base + it.dy_off);
-    a += (size_t)img * T9_P * 16 + hf * 8;
-    dy += (size_t)img * T9_P * 16 + hf * 8;
+    a += (size_t)img * T9_P * 16 + tid * 8;
+    dy += (size_t)img * T9_P * 16 + tid * 8;
 #pragma unroll
-    for (int k = 0; k < T9_NU; ++k) {
-      const int pp = (tid + 256 * k) >> 1;      // pixel pair
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        ra[k][e] = *reinterpret_cast<const uint4*>(a + (size_t)(2 * pp + e) * 16);
-        rd[k][e] = *reinterpret_cast<const uint4*>(dy + (size_t)(2 * pp + e) * 16);
-      }
+    for (int k = 0; k < T9_LD; ++k) {
+      ra[k] = *reinterpret_cast<const uint4*>(a + (size_t)k * 256 * 8);
+      rd[k] = *reinterpret_cast<const uint4*>(dy + (size_t)k * 256 * 8);
     }
   };
   float2 cf[8];
@@ -435,14 +437,18 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
     }
     return make_uint4(r_[0], r_[1], r_[2], r_[3]);
   };
-  // transposing store: channel e of the two pixels of a pair becomes one dword of channel row 8*hf + e
-  auto store_pair = [&](uint32_t* dst, int cstride2, const uint4& q0, const uint4& q1) {
-    const uint32_t w0[4] = {q0.x, q0.y, q0.z, q0.w}, w1[4] = {q1.x, q1.y, q1.z, q1.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      dst[(2 * i) * cstride2] = (w0[i] & 0xffffu) | (w1[i] << 16);
-      dst[(2 * i + 1) * cstride2] = (w0[i] >> 16) | (w1[i] & 0xffff0000u);
-    }
+  // transposing store of one unit: the even-pixel lane keeps its channels 0..3 and takes the partner's, the odd-pixel
+  // lane its channels 4..7; dst points at channel row 8*hf + 4*odd, pixel pair pp
+  auto store_unit = [&](uint32_t* dst, int cstride2, const uint4& q) {
+    const uint32_t send0 = odd ? q.x : q.z, send1 = odd ? q.y : q.w;
+    const uint32_t recv0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)send0, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]: lane ^ 2
+    const uint32_t recv1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)send1, 0x4E, 0xF, 0xF, true);
+    const uint32_t f0 = odd ? recv0 : q.x, f1 = odd ? recv1 : q.y;   // the pair's first (even) pixel
+    const uint32_t s0 = odd ? q.z : recv0, s1 = odd ? q.w : recv1;   // its second pixel
+    dst[0] = (f0 & 0xffffu) | (s0 << 16);
+    dst[cstride2] = (f0 >> 16) | (s0 & 0xffff0000u);
+    dst[2 * cstride2] = (f1 & 0xffffu) | (s1 << 16);
+    dst[3 * cstride2] = (f1 >> 16) | (s1 & 0xffff0000u);
   };
 
   floatx4 acc[9];
@@ -462,16 +468,16 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
       }
     }
 #pragma unroll
-    for (int k = 0; k < T9_NU; ++k) {
-      const int pp = (tid + 256 * k) >> 1;
-      uint4 q0 = ra[k][0], q1 = ra[k][1];
-      if (bn) { q0 = bn_relu8(q0); q1 = bn_relu8(q1); }
-      store_pair(sA32 + ((hf * 8 * SA + W) >> 1) + pp, SA >> 1, q0, q1);
-      store_pair(sD32 + ((hf * 8 * SD) >> 1) + pp, SD >> 1, rd[k][0], rd[k][1]);
+    for (int k = 0; k < T9_LD; ++k) {
+      const int pp = (tid >> 2) + 64 * k;       // pixel pair of unit tid + 256*k
+      uint4 q = ra[k];
+      if (bn) q = bn_relu8(q);
+      store_unit(sA32 + (((hf * 8 + odd * 4) * SA + W) >> 1) + pp, SA >> 1, q);
+      store_unit(sD32 + (((hf * 8 + odd * 4) * SD) >> 1) + pp, SD >> 1, rd[k]);
     }
     if (i + 1 < total) load_image(i + 1);
     __syncthreads();
-#pragma unroll 2
+#pragma unroll 4
     for (int st = 0; st < T9_P / 128; ++st) {
       const int px = (wave * (T9_P / 128) + st) * 32 + g * 8;   // first pixel of the lane's chunk
       const int col = px & (W - 1);
