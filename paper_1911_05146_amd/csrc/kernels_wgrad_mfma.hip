@@ -382,7 +382,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int T9_P = 1024, T9_NU = T9_P / 256;   // pixels per image; staging units (pixel pair x 8 channels) per thread and operand
 __host__ __device__ constexpr int t9_sa(int H, int W) { return (H + 2) * W + 8; }   // channel stride of the padded input tile (bf16):
 __host__ __device__ constexpr int t9_sd(int H, int W) { return H * W + 8; }         // = 8 mod 16, so 16 channels hit 16 bank groups
-__host__ __device__ constexpr int t9_lds_bytes(int H, int W) { return 16 * (t9_sa(H, W) + t9_sd(H, W)) * 2; }
+__host__ __device__ constexpr int t9_lds_bytes(int H, int W) { return 16 * (t9_sa(H, W) + t9_sd(H, W)) * 2 + MAX_GROUP * 16 * 8; }   // tiles + {scale, shift} per member and channel
 constexpr int T9_MAX_LDS = t9_lds_bytes(32, 32);   // the widest rows pad the most
 
 __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __restrict__ items, int ng, PtrTab bases, PtrTab caller_dy,
@@ -411,9 +411,10 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
   // swap half of their channels (DPP within the quad), so that each ends up with 4 channels of both pixels and writes
   // them as 4 dwords {pixel 2pp, pixel 2pp+1} into the channel-major tiles.
   constexpr int T9_LD = 2 * T9_NU;               // loads per thread, operand and image
-  uint4 ra[T9_LD], rd[T9_LD];
+  struct Regs { uint4 a[T9_LD], d[T9_LD]; };
+  Regs set0, set1;                               // two images on their way: a set is refilled as soon as it has been staged
   const int odd = (tid >> 1) & 1;                // this thread's pixels are the odd ones of their pairs
-  auto load_image = [&](int i) {
+  auto load_image = [&](int i, Regs& rg) {
     const int z = i / nimg, img = img0 + (i - z * nimg);
     const char* base = (const char*)pick(bases, z);
     const bf16_t* a = it.a_off == WGRAD_DY_CALLER ? (const bf16_t*)pick(caller_a, z) : (const bf16_t*)(base + it.a_off);
@@ -422,10 +423,21 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
     dy += (size_t)img * T9_P * 16 + tid * 8;
 #pragma unroll
     for (int k = 0; k < T9_LD; ++k) {
-      ra[k] = *reinterpret_cast<const uint4*>(a + (size_t)k * 256 * 8);
-      rd[k] = *reinterpret_cast<const uint4*>(dy + (size_t)k * 256 * 8);
+      rg.a[k] = *reinterpret_cast<const uint4*>(a + (size_t)k * 256 * 8);
+      rg.d[k] = *reinterpret_cast<const uint4*>(dy + (size_t)k * 256 * 8);
     }
   };
+  // {scale, shift} of the BatchNorm recomputed on the input, for every member of the launch: in LDS once, so that the
+  // images do not wait for a round trip to memory each
+  float2* sCf = reinterpret_cast<float2*>(sD + 16 * SD);
+  const bool bn = it.stats_off != WGRAD_NO_BN;
+  if (bn && tid < ng * 16) {
+    const int z = tid >> 4, c = tid & 15;
+    const float* stt = (const float*)((const char*)pick(bases, z) + it.stats_off);
+    const float sc = params[it.gamma_off + c] * stt[16 + c];
+    sCf[tid] = make_float2(sc, params[it.beta_off + c] - stt[c] * sc);
+  }
+  __syncthreads();
   float2 cf[8];
   auto bn_relu8 = [&](const uint4& q) {
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -455,27 +467,22 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
 #pragma unroll
   for (int i = 0; i < 9; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
   const int r = lane & 15, g = lane >> 4;
-  const bool bn = it.stats_off != WGRAD_NO_BN;
-  if (total > 0) load_image(0);
-  for (int i = 0; i < total; ++i) {
-    if (bn && i % nimg == 0) {                  // a new member: its BatchNorm statistics
-      const float* stt = (const float*)((const char*)pick(bases, i / nimg) + it.stats_off);
+  if (total > 0) load_image(0, set0);
+  if (total > 1) load_image(1, set1);
+  auto image = [&](int i, Regs& rg) {
+    if (bn && i % nimg == 0) {                  // a new member: its coefficients
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int c = hf * 8 + e;
-        const float sc = params[it.gamma_off + c] * stt[16 + c];
-        cf[e] = make_float2(sc, params[it.beta_off + c] - stt[c] * sc);
-      }
+      for (int e = 0; e < 8; ++e) cf[e] = sCf[(i / nimg) * 16 + hf * 8 + e];
     }
 #pragma unroll
     for (int k = 0; k < T9_LD; ++k) {
       const int pp = (tid >> 2) + 64 * k;       // pixel pair of unit tid + 256*k
-      uint4 q = ra[k];
+      uint4 q = rg.a[k];
       if (bn) q = bn_relu8(q);
       store_unit(sA32 + (((hf * 8 + odd * 4) * SA + W) >> 1) + pp, SA >> 1, q);
-      store_unit(sD32 + (((hf * 8 + odd * 4) * SD) >> 1) + pp, SD >> 1, rd[k]);
+      store_unit(sD32 + (((hf * 8 + odd * 4) * SD) >> 1) + pp, SD >> 1, rg.d[k]);
     }
-    if (i + 1 < total) load_image(i + 1);
+    if (i + 2 < total) load_image(i + 2, rg);
     __syncthreads();
 #pragma unroll 4
     for (int st = 0; st < T9_P / 128; ++st) {
@@ -502,6 +509,10 @@ __global__ __launch_bounds__(256) void k_wgrad_grouped_t9(const WgradItem* __res
       }
     }
     __syncthreads();
+  };
+  for (int i = 0; i < total; i += 2) {
+    image(i, set0);
+    if (i + 1 < total) image(i + 1, set1);
   }
   // the four waves' sums through LDS, then one atomic per output element and work-group
   float* red = reinterpret_cast<float*>(smem_t9);
