@@ -157,9 +157,12 @@ def test_config1_resnet20_layerwise(gpu, oracle):
 
 
 def test_config2_resnet110_partition_full_size_layerwise(gpu, oracle):
+    """Full size in the launch configuration bench.py times; the other fusion level and the fp32 mode on two of the eight
+    micro-batches (same micro-batch size, same kernels)."""
     layerwise(oracle, W.config(2), "bf16")
-    layerwise(oracle, W.config(2), "bf16", fusion=1)
-    layerwise(oracle, W.config(2), "f32")
+    small = W.with_microbatching(W.config(2), 16, 2, loss_divisor=128)
+    layerwise(oracle, small, "bf16", fusion=1)
+    layerwise(oracle, small, "f32")
 
 
 def test_config3_resnet1001_partition_full_size_layerwise(gpu, oracle):
@@ -169,14 +172,16 @@ def test_config3_resnet1001_partition_full_size_layerwise(gpu, oracle):
 
 def test_config3_other_schedules_layerwise(gpu, oracle):
     spec = W.with_microbatching(W.config(3), 32, 2, loss_divisor=256)
-    layerwise(oracle, spec, "bf16", fusion=1)
-    layerwise(oracle, spec, "bf16", fusion=0)
+    layerwise(oracle, spec, "bf16", fusion=1, blockwise=False)
+    layerwise(oracle, spec, "bf16", fusion=0, blockwise=False)
     layerwise(oracle, spec, "bf16", grouped=False)
     layerwise(oracle, W.with_microbatching(W.config(3), 8, 2, loss_divisor=256), "f32")
 
 
 def test_config6_wide_resnet1001_partition_full_size_layerwise(gpu, oracle):
-    layerwise(oracle, W.config(6), "bf16")
+    """Layer by layer at full size; block by block on two of the eight micro-batches."""
+    layerwise(oracle, W.config(6), "bf16", blockwise=False)
+    layerwise(oracle, W.with_microbatching(W.config(6), 32, 2, loss_divisor=256), "bf16")
 
 
 def test_config4_resnet1001_whole_full_size_layerwise(gpu, oracle):
